@@ -1,0 +1,499 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something other than itself -
+self-describing payloads, closed forms, numpy library routines, brute-force enumeration with an
+independent few-line model, and the invariants the paper fixes (Section 3.1: correctness never
+depends on the cache tier; Section 3.2: revocation falls back to the host copy; Section 5.2: block
+table resolution)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from oracle import OracleClass, OracleError
+
+
+def make_kv(n_layers=3, chunk=64, n_obj=40, n_cache=17, n_local=5, seed=0, poison=False, mode=W.FILL_TAG,
+            extra_host=8):
+    """Small KV class: objects start on the host, host slot != object id, payload = tag or normal fill."""
+    n_host = n_obj + extra_host
+    oc = OracleClass(n_layers, 2, chunk, n_obj + 8, n_host, n_cache, n_local, poison)
+    hs = W.rng(seed, 100).permutation(n_host)[:n_obj]
+    ids = oc.register(n_obj, hs, O.HOST)
+    assert list(ids) == list(range(n_obj))
+    so = np.full(n_host, W.NO_OBJECT, dtype=np.uint32)
+    so[hs] = ids
+    for p in range(2):
+        W.fill_array(oc.plane(O.HOST, p), so, seed, W.CLS_KV, p, mode)
+    oc.adopt(ids)
+    return oc, ids, hs
+
+
+def place_fraction(oc, ids, p, seed):
+    order = W.rng(seed, 101).permutation(len(ids))
+    n = int(round(p * len(ids)))
+    chosen = np.asarray(ids)[order[:n]]
+    st = oc.place(chosen)
+    return chosen, st
+
+
+def random_tables(n_obj, n_seq, max_blocks, seed):
+    g = W.rng(seed, 102)
+    n_blocks = g.integers(0, max_blocks + 1, size=n_seq).astype(np.int32)
+    n_blocks[0] = max_blocks                     # one full row
+    table = g.integers(0, n_obj, size=(n_seq, max_blocks)).astype(np.int32)   # duplicates allowed
+    sdb = np.concatenate([[0], np.cumsum(n_blocks)[:-1]]).astype(np.uint64)
+    return table, n_blocks, sdb, int(n_blocks.sum())
+
+
+def check_tags(oc, dst, plane, layer, table, n_blocks, sdb, seed, chunk):
+    for s in range(table.shape[0]):
+        for j in range(n_blocks[s]):
+            d = int(sdb[s]) + j
+            assert W.check_tag(dst[d * chunk:(d + 1) * chunk], seed, W.CLS_KV, plane, layer, int(table[s, j])), \
+                (plane, layer, s, j)
+
+
+# ---- self-describing payload: no reference buffer at all --------------------------------------------------
+
+@pytest.mark.parametrize("p_cache", [0.0, 0.3, 0.6, 1.0])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_fetch_kv_every_destination_word_names_its_request(p_cache, seed):
+    chunk = 48
+    oc, ids, _ = make_kv(n_layers=3, chunk=chunk, n_obj=40, n_cache=40, seed=seed)
+    place_fraction(oc, ids, p_cache, seed)
+    table, n_blocks, sdb, cap = random_tables(40, 5, 9, seed)
+    for layer in range(3):
+        k, v, miss, counts = oc.fetch_kv(layer, table, n_blocks, sdb, cap)
+        check_tags(oc, k, 0, layer, table, n_blocks, sdb, seed, chunk)
+        check_tags(oc, v, 1, layer, table, n_blocks, sdb, seed, chunk)
+        assert counts["n_requests"] == cap and counts["n_invalid"] == 0 and counts["n_lost"] == 0
+
+
+# ---- tier independence (Section 3.1) ----------------------------------------------------------------------
+
+def test_fetch_is_identical_for_every_residency_assignment():
+    results = {}
+    for seed in (0, 1, 2):
+        for p in (0.0, 0.3, 0.6, 1.0):
+            oc, ids, _ = make_kv(n_layers=2, chunk=256, n_obj=64, n_cache=64, seed=seed, mode=W.FILL_NORMAL)
+            place_fraction(oc, ids, p, seed + 7)
+            table, n_blocks, sdb, cap = random_tables(64, 6, 11, seed)
+            k, v, miss, counts = oc.fetch_kv(1, table, n_blocks, sdb, cap)
+            kp, vp, _, _ = oc.fetch_kv(1, table, n_blocks, sdb, cap, plain=True)
+            assert np.array_equal(k, kp) and np.array_equal(v, vp)
+            results.setdefault(seed, []).append((k.copy(), v.copy(), counts))
+    for seed, rs in results.items():
+        for k, v, _ in rs[1:]:
+            assert np.array_equal(k, rs[0][0]) and np.array_equal(v, rs[0][1])
+        assert rs[0][2]["n_cache"] == 0 and rs[-1][2]["n_host"] == 0        # p = 0 and p = 1
+
+
+# ---- library cross-checks ---------------------------------------------------------------------------------
+
+def test_fetch_equals_numpy_take_on_the_host_plane():
+    oc, ids, hs = make_kv(n_layers=2, chunk=128, n_obj=50, n_cache=20, seed=3, mode=W.FILL_NORMAL)
+    place_fraction(oc, ids, 0.4, 3)
+    table, n_blocks, sdb, cap = random_tables(50, 4, 10, 3)
+    for layer in range(2):
+        k, v, _, _ = oc.fetch_kv(layer, table, n_blocks, sdb, cap)
+        flat = np.concatenate([table[s, :n_blocks[s]] for s in range(4)])
+        for plane, got in ((0, k), (1, v)):
+            want = np.take(oc.plane(O.HOST, plane)[layer], hs[flat], axis=0).reshape(-1)
+            assert np.array_equal(got, want)
+
+
+def test_torch_index_select_reproduces_the_gather():
+    import torch
+    oc, ids, hs = make_kv(n_layers=1, chunk=96, n_obj=30, n_cache=30, seed=4, mode=W.FILL_NORMAL)
+    place_fraction(oc, ids, 1.0, 4)
+    table, n_blocks, sdb, cap = random_tables(30, 3, 7, 4)
+    k, _, _, _ = oc.fetch_kv(0, table, n_blocks, sdb, cap)
+    flat = np.concatenate([table[s, :n_blocks[s]] for s in range(3)])
+    slots = np.array([oc.lookup(b)[1] for b in flat])
+    want = torch.index_select(torch.from_numpy(oc.plane(O.CACHE, 0)[0].copy()), 0, torch.from_numpy(slots))
+    assert np.array_equal(k, want.numpy().reshape(-1))
+
+
+def test_all_cached_identity_table_is_one_memcpy():
+    n = 24
+    oc, ids, _ = make_kv(n_layers=2, chunk=64, n_obj=n, n_cache=n, seed=5, mode=W.FILL_NORMAL)
+    st = oc.place(ids)                                    # in id order: lowest free slot == id
+    assert (st == O.OK).all()
+    table = np.arange(n, dtype=np.int32).reshape(1, n)
+    k, v, miss, counts = oc.fetch_kv(1, table, np.array([n], np.int32), np.array([0], np.uint64), n)
+    assert np.array_equal(k, oc.plane(O.CACHE, 0)[1].reshape(-1))
+    assert np.array_equal(v, oc.plane(O.CACHE, 1)[1].reshape(-1))
+    assert miss.size == 0 and counts["n_cache"] == n
+
+
+# ---- brute force on tiny inputs against an independent model ----------------------------------------------
+
+def test_brute_force_three_blocks_all_tables_residencies_and_revocations():
+    """3 blocks, 1 layer, every order of the table, every subset placed, every subset then revoked.
+    Model: a dict block -> bytes (the value never changes) and a dict block -> 'H'/'C'."""
+    chunk = 16
+    for perm in itertools.permutations(range(3)):
+        for placed in itertools.product([0, 1], repeat=3):
+            for revoked in itertools.product([0, 1], repeat=3):
+                oc = OracleClass(1, 2, chunk, 3, 3, 3, 0, poison=True)
+                ids = oc.register(3, [2, 0, 1], O.HOST)
+                value = {}
+                for b in range(3):
+                    kb = np.full(chunk, 10 + b, np.uint8); vb = np.full(chunk, 20 + b, np.uint8)
+                    oc.set_object(b, kb, vb)
+                    value[b] = (kb, vb)
+                where = {b: "H" for b in range(3)}
+                oc.place([b for b in range(3) if placed[b]])
+                for b in range(3):
+                    if placed[b]: where[b] = "C"
+                oc.revoke([b for b in range(3) if revoked[b]])
+                for b in range(3):
+                    if revoked[b]: where[b] = "H"
+                table = np.array([perm], dtype=np.int32)
+                k, v, miss, counts = oc.fetch_kv(0, table, np.array([3], np.int32), np.array([0], np.uint64), 3)
+                for j, b in enumerate(perm):
+                    assert np.array_equal(k[j * chunk:(j + 1) * chunk], value[b][0])
+                    assert np.array_equal(v[j * chunk:(j + 1) * chunk], value[b][1])
+                assert sorted(miss) == [j for j, b in enumerate(perm) if where[b] == "H"]
+                assert counts["n_cache"] == sum(1 for b in perm if where[b] == "C")
+                for b in range(3):
+                    assert oc.lookup(b)[0] == (O.CACHE if where[b] == "C" else O.HOST)
+                    assert oc.lookup(b)[2] == placed[b] + (placed[b] and revoked[b])
+                oc.close()
+
+
+# ---- round trips (Sections 5.1-5.2) ------------------------------------------------------------------------
+
+def test_evict_of_fetched_bytes_is_identity_and_evict_of_new_bytes_is_returned():
+    chunk = 80
+    oc, ids, _ = make_kv(n_layers=2, chunk=chunk, n_obj=32, n_cache=20, seed=6, mode=W.FILL_NORMAL)
+    place_fraction(oc, ids, 0.5, 6)
+    perm = W.rng(6, 1).permutation(32).astype(np.int32)
+    table = perm.reshape(4, 8)
+    nb = np.full(4, 8, np.int32); sdb = (np.arange(4) * 8).astype(np.uint64)
+    before = [oc.fetch_kv(l, table, nb, sdb, 32)[:2] for l in range(2)]
+    host_before = [oc.plane(O.HOST, p).copy() for p in range(2)]
+    cache_before = [oc.plane(O.CACHE, p).copy() for p in range(2)]
+    for l in range(2):
+        oc.evict(l, table.reshape(-1), before[l][0], before[l][1], np.arange(32), 32)
+    for p in range(2):
+        assert np.array_equal(oc.plane(O.HOST, p), host_before[p])
+        assert np.array_equal(oc.plane(O.CACHE, p), cache_before[p])
+    # new bytes
+    g = W.rng(6, 2)
+    yk = g.integers(0, 256, size=32 * chunk, dtype=np.uint8); yv = g.integers(0, 256, size=32 * chunk, dtype=np.uint8)
+    oc.evict(1, table.reshape(-1), yk, yv, np.arange(32), 32)
+    k, v, _, _ = oc.fetch_kv(1, table, nb, sdb, 32)
+    assert np.array_equal(k, yk) and np.array_equal(v, yv)
+    k0, v0, _, _ = oc.fetch_kv(0, table, nb, sdb, 32)      # the other layer is untouched
+    assert np.array_equal(k0, before[0][0]) and np.array_equal(v0, before[0][1])
+    # every copy of a cached object stays identical to its host copy
+    for b in range(32):
+        t, slot, _, hs = oc.lookup(b)
+        if t == O.CACHE:
+            for p in range(2):
+                assert np.array_equal(oc.plane(O.CACHE, p)[:, slot], oc.plane(O.HOST, p)[:, hs])
+    # a revoked object is then served, with the new bytes, from the host
+    cached = [b for b in range(32) if oc.lookup(b)[0] == O.CACHE]
+    oc.revoke(cached)
+    k, v, miss, _ = oc.fetch_kv(1, table, nb, sdb, 32)
+    assert np.array_equal(k, yk) and np.array_equal(v, yv) and miss.size == 32
+
+
+def test_evict_all_layers_layout_and_duplicate_rejection():
+    chunk, L = 32, 3
+    oc, ids, _ = make_kv(n_layers=L, chunk=chunk, n_obj=10, n_cache=10, seed=7)
+    oc.place([1, 4])
+    stride = 6
+    g = W.rng(7, 3)
+    sk = g.integers(0, 256, size=L * stride * chunk, dtype=np.uint8)
+    sv = g.integers(0, 256, size=L * stride * chunk, dtype=np.uint8)
+    ev = np.array([4, 7, 1], np.uint32); sb = np.array([5, 0, 2], np.uint64)
+    oc.evict(-1, ev, sk, sv, sb, stride)
+    for l in range(L):
+        table = ev.astype(np.int32).reshape(1, 3)
+        k, v, _, _ = oc.fetch_kv(l, table, np.array([3], np.int32), np.array([0], np.uint64), 3)
+        for j in range(3):
+            o = (l * stride + int(sb[j])) * chunk
+            assert np.array_equal(k[j * chunk:(j + 1) * chunk], sk[o:o + chunk])
+            assert np.array_equal(v[j * chunk:(j + 1) * chunk], sv[o:o + chunk])
+    snap = [oc.plane(O.HOST, p).copy() for p in range(2)]
+    with pytest.raises(OracleError) as e:
+        oc.evict(0, [2, 3, 2], sk, sv, [0, 1, 2], stride)
+    assert e.value.code == O.EINVAL
+    with pytest.raises(OracleError) as e:
+        oc.evict(0, [2], sk, sv, [stride], stride)
+    assert e.value.code == O.EINVAL
+    with pytest.raises(OracleError) as e:
+        oc.evict(0, [99], sk, sv, [0], stride)
+    assert e.value.code == O.ENOENT
+    for p in range(2):
+        assert np.array_equal(oc.plane(O.HOST, p), snap[p])
+
+
+# ---- revocation (Section 3.2) -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("poison", [False, True])
+def test_revocation_falls_back_to_host_and_grows_the_miss_set_exactly(poison):
+    chunk = 64
+    oc, ids, _ = make_kv(n_layers=2, chunk=chunk, n_obj=48, n_cache=48, seed=8, poison=poison, mode=W.FILL_NORMAL)
+    placed, _ = place_fraction(oc, ids, 0.7, 8)
+    table, n_blocks, sdb, cap = random_tables(48, 5, 12, 8)
+    k0, v0, miss0, c0 = oc.fetch_kv(0, table, n_blocks, sdb, cap)
+    R = placed[W.rng(8, 9).permutation(placed.size)[:placed.size // 3]]
+    slots = [oc.lookup(b)[1] for b in R]
+    gens = [oc.lookup(b)[2] for b in R]
+    oc.revoke(R)
+    assert oc.revoked_log == [int(b) for b in R]              # callbacks, in order, once each
+    for b, g in zip(R, gens):
+        assert oc.lookup(b)[:3] == (O.HOST, -1, g + 1)
+    if poison:
+        for s in slots:
+            assert (oc.plane(O.CACHE, 0)[:, s] == O.POISON).all() and (oc.plane(O.CACHE, 1)[:, s] == O.POISON).all()
+    k1, v1, miss1, c1 = oc.fetch_kv(0, table, n_blocks, sdb, cap)
+    assert np.array_equal(k0, k1) and np.array_equal(v0, v1)
+    grown = set(miss1) - set(miss0)
+    want = {s * table.shape[1] + j for s in range(table.shape[0]) for j in range(n_blocks[s])
+            if table[s, j] in set(int(b) for b in R)}
+    assert grown == want and set(miss0) <= set(miss1)
+    assert c1["n_host"] == c0["n_host"] + len(want) and c1["n_cache"] == c0["n_cache"] - len(want)
+    # revoking again, or revoking host objects, is a no-op with no callback
+    oc.revoke(R)
+    assert len(oc.revoked_log) == len(R)
+    # freed slots are reused lowest first
+    st = oc.place(R[:3])
+    assert (st == O.OK).all()
+    assert sorted(oc.lookup(b)[1] for b in R[:3]) == sorted(slots)[:3]
+    assert [oc.lookup(b)[2] for b in R[:3]] == [g + 2 for g in gens[:3]]
+
+
+def test_miss_list_is_exactly_the_host_and_lost_requests_in_request_order():
+    oc, ids, _ = make_kv(n_layers=1, chunk=32, n_obj=30, n_cache=30, seed=9)
+    place_fraction(oc, ids, 0.5, 9)
+    table, n_blocks, sdb, cap = random_tables(30, 4, 8, 9)
+    _, _, miss, counts = oc.fetch_kv(0, table, n_blocks, sdb, cap)
+    want = [s * 8 + j for s in range(4) for j in range(n_blocks[s]) if oc.lookup(table[s, j])[0] in (O.HOST, O.NONE)]
+    assert list(miss) == want and counts["n_host"] == len(want)
+
+
+# ---- placement (Sections 3.2, 4.3) ------------------------------------------------------------------------
+
+def test_place_takes_lowest_free_slot_copies_the_host_bytes_and_reports_enospc():
+    oc, ids, hs = make_kv(n_layers=2, chunk=32, n_obj=12, n_cache=4, seed=10, mode=W.FILL_NORMAL)
+    st = oc.place([7, 3, 9])
+    assert list(st) == [O.OK] * 3
+    assert [oc.lookup(b)[:3] for b in (7, 3, 9)] == [(O.CACHE, 0, 1), (O.CACHE, 1, 1), (O.CACHE, 2, 1)]
+    for b in (7, 3, 9):
+        for p in range(2):
+            assert np.array_equal(oc.plane(O.CACHE, p)[:, oc.lookup(b)[1]], oc.plane(O.HOST, p)[:, hs[b]])
+    st = oc.place([3, 5, 6, 6])                  # already cached -> OK no-op; one slot left; then full
+    assert list(st) == [O.OK, O.OK, O.ENOSPC, O.ENOSPC]
+    assert oc.lookup(3)[:3] == (O.CACHE, 1, 1) and oc.lookup(5)[:3] == (O.CACHE, 3, 1)
+    assert oc.lookup(6)[:3] == (O.HOST, -1, 0)
+    oc.revoke([3])
+    assert list(oc.place([6])) == [O.OK] and oc.lookup(6)[:3] == (O.CACHE, 1, 1)
+    with pytest.raises(OracleError) as e:
+        oc.place([0, 500])
+    assert e.value.code == O.ENOENT and oc.lookup(0)[0] == O.HOST
+
+
+def test_fetch_never_changes_the_directory_or_any_tier():
+    oc, ids, _ = make_kv(n_layers=2, chunk=32, n_obj=20, n_cache=8, n_local=3, seed=11)
+    place_fraction(oc, ids, 0.4, 11)
+    snap_dir = [oc.lookup(b) for b in range(20)]
+    snap = [oc.plane(w, p).copy() for w in (O.HOST, O.CACHE, O.LOCAL) for p in range(2)]
+    table, n_blocks, sdb, cap = random_tables(20, 4, 6, 11)
+    oc.fetch_kv(1, table, n_blocks, sdb, cap)
+    assert snap_dir == [oc.lookup(b) for b in range(20)]
+    for a, (w, p) in zip(snap, [(w, p) for w in (O.HOST, O.CACHE, O.LOCAL) for p in range(2)]):
+        assert np.array_equal(a, oc.plane(w, p))
+
+
+# ---- local tier, demotion, lossy objects ------------------------------------------------------------------
+
+def test_local_objects_append_evict_demote_then_place():
+    chunk, L = 64, 2
+    oc, ids, hs = make_kv(n_layers=L, chunk=chunk, n_obj=6, n_cache=4, n_local=2, seed=12, extra_host=8)
+    free = sorted(set(range(oc.n_slots[O.HOST])) - set(int(h) for h in hs))
+    tail = oc.register(2, free[:2], O.LOCAL)
+    assert [oc.lookup(t)[:2] for t in tail] == [(O.LOCAL, 0), (O.LOCAL, 1)]
+    with pytest.raises(OracleError) as e:
+        oc.register(1, free[2:3], O.LOCAL)                         # local pool full
+    assert e.value.code == O.ENOSPC
+    with pytest.raises(OracleError) as e:
+        oc.register(1, free[:1], O.HOST)                           # host slot taken
+    assert e.value.code == O.EINVAL
+    rows = {}
+    for t in tail:
+        for p in range(2):
+            for l in range(L):
+                for r in range(4):
+                    d = W.rng(12, int(t), p, l, r).integers(0, 256, size=16, dtype=np.uint8)
+                    oc.write_local(t, p, l, r * 16, d)
+                    rows[(int(t), p, l, r)] = d
+    table = np.array([[0, int(tail[0])], [int(tail[1]), 3]], np.int32)
+    nb = np.array([2, 2], np.int32); sdb = np.array([0, 2], np.uint64)
+    k, v, miss, counts = oc.fetch_kv(1, table, nb, sdb, 4)
+    assert counts["n_local"] == 2 and counts["n_host"] == 2 and list(miss) == [0, 3]
+    want_k = np.concatenate([rows[(int(tail[0]), 0, 1, r)] for r in range(4)])
+    assert np.array_equal(k[chunk:2 * chunk], want_k)
+    # write back + leave local HBM: source is the local pool itself
+    oc.evict(-1, tail, oc.plane(O.LOCAL, 0), oc.plane(O.LOCAL, 1), [0, 1], oc.n_slots[O.LOCAL], O.EVICT_DEMOTE)
+    assert [oc.lookup(t)[:3] for t in tail] == [(O.HOST, -1, 1), (O.HOST, -1, 1)]
+    k2, v2, miss2, _ = oc.fetch_kv(1, table, nb, sdb, 4)
+    assert np.array_equal(k, k2) and np.array_equal(v, v2) and list(miss2) == [0, 1, 2, 3]
+    assert list(oc.place(tail)) == [O.OK, O.OK]
+    k3, v3, miss3, _ = oc.fetch_kv(1, table, nb, sdb, 4)
+    assert np.array_equal(k, k3) and np.array_equal(v, v3) and list(miss3) == [0, 3]
+    fresh = oc.register(1, free[2:3], O.LOCAL)                      # the local slot is free again
+    assert oc.lookup(fresh[0])[:2] == (O.LOCAL, 0)
+    with pytest.raises(OracleError):                                 # demote needs all layers
+        oc.evict(0, fresh, oc.plane(O.LOCAL, 0)[0], oc.plane(O.LOCAL, 1)[0], [0], 2, O.EVICT_DEMOTE)
+
+
+def test_invalid_requests_are_skipped_and_counted():
+    oc, ids, _ = make_kv(n_layers=1, chunk=32, n_obj=8, n_cache=8, seed=13)
+    table = np.array([[0, -1, 2, 99], [3, 4, 5, 6]], np.int32)
+    nb = np.array([4, 9], np.int32)                                  # 9 is clamped to max_blocks = 4
+    sdb = np.array([0, 4], np.uint64)
+    k = np.full(6 * 32, 0xEE, np.uint8); v = np.full(6 * 32, 0xEE, np.uint8)
+    k, v, miss, counts = oc.fetch_kv(0, table, nb, sdb, 6, dst_k=k, dst_v=v)
+    assert counts == dict(n_requests=8, n_local=0, n_cache=0, n_host=4, n_lost=0, n_invalid=4)
+    assert list(miss) == [0, 2, 4, 5]
+    for d in (1, 3):
+        assert (k[d * 32:(d + 1) * 32] == 0xEE).all()
+    assert W.check_tag(k[5 * 32:6 * 32], 13, W.CLS_KV, 0, 0, 4)
+
+
+# ---- experts (Section 4.3) --------------------------------------------------------------------------------
+
+def make_experts(n_layers=3, E=10, chunk=96, n_cache=12, n_local_per_layer=2, seed=0, lossy_local=False):
+    n = n_layers * E
+    oc = OracleClass(1, 1, chunk, n, n, n_cache, n_layers * n_local_per_layer, poison=True)
+    hs = W.rng(seed, 110).permutation(n)
+    local = np.zeros(n, bool)
+    for l in range(n_layers):
+        local[l * E + W.rng(seed, 111, l).permutation(E)[:n_local_per_layer]] = True
+    # registration is in id order, so tier changes run by run
+    ids = []
+    i = 0
+    while i < n:
+        j = i
+        while j < n and local[j] == local[i]:
+            j += 1
+        ids.extend(oc.register(j - i, hs[i:j], O.LOCAL if local[i] else O.HOST))
+        i = j
+    assert ids == list(range(n))
+    so = np.full(n, W.NO_OBJECT, np.uint32); so[hs] = np.arange(n)
+    W.fill_array(oc.plane(O.HOST, 0), so, seed, W.CLS_EXPERT, 0, W.FILL_TAG)
+    lo = np.full(oc.n_slots[O.LOCAL], W.NO_OBJECT, np.uint32)
+    for b in np.nonzero(local)[0]:
+        lo[oc.lookup(b)[1]] = b
+    W.fill_array(oc.plane(O.LOCAL, 0), lo, seed, W.CLS_EXPERT, 0, W.FILL_TAG)
+    oc.adopt(np.arange(n))
+    return oc, local
+
+
+def test_expert_fetch_union_ranks_and_bytes():
+    E, chunk, seed = 10, 96, 3
+    oc, local = make_experts(E=E, chunk=chunk, seed=seed)
+    host_only = [b for b in range(3 * E) if not local[b]]
+    oc.place(host_only[::2])
+    g = W.rng(seed, 5)
+    for layer in range(3):
+        topk = g.integers(0, E, size=(7, 2)).astype(np.int32)
+        staging, kind, where, miss, counts = oc.fetch_experts(layer, E, topk, E)
+        U = sorted(set(int(e) for e in topk.reshape(-1)))
+        assert [e for e in range(E) if kind[e] != O.UNSELECTED] == U
+        rank = 0
+        want_miss = []
+        for e in U:
+            b = layer * E + e
+            t, slot, _, _ = oc.lookup(b)
+            if t == O.LOCAL:
+                assert kind[e] == O.IN_PLACE and where[e] == slot
+                assert W.check_tag(oc.plane(O.LOCAL, 0)[0, slot], seed, W.CLS_EXPERT, 0, 0, b)
+            else:
+                assert kind[e] == O.STAGED and where[e] == rank
+                assert W.check_tag(staging[rank * chunk:(rank + 1) * chunk], seed, W.CLS_EXPERT, 0, 0, b)
+                if t == O.HOST:
+                    want_miss.append(e)
+                rank += 1
+        assert list(miss) == want_miss
+        assert counts["n_requests"] == len(U) and counts["n_local"] == sum(local[layer * E + e] for e in U)
+        assert (staging[rank * chunk:] == 0).all()                 # nothing beyond the used staging slots
+
+
+def test_expert_fetch_staging_overflow_invalid_ids_and_revocation():
+    E, chunk, seed = 6, 32, 4
+    oc, local = make_experts(n_layers=1, E=E, chunk=chunk, n_cache=6, n_local_per_layer=1, seed=seed)
+    non_local = [e for e in range(E) if not local[e]]
+    oc.place(non_local)
+    topk = np.array([[0, 1], [2, 3], [4, 5], [-1, 6]], np.int32)
+    staging, kind, where, miss, counts = oc.fetch_experts(0, E, topk, 3)
+    assert counts["n_invalid"] == 2 + (len(non_local) - 3) and counts["n_cache"] == 3 and miss.size == 0
+    assert [kind[e] for e in non_local] == [O.STAGED] * 3 + [O.OVERFLOW] * (len(non_local) - 3)
+    s_before, *_ = oc.fetch_experts(0, E, topk, E)
+    oc.revoke(non_local[1:3])
+    s_after, kind, where, miss, counts = oc.fetch_experts(0, E, topk, E)
+    assert np.array_equal(s_before, s_after) and list(miss) == non_local[1:3] and counts["n_host"] == 2
+
+
+def test_lossy_object_is_lost_after_revocation_and_leaves_dst_untouched():
+    oc = OracleClass(1, 1, 32, 4, 4, 2, 2, poison=True)
+    a = oc.register(1, None, O.LOCAL)[0]
+    with pytest.raises(OracleError):
+        oc.register(1, None, O.HOST)
+    b = oc.register(1, [0], O.HOST)[0]
+    oc.set_object(a, np.full(32, 7, np.uint8)); oc.set_object(b, np.full(32, 9, np.uint8))
+    assert list(oc.place([a, b])) == [O.OK, O.OK] and oc.lookup(a)[0] == O.LOCAL      # local stays local
+    with pytest.raises(OracleError) as e:                                             # cannot demote with no host copy
+        oc.evict(-1, [a], oc.plane(O.LOCAL, 0), None, [0], 2, O.EVICT_DEMOTE)
+    assert e.value.code == O.EINVAL
+
+
+# ---- random operation sequences: the invariants hold after every step ------------------------------------
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_operation_sequences_keep_tiered_and_plain_fetch_equal(seed):
+    chunk, L, n = 32, 2, 24
+    oc, ids, _ = make_kv(n_layers=L, chunk=chunk, n_obj=n, n_cache=9, n_local=0, seed=seed, poison=True,
+                         mode=W.FILL_NORMAL)
+    g = W.rng(seed, 200)
+    model_tier = {b: O.HOST for b in range(n)}
+    for step in range(60):
+        op = g.integers(0, 4)
+        sub = g.permutation(n)[:g.integers(1, 8)].astype(np.uint32)
+        if op == 0:
+            st = oc.place(sub)
+            for b, s in zip(sub, st):
+                if s == O.OK: model_tier[int(b)] = O.CACHE
+            assert sum(1 for t in model_tier.values() if t == O.CACHE) <= 9
+        elif op == 1:
+            oc.revoke(sub)
+            for b in sub: model_tier[int(b)] = O.HOST
+        elif op == 2:
+            layer = int(g.integers(-1, L))
+            nl = L if layer < 0 else 1
+            sk = g.integers(0, 256, size=nl * sub.size * chunk, dtype=np.uint8)
+            sv = g.integers(0, 256, size=nl * sub.size * chunk, dtype=np.uint8)
+            oc.evict(layer, sub, sk, sv, g.permutation(sub.size), sub.size)
+        table, n_blocks, sdb, cap = random_tables(n, 3, 7, seed * 1000 + step)
+        for layer in range(L):
+            k, v, miss, counts = oc.fetch_kv(layer, table, n_blocks, sdb, cap)
+            kp, vp, _, _ = oc.fetch_kv(layer, table, n_blocks, sdb, cap, plain=True)
+            assert np.array_equal(k, kp) and np.array_equal(v, vp)
+        for b in range(n):
+            assert oc.lookup(b)[0] == model_tier[b]
+        used = sorted(oc.lookup(b)[1] for b in range(n) if model_tier[b] == O.CACHE)
+        assert len(set(used)) == len(used)                           # no two objects share a slot
+
+
+def test_threads_do_not_change_the_result():
+    oc, ids, _ = make_kv(n_layers=1, chunk=256, n_obj=200, n_cache=120, seed=14, mode=W.FILL_NORMAL)
+    place_fraction(oc, ids, 0.6, 14)
+    table, n_blocks, sdb, cap = random_tables(200, 8, 40, 14)
+    a = oc.fetch_kv(0, table, n_blocks, sdb, cap, threads=1)
+    b = oc.fetch_kv(0, table, n_blocks, sdb, cap, threads=4)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and list(a[2]) == list(b[2]) and a[3] == b[3]
