@@ -1,0 +1,227 @@
+/*
+ * harvest.h - C ABI of the MI355X tiered cache fetch library (libharvest.so).
+ *
+ * The library implements the data path of Harvest (arxiv 2602.00328): objects
+ * (paged KV-cache blocks, MoE expert weights) live in one of three tiers -
+ * local HBM of the compute GPU, a cache tier in spare HBM that may be revoked
+ * at any time, and an authoritative copy in pinned host DRAM (paper Section
+ * 3.1).  A residency directory in device memory maps object -> (tier, slot,
+ * generation) (Section 4.3 "expert residency map", Section 5.2 "unified KV
+ * block table"), and fetches resolve every requested object through it inside
+ * HIP kernels and gather the bytes into the caller's working layout.
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  "d_" arguments are DEVICE pointers, "h_"/unprefixed
+ *     pointer arguments are HOST pointers.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the null stream).
+ *   - Ownership: all pools, destination / staging / source buffers and streams
+ *     belong to the caller and are only borrowed; they must outlive the
+ *     context (pools) or the enqueued work (buffers).  The library owns the
+ *     device directory, its per-stream scratch lists and its events.
+ *   - Data-moving calls are asynchronous: they enqueue on `stream` and return;
+ *     results are valid in stream order.  Directory edits made by place /
+ *     revoke / evict(DEMOTE) / register are visible to every fetch enqueued
+ *     after the call returns (place: on the same stream; other streams may
+ *     still see the older, equally correct, host entry for a while).
+ *   - Return value: HARVEST_OK (0) or a negative harvest_status.  A fetch never
+ *     fails because of residency (Section 3.1: correctness never depends on
+ *     the cache tier).
+ *   - No call mutates the directory except register / place / revoke /
+ *     evict(DEMOTE).  In particular a fetch never promotes an object (Section
+ *     4.3: on a miss the runtime does not fetch into the cache tier), and the
+ *     library never writes back on its own (Section 3.1: no dirty tracking).
+ *   - A context is not thread safe; operations that touch the same object from
+ *     different streams must be ordered by the caller.
+ *
+ * Pool layout (per class, per plane):  [layer][slot][chunk_bytes]  - an object
+ * occupies the same slot number in every layer and plane of its tier.  KV
+ * objects are logical blocks with planes K and V and one chunk per model layer;
+ * expert objects have one plane and one storage layer, and the object for
+ * (model layer l, expert e) must be number l * n_experts + e.
+ */
+#ifndef HARVEST_H
+#define HARVEST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct harvest_ctx harvest_ctx;   /* opaque, owned by the library */
+typedef uint32_t harvest_obj;             /* dense per-class object number, assigned by harvest_register */
+
+enum harvest_tier { HARVEST_HOST = 0, HARVEST_CACHE = 1, HARVEST_LOCAL = 2, HARVEST_NONE = 3 };
+
+enum harvest_status {
+    HARVEST_OK = 0,
+    HARVEST_EINVAL = -1,   /* bad argument; nothing was enqueued or changed */
+    HARVEST_ENOSPC = -2,   /* no free slot: NOT fatal for place - the object stays on the host (Figure 4) */
+    HARVEST_ENOENT = -3,   /* unknown object / class */
+    HARVEST_EHIP = -4,     /* a HIP runtime call failed */
+    HARVEST_ELOST = -5,    /* lossy object whose cache copy was revoked (Section 3.1) */
+    HARVEST_ENODEV = -6    /* data-moving call on a context created with HARVEST_FLAG_NO_DEVICE */
+};
+
+enum harvest_class { HARVEST_KV = 0, HARVEST_EXPERT = 1, HARVEST_N_CLASSES = 2 };
+
+enum harvest_flags {
+    HARVEST_FLAG_NO_DEVICE = 1,  /* directory bookkeeping only (no HIP call at all): for host-side tests */
+    HARVEST_FLAG_POISON = 2,     /* revoke overwrites the freed cache slot with 0xA5 after the drain */
+    HARVEST_FLAG_PROFILE = 4     /* bracket the gather kernels with events; read them with harvest_profile */
+};
+
+enum harvest_evict_flags {
+    HARVEST_EVICT_DEMOTE = 1     /* local objects leave local HBM after the write-back: directory -> HOST, slot freed */
+};
+
+/* Invoked on the thread calling harvest_revoke, after the entry has been invalidated, in-flight work on the slot
+ * has drained and the slot has been freed (Section 3.2). */
+typedef void (*harvest_revoke_cb)(int cls, harvest_obj id, void *user);
+
+typedef struct harvest_class_config {
+    uint32_t n_layers;        /* chunks per object per plane; 0 = class unused */
+    uint32_t n_planes;        /* 1 or 2 */
+    uint64_t chunk_bytes;     /* multiple of 16 */
+    uint32_t max_objects;
+    uint32_t n_host_slots, n_cache_slots, n_local_slots;
+    uint32_t n_experts;       /* HARVEST_EXPERT only: experts per model layer */
+    void *host_pool[2];       /* pinned (hipHostMalloc) host memory, per plane; NULL iff n_host_slots == 0 */
+    void *d_cache_pool[2];    /* device memory, per plane; 256-byte aligned */
+    void *d_local_pool[2];    /* device memory, per plane; 256-byte aligned */
+} harvest_class_config;
+
+typedef struct harvest_config {
+    uint32_t flags;                 /* harvest_flags */
+    int32_t device;                 /* HIP device ordinal the pools live on */
+    harvest_class_config cls[HARVEST_N_CLASSES];
+    uint32_t gather_wg_per_cu;      /* persistent workgroups per CU for the HBM-tier gather; 0 = default */
+    uint32_t host_wgs;              /* workgroups of the host-tier (PCIe) gather; 0 = default */
+    uint32_t reserved[6];           /* must be 0 */
+} harvest_config;
+
+typedef struct harvest_fetch_counts {
+    uint64_t n_requests;  /* requests examined (KV: sum of clamped n_blocks; experts: size of the distinct set) */
+    uint64_t n_local;     /* served from local HBM (experts: used in place, no bytes moved) */
+    uint64_t n_cache;     /* served from the cache tier */
+    uint64_t n_host;      /* served from the host copy (the miss list) */
+    uint64_t n_lost;      /* lossy and revoked: destination left untouched */
+    uint64_t n_invalid;   /* skipped: unknown object, destination out of range, staging full */
+} harvest_fetch_counts;
+
+typedef struct harvest_stats_t {
+    harvest_fetch_counts fetch[HARVEST_N_CLASSES];   /* running totals over all fetches */
+    uint64_t n_placed[HARVEST_N_CLASSES], n_place_enospc[HARVEST_N_CLASSES];
+    uint64_t n_revoked[HARVEST_N_CLASSES], n_evicted[HARVEST_N_CLASSES], n_demoted[HARVEST_N_CLASSES];
+    uint64_t cache_slots_in_use[HARVEST_N_CLASSES], local_slots_in_use[HARVEST_N_CLASSES];
+} harvest_stats_t;
+
+typedef struct harvest_profile_t {
+    uint64_t hbm_launches;  double hbm_ms;    /* HBM-tier gather kernel: launches and summed event time */
+    uint64_t host_launches; double host_ms;   /* host-tier gather kernel */
+} harvest_profile_t;
+
+/* ---- life cycle ------------------------------------------------------------------------------------------- */
+
+/* Creates a context over caller-owned pools.  Allocates the device directory (8 bytes per object).  EINVAL on
+ * misaligned / missing pools or chunk_bytes % 16 != 0; EHIP if the device cannot be used. */
+int harvest_create(const harvest_config *cfg, harvest_ctx **out);
+
+/* Waits for all work the library enqueued, frees everything the library owns. */
+int harvest_destroy(harvest_ctx *ctx);
+
+/* ---- directory (Sections 3.1, 3.2, 4.3) ------------------------------------------------------------------- */
+
+/* Registers n new objects of class cls; they get consecutive numbers, written to out_ids (may be NULL).
+ * tier = HARVEST_HOST: the object lives in its host slot (Section 4.3: at start "the remaining experts reside in
+ * host DRAM").  tier = HARVEST_LOCAL: the object takes the lowest free local slot (Section 4.3: "a user-defined
+ * subset ... is loaded into local HBM"); the caller then fills that slot (see harvest_lookup).
+ * host_slot[i] = slot of the authoritative host copy (backed mode, Section 3.1); host_slot == NULL registers lossy
+ * objects, allowed for HARVEST_LOCAL only.  cb/user: revocation callback for these objects (may be NULL).
+ * All-or-nothing: EINVAL (slot out of range / already owned / repeated), ENOSPC (max_objects or local pool
+ * exhausted).  Synchronous. */
+int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_slot, int tier,
+                     harvest_revoke_cb cb, void *user, harvest_obj *out_ids);
+
+/* Host-side copy of one directory entry.  slot = cache / local slot, or -1.  ENOENT for unknown ids. */
+int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t *slot, uint32_t *gen,
+                   int64_t *host_slot);
+
+/* Placement = the paper's harvest_alloc + explicit migration + placement-map update (Sections 3.2, 4.3): for each
+ * id on the host, take the lowest free cache slot, copy host copy -> slot on `stream`, then publish
+ * (CACHE, slot, gen+1).  per_obj_status[i] (may be NULL): OK (also for objects already in HBM: no-op), ENOSPC (cache
+ * pool full - object stays on the host), ELOST, EINVAL (lossy object).  The call fails as a whole, changing
+ * nothing, only for unknown ids (ENOENT). */
+int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *per_obj_status);
+
+/* Revocation (Section 3.2, "explicit and ordered"): for each id in the cache tier: publish (HOST, gen+1) - or
+ * (NONE) for a lossy object -, wait until every fetch / evict / place enqueued so far on any stream this context
+ * has seen has completed (the drain), free the slot (poison it if asked), then invoke the callback.  Ids not in the
+ * cache tier are skipped.  Synchronous; ENOENT for unknown ids (nothing changed). */
+int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n);
+
+/* ---- fetch (Sections 4.3, 5.2) ---------------------------------------------------------------------------- */
+
+/* KV fetch (Section 5.2: resolve each required block through the block table, reload what is not local).
+ * Request r = s * max_blocks + j, for j < min(max(d_n_blocks[s], 0), max_blocks), asks for block
+ * d_block_table[r]; its K chunk of `layer` is copied to d_dst_k + (d_seq_dst_block[s] + j) * chunk_bytes and its V
+ * chunk likewise into d_dst_v.  d_dst_k / d_dst_v hold dst_capacity_blocks chunks each.  Requests naming an unknown
+ * block or a destination >= dst_capacity_blocks are skipped and counted; lost blocks leave the destination
+ * untouched.  HBM-tier requests run on `stream`, host-tier requests on a library-owned side stream that is joined
+ * back before this call's work on `stream` ends.  EINVAL: layer out of range, class unused, n_seq * max_blocks
+ * >= 2^31. */
+int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                     uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                     const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream);
+
+/* Expert fetch (Section 4.3: experts are paged whole and must be resident before the FFN runs).  U = the distinct
+ * valid expert numbers in d_topk_ids[n_tokens][k].  For e in U ascending: a local expert is used in place
+ * (d_expert_ptr[e] = its address in the local pool, no bytes move); a cache- or host-tier expert is copied into
+ * staging slot r = number of earlier staged members of U (d_expert_ptr[e] = d_staging + r * chunk_bytes), or, when
+ * r >= n_staging_slots, skipped and counted invalid (pointer NULL); a lost expert gets NULL.  Experts not in U get
+ * NULL.  d_expert_ptr has n_experts entries. */
+int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,
+                          void *d_staging, uint32_t n_staging_slots, void **d_expert_ptr, void *stream);
+
+/* Synchronises `stream` and reports the last fetch enqueued on it: its counts and its miss list (requests served
+ * from host or lost: KV request numbers r, or expert numbers e; order unspecified).  miss_idx may be NULL; at most
+ * miss_cap entries are written, *n_miss receives the full count. */
+int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
+                       uint32_t miss_cap, uint32_t *n_miss);
+
+/* ---- write-back (Sections 5.1, 5.2) ----------------------------------------------------------------------- */
+
+/* Eviction / write-back: the source bytes become the value of each object: they are written to its host slot (when
+ * backed) and to the HBM slot the directory names, so every copy stays identical.  ids and src_block are HOST
+ * arrays of n entries.  layer >= 0: that layer only, each source plane is [src_layer_stride][chunk_bytes];
+ * layer < 0: all layers, each source plane is [n_layers][src_layer_stride][chunk_bytes].  Object i reads source
+ * chunk src_block[i] (< src_layer_stride).  d_src1 is ignored for one-plane classes.  HARVEST_EVICT_DEMOTE (all
+ * layers, or a one-layer class): local objects leave local HBM - slot freed, directory -> (HOST, gen+1) once the
+ * copy is done; the source may be the local pool itself.  EINVAL: repeated id, src_block out of range, demoting a
+ * lossy object; ENOENT; ELOST.  On error nothing is enqueued or changed. */
+int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, uint32_t n, const void *d_src0,
+                  const void *d_src1, const uint64_t *src_block, uint64_t src_layer_stride, int flags, void *stream);
+
+/* ---- introspection ---------------------------------------------------------------------------------------- */
+
+/* Running totals.  Synchronises the streams the context has seen. */
+int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out);
+
+/* With HARVEST_FLAG_PROFILE: synchronises, returns and resets the event timings of the gather kernels. */
+int harvest_profile(harvest_ctx *ctx, harvest_profile_t *out);
+
+/* A plain contiguous device copy with the gather kernel's inner loop (bytes % 16 == 0): the achievable ceiling the
+ * gather is compared with, and the known-size kernel used to calibrate hardware byte counters. */
+int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *stream);
+
+/* Pinned host memory of exactly `bytes` bytes (hipHostMalloc, mapped); NULL on failure. */
+void *harvest_pinned_alloc(size_t bytes);
+int harvest_pinned_free(void *p);
+
+const char *harvest_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARVEST_H */

@@ -1,0 +1,135 @@
+"""TEST INFRASTRUCTURE - adapts the CPU oracle to the harness interface the scenario drivers use.
+
+``kv_layers`` restricts the KV class to a subset of model layers (layers are independent in every operation, so an
+oracle that materialises only layer L is a complete oracle for the fetches of layer L); this keeps a full-size check
+within host memory.  Calls that concern other layers are ignored.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as W
+from . import OracleClass, HOST, CACHE, LOCAL, NONE, EVICT_DEMOTE, IN_PLACE, STAGED  # noqa: F401
+
+KV, EXPERT = 0, 1
+
+
+class OracleEngine:
+    name = "oracle"
+
+    def __init__(self, kv=None, expert=None, poison=False, kv_layers=None, threads=1):
+        """kv / expert: objects with n_layers, n_planes, chunk_bytes, max_objects, n_host_slots, n_cache_slots,
+        n_local_slots (and n_experts)."""
+        self.spec = {KV: kv, EXPERT: expert}
+        self.threads = threads
+        self.kv_layers = list(range(kv.n_layers)) if (kv is not None and kv_layers is None) else kv_layers
+        self.c = {}
+        for k, sp in self.spec.items():
+            if sp is None:
+                continue
+            nl = len(self.kv_layers) if k == KV else sp.n_layers
+            self.c[k] = OracleClass(nl, sp.n_planes, sp.chunk_bytes, sp.max_objects, sp.n_host_slots,
+                                    sp.n_cache_slots, sp.n_local_slots, poison)
+
+    def close(self):
+        for c in self.c.values():
+            c.close()
+
+    def _layers(self, cls):
+        return self.kv_layers if cls == KV else list(range(self.spec[cls].n_layers))
+
+    # ---- harness-side initialisation -----------------------------------------------------------------------
+    def fill_host(self, cls, slot_object, seed, wl_cls, mode, sigma):
+        self._fill(cls, HOST, slot_object, seed, wl_cls, mode, sigma)
+
+    def fill_local(self, cls, slot_object, seed, wl_cls, mode, sigma):
+        self._fill(cls, LOCAL, slot_object, seed, wl_cls, mode, sigma)
+
+    def _fill(self, cls, tier, slot_object, seed, wl_cls, mode, sigma):
+        c = self.c[cls]
+        for p in range(c.n_planes):
+            plane = c.plane(tier, p)
+            for i, layer in enumerate(self._layers(cls)):      # chunks are keyed by their absolute layer number
+                W.fill_array(plane[i:i + 1], slot_object, seed, wl_cls, p, mode, sigma, layer_base=layer)
+
+    def adopt(self, cls, ids):
+        self.c[cls].adopt(ids)
+
+    def write_local(self, cls, obj, plane, layer, offset, data):
+        if layer in self._layers(cls):
+            self.c[cls].write_local(obj, plane, self._layers(cls).index(layer), offset, data)
+
+    # ---- directory ---------------------------------------------------------------------------------------------
+    def register(self, cls, n, host_slots=None, tier=HOST):
+        return self.c[cls].register(n, host_slots, tier)
+
+    def lookup(self, cls, obj):
+        return self.c[cls].lookup(obj)
+
+    def place(self, cls, ids):
+        return self.c[cls].place(ids)
+
+    def revoke(self, cls, ids):
+        c = self.c[cls]
+        n0 = len(c.revoked_log)
+        c.revoke(ids)
+        return c.revoked_log[n0:]
+
+    # ---- data path -------------------------------------------------------------------------------------------
+    def has_layer(self, layer):
+        return layer in self.kv_layers
+
+    def fetch_kv(self, layer, table, n_blocks, seq_dst_block, cap):
+        """-> (k bytes, v bytes, sorted miss list, counts) as numpy / dict."""
+        c = self.c[KV]
+        k, v, miss, counts = c.fetch_kv(self.kv_layers.index(layer), table, n_blocks, seq_dst_block, cap,
+                                        threads=self.threads)
+        return k, v, np.sort(miss), counts
+
+    def fetch_experts(self, layer, topk, n_staging):
+        """-> (list over experts: None or the expert's bytes as the FFN would see them, kinds, sorted miss, counts)."""
+        c = self.c[EXPERT]
+        E = self.spec[EXPERT].n_experts
+        staging, kind, where, miss, counts = c.fetch_experts(layer, E, topk, n_staging)
+        out = []
+        for e in range(E):
+            if kind[e] == IN_PLACE:
+                out.append(c.plane(LOCAL, 0)[0, where[e]].copy())
+            elif kind[e] == STAGED:
+                out.append(staging[where[e] * c.chunk_bytes:(where[e] + 1) * c.chunk_bytes].copy())
+            else:
+                out.append(None)
+        return out, kind, where, np.sort(miss), counts
+
+    # begin/end pairs: a CPU has nothing in flight, so "begin" does the work
+    def fetch_kv_begin(self, *a, **k):
+        return self.fetch_kv(*a, **k)
+
+    def fetch_experts_begin(self, *a, **k):
+        return self.fetch_experts(*a, **k)
+
+    def fetch_end(self, handle):
+        return handle
+
+    def evict(self, cls, layer, ids, src0, src1, src_block, stride, flags=0):
+        """src planes: numpy uint8, [stride][chunk] (layer >= 0) or [n_layers][stride][chunk] (layer < 0)."""
+        c = self.c[cls]
+        layers = self._layers(cls)
+        if layer >= 0:
+            if layer in layers:
+                c.evict(layers.index(layer), ids, src0, src1, src_block, stride, flags)
+            return
+        chunk = c.chunk_bytes
+        sel = lambda a: None if a is None else np.ascontiguousarray(
+            np.asarray(a, dtype=np.uint8).reshape(self.spec[cls].n_layers, stride, chunk)[layers])
+        c.evict(-1, ids, sel(src0), sel(src1), src_block, stride, flags)
+
+    def evict_from_local(self, cls, ids, flags=0):
+        """Write back local objects, the source being their own local slots (all layers)."""
+        c = self.c[cls]
+        slots = [c.lookup(i)[1] for i in ids]
+        c.evict(-1, ids, c.plane(LOCAL, 0), c.plane(LOCAL, 1) if c.n_planes == 2 else None, slots, c.n_slots[LOCAL],
+                flags)
+
+    def tier_plane(self, cls, tier, plane=0):
+        return self.c[cls].plane(tier, plane)

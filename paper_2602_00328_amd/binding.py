@@ -1,0 +1,278 @@
+"""ctypes binding of libharvest.so: the same names as include/harvest.h, argument marshalling only.
+
+Every step of the fetch path runs inside the library's HIP kernels; this module never touches payload bytes.  PyTorch
+is used by the ``Harvest`` convenience class for device memory and streams only.  If the library has not been built
+the import of this module fails loudly - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import _build
+
+HOST, CACHE, LOCAL, NONE = 0, 1, 2, 3
+OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV = 0, -1, -2, -3, -4, -5, -6
+KV, EXPERT = 0, 1
+FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE = 1, 2, 4
+EVICT_DEMOTE = 1
+
+u32, u64, i32, i64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+
+
+class harvest_class_config(ctypes.Structure):
+    _fields_ = [("n_layers", u32), ("n_planes", u32), ("chunk_bytes", u64), ("max_objects", u32),
+                ("n_host_slots", u32), ("n_cache_slots", u32), ("n_local_slots", u32), ("n_experts", u32),
+                ("host_pool", vp * 2), ("d_cache_pool", vp * 2), ("d_local_pool", vp * 2)]
+
+
+class harvest_config(ctypes.Structure):
+    _fields_ = [("flags", u32), ("device", i32), ("cls", harvest_class_config * 2),
+                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("reserved", u32 * 6)]
+
+
+class harvest_fetch_counts(ctypes.Structure):
+    _fields_ = [(n, u64) for n in ("n_requests", "n_local", "n_cache", "n_host", "n_lost", "n_invalid")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class harvest_stats_t(ctypes.Structure):
+    _fields_ = [("fetch", harvest_fetch_counts * 2), ("n_placed", u64 * 2), ("n_place_enospc", u64 * 2),
+                ("n_revoked", u64 * 2), ("n_evicted", u64 * 2), ("n_demoted", u64 * 2),
+                ("cache_slots_in_use", u64 * 2), ("local_slots_in_use", u64 * 2)]
+
+
+class harvest_profile_t(ctypes.Structure):
+    _fields_ = [("hbm_launches", u64), ("hbm_ms", ctypes.c_double), ("host_launches", u64),
+                ("host_ms", ctypes.c_double)]
+
+
+REVOKE_CB = ctypes.CFUNCTYPE(None, ctypes.c_int, u32, vp)
+
+SYMBOLS = {
+    "harvest_create": (ctypes.c_int, [ctypes.POINTER(harvest_config), ctypes.POINTER(vp)]),
+    "harvest_destroy": (ctypes.c_int, [vp]),
+    "harvest_register": (ctypes.c_int, [vp, ctypes.c_int, u32, vp, ctypes.c_int, REVOKE_CB, vp, vp]),
+    "harvest_lookup": (ctypes.c_int, [vp, ctypes.c_int, u32, vp, vp, vp, vp]),
+    "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
+    "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
+    "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
+    "harvest_fetch_experts": (ctypes.c_int, [vp, u32, vp, u32, u32, vp, u32, vp, vp]),
+    "harvest_fetch_info": (ctypes.c_int, [vp, vp, ctypes.POINTER(harvest_fetch_counts), vp, u32, vp]),
+    "harvest_evict": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, vp, u32, vp, vp, vp, u64, ctypes.c_int, vp]),
+    "harvest_stats": (ctypes.c_int, [vp, ctypes.POINTER(harvest_stats_t)]),
+    "harvest_profile": (ctypes.c_int, [vp, ctypes.POINTER(harvest_profile_t)]),
+    "harvest_plain_copy": (ctypes.c_int, [vp, vp, u64, vp]),
+    "harvest_pinned_alloc": (vp, [ctypes.c_size_t]),
+    "harvest_pinned_free": (ctypes.c_int, [vp]),
+    "harvest_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+
+def _load():
+    if not os.path.exists(_build.LIB_PATH):
+        raise ImportError(f"{_build.LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc, gfx950). There is no fallback for the HIP library.")
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    for name, (res, args) in SYMBOLS.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+LIB_PATH = _build.LIB_PATH
+
+
+class HarvestError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {lib.harvest_strerror(code).decode()} ({code})")
+        self.code = code
+
+
+def _chk(rc, what):
+    if rc != OK:
+        raise HarvestError(rc, what)
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(vp)
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return vp(t)
+    return vp(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return vp(stream)
+    return vp(stream.cuda_stream)
+
+
+@dataclass
+class ClassSpec:
+    n_layers: int
+    n_planes: int
+    chunk_bytes: int
+    max_objects: int
+    n_host_slots: int
+    n_cache_slots: int
+    n_local_slots: int
+    n_experts: int = 0
+
+
+class Harvest:
+    """A library context plus the pools it borrows (allocated here with torch / harvest_pinned_alloc)."""
+
+    def __init__(self, kv: ClassSpec | None = None, expert: ClassSpec | None = None, flags: int = 0, device: int = 0,
+                 gather_wg_per_cu: int = 0, host_wgs: int = 0):
+        self.flags, self.device = flags, device
+        self.spec = {KV: kv, EXPERT: expert}
+        self.no_device = bool(flags & FLAG_NO_DEVICE)
+        self._host_ptr = {}        # (cls, plane) -> address
+        self._host_np = {}
+        self._dev = {}             # (cls, tier, plane) -> torch tensor
+        self.revoked_log = []      # (cls, id) in callback order
+        self._cb = REVOKE_CB(lambda c, i, _u: self.revoked_log.append((int(c), int(i))))
+        cfg = harvest_config()
+        cfg.flags, cfg.device = flags, device
+        cfg.gather_wg_per_cu, cfg.host_wgs = gather_wg_per_cu, host_wgs
+        for k, sp in self.spec.items():
+            if sp is None:
+                continue
+            cc = cfg.cls[k]
+            cc.n_layers, cc.n_planes, cc.chunk_bytes = sp.n_layers, sp.n_planes, sp.chunk_bytes
+            cc.max_objects, cc.n_experts = sp.max_objects, sp.n_experts
+            cc.n_host_slots, cc.n_cache_slots, cc.n_local_slots = sp.n_host_slots, sp.n_cache_slots, sp.n_local_slots
+            if self.no_device:
+                continue
+            import torch
+            dev = torch.device("cuda", device)
+            for p in range(sp.n_planes):
+                nbytes = sp.n_layers * sp.n_host_slots * sp.chunk_bytes
+                if nbytes:
+                    ptr = lib.harvest_pinned_alloc(nbytes)
+                    if not ptr:
+                        raise HarvestError(EHIP, f"pinned allocation of {nbytes} bytes")
+                    self._host_ptr[(k, p)] = ptr
+                    buf = (ctypes.c_uint8 * nbytes).from_address(ptr)
+                    self._host_np[(k, p)] = np.frombuffer(buf, dtype=np.uint8).reshape(
+                        sp.n_layers, sp.n_host_slots, sp.chunk_bytes)
+                    cc.host_pool[p] = ptr
+                for tier, n_slots, field in ((CACHE, sp.n_cache_slots, cc.d_cache_pool),
+                                             (LOCAL, sp.n_local_slots, cc.d_local_pool)):
+                    if n_slots:
+                        t = torch.zeros((sp.n_layers, n_slots, sp.chunk_bytes), dtype=torch.uint8, device=dev)
+                        self._dev[(k, tier, p)] = t
+                        field[p] = t.data_ptr()
+        h = vp()
+        _chk(lib.harvest_create(ctypes.byref(cfg), ctypes.byref(h)), "harvest_create")
+        self.h = h
+
+    # ---- pools ------------------------------------------------------------------------------------------------
+    def host_plane(self, cls, plane=0) -> np.ndarray:
+        return self._host_np[(cls, plane)]
+
+    def host_ptr(self, cls, plane=0) -> int:
+        return self._host_ptr[(cls, plane)]
+
+    def dev_plane(self, cls, tier, plane=0):
+        return self._dev[(cls, tier, plane)]
+
+    def close(self):
+        if getattr(self, "h", None):
+            _chk(lib.harvest_destroy(self.h), "harvest_destroy")
+            self.h = None
+            self._host_np.clear()
+            for ptr in self._host_ptr.values():
+                lib.harvest_pinned_free(ptr)
+            self._host_ptr.clear()
+            self._dev.clear()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- directory ----------------------------------------------------------------------------------------------
+    def register(self, cls, n, host_slots=None, tier=HOST) -> np.ndarray:
+        hs = None if host_slots is None else np.ascontiguousarray(host_slots, dtype=np.int64)
+        out = np.empty(n, dtype=np.uint32)
+        _chk(lib.harvest_register(self.h, cls, n, _np_ptr(hs), tier, self._cb, None, _np_ptr(out)), "harvest_register")
+        return out
+
+    def lookup(self, cls, obj):
+        t, s, g, hs = ctypes.c_int(), i64(), u32(), i64()
+        _chk(lib.harvest_lookup(self.h, cls, int(obj), ctypes.byref(t), ctypes.byref(s), ctypes.byref(g),
+                                ctypes.byref(hs)), "harvest_lookup")
+        return t.value, s.value, g.value, hs.value
+
+    def place(self, cls, ids, stream=None) -> np.ndarray:
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        st = np.zeros(ids.size, dtype=np.int32)
+        sp = vp(0) if self.no_device else _stream_ptr(stream)
+        _chk(lib.harvest_place(self.h, cls, _np_ptr(ids), ids.size, sp, _np_ptr(st)), "harvest_place")
+        return st
+
+    def revoke(self, cls, ids):
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        _chk(lib.harvest_revoke(self.h, cls, _np_ptr(ids), ids.size), "harvest_revoke")
+
+    # ---- data path ----------------------------------------------------------------------------------------------
+    def fetch_kv(self, layer, d_table, d_n_blocks, d_dst_k, d_dst_v, d_seq_dst_block, dst_capacity_blocks, stream=None):
+        """d_table int32 [n_seq][max_blocks], d_n_blocks int32 [n_seq], d_seq_dst_block int64/uint64 [n_seq]: torch
+        device tensors."""
+        n_seq, max_blocks = d_table.shape
+        _chk(lib.harvest_fetch_kv(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
+                                  _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block), dst_capacity_blocks,
+                                  _stream_ptr(stream)), "harvest_fetch_kv")
+
+    def fetch_experts(self, layer, d_topk, d_staging, n_staging_slots, d_expert_ptr, stream=None):
+        n_tokens, k = d_topk.shape
+        _chk(lib.harvest_fetch_experts(self.h, layer, _dev_ptr(d_topk), n_tokens, k, _dev_ptr(d_staging),
+                                       n_staging_slots, _dev_ptr(d_expert_ptr), _stream_ptr(stream)),
+             "harvest_fetch_experts")
+
+    def fetch_info(self, stream=None, miss_cap=0):
+        counts = harvest_fetch_counts()
+        miss = np.zeros(max(1, miss_cap), dtype=np.uint32)
+        n_miss = u32()
+        _chk(lib.harvest_fetch_info(self.h, _stream_ptr(stream), ctypes.byref(counts), _np_ptr(miss), miss_cap,
+                                    ctypes.byref(n_miss)), "harvest_fetch_info")
+        return counts.as_dict(), miss[:min(n_miss.value, miss_cap)].copy(), n_miss.value
+
+    def evict(self, cls, layer, ids, d_src0, d_src1, src_block, src_layer_stride, flags=0, stream=None):
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        sb = np.ascontiguousarray(src_block, dtype=np.uint64)
+        assert sb.shape == ids.shape
+        sp = vp(0) if self.no_device else _stream_ptr(stream)
+        _chk(lib.harvest_evict(self.h, cls, layer, _np_ptr(ids), ids.size, _dev_ptr(d_src0), _dev_ptr(d_src1),
+                               _np_ptr(sb), src_layer_stride, flags, sp), "harvest_evict")
+
+    # ---- introspection ------------------------------------------------------------------------------------------
+    def stats(self) -> harvest_stats_t:
+        out = harvest_stats_t()
+        _chk(lib.harvest_stats(self.h, ctypes.byref(out)), "harvest_stats")
+        return out
+
+    def profile(self) -> harvest_profile_t:
+        out = harvest_profile_t()
+        _chk(lib.harvest_profile(self.h, ctypes.byref(out)), "harvest_profile")
+        return out
+
+
+def plain_copy(d_dst, d_src, nbytes, stream=None):
+    _chk(lib.harvest_plain_copy(_dev_ptr(d_dst), _dev_ptr(d_src), nbytes, _stream_ptr(stream)), "harvest_plain_copy")

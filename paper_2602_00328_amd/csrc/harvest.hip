@@ -1,0 +1,830 @@
+// Host side of libharvest.so: the C ABI of include/harvest.h over the kernels in kernels.h.
+//
+// Structure
+//   ClassState  - per object class: host mirror of the directory, slot allocators, device directory.
+//   StreamState - per caller stream: device scratch (HBM list, host list, miss list, counters), a side stream for
+//                 the host-tier gather, fork/join events and the "last operation" event the revocation drain waits on.
+//   Staging     - pinned host blocks through which host-built lists reach the device without blocking the caller.
+//   ctl stream  - the single writer of the device directory: every directory edit is a dir_write kernel on it, so
+//                 edits reach the device in the order the host made them (paper Section 3.2: revocation is ordered).
+#include "../../include/harvest.h"
+#include "kernels.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <set>
+#include <unordered_set>
+#include <vector>
+
+using namespace hv;
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess) {                                                                         \
+            fprintf(stderr, "libharvest: %s failed: %s (%s:%d)\n", #expr, hipGetErrorString(e_), __FILE__, \
+                    __LINE__);                                                                          \
+            return HARVEST_EHIP;                                                                        \
+        }                                                                                               \
+    } while (0)
+
+namespace {
+
+struct ClassState {
+    harvest_class_config cfg{};
+    bool used = false;
+    uint64_t host_dev[2] = { 0, 0 };        // device-visible address of the pinned host pool planes
+    uint32_t n_objects = 0;
+    std::vector<uint8_t> tier;              // mirror of the directory
+    std::vector<int64_t> slot;              // cache / local slot or -1
+    std::vector<uint32_t> gen;
+    std::vector<int64_t> host_slot;         // -1 = lossy
+    std::vector<harvest_revoke_cb> cb;
+    std::vector<void *> cb_user;
+    std::vector<uint8_t> host_used;
+    std::set<uint32_t> cache_free, local_free;   // begin() = lowest free slot
+    uint64_t *d_dir = nullptr;
+    // host-side statistics
+    uint64_t n_placed = 0, n_enospc = 0, n_revoked = 0, n_evicted = 0, n_demoted = 0;
+
+    uint64_t packed(uint32_t id) const
+    {
+        uint32_t t = tier[id];
+        uint32_t s = t == T_HOST ? (uint32_t)host_slot[id] : (t == T_NONE ? 0u : (uint32_t)slot[id]);
+        return make_entry(t, s, gen[id]);
+    }
+    uint64_t addr(int t, uint32_t plane, uint32_t layer, uint64_t s) const
+    {
+        uint64_t base = t == T_HOST ? host_dev[plane]
+                                    : (t == T_CACHE ? (uint64_t)cfg.d_cache_pool[plane] : (uint64_t)cfg.d_local_pool[plane]);
+        uint64_t ns = t == T_HOST ? cfg.n_host_slots : (t == T_CACHE ? cfg.n_cache_slots : cfg.n_local_slots);
+        return base + ((uint64_t)layer * ns + s) * cfg.chunk_bytes;
+    }
+};
+
+struct Staging {
+    void *h = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool busy = false;
+};
+
+struct ProfPair { hipEvent_t a, b; int which; };
+
+struct StreamState {
+    hipStream_t s = nullptr;
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, last = nullptr, ctl_done = nullptr, pre_ctl = nullptr;
+    bool last_valid = false;
+    // fetch scratch
+    uint32_t req_cap = 0;
+    Item *hbm_items = nullptr, *host_items = nullptr;
+    uint32_t *miss_idx = nullptr;
+    uint32_t *cnt = nullptr;                // [2][C_N], ping-pong
+    int cur = 0;                            // buffer the NEXT fetch uses
+    int last_cur = -1;                      // buffer of the last fetch (-1: none yet)
+    // control scratch (host-built lists)
+    void *ctl_buf = nullptr;
+    size_t ctl_cap = 0;
+};
+
+}  // namespace
+
+struct harvest_ctx {
+    harvest_config cfg{};
+    bool no_device = false, poison = false, profile = false;
+    int n_cu = 256;
+    uint32_t gather_grid = 0, host_grid = 0;
+    ClassState cls[HARVEST_N_CLASSES];
+    hipStream_t ctl = nullptr;
+    unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
+    std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
+    std::deque<Staging> staging;          // deque: references stay valid when it grows
+    std::vector<ProfPair> prof;
+    std::vector<hipEvent_t> prof_pool;
+    std::mutex mu;
+};
+
+namespace {
+
+int device_guard(harvest_ctx *ctx)
+{
+    if (ctx->no_device) return HARVEST_OK;
+    HIP_TRY(hipSetDevice(ctx->cfg.device));
+    return HARVEST_OK;
+}
+
+int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
+{
+    hipStream_t s = (hipStream_t)stream;
+    auto it = ctx->streams.find(s);
+    if (it != ctx->streams.end()) { *out = it->second.get(); return HARVEST_OK; }
+    auto ss = std::make_unique<StreamState>();
+    ss->s = s;
+    HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
+    for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last, &ss->ctl_done, &ss->pre_ctl })
+        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    HIP_TRY(hipMalloc(&ss->cnt, 2 * C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(ss->cnt, 0, 2 * C_N * sizeof(uint32_t)));
+    *out = ss.get();
+    ctx->streams[s] = std::move(ss);
+    return HARVEST_OK;
+}
+
+int ensure_req_cap(StreamState *ss, uint32_t n_req)
+{
+    if (n_req <= ss->req_cap) return HARVEST_OK;
+    // growing: earlier work on this stream may still read the old lists
+    HIP_TRY(hipStreamSynchronize(ss->s));
+    HIP_TRY(hipStreamSynchronize(ss->side));
+    if (ss->hbm_items) HIP_TRY(hipFree(ss->hbm_items));
+    if (ss->host_items) HIP_TRY(hipFree(ss->host_items));
+    if (ss->miss_idx) HIP_TRY(hipFree(ss->miss_idx));
+    ss->hbm_items = ss->host_items = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
+    uint32_t cap = std::max<uint32_t>(1024, n_req + n_req / 4);
+    HIP_TRY(hipMalloc(&ss->hbm_items, (size_t)cap * 2 * sizeof(Item)));
+    HIP_TRY(hipMalloc(&ss->host_items, (size_t)cap * 2 * sizeof(Item)));
+    HIP_TRY(hipMalloc(&ss->miss_idx, (size_t)cap * sizeof(uint32_t)));
+    ss->req_cap = cap;
+    return HARVEST_OK;
+}
+
+int ensure_ctl_cap(StreamState *ss, size_t bytes)
+{
+    if (bytes <= ss->ctl_cap) return HARVEST_OK;
+    HIP_TRY(hipStreamSynchronize(ss->s));
+    if (ss->ctl_buf) HIP_TRY(hipFree(ss->ctl_buf));
+    ss->ctl_buf = nullptr; ss->ctl_cap = 0;
+    size_t cap = std::max<size_t>(1 << 16, bytes + bytes / 4);
+    HIP_TRY(hipMalloc(&ss->ctl_buf, cap));
+    ss->ctl_cap = cap;
+    return HARVEST_OK;
+}
+
+// A pinned block nobody on the device still reads.
+int acquire_staging(harvest_ctx *ctx, size_t bytes, Staging **out)
+{
+    for (auto &st : ctx->staging) {
+        if (st.cap < bytes) continue;
+        if (st.busy) {
+            hipError_t q = hipEventQuery(st.done);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) return HARVEST_EHIP;
+            st.busy = false;
+        }
+        *out = &st;
+        return HARVEST_OK;
+    }
+    Staging st;
+    st.cap = std::max<size_t>(1 << 16, bytes);
+    HIP_TRY(hipHostMalloc(&st.h, st.cap, hipHostMallocDefault));
+    HIP_TRY(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
+    ctx->staging.push_back(st);
+    *out = &ctx->staging.back();
+    return HARVEST_OK;
+}
+
+int release_after(Staging *st, hipStream_t s)
+{
+    HIP_TRY(hipEventRecord(st->done, s));
+    st->busy = true;
+    return HARVEST_OK;
+}
+
+uint32_t tiles_per_chunk(uint64_t chunk_bytes) { return (uint32_t)((chunk_bytes + TILE - 1) / TILE); }
+
+uint32_t grid_for(uint64_t n_tiles, uint32_t max_grid)
+{
+    return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(n_tiles, max_grid));
+}
+
+ClassDev class_dev(const ClassState &c)
+{
+    ClassDev d{};
+    d.dir = c.d_dir;
+    d.n_objects = c.n_objects;
+    d.n_planes = c.cfg.n_planes;
+    d.chunk_bytes = c.cfg.chunk_bytes;
+    for (uint32_t p = 0; p < 2; ++p) {
+        d.pool[T_HOST][p] = c.host_dev[p];
+        d.pool[T_CACHE][p] = (uint64_t)c.cfg.d_cache_pool[p];
+        d.pool[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p];
+    }
+    d.n_slots[T_HOST] = c.cfg.n_host_slots;
+    d.n_slots[T_CACHE] = c.cfg.n_cache_slots;
+    d.n_slots[T_LOCAL] = c.cfg.n_local_slots;
+    return d;
+}
+
+// Publishes the mirror entries of `ids` to the device directory on the ctl stream.  If `after` is given, the write
+// waits for that event first (the copy that makes the new entry true).
+int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipEvent_t after)
+{
+    if (ctx->no_device || ids.empty()) return HARVEST_OK;
+    size_t n = ids.size();
+    size_t bytes = n * (sizeof(uint64_t) + sizeof(uint32_t));
+    Staging *st;
+    int rc = acquire_staging(ctx, bytes, &st);
+    if (rc) return rc;
+    uint64_t *ent = (uint64_t *)st->h;
+    uint32_t *idv = (uint32_t *)(ent + n);
+    for (size_t i = 0; i < n; ++i) { ent[i] = c.packed(ids[i]); idv[i] = ids[i]; }
+    if (after) HIP_TRY(hipStreamWaitEvent(ctx->ctl, after, 0));
+    void *d_st = nullptr;
+    HIP_TRY(hipHostGetDevicePointer(&d_st, st->h, 0));
+    uint64_t *d_ent = (uint64_t *)d_st;
+    uint32_t *d_ids = (uint32_t *)(d_ent + n);
+    hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, ctx->ctl, c.d_dir, d_ids, d_ent,
+                       (uint32_t)n);
+    HIP_TRY(hipGetLastError());
+    return release_after(st, ctx->ctl);
+}
+
+int mark_last(StreamState *ss)
+{
+    HIP_TRY(hipEventRecord(ss->last, ss->s));
+    ss->last_valid = true;
+    return HARVEST_OK;
+}
+
+hipEvent_t prof_event(harvest_ctx *ctx)
+{
+    if (!ctx->prof_pool.empty()) { hipEvent_t e = ctx->prof_pool.back(); ctx->prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Launches the HBM-tier gather on the caller's stream and the host-tier gather on the side stream, joined back.
+int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, uint32_t items_per_req, uint32_t *cnt)
+{
+    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
+    HIP_TRY(hipEventRecord(ss->fork, ss->s));
+    HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
+    hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
+    if (ctx->profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
+    if (pa) HIP_TRY(hipEventRecord(pa, ss->s));
+    hipLaunchKernelGGL(copy_items<true>, dim3(ctx->gather_grid), dim3(WG), 0, ss->s, ss->hbm_items, cnt + C_HBM_REQ, 0u,
+                       items_per_req, c.cfg.chunk_bytes, tpc);
+    HIP_TRY(hipGetLastError());
+    if (pb) HIP_TRY(hipEventRecord(pb, ss->s));
+    if (c.cfg.n_host_slots) {
+        if (pc) HIP_TRY(hipEventRecord(pc, ss->side));
+        hipLaunchKernelGGL(copy_items<false>, dim3(ctx->host_grid), dim3(WG), 0, ss->side, ss->host_items,
+                           cnt + C_HOST_REQ, 0u, items_per_req, c.cfg.chunk_bytes, tpc);
+        HIP_TRY(hipGetLastError());
+        if (pd) HIP_TRY(hipEventRecord(pd, ss->side));
+    }
+    HIP_TRY(hipEventRecord(ss->join, ss->side));
+    HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
+    if (ctx->profile) {
+        ctx->prof.push_back({ pa, pb, 0 });
+        if (c.cfg.n_host_slots) ctx->prof.push_back({ pc, pd, 1 });
+        else { ctx->prof_pool.push_back(pc); ctx->prof_pool.push_back(pd); }
+    }
+    return mark_last(ss);
+}
+
+int check_class(harvest_ctx *ctx, int cls)
+{
+    if (!ctx) return HARVEST_EINVAL;
+    if (cls < 0 || cls >= HARVEST_N_CLASSES || !ctx->cls[cls].used) return HARVEST_ENOENT;
+    return HARVEST_OK;
+}
+
+}  // namespace
+
+// =============================================================================================================
+extern "C" {
+
+const char *harvest_strerror(int status)
+{
+    switch (status) {
+    case HARVEST_OK: return "ok";
+    case HARVEST_EINVAL: return "invalid argument";
+    case HARVEST_ENOSPC: return "no free slot";
+    case HARVEST_ENOENT: return "unknown object or class";
+    case HARVEST_EHIP: return "HIP runtime error";
+    case HARVEST_ELOST: return "lossy object was revoked";
+    case HARVEST_ENODEV: return "context has no device";
+    }
+    return "unknown status";
+}
+
+void *harvest_pinned_alloc(size_t bytes)
+{
+    void *p = nullptr;
+    if (hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault) != hipSuccess) return nullptr;
+    return p;
+}
+
+int harvest_pinned_free(void *p)
+{
+    if (!p) return HARVEST_OK;
+    HIP_TRY(hipHostFree(p));
+    return HARVEST_OK;
+}
+
+int harvest_create(const harvest_config *cfg, harvest_ctx **out)
+{
+    if (!cfg || !out) return HARVEST_EINVAL;
+    *out = nullptr;
+    for (uint32_t r : cfg->reserved) if (r) return HARVEST_EINVAL;
+    auto ctx = std::make_unique<harvest_ctx>();
+    ctx->cfg = *cfg;
+    ctx->no_device = cfg->flags & HARVEST_FLAG_NO_DEVICE;
+    ctx->poison = cfg->flags & HARVEST_FLAG_POISON;
+    ctx->profile = cfg->flags & HARVEST_FLAG_PROFILE;
+    bool any = false;
+    for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
+        const harvest_class_config &cc = cfg->cls[k];
+        if (cc.n_layers == 0) continue;
+        if (cc.n_planes < 1 || cc.n_planes > 2 || cc.chunk_bytes == 0 || cc.chunk_bytes % 16 || cc.max_objects == 0)
+            return HARVEST_EINVAL;
+        if (cc.max_objects > 0x3FFFFFFFu || cc.n_host_slots > 0x3FFFFFFFu || cc.n_cache_slots > 0x3FFFFFFFu ||
+            cc.n_local_slots > 0x3FFFFFFFu)
+            return HARVEST_EINVAL;
+        if (k == HARVEST_EXPERT && (cc.n_layers != 1 || cc.n_planes != 1 || cc.n_experts == 0 ||
+                                    cc.n_experts > MAX_EXPERTS))
+            return HARVEST_EINVAL;
+        if (!ctx->no_device) {
+            for (uint32_t p = 0; p < cc.n_planes; ++p) {
+                if (cc.n_host_slots && !cc.host_pool[p]) return HARVEST_EINVAL;
+                if (cc.n_cache_slots && !cc.d_cache_pool[p]) return HARVEST_EINVAL;
+                if (cc.n_local_slots && !cc.d_local_pool[p]) return HARVEST_EINVAL;
+                if (((uint64_t)cc.host_pool[p] | (uint64_t)cc.d_cache_pool[p] | (uint64_t)cc.d_local_pool[p]) & 15)
+                    return HARVEST_EINVAL;
+            }
+        }
+        ClassState &c = ctx->cls[k];
+        c.cfg = cc;
+        c.used = true;
+        any = true;
+        c.host_used.assign(cc.n_host_slots, 0);
+        for (uint32_t s = 0; s < cc.n_cache_slots; ++s) c.cache_free.insert(c.cache_free.end(), s);
+        for (uint32_t s = 0; s < cc.n_local_slots; ++s) c.local_free.insert(c.local_free.end(), s);
+    }
+    if (!any) return HARVEST_EINVAL;
+    if (!ctx->no_device) {
+        HIP_TRY(hipSetDevice(cfg->device));
+        hipDeviceProp_t prop;
+        HIP_TRY(hipGetDeviceProperties(&prop, cfg->device));
+        ctx->n_cu = prop.multiProcessorCount;
+        ctx->gather_grid = (cfg->gather_wg_per_cu ? cfg->gather_wg_per_cu : 8) * ctx->n_cu;
+        ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 64;
+        HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
+        HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
+        HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
+        for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
+            ClassState &c = ctx->cls[k];
+            if (!c.used) continue;
+            HIP_TRY(hipMalloc(&c.d_dir, (size_t)c.cfg.max_objects * sizeof(uint64_t)));
+            HIP_TRY(hipMemset(c.d_dir, 0xFF, (size_t)c.cfg.max_objects * sizeof(uint64_t)));   // tier NONE everywhere
+            for (uint32_t p = 0; p < c.cfg.n_planes; ++p) {
+                if (!c.cfg.n_host_slots) continue;
+                void *d = nullptr;
+                if (hipHostGetDevicePointer(&d, c.cfg.host_pool[p], 0) != hipSuccess) {
+                    fprintf(stderr, "libharvest: host pool plane %u of class %d is not pinned, mapped host memory\n", p, k);
+                    return HARVEST_EINVAL;
+                }
+                c.host_dev[p] = (uint64_t)d;
+            }
+        }
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    *out = ctx.release();
+    return HARVEST_OK;
+}
+
+int harvest_destroy(harvest_ctx *ctx)
+{
+    if (!ctx) return HARVEST_OK;
+    if (!ctx->no_device) {
+        int rc = device_guard(ctx);
+        if (rc) return rc;
+        for (auto &kv : ctx->streams) {
+            StreamState *ss = kv.second.get();
+            (void)hipStreamSynchronize(ss->s);
+            (void)hipStreamSynchronize(ss->side);
+        }
+        (void)hipStreamSynchronize(ctx->ctl);
+        for (auto &kv : ctx->streams) {
+            StreamState *ss = kv.second.get();
+            (void)hipStreamDestroy(ss->side);
+            for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
+            (void)hipFree(ss->hbm_items); (void)hipFree(ss->host_items); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
+            (void)hipFree(ss->ctl_buf);
+        }
+        for (auto &st : ctx->staging) { (void)hipEventDestroy(st.done); (void)hipHostFree(st.h); }
+        for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
+        for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
+        for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
+        (void)hipFree(ctx->d_totals);
+        (void)hipStreamDestroy(ctx->ctl);
+    }
+    delete ctx;
+    return HARVEST_OK;
+}
+
+int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_slot, int tier, harvest_revoke_cb cb,
+                     void *user, harvest_obj *out_ids)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    if (tier != HARVEST_HOST && tier != HARVEST_LOCAL) return HARVEST_EINVAL;
+    if (!host_slot && tier != HARVEST_LOCAL) return HARVEST_EINVAL;
+    if ((uint64_t)c.n_objects + n > c.cfg.max_objects) return HARVEST_ENOSPC;
+    if (host_slot) {
+        std::unordered_set<int64_t> seen;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (host_slot[i] < 0 || host_slot[i] >= (int64_t)c.cfg.n_host_slots) return HARVEST_EINVAL;
+            if (c.host_used[host_slot[i]] || !seen.insert(host_slot[i]).second) return HARVEST_EINVAL;
+        }
+    }
+    if (tier == HARVEST_LOCAL && c.local_free.size() < n) return HARVEST_ENOSPC;
+    if ((rc = device_guard(ctx))) return rc;
+    std::vector<uint32_t> ids(n);
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t id = c.n_objects++;
+        ids[i] = id;
+        c.tier.push_back((uint8_t)tier);
+        c.gen.push_back(0);
+        c.host_slot.push_back(host_slot ? host_slot[i] : -1);
+        if (host_slot) c.host_used[host_slot[i]] = 1;
+        c.cb.push_back(cb);
+        c.cb_user.push_back(user);
+        int64_t s = -1;
+        if (tier == HARVEST_LOCAL) { s = *c.local_free.begin(); c.local_free.erase(c.local_free.begin()); }
+        c.slot.push_back(s);
+        if (out_ids) out_ids[i] = id;
+    }
+    if ((rc = publish(ctx, c, ids, nullptr))) return rc;
+    if (!ctx->no_device) HIP_TRY(hipStreamSynchronize(ctx->ctl));
+    return HARVEST_OK;
+}
+
+int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t *slot, uint32_t *gen,
+                   int64_t *host_slot)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    if (id >= c.n_objects) return HARVEST_ENOENT;
+    if (tier) *tier = c.tier[id];
+    if (slot) *slot = c.slot[id];
+    if (gen) *gen = c.gen[id];
+    if (host_slot) *host_slot = c.host_slot[id];
+    return HARVEST_OK;
+}
+
+int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *status)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    if (n && !ids) return HARVEST_EINVAL;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+    if ((rc = device_guard(ctx))) return rc;
+    std::vector<uint32_t> moved;
+    std::vector<Item> items;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t id = ids[i];
+        int st = HARVEST_OK;
+        if (c.tier[id] == T_NONE) st = HARVEST_ELOST;
+        else if (c.tier[id] != T_HOST) st = HARVEST_OK;
+        else if (c.host_slot[id] < 0) st = HARVEST_EINVAL;
+        else if (c.cache_free.empty()) { st = HARVEST_ENOSPC; c.n_enospc++; }
+        else {
+            uint32_t s = *c.cache_free.begin();
+            c.cache_free.erase(c.cache_free.begin());
+            for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
+                for (uint32_t l = 0; l < c.cfg.n_layers; ++l)
+                    items.push_back({ c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]), c.addr(T_CACHE, p, l, s) });
+            c.tier[id] = T_CACHE; c.slot[id] = s; c.gen[id] += 1;
+            c.n_placed++;
+            moved.push_back(id);
+        }
+        if (status) status[i] = st;
+    }
+    if (ctx->no_device || moved.empty()) return HARVEST_OK;
+    StreamState *ss;
+    if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    size_t bytes = items.size() * sizeof(Item);
+    if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
+    Staging *st;
+    if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
+    memcpy(st->h, items.data(), bytes);
+    HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
+    if ((rc = release_after(st, ss->s))) return rc;
+    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
+    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
+    hipLaunchKernelGGL(copy_items<false>, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf,
+                       (const uint32_t *)nullptr, (uint32_t)items.size(), 1u, c.cfg.chunk_bytes, tpc);
+    HIP_TRY(hipGetLastError());
+    // the new entries become visible only after the copy; later work on `stream` waits for the publication
+    HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
+    if ((rc = publish(ctx, c, moved, ss->pre_ctl))) return rc;
+    HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
+    HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
+    return mark_last(ss);
+}
+
+int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    if (n && !ids) return HARVEST_EINVAL;
+    std::vector<uint32_t> hit;
+    std::vector<uint32_t> old_slot;
+    std::vector<std::pair<harvest_revoke_cb, void *>> cbs;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        ClassState &c = ctx->cls[cls];
+        for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+        if ((rc = device_guard(ctx))) return rc;
+        // 1. invalidate
+        for (uint32_t i = 0; i < n; ++i) {
+            uint32_t id = ids[i];
+            if (c.tier[id] != T_CACHE) continue;
+            hit.push_back(id);
+            old_slot.push_back((uint32_t)c.slot[id]);
+            c.tier[id] = c.host_slot[id] >= 0 ? T_HOST : T_NONE;
+            c.slot[id] = -1;
+            c.gen[id] += 1;
+            c.n_revoked++;
+            cbs.push_back({ c.cb[id], c.cb_user[id] });
+        }
+        if (hit.empty()) return HARVEST_OK;
+        if (!ctx->no_device) {
+            if ((rc = publish(ctx, c, hit, nullptr))) return rc;
+            HIP_TRY(hipStreamSynchronize(ctx->ctl));
+            // 2. drain: everything enqueued so far that could still read the slots
+            for (auto &kv : ctx->streams)
+                if (kv.second->last_valid) HIP_TRY(hipEventSynchronize(kv.second->last));
+            // 3. (poison and) free
+            if (ctx->poison) {
+                std::vector<Item> items;
+                for (uint32_t s : old_slot)
+                    for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
+                        for (uint32_t l = 0; l < c.cfg.n_layers; ++l) items.push_back({ 0, c.addr(T_CACHE, p, l, s) });
+                size_t bytes = items.size() * sizeof(Item);
+                Staging *st;
+                if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
+                memcpy(st->h, items.data(), bytes);
+                void *d_items = nullptr;
+                HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
+                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
+                uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
+                hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items,
+                                   (uint32_t)items.size(), c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(hipStreamSynchronize(ctx->ctl));
+            }
+        }
+        for (uint32_t s : old_slot) c.cache_free.insert(s);
+    }
+    // 4. notify (outside the lock: a callback may call back into the library)
+    for (size_t i = 0; i < hit.size(); ++i)
+        if (cbs[i].first) cbs[i].first(cls, hit[i], cbs[i].second);
+    return HARVEST_OK;
+}
+
+int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                     uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                     const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream)
+{
+    int rc = check_class(ctx, HARVEST_KV);
+    if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[HARVEST_KV];
+    if (layer >= c.cfg.n_layers) return HARVEST_EINVAL;
+    uint64_t total = (uint64_t)n_seq * max_blocks;
+    if (total >= (1ull << 31)) return HARVEST_EINVAL;
+    if ((rc = device_guard(ctx))) return rc;
+    StreamState *ss;
+    if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    if (total == 0) { ss->last_cur = -1; return HARVEST_OK; }
+    if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
+        return HARVEST_EINVAL;
+    if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
+    if ((rc = ensure_req_cap(ss, (uint32_t)total))) return rc;
+    uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
+    hipLaunchKernelGGL(resolve_kv, dim3((uint32_t)((total + WG - 1) / WG)), dim3(WG), 0, ss->s, class_dev(c), layer,
+                       d_block_table, d_n_blocks, n_seq, max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
+                       d_seq_dst_block, dst_capacity_blocks, ss->hbm_items, ss->host_items, ss->miss_idx, cnt, cnt_next,
+                       ctx->d_totals + HARVEST_KV * C_N);
+    HIP_TRY(hipGetLastError());
+    ss->last_cur = ss->cur;
+    ss->cur ^= 1;
+    return launch_gathers(ctx, ss, c, c.cfg.n_planes, cnt);
+}
+
+int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,
+                          void *d_staging, uint32_t n_staging_slots, void **d_expert_ptr, void *stream)
+{
+    int rc = check_class(ctx, HARVEST_EXPERT);
+    if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[HARVEST_EXPERT];
+    uint32_t E = c.cfg.n_experts;
+    if ((uint64_t)(layer + 1) * E > c.cfg.max_objects) return HARVEST_EINVAL;
+    uint64_t n_ids = (uint64_t)n_tokens * k;
+    if (n_ids >= (1ull << 31) || !d_expert_ptr || (n_ids && !d_topk_ids)) return HARVEST_EINVAL;
+    if (n_staging_slots && (!d_staging || ((uint64_t)d_staging & 15))) return HARVEST_EINVAL;
+    if ((rc = device_guard(ctx))) return rc;
+    StreamState *ss;
+    if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    if ((rc = ensure_req_cap(ss, E))) return rc;
+    uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
+    hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
+                       (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_items, ss->host_items,
+                       ss->miss_idx, cnt, cnt_next, ctx->d_totals + HARVEST_EXPERT * C_N);
+    HIP_TRY(hipGetLastError());
+    ss->last_cur = ss->cur;
+    ss->cur ^= 1;
+    return launch_gathers(ctx, ss, c, 1, cnt);
+}
+
+int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
+                       uint32_t miss_cap, uint32_t *n_miss)
+{
+    if (!ctx) return HARVEST_EINVAL;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    int rc = device_guard(ctx);
+    if (rc) return rc;
+    auto it = ctx->streams.find((hipStream_t)stream);
+    if (it == ctx->streams.end()) return HARVEST_ENOENT;
+    StreamState *ss = it->second.get();
+    HIP_TRY(hipStreamSynchronize(ss->s));
+    uint32_t h[C_N] = { 0 };
+    if (ss->last_cur >= 0) HIP_TRY(hipMemcpy(h, ss->cnt + ss->last_cur * C_N, sizeof h, hipMemcpyDeviceToHost));
+    if (counts) {
+        counts->n_requests = h[C_REQ]; counts->n_local = h[C_LOCAL]; counts->n_cache = h[C_CACHE];
+        counts->n_host = h[C_HOST]; counts->n_lost = h[C_LOST]; counts->n_invalid = h[C_INVALID];
+    }
+    if (n_miss) *n_miss = h[C_MISS];
+    uint32_t m = std::min(h[C_MISS], miss_cap);
+    if (miss_idx && m) HIP_TRY(hipMemcpy(miss_idx, ss->miss_idx, m * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    return HARVEST_OK;
+}
+
+int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, uint32_t n, const void *d_src0,
+                  const void *d_src1, const uint64_t *src_block, uint64_t src_layer_stride, int flags, void *stream)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    if (n && (!ids || !src_block)) return HARVEST_EINVAL;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    if (layer >= (int)c.cfg.n_layers) return HARVEST_EINVAL;
+    bool demote_flag = flags & HARVEST_EVICT_DEMOTE;
+    if (demote_flag && layer >= 0 && c.cfg.n_layers != 1) return HARVEST_EINVAL;
+    {
+        std::unordered_set<uint32_t> seen;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+            if (src_block[i] >= src_layer_stride) return HARVEST_EINVAL;
+            if (c.tier[ids[i]] == T_NONE) return HARVEST_ELOST;
+            if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) return HARVEST_EINVAL;
+            if (!seen.insert(ids[i]).second) return HARVEST_EINVAL;
+        }
+    }
+    if (n == 0) return HARVEST_OK;
+    if (!ctx->no_device) {
+        if (!d_src0 || (c.cfg.n_planes == 2 && !d_src1)) return HARVEST_EINVAL;
+        if (((uint64_t)d_src0 | (uint64_t)d_src1) & 15) return HARVEST_EINVAL;
+    }
+    if ((rc = device_guard(ctx))) return rc;
+    const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
+    uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
+    std::vector<Item2> items;
+    std::vector<uint32_t> demoted;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t id = ids[i];
+        bool demote = demote_flag && c.tier[id] == T_LOCAL;
+        for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
+            for (uint32_t l = l0; l < l1; ++l) {
+                uint64_t li = layer < 0 ? l : 0;
+                Item2 it{};
+                it.src = src[p] + (li * src_layer_stride + src_block[i]) * c.cfg.chunk_bytes;
+                if (c.host_slot[id] >= 0) it.dst0 = c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]);
+                if (c.tier[id] == T_CACHE) it.dst1 = c.addr(T_CACHE, p, l, (uint64_t)c.slot[id]);
+                if (c.tier[id] == T_LOCAL && !demote) {
+                    uint64_t d = c.addr(T_LOCAL, p, l, (uint64_t)c.slot[id]);
+                    if (d != it.src) it.dst1 = d;       // a source that already is the slot needs no copy
+                }
+                if (it.dst0 || it.dst1) items.push_back(it);
+            }
+        c.n_evicted++;
+        if (demote) {
+            c.local_free.insert((uint32_t)c.slot[id]);
+            c.tier[id] = T_HOST; c.slot[id] = -1; c.gen[id] += 1;
+            c.n_demoted++;
+            demoted.push_back(id);
+        }
+    }
+    if (ctx->no_device) return HARVEST_OK;
+    StreamState *ss;
+    if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    if (!items.empty()) {
+        size_t bytes = items.size() * sizeof(Item2);
+        if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
+        Staging *st;
+        if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
+        memcpy(st->h, items.data(), bytes);
+        HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
+        if ((rc = release_after(st, ss->s))) return rc;
+        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
+        uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
+        hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
+                           (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+        HIP_TRY(hipGetLastError());
+    }
+    if (!demoted.empty()) {
+        HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
+        if ((rc = publish(ctx, c, demoted, ss->pre_ctl))) return rc;
+        HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
+        HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
+    }
+    return mark_last(ss);
+}
+
+int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out)
+{
+    if (!ctx || !out) return HARVEST_EINVAL;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    memset(out, 0, sizeof *out);
+    unsigned long long h[HARVEST_N_CLASSES * C_N] = { 0 };
+    if (!ctx->no_device) {
+        int rc = device_guard(ctx);
+        if (rc) return rc;
+        for (auto &kv : ctx->streams) HIP_TRY(hipStreamSynchronize(kv.second->s));
+        HIP_TRY(hipMemcpy(h, ctx->d_totals, sizeof h, hipMemcpyDeviceToHost));
+    }
+    for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
+        const ClassState &c = ctx->cls[k];
+        if (!c.used) continue;
+        const unsigned long long *t = h + k * C_N;
+        out->fetch[k].n_requests = t[C_REQ]; out->fetch[k].n_local = t[C_LOCAL]; out->fetch[k].n_cache = t[C_CACHE];
+        out->fetch[k].n_host = t[C_HOST]; out->fetch[k].n_lost = t[C_LOST]; out->fetch[k].n_invalid = t[C_INVALID];
+        out->n_placed[k] = c.n_placed; out->n_place_enospc[k] = c.n_enospc; out->n_revoked[k] = c.n_revoked;
+        out->n_evicted[k] = c.n_evicted; out->n_demoted[k] = c.n_demoted;
+        out->cache_slots_in_use[k] = c.cfg.n_cache_slots - c.cache_free.size();
+        out->local_slots_in_use[k] = c.cfg.n_local_slots - c.local_free.size();
+    }
+    return HARVEST_OK;
+}
+
+int harvest_profile(harvest_ctx *ctx, harvest_profile_t *out)
+{
+    if (!ctx || !out) return HARVEST_EINVAL;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    memset(out, 0, sizeof *out);
+    int rc = device_guard(ctx);
+    if (rc) return rc;
+    for (auto &kv : ctx->streams) {
+        HIP_TRY(hipStreamSynchronize(kv.second->s));
+        HIP_TRY(hipStreamSynchronize(kv.second->side));
+    }
+    for (auto &pp : ctx->prof) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, pp.a, pp.b));
+        if (pp.which == 0) { out->hbm_launches++; out->hbm_ms += ms; }
+        else { out->host_launches++; out->host_ms += ms; }
+        ctx->prof_pool.push_back(pp.a);
+        ctx->prof_pool.push_back(pp.b);
+    }
+    ctx->prof.clear();
+    return HARVEST_OK;
+}
+
+int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *stream)
+{
+    if (!d_dst || !d_src || bytes % 16 || (((uint64_t)d_dst | (uint64_t)d_src) & 15)) return HARVEST_EINVAL;
+    if (bytes == 0) return HARVEST_OK;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    int n_cu = 0;
+    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    uint64_t n_tiles = (bytes + TILE - 1) / TILE;
+    uint32_t grid = grid_for(n_tiles, 8u * (uint32_t)n_cu);
+    hipLaunchKernelGGL(plain_copy<true>, dim3(grid), dim3(WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
+                       bytes);
+    HIP_TRY(hipGetLastError());
+    return HARVEST_OK;
+}
+
+}  // extern "C"

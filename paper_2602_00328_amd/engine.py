@@ -1,0 +1,193 @@
+"""Harness-facing wrapper of the HIP library: numpy in, numpy out, device buffers managed with torch.
+
+This is what tests and the benchmark drive.  It only marshals: tables, routing ids and sources are copied to device
+tensors, the library is called through the C ABI, destinations are copied back for comparison.  No payload byte is
+produced or altered here.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads as W
+from . import binding as B
+from .binding import KV, EXPERT, HOST, CACHE, LOCAL, NONE  # noqa: F401
+
+IN_PLACE, STAGED, OVERFLOW_OR_LOST = 1, 2, 3
+
+
+class HipEngine:
+    name = "hip"
+
+    def __init__(self, kv=None, expert=None, poison=False, device=0, profile=False, gather_wg_per_cu=0, host_wgs=0,
+                 two_streams=False):
+        """two_streams: KV work and expert work are enqueued on two HIP streams of their own (default priority)."""
+        flags = (B.FLAG_POISON if poison else 0) | (B.FLAG_PROFILE if profile else 0)
+        self.dev = torch.device("cuda", device)
+        torch.cuda.set_device(self.dev)
+        self.spec = {KV: kv, EXPERT: expert}
+        self.streams = {k: (torch.cuda.Stream(self.dev) if two_streams else None) for k in (KV, EXPERT)}
+        self.h = B.Harvest(kv=kv, expert=expert, flags=flags, device=device, gather_wg_per_cu=gather_wg_per_cu,
+                           host_wgs=host_wgs)
+        self._dst = {}
+
+    def _on(self, cls):
+        """Context in which torch's own copies and the library call share the stream of this class."""
+        s = self.streams[cls]
+        return torch.cuda.stream(s if s is not None else torch.cuda.current_stream(self.dev))
+
+    def close(self):
+        torch.cuda.synchronize(self.dev)
+        self.h.close()
+        self._dst.clear()
+
+    # ---- harness-side initialisation -----------------------------------------------------------------------
+    def fill_host(self, cls, slot_object, seed, wl_cls, mode, sigma):
+        sp = self.spec[cls]
+        for p in range(sp.n_planes):
+            W.fill_pool(self.h.host_ptr(cls, p), sp.n_layers, sp.n_host_slots, sp.chunk_bytes, slot_object, seed,
+                        wl_cls, p, mode, sigma)
+
+    def fill_local(self, cls, slot_object, seed, wl_cls, mode, sigma):
+        sp = self.spec[cls]
+        for p in range(sp.n_planes):
+            t = self.h.dev_plane(cls, LOCAL, p)
+            tmp = np.zeros((1, sp.n_local_slots, sp.chunk_bytes), dtype=np.uint8)
+            used = torch.from_numpy((np.asarray(slot_object) != W.NO_OBJECT)).to(self.dev)
+            for layer in range(sp.n_layers):
+                W.fill_array(tmp, slot_object, seed, wl_cls, p, mode, sigma, layer_base=layer)
+                up = torch.from_numpy(tmp[0]).to(self.dev)
+                t[layer][used] = up[used]
+        torch.cuda.synchronize(self.dev)
+
+    def adopt(self, cls, ids):
+        pass                                     # the library has no notion of a tier-free value
+
+    def write_local(self, cls, obj, plane, layer, offset, data):
+        tier, slot, _, _ = self.h.lookup(cls, obj)
+        assert tier == LOCAL
+        with self._on(cls):
+            d = torch.from_numpy(np.ascontiguousarray(data, dtype=np.uint8)).to(self.dev)
+            self.h.dev_plane(cls, LOCAL, plane)[layer, slot, offset:offset + d.numel()] = d
+
+    # ---- directory ---------------------------------------------------------------------------------------------
+    def register(self, cls, n, host_slots=None, tier=HOST):
+        return self.h.register(cls, n, host_slots, tier)
+
+    def lookup(self, cls, obj):
+        return self.h.lookup(cls, obj)
+
+    def place(self, cls, ids):
+        with self._on(cls):
+            return self.h.place(cls, ids)
+
+    def revoke(self, cls, ids):
+        n0 = len(self.h.revoked_log)
+        self.h.revoke(cls, ids)
+        return [i for _c, i in self.h.revoked_log[n0:]]
+
+    # ---- data path -------------------------------------------------------------------------------------------
+    def has_layer(self, layer):
+        return True
+
+    def _dst_buffers(self, cap, fill=0):
+        sp = self.spec[KV]
+        key = (cap, sp.chunk_bytes)
+        if key not in self._dst:
+            self._dst.clear()
+            self._dst[key] = [torch.empty(cap * sp.chunk_bytes, dtype=torch.uint8, device=self.dev)
+                              for _ in range(sp.n_planes)]
+        for t in self._dst[key]:
+            t.fill_(fill)
+        return self._dst[key]
+
+    def fetch_kv_device(self, layer, d_table, d_n_blocks, d_sdb, cap, dst=None, stream=None):
+        """All-device variant (what the benchmark times): nothing is copied to or from the host."""
+        dst = dst or self._dst_buffers(cap)
+        self.h.fetch_kv(layer, d_table, d_n_blocks, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, cap, stream)
+        return dst
+
+    def fetch_kv_begin(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0):
+        """Enqueue only; fetch_end(handle) waits and copies the results back."""
+        sp = self.spec[KV]
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        with self._on(KV):
+            d_table = torch.from_numpy(table).to(self.dev)
+            d_nb = torch.from_numpy(np.ascontiguousarray(n_blocks, dtype=np.int32)).to(self.dev)
+            d_sdb = torch.from_numpy(np.ascontiguousarray(seq_dst_block, dtype=np.uint64).view(np.int64)).to(self.dev)
+            dst = [torch.full((cap * sp.chunk_bytes,), dst_fill, dtype=torch.uint8, device=self.dev)
+                   for _ in range(sp.n_planes)]
+            self.h.fetch_kv(layer, d_table, d_nb, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, cap)
+        return ("kv", dst, table.size, (d_table, d_nb, d_sdb))
+
+    def fetch_kv(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0):
+        return self.fetch_end(self.fetch_kv_begin(layer, table, n_blocks, seq_dst_block, cap, dst_fill))
+
+    def fetch_experts_begin(self, layer, topk, n_staging, staging_fill=0):
+        sp = self.spec[EXPERT]
+        with self._on(EXPERT):
+            d_topk = torch.from_numpy(np.ascontiguousarray(topk, dtype=np.int32)).to(self.dev)
+            staging = torch.full((max(1, n_staging) * sp.chunk_bytes,), staging_fill, dtype=torch.uint8,
+                                 device=self.dev)
+            ptrs = torch.zeros(sp.n_experts, dtype=torch.int64, device=self.dev)
+            self.h.fetch_experts(layer, d_topk, staging, n_staging, ptrs)
+        return ("experts", staging, n_staging, ptrs, d_topk)
+
+    def fetch_experts(self, layer, topk, n_staging, staging_fill=0):
+        return self.fetch_end(self.fetch_experts_begin(layer, topk, n_staging, staging_fill))
+
+    def fetch_end(self, handle):
+        if handle[0] == "kv":
+            _, dst, n_req, _keep = handle
+            with self._on(KV):
+                counts, miss, n_miss = self.h.fetch_info(miss_cap=n_req)
+                assert n_miss == miss.size
+                k = dst[0].cpu().numpy()
+                v = dst[1].cpu().numpy() if len(dst) > 1 else None
+            return k, v, np.sort(miss), counts
+        _, staging, n_staging, ptrs, _keep = handle
+        sp = self.spec[EXPERT]
+        E = sp.n_experts
+        with self._on(EXPERT):
+            counts, miss, n_miss = self.h.fetch_info(miss_cap=E)
+            ptrs = ptrs.cpu().numpy()
+            local = self.h.dev_plane(EXPERT, LOCAL, 0) if sp.n_local_slots else None
+            s0 = staging.data_ptr()
+            out, kind, where = [], np.zeros(E, np.int32), np.full(E, -1, np.int64)
+            for e in range(E):
+                p = int(ptrs[e])
+                if p == 0:
+                    out.append(None)
+                elif s0 <= p < s0 + n_staging * sp.chunk_bytes:
+                    r = (p - s0) // sp.chunk_bytes
+                    assert (p - s0) % sp.chunk_bytes == 0
+                    kind[e], where[e] = STAGED, r
+                    out.append(staging[r * sp.chunk_bytes:(r + 1) * sp.chunk_bytes].cpu().numpy())
+                else:
+                    l0 = local.data_ptr()
+                    assert l0 <= p < l0 + sp.n_local_slots * sp.chunk_bytes and (p - l0) % sp.chunk_bytes == 0
+                    slot = (p - l0) // sp.chunk_bytes
+                    kind[e], where[e] = IN_PLACE, slot
+                    out.append(local[0, slot].cpu().numpy())
+        self.last_staging = staging
+        return out, kind, where, np.sort(miss), counts
+
+    def evict(self, cls, layer, ids, src0, src1, src_block, stride, flags=0):
+        with self._on(cls):
+            d0 = torch.from_numpy(np.ascontiguousarray(src0, dtype=np.uint8)).to(self.dev)
+            d1 = None if src1 is None else torch.from_numpy(np.ascontiguousarray(src1, dtype=np.uint8)).to(self.dev)
+            self.h.evict(cls, layer, ids, d0, d1, src_block, stride, flags)
+            torch.cuda.current_stream().synchronize()          # d0 / d1 are freed when this returns
+
+    def evict_from_local(self, cls, ids, flags=0):
+        sp = self.spec[cls]
+        slots = [self.h.lookup(cls, i)[1] for i in ids]
+        with self._on(cls):
+            self.h.evict(cls, -1, ids, self.h.dev_plane(cls, LOCAL, 0),
+                         self.h.dev_plane(cls, LOCAL, 1) if sp.n_planes == 2 else None, slots, sp.n_local_slots, flags)
+
+    def tier_plane(self, cls, tier, plane=0):
+        if tier == HOST:
+            torch.cuda.synchronize(self.dev)
+            return self.h.host_plane(cls, plane)
+        return self.h.dev_plane(cls, tier, plane).cpu().numpy()

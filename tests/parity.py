@@ -1,0 +1,91 @@
+"""Shared helpers of the parity tests: build an oracle engine and a HIP engine over the same workload, compare what
+they return, byte for byte."""
+import numpy as np
+
+import workloads as W
+from workloads import scenarios as S
+
+
+def make_engines(kv_wl=None, ex_wl=None, poison=False, two_streams=False, kv_layers=None, cache_slack=0,
+                 local_slack=0, hip_kwargs=None, kv_spec=None, ex_spec=None):
+    from oracle.engine import OracleEngine
+    from paper_2602_00328_amd.engine import HipEngine
+    kv = kv_spec or (S.kv_spec(kv_wl, cache_slack, local_slack) if kv_wl is not None else None)
+    ex = ex_spec or (S.expert_spec(ex_wl) if ex_wl is not None else None)
+    eo = OracleEngine(kv=kv, expert=ex, poison=poison, kv_layers=kv_layers)
+    eh = HipEngine(kv=kv, expert=ex, poison=poison, two_streams=two_streams, **(hip_kwargs or {}))
+    return eo, eh
+
+
+def first_diff(a, b):
+    d = np.nonzero(a != b)[0]
+    return None if d.size == 0 else (int(d[0]), int(a[d[0]]), int(b[d[0]]), int(d.size))
+
+
+def assert_kv_equal(o, h, what, counts=True):
+    ko, vo, mo, co = o
+    kh, vh, mh, ch = h
+    assert ko.shape == kh.shape, what
+    assert np.array_equal(ko, kh), f"{what}: K differs (first byte, oracle, hip, n): {first_diff(ko, kh)}"
+    if vo is not None:
+        assert np.array_equal(vo, vh), f"{what}: V differs (first byte, oracle, hip, n): {first_diff(vo, vh)}"
+    if counts:
+        assert co == ch, f"{what}: counts {co} != {ch}"
+        assert np.array_equal(mo, mh), f"{what}: miss lists differ"
+
+
+def assert_experts_equal(o, h, what, counts=True):
+    oo, kind_o, where_o, mo, co = o
+    oh, kind_h, where_h, mh, ch = h
+    assert len(oo) == len(oh)
+    for e, (a, b) in enumerate(zip(oo, oh)):
+        assert (a is None) == (b is None), f"{what}: expert {e} presence differs"
+        if a is not None:
+            assert np.array_equal(a, b), f"{what}: expert {e} bytes differ: {first_diff(a, b)}"
+    # oracle kinds 3 (overflow) and 4 (lost) both surface as a NULL pointer
+    assert np.array_equal(np.where(kind_o >= 3, 0, kind_o), kind_h), f"{what}: kinds {kind_o} vs {kind_h}"
+    if counts:
+        sel = kind_h > 0
+        assert np.array_equal(where_o[sel], where_h[sel]), f"{what}: staging ranks / local slots differ"
+        assert co == ch, f"{what}: counts {co} != {ch}"
+        assert np.array_equal(mo, mh), f"{what}: miss lists differ"
+
+
+def assert_dirs_equal(eo, eh, cls, n, what=""):
+    for i in range(n):
+        assert eo.lookup(cls, i) == eh.lookup(cls, i), f"{what}: directory entry {i}: {eo.lookup(cls, i)} != {eh.lookup(cls, i)}"
+
+
+def assert_tiers_equal(eo, eh, cls, n_planes, tiers=(S.HOST, S.CACHE, S.LOCAL), what=""):
+    for tier in tiers:
+        for p in range(n_planes):
+            a, b = eo.tier_plane(cls, tier, p), eh.tier_plane(cls, tier, p)
+            if a.size == 0 and b.size == 0:
+                continue
+            assert a.shape == b.shape
+            assert np.array_equal(a, b), f"{what}: tier {tier} plane {p} differs: {first_diff(a.reshape(-1), b.reshape(-1))}"
+
+
+def smoke():
+    """One tiny pass of every entry point on cuda:0 against the oracle."""
+    wl = W.kv_decode(seed=3, n_layers=2, n_seq=3, min_len=40, max_len=90, n_steps=20, fill_mode=W.FILL_TAG)
+    ex = W.expert_offload(seed=3, shape=W.ExpertShape(n_layers=2, n_experts=8, d_model=32, d_ff=50), n_tokens=6,
+                          fill_mode=W.FILL_TAG)
+    eo, eh = make_engines(wl, ex, poison=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        for t in range(20):
+            assert_kv_equal(ro.step(t), rh.step(t), f"smoke kv step {t}")
+            assert_experts_equal(xo.fetch(t, t % 2), xh.fetch(t, t % 2), f"smoke experts step {t}")
+            if t == 10:
+                assert ro.revoke_quarter(t)[1] == rh.revoke_quarter(t)[1]
+                assert xo.revoke_quarter(t)[1] == xh.revoke_quarter(t)[1]
+            if t == 15:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
+        assert_dirs_equal(eo, eh, S.KV, wl.n_objects, "smoke")
+        assert_tiers_equal(eo, eh, S.KV, 2, what="smoke")
+    finally:
+        eh.close()
+        eo.close()

@@ -1,0 +1,154 @@
+"""CPU-only checks of the HIP library: it loads, exports exactly what include/harvest.h declares, its structs have
+the layout the binding assumes, and its host-side logic (directory mirror, slot allocators, argument validation,
+callback order) agrees with the oracle's directory under random operation sequences.  No kernel is launched: the
+context is created with HARVEST_FLAG_NO_DEVICE."""
+import os
+import re
+import subprocess
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from paper_2602_00328_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "harvest.h")
+
+
+def test_library_exports_every_declared_symbol_and_nothing_is_undeclared():
+    text = open(HEADER).read()
+    declared = set(re.findall(r"\b(harvest_[a-z_]+)\s*\(", text)) - {"harvest_revoke_cb"}
+    assert declared == set(B.SYMBOLS), (declared ^ set(B.SYMBOLS))
+    out = subprocess.check_output(["nm", "-D", "--defined-only", B.LIB_PATH], text=True)
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l and "harvest_" in l}
+    assert declared <= exported, declared - exported
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    src = tmp_path / "sz.c"
+    src.write_text('#include <stdio.h>\n#include "harvest.h"\nint main(void){printf("%zu %zu %zu %zu %zu %zu\\n",'
+                   'sizeof(harvest_class_config),sizeof(harvest_config),sizeof(harvest_fetch_counts),'
+                   'sizeof(harvest_stats_t),sizeof(harvest_profile_t),offsetof(harvest_config,gather_wg_per_cu));return 0;}\n')
+    exe = tmp_path / "sz"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = [int(x) for x in subprocess.check_output([str(exe)], text=True).split()]
+    want = [ctypes.sizeof(B.harvest_class_config), ctypes.sizeof(B.harvest_config),
+            ctypes.sizeof(B.harvest_fetch_counts), ctypes.sizeof(B.harvest_stats_t),
+            ctypes.sizeof(B.harvest_profile_t), B.harvest_config.gather_wg_per_cu.offset]
+    assert got == want
+
+
+def test_status_codes_agree_with_the_oracle_where_they_mean_the_same():
+    assert (B.OK, B.EINVAL, B.ENOSPC, B.ENOENT, B.ELOST) == (O.OK, O.EINVAL, O.ENOSPC, O.ENOENT, O.ELOST)
+    assert (B.HOST, B.CACHE, B.LOCAL, B.NONE) == (O.HOST, O.CACHE, O.LOCAL, O.NONE)
+    assert B.lib.harvest_strerror(B.ENOSPC) == b"no free slot"
+
+
+def spec(n_layers=2, n_planes=2, chunk=64, max_objects=40, n_host=48, n_cache=9, n_local=4, n_experts=0):
+    return B.ClassSpec(n_layers, n_planes, chunk, max_objects, n_host, n_cache, n_local, n_experts)
+
+
+def test_create_rejects_bad_configurations():
+    for bad in (spec(chunk=40), spec(n_planes=3), spec(max_objects=0)):
+        with pytest.raises(B.HarvestError) as e:
+            B.Harvest(kv=bad, flags=B.FLAG_NO_DEVICE)
+        assert e.value.code == B.EINVAL
+    with pytest.raises(B.HarvestError):
+        B.Harvest(flags=B.FLAG_NO_DEVICE)                                  # no class at all
+    with pytest.raises(B.HarvestError):
+        B.Harvest(expert=spec(n_layers=1, n_planes=1, n_experts=0), flags=B.FLAG_NO_DEVICE)
+    h = B.Harvest(kv=spec(), flags=B.FLAG_NO_DEVICE)
+    with pytest.raises(B.HarvestError) as e:
+        h.register(B.EXPERT, 1, [0])                                       # class not configured
+    assert e.value.code == B.ENOENT
+    h.close()
+
+
+def test_data_calls_refuse_to_run_without_a_device():
+    h = B.Harvest(kv=spec(), expert=spec(n_layers=1, n_planes=1, n_experts=4), flags=B.FLAG_NO_DEVICE)
+    rc = B.lib.harvest_fetch_kv(h.h, 0, None, None, 1, 1, None, None, None, 1, None)
+    assert rc == B.ENODEV
+    rc = B.lib.harvest_fetch_experts(h.h, 0, None, 1, 1, None, 0, None, None)
+    assert rc == B.ENODEV
+    assert B.lib.harvest_fetch_info(h.h, None, None, None, 0, None) == B.ENODEV
+    h.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_host_logic_matches_the_oracle_directory_under_random_operations(seed):
+    sp = spec()
+    h = B.Harvest(kv=sp, flags=B.FLAG_NO_DEVICE)
+    oc = O.OracleClass(sp.n_layers, sp.n_planes, sp.chunk_bytes, sp.max_objects, sp.n_host_slots, sp.n_cache_slots,
+                       sp.n_local_slots)
+    g = W.rng(seed, 300)
+    free_host = list(g.permutation(sp.n_host_slots))
+    dummy = np.zeros(sp.n_layers * 8 * sp.chunk_bytes, np.uint8)
+
+    def both(fo, fh):
+        eo = eh = None
+        try:
+            ro = fo()
+        except O.OracleError as e:
+            ro, eo = None, e.code
+        try:
+            rh = fh()
+        except B.HarvestError as e:
+            rh, eh = None, e.code
+        assert eo == eh, (eo, eh)
+        return ro, rh
+
+    for step in range(120):
+        n = oc.n_objects
+        op = int(g.integers(0, 6))
+        if op == 0 and free_host:                                            # register
+            k = int(g.integers(1, 4))
+            hs = [int(free_host.pop()) for _ in range(min(k, len(free_host)))]
+            tier = O.LOCAL if g.random() < 0.4 else O.HOST
+            if g.random() < 0.1:
+                hs[0] = int(g.integers(-2, sp.n_host_slots + 2))            # maybe invalid or taken
+            ro, rh = both(lambda: oc.register(len(hs), hs, tier), lambda: h.register(B.KV, len(hs), hs, tier))
+            if ro is not None:
+                assert np.array_equal(ro, rh)
+            else:
+                free_host.extend(hs[1:])
+        elif n:
+            ids = g.integers(0, n + (1 if g.random() < 0.05 else 0), size=int(g.integers(1, 6))).astype(np.uint32)
+            if op == 1:
+                ro, rh = both(lambda: oc.place(ids), lambda: h.place(B.KV, ids))
+                if ro is not None:
+                    assert np.array_equal(ro, rh)
+            elif op == 2:
+                n0, m0 = len(oc.revoked_log), len(h.revoked_log)
+                both(lambda: oc.revoke(ids), lambda: h.revoke(B.KV, ids))
+                assert oc.revoked_log[n0:] == [i for _c, i in h.revoked_log[m0:]]
+            elif op in (3, 4):
+                layer = int(g.integers(-1, sp.n_layers))
+                flags = O.EVICT_DEMOTE if (op == 4 and layer < 0) else 0
+                sb = g.integers(0, 8 + (1 if g.random() < 0.05 else 0), size=ids.size).astype(np.uint64)
+                both(lambda: oc.evict(layer, ids, dummy, dummy, sb, 8, flags),
+                     lambda: h.evict(B.KV, layer, ids, None, None, sb, 8, flags))
+            else:
+                bad = int(n + 3)
+                both(lambda: oc.lookup(bad), lambda: h.lookup(B.KV, bad))
+        for i in range(oc.n_objects):
+            assert oc.lookup(i) == h.lookup(B.KV, i), (step, i)
+    st = h.stats()
+    in_cache = sum(1 for i in range(oc.n_objects) if oc.lookup(i)[0] == O.CACHE)
+    in_local = sum(1 for i in range(oc.n_objects) if oc.lookup(i)[0] == O.LOCAL)
+    assert st.cache_slots_in_use[B.KV] == in_cache and st.local_slots_in_use[B.KV] == in_local
+    h.close()
+    oc.close()
+
+
+def test_lossy_objects_host_logic():
+    h = B.Harvest(kv=spec(), flags=B.FLAG_NO_DEVICE)
+    a = h.register(B.KV, 1, None, B.LOCAL)[0]
+    with pytest.raises(B.HarvestError):
+        h.register(B.KV, 1, None, B.HOST)
+    with pytest.raises(B.HarvestError) as e:
+        h.evict(B.KV, -1, [a], None, None, [0], 4, B.EVICT_DEMOTE)
+    assert e.value.code == B.EINVAL and h.lookup(B.KV, a)[0] == B.LOCAL
+    h.close()

@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+Everything is byte work, so the bar is bit-exact (numpy.array_equal on raw bytes) for payload, directory entries,
+statuses, counts and (sorted) miss lists."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads import scenarios as S
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+# ---- config 1: tiny KV fetch, scatter back, round trip ------------------------------------------------------
+
+@pytest.mark.parametrize("fill", [W.FILL_NORMAL, W.FILL_TAG])
+def test_config1_tiny_kv_fetch_and_round_trip(fill):
+    say(f"config1 fill={fill}")
+    wl = W.kv_tiny(0, fill_mode=fill)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        assert np.array_equal(ro.place_status, rh.place_status) and (rh.place_status == 0).all()
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects, "after place")
+        P.assert_tiers_equal(eo, eh, S.KV, 2, tiers=(S.HOST, S.CACHE), what="after place")
+        a, b = ro.fetch(0), rh.fetch(0)
+        P.assert_kv_equal(a, b, "config1 fetch")
+        assert b[3]["n_cache"] + b[3]["n_host"] == 256 and b[3]["n_invalid"] == 0
+        if fill == W.FILL_TAG:                                  # no reference buffer needed at all
+            chunk = wl.shape.chunk_bytes
+            flat = np.concatenate(wl.tables)
+            for j, blk in enumerate(flat):
+                assert W.check_tag(b[0][j * chunk:(j + 1) * chunk], 0, W.CLS_KV, 0, 0, int(blk))
+                assert W.check_tag(b[1][j * chunk:(j + 1) * chunk], 0, W.CLS_KV, 1, 0, int(blk))
+        # scatter the gathered bytes back: every tier must be unchanged
+        ids = np.concatenate(wl.tables).astype(np.uint32)
+        for e, r in ((eo, a), (eh, b)):
+            e.evict(S.KV, 0, ids, r[0], r[1], np.arange(256), 256)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, tiers=(S.HOST, S.CACHE), what="after identity evict")
+        P.assert_kv_equal(a, rh.fetch(0), "fetch after identity evict")
+        # scatter new bytes, gather them again
+        g = W.rng(0, 500)
+        yk = g.integers(0, 256, size=a[0].size, dtype=np.uint8)
+        yv = g.integers(0, 256, size=a[0].size, dtype=np.uint8)
+        for e in (eo, eh):
+            e.evict(S.KV, 0, ids, yk, yv, np.arange(256), 256)
+        c, d = ro.fetch(0), rh.fetch(0)
+        P.assert_kv_equal(c, d, "fetch after evict of new bytes")
+        assert np.array_equal(d[0], yk) and np.array_equal(d[1], yv)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, tiers=(S.HOST, S.CACHE), what="after evict of new bytes")
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- tier independence on the GPU -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("p_cache", [0.0, 0.35, 1.0])
+def test_fetch_is_the_same_for_every_residency(p_cache):
+    say(f"residency p={p_cache}")
+    wl = W.kv_decode(seed=1, n_layers=2, n_seq=3, min_len=300, max_len=900, p_cache=p_cache, n_steps=1)
+    ref = W.kv_decode(seed=1, n_layers=2, n_seq=3, min_len=300, max_len=900, p_cache=0.5, n_steps=1)
+    eo, eh = P.make_engines(wl)
+    eo2, _unused = None, None
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for layer in range(2):
+            a, b = ro.fetch(layer), rh.fetch(layer)
+            P.assert_kv_equal(a, b, f"p={p_cache} layer {layer}")
+            if p_cache == 0.0:
+                assert b[3]["n_cache"] == 0
+            if p_cache == 1.0:
+                assert b[3]["n_host"] == 0 and b[2].size == 0
+        assert all(np.array_equal(x, y) for x, y in zip(wl.tables, ref.tables))   # same requests, other residency
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- config 2, small: decode steps with append, write-back, demotion, placement -------------------------------
+
+def test_kv_decode_steps_small():
+    say("kv decode small")
+    wl = W.kv_decode(seed=2, n_layers=3, n_seq=4, min_len=500, max_len=2000, n_steps=40)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(40):
+            P.assert_kv_equal(ro.step(t), rh.step(t), f"decode step {t}")
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects, "after 40 steps")
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="after 40 steps")
+        st = eh.h.stats()
+        assert st.n_demoted[0] == sum(len(f) for f in wl.future_blocks) and st.fetch[0].n_invalid == 0
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- chunk sizes that are not a multiple of the 32 KiB tile -----------------------------------------------------
+
+@pytest.mark.parametrize("heads,dim,tokens", [(1, 8, 1), (3, 8, 16), (8, 129 - 1, 16), (8, 136, 16), (5, 200, 48)])
+def test_ragged_chunk_sizes(heads, dim, tokens):
+    shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim)
+    say(f"ragged chunk {shape.chunk_bytes} bytes")
+    wl = W.kv_decode(seed=4, n_seq=3, min_len=20 * tokens, max_len=60 * tokens, n_steps=2 * tokens, shape=shape,
+                     fill_mode=W.FILL_TAG)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(2 * tokens):
+            P.assert_kv_equal(ro.step(t), rh.step(t), f"chunk {shape.chunk_bytes} step {t}")
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what=f"chunk {shape.chunk_bytes}")
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- degenerate requests ----------------------------------------------------------------------------------------
+
+def test_empty_invalid_duplicate_and_overflowing_requests():
+    say("edge cases")
+    wl = W.kv_decode(seed=5, n_layers=1, n_seq=2, min_len=64, max_len=128, n_steps=1, fill_mode=W.FILL_TAG)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        n = wl.n_closed
+        sdb = np.array([0, 6], np.uint64)
+        cases = {
+            "all empty": (np.zeros((2, 5), np.int32), np.array([0, 0], np.int32), sdb, 12),
+            "negative and oversized n_blocks": (np.arange(10, dtype=np.int32).reshape(2, 5) % n,
+                                                np.array([-3, 99], np.int32), sdb, 12),
+            "unknown and negative ids": (np.array([[0, -1, 2, 10 ** 6, 1], [n + 50, 1, 1, 1, 0]], np.int32),
+                                         np.array([5, 5], np.int32), sdb, 12),
+            "duplicates": (np.full((2, 5), 3, np.int32), np.array([5, 4], np.int32), sdb, 12),
+            "destination overflow": (np.arange(10, dtype=np.int32).reshape(2, 5) % n, np.array([5, 5], np.int32),
+                                     np.array([0, 9], np.uint64), 12),
+        }
+        for name, (table, nb, s, cap) in cases.items():
+            say(f"  {name}")
+            a = eo.c[S.KV].fetch_kv(0, table, nb, s, cap, dst_k=np.full(cap * wl.shape.chunk_bytes, 0xEE, np.uint8),
+                                    dst_v=np.full(cap * wl.shape.chunk_bytes, 0xEE, np.uint8))
+            a = (a[0], a[1], np.sort(a[2]), a[3])
+            b = eh.fetch_kv(0, table, nb, s, cap, dst_fill=0xEE)
+            P.assert_kv_equal(a, b, name)
+        # no sequences at all
+        eh.h.fetch_kv(0, __import__("torch").zeros((0, 4), dtype=__import__("torch").int32, device="cuda"),
+                      None, None, None, None, 0)
+        counts, miss, n_miss = eh.h.fetch_info()
+        assert counts["n_requests"] == 0 and n_miss == 0
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- config 3, small: expert fetch with local / cached / host experts -------------------------------------------
+
+def test_expert_fetch_small():
+    say("experts small")
+    sh = W.ExpertShape(n_layers=4, n_experts=16, d_model=64, d_ff=100)          # 38 400-byte experts: ragged tiles
+    ex = W.expert_offload(seed=6, shape=sh, n_tokens=64)
+    eo, eh = P.make_engines(ex_wl=ex)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        assert np.array_equal(xo.place_status, xh.place_status)
+        for t in range(3):
+            for layer in range(4):
+                a, b = xo.fetch(t, layer), xh.fetch(t, layer)
+                P.assert_experts_equal(a, b, f"experts step {t} layer {layer}")
+                U = sorted(set(int(e) for e in ex.routing(t, layer).reshape(-1)))
+                assert [e for e in range(16) if b[0][e] is not None] == U
+        # staging too small, ids out of range
+        topk = np.array([[0, 1], [2, 3], [4, 5], [-7, 16], [6, 7]], np.int32)
+        for n_staging in (0, 2, 16):
+            a = eo.fetch_experts(1, topk, n_staging)
+            b = eh.fetch_experts(1, topk, n_staging)
+            P.assert_experts_equal(a, b, f"staging {n_staging}")
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- config 4, small: cache tier driven by an LRU policy --------------------------------------------------------
+
+def test_expert_lru_small():
+    say("experts lru small")
+    sh = W.ExpertShape(n_layers=3, n_experts=60, d_model=32, d_ff=44)
+    ex = W.expert_lru(seed=7, shape=sh, n_tokens=24, top_k=4)
+    eo, eh = P.make_engines(ex_wl=ex, poison=True)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        hits = 0
+        for t in range(6):
+            for layer in range(3):
+                a, b = xo.fetch(t, layer), xh.fetch(t, layer)
+                P.assert_experts_equal(a, b, f"lru step {t} layer {layer}")
+                hits += b[4]["n_cache"]
+                ua, ub = xo.lru_update(t, layer), xh.lru_update(t, layer)
+                assert ua[0] == ub[0] and ua[1] == ub[1] and ua[2] == ub[2] and np.array_equal(ua[3], ub[3])
+        assert hits > 0
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+        P.assert_tiers_equal(eo, eh, S.EXPERT, 1, tiers=(S.CACHE,), what="lru cache pool (poisoned slots included)")
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- config 5, small: KV and experts on two streams with periodic revocation -------------------------------------
+
+@pytest.mark.parametrize("overlap_revoke", [False, True])
+def test_revocation_stress_two_streams(overlap_revoke):
+    say(f"revocation stress overlap={overlap_revoke}")
+    wl = W.kv_decode(seed=8, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=60)
+    sh = W.ExpertShape(n_layers=2, n_experts=16, d_model=64, d_ff=100)
+    ex = W.expert_offload(seed=8, shape=sh, n_tokens=64)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        n_revoked = 0
+        for t in range(60):
+            layer = t % 2
+            revoke_now = t % 10 == 0 and t > 0
+            ha, hx = rh.fetch_begin(layer), xh.fetch_begin(t, layer)          # both in flight on their own streams
+            a, x = ro.fetch(layer), xo.fetch(t, layer)
+            if revoke_now and overlap_revoke:                                 # revoke while the fetches are in flight
+                rk_o, rk_h = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                rx_o, rx_h = xo.revoke_quarter(t), xh.revoke_quarter(t)
+            b, y = eh.fetch_end(ha), eh.fetch_end(hx)
+            racy = revoke_now and overlap_revoke      # such a fetch may have resolved before or after the revocation
+            P.assert_kv_equal(a, b, f"stress kv step {t}", counts=not racy)
+            P.assert_experts_equal(x, y, f"stress experts step {t}", counts=not racy)
+            if revoke_now and not overlap_revoke:
+                rk_o, rk_h = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                rx_o, rx_h = xo.revoke_quarter(t), xh.revoke_quarter(t)
+            if revoke_now:
+                assert np.array_equal(rk_o[0], rk_h[0]) and rk_o[1] == rk_h[1] == [int(i) for i in rk_o[0]]
+                assert np.array_equal(rx_o[0], rx_h[0]) and rx_o[1] == rx_h[1]
+                n_revoked += len(rk_o[0]) + len(rx_o[0])
+            if t % 10 == 5:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
+            ro.append(t); rh.append(t)
+        assert n_revoked > 20
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="stress kv")
+        P.assert_tiers_equal(eo, eh, S.EXPERT, 1, what="stress experts")
+    finally:
+        eh.close(); eo.close()
+
+
+# ---- lossy objects ------------------------------------------------------------------------------------------------
+
+def test_plain_copy_and_profile_counters():
+    import torch
+    from paper_2602_00328_amd import binding as B
+    say("plain copy")
+    for n in (16, 4096, 32768 + 16, 5 * 32768, (1 << 20) + 48):
+        src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        B.plain_copy(dst, src, n)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
+    with pytest.raises(B.HarvestError):
+        B.plain_copy(dst, src, 24)
+
+
+def test_smoke_entry():
+    say("smoke")
+    P.smoke()

@@ -51,11 +51,15 @@ def test_kv_decode_matches_the_config():
     nb = w.n_blocks()
     assert all(nb[s] == w.seq_lens[s] // 16 + 1 for s in range(4))
     ids = np.concatenate(w.tables + w.future_blocks)
-    assert len(set(ids)) == ids.size == w.n_objects
+    assert sorted(ids) == list(range(w.n_objects))
+    C = w.n_closed
+    assert [int(t[-1]) for t in w.tables] == [C + s for s in range(4)]
     assert all((w.seq_lens[s] + 200) // 16 + 1 == nb[s] + len(w.future_blocks[s]) for s in range(4))
+    opened = sorted((int(b), s) for s in range(4) for b in w.future_blocks[s])
+    assert [b for b, _ in opened] == list(range(C + 4, w.n_objects))      # numbered in opening order
     assert abs(w.resident.mean() - 0.7) < 0.02
-    tails = {int(t[-1]) for t in w.tables}
-    assert not (set(w.place_order) & tails)
+    assert set(w.place_order) == set(np.nonzero(w.resident[:C])[0])
+    assert sorted(w.host_slot) == list(range(w.n_objects)) and not np.array_equal(w.host_slot, np.arange(w.n_objects))
 
 
 def test_zipf_routing_draws_distinct_experts_with_the_stated_popularity():

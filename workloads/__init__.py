@@ -56,7 +56,7 @@ def _load():
         lib.wl_fill_pool.restype = None
         lib.wl_fill_pool.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_size_t,
                                      ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
-                                     ctypes.c_int, ctypes.c_void_p]
+                                     ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32]
         _lib = lib
     return _lib
 
@@ -85,10 +85,12 @@ def normal_table(sigma: float) -> np.ndarray:
 
 
 def fill_pool(pool_ptr: int, n_layers: int, n_slots: int, chunk_bytes: int, slot_object: np.ndarray,
-              seed: int, cls: int, plane: int, mode: int = FILL_NORMAL, sigma: float = 1.0) -> None:
+              seed: int, cls: int, plane: int, mode: int = FILL_NORMAL, sigma: float = 1.0,
+              layer_base: int = 0) -> None:
     """Fill a pool plane laid out [layer][slot][chunk_bytes] at raw address ``pool_ptr``.
 
-    ``slot_object[s]`` is the object whose bytes go to slot s (NO_OBJECT = leave untouched).
+    ``slot_object[s]`` is the object whose bytes go to slot s (NO_OBJECT = leave untouched); the buffer's first
+    layer is model layer ``layer_base``.
     """
     assert chunk_bytes % 16 == 0
     so = np.ascontiguousarray(slot_object, dtype=np.uint32)
@@ -96,14 +98,15 @@ def fill_pool(pool_ptr: int, n_layers: int, n_slots: int, chunk_bytes: int, slot
     table = normal_table(sigma) if mode == FILL_NORMAL else None
     _load().wl_fill_pool(ctypes.c_void_p(pool_ptr), n_layers, n_slots, chunk_bytes,
                          so.ctypes.data_as(ctypes.c_void_p), ctypes.c_uint64(seed & (2**64 - 1)), cls, plane, mode,
-                         table.ctypes.data_as(ctypes.c_void_p) if table is not None else None)
+                         table.ctypes.data_as(ctypes.c_void_p) if table is not None else None, layer_base)
 
 
 def fill_array(arr: np.ndarray, slot_object, seed: int, cls: int, plane: int,
-               mode: int = FILL_NORMAL, sigma: float = 1.0) -> None:
+               mode: int = FILL_NORMAL, sigma: float = 1.0, layer_base: int = 0) -> None:
     """fill_pool on a C-contiguous uint8 array of shape [n_layers, n_slots, chunk_bytes]."""
     assert arr.dtype == np.uint8 and arr.flags.c_contiguous and arr.ndim == 3
-    fill_pool(arr.ctypes.data, arr.shape[0], arr.shape[1], arr.shape[2], slot_object, seed, cls, plane, mode, sigma)
+    fill_pool(arr.ctypes.data, arr.shape[0], arr.shape[1], arr.shape[2], slot_object, seed, cls, plane, mode, sigma,
+              layer_base)
 
 
 def chunk(seed: int, cls: int, plane: int, layer: int, obj: int, chunk_bytes: int,
@@ -150,12 +153,16 @@ class KVShape:
 
 @dataclass
 class KVWorkload:
+    """Object numbering: closed blocks 0..C-1, then the open tail of each sequence, then the blocks that decode steps
+    open, in the order they are opened - i.e. the order in which a harness registers them."""
     shape: KVShape
     seed: int
     seq_lens: np.ndarray                 # tokens per sequence at step 0
     n_objects: int                       # logical blocks, including those that decode steps will open
-    tables: list                         # per sequence: int32 logical block ids, in order; last one is the open tail
-    future_blocks: list                  # per sequence: ids of the blocks opened by later steps
+    tables: list                         # per sequence: int32 block numbers in order; with has_tails the last is the open tail
+    has_tails: bool
+    future_blocks: list                  # per sequence: numbers of the blocks opened by later steps
+    host_slot: np.ndarray                # int64[n_objects]: a seeded permutation, so host slot != block number
     resident: np.ndarray                 # bool[n_objects]: goes to the cache tier once the block is closed
     place_order: np.ndarray              # closed blocks with resident=True, in the seeded order they are placed
     p_cache: float
@@ -165,6 +172,10 @@ class KVWorkload:
     @property
     def n_seq(self) -> int:
         return len(self.tables)
+
+    @property
+    def n_closed(self) -> int:
+        return sum(len(t) for t in self.tables) - (self.n_seq if self.has_tails else 0)
 
     def n_blocks(self) -> np.ndarray:
         return np.array([len(t) for t in self.tables], dtype=np.int32)
@@ -181,7 +192,8 @@ def kv_tiny(seed: int = 0, fill_mode: int = FILL_NORMAL) -> KVWorkload:
     resident = np.zeros(n_pool, dtype=bool)
     resident[order[:n_res]] = True
     return KVWorkload(shape=shape, seed=seed, seq_lens=np.full(n_seq, 256, dtype=np.int64), n_objects=n_pool,
-                      tables=tables, future_blocks=[np.zeros(0, np.int32) for _ in range(n_seq)],
+                      tables=tables, has_tails=False, future_blocks=[np.zeros(0, np.int32) for _ in range(n_seq)],
+                      host_slot=rng(seed, 3).permutation(n_pool).astype(np.int64),
                       resident=resident, place_order=order[:n_res].copy(), p_cache=0.6, fill_mode=fill_mode)
 
 
@@ -190,27 +202,32 @@ def kv_decode(seed: int = 0, n_layers: int = 32, n_seq: int = 4, min_len: int = 
               shape: KVShape | None = None) -> KVWorkload:
     """Long-context decode: sequence lengths ~U[min_len, max_len], blocks i.i.d. Bernoulli(p_cache) in the cache tier.
 
-    Every sequence ends in an open tail block (local tier) that decode steps append to; blocks a sequence will
-    open during ``n_steps`` steps are pre-numbered in ``future_blocks``.
+    Every sequence ends in an open tail block (local tier) that decode steps append to.  A step appends one token
+    per sequence; a tail that becomes full is closed and a new one opened, so the blocks opened during ``n_steps``
+    steps are numbered here in (step, sequence) order.
     """
     shape = shape or KVShape(n_layers=n_layers)
     bt = shape.block_tokens
     lens = rng(seed, 10).integers(min_len, max_len + 1, size=n_seq).astype(np.int64)
-    # blocks at step 0: a length that is a multiple of the block size still owns an (empty) open tail
-    n_now = [int(l // bt) + 1 for l in lens]
-    n_future = [int((l + n_steps) // bt) + 1 - nb for l, nb in zip(lens, n_now)]
-    total = sum(n_now) + sum(n_future)
-    perm = rng(seed, 11).permutation(total).astype(np.int32)
-    tables, future, at = [], [], 0
-    for nb in n_now:
-        tables.append(perm[at:at + nb].copy()); at += nb
-    for nf in n_future:
-        future.append(perm[at:at + nf].copy()); at += nf
+    n_closed = [int(l // bt) for l in lens]             # a length that is a multiple of bt owns an empty open tail
+    C = sum(n_closed)
+    perm = rng(seed, 11).permutation(C).astype(np.int32)
+    tables, at = [], 0
+    for s, nc in enumerate(n_closed):
+        tables.append(np.concatenate([perm[at:at + nc], np.array([C + s], np.int32)])); at += nc
+    future = [[] for _ in range(n_seq)]
+    nxt = C + n_seq
+    for t in range(n_steps):
+        for s in range(n_seq):
+            if (lens[s] + t + 1) % bt == 0:
+                future[s].append(nxt); nxt += 1
+    total = nxt
     resident = rng(seed, 12).random(total) < p_cache
-    closed = np.concatenate([t[:-1] for t in tables]) if tables else np.zeros(0, np.int32)
-    order = closed[rng(seed, 13).permutation(closed.size)]
-    place_order = order[resident[order]].astype(np.int32)
-    return KVWorkload(shape=shape, seed=seed, seq_lens=lens, n_objects=total, tables=tables, future_blocks=future,
+    order = rng(seed, 13).permutation(C).astype(np.int32)
+    place_order = order[resident[order]]
+    return KVWorkload(shape=shape, seed=seed, seq_lens=lens, n_objects=total, tables=tables, has_tails=True,
+                      future_blocks=[np.array(f, np.int32) for f in future],
+                      host_slot=rng(seed, 14).permutation(total).astype(np.int64),
                       resident=resident, place_order=place_order, p_cache=p_cache, fill_mode=fill_mode)
 
 

@@ -75,16 +75,18 @@ void wl_fill_chunk_tag(uint32_t *dst, size_t chunk_bytes, uint64_t seed, uint32_
 /*
  * Fill a whole pool plane laid out [layer][slot][chunk_bytes].
  * slot_object[s] = object id whose bytes go to slot s, or 0xFFFFFFFF to leave
- * the slot untouched.  mode 0 = normal (table required), 1 = tag.
+ * the slot untouched.  mode 0 = normal (table required), 1 = tag.  The first
+ * layer of the buffer is model layer layer_base (a buffer may hold a slice of
+ * the layers).
  */
 void wl_fill_pool(void *pool, uint32_t n_layers, uint32_t n_slots, size_t chunk_bytes,
                   const uint32_t *slot_object, uint64_t seed, uint32_t cls, uint32_t plane,
-                  int mode, const uint16_t *table)
+                  int mode, const uint16_t *table, uint32_t layer_base)
 {
     long total = (long)n_layers * (long)n_slots;
 #pragma omp parallel for schedule(static)
     for (long i = 0; i < total; ++i) {
-        uint32_t layer = (uint32_t)(i / n_slots);
+        uint32_t layer = layer_base + (uint32_t)(i / n_slots);
         uint32_t slot = (uint32_t)(i % n_slots);
         uint32_t obj = slot_object[slot];
         if (obj == 0xFFFFFFFFu)
