@@ -11,6 +11,10 @@ import os
 from dataclasses import dataclass
 
 import numpy as np
+import torch  # noqa: F401  - must be imported BEFORE the library is loaded: PyTorch bundles its own HIP runtime
+#                (same SONAME as the system one), and a process must hold exactly one; loading libharvest.so after
+#                torch makes the dynamic loader bind it to the runtime torch already mapped, so streams and device
+#                pointers are shared.
 
 from . import _build
 
@@ -114,7 +118,6 @@ def _dev_ptr(t):
 
 def _stream_ptr(stream):
     if stream is None:
-        import torch
         stream = torch.cuda.current_stream()
     if isinstance(stream, int):
         return vp(stream)
@@ -158,7 +161,6 @@ class Harvest:
             cc.n_host_slots, cc.n_cache_slots, cc.n_local_slots = sp.n_host_slots, sp.n_cache_slots, sp.n_local_slots
             if self.no_device:
                 continue
-            import torch
             dev = torch.device("cuda", device)
             for p in range(sp.n_planes):
                 nbytes = sp.n_layers * sp.n_host_slots * sp.chunk_bytes

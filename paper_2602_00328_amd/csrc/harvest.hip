@@ -319,7 +319,11 @@ const char *harvest_strerror(int status)
 void *harvest_pinned_alloc(size_t bytes)
 {
     void *p = nullptr;
-    if (hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault) != hipSuccess) return nullptr;
+    hipError_t e = hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        fprintf(stderr, "libharvest: hipHostMalloc(%zu) failed: %s\n", bytes, hipGetErrorString(e));
+        return nullptr;
+    }
     return p;
 }
 

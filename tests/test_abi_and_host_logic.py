@@ -27,6 +27,11 @@ def test_library_exports_every_declared_symbol_and_nothing_is_undeclared():
     assert declared <= exported, declared - exported
 
 
+def test_process_holds_exactly_one_hip_runtime():
+    mapped = {l.split()[-1] for l in open("/proc/self/maps") if "libamdhip64" in l}
+    assert len(mapped) == 1, mapped
+
+
 def test_struct_layouts_match_the_header(tmp_path):
     src = tmp_path / "sz.c"
     src.write_text('#include <stdio.h>\n#include "harvest.h"\nint main(void){printf("%zu %zu %zu %zu %zu %zu\\n",'

@@ -175,7 +175,8 @@ class KVWorkload:
 
     @property
     def n_closed(self) -> int:
-        return sum(len(t) for t in self.tables) - (self.n_seq if self.has_tails else 0)
+        """Blocks that exist, closed, at step 0 (for the tiny config: the whole pool, requested or not)."""
+        return self.n_objects - (self.n_seq if self.has_tails else 0) - sum(len(f) for f in self.future_blocks)
 
     def n_blocks(self) -> np.ndarray:
         return np.array([len(t) for t in self.tables], dtype=np.int32)
