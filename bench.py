@@ -1,0 +1,310 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiered cache fetch on one MI355X.
+
+Workload (benchmark configs[1]): long-context KV decode fetch, Llama-3-8B-shaped - 32 layers, 8 KV heads x 128,
+bf16, 16-token blocks (32 KiB K + 32 KiB V per block per layer), 4 sequences with seeded lengths in [32K, 128K] tokens,
+70% of the closed blocks in the HBM cache tier, 30% host-only.  One step = one pass of the whole hot path: resolve every
+block of every sequence through the device directory, gather one layer's K and V into the contiguous working layout
+(HBM tier on the caller's stream, host tier over PCIe on the side stream, joined), append one token per sequence, and,
+when a tail block fills, write it back, demote it, place it in the cache tier and open a new tail.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=32, help="layers materialised in the pools (footprint knob)")
+    ap.add_argument("--iso-steps", type=int, default=20, help="fetches per isolation point (100%% cache / 100%% host)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-isolation", action="store_true")
+    ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
+    return ap.parse_args()
+
+
+class DeviceDecode:
+    """Keeps the decode state of workloads.scenarios.KVRun on the device so that a timed step moves no table or
+    payload over PCIe except what the method itself moves."""
+
+    def __init__(self, run, eng, wl, n_steps):
+        import numpy as np
+        import torch
+        import workloads as W
+        self.run, self.eng, self.wl = run, eng, wl
+        self.dev = eng.dev
+        sh = wl.shape
+        table, nb = run.table_arrays()
+        self.d_table = torch.from_numpy(table).to(self.dev)
+        self.d_nb = torch.from_numpy(nb).to(self.dev)
+        self.d_sdb = torch.from_numpy(run.seq_dst_block.view(np.int64)).to(self.dev)
+        self.dst = [torch.zeros(run.cap * sh.chunk_bytes, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        # the rows every step appends, generated up front: [step][plane][layer][seq][row_bytes]
+        rows = np.empty((n_steps, 2, sh.n_layers, wl.n_seq, sh.row_bytes), dtype=np.uint8)
+        for t in range(n_steps):
+            for s in range(wl.n_seq):
+                rows[t, :, :, s] = W.append_rows(wl, t, s)
+        self.rows = torch.from_numpy(rows).to(self.dev)
+        self.local = [eng.h.dev_plane(0, 2, p).view(sh.n_layers, -1, sh.row_bytes) for p in range(2)]
+        self.t = 0
+
+    def fetch(self, layer):
+        self.eng.fetch_kv_device(layer, self.d_table, self.d_nb, self.d_sdb, self.run.cap, dst=self.dst)
+
+    def step(self):
+        import torch
+        run, wl, sh = self.run, self.wl, self.wl.shape
+        t = self.t
+        self.fetch(t % sh.n_layers)
+        # append one token per sequence: rows go straight into the open tail blocks in local HBM
+        idx = []
+        for s in range(wl.n_seq):
+            slot = self.eng.h.lookup(0, run.tables[s][-1])[1]
+            idx.append(slot * sh.block_tokens + run.lens[s] % sh.block_tokens)
+        d_idx = torch.tensor(idx, dtype=torch.int64, device=self.dev)
+        for p in range(2):
+            self.local[p].index_copy_(1, d_idx, self.rows[t, p])
+        for s in range(wl.n_seq):
+            run.lens[s] += 1
+            if run.lens[s] % sh.block_tokens == 0:
+                tail = run.tables[s][-1]
+                self.eng.evict_from_local(0, [tail], 1)
+                if wl.resident[tail]:
+                    self.eng.place(0, [tail])
+                new = int(wl.future_blocks[s][run.n_future[s]])
+                run.n_future[s] += 1
+                got = self.eng.register(0, 1, wl.host_slot[new:new + 1], 2)
+                assert int(got[0]) == new
+                run.tables[s].append(new)
+                self.d_table[s, len(run.tables[s]) - 1] = new
+                self.d_nb[s] += 1
+        self.t += 1
+
+
+COUNT_KEYS = ("n_requests", "n_local", "n_cache", "n_host", "n_lost", "n_invalid")
+
+
+def kv_totals(stats):
+    return {k: int(getattr(stats.fetch[0], k)) for k in COUNT_KEYS}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); the path has no collectives - "
+            "see DESIGN.md for how it would shard.")
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import workloads as W
+    from workloads import scenarios as S
+    from paper_2602_00328_amd import binding as B
+    from paper_2602_00328_amd.engine import HipEngine
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda", 0)
+    n_total = args.warmup + args.steps
+    t0 = time.time()
+    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total)
+    sh = wl.shape
+    chunk = sh.chunk_bytes
+    n_blocks0 = int(sum(len(t) for t in wl.tables))
+    log(f"[bench] workload: {wl.n_seq} sequences, lengths {wl.seq_lens.tolist()}, {n_blocks0} blocks, "
+        f"{args.layers} layers materialised, host pool {wl.n_objects * 2 * chunk * args.layers / 2**30:.1f} GiB")
+    all_cache_slack = int(wl.n_objects - wl.resident.sum())
+    eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack), profile=True)
+    run = S.KVRun(eng, wl)
+    torch.cuda.synchronize()
+    log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
+    dd = DeviceDecode(run, eng, wl, n_total)
+
+    # ---- calibration kernel of known size (for hardware byte counters) + achievable-copy ceiling ----
+    cal_bytes = 2 << 30
+    src = torch.empty(cal_bytes, dtype=torch.uint8, device=dev).random_(0, 256)
+    dstc = torch.empty(cal_bytes, dtype=torch.uint8, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    B.plain_copy(dstc, src, cal_bytes)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(max(1, args.calibrate)):
+        B.plain_copy(dstc, src, cal_bytes)
+    ev[1].record()
+    torch.cuda.synchronize()
+    plain_gbs = 2 * cal_bytes * max(1, args.calibrate) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    del src, dstc
+    # ---- PCIe peak: 1 GiB pinned -> device DMA, median of 10 ----
+    pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    dbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    ts = []
+    for _ in range(11):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        dbuf.copy_(pin, non_blocking=True)
+        torch.cuda.synchronize()
+        ts.append(time.perf_counter() - a)
+    pcie_peak_gbs = (1 << 30) / float(np.median(ts[1:])) / 1e9
+    del pin, dbuf
+    log(f"[bench] plain copy {plain_gbs:.0f} GB/s read+write; PCIe H2D DMA peak {pcie_peak_gbs:.1f} GB/s")
+
+    # ---- warm-up, then the timed region ----
+    for _ in range(args.warmup):
+        dd.step()
+    torch.cuda.synchronize()
+    eng.h.profile()
+    c0 = kv_totals(eng.h.stats())
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        dd.step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    pr = eng.h.profile()
+    c1 = kv_totals(eng.h.stats())
+    d = {k: c1[k] - c0[k] for k in COUNT_KEYS}
+    sec = t_end - t_start
+    ms_per_step = sec * 1e3 / args.steps
+    payload = d["n_requests"] * 2 * chunk                   # bytes delivered into the working layout
+    hbm_payload = (d["n_local"] + d["n_cache"]) * 2 * chunk
+    host_payload = d["n_host"] * 2 * chunk
+    value = 2 * payload / sec / 1e9
+    hbm_ms = pr.hbm_ms / max(1, pr.hbm_launches)
+    host_ms = pr.host_ms / max(1, pr.host_launches)
+    hbm_alg_bytes = 2 * hbm_payload / max(1, pr.hbm_launches)     # read + write, per launch
+    host_bytes = host_payload / max(1, pr.host_launches)
+    hbm_gbs = hbm_alg_bytes / (hbm_ms * 1e-3) / 1e9
+    host_gbs = host_bytes / (host_ms * 1e-3) / 1e9
+    log(f"[bench] {args.steps} steps in {sec:.3f}s: {ms_per_step:.3f} ms/step, {value:.0f} GB/s read+write, "
+        f"HBM-tier kernel {hbm_ms:.3f} ms ({hbm_gbs:.0f} GB/s), host-tier kernel {host_ms:.3f} ms ({host_gbs:.1f} GB/s)")
+
+    # ---- bit-exactness of the timed configuration against the oracle, and the oracle's own speed ----
+    bit_exact, cpu_baseline = None, None
+    if not args.no_cpu_baseline:
+        from oracle.engine import OracleEngine
+        layer = dd.t % sh.n_layers
+        ncores = len(os.sched_getaffinity(0))
+        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total)
+        eo = OracleEngine(kv=S.kv_spec(wl1, cache_slack=0 if args.no_isolation else all_cache_slack), kv_layers=[layer],
+                          threads=ncores)
+        ro = S.KVRun(eo, wl1)
+        for t in range(n_total):                         # bring the oracle to the same point of the decode
+            ro.append(t)
+        want = ro.fetch(layer)
+        dd.fetch(layer)
+        torch.cuda.synchronize()
+        counts, miss, n_miss = eng.h.fetch_info(miss_cap=dd.d_table.numel())
+        got_k, got_v = dd.dst[0].cpu().numpy(), dd.dst[1].cpu().numpy()
+        bit_exact = bool(np.array_equal(want[0], got_k) and np.array_equal(want[1], got_v) and counts == want[3]
+                         and np.array_equal(np.sort(miss), want[2]))
+        log(f"[bench] layer {layer} after {n_total} steps vs oracle: bit_exact={bit_exact}")
+        step_payload = want[3]["n_requests"] * 2 * chunk
+        res = {}
+        for threads in (1, ncores):
+            eo.threads = threads
+            ro.fetch(layer)
+            a = time.perf_counter()
+            n = 0
+            while n < 3 or time.perf_counter() - a < 6.0:
+                ro.fetch(layer)
+                n += 1
+            res[threads] = 2 * step_payload * n / (time.perf_counter() - a) / 1e9
+        cpu_baseline = {"value": round(res[ncores], 2), "unit": "GB/s", "cores": ncores, "kind": "oracle",
+                        "single_thread_value": round(res[1], 2),
+                        "sample": f"the same decode state, one layer's full fetch ({want[3]['n_requests']} blocks, "
+                                  f"{step_payload / 2**30:.2f} GiB payload) repeated for >= 6 s per thread count, "
+                                  "all tiers in host DRAM"}
+        log(f"[bench] oracle: {res[1]:.1f} GB/s on 1 thread, {res[ncores]:.1f} GB/s on {ncores} threads")
+        eo.close()
+
+    # ---- isolation points: the same request list with every block in the cache tier, then every block on the host ----
+    iso = {}
+    if not args.no_isolation:
+        closed = [b for s in range(wl.n_seq) for b in run.tables[s][:-1]]
+        host_only = [b for b in closed if eng.lookup(0, b)[0] == 0]
+        st = eng.place(0, host_only)
+        assert (st == 0).all()
+        torch.cuda.synchronize()
+        for name, n_it in (("all_cache", args.iso_steps), ("all_host", max(2, args.iso_steps // 4))):
+            if name == "all_host":
+                eng.revoke(0, closed)
+            dd.fetch(0)
+            torch.cuda.synchronize()
+            counts, _, _ = eng.h.fetch_info()
+            eng.h.profile()
+            a = time.perf_counter()
+            for i in range(n_it):
+                dd.fetch(i % sh.n_layers)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - a
+            p = eng.h.profile()
+            pay = counts["n_requests"] * 2 * chunk
+            if name == "all_cache":
+                k_ms = p.hbm_ms / p.hbm_launches
+                iso[name] = {"ms_per_fetch": round(dt * 1e3 / n_it, 4), "kernel_ms": round(k_ms, 4),
+                             "hbm_gbs_read_write": round(2 * pay / (k_ms * 1e-3) / 1e9, 1),
+                             "frac_of_hbm_peak": round(2 * pay / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                             "objects_per_s": round(counts["n_requests"] / (dt / n_it))}
+            else:
+                k_ms = p.host_ms / p.host_launches
+                g = counts["n_host"] * 2 * chunk / (k_ms * 1e-3) / 1e9
+                iso[name] = {"ms_per_fetch": round(dt * 1e3 / n_it, 4), "kernel_ms": round(k_ms, 4),
+                             "pcie_gbs": round(g, 2), "frac_of_pcie_peak": round(g / pcie_peak_gbs, 4),
+                             "objects_per_s": round(counts["n_requests"] / (dt / n_it))}
+            log(f"[bench] isolation {name}: {iso[name]}")
+
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "copy_items_hbm_kv_decode_pmc.txt")
+    if os.path.exists(tf):
+        m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tf).read())
+        if m:
+            traffic = float(m.group(1))
+
+    out = {
+        "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "configs[1]: long-context KV decode fetch, Llama-3-8B-shaped (32 layers, 8 KV heads x 128, "
+                               "bf16, block 16), 4 sequences U[32K,128K] tokens, 70% HBM cache tier / 30% host, one layer "
+                               "gathered per step, one token appended per step",
+                   "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
+                   "payload_bytes_per_step": payload // args.steps},
+        "objects_per_s": round(d["n_requests"] / sec),
+        "bit_exact": bit_exact,
+        "served": {k: v // args.steps for k, v in d.items()},
+        "roofline": {"bound": "hbm", "kernel": "copy_items<1,true> (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
+                     "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1)},
+        "host_tier": {"bound": "pcie", "kernel": "copy_items<8,false> (host-tier gather, zero-copy over PCIe)",
+                      "achieved": round(host_gbs, 2), "peak": round(pcie_peak_gbs, 2), "unit": "GB/s",
+                      "frac": round(host_gbs / pcie_peak_gbs, 4), "launches": int(pr.host_launches),
+                      "avg_launch_ms": round(host_ms, 5), "bytes_per_launch": round(host_bytes),
+                      "peak_source": "1 GiB pinned->device hipMemcpyAsync, median of 10, same run"},
+        "overlap": {"max_kernel_ms_over_step_ms": round(max(hbm_ms, host_ms) / ms_per_step, 4)},
+        "isolation": iso,
+        "cpu_baseline": cpu_baseline,
+    }
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

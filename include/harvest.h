@@ -96,8 +96,9 @@ typedef struct harvest_config {
     uint32_t flags;                 /* harvest_flags */
     int32_t device;                 /* HIP device ordinal the pools live on */
     harvest_class_config cls[HARVEST_N_CLASSES];
-    uint32_t gather_wg_per_cu;      /* persistent workgroups per CU for the HBM-tier gather; 0 = default */
-    uint32_t host_wgs;              /* workgroups of the host-tier (PCIe) gather; 0 = default */
+    uint32_t gather_wg_per_cu;      /* tuning: cap the HBM-tier gather at this many workgroups per CU (they then loop
+                                       over tiles); 0 = default, one workgroup per 4 KiB tile */
+    uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (8) */
     uint32_t reserved[6];           /* must be 0 */
 } harvest_config;
 

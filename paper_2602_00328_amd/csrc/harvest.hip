@@ -91,6 +91,10 @@ struct StreamState {
     // control scratch (host-built lists)
     void *ctl_buf = nullptr;
     size_t ctl_cap = 0;
+    // pinned words the HBM-tier gather reports its request count to, per class: a hint for the next grid size
+    uint32_t *h_feedback = nullptr;
+    uint32_t *d_feedback = nullptr;
+    bool feedback_valid[HARVEST_N_CLASSES] = { false, false };
 };
 
 }  // namespace
@@ -99,7 +103,7 @@ struct harvest_ctx {
     harvest_config cfg{};
     bool no_device = false, poison = false, profile = false;
     int n_cu = 256;
-    uint32_t gather_grid = 0, host_grid = 0;
+    uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0;
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
@@ -131,6 +135,9 @@ int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ss->cnt, 2 * C_N * sizeof(uint32_t)));
     HIP_TRY(hipMemset(ss->cnt, 0, 2 * C_N * sizeof(uint32_t)));
+    HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
+    memset(ss->h_feedback, 0, 64);
+    HIP_TRY(hipHostGetDevicePointer((void **)&ss->d_feedback, ss->h_feedback, 0));
     *out = ss.get();
     ctx->streams[s] = std::move(ss);
     return HARVEST_OK;
@@ -196,7 +203,9 @@ int release_after(Staging *st, hipStream_t s)
     return HARVEST_OK;
 }
 
-uint32_t tiles_per_chunk(uint64_t chunk_bytes) { return (uint32_t)((chunk_bytes + TILE - 1) / TILE); }
+uint32_t tiles_per_chunk(uint64_t chunk_bytes, uint32_t tile) { return (uint32_t)((chunk_bytes + tile - 1) / tile); }
+
+constexpr uint32_t MAX_GRID = 0x7FFFFFFFu;
 
 uint32_t grid_for(uint64_t n_tiles, uint32_t max_grid)
 {
@@ -261,30 +270,48 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 }
 
 // Launches the HBM-tier gather on the caller's stream and the host-tier gather on the side stream, joined back.
-int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, uint32_t items_per_req, uint32_t *cnt)
+// max_req bounds the number of requests either list can hold; the HBM-tier grid has one workgroup per tile of that
+// bound (workgroups beyond the device-side count exit at once).
+int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t items_per_req, uint32_t *cnt,
+                   uint64_t max_req)
 {
-    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
+    uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
+    uint32_t tpc_host = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
     if (ctx->profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
-    if (pa) HIP_TRY(hipEventRecord(pa, ss->s));
-    hipLaunchKernelGGL(copy_items<true>, dim3(ctx->gather_grid), dim3(WG), 0, ss->s, ss->hbm_items, cnt + C_HBM_REQ, 0u,
-                       items_per_req, c.cfg.chunk_bytes, tpc);
-    HIP_TRY(hipGetLastError());
-    if (pb) HIP_TRY(hipEventRecord(pb, ss->s));
-    if (c.cfg.n_host_slots) {
+    bool host_tier = c.cfg.n_host_slots != 0;
+    if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
         if (pc) HIP_TRY(hipEventRecord(pc, ss->side));
-        hipLaunchKernelGGL(copy_items<false>, dim3(ctx->host_grid), dim3(WG), 0, ss->side, ss->host_items,
-                           cnt + C_HOST_REQ, 0u, items_per_req, c.cfg.chunk_bytes, tpc);
+        hipLaunchKernelGGL((copy_items<UNROLL_HOST, false>), dim3(ctx->host_grid), dim3(WG), 0, ss->side,
+                           ss->host_items, cnt + C_HOST_REQ, 0u, items_per_req, c.cfg.chunk_bytes, tpc_host,
+                           (uint32_t *)nullptr);
         HIP_TRY(hipGetLastError());
         if (pd) HIP_TRY(hipEventRecord(pd, ss->side));
     }
+    // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the
+    // previous gather of this class on this stream reported (plus slack), never below a floor that still fills the
+    // chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
+    uint64_t max_tiles = max_req * items_per_req * tpc_hbm;
+    uint64_t want = max_tiles;
+    if (ss->feedback_valid[cls]) {
+        uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
+        uint64_t guess = (seen + seen / 16 + 8) * items_per_req * tpc_hbm;
+        want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
+    }
+    uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
+    if (pa) HIP_TRY(hipEventRecord(pa, ss->s));
+    hipLaunchKernelGGL((copy_items<1, true>), dim3(grid), dim3(WG), 0, ss->s, ss->hbm_items, cnt + C_HBM_REQ, 0u,
+                       items_per_req, c.cfg.chunk_bytes, tpc_hbm, ss->d_feedback + cls);
+    ss->feedback_valid[cls] = true;
+    HIP_TRY(hipGetLastError());
+    if (pb) HIP_TRY(hipEventRecord(pb, ss->s));
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
     if (ctx->profile) {
         ctx->prof.push_back({ pa, pb, 0 });
-        if (c.cfg.n_host_slots) ctx->prof.push_back({ pc, pd, 1 });
+        if (host_tier) ctx->prof.push_back({ pc, pd, 1 });
         else { ctx->prof_pool.push_back(pc); ctx->prof_pool.push_back(pd); }
     }
     return mark_last(ss);
@@ -379,8 +406,9 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
         hipDeviceProp_t prop;
         HIP_TRY(hipGetDeviceProperties(&prop, cfg->device));
         ctx->n_cu = prop.multiProcessorCount;
-        ctx->gather_grid = (cfg->gather_wg_per_cu ? cfg->gather_wg_per_cu : 8) * ctx->n_cu;
-        ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 64;
+        ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
+        ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 8;
+        ctx->ctl_grid = 8 * ctx->n_cu;
         HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
         HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
         HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
@@ -423,6 +451,7 @@ int harvest_destroy(harvest_ctx *ctx)
             for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
             (void)hipFree(ss->hbm_items); (void)hipFree(ss->host_items); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
             (void)hipFree(ss->ctl_buf);
+            (void)hipHostFree(ss->h_feedback);
         }
         for (auto &st : ctx->staging) { (void)hipEventDestroy(st.done); (void)hipHostFree(st.h); }
         for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
@@ -529,10 +558,10 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     memcpy(st->h, items.data(), bytes);
     HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
     if ((rc = release_after(st, ss->s))) return rc;
-    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
-    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
-    hipLaunchKernelGGL(copy_items<false>, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf,
-                       (const uint32_t *)nullptr, (uint32_t)items.size(), 1u, c.cfg.chunk_bytes, tpc);
+    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
+    hipLaunchKernelGGL((copy_items<UNROLL_HOST, false>), dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf,
+                       (const uint32_t *)nullptr, (uint32_t)items.size(), 1u, c.cfg.chunk_bytes, tpc, (uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
     // the new entries become visible only after the copy; later work on `stream` waits for the publication
     HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
@@ -586,8 +615,8 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
                 memcpy(st->h, items.data(), bytes);
                 void *d_items = nullptr;
                 HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
-                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
-                uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
+                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+                uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
                 hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items,
                                    (uint32_t)items.size(), c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
                 HIP_TRY(hipGetLastError());
@@ -630,7 +659,7 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
     HIP_TRY(hipGetLastError());
     ss->last_cur = ss->cur;
     ss->cur ^= 1;
-    return launch_gathers(ctx, ss, c, c.cfg.n_planes, cnt);
+    return launch_gathers(ctx, ss, c, HARVEST_KV, c.cfg.n_planes, cnt, total);
 }
 
 int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,
@@ -657,7 +686,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     HIP_TRY(hipGetLastError());
     ss->last_cur = ss->cur;
     ss->cur ^= 1;
-    return launch_gathers(ctx, ss, c, 1, cnt);
+    return launch_gathers(ctx, ss, c, HARVEST_EXPERT, 1, cnt, std::min<uint64_t>(E, n_staging_slots));
 }
 
 int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
@@ -750,8 +779,8 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         memcpy(st->h, items.data(), bytes);
         HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
         if ((rc = release_after(st, ss->s))) return rc;
-        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes);
-        uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->gather_grid);
+        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+        uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
         hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
                            (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
         HIP_TRY(hipGetLastError());
@@ -823,9 +852,10 @@ int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *str
     HIP_TRY(hipGetDevice(&dev));
     int n_cu = 0;
     HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    uint64_t n_tiles = (bytes + TILE - 1) / TILE;
-    uint32_t grid = grid_for(n_tiles, 8u * (uint32_t)n_cu);
-    hipLaunchKernelGGL(plain_copy<true>, dim3(grid), dim3(WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
+    (void)n_cu;
+    uint64_t n_tiles = (bytes + TILE_HBM - 1) / TILE_HBM;
+    uint32_t grid = grid_for(n_tiles, MAX_GRID);
+    hipLaunchKernelGGL(plain_copy, dim3(grid), dim3(WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
                        bytes);
     HIP_TRY(hipGetLastError());
     return HARVEST_OK;

@@ -4,8 +4,11 @@
 //   resolve_kv / resolve_experts : directory lookup (paper Section 5.2 block table, Section 4.3 residency map),
 //                                  classification by tier, wave-level compaction into an HBM list and a host
 //                                  (miss) list;
-//   copy_items                   : the gather itself - one workgroup per 32 KiB tile, 16-byte vector accesses,
-//                                  all loads of a tile in flight before its first store;
+//   copy_items                   : the gather itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte
+//                                  non-temporal load and store per thread, as many workgroups as tiles (measured
+//                                  on MI355X: many short workgroups beat deep unrolling and persistent grids by
+//                                  ~15%).  Host tier: a few persistent workgroups with 8 loads in flight per
+//                                  thread, enough to keep the PCIe link full while leaving the CUs to the HBM tier;
 //   copy_items2                  : the scatter of the write-back path (one source, up to two destinations);
 //   fill_items, dir_write        : slot poisoning after revocation, directory publication.
 #pragma once
@@ -17,8 +20,9 @@ namespace hv {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WG = 256;                         // 4 wavefronts
-constexpr int UNROLL = 8;                       // 16-byte accesses per thread per tile
-constexpr uint32_t TILE = WG * 16 * UNROLL;     // 32 KiB: one KV chunk at the paper-shaped config
+constexpr uint32_t TILE_HBM = WG * 16;          // 4 KiB: one 16-byte access per thread
+constexpr int UNROLL_HOST = 8;
+constexpr uint32_t TILE_HOST = WG * 16 * UNROLL_HOST;   // 32 KiB: 8 accesses in flight per thread over PCIe
 
 // directory entry: [1:0] tier, [31:2] slot in that tier (host slot for HOST), [63:32] generation
 constexpr uint64_t TIER_MASK = 3;
@@ -262,12 +266,13 @@ __device__ inline void st16(u32x4 *p, u32x4 v)
     else *p = v;
 }
 
-template <bool NT>
+template <int UNROLL, bool NT>
 __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint32_t tid)
 {
+    constexpr uint32_t TILE = WG * 16 * UNROLL;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
     u32x4 *d = reinterpret_cast<u32x4 *>(dst);
-    if (len == TILE) {
+    if (len >= TILE) {
         u32x4 v[UNROLL];
 #pragma unroll
         for (int i = 0; i < UNROLL; ++i) v[i] = ld16<NT>(s + tid + i * WG);
@@ -279,27 +284,40 @@ __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint3
     }
 }
 
-// n_req = *n_req_ptr when given (a count produced on the device), else n_req_val.
-template <bool NT>
+// Tiles of a list of (src, dst) chunks; n_req = *n_req_ptr when given (a count produced on the device), else
+// n_req_val.  The grid may be any size: with one workgroup per tile the loop body runs once.  `feedback`, when given,
+// is a word of pinned host memory that receives n_req: the host sizes the next launch's grid from it, because
+// workgroups that find no tile are not free (about 0.2 ns each on MI355X).
+template <int UNROLL, bool NT>
 __global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, const uint32_t *n_req_ptr,
                                                  uint32_t n_req_val, uint32_t items_per_req, uint64_t chunk_bytes,
-                                                 uint32_t tiles_per_chunk)
+                                                 uint32_t tiles_per_chunk, uint32_t *feedback)
 {
+    constexpr uint32_t TILE = WG * 16 * UNROLL;
+    // The first tile's list entry is fetched before the count is known, so that the two scalar loads overlap: a
+    // workgroup lives for one load and one store, and every dependent load in front of them costs bandwidth.  The
+    // host never launches more workgroups than the list has room for, so the early read stays inside the list.
+    uint64_t t = blockIdx.x;
+    uint64_t it = t / tiles_per_chunk;
+    Item x = items[it];
     uint64_t n_req = n_req_ptr ? *n_req_ptr : n_req_val;
+    if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = (uint32_t)n_req;
     uint64_t n_tiles = n_req * items_per_req * tiles_per_chunk;
-    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint64_t it = t / tiles_per_chunk;
+    while (t < n_tiles) {
         uint64_t off = (t - it * tiles_per_chunk) * TILE;
-        Item x = items[it];
-        uint64_t len = chunk_bytes - off;
-        copy_tile<NT>(x.src + off, x.dst + off, len < TILE ? len : TILE, threadIdx.x);
+        copy_tile<UNROLL, NT>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
+        t += gridDim.x;
+        if (t >= n_tiles) break;
+        it = t / tiles_per_chunk;
+        x = items[it];
     }
 }
 
-// One source, one or two destinations (dst1 == 0: none): the write-back path reads each source byte once.
+// One source, one or two destinations (dst == 0: none): the write-back path reads each source byte once.
 __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ items, uint32_t n_items,
                                                   uint64_t chunk_bytes, uint32_t tiles_per_chunk)
 {
+    constexpr uint32_t TILE = TILE_HOST;
     uint64_t n_tiles = (uint64_t)n_items * tiles_per_chunk;
     for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         uint64_t it = t / tiles_per_chunk;
@@ -322,6 +340,7 @@ __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ item
 __global__ __launch_bounds__(WG) void fill_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
                                                  uint32_t tiles_per_chunk, uint32_t pattern)
 {
+    constexpr uint32_t TILE = TILE_HOST;
     uint64_t n_tiles = (uint64_t)n_items * tiles_per_chunk;
     u32x4 v = { pattern, pattern, pattern, pattern };
     for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
@@ -342,15 +361,13 @@ __global__ __launch_bounds__(WG) void dir_write(uint64_t *dir, const uint32_t *_
     if (i < n) dir[ids[i]] = entries[i];
 }
 
-// Plain contiguous copy with the same inner loop (reference ceiling / counter calibration).
-template <bool NT>
+// Plain contiguous copy with the HBM-tier inner loop (reference ceiling / counter calibration).
 __global__ __launch_bounds__(WG) void plain_copy(uint64_t dst, uint64_t src, uint64_t bytes)
 {
-    uint64_t n_tiles = (bytes + TILE - 1) / TILE;
+    uint64_t n_tiles = (bytes + TILE_HBM - 1) / TILE_HBM;
     for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint64_t off = t * TILE;
-        uint64_t len = bytes - off;
-        copy_tile<NT>(src + off, dst + off, len < TILE ? len : TILE, threadIdx.x);
+        uint64_t off = t * TILE_HBM;
+        copy_tile<1, true>(src + off, dst + off, bytes - off, threadIdx.x);
     }
 }
 
