@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--iso-steps", type=int, default=20, help="fetches per isolation point (100%% cache / 100%% host)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolation", action="store_true")
+    ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     return ap.parse_args()
 
@@ -130,7 +131,8 @@ def main():
     log(f"[bench] workload: {wl.n_seq} sequences, lengths {wl.seq_lens.tolist()}, {n_blocks0} blocks, "
         f"{args.layers} layers materialised, host pool {wl.n_objects * 2 * chunk * args.layers / 2**30:.1f} GiB")
     all_cache_slack = int(wl.n_objects - wl.resident.sum())
-    eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack), profile=True)
+    eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack), profile=True,
+                    host_wgs=args.host_wgs)
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
@@ -270,7 +272,7 @@ def main():
             log(f"[bench] isolation {name}: {iso[name]}")
 
     traffic = None
-    tf = os.path.join(ROOT, "profiles", "copy_items_hbm_kv_decode_pmc.txt")
+    tf = os.path.join(ROOT, "profiles", "gather_hbm_kv_decode_pmc.txt")
     if os.path.exists(tf):
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tf).read())
         if m:
@@ -289,11 +291,11 @@ def main():
         "objects_per_s": round(d["n_requests"] / sec),
         "bit_exact": bit_exact,
         "served": {k: v // args.steps for k, v in d.items()},
-        "roofline": {"bound": "hbm", "kernel": "copy_items<1,true> (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "gather<1,true> (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
                      "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1)},
-        "host_tier": {"bound": "pcie", "kernel": "copy_items<8,false> (host-tier gather, zero-copy over PCIe)",
+        "host_tier": {"bound": "pcie", "kernel": "gather<8,false> (host-tier gather, zero-copy over PCIe)",
                       "achieved": round(host_gbs, 2), "peak": round(pcie_peak_gbs, 2), "unit": "GB/s",
                       "frac": round(host_gbs / pcie_peak_gbs, 4), "launches": int(pr.host_launches),
                       "avg_launch_ms": round(host_ms, 5), "bytes_per_launch": round(host_bytes),

@@ -83,7 +83,9 @@ struct StreamState {
     bool last_valid = false;
     // fetch scratch
     uint32_t req_cap = 0;
-    Item *hbm_items = nullptr, *host_items = nullptr;
+    Rec *hbm_recs = nullptr, *host_recs = nullptr, *tmp_recs = nullptr;
+    uint8_t *kind = nullptr;
+    uint32_t *blk_counts = nullptr;
     uint32_t *miss_idx = nullptr;
     uint32_t *cnt = nullptr;                // [2][C_N], ping-pong
     int cur = 0;                            // buffer the NEXT fetch uses
@@ -149,13 +151,17 @@ int ensure_req_cap(StreamState *ss, uint32_t n_req)
     // growing: earlier work on this stream may still read the old lists
     HIP_TRY(hipStreamSynchronize(ss->s));
     HIP_TRY(hipStreamSynchronize(ss->side));
-    if (ss->hbm_items) HIP_TRY(hipFree(ss->hbm_items));
-    if (ss->host_items) HIP_TRY(hipFree(ss->host_items));
-    if (ss->miss_idx) HIP_TRY(hipFree(ss->miss_idx));
-    ss->hbm_items = ss->host_items = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
+    for (void *p : { (void *)ss->hbm_recs, (void *)ss->host_recs, (void *)ss->tmp_recs, (void *)ss->kind,
+                     (void *)ss->blk_counts, (void *)ss->miss_idx })
+        if (p) HIP_TRY(hipFree(p));
+    ss->hbm_recs = ss->host_recs = ss->tmp_recs = nullptr;
+    ss->kind = nullptr; ss->blk_counts = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
     uint32_t cap = std::max<uint32_t>(1024, n_req + n_req / 4);
-    HIP_TRY(hipMalloc(&ss->hbm_items, (size_t)cap * 2 * sizeof(Item)));
-    HIP_TRY(hipMalloc(&ss->host_items, (size_t)cap * 2 * sizeof(Item)));
+    HIP_TRY(hipMalloc(&ss->hbm_recs, (size_t)cap * sizeof(Rec)));
+    HIP_TRY(hipMalloc(&ss->host_recs, (size_t)cap * sizeof(Rec)));
+    HIP_TRY(hipMalloc(&ss->tmp_recs, (size_t)cap * sizeof(Rec)));
+    HIP_TRY(hipMalloc(&ss->kind, (size_t)cap));
+    HIP_TRY(hipMalloc(&ss->blk_counts, (size_t)((cap + WG - 1) / WG) * 4 * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ss->miss_idx, (size_t)cap * sizeof(uint32_t)));
     ss->req_cap = cap;
     return HARVEST_OK;
@@ -270,42 +276,54 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 }
 
 // Launches the HBM-tier gather on the caller's stream and the host-tier gather on the side stream, joined back.
-// max_req bounds the number of requests either list can hold; the HBM-tier grid has one workgroup per tile of that
-// bound (workgroups beyond the device-side count exit at once).
-int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t items_per_req, uint32_t *cnt,
-                   uint64_t max_req)
+// max_req bounds the number of requests either list can hold; dst_base: where plane p of the working layout starts.
+int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
+                   uint64_t dst_base0, uint64_t dst_base1)
 {
+    GatherArgs ga{};
+    for (uint32_t p = 0; p < 2; ++p) {
+        ga.src_base[T_HOST][p] = c.host_dev[p];
+        ga.src_base[T_CACHE][p] = (uint64_t)c.cfg.d_cache_pool[p];
+        ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p];
+    }
+    ga.dst_base[0] = dst_base0;
+    ga.dst_base[1] = dst_base1;
+    ga.chunk_bytes = c.cfg.chunk_bytes;
     uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
     uint32_t tpc_host = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+    uint32_t planes = c.cfg.n_planes;
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
     if (ctx->profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
     bool host_tier = c.cfg.n_host_slots != 0;
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
+        ga.tiles_per_chunk = tpc_host;
+        ga.n_planes = planes;
         if (pc) HIP_TRY(hipEventRecord(pc, ss->side));
-        hipLaunchKernelGGL((copy_items<UNROLL_HOST, false>), dim3(ctx->host_grid), dim3(WG), 0, ss->side,
-                           ss->host_items, cnt + C_HOST_REQ, 0u, items_per_req, c.cfg.chunk_bytes, tpc_host,
-                           (uint32_t *)nullptr);
+        hipLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
+                           (const uint32_t *)(cnt + C_HOST_REQ), ga);
         HIP_TRY(hipGetLastError());
         if (pd) HIP_TRY(hipEventRecord(pd, ss->side));
     }
     // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the
     // previous gather of this class on this stream reported (plus slack), never below a floor that still fills the
     // chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
-    uint64_t max_tiles = max_req * items_per_req * tpc_hbm;
+    uint64_t max_tiles = max_req * tpc_hbm;
     uint64_t want = max_tiles;
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
-        uint64_t guess = (seen + seen / 16 + 8) * items_per_req * tpc_hbm;
+        uint64_t guess = (seen + seen / 16 + 8) * tpc_hbm;
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
     }
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
+    ga.tiles_per_chunk = tpc_hbm;
+    ga.n_planes = planes;
     if (pa) HIP_TRY(hipEventRecord(pa, ss->s));
-    hipLaunchKernelGGL((copy_items<1, true>), dim3(grid), dim3(WG), 0, ss->s, ss->hbm_items, cnt + C_HBM_REQ, 0u,
-                       items_per_req, c.cfg.chunk_bytes, tpc_hbm, ss->d_feedback + cls);
-    ss->feedback_valid[cls] = true;
+    hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
+                       (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
     HIP_TRY(hipGetLastError());
+    ss->feedback_valid[cls] = true;
     if (pb) HIP_TRY(hipEventRecord(pb, ss->s));
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
@@ -449,7 +467,8 @@ int harvest_destroy(harvest_ctx *ctx)
             StreamState *ss = kv.second.get();
             (void)hipStreamDestroy(ss->side);
             for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
-            (void)hipFree(ss->hbm_items); (void)hipFree(ss->host_items); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
+            (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
+            (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
             (void)hipFree(ss->ctl_buf);
             (void)hipHostFree(ss->h_feedback);
         }
@@ -560,8 +579,8 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     if ((rc = release_after(st, ss->s))) return rc;
     uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
     uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
-    hipLaunchKernelGGL((copy_items<UNROLL_HOST, false>), dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf,
-                       (const uint32_t *)nullptr, (uint32_t)items.size(), 1u, c.cfg.chunk_bytes, tpc, (uint32_t *)nullptr);
+    hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
+                       c.cfg.chunk_bytes, tpc);
     HIP_TRY(hipGetLastError());
     // the new entries become visible only after the copy; later work on `stream` waits for the publication
     HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
@@ -651,15 +670,20 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
         return HARVEST_EINVAL;
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, (uint32_t)total))) return rc;
+    if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
-    hipLaunchKernelGGL(resolve_kv, dim3((uint32_t)((total + WG - 1) / WG)), dim3(WG), 0, ss->s, class_dev(c), layer,
-                       d_block_table, d_n_blocks, n_seq, max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
-                       d_seq_dst_block, dst_capacity_blocks, ss->hbm_items, ss->host_items, ss->miss_idx, cnt, cnt_next,
-                       ctx->d_totals + HARVEST_KV * C_N);
+    uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
+    hipLaunchKernelGGL(classify_kv, dim3(n_wg), dim3(WG), 0, ss->s, class_dev(c), layer, d_block_table, d_n_blocks, n_seq,
+                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts, cnt,
+                       cnt_next, ctx->d_totals + HARVEST_KV * C_N);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)ss->tmp_recs,
+                       (const uint8_t *)ss->kind, (const uint32_t *)ss->blk_counts, ss->hbm_recs, ss->host_recs,
+                       ss->miss_idx, cnt);
     HIP_TRY(hipGetLastError());
     ss->last_cur = ss->cur;
     ss->cur ^= 1;
-    return launch_gathers(ctx, ss, c, HARVEST_KV, c.cfg.n_planes, cnt, total);
+    return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v);
 }
 
 int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,
@@ -678,15 +702,16 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, E))) return rc;
     uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
     hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
-                       (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_items, ss->host_items,
+                       (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_recs, ss->host_recs,
                        ss->miss_idx, cnt, cnt_next, ctx->d_totals + HARVEST_EXPERT * C_N);
     HIP_TRY(hipGetLastError());
     ss->last_cur = ss->cur;
     ss->cur ^= 1;
-    return launch_gathers(ctx, ss, c, HARVEST_EXPERT, 1, cnt, std::min<uint64_t>(E, n_staging_slots));
+    return launch_gathers(ctx, ss, c, HARVEST_EXPERT, cnt, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
 }
 
 int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,

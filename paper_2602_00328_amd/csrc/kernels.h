@@ -1,16 +1,23 @@
 // Device code of the tiered cache fetch for gfx950 (CDNA4, wave64).
 //
-// Everything here is byte movement plus a few integers of metadata: no floating point, no MFMA.  The kernels are
-//   resolve_kv / resolve_experts : directory lookup (paper Section 5.2 block table, Section 4.3 residency map),
-//                                  classification by tier, wave-level compaction into an HBM list and a host
-//                                  (miss) list;
-//   copy_items                   : the gather itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte
-//                                  non-temporal load and store per thread, as many workgroups as tiles (measured
-//                                  on MI355X: many short workgroups beat deep unrolling and persistent grids by
-//                                  ~15%).  Host tier: a few persistent workgroups with 8 loads in flight per
-//                                  thread, enough to keep the PCIe link full while leaving the CUs to the HBM tier;
-//   copy_items2                  : the scatter of the write-back path (one source, up to two destinations);
-//   fill_items, dir_write        : slot poisoning after revocation, directory publication.
+// Everything here is byte movement plus a few integers of metadata: no floating point, no MFMA.
+//
+//   classify_kv + compact_kv : directory lookup (paper Section 5.2: the extended KV block table), classification of
+//                              every request by tier, and an ORDER-PRESERVING compaction into an HBM list and a host
+//                              (miss) list: wavefront ballots rank the lanes, LDS carries the wave totals, and the
+//                              workgroup totals of the first kernel become the offsets of the second.  Keeping the
+//                              lists in request order makes the gather's writes one ascending stream, worth ~6% of
+//                              HBM bandwidth over lists ordered by racing atomics.
+//   resolve_experts          : the same for expert weights (Section 4.3: residency map) - one workgroup forms the
+//                              distinct set of routed experts and walks it in ascending order.
+//   gather                   : the copy itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte non-temporal
+//                              load and store per thread, as many workgroups as tiles, plane K before plane V
+//                              (measured on MI355X: short workgroups beat deep unrolling and persistent grids by
+//                              ~15%, non-temporal accesses are worth ~11%, one plane at a time ~2%).  Host tier: a
+//                              few persistent workgroups with 8 loads in flight per thread - enough to keep the PCIe
+//                              link full while leaving the CUs to the HBM tier.
+//   copy_items, copy_items2, fill_items, dir_write : host-built lists - placement, write-back (one source, up to two
+//                              destinations), slot poisoning after revocation, directory publication.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -20,6 +27,7 @@ namespace hv {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WG = 256;                         // 4 wavefronts
+constexpr int WAVES = WG / 64;
 constexpr uint32_t TILE_HBM = WG * 16;          // 4 KiB: one 16-byte access per thread
 constexpr int UNROLL_HOST = 8;
 constexpr uint32_t TILE_HOST = WG * 16 * UNROLL_HOST;   // 32 KiB: 8 accesses in flight per thread over PCIe
@@ -34,11 +42,18 @@ __host__ __device__ inline uint64_t make_entry(uint32_t tier, uint32_t slot, uin
 }
 enum { T_HOST = 0, T_CACHE = 1, T_LOCAL = 2, T_NONE = 3 };
 
+// One request of a fetch, the same for every plane of its class:
+//   src = byte offset of the chunk inside its tier's plane pool, tier in bits [1:0] (offsets are multiples of 16);
+//   dst = byte offset of the chunk inside the destination plane.
+struct Rec { uint64_t src, dst; };
+// Host-built lists carry absolute addresses.
 struct Item { uint64_t src, dst; };
 struct Item2 { uint64_t src, dst0, dst1, pad; };
 
 // per-fetch counters (uint32) and running totals (uint64) share these indices
 enum { C_REQ = 0, C_LOCAL, C_CACHE, C_HOST, C_LOST, C_INVALID, C_HBM_REQ, C_HOST_REQ, C_MISS, C_N = 16 };
+// request kinds handed from classify_kv to compact_kv
+enum { K_NONE = 0, K_HBM = 1, K_HOST = 2, K_LOST = 3 };
 
 struct ClassDev {
     const uint64_t *dir;
@@ -49,19 +64,27 @@ struct ClassDev {
     uint32_t pad;
 };
 
+struct GatherArgs {
+    uint64_t src_base[3][2];  // [tier][plane]
+    uint64_t dst_base[2];     // [plane]
+    uint64_t chunk_bytes;
+    uint32_t tiles_per_chunk;
+    uint32_t n_planes;
+};
+
 __device__ inline uint32_t lane_id() { return __lane_id(); }
 
 // Selects instead of indexing: a variable index into a kernel-argument struct would send it to scratch memory.
-__device__ inline uint64_t pool_of(const ClassDev &c, int tier, uint32_t plane)
-{
-    uint64_t h = plane ? c.pool[T_HOST][1] : c.pool[T_HOST][0];
-    uint64_t k = plane ? c.pool[T_CACHE][1] : c.pool[T_CACHE][0];
-    uint64_t l = plane ? c.pool[T_LOCAL][1] : c.pool[T_LOCAL][0];
-    return tier == T_HOST ? h : (tier == T_CACHE ? k : l);
-}
 __device__ inline uint32_t slots_of(const ClassDev &c, int tier)
 {
     return tier == T_HOST ? c.n_slots[T_HOST] : (tier == T_CACHE ? c.n_slots[T_CACHE] : c.n_slots[T_LOCAL]);
+}
+__device__ inline uint64_t src_base_of(const GatherArgs &a, uint32_t tier, uint32_t plane)
+{
+    uint64_t h = plane ? a.src_base[T_HOST][1] : a.src_base[T_HOST][0];
+    uint64_t k = plane ? a.src_base[T_CACHE][1] : a.src_base[T_CACHE][0];
+    uint64_t l = plane ? a.src_base[T_LOCAL][1] : a.src_base[T_LOCAL][0];
+    return tier == T_HOST ? h : (tier == T_CACHE ? k : l);
 }
 
 // Exclusive rank of this lane among the lanes of its wavefront for which pred holds, and the wave total.
@@ -72,86 +95,116 @@ __device__ inline uint32_t wave_rank(bool pred, uint32_t &total)
     return (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));
 }
 
-// One atomic per wavefront reserves `total` consecutive list positions; every lane learns the base.
-__device__ inline uint32_t wave_reserve(uint32_t *counter, uint32_t total)
+__device__ inline uint32_t wave_sum(uint32_t v)
 {
-    uint32_t base = 0;
-    if (lane_id() == 0 && total) base = atomicAdd(counter, total);
-    return __shfl(base, 0);
-}
-
-__device__ inline void wave_count(bool pred, uint32_t *cnt, unsigned long long *totals, int which)
-{
-    uint32_t n = (uint32_t)__popcll(__ballot(pred));
-    if (lane_id() == 0 && n) {
-        atomicAdd(&cnt[which], n);
-        atomicAdd(&totals[which], (unsigned long long)n);
-    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// KV: one thread per (sequence, block-table column).
+// KV, pass 1: one thread per (sequence, block-table column) looks its block up and says what kind of request
+// it is; every workgroup leaves its three list totals in blk_counts[4 * blockIdx + 0..2].
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void resolve_kv(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
-                                                 const int32_t *__restrict__ n_blocks, uint32_t n_seq,
-                                                 uint32_t max_blocks, uint64_t dst_k, uint64_t dst_v,
-                                                 const uint64_t *__restrict__ seq_dst_block, uint64_t dst_cap,
-                                                 Item *__restrict__ hbm_items, Item *__restrict__ host_items,
-                                                 uint32_t *__restrict__ miss_idx, uint32_t *cnt, uint32_t *cnt_next,
-                                                 unsigned long long *totals)
+__global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
+                                                  const int32_t *__restrict__ n_blocks, uint32_t n_seq,
+                                                  uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
+                                                  uint64_t dst_cap, Rec *__restrict__ tmp, uint8_t *__restrict__ kind,
+                                                  uint32_t *__restrict__ blk_counts, uint32_t *cnt, uint32_t *cnt_next,
+                                                  unsigned long long *totals)
 {
-    uint32_t r = blockIdx.x * WG + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x < C_N) cnt_next[threadIdx.x] = 0;   // the counters of the NEXT fetch
+    __shared__ uint32_t s_cnt[C_N];
+    uint32_t tid = threadIdx.x;
+    uint32_t r = blockIdx.x * WG + tid;
+    if (tid < C_N) s_cnt[tid] = 0;
+    if (blockIdx.x == 0 && tid < C_N) cnt_next[tid] = 0;        // the counters of the NEXT fetch on this stream
+    __syncthreads();
     uint32_t total = n_seq * max_blocks;
     int tier = -1;                       // -1 no request, 0..3 tier, 4 invalid
-    uint64_t src_chunk = 0, dst_chunk = 0;
+    Rec rec = { 0, 0 };
     if (r < total) {
         uint32_t s = r / max_blocks, j = r - s * max_blocks;
         int32_t nb = n_blocks[s];
         nb = nb < 0 ? 0 : (nb > (int32_t)max_blocks ? (int32_t)max_blocks : nb);
         if (j < (uint32_t)nb) {
             int32_t b = table[r];
-            dst_chunk = seq_dst_block[s] + j;
+            uint64_t dst_chunk = seq_dst_block[s] + j;
             if (b < 0 || (uint32_t)b >= c.n_objects || dst_chunk >= dst_cap) {
                 tier = 4;
             } else {
                 uint64_t e = c.dir[b];
                 tier = (int)entry_tier(e);
                 uint32_t slot = entry_slot(e);
+                rec.dst = dst_chunk * c.chunk_bytes;
                 if (tier != T_NONE) {
                     if (slot >= slots_of(c, tier)) tier = 4;        // never true for a directory the library wrote
-                    else src_chunk = (uint64_t)layer * slots_of(c, tier) + slot;
+                    else rec.src = (((uint64_t)layer * slots_of(c, tier) + slot) * c.chunk_bytes) | (uint64_t)tier;
                 }
             }
         }
     }
-    bool is_hbm = tier == T_LOCAL || tier == T_CACHE;
-    bool is_host = tier == T_HOST;
-    bool is_miss = tier == T_HOST || tier == T_NONE;
-    uint32_t n_hbm, n_host, n_miss;
-    uint32_t p_hbm = wave_rank(is_hbm, n_hbm);
-    uint32_t p_host = wave_rank(is_host, n_host);
-    uint32_t p_miss = wave_rank(is_miss, n_miss);
-    p_hbm += wave_reserve(&cnt[C_HBM_REQ], n_hbm);
-    p_host += wave_reserve(&cnt[C_HOST_REQ], n_host);
-    p_miss += wave_reserve(&cnt[C_MISS], n_miss);
-    if (is_hbm || is_host) {
-        Item *list = is_hbm ? hbm_items : host_items;
-        uint32_t pos = is_hbm ? p_hbm : p_host;
-        for (uint32_t p = 0; p < c.n_planes; ++p) {
-            Item it;
-            it.src = pool_of(c, tier, p) + src_chunk * c.chunk_bytes;
-            it.dst = (p ? dst_v : dst_k) + dst_chunk * c.chunk_bytes;
-            list[(uint64_t)pos * c.n_planes + p] = it;
-        }
+    uint32_t k = (tier == T_LOCAL || tier == T_CACHE) ? K_HBM
+                                                      : (tier == T_HOST ? K_HOST : (tier == T_NONE ? K_LOST : K_NONE));
+    if (r < total) {
+        kind[r] = (uint8_t)k;
+        if (k == K_HBM || k == K_HOST) tmp[r] = rec;
     }
-    if (is_miss) miss_idx[p_miss] = r;
-    wave_count(tier >= 0, cnt, totals, C_REQ);
-    wave_count(tier == T_LOCAL, cnt, totals, C_LOCAL);
-    wave_count(tier == T_CACHE, cnt, totals, C_CACHE);
-    wave_count(tier == T_HOST, cnt, totals, C_HOST);
-    wave_count(tier == T_NONE, cnt, totals, C_LOST);
-    wave_count(tier == 4, cnt, totals, C_INVALID);
+    // wave ballots -> LDS -> one atomic per counter per workgroup
+    const int which[6] = { C_REQ, C_LOCAL, C_CACHE, C_HOST, C_LOST, C_INVALID };
+    const bool pred[6] = { tier >= 0, tier == T_LOCAL, tier == T_CACHE, tier == T_HOST, tier == T_NONE, tier == 4 };
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        uint32_t n = (uint32_t)__popcll(__ballot(pred[i]));
+        if (lane_id() == 0 && n) atomicAdd(&s_cnt[which[i]], n);
+    }
+    __syncthreads();
+    if (tid <= C_INVALID && s_cnt[tid]) {
+        atomicAdd(&cnt[tid], s_cnt[tid]);
+        atomicAdd(&totals[tid], (unsigned long long)s_cnt[tid]);
+    }
+    if (tid == 0) {
+        blk_counts[blockIdx.x * 4 + 0] = s_cnt[C_LOCAL] + s_cnt[C_CACHE];
+        blk_counts[blockIdx.x * 4 + 1] = s_cnt[C_HOST];
+        blk_counts[blockIdx.x * 4 + 2] = s_cnt[C_HOST] + s_cnt[C_LOST];
+    }
+}
+
+// KV, pass 2: list position = (totals of the workgroups before mine) + (totals of the waves before mine in the
+// workgroup) + (rank in my wave), so the lists come out in request order.
+__global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__restrict__ tmp,
+                                                 const uint8_t *__restrict__ kind, const uint32_t *__restrict__ blk_counts,
+                                                 Rec *__restrict__ hbm_recs, Rec *__restrict__ host_recs,
+                                                 uint32_t *__restrict__ miss_idx, uint32_t *cnt)
+{
+    __shared__ uint32_t s_pre[3];
+    __shared__ uint32_t s_wave[WAVES][3];
+    uint32_t tid = threadIdx.x, wave = tid >> 6;
+    uint32_t r = blockIdx.x * WG + tid;
+    if (wave == 0) {
+        uint32_t a0 = 0, a1 = 0, a2 = 0;
+        for (uint32_t b = lane_id(); b < blockIdx.x; b += 64) {
+            a0 += blk_counts[b * 4 + 0]; a1 += blk_counts[b * 4 + 1]; a2 += blk_counts[b * 4 + 2];
+        }
+        a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2);
+        if (lane_id() == 0) { s_pre[0] = a0; s_pre[1] = a1; s_pre[2] = a2; }
+    }
+    uint32_t k = r < total ? kind[r] : (uint32_t)K_NONE;
+    uint32_t n_hbm, n_host, n_miss;
+    uint32_t p_hbm = wave_rank(k == K_HBM, n_hbm);
+    uint32_t p_host = wave_rank(k == K_HOST, n_host);
+    uint32_t p_miss = wave_rank(k == K_HOST || k == K_LOST, n_miss);
+    if (lane_id() == 0) { s_wave[wave][0] = n_hbm; s_wave[wave][1] = n_host; s_wave[wave][2] = n_miss; }
+    __syncthreads();
+    uint32_t b_hbm = s_pre[0], b_host = s_pre[1], b_miss = s_pre[2];
+    for (uint32_t w = 0; w < wave; ++w) { b_hbm += s_wave[w][0]; b_host += s_wave[w][1]; b_miss += s_wave[w][2]; }
+    if (k == K_HBM) hbm_recs[b_hbm + p_hbm] = tmp[r];
+    if (k == K_HOST) host_recs[b_host + p_host] = tmp[r];
+    if (k == K_HOST || k == K_LOST) miss_idx[b_miss + p_miss] = r;
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+        uint32_t t0 = s_pre[0], t1 = s_pre[1], t2 = s_pre[2];
+        for (uint32_t w = 0; w < WAVES; ++w) { t0 += s_wave[w][0]; t1 += s_wave[w][1]; t2 += s_wave[w][2]; }
+        cnt[C_HBM_REQ] = t0; cnt[C_HOST_REQ] = t1; cnt[C_MISS] = t2;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -163,8 +216,8 @@ constexpr uint32_t MAX_EXPERTS = 8192;
 __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer, uint32_t n_experts,
                                                       const int32_t *__restrict__ topk, uint32_t n_ids,
                                                       uint64_t staging, uint32_t n_staging,
-                                                      uint64_t *__restrict__ expert_ptr, Item *__restrict__ hbm_items,
-                                                      Item *__restrict__ host_items, uint32_t *__restrict__ miss_idx,
+                                                      uint64_t *__restrict__ expert_ptr, Rec *__restrict__ hbm_recs,
+                                                      Rec *__restrict__ host_recs, uint32_t *__restrict__ miss_idx,
                                                       uint32_t *cnt, uint32_t *cnt_next, unsigned long long *totals)
 {
     __shared__ uint32_t bitmap[MAX_EXPERTS / 32];
@@ -216,14 +269,14 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
                     atomicAdd(&s_cnt[C_INVALID], 1u);
                 } else {
                     ptr = staging + (uint64_t)rank * c.chunk_bytes;
-                    Item it;
-                    it.src = pool_of(c, tier, 0) + (uint64_t)slot * c.chunk_bytes;
-                    it.dst = ptr;
+                    Rec it;                 // few, large objects: their order in the lists does not matter
+                    it.src = ((uint64_t)slot * c.chunk_bytes) | (uint64_t)tier;
+                    it.dst = (uint64_t)rank * c.chunk_bytes;
                     if (tier == T_CACHE) {
-                        hbm_items[atomicAdd(&s_cnt[C_HBM_REQ], 1u)] = it;
+                        hbm_recs[atomicAdd(&s_cnt[C_HBM_REQ], 1u)] = it;
                         atomicAdd(&s_cnt[C_CACHE], 1u);
                     } else {
-                        host_items[atomicAdd(&s_cnt[C_HOST_REQ], 1u)] = it;
+                        host_recs[atomicAdd(&s_cnt[C_HOST_REQ], 1u)] = it;
                         miss_idx[atomicAdd(&s_cnt[C_MISS], 1u)] = e;
                         atomicAdd(&s_cnt[C_HOST], 1u);
                     }
@@ -251,7 +304,7 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The gather: persistent workgroups walk the tiles of a list of (src, dst) chunks.
+// The gather.
 // ---------------------------------------------------------------------------------------------------------
 template <bool NT>
 __device__ inline u32x4 ld16(const u32x4 *p)
@@ -284,32 +337,92 @@ __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint3
     }
 }
 
-// Tiles of a list of (src, dst) chunks; n_req = *n_req_ptr when given (a count produced on the device), else
-// n_req_val.  The grid may be any size: with one workgroup per tile the loop body runs once.  `feedback`, when given,
-// is a word of pinned host memory that receives n_req: the host sizes the next launch's grid from it, because
-// workgroups that find no tile are not free (about 0.2 ns each on MI355X).
+// Tiles of the chunks named by a request list whose length lives on the device.  blockIdx.y is the plane, so a
+// two-plane class is gathered plane after plane.  The grid's x size is free: with one workgroup per tile the loop body
+// runs once; a smaller grid loops.  `feedback`, when given, is a word of pinned host memory that receives the list
+// length: the host sizes the next launch from it, because workgroups that find no tile are not free (about 0.2 ns
+// each on MI355X).
 template <int UNROLL, bool NT>
-__global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, const uint32_t *n_req_ptr,
-                                                 uint32_t n_req_val, uint32_t items_per_req, uint64_t chunk_bytes,
-                                                 uint32_t tiles_per_chunk, uint32_t *feedback)
+__global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                             GatherArgs a, uint32_t *feedback)
 {
     constexpr uint32_t TILE = WG * 16 * UNROLL;
-    // The first tile's list entry is fetched before the count is known, so that the two scalar loads overlap: a
+    uint32_t bx = blockIdx.x, gx = gridDim.x;
+    // The first tile's list entry is fetched before the length is known, so that the two scalar loads overlap: a
     // workgroup lives for one load and one store, and every dependent load in front of them costs bandwidth.  The
-    // host never launches more workgroups than the list has room for, so the early read stays inside the list.
-    uint64_t t = blockIdx.x;
-    uint64_t it = t / tiles_per_chunk;
-    Item x = items[it];
-    uint64_t n_req = n_req_ptr ? *n_req_ptr : n_req_val;
-    if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = (uint32_t)n_req;
-    uint64_t n_tiles = n_req * items_per_req * tiles_per_chunk;
+    // host never launches more workgroups (in x) than the list has room for tiles, so the early read stays inside
+    // the list; it also guarantees capacity * tiles_per_chunk < 2^32, so tile numbers fit 32-bit division.
+    uint32_t tpc = a.tiles_per_chunk;
+    uint64_t t = bx;
+    uint32_t idx = (uint32_t)t / tpc;
+    Rec x = recs[idx];
+    uint32_t n_req = *n_req_ptr;
+    uint32_t plane = blockIdx.y;
+    if (feedback && bx == 0 && plane == 0 && threadIdx.x == 0) *feedback = n_req;
+    uint64_t n_tiles = (uint64_t)n_req * tpc;
+    uint64_t dst_base = plane ? a.dst_base[1] : a.dst_base[0];
     while (t < n_tiles) {
-        uint64_t off = (t - it * tiles_per_chunk) * TILE;
-        copy_tile<UNROLL, NT>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
-        t += gridDim.x;
+        uint64_t off = (uint64_t)((uint32_t)t - idx * tpc) * TILE;
+        uint64_t src = src_base_of(a, (uint32_t)(x.src & 3), plane) + (x.src & ~(uint64_t)3) + off;
+        copy_tile<UNROLL, NT>(src, dst_base + x.dst + off, a.chunk_bytes - off, threadIdx.x);
+        t += gx;
         if (t >= n_tiles) break;
-        it = t / tiles_per_chunk;
-        x = items[it];
+        idx = (uint32_t)t / tpc;
+        x = recs[idx];
+    }
+}
+
+// Host tier: the same request list format, read over PCIe from pinned host memory by a few persistent workgroups.
+// Both planes of a tile are loaded before either is stored, so a two-plane class keeps 16 x 16 bytes in flight per
+// thread: the link needs bytes in flight, not workgroups, and every workgroup spared leaves the HBM tier alone.
+__global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                                  GatherArgs a)
+{
+    constexpr int U = UNROLL_HOST;
+    uint32_t tpc = a.tiles_per_chunk;
+    uint64_t n_tiles = (uint64_t)(*n_req_ptr) * tpc;
+    uint32_t tid = threadIdx.x;
+    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint32_t idx = (uint32_t)t / tpc;
+        Rec x = recs[idx];
+        uint64_t off = (uint64_t)((uint32_t)t - idx * tpc) * TILE_HOST;
+        uint64_t len = a.chunk_bytes - off;
+        uint64_t so = (x.src & ~(uint64_t)3) + off;
+        uint32_t tier = (uint32_t)(x.src & 3);
+        if (a.n_planes == 2 && len >= TILE_HOST) {
+            const u32x4 *s0 = reinterpret_cast<const u32x4 *>(src_base_of(a, tier, 0) + so) + tid;
+            const u32x4 *s1 = reinterpret_cast<const u32x4 *>(src_base_of(a, tier, 1) + so) + tid;
+            u32x4 *d0 = reinterpret_cast<u32x4 *>(a.dst_base[0] + x.dst + off) + tid;
+            u32x4 *d1 = reinterpret_cast<u32x4 *>(a.dst_base[1] + x.dst + off) + tid;
+            u32x4 v0[U], v1[U];
+#pragma unroll
+            for (int i = 0; i < U; ++i) v0[i] = s0[i * WG];
+#pragma unroll
+            for (int i = 0; i < U; ++i) v1[i] = s1[i * WG];
+#pragma unroll
+            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v0[i], d0 + i * WG);
+#pragma unroll
+            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v1[i], d1 + i * WG);
+        } else {
+            for (uint32_t p = 0; p < a.n_planes; ++p)
+                copy_tile<U, false>(src_base_of(a, tier, p) + so, (p ? a.dst_base[1] : a.dst_base[0]) + x.dst + off, len,
+                                    tid);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Host-built lists (absolute addresses).
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
+                                                 uint32_t tiles_per_chunk)
+{
+    uint64_t n_tiles = (uint64_t)n_items * tiles_per_chunk;
+    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint64_t it = t / tiles_per_chunk;
+        uint64_t off = (t - it * tiles_per_chunk) * TILE_HOST;
+        Item x = items[it];
+        copy_tile<UNROLL_HOST, false>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
     }
 }
 
