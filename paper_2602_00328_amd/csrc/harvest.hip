@@ -9,6 +9,7 @@
 //                 edits reach the device in the order the host made them (paper Section 3.2: revocation is ordered).
 #include "../../include/harvest.h"
 #include "kernels.h"
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -300,11 +301,10 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
         ga.tiles_per_chunk = tpc_host;
         ga.n_planes = planes;
-        if (pc) HIP_TRY(hipEventRecord(pc, ss->side));
-        hipLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
-                           (const uint32_t *)(cnt + C_HOST_REQ), ga);
+        // with profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end
+        hipExtLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0,
+                              (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga);
         HIP_TRY(hipGetLastError());
-        if (pd) HIP_TRY(hipEventRecord(pd, ss->side));
     }
     // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the
     // previous gather of this class on this stream reported (plus slack), never below a floor that still fills the
@@ -319,12 +319,10 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     ga.tiles_per_chunk = tpc_hbm;
     ga.n_planes = planes;
-    if (pa) HIP_TRY(hipEventRecord(pa, ss->s));
-    hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
-                       (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
+    hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
+                          (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
     HIP_TRY(hipGetLastError());
     ss->feedback_valid[cls] = true;
-    if (pb) HIP_TRY(hipEventRecord(pb, ss->s));
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
     if (ctx->profile) {
