@@ -1,0 +1,115 @@
+"""GPU parity at the real shapes of the benchmark's configs (32 KiB KV chunks at 32K-128K-token contexts, 150 MiB and
+16.5 MiB experts), in the launch configuration bench.py times.  The only reduction is the number of model layers
+materialised in the pools (per-step shapes - blocks per layer, expert size - are what the kernels see and stay real);
+for KV the oracle materialises one layer and every fetch of that layer is compared in full."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads import scenarios as S
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def test_config2_long_context_decode_real_shapes():
+    L, check_layer, steps = 4, 1, 34
+    say(f"config 2 at real per-step shapes, {L} layers materialised, oracle on layer {check_layer}")
+    wl = W.kv_decode(seed=0, n_layers=L, n_steps=steps)
+    assert int(sum(len(t) for t in wl.tables)) > 12000 and wl.shape.chunk_bytes == 32768
+    eo, eh = P.make_engines(wl, kv_layers=[check_layer])
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        assert np.array_equal(ro.place_status, rh.place_status)
+        compared = 0
+        for t in range(steps):
+            layer = t % L
+            got = rh.fetch(layer)
+            if layer == check_layer:
+                say(f"  step {t}: comparing {got[3]['n_requests']} blocks")
+                P.assert_kv_equal(ro.fetch(layer), got, f"config 2 step {t}")
+                compared += 1
+            ro.append(t); rh.append(t)
+        assert compared >= 8 and got[3]["n_cache"] > 8000 and got[3]["n_host"] > 3000
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
+def test_config3_phi_shaped_experts_real_size():
+    say("config 3: 150 MiB experts, 2 layers materialised")
+    ex = W.expert_offload(seed=0, shape=W.ExpertShape(n_layers=2))
+    assert ex.shape.chunk_bytes == 150 * 2**20
+    eo, eh = P.make_engines(ex_wl=ex)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        assert np.array_equal(xo.place_status, xh.place_status)
+        for t in range(2):
+            for layer in range(2):
+                say(f"  step {t} layer {layer}")
+                P.assert_experts_equal(xo.fetch(t, layer), xh.fetch(t, layer), f"config 3 step {t} layer {layer}")
+    finally:
+        eh.close(); eo.close()
+
+
+def test_config4_qwen_shaped_experts_lru_real_size():
+    say("config 4: 16.5 MiB experts, LRU cache tier, 2 layers materialised")
+    ex = W.expert_lru(seed=0, shape=W.ExpertShape(n_layers=2, n_experts=60, d_model=2048, d_ff=1408))
+    assert ex.shape.chunk_bytes == 17301504 and ex.lru_capacity == 24
+    eo, eh = P.make_engines(ex_wl=ex, poison=True)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        hits = 0
+        for t in range(3):
+            for layer in range(2):
+                say(f"  step {t} layer {layer}")
+                a, b = xo.fetch(t, layer), xh.fetch(t, layer)
+                P.assert_experts_equal(a, b, f"config 4 step {t} layer {layer}")
+                hits += b[4]["n_cache"]
+                ua, ub = xo.lru_update(t, layer), xh.lru_update(t, layer)
+                assert ua[0] == ub[0] and ua[1] == ub[1] and ua[2] == ub[2] and np.array_equal(ua[3], ub[3])
+        assert hits >= 2 * 2 * 20
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
+def test_config5_revocation_stress_real_shapes_two_streams():
+    say("config 5: config 2 KV (2 layers) on one stream + config 3 experts (1 layer) on another, revocations in flight")
+    wl = W.kv_decode(seed=0, n_layers=2, n_steps=26)
+    ex = W.expert_offload(seed=0, shape=W.ExpertShape(n_layers=1))
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        for t in range(26):
+            layer = t % 2
+            revoke_now = t % 10 == 0 and t > 0
+            ha, hx = rh.fetch_begin(layer), xh.fetch_begin(t, 0)
+            if revoke_now:                                            # while both fetches are in flight
+                rk_o, rk_h = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                rx_o, rx_h = xo.revoke_quarter(t), xh.revoke_quarter(t)
+                assert np.array_equal(rk_o[0], rk_h[0]) and rk_o[1] == rk_h[1]
+                assert np.array_equal(rx_o[0], rx_h[0]) and rx_o[1] == rx_h[1]
+                say(f"  step {t}: revoked {len(rk_o[0])} KV blocks and {len(rx_o[0])} experts with fetches in flight")
+            b, y = eh.fetch_end(ha), eh.fetch_end(hx)
+            if t % 2 == 0 or revoke_now:                              # compare every other step in full (1.5 GiB each)
+                # the oracle fetches after the revocation: bytes must not depend on when the fetch resolved
+                a, x = ro.fetch(layer), xo.fetch(t, 0)
+                P.assert_kv_equal(a, b, f"config 5 kv step {t}", counts=not revoke_now)
+                P.assert_experts_equal(x, y, f"config 5 experts step {t}", counts=not revoke_now)
+            if t % 10 == 5:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
+            ro.append(t); rh.append(t)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
