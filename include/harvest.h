@@ -6,8 +6,8 @@
  * local HBM of the compute GPU, a cache tier in spare HBM that may be revoked
  * at any time, and an authoritative copy in pinned host DRAM (paper Section
  * 3.1).  A residency directory in device memory maps object -> (tier, slot,
- * generation) (Section 4.3 "expert residency map", Section 5.2 "unified KV
- * block table"), and fetches resolve every requested object through it inside
+ * generation) (the per-expert residency map of Section 4.3, the block table
+ * extended with residency of Section 5.2), and fetches resolve every requested object through it inside
  * HIP kernels and gather the bytes into the caller's working layout.
  *
  * Conventions for every entry point
@@ -73,7 +73,8 @@ enum harvest_flags {
 };
 
 enum harvest_evict_flags {
-    HARVEST_EVICT_DEMOTE = 1     /* local objects leave local HBM after the write-back: directory -> HOST, slot freed */
+    HARVEST_EVICT_DEMOTE = 1     /* local objects leave local HBM after the write-back: slot freed, directory -> HOST
+                                    (backed objects) or -> CACHE (lossy objects) */
 };
 
 /* Invoked on the thread calling harvest_revoke, after the entry has been invalidated, in-flight work on the slot
@@ -135,9 +136,9 @@ int harvest_destroy(harvest_ctx *ctx);
 /* ---- directory (Sections 3.1, 3.2, 4.3) ------------------------------------------------------------------- */
 
 /* Registers n new objects of class cls; they get consecutive numbers, written to out_ids (may be NULL).
- * tier = HARVEST_HOST: the object lives in its host slot (Section 4.3: at start "the remaining experts reside in
- * host DRAM").  tier = HARVEST_LOCAL: the object takes the lowest free local slot (Section 4.3: "a user-defined
- * subset ... is loaded into local HBM"); the caller then fills that slot (see harvest_lookup).
+ * tier = HARVEST_HOST: the object lives in its host slot (Section 4.3: at start every expert the user did not pick
+ * for local HBM sits in host DRAM).  tier = HARVEST_LOCAL: the object takes the lowest free local slot (Section 4.3:
+ * the experts the user picked are loaded into local HBM); the caller then fills that slot (see harvest_lookup).
  * host_slot[i] = slot of the authoritative host copy (backed mode, Section 3.1); host_slot == NULL registers lossy
  * objects, allowed for HARVEST_LOCAL only.  cb/user: revocation callback for these objects (may be NULL).
  * All-or-nothing: EINVAL (slot out of range / already owned / repeated), ENOSPC (max_objects or local pool
@@ -156,7 +157,7 @@ int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t
  * nothing, only for unknown ids (ENOENT). */
 int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *per_obj_status);
 
-/* Revocation (Section 3.2, "explicit and ordered"): for each id in the cache tier: publish (HOST, gen+1) - or
+/* Revocation (Section 3.2: an explicit call whose steps come in a fixed order): for each id in the cache tier: publish (HOST, gen+1) - or
  * (NONE) for a lossy object -, wait until every fetch / evict / place enqueued so far on any stream this context
  * has seen has completed (the drain), free the slot (poison it if asked), then invoke the callback.  Ids not in the
  * cache tier are skipped.  Synchronous; ENOENT for unknown ids (nothing changed). */
@@ -199,8 +200,10 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
  * layer < 0: all layers, each source plane is [n_layers][src_layer_stride][chunk_bytes].  Object i reads source
  * chunk src_block[i] (< src_layer_stride).  d_src1 is ignored for one-plane classes.  HARVEST_EVICT_DEMOTE (all
  * layers, or a one-layer class): local objects leave local HBM - slot freed, directory -> (HOST, gen+1) once the
- * copy is done; the source may be the local pool itself.  EINVAL: repeated id, src_block out of range, demoting a
- * lossy object; ENOENT; ELOST.  On error nothing is enqueued or changed. */
+ * copy is done; the source may be the local pool itself.  A lossy local object (no host slot; Section 5.2: KV state
+ * need not be duplicated in a lower tier) moves into the lowest free cache slot instead -> (CACHE, slot, gen+1);
+ * ENOSPC, with nothing changed, if the cache tier cannot take every lossy object of the call.  EINVAL: repeated id,
+ * src_block out of range; ENOENT; ELOST (the object was revoked).  On error nothing is enqueued or changed. */
 int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, uint32_t n, const void *d_src0,
                   const void *d_src1, const uint64_t *src_block, uint64_t src_layer_stride, int flags, void *stream);
 

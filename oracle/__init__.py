@@ -42,33 +42,43 @@ def build(force: bool = True) -> str:
     return _LIB_PATH
 
 
+def _bind(path):
+    L = ctypes.CDLL(path)
+    vp, u32, u64, i32, i64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_int64
+    L.orc_create.restype = vp
+    L.orc_create.argtypes = [u32, u32, u64, u32, u32, u32, u32, i32]
+    L.orc_destroy.argtypes = [vp]
+    L.orc_plane.restype = vp
+    L.orc_plane.argtypes = [vp, i32, u32]
+    L.orc_n_objects.restype = u32
+    L.orc_n_objects.argtypes = [vp]
+    L.orc_register.argtypes = [vp, u32, vp, i32, vp]
+    L.orc_lookup.argtypes = [vp, u32, vp, vp, vp, vp]
+    L.orc_set_object.argtypes = [vp, u32, vp, vp]
+    L.orc_adopt.argtypes = [vp, u32]
+    L.orc_write_local.argtypes = [vp, u32, u32, u32, u64, vp, u64]
+    L.orc_place.argtypes = [vp, vp, u32, vp]
+    L.orc_revoke.argtypes = [vp, vp, u32, _CB, vp]
+    L.orc_fetch_kv.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp, i32]
+    L.orc_fetch_kv_plain.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64]
+    L.orc_fetch_experts.argtypes = [vp, u32, u32, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp]
+    L.orc_evict.argtypes = [vp, i32, vp, u32, vp, vp, vp, u64, i32]
+    return L
+
+
 def _load():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             build()
-        L = ctypes.CDLL(_LIB_PATH)
-        vp, u32, u64, i32, i64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_int64
-        L.orc_create.restype = vp
-        L.orc_create.argtypes = [u32, u32, u64, u32, u32, u32, u32, i32]
-        L.orc_destroy.argtypes = [vp]
-        L.orc_plane.restype = vp
-        L.orc_plane.argtypes = [vp, i32, u32]
-        L.orc_n_objects.restype = u32
-        L.orc_n_objects.argtypes = [vp]
-        L.orc_register.argtypes = [vp, u32, vp, i32, vp]
-        L.orc_lookup.argtypes = [vp, u32, vp, vp, vp, vp]
-        L.orc_set_object.argtypes = [vp, u32, vp, vp]
-        L.orc_adopt.argtypes = [vp, u32]
-        L.orc_write_local.argtypes = [vp, u32, u32, u32, u64, vp, u64]
-        L.orc_place.argtypes = [vp, vp, u32, vp]
-        L.orc_revoke.argtypes = [vp, vp, u32, _CB, vp]
-        L.orc_fetch_kv.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp, i32]
-        L.orc_fetch_kv_plain.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64]
-        L.orc_fetch_experts.argtypes = [vp, u32, u32, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp]
-        L.orc_evict.argtypes = [vp, i32, vp, u32, vp, vp, vp, u64, i32]
-        _lib = L
+        _lib = _bind(_LIB_PATH)
     return _lib
+
+
+def use_library(path=None):
+    """Tests only: make new OracleClass objects use another build of the oracle (None = the regular one)."""
+    global _lib
+    _lib = _bind(path) if path else None
 
 
 def _p(a):

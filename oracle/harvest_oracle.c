@@ -10,8 +10,8 @@
  * host DRAM (backing store).  Each object is either backed (it owns a host
  * slot holding the authoritative copy) or lossy (no host copy; once revoked it
  * is gone until reconstructed).  A residency directory maps object -> (tier,
- * slot, generation) (Section 4.3 "expert residency map", Section 5.2 "unified
- * KV block table").
+ * slot, generation) (the per-expert residency map of Section 4.3, the
+ * block table extended with residency of Section 5.2).
  *
  * Storage of one class of objects: every tier is a set of planes (KV: K and
  * V; experts: one), each plane laid out [layer][slot][chunk_bytes].  An object
@@ -127,8 +127,9 @@ static int64_t lowest_free(const uint8_t *used, uint32_t n)
 }
 
 /*
- * Section 3.1 / 4.3: objects enter the system either in local HBM ("a
- * user-defined subset of experts is loaded into local HBM") or in host DRAM.
+ * Section 3.1 / 4.3: objects enter the system either in local HBM (at start
+ * the user picks the experts that are loaded there) or in host DRAM (all the
+ * others).
  * host_slot == NULL registers lossy objects (local tier only: a lossy object
  * with no copy anywhere would be meaningless).  All-or-nothing.
  */
@@ -211,7 +212,7 @@ int orc_set_object(orc_class *c, uint32_t id, const uint8_t *src0, const uint8_t
 /*
  * Harness write into an object that lives in local HBM (a decode step
  * appending a token's rows to the open tail block): the application owns local
- * HBM (Section 3.1, "compute GPU HBM (authoritative)"), so this is not a
+ * HBM (Section 3.1 names the compute GPU's HBM the authoritative tier), so this is not a
  * library call; `truth` follows because the local copy IS the value.
  */
 int orc_write_local(orc_class *c, uint32_t id, uint32_t plane, uint32_t layer, uint64_t offset,
@@ -227,8 +228,8 @@ int orc_write_local(orc_class *c, uint32_t id, uint32_t plane, uint32_t layer, u
 
 /*
  * Placement (Section 3.2: harvest_alloc + explicit copy + record in the
- * placement map; Section 4.3: the rebalancer "migrates selected expert weights
- * into peer HBM").  Equal-size slots make best-fit degenerate, so the lowest
+ * placement map; Section 4.3: the rebalancer moves chosen experts into peer
+ * HBM as room appears).  Equal-size slots make best-fit degenerate, so the lowest
  * free slot is taken.  A failed allocation leaves the object on the host
  * (Figure 4 caption).  status[i] per object; the call itself fails only on an
  * unknown id.
@@ -260,8 +261,8 @@ int orc_place(orc_class *c, const uint32_t *ids, uint32_t n, int *status)
 }
 
 /*
- * Revocation (Section 3.2 "Revocation and deallocation are explicit and
- * ordered"): invalidate the entry, (drain - nothing is in flight on a CPU),
+ * Revocation (Section 3.2: an explicit call whose steps come in a fixed
+ * order): invalidate the entry, (drain - nothing is in flight on a CPU),
  * free the slot, then invoke the callback.  Backed objects fall back to their
  * host copy (Sections 4.3, 5.2); lossy ones are gone (Section 3.1).  With
  * poison on, the freed slot is overwritten so that a stale read cannot pass
@@ -295,9 +296,9 @@ int orc_revoke(orc_class *c, const uint32_t *ids, uint32_t n, orc_revoke_cb cb, 
 }
 
 /*
- * KV fetch, tiered definition (Section 5.2: "decode workers consult an
- * extended KV block table to resolve the physical location of each required KV
- * block"; non-local blocks are reloaded; after revocation the entry falls back
+ * KV fetch, tiered definition (Section 5.2: the decode worker looks every
+ * block it needs up in the block table, which says where the block lives;
+ * non-local blocks are reloaded; after revocation the entry falls back
  * to host DRAM).  Request r = s * max_blocks + j asks for block table[r] of
  * sequence s and lands in dst block seq_dst_block[s] + j of dst_k / dst_v.
  * Invalid requests (unknown block, dst index beyond dst_capacity_blocks) are
@@ -374,9 +375,9 @@ int orc_fetch_kv_plain(orc_class *c, uint32_t layer, const int32_t *table, const
 }
 
 /*
- * Expert fetch (Section 4.3: experts are paged whole, "an entire expert's
- * parameters must be resident in GPU memory before its feedforward computation
- * can execute"; the residency map says local HBM / peer HBM / host DRAM).
+ * Expert fetch (Section 4.3: experts are paged whole - the FFN of an expert
+ * cannot start before all of its weights are in GPU memory; the residency map
+ * says local HBM / peer HBM / host DRAM).
  * Objects of this class are numbered layer * n_experts + e and have one plane
  * and one storage layer.  U = distinct valid ids in topk.  For e in U,
  * ascending: local -> used in place (kind 1, where = local slot, no bytes
@@ -427,9 +428,9 @@ int orc_fetch_experts(orc_class *c, uint32_t layer, uint32_t n_experts, const in
 }
 
 /*
- * Eviction / write-back (Section 5.2: workers "request block evictions,
- * allowing handlers to migrate blocks out of local HBM"; Section 5.1: "keep the
- * authoritative copy of spilled KV in host DRAM"; Section 3.1: the runtime
+ * Eviction / write-back (Section 5.2: under memory pressure a worker asks for
+ * blocks to be moved out of local HBM; Section 5.1: the copy that counts for
+ * spilled KV is the one in host DRAM; Section 3.1: the runtime
  * never writes back on its own, so this explicit call is the only way bytes
  * reach a lower tier).  For each id the source bytes become the object's
  * value: written to its host slot (when backed) and to whichever HBM slot the
@@ -438,7 +439,11 @@ int orc_fetch_experts(orc_class *c, uint32_t layer, uint32_t n_experts, const in
  * layer >= 0: only that layer; each src plane is [src_layer_stride][chunk].
  * layer  < 0: all layers; each src plane is [n_layers][src_layer_stride][chunk].
  * ORC_EVICT_DEMOTE (all layers only): a local object leaves local HBM - its
- * slot is released and the directory now says host.
+ * slot is released.  A backed object then lives on the host; a lossy one
+ * (Section 5.2: KV state need not be duplicated in a lower tier)
+ * moves into the lowest free cache slot instead and has no other copy - if the
+ * cache tier cannot take all lossy objects of the call, ORC_ENOSPC and nothing
+ * changes.
  * Duplicate ids make the write order undefined: rejected, nothing written.
  */
 int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const uint8_t *src_k, const uint8_t *src_v,
@@ -447,18 +452,27 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
     const uint8_t *src[2] = { src_k, src_v };
     if (layer >= (int)c->n_layers) return ORC_EINVAL;
     if ((flags & ORC_EVICT_DEMOTE) && layer >= 0 && c->n_layers != 1) return ORC_EINVAL;
+    uint32_t need_cache = 0;
     for (uint32_t i = 0; i < n; ++i) {
         if (ids[i] >= c->n_objects) return ORC_ENOENT;
         if (src_block[i] >= src_layer_stride) return ORC_EINVAL;
         if (c->tier[ids[i]] == T_NONE) return ORC_ELOST;
-        if ((flags & ORC_EVICT_DEMOTE) && c->tier[ids[i]] == T_LOCAL && c->host_slot[ids[i]] < 0) return ORC_EINVAL;
+        if ((flags & ORC_EVICT_DEMOTE) && c->tier[ids[i]] == T_LOCAL && c->host_slot[ids[i]] < 0) need_cache++;
         for (uint32_t j = 0; j < i; ++j)
             if (ids[j] == ids[i]) return ORC_EINVAL;
     }
+    uint32_t free_cache = 0;
+    for (uint32_t s = 0; s < c->n_cache_slots; ++s) free_cache += !c->cache_used[s];
+    if (need_cache > free_cache) return ORC_ENOSPC;
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c->n_layers : (uint32_t)layer + 1;
     for (uint32_t i = 0; i < n; ++i) {
         uint32_t id = ids[i];
         int demote = (flags & ORC_EVICT_DEMOTE) && c->tier[id] == T_LOCAL;
+        int64_t to_cache = -1;
+        if (demote && c->host_slot[id] < 0) {
+            to_cache = lowest_free(c->cache_used, c->n_cache_slots);
+            c->cache_used[to_cache] = 1;
+        }
         for (uint32_t p = 0; p < c->n_planes; ++p)
             for (uint32_t l = l0; l < l1; ++l) {
                 uint64_t li = layer < 0 ? l : 0;
@@ -468,6 +482,8 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
                     memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);
                 if (c->tier[id] == T_CACHE)
                     memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);
+                if (to_cache >= 0)
+                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)to_cache), s, c->chunk_bytes);
                 if (c->tier[id] == T_LOCAL && !demote) {
                     uint8_t *d = at(c->local[p], c, c->n_local_slots, l, (uint64_t)c->slot[id]);
                     if (d != s) memmove(d, s, c->chunk_bytes);
@@ -476,7 +492,9 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
             }
         if (demote) {
             c->local_used[c->slot[id]] = 0;
-            c->tier[id] = T_HOST; c->slot[id] = -1; c->gen[id] += 1;
+            if (to_cache >= 0) { c->tier[id] = T_CACHE; c->slot[id] = to_cache; }
+            else { c->tier[id] = T_HOST; c->slot[id] = -1; }
+            c->gen[id] += 1;
         }
     }
     return ORC_OK;

@@ -749,13 +749,15 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     if (demote_flag && layer >= 0 && c.cfg.n_layers != 1) return HARVEST_EINVAL;
     {
         std::unordered_set<uint32_t> seen;
+        size_t need_cache = 0;
         for (uint32_t i = 0; i < n; ++i) {
             if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
             if (src_block[i] >= src_layer_stride) return HARVEST_EINVAL;
             if (c.tier[ids[i]] == T_NONE) return HARVEST_ELOST;
-            if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) return HARVEST_EINVAL;
+            if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) need_cache++;
             if (!seen.insert(ids[i]).second) return HARVEST_EINVAL;
         }
+        if (need_cache > c.cache_free.size()) return HARVEST_ENOSPC;
     }
     if (n == 0) return HARVEST_OK;
     if (!ctx->no_device) {
@@ -770,6 +772,11 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     for (uint32_t i = 0; i < n; ++i) {
         uint32_t id = ids[i];
         bool demote = demote_flag && c.tier[id] == T_LOCAL;
+        int64_t to_cache = -1;                  // a lossy object leaves local HBM for the cache tier: it has no host copy
+        if (demote && c.host_slot[id] < 0) {
+            to_cache = *c.cache_free.begin();
+            c.cache_free.erase(c.cache_free.begin());
+        }
         for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
             for (uint32_t l = l0; l < l1; ++l) {
                 uint64_t li = layer < 0 ? l : 0;
@@ -777,6 +784,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
                 it.src = src[p] + (li * src_layer_stride + src_block[i]) * c.cfg.chunk_bytes;
                 if (c.host_slot[id] >= 0) it.dst0 = c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]);
                 if (c.tier[id] == T_CACHE) it.dst1 = c.addr(T_CACHE, p, l, (uint64_t)c.slot[id]);
+                if (to_cache >= 0) it.dst1 = c.addr(T_CACHE, p, l, (uint64_t)to_cache);
                 if (c.tier[id] == T_LOCAL && !demote) {
                     uint64_t d = c.addr(T_LOCAL, p, l, (uint64_t)c.slot[id]);
                     if (d != it.src) it.dst1 = d;       // a source that already is the slot needs no copy
@@ -786,7 +794,9 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         c.n_evicted++;
         if (demote) {
             c.local_free.insert((uint32_t)c.slot[id]);
-            c.tier[id] = T_HOST; c.slot[id] = -1; c.gen[id] += 1;
+            if (to_cache >= 0) { c.tier[id] = T_CACHE; c.slot[id] = to_cache; }
+            else { c.tier[id] = T_HOST; c.slot[id] = -1; }
+            c.gen[id] += 1;
             c.n_demoted++;
             demoted.push_back(id);
         }

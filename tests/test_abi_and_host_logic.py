@@ -112,6 +112,12 @@ def test_host_logic_matches_the_oracle_directory_under_random_operations(seed):
             k = int(g.integers(1, 4))
             hs = [int(free_host.pop()) for _ in range(min(k, len(free_host)))]
             tier = O.LOCAL if g.random() < 0.4 else O.HOST
+            if tier == O.LOCAL and g.random() < 0.3:                       # lossy objects: no host slot
+                free_host.extend(hs)
+                ro, rh = both(lambda: oc.register(1, None, tier), lambda: h.register(B.KV, 1, None, tier))
+                if ro is not None:
+                    assert np.array_equal(ro, rh)
+                continue
             if g.random() < 0.1:
                 hs[0] = int(g.integers(-2, sp.n_host_slots + 2))            # maybe invalid or taken
             ro, rh = both(lambda: oc.register(len(hs), hs, tier), lambda: h.register(B.KV, len(hs), hs, tier))
@@ -149,11 +155,19 @@ def test_host_logic_matches_the_oracle_directory_under_random_operations(seed):
 
 
 def test_lossy_objects_host_logic():
-    h = B.Harvest(kv=spec(), flags=B.FLAG_NO_DEVICE)
-    a = h.register(B.KV, 1, None, B.LOCAL)[0]
+    h = B.Harvest(kv=spec(n_cache=1), flags=B.FLAG_NO_DEVICE)
+    a, a2 = h.register(B.KV, 2, None, B.LOCAL)
     with pytest.raises(B.HarvestError):
         h.register(B.KV, 1, None, B.HOST)
+    with pytest.raises(B.HarvestError) as e:                       # one cache slot, two lossy objects
+        h.evict(B.KV, -1, [a, a2], None, None, [0, 1], 4, B.EVICT_DEMOTE)
+    assert e.value.code == B.ENOSPC and h.lookup(B.KV, a)[0] == B.LOCAL
+    h.evict(B.KV, -1, [a], None, None, [0], 4, B.EVICT_DEMOTE)
+    assert h.lookup(B.KV, a) == (B.CACHE, 0, 1, -1)
+    h.revoke(B.KV, [a])
+    assert h.lookup(B.KV, a)[:3] == (B.NONE, -1, 2) and h.revoked_log == [(B.KV, int(a))]
+    assert list(h.place(B.KV, [a])) == [B.ELOST]
     with pytest.raises(B.HarvestError) as e:
-        h.evict(B.KV, -1, [a], None, None, [0], 4, B.EVICT_DEMOTE)
-    assert e.value.code == B.EINVAL and h.lookup(B.KV, a)[0] == B.LOCAL
+        h.evict(B.KV, 0, [a], None, None, [0], 4)
+    assert e.value.code == B.ELOST
     h.close()

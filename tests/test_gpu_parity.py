@@ -252,6 +252,45 @@ def test_revocation_stress_two_streams(overlap_revoke):
 
 # ---- lossy objects ------------------------------------------------------------------------------------------------
 
+def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation():
+    from types import SimpleNamespace
+    say("lossy objects")
+    chunk = 4096 + 48
+    spec = SimpleNamespace(n_layers=2, n_planes=2, chunk_bytes=chunk, max_objects=8, n_host_slots=4, n_cache_slots=3,
+                           n_local_slots=3, n_experts=0)
+    eo, eh = P.make_engines(kv_spec=spec, poison=True)
+    try:
+        for e in (eo, eh):
+            lossy = e.register(S.KV, 3, None, S.LOCAL)
+            backed = e.register(S.KV, 2, [3, 1], S.HOST)
+            so = np.full(4, W.NO_OBJECT, np.uint32); so[3] = backed[0]; so[1] = backed[1]
+            e.fill_host(S.KV, so, 9, W.CLS_KV, W.FILL_TAG, 1.0)
+            e.adopt(S.KV, backed)
+            for obj in lossy:
+                for p in range(2):
+                    for l in range(2):
+                        e.write_local(S.KV, obj, p, l, 0, W.chunk(9, W.CLS_APPEND, p, l, int(obj), chunk, W.FILL_TAG))
+            assert list(e.place(S.KV, [backed[0]])) == [0]
+            e.evict_from_local(S.KV, lossy[:2], S.EVICT_DEMOTE)            # two lossy blocks take the last two cache slots
+        P.assert_dirs_equal(eo, eh, S.KV, 5)
+        assert eh.lookup(S.KV, 0)[0] == S.CACHE and eh.lookup(S.KV, 2)[0] == S.LOCAL
+        table = np.array([[0, 3, 1, 2, 4]], np.int32)
+        nb, sdb = np.array([5], np.int32), np.array([0], np.uint64)
+        for layer in range(2):
+            P.assert_kv_equal(eo.fetch_kv(layer, table, nb, sdb, 5), eh.fetch_kv(layer, table, nb, sdb, 5), f"lossy {layer}")
+        assert eo.revoke(S.KV, [0, 3]) == eh.revoke(S.KV, [0, 3]) == [0, 3]
+        P.assert_dirs_equal(eo, eh, S.KV, 5)
+        assert eh.lookup(S.KV, 0)[0] == S.NONE and eh.lookup(S.KV, 3)[0] == S.HOST
+        c = eo.c[S.KV]
+        a = c.fetch_kv(1, table, nb, sdb, 5, dst_k=np.full(5 * chunk, 0xEE, np.uint8), dst_v=np.full(5 * chunk, 0xEE, np.uint8))
+        b = eh.fetch_kv(1, table, nb, sdb, 5, dst_fill=0xEE)
+        P.assert_kv_equal((a[0], a[1], np.sort(a[2]), a[3]), b, "after revocation")
+        assert b[3]["n_lost"] == 1 and (b[0][:chunk] == 0xEE).all() and list(b[2]) == [0, 1, 4]
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="lossy")
+    finally:
+        eh.close(); eo.close()
+
+
 def test_plain_copy_and_profile_counters():
     import torch
     from paper_2602_00328_amd import binding as B

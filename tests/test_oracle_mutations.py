@@ -1,0 +1,114 @@
+"""Are the oracle's pins sharp?  Plant one plausible mistake at a time in a copy of the oracle's source (on the CPU, in a
+temporary build) and require that the pin suite notices every one of them.  The unmutated build must pass the same battery."""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle as O
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(O.__file__)), "harvest_oracle.c")
+
+# (what the mistake is, text to find, text to put)
+MUTATIONS = [
+    ("transposed pool indexing (slot-major instead of layer-major)",
+     "return plane + ((uint64_t)layer * n_slots + slot) * c->chunk_bytes;",
+     "return plane + ((uint64_t)slot * c->n_layers + layer) * c->chunk_bytes;"),
+    ("cache-tier objects resolved through their host slot number",
+     "case T_CACHE: return at(c->cache[plane], c, c->n_cache_slots, layer, (uint64_t)c->slot[id]);",
+     "case T_CACHE: return at(c->cache[plane], c, c->n_cache_slots, layer, (uint64_t)c->host_slot[id] % c->n_cache_slots);"),
+    ("host copy looked up by object number instead of host slot",
+     "case T_HOST:  return at(c->host[plane], c, c->n_host_slots, layer, (uint64_t)c->host_slot[id]);",
+     "case T_HOST:  return at(c->host[plane], c, c->n_host_slots, layer, (uint64_t)id);"),
+    ("K and V destinations swapped in the KV fetch",
+     "if (src) memcpy(dst[p] + (seq_dst_block[s] + j) * c->chunk_bytes, src, c->chunk_bytes);",
+     "if (src) memcpy(dst[c->n_planes - 1 - p] + (seq_dst_block[s] + j) * c->chunk_bytes, src, c->chunk_bytes);"),
+    ("sequence offset dropped from the destination index",
+     "if (src) memcpy(dst[p] + (seq_dst_block[s] + j) * c->chunk_bytes, src, c->chunk_bytes);",
+     "if (src) memcpy(dst[p] + (uint64_t)j * c->chunk_bytes, src, c->chunk_bytes);"),
+    ("placement copies only the first layer",
+     "for (uint32_t l = 0; l < c->n_layers; ++l)\n                        memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)s),",
+     "for (uint32_t l = 0; l < 1; ++l)\n                        memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)s),"),
+    ("placement takes the highest free slot",
+     "int64_t s = lowest_free(c->cache_used, c->n_cache_slots);\n            if (s < 0) st = ORC_ENOSPC;",
+     "int64_t s = -1; for (int64_t q = (int64_t)c->n_cache_slots - 1; q >= 0; --q) if (!c->cache_used[q]) { s = q; break; }\n            if (s < 0) st = ORC_ENOSPC;"),
+    ("a full cache tier reported as success",
+     "if (s < 0) st = ORC_ENOSPC;", "if (s < 0) st = ORC_OK;"),
+    ("revocation forgets the generation",
+     "c->slot[id] = -1; c->gen[id] += 1;\n    }\n    for (uint32_t i = 0; i < n; ++i) {               /* free (+ poison) */",
+     "c->slot[id] = -1;\n    }\n    for (uint32_t i = 0; i < n; ++i) {               /* free (+ poison) */"),
+    ("revocation never frees the slot",
+     "c->cache_used[old[i]] = 0;", "c->cache_used[old[i]] = 1;"),
+    ("revoked lossy objects fall back to a host copy they do not have",
+     "c->tier[id] = c->host_slot[id] >= 0 ? T_HOST : T_NONE;", "c->tier[id] = T_HOST;"),
+    ("write-back skips the cache-tier copy",
+     "if (c->tier[id] == T_CACHE)\n                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);",
+     "if (0)\n                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);"),
+    ("write-back skips the host copy",
+     "if (c->host_slot[id] >= 0)\n                    memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);",
+     "if (0)\n                    memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);"),
+    ("all-layer write-back reads every layer from the first source layer",
+     "uint64_t li = layer < 0 ? l : 0;", "uint64_t li = 0;"),
+    ("demotion keeps the local slot",
+     "c->local_used[c->slot[id]] = 0;", ""),
+    ("cache hits listed as misses",
+     "case T_CACHE: k.n_cache++; break;", "case T_CACHE: k.n_cache++; if (miss_idx) miss_idx[nm] = r; nm++; break;"),
+    ("local experts consume a staging slot",
+     "kind[e] = 1; where[e] = c->slot[id]; kc.n_local++;", "kind[e] = 1; where[e] = c->slot[id]; kc.n_local++; rank++;"),
+    ("expert object number ignores the layer",
+     "uint32_t id = layer * n_experts + e;", "uint32_t id = e;"),
+    ("lossy objects demoted to the host tier, where they have no copy",
+     "if (to_cache >= 0) { c->tier[id] = T_CACHE; c->slot[id] = to_cache; }\n            else { c->tier[id] = T_HOST; c->slot[id] = -1; }",
+     "{ c->tier[id] = T_HOST; c->slot[id] = -1; }"),
+    ("duplicate ids accepted by the write-back",
+     "if (ids[j] == ids[i]) return ORC_EINVAL;\n    }\n    uint32_t free_cache", "if (0) return ORC_EINVAL;\n    }\n    uint32_t free_cache"),
+]
+
+
+def battery():
+    """The pin suite, called directly (parametrised tests with their parameter sets)."""
+    for p in (0.0, 0.3, 0.6, 1.0):
+        for seed in (0, 1, 2):
+            pins.test_fetch_kv_every_destination_word_names_its_request(p, seed)
+    pins.test_fetch_is_identical_for_every_residency_assignment()
+    pins.test_fetch_equals_numpy_take_on_the_host_plane()
+    pins.test_torch_index_select_reproduces_the_gather()
+    pins.test_all_cached_identity_table_is_one_memcpy()
+    pins.test_brute_force_three_blocks_all_tables_residencies_and_revocations()
+    pins.test_evict_of_fetched_bytes_is_identity_and_evict_of_new_bytes_is_returned()
+    pins.test_evict_all_layers_layout_and_duplicate_rejection()
+    for poison in (False, True):
+        pins.test_revocation_falls_back_to_host_and_grows_the_miss_set_exactly(poison)
+    pins.test_miss_list_is_exactly_the_host_and_lost_requests_in_request_order()
+    pins.test_place_takes_lowest_free_slot_copies_the_host_bytes_and_reports_enospc()
+    pins.test_fetch_never_changes_the_directory_or_any_tier()
+    pins.test_local_objects_append_evict_demote_then_place()
+    pins.test_invalid_requests_are_skipped_and_counted()
+    pins.test_expert_fetch_union_ranks_and_bytes()
+    pins.test_expert_fetch_staging_overflow_invalid_ids_and_revocation()
+    pins.test_lossy_object_is_lost_after_revocation_and_leaves_dst_untouched()
+    for seed in range(3):
+        pins.test_random_operation_sequences_keep_tiered_and_plain_fetch_equal(seed)
+
+
+def test_the_unmutated_oracle_passes_the_battery():
+    O.use_library(None)
+    battery()
+
+
+@pytest.mark.parametrize("what,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_every_planted_mistake_is_caught(what, old, new, tmp_path):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site not found exactly once: {what}"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["gcc", "-O1", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-w", "-o", str(lib), str(src)])
+    O.use_library(str(lib))
+    try:
+        with pytest.raises((AssertionError, O.OracleError, pytest.fail.Exception)):
+            battery()
+    finally:
+        O.use_library(None)

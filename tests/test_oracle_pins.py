@@ -1,8 +1,8 @@
 """Pins for the CPU oracle: every check here compares the oracle with something other than itself -
 self-describing payloads, closed forms, numpy library routines, brute-force enumeration with an
-independent few-line model, and the invariants the paper fixes (Section 3.1: correctness never
-depends on the cache tier; Section 3.2: revocation falls back to the host copy; Section 5.2: block
-table resolution)."""
+independent few-line model, and the invariants the paper fixes (Section 3.1: what the cache tier
+holds must not change any result; Section 3.2: a revoked object is served from its host copy;
+Section 5.2: blocks are found through the block table)."""
 import itertools
 
 import numpy as np
@@ -441,16 +441,45 @@ def test_expert_fetch_staging_overflow_invalid_ids_and_revocation():
 
 
 def test_lossy_object_is_lost_after_revocation_and_leaves_dst_untouched():
-    oc = OracleClass(1, 1, 32, 4, 4, 2, 2, poison=True)
-    a = oc.register(1, None, O.LOCAL)[0]
+    """A lossy object has no host copy: leaving local HBM it can only go to the cache tier, and a revocation there
+    loses it (Section 3.1: the application tolerates the loss and reconstructs)."""
+    chunk = 32
+    oc = OracleClass(2, 2, chunk, 6, 4, 2, 3, poison=True)
+    a, a2, a3 = oc.register(3, None, O.LOCAL)
     with pytest.raises(OracleError):
-        oc.register(1, None, O.HOST)
+        oc.register(1, None, O.HOST)                           # a lossy object needs a copy somewhere
     b = oc.register(1, [0], O.HOST)[0]
-    oc.set_object(a, np.full(32, 7, np.uint8)); oc.set_object(b, np.full(32, 9, np.uint8))
-    assert list(oc.place([a, b])) == [O.OK, O.OK] and oc.lookup(a)[0] == O.LOCAL      # local stays local
-    with pytest.raises(OracleError) as e:                                             # cannot demote with no host copy
-        oc.evict(-1, [a], oc.plane(O.LOCAL, 0), None, [0], 2, O.EVICT_DEMOTE)
-    assert e.value.code == O.EINVAL
+    rows = {}
+    for obj in (a, a2, a3):
+        for p in range(2):
+            for l in range(2):
+                rows[(obj, p, l)] = W.rng(15, int(obj), p, l).integers(0, 256, size=chunk, dtype=np.uint8)
+                oc.write_local(obj, p, l, 0, rows[(obj, p, l)])
+    oc.set_object(b, np.full(2 * chunk, 9, np.uint8), np.full(2 * chunk, 8, np.uint8))
+    assert list(oc.place([a, b])) == [O.OK, O.OK] and oc.lookup(a)[0] == O.LOCAL      # local stays local; b takes slot 0
+    with pytest.raises(OracleError) as e:                       # one cache slot left, two lossy objects to take in
+        oc.evict(-1, [a, a2], oc.plane(O.LOCAL, 0), oc.plane(O.LOCAL, 1), [0, 1], 3, O.EVICT_DEMOTE)
+    assert e.value.code == O.ENOSPC and oc.lookup(a)[:2] == (O.LOCAL, 0) and oc.lookup(a2)[:2] == (O.LOCAL, 1)
+    oc.evict(-1, [a], oc.plane(O.LOCAL, 0), oc.plane(O.LOCAL, 1), [0], 3, O.EVICT_DEMOTE)
+    assert oc.lookup(a) == (O.CACHE, 1, 1, -1)
+    table = np.array([[int(a), int(b), int(a2)]], np.int32)
+    nb, sdb = np.array([3], np.int32), np.array([0], np.uint64)
+    for l in range(2):
+        k, v, miss, counts = oc.fetch_kv(l, table, nb, sdb, 3)
+        assert np.array_equal(k[:chunk], rows[(a, 0, l)]) and np.array_equal(v[:chunk], rows[(a, 1, l)])
+        assert np.array_equal(k[2 * chunk:], rows[(a2, 0, l)])
+        assert counts["n_cache"] == 2 and counts["n_local"] == 1 and miss.size == 0
+    oc.revoke([a, b])
+    assert oc.revoked_log == [int(a), int(b)]
+    assert oc.lookup(a)[:3] == (O.NONE, -1, 2) and oc.lookup(b)[:3] == (O.HOST, -1, 2)
+    k = np.full(3 * chunk, 0xEE, np.uint8); v = np.full(3 * chunk, 0xEE, np.uint8)
+    k, v, miss, counts = oc.fetch_kv(0, table, nb, sdb, 3, dst_k=k, dst_v=v)
+    assert (k[:chunk] == 0xEE).all() and (v[:chunk] == 0xEE).all()                   # lost: destination untouched
+    assert (k[chunk:2 * chunk] == 9).all() and counts["n_lost"] == 1 and counts["n_host"] == 1 and list(miss) == [0, 1]
+    assert list(oc.place([a])) == [O.ELOST]
+    with pytest.raises(OracleError) as e:
+        oc.evict(0, [a], k, v, [0], 3)
+    assert e.value.code == O.ELOST
 
 
 # ---- random operation sequences: the invariants hold after every step ------------------------------------
