@@ -113,3 +113,31 @@ def test_config5_revocation_stress_real_shapes_two_streams():
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
     finally:
         eh.close(); eo.close()
+
+
+def test_revocation_drains_fetches_that_are_still_queued():
+    """Three fetches of ~4.5 ms each are queued back to back, then a quarter of the cache tier is revoked at once, with
+    poisoning on, and other blocks are placed into the freed slots.  The last gather starts milliseconds after the
+    revocation was requested: only the drain (Section 3.2: work in flight on the region finishes before it is freed)
+    keeps it from reading poisoned or re-used slots."""
+    say("drain ordering")
+    wl = W.kv_decode(seed=5, n_layers=3, n_steps=1)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=0)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        want = [ro.fetch(layer) for layer in range(3)]
+        handles = [rh.fetch_begin(layer) for layer in range(3)]           # ~13 ms of queued work
+        ids_o, called_o = ro.revoke_quarter(0)
+        ids_h, called_h = rh.revoke_quarter(0)                            # returns only after the drain
+        assert np.array_equal(ids_o, ids_h) and called_o == called_h and len(ids_h) > 1500
+        host_only = [b for b in range(wl.n_closed) if not wl.resident[b]][:len(ids_h)]
+        st_o, st_h = eo.place(S.KV, host_only), eh.place(S.KV, host_only)  # re-use the freed slots for other blocks
+        assert np.array_equal(st_o, st_h) and (st_h == 0).all()
+        for layer in range(3):
+            P.assert_kv_equal(want[layer], eh.fetch_end(handles[layer]), f"queued fetch {layer}", counts=False)
+        for layer in range(3):                                            # and the new residency serves the same bytes
+            a, b = ro.fetch(layer), rh.fetch(layer)
+            P.assert_kv_equal(a, b, f"after re-use, layer {layer}")
+            assert np.array_equal(a[0], want[layer][0]) and np.array_equal(a[1], want[layer][1])
+    finally:
+        eh.close(); eo.close()
