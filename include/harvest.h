@@ -19,7 +19,10 @@
  *     context (pools) or the enqueued work (buffers).  The library owns the
  *     device directory, its per-stream scratch lists and its events.
  *   - Data-moving calls are asynchronous: they enqueue on `stream` and return;
- *     results are valid in stream order.  Directory edits made by place /
+ *     results are valid in stream order.  The first call on a stream, and a
+ *     call with more requests than any before it on that stream, allocates
+ *     per-stream scratch (hipMalloc) and waits for that stream's earlier work;
+ *     steady-state calls allocate nothing.  Directory edits made by place /
  *     revoke / evict(DEMOTE) / register are visible to every fetch enqueued
  *     after the call returns (place: on the same stream; other streams may
  *     still see the older, equally correct, host entry for a while).

@@ -340,6 +340,38 @@ int check_class(harvest_ctx *ctx, int cls)
     return HARVEST_OK;
 }
 
+// Device-side set-up of a context; on failure the caller destroys the half-built context, which frees whatever exists.
+int init_device(harvest_ctx *ctx, const harvest_config *cfg)
+{
+    HIP_TRY(hipSetDevice(cfg->device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, cfg->device));
+    ctx->n_cu = prop.multiProcessorCount;
+    ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
+    ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 8;
+    ctx->ctl_grid = 8 * ctx->n_cu;
+    HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
+    HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
+    HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
+    for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
+        ClassState &c = ctx->cls[k];
+        if (!c.used) continue;
+        HIP_TRY(hipMalloc(&c.d_dir, (size_t)c.cfg.max_objects * sizeof(uint64_t)));
+        HIP_TRY(hipMemset(c.d_dir, 0xFF, (size_t)c.cfg.max_objects * sizeof(uint64_t)));   // tier NONE everywhere
+        for (uint32_t p = 0; p < c.cfg.n_planes; ++p) {
+            if (!c.cfg.n_host_slots) continue;
+            void *d = nullptr;
+            if (hipHostGetDevicePointer(&d, c.cfg.host_pool[p], 0) != hipSuccess) {
+                fprintf(stderr, "libharvest: host pool plane %u of class %d is not pinned, mapped host memory\n", p, k);
+                return HARVEST_EINVAL;
+            }
+            c.host_dev[p] = (uint64_t)d;
+        }
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    return HARVEST_OK;
+}
+
 }  // namespace
 
 // =============================================================================================================
@@ -418,32 +450,11 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
     }
     if (!any) return HARVEST_EINVAL;
     if (!ctx->no_device) {
-        HIP_TRY(hipSetDevice(cfg->device));
-        hipDeviceProp_t prop;
-        HIP_TRY(hipGetDeviceProperties(&prop, cfg->device));
-        ctx->n_cu = prop.multiProcessorCount;
-        ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
-        ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 8;
-        ctx->ctl_grid = 8 * ctx->n_cu;
-        HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
-        HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
-        HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
-        for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
-            ClassState &c = ctx->cls[k];
-            if (!c.used) continue;
-            HIP_TRY(hipMalloc(&c.d_dir, (size_t)c.cfg.max_objects * sizeof(uint64_t)));
-            HIP_TRY(hipMemset(c.d_dir, 0xFF, (size_t)c.cfg.max_objects * sizeof(uint64_t)));   // tier NONE everywhere
-            for (uint32_t p = 0; p < c.cfg.n_planes; ++p) {
-                if (!c.cfg.n_host_slots) continue;
-                void *d = nullptr;
-                if (hipHostGetDevicePointer(&d, c.cfg.host_pool[p], 0) != hipSuccess) {
-                    fprintf(stderr, "libharvest: host pool plane %u of class %d is not pinned, mapped host memory\n", p, k);
-                    return HARVEST_EINVAL;
-                }
-                c.host_dev[p] = (uint64_t)d;
-            }
+        int rc = init_device(ctx.get(), cfg);
+        if (rc) {
+            harvest_destroy(ctx.release());
+            return rc;
         }
-        HIP_TRY(hipDeviceSynchronize());
     }
     *out = ctx.release();
     return HARVEST_OK;
