@@ -22,7 +22,12 @@
  *     results are valid in stream order.  The first call on a stream, and a
  *     call with more requests than any before it on that stream, allocates
  *     per-stream scratch (hipMalloc) and waits for that stream's earlier work;
- *     steady-state calls allocate nothing.  Directory edits made by place /
+ *     steady-state calls allocate nothing.  harvest_fetch_kv and
+ *     harvest_fetch_experts may be recorded into a HIP graph (stream capture)
+ *     once such a call has run on that stream outside capture: they use no
+ *     memset and read residency from device memory, so a replay follows every
+ *     place / revoke made since.  While a context has recorded work,
+ *     harvest_revoke drains by waiting for the whole device.  Directory edits made by place /
  *     revoke / evict(DEMOTE) / register are visible to every fetch enqueued
  *     after the call returns (place: on the same stream; other streams may
  *     still see the older, equally correct, host entry for a while).

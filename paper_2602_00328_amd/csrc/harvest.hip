@@ -88,9 +88,8 @@ struct StreamState {
     uint8_t *kind = nullptr;
     uint32_t *blk_counts = nullptr;
     uint32_t *miss_idx = nullptr;
-    uint32_t *cnt = nullptr;                // [2][C_N], ping-pong
-    int cur = 0;                            // buffer the NEXT fetch uses
-    int last_cur = -1;                      // buffer of the last fetch (-1: none yet)
+    uint32_t *cnt = nullptr;                // [C_N] counters of the last fetch; every fetch overwrites all of them
+    bool fetched = false;                   // a fetch has been enqueued on this stream
     // control scratch (host-built lists)
     void *ctl_buf = nullptr;
     size_t ctl_cap = 0;
@@ -114,6 +113,7 @@ struct harvest_ctx {
     std::deque<Staging> staging;          // deque: references stay valid when it grows
     std::vector<ProfPair> prof;
     std::vector<hipEvent_t> prof_pool;
+    bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
     std::mutex mu;
 };
 
@@ -126,18 +126,29 @@ int device_guard(harvest_ctx *ctx)
     return HARVEST_OK;
 }
 
+bool is_capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) return false;
+    return st != hipStreamCaptureStatusNone;
+}
+
 int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
 {
     hipStream_t s = (hipStream_t)stream;
     auto it = ctx->streams.find(s);
     if (it != ctx->streams.end()) { *out = it->second.get(); return HARVEST_OK; }
+    if (is_capturing(s)) {
+        fprintf(stderr, "libharvest: first use of a stream allocates its scratch - call once outside graph capture\n");
+        return HARVEST_EINVAL;
+    }
     auto ss = std::make_unique<StreamState>();
     ss->s = s;
     HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
     for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last, &ss->ctl_done, &ss->pre_ctl })
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
-    HIP_TRY(hipMalloc(&ss->cnt, 2 * C_N * sizeof(uint32_t)));
-    HIP_TRY(hipMemset(ss->cnt, 0, 2 * C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
     HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
     memset(ss->h_feedback, 0, 64);
     HIP_TRY(hipHostGetDevicePointer((void **)&ss->d_feedback, ss->h_feedback, 0));
@@ -149,6 +160,10 @@ int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
 int ensure_req_cap(StreamState *ss, uint32_t n_req)
 {
     if (n_req <= ss->req_cap) return HARVEST_OK;
+    if (is_capturing(ss->s)) {
+        fprintf(stderr, "libharvest: this fetch needs larger scratch lists - run it once outside graph capture\n");
+        return HARVEST_EINVAL;
+    }
     // growing: earlier work on this stream may still read the old lists
     HIP_TRY(hipStreamSynchronize(ss->s));
     HIP_TRY(hipStreamSynchronize(ss->side));
@@ -162,7 +177,7 @@ int ensure_req_cap(StreamState *ss, uint32_t n_req)
     HIP_TRY(hipMalloc(&ss->host_recs, (size_t)cap * sizeof(Rec)));
     HIP_TRY(hipMalloc(&ss->tmp_recs, (size_t)cap * sizeof(Rec)));
     HIP_TRY(hipMalloc(&ss->kind, (size_t)cap));
-    HIP_TRY(hipMalloc(&ss->blk_counts, (size_t)((cap + WG - 1) / WG) * 4 * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->blk_counts, (size_t)((cap + WG - 1) / WG) * BC_N * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ss->miss_idx, (size_t)cap * sizeof(uint32_t)));
     ss->req_cap = cap;
     return HARVEST_OK;
@@ -261,8 +276,14 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
     return release_after(st, ctx->ctl);
 }
 
-int mark_last(StreamState *ss)
+// Remembers the end of this call's work on the stream for the revocation drain.  Work recorded into a HIP graph runs
+// whenever the caller replays the graph, which no event of ours can see: the drain then waits for the whole device.
+int mark_last(harvest_ctx *ctx, StreamState *ss)
 {
+    if (is_capturing(ss->s)) {
+        ctx->captured_work = true;
+        return HARVEST_OK;
+    }
     HIP_TRY(hipEventRecord(ss->last, ss->s));
     ss->last_valid = true;
     return HARVEST_OK;
@@ -296,14 +317,19 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
+    if (ctx->profile && is_capturing(ss->s)) return HARVEST_EINVAL;   // timing events cannot be recorded into a graph
     if (ctx->profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
     bool host_tier = c.cfg.n_host_slots != 0;
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
         ga.tiles_per_chunk = tpc_host;
         ga.n_planes = planes;
         // with profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end
-        hipExtLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0,
-                              (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga);
+        if (pc)
+            hipExtLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0,
+                                  (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga);
+        else
+            hipLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
+                               (const uint32_t *)(cnt + C_HOST_REQ), ga);
         HIP_TRY(hipGetLastError());
     }
     // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the
@@ -319,8 +345,12 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     ga.tiles_per_chunk = tpc_hbm;
     ga.n_planes = planes;
-    hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
-                          (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
+    if (pa)
+        hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
+                              (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
+    else
+        hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
+                           (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
     HIP_TRY(hipGetLastError());
     ss->feedback_valid[cls] = true;
     HIP_TRY(hipEventRecord(ss->join, ss->side));
@@ -330,7 +360,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         if (host_tier) ctx->prof.push_back({ pc, pd, 1 });
         else { ctx->prof_pool.push_back(pc); ctx->prof_pool.push_back(pd); }
     }
-    return mark_last(ss);
+    return mark_last(ctx, ss);
 }
 
 int check_class(harvest_ctx *ctx, int cls)
@@ -596,7 +626,7 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     if ((rc = publish(ctx, c, moved, ss->pre_ctl))) return rc;
     HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
-    return mark_last(ss);
+    return mark_last(ctx, ss);
 }
 
 int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n)
@@ -629,6 +659,7 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
             if ((rc = publish(ctx, c, hit, nullptr))) return rc;
             HIP_TRY(hipStreamSynchronize(ctx->ctl));
             // 2. drain: everything enqueued so far that could still read the slots
+            if (ctx->captured_work) HIP_TRY(hipDeviceSynchronize());
             for (auto &kv : ctx->streams)
                 if (kv.second->last_valid) HIP_TRY(hipEventSynchronize(kv.second->last));
             // 3. (poison and) free
@@ -674,24 +705,22 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
-    if (total == 0) { ss->last_cur = -1; return HARVEST_OK; }
+    if (total == 0) { ss->fetched = false; return HARVEST_OK; }
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, (uint32_t)total))) return rc;
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
-    uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
+    uint32_t *cnt = ss->cnt;
     uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
     hipLaunchKernelGGL(classify_kv, dim3(n_wg), dim3(WG), 0, ss->s, class_dev(c), layer, d_block_table, d_n_blocks, n_seq,
-                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts, cnt,
-                       cnt_next, ctx->d_totals + HARVEST_KV * C_N);
+                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)ss->tmp_recs,
                        (const uint8_t *)ss->kind, (const uint32_t *)ss->blk_counts, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt);
+                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N);
     HIP_TRY(hipGetLastError());
-    ss->last_cur = ss->cur;
-    ss->cur ^= 1;
+    ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v);
 }
 
@@ -713,13 +742,12 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, E))) return rc;
-    uint32_t *cnt = ss->cnt + ss->cur * C_N, *cnt_next = ss->cnt + (ss->cur ^ 1) * C_N;
+    uint32_t *cnt = ss->cnt;
     hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
                        (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt, cnt_next, ctx->d_totals + HARVEST_EXPERT * C_N);
+                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_EXPERT * C_N);
     HIP_TRY(hipGetLastError());
-    ss->last_cur = ss->cur;
-    ss->cur ^= 1;
+    ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_EXPERT, cnt, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
 }
 
@@ -736,7 +764,7 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
     StreamState *ss = it->second.get();
     HIP_TRY(hipStreamSynchronize(ss->s));
     uint32_t h[C_N] = { 0 };
-    if (ss->last_cur >= 0) HIP_TRY(hipMemcpy(h, ss->cnt + ss->last_cur * C_N, sizeof h, hipMemcpyDeviceToHost));
+    if (ss->fetched) HIP_TRY(hipMemcpy(h, ss->cnt, sizeof h, hipMemcpyDeviceToHost));
     if (counts) {
         counts->n_requests = h[C_REQ]; counts->n_local = h[C_LOCAL]; counts->n_cache = h[C_CACHE];
         counts->n_host = h[C_HOST]; counts->n_lost = h[C_LOST]; counts->n_invalid = h[C_INVALID];
@@ -835,7 +863,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
         HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
     }
-    return mark_last(ss);
+    return mark_last(ctx, ss);
 }
 
 int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out)

@@ -104,20 +104,21 @@ __device__ inline uint32_t wave_sum(uint32_t v)
 
 // ---------------------------------------------------------------------------------------------------------
 // KV, pass 1: one thread per (sequence, block-table column) looks its block up and says what kind of request
-// it is; every workgroup leaves its three list totals in blk_counts[4 * blockIdx + 0..2].
+// it is; every workgroup leaves its totals in blk_counts[BC_N * blockIdx + ...].  Nothing is accumulated with
+// atomics and nothing needs zeroing, so a fetch can be replayed from a captured graph as it is.
 // ---------------------------------------------------------------------------------------------------------
+enum { BC_HBM = 0, BC_HOST, BC_MISS, BC_REQ, BC_LOCAL, BC_CACHE, BC_LOST, BC_INVALID, BC_N = 8 };
+
 __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
                                                   const int32_t *__restrict__ n_blocks, uint32_t n_seq,
                                                   uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
                                                   uint64_t dst_cap, Rec *__restrict__ tmp, uint8_t *__restrict__ kind,
-                                                  uint32_t *__restrict__ blk_counts, uint32_t *cnt, uint32_t *cnt_next,
-                                                  unsigned long long *totals)
+                                                  uint32_t *__restrict__ blk_counts)
 {
-    __shared__ uint32_t s_cnt[C_N];
+    __shared__ uint32_t s_cnt[BC_N];
     uint32_t tid = threadIdx.x;
     uint32_t r = blockIdx.x * WG + tid;
-    if (tid < C_N) s_cnt[tid] = 0;
-    if (blockIdx.x == 0 && tid < C_N) cnt_next[tid] = 0;        // the counters of the NEXT fetch on this stream
+    if (tid < BC_N) s_cnt[tid] = 0;
     __syncthreads();
     uint32_t total = n_seq * max_blocks;
     int tier = -1;                       // -1 no request, 0..3 tier, 4 invalid
@@ -149,44 +150,48 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
         kind[r] = (uint8_t)k;
         if (k == K_HBM || k == K_HOST) tmp[r] = rec;
     }
-    // wave ballots -> LDS -> one atomic per counter per workgroup
-    const int which[6] = { C_REQ, C_LOCAL, C_CACHE, C_HOST, C_LOST, C_INVALID };
-    const bool pred[6] = { tier >= 0, tier == T_LOCAL, tier == T_CACHE, tier == T_HOST, tier == T_NONE, tier == 4 };
+    // wave ballots -> LDS -> one row of totals per workgroup
+    const int which[BC_N] = { BC_HBM, BC_HOST, BC_MISS, BC_REQ, BC_LOCAL, BC_CACHE, BC_LOST, BC_INVALID };
+    const bool pred[BC_N] = { k == K_HBM, k == K_HOST, k == K_HOST || k == K_LOST, tier >= 0,
+                              tier == T_LOCAL, tier == T_CACHE, tier == T_NONE, tier == 4 };
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < BC_N; ++i) {
         uint32_t n = (uint32_t)__popcll(__ballot(pred[i]));
         if (lane_id() == 0 && n) atomicAdd(&s_cnt[which[i]], n);
     }
     __syncthreads();
-    if (tid <= C_INVALID && s_cnt[tid]) {
-        atomicAdd(&cnt[tid], s_cnt[tid]);
-        atomicAdd(&totals[tid], (unsigned long long)s_cnt[tid]);
-    }
-    if (tid == 0) {
-        blk_counts[blockIdx.x * 4 + 0] = s_cnt[C_LOCAL] + s_cnt[C_CACHE];
-        blk_counts[blockIdx.x * 4 + 1] = s_cnt[C_HOST];
-        blk_counts[blockIdx.x * 4 + 2] = s_cnt[C_HOST] + s_cnt[C_LOST];
-    }
+    if (tid < BC_N) blk_counts[blockIdx.x * BC_N + tid] = s_cnt[tid];
 }
 
 // KV, pass 2: list position = (totals of the workgroups before mine) + (totals of the waves before mine in the
-// workgroup) + (rank in my wave), so the lists come out in request order.
+// workgroup) + (rank in my wave), so the lists come out in request order.  The last workgroup has seen every
+// total: it writes the counters of this fetch and adds them to the running totals.
 __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__restrict__ tmp,
                                                  const uint8_t *__restrict__ kind, const uint32_t *__restrict__ blk_counts,
                                                  Rec *__restrict__ hbm_recs, Rec *__restrict__ host_recs,
-                                                 uint32_t *__restrict__ miss_idx, uint32_t *cnt)
+                                                 uint32_t *__restrict__ miss_idx, uint32_t *cnt,
+                                                 unsigned long long *totals)
 {
-    __shared__ uint32_t s_pre[3];
+    __shared__ uint32_t s_pre[BC_N];
     __shared__ uint32_t s_wave[WAVES][3];
     uint32_t tid = threadIdx.x, wave = tid >> 6;
     uint32_t r = blockIdx.x * WG + tid;
+    bool last = blockIdx.x == gridDim.x - 1;
     if (wave == 0) {
-        uint32_t a0 = 0, a1 = 0, a2 = 0;
-        for (uint32_t b = lane_id(); b < blockIdx.x; b += 64) {
-            a0 += blk_counts[b * 4 + 0]; a1 += blk_counts[b * 4 + 1]; a2 += blk_counts[b * 4 + 2];
+        uint32_t a[BC_N];
+#pragma unroll
+        for (int i = 0; i < BC_N; ++i) a[i] = 0;
+        uint32_t upto = last ? gridDim.x : blockIdx.x;          // the last workgroup sums everybody, itself included
+        for (uint32_t b = lane_id(); b < upto; b += 64) {
+#pragma unroll
+            for (int i = 0; i < BC_N; ++i) a[i] += blk_counts[b * BC_N + i];
         }
-        a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2);
-        if (lane_id() == 0) { s_pre[0] = a0; s_pre[1] = a1; s_pre[2] = a2; }
+#pragma unroll
+        for (int i = 0; i < BC_N; ++i) a[i] = wave_sum(a[i]);
+        if (lane_id() == 0) {
+#pragma unroll
+            for (int i = 0; i < BC_N; ++i) s_pre[i] = a[i];
+        }
     }
     uint32_t k = r < total ? kind[r] : (uint32_t)K_NONE;
     uint32_t n_hbm, n_host, n_miss;
@@ -195,15 +200,25 @@ __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__re
     uint32_t p_miss = wave_rank(k == K_HOST || k == K_LOST, n_miss);
     if (lane_id() == 0) { s_wave[wave][0] = n_hbm; s_wave[wave][1] = n_host; s_wave[wave][2] = n_miss; }
     __syncthreads();
-    uint32_t b_hbm = s_pre[0], b_host = s_pre[1], b_miss = s_pre[2];
+    uint32_t b_hbm = s_pre[BC_HBM], b_host = s_pre[BC_HOST], b_miss = s_pre[BC_MISS];
+    if (last) {                                                  // its prefix sums included its own row: take it out
+        b_hbm -= blk_counts[blockIdx.x * BC_N + BC_HBM];
+        b_host -= blk_counts[blockIdx.x * BC_N + BC_HOST];
+        b_miss -= blk_counts[blockIdx.x * BC_N + BC_MISS];
+    }
     for (uint32_t w = 0; w < wave; ++w) { b_hbm += s_wave[w][0]; b_host += s_wave[w][1]; b_miss += s_wave[w][2]; }
     if (k == K_HBM) hbm_recs[b_hbm + p_hbm] = tmp[r];
     if (k == K_HOST) host_recs[b_host + p_host] = tmp[r];
     if (k == K_HOST || k == K_LOST) miss_idx[b_miss + p_miss] = r;
-    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
-        uint32_t t0 = s_pre[0], t1 = s_pre[1], t2 = s_pre[2];
-        for (uint32_t w = 0; w < WAVES; ++w) { t0 += s_wave[w][0]; t1 += s_wave[w][1]; t2 += s_wave[w][2]; }
-        cnt[C_HBM_REQ] = t0; cnt[C_HOST_REQ] = t1; cnt[C_MISS] = t2;
+    if (last && tid == 0) {
+        cnt[C_HBM_REQ] = s_pre[BC_HBM]; cnt[C_HOST_REQ] = s_pre[BC_HOST]; cnt[C_MISS] = s_pre[BC_MISS];
+        const int from[6] = { BC_REQ, BC_LOCAL, BC_CACHE, BC_HOST, BC_LOST, BC_INVALID };
+        const int to[6] = { C_REQ, C_LOCAL, C_CACHE, C_HOST, C_LOST, C_INVALID };
+        for (int i = 0; i < 6; ++i) {
+            uint32_t v = s_pre[from[i]];
+            cnt[to[i]] = v;
+            if (v) atomicAdd(&totals[to[i]], (unsigned long long)v);
+        }
     }
 }
 
@@ -218,7 +233,7 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
                                                       uint64_t staging, uint32_t n_staging,
                                                       uint64_t *__restrict__ expert_ptr, Rec *__restrict__ hbm_recs,
                                                       Rec *__restrict__ host_recs, uint32_t *__restrict__ miss_idx,
-                                                      uint32_t *cnt, uint32_t *cnt_next, unsigned long long *totals)
+                                                      uint32_t *cnt, unsigned long long *totals)
 {
     __shared__ uint32_t bitmap[MAX_EXPERTS / 32];
     __shared__ uint32_t s_cnt[C_N];
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
     __shared__ uint32_t running;
     uint32_t tid = threadIdx.x;
     for (uint32_t i = tid; i < MAX_EXPERTS / 32; i += WG) bitmap[i] = 0;
-    if (tid < C_N) { s_cnt[tid] = 0; cnt_next[tid] = 0; }
+    if (tid < C_N) s_cnt[tid] = 0;
     if (tid == 0) running = 0;
     __syncthreads();
     for (uint32_t i = tid; i < n_ids; i += WG) {

@@ -1,0 +1,73 @@
+"""A KV fetch recorded into a HIP graph: the graph's launch parameters never change, the residency directory in device
+memory does.  Every replay - with eager placements, revocations, evictions and synchronisations between them - must
+deliver exactly what an eager fetch and the oracle deliver for the residency of that moment."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from workloads import scenarios as S
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def test_captured_fetch_follows_residency_changes_across_replays():
+    print("graph capture", flush=True)
+    wl = W.kv_decode(seed=11, n_layers=2, n_seq=3, min_len=2000, max_len=6000, p_cache=0.6, n_steps=1)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=64)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        dev = eh.dev
+        table, nb = rh.table_arrays()
+        d_table = torch.from_numpy(table).to(dev)
+        d_nb = torch.from_numpy(nb).to(dev)
+        d_sdb = torch.from_numpy(rh.seq_dst_block.view(np.int64)).to(dev)
+        chunk = wl.shape.chunk_bytes
+        dst = [torch.zeros(rh.cap * chunk, dtype=torch.uint8, device=dev) for _ in range(2)]
+        s = torch.cuda.Stream(dev)
+        with torch.cuda.stream(s):                     # once outside capture: allocates this stream's scratch
+            eh.h.fetch_kv(1, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            eh.h.fetch_kv(1, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+
+        def replay_and_check(what):
+            for t in dst:
+                t.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s):
+                counts, miss, n_miss = eh.h.fetch_info(miss_cap=table.size)
+            got = (dst[0].cpu().numpy(), dst[1].cpu().numpy(), np.sort(miss), counts)
+            P.assert_kv_equal(ro.fetch(1), got, what)
+            P.assert_kv_equal(rh.fetch(1), got, what + " (eager)")            # eager work between the replays
+            return counts
+
+        c0 = replay_and_check("replay 1")
+        c1 = replay_and_check("replay 2 (unchanged)")
+        assert c0 == c1
+        ids_o, _ = ro.revoke_quarter(1)
+        ids_h, _ = rh.revoke_quarter(1)
+        assert np.array_equal(ids_o, ids_h) and len(ids_h) > 50
+        c2 = replay_and_check("replay 3 (a quarter revoked, slots poisoned)")
+        assert c2["n_host"] > c1["n_host"] and c2["n_cache"] < c1["n_cache"]
+        host_only = [b for b in range(wl.n_closed) if eh.lookup(S.KV, b)[0] == S.HOST][:40]
+        assert np.array_equal(eo.place(S.KV, host_only), eh.place(S.KV, host_only))
+        c3 = replay_and_check("replay 4 (other blocks placed into the freed slots)")
+        assert c3["n_cache"] == c2["n_cache"] + sum(1 for b in host_only if b in set(table[:, :].reshape(-1).tolist()))
+        # new bytes through the write-back path, then replay again
+        ev = np.array(sorted(set(int(b) for b in table[0, :8])), np.uint32)
+        gk = W.rng(11, 7).integers(0, 256, size=ev.size * chunk, dtype=np.uint8)
+        gv = W.rng(11, 8).integers(0, 256, size=ev.size * chunk, dtype=np.uint8)
+        for e in (eo, eh):
+            e.evict(S.KV, 1, ev, gk, gv, np.arange(ev.size), ev.size)
+        replay_and_check("replay 5 (after a write-back)")
+        assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+        replay_and_check("replay 6 (revoked blocks placed again)")
+    finally:
+        eh.close(); eo.close()
