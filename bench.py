@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
+    ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     return ap.parse_args()
 
@@ -46,7 +47,7 @@ class DeviceDecode:
     """Keeps the decode state of workloads.scenarios.KVRun on the device so that a timed step moves no table or
     payload over PCIe except what the method itself moves."""
 
-    def __init__(self, run, eng, wl, n_steps):
+    def __init__(self, run, eng, wl, n_steps, head_major=False):
         import numpy as np
         import torch
         import workloads as W
@@ -66,9 +67,17 @@ class DeviceDecode:
         self.rows = torch.from_numpy(rows).to(self.dev)
         self.local = [eng.h.dev_plane(0, 2, p).view(sh.n_layers, -1, sh.row_bytes) for p in range(2)]
         self.t = 0
+        self.head_major = head_major
+        final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
+        self.d_cap = torch.tensor(final, dtype=torch.int32, device=self.dev)
 
     def fetch(self, layer):
-        self.eng.fetch_kv_device(layer, self.d_table, self.d_nb, self.d_sdb, self.run.cap, dst=self.dst)
+        if self.head_major:
+            sh = self.wl.shape
+            self.eng.h.fetch_kv_head_major(layer, self.d_table, self.d_nb, self.dst[0], self.dst[1], self.d_sdb,
+                                           self.d_cap, self.run.cap, sh.n_kv_heads, sh.block_tokens)
+        else:
+            self.eng.fetch_kv_device(layer, self.d_table, self.d_nb, self.d_sdb, self.run.cap, dst=self.dst)
 
     def step(self):
         import torch
@@ -136,7 +145,7 @@ def main():
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
-    dd = DeviceDecode(run, eng, wl, n_total)
+    dd = DeviceDecode(run, eng, wl, n_total, head_major=args.head_major)
 
     # ---- calibration kernel of known size (for hardware byte counters) + achievable-copy ceiling ----
     cal_bytes = 2 << 30
@@ -208,7 +217,13 @@ def main():
         ro = S.KVRun(eo, wl1)
         for t in range(n_total):                         # bring the oracle to the same point of the decode
             ro.append(t)
-        want = ro.fetch(layer)
+        if args.head_major:
+            table, nb = ro.table_arrays()
+            final = [len(t) + len(f) for t, f in zip(wl1.tables, wl1.future_blocks)]
+            want = eo.fetch_kv_head_major(layer, table, nb, ro.seq_dst_block, np.array(final, np.uint32), ro.cap,
+                                          sh.n_kv_heads, sh.block_tokens)
+        else:
+            want = ro.fetch(layer)
         dd.fetch(layer)
         torch.cuda.synchronize()
         counts, miss, n_miss = eng.h.fetch_info(miss_cap=dd.d_table.numel())
@@ -286,12 +301,13 @@ def main():
         "config": {"workload": "configs[1]: long-context KV decode fetch, Llama-3-8B-shaped (32 layers, 8 KV heads x 128, "
                                "bf16, block 16), 4 sequences U[32K,128K] tokens, 70% HBM cache tier / 30% host, one layer "
                                "gathered per step, one token appended per step",
+                   "working_layout": "head-major" if args.head_major else "token-major",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},
         "objects_per_s": round(d["n_requests"] / sec),
         "bit_exact": bit_exact,
         "served": {k: v // args.steps for k, v in d.items()},
-        "roofline": {"bound": "hbm", "kernel": "gather<1,true> (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true>" if args.head_major else "gather<1,true>") + " (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
                      "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1)},

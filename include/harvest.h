@@ -185,6 +185,18 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
                      uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                      const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream);
 
+/* The same fetch into a head-major working layout (the paper leaves layouts open; attention kernels that walk one head at
+ * a time want this one).  A pool block is [block_tokens][n_heads][head_bytes] with head_bytes = chunk_bytes /
+ * (block_tokens * n_heads), a multiple of 16.  Sequence s owns d_seq_cap_blocks[s] (< 65536) destination blocks starting at
+ * block d_seq_dst_block[s], laid out [n_heads][d_seq_cap_blocks[s] * block_tokens][head_bytes]; request (s, j) fills rows
+ * j * block_tokens ... of every head strip.  Skipped and counted invalid: unknown block, j >= d_seq_cap_blocks[s], a
+ * sequence region that ends beyond dst_capacity_blocks.  EINVAL additionally when chunk_bytes does not factor as
+ * stated. */
+int harvest_fetch_kv_head_major(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table,
+                                const int32_t *d_n_blocks, uint32_t n_seq, uint32_t max_blocks, void *d_dst_k,
+                                void *d_dst_v, const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks,
+                                uint64_t dst_capacity_blocks, uint32_t n_heads, uint32_t block_tokens, void *stream);
+
 /* Expert fetch (Section 4.3: experts are paged whole and must be resident before the FFN runs).  U = the distinct
  * valid expert numbers in d_topk_ids[n_tokens][k].  For e in U ascending: a local expert is used in place
  * (d_expert_ptr[e] = its address in the local pool, no bytes move); a cache- or host-tier expert is copied into

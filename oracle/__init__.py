@@ -61,6 +61,7 @@ def _bind(path):
     L.orc_revoke.argtypes = [vp, vp, u32, _CB, vp]
     L.orc_fetch_kv.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp, i32]
     L.orc_fetch_kv_plain.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64]
+    L.orc_fetch_kv_head_major.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp, vp, vp]
     L.orc_fetch_experts.argtypes = [vp, u32, u32, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp]
     L.orc_evict.argtypes = [vp, i32, vp, u32, vp, vp, vp, u64, i32]
     return L
@@ -212,6 +213,30 @@ class OracleClass:
                                  threads)
         if rc != OK:
             raise OracleError(rc, "fetch_kv")
+        return dst_k, dst_v, miss[:n_miss.value].copy(), counts.as_dict()
+
+    def fetch_kv_head_major(self, layer, table, n_blocks, seq_dst_block, seq_cap_blocks, dst_capacity_blocks, n_heads,
+                            block_tokens, dst_k=None, dst_v=None):
+        """Returns (dst_k, dst_v, miss_idx, counts); destination per sequence is [n_heads][cap * block_tokens][head_bytes]."""
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        n_seq, max_blocks = table.shape
+        n_blocks = np.ascontiguousarray(n_blocks, dtype=np.int32)
+        sdb = np.ascontiguousarray(seq_dst_block, dtype=np.uint64)
+        cap = np.ascontiguousarray(seq_cap_blocks, dtype=np.uint32)
+        assert n_blocks.shape == (n_seq,) and sdb.shape == (n_seq,) and cap.shape == (n_seq,)
+        nbytes = dst_capacity_blocks * self.chunk_bytes
+        if dst_k is None:
+            dst_k = np.zeros(nbytes, dtype=np.uint8)
+        if dst_v is None and self.n_planes == 2:
+            dst_v = np.zeros(nbytes, dtype=np.uint8)
+        miss = np.zeros(max(1, n_seq * max_blocks), dtype=np.uint32)
+        n_miss = ctypes.c_uint32()
+        counts = Counts()
+        rc = self.L.orc_fetch_kv_head_major(self.h, layer, _p(table), _p(n_blocks), n_seq, max_blocks, _p(dst_k),
+                                            _p(dst_v), _p(sdb), _p(cap), dst_capacity_blocks, n_heads, block_tokens,
+                                            _p(miss), ctypes.byref(n_miss), ctypes.byref(counts))
+        if rc != OK:
+            raise OracleError(rc, "fetch_kv_head_major")
         return dst_k, dst_v, miss[:n_miss.value].copy(), counts.as_dict()
 
     def fetch_experts(self, layer, n_experts, topk, n_staging_slots, staging=None):

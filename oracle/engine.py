@@ -86,6 +86,15 @@ class OracleEngine:
                                         threads=self.threads)
         return k, v, np.sort(miss), counts
 
+    def fetch_kv_head_major(self, layer, table, n_blocks, seq_dst_block, seq_cap_blocks, cap, n_heads, block_tokens,
+                            dst_fill=0):
+        c = self.c[KV]
+        n = cap * c.chunk_bytes
+        k, v, miss, counts = c.fetch_kv_head_major(self.kv_layers.index(layer), table, n_blocks, seq_dst_block,
+                                                   seq_cap_blocks, cap, n_heads, block_tokens,
+                                                   dst_k=np.full(n, dst_fill, np.uint8), dst_v=np.full(n, dst_fill, np.uint8))
+        return k, v, np.sort(miss), counts
+
     def fetch_experts(self, layer, topk, n_staging):
         """-> (list over experts: None or the expert's bytes as the FFN would see them, kinds, sorted miss, counts)."""
         c = self.c[EXPERT]

@@ -352,6 +352,60 @@ int orc_fetch_kv(orc_class *c, uint32_t layer, const int32_t *table, const int32
     return ORC_OK;
 }
 
+/*
+ * KV fetch into a head-major working layout (the layout attention kernels that
+ * walk one head at a time want; the paper leaves layouts open).  A block in a
+ * pool is token-major: [block_tokens][n_heads][head_bytes].  Sequence s owns
+ * seq_cap_blocks[s] destination blocks starting at block seq_dst_block[s], laid
+ * out [n_heads][seq_cap_blocks[s] * block_tokens][head_bytes]; request (s, j)
+ * fills rows j * block_tokens ... of every head strip.  Invalid (skipped and
+ * counted): unknown block, j >= seq_cap_blocks[s], or a sequence region that
+ * does not fit dst_capacity_blocks.  Everything else as orc_fetch_kv.
+ */
+int orc_fetch_kv_head_major(orc_class *c, uint32_t layer, const int32_t *table, const int32_t *n_blocks,
+                            uint32_t n_seq, uint32_t max_blocks, uint8_t *dst_k, uint8_t *dst_v,
+                            const uint64_t *seq_dst_block, const uint32_t *seq_cap_blocks,
+                            uint64_t dst_capacity_blocks, uint32_t n_heads, uint32_t block_tokens, uint32_t *miss_idx,
+                            uint32_t *n_miss, orc_counts *counts)
+{
+    if (layer >= c->n_layers || n_heads == 0 || block_tokens == 0) return ORC_EINVAL;
+    if (c->chunk_bytes % ((uint64_t)n_heads * block_tokens)) return ORC_EINVAL;
+    uint64_t head_bytes = c->chunk_bytes / ((uint64_t)n_heads * block_tokens);
+    uint8_t *dst[2] = { dst_k, dst_v };
+    orc_counts k = { 0, 0, 0, 0, 0, 0 };
+    uint32_t nm = 0;
+    for (uint32_t s = 0; s < n_seq; ++s) {
+        int64_t nb = n_blocks[s] < 0 ? 0 : n_blocks[s];
+        if (nb > (int64_t)max_blocks) nb = max_blocks;
+        int fits = seq_dst_block[s] + seq_cap_blocks[s] <= dst_capacity_blocks;
+        uint64_t strip = (uint64_t)seq_cap_blocks[s] * block_tokens * head_bytes;       /* one head of this sequence */
+        for (int64_t j = 0; j < nb; ++j) {
+            uint32_t r = s * max_blocks + (uint32_t)j;
+            int32_t b = table[r];
+            k.n_requests++;
+            if (b < 0 || (uint32_t)b >= c->n_objects || !fits || (uint64_t)j >= seq_cap_blocks[s]) { k.n_invalid++; continue; }
+            int t = c->tier[b];
+            if (t == T_LOCAL) k.n_local++;
+            else if (t == T_CACHE) k.n_cache++;
+            else if (t == T_HOST) k.n_host++;
+            else k.n_lost++;
+            if (t == T_HOST || t == T_NONE) { if (miss_idx) miss_idx[nm] = r; nm++; }
+            if (t == T_NONE) continue;
+            for (uint32_t p = 0; p < c->n_planes; ++p) {
+                const uint8_t *src = resolve(c, (uint32_t)b, p, layer);
+                uint8_t *seq_base = dst[p] + seq_dst_block[s] * c->chunk_bytes;
+                for (uint32_t tok = 0; tok < block_tokens; ++tok)
+                    for (uint32_t h = 0; h < n_heads; ++h)
+                        memcpy(seq_base + h * strip + ((uint64_t)j * block_tokens + tok) * head_bytes,
+                               src + ((uint64_t)tok * n_heads + h) * head_bytes, head_bytes);
+            }
+        }
+    }
+    if (n_miss) *n_miss = nm;
+    if (counts) *counts = k;
+    return ORC_OK;
+}
+
 /* KV fetch, plain definition: every valid request receives the current value of its block. */
 int orc_fetch_kv_plain(orc_class *c, uint32_t layer, const int32_t *table, const int32_t *n_blocks, uint32_t n_seq,
                        uint32_t max_blocks, uint8_t *dst_k, uint8_t *dst_v, const uint64_t *seq_dst_block,

@@ -66,6 +66,7 @@ SYMBOLS = {
     "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
     "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
+    "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
     "harvest_fetch_experts": (ctypes.c_int, [vp, u32, vp, u32, u32, vp, u32, vp, vp]),
     "harvest_fetch_info": (ctypes.c_int, [vp, vp, ctypes.POINTER(harvest_fetch_counts), vp, u32, vp]),
     "harvest_evict": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, vp, u32, vp, vp, vp, u64, ctypes.c_int, vp]),
@@ -241,6 +242,15 @@ class Harvest:
         _chk(lib.harvest_fetch_kv(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
                                   _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block), dst_capacity_blocks,
                                   _stream_ptr(stream)), "harvest_fetch_kv")
+
+    def fetch_kv_head_major(self, layer, d_table, d_n_blocks, d_dst_k, d_dst_v, d_seq_dst_block, d_seq_cap_blocks,
+                            dst_capacity_blocks, n_heads, block_tokens, stream=None):
+        """As fetch_kv; d_seq_cap_blocks int32/uint32 [n_seq] device tensor."""
+        n_seq, max_blocks = d_table.shape
+        _chk(lib.harvest_fetch_kv_head_major(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
+                                             _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block),
+                                             _dev_ptr(d_seq_cap_blocks), dst_capacity_blocks, n_heads, block_tokens,
+                                             _stream_ptr(stream)), "harvest_fetch_kv_head_major")
 
     def fetch_experts(self, layer, d_topk, d_staging, n_staging_slots, d_expert_ptr, stream=None):
         n_tokens, k = d_topk.shape

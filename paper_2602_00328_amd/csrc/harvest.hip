@@ -300,7 +300,7 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 // Launches the HBM-tier gather on the caller's stream and the host-tier gather on the side stream, joined back.
 // max_req bounds the number of requests either list can hold; dst_base: where plane p of the working layout starts.
 int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
-                   uint64_t dst_base0, uint64_t dst_base1)
+                   uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr)
 {
     GatherArgs ga{};
     for (uint32_t p = 0; p < 2; ++p) {
@@ -324,7 +324,16 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         ga.tiles_per_chunk = tpc_host;
         ga.n_planes = planes;
         // with profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end
-        if (pc)
+        if (hm) {
+            dim3 g(std::max(1u, ctx->host_grid / planes), planes);
+            if (pc)
+                hipExtLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, pc, pd, 0,
+                                      (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga, *hm,
+                                      (uint32_t *)nullptr);
+            else
+                hipLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
+                                   (const uint32_t *)(cnt + C_HOST_REQ), ga, *hm, (uint32_t *)nullptr);
+        } else if (pc)
             hipExtLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0,
                                   (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga);
         else
@@ -345,7 +354,15 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     ga.tiles_per_chunk = tpc_hbm;
     ga.n_planes = planes;
-    if (pa)
+    if (hm) {
+        if (pa)
+            hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
+                                  (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, *hm,
+                                  ss->d_feedback + cls);
+        else
+            hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
+                               (const uint32_t *)(cnt + C_HBM_REQ), ga, *hm, ss->d_feedback + cls);
+    } else if (pa)
         hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
                               (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
     else
@@ -690,9 +707,10 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
     return HARVEST_OK;
 }
 
-int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
-                     uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
-                     const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream)
+static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                         uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                         const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
+                         uint32_t n_heads, uint32_t block_tokens, void *stream)
 {
     int rc = check_class(ctx, HARVEST_KV);
     if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
@@ -702,6 +720,16 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
     if (layer >= c.cfg.n_layers) return HARVEST_EINVAL;
     uint64_t total = (uint64_t)n_seq * max_blocks;
     if (total >= (1ull << 31)) return HARVEST_EINVAL;
+    HmArgs hm{};
+    bool head_major = d_seq_cap_blocks != nullptr || n_heads != 0;
+    if (head_major) {
+        if (!n_heads || !block_tokens || c.cfg.chunk_bytes % ((uint64_t)n_heads * block_tokens)) return HARVEST_EINVAL;
+        uint64_t head_bytes = c.cfg.chunk_bytes / ((uint64_t)n_heads * block_tokens);
+        if (head_bytes % 16 || (total && !d_seq_cap_blocks)) return HARVEST_EINVAL;
+        hm.n_heads = n_heads;
+        hm.upr = (uint32_t)(head_bytes / 16);
+        hm.ups = hm.upr * block_tokens;
+    }
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
@@ -714,14 +742,34 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
     uint32_t *cnt = ss->cnt;
     uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
     hipLaunchKernelGGL(classify_kv, dim3(n_wg), dim3(WG), 0, ss->s, class_dev(c), layer, d_block_table, d_n_blocks, n_seq,
-                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts);
+                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts,
+                       d_seq_cap_blocks, (uint64_t)hm.ups * 16);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)ss->tmp_recs,
                        (const uint8_t *)ss->kind, (const uint32_t *)ss->blk_counts, ss->hbm_recs, ss->host_recs,
                        ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N);
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
-    return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v);
+    return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
+                          head_major ? &hm : nullptr);
+}
+
+int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                     uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                     const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream)
+{
+    return fetch_kv_impl(ctx, layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v, d_seq_dst_block,
+                         nullptr, dst_capacity_blocks, 0, 0, stream);
+}
+
+int harvest_fetch_kv_head_major(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                                uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                                const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks,
+                                uint64_t dst_capacity_blocks, uint32_t n_heads, uint32_t block_tokens, void *stream)
+{
+    if (!n_heads || !block_tokens) return HARVEST_EINVAL;
+    return fetch_kv_impl(ctx, layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v, d_seq_dst_block,
+                         d_seq_cap_blocks, dst_capacity_blocks, n_heads, block_tokens, stream);
 }
 
 int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,

@@ -113,8 +113,12 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
                                                   const int32_t *__restrict__ n_blocks, uint32_t n_seq,
                                                   uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
                                                   uint64_t dst_cap, Rec *__restrict__ tmp, uint8_t *__restrict__ kind,
-                                                  uint32_t *__restrict__ blk_counts)
+                                                  uint32_t *__restrict__ blk_counts,
+                                                  const uint32_t *__restrict__ seq_cap_blocks, uint64_t strip_bytes)
 {
+    // seq_cap_blocks != nullptr selects the head-major working layout: sequence s owns seq_cap_blocks[s] destination
+    // blocks, laid out [head][token][head_bytes]; strip_bytes = block_tokens * head_bytes is what one block adds to
+    // one head's strip.  The record then carries the sequence's capacity (in blocks) in bits [63:48] of src.
     __shared__ uint32_t s_cnt[BC_N];
     uint32_t tid = threadIdx.x;
     uint32_t r = blockIdx.x * WG + tid;
@@ -129,17 +133,24 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
         nb = nb < 0 ? 0 : (nb > (int32_t)max_blocks ? (int32_t)max_blocks : nb);
         if (j < (uint32_t)nb) {
             int32_t b = table[r];
-            uint64_t dst_chunk = seq_dst_block[s] + j;
-            if (b < 0 || (uint32_t)b >= c.n_objects || dst_chunk >= dst_cap) {
+            uint64_t first = seq_dst_block[s];
+            uint64_t dst_chunk = first + j;
+            bool fits = dst_chunk < dst_cap;
+            uint64_t cap = 0;
+            if (seq_cap_blocks) {
+                cap = seq_cap_blocks[s];
+                fits = first + cap <= dst_cap && j < cap && cap < 65536;
+            }
+            if (b < 0 || (uint32_t)b >= c.n_objects || !fits) {
                 tier = 4;
             } else {
                 uint64_t e = c.dir[b];
                 tier = (int)entry_tier(e);
                 uint32_t slot = entry_slot(e);
-                rec.dst = dst_chunk * c.chunk_bytes;
+                rec.dst = seq_cap_blocks ? first * c.chunk_bytes + (uint64_t)j * strip_bytes : dst_chunk * c.chunk_bytes;
                 if (tier != T_NONE) {
                     if (slot >= slots_of(c, tier)) tier = 4;        // never true for a directory the library wrote
-                    else rec.src = (((uint64_t)layer * slots_of(c, tier) + slot) * c.chunk_bytes) | (uint64_t)tier;
+                    else rec.src = (((uint64_t)layer * slots_of(c, tier) + slot) * c.chunk_bytes) | (uint64_t)tier | (cap << 48);
                 }
             }
         }
@@ -321,17 +332,23 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
 // ---------------------------------------------------------------------------------------------------------
 // The gather.
 // ---------------------------------------------------------------------------------------------------------
+// Every payload access names the global address space: an address computed as an integer would otherwise compile to
+// flat_load / flat_store, which pay for an aperture check on each access; global_load / global_store do not.
+typedef __attribute__((address_space(1))) u32x4 g_u32x4;
+
 template <bool NT>
 __device__ inline u32x4 ld16(const u32x4 *p)
 {
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
+    const g_u32x4 *g = (const g_u32x4 *)(uint64_t)p;
+    if (NT) return __builtin_nontemporal_load(g);
+    return *g;
 }
 template <bool NT>
 __device__ inline void st16(u32x4 *p, u32x4 v)
 {
-    if (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    g_u32x4 *g = (g_u32x4 *)(uint64_t)p;
+    if (NT) __builtin_nontemporal_store(v, g);
+    else *g = v;
 }
 
 template <int UNROLL, bool NT>
@@ -387,6 +404,84 @@ __global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const
     }
 }
 
+// The gather into a head-major working layout: a pool block is [token][head][head_bytes], the destination of a
+// sequence is [head][token][head_bytes].  Threads walk the block in DESTINATION order (16-byte units), so stores are
+// fully contiguous per head strip and loads come as head_bytes-long runs (256 B at the paper-shaped config: two whole
+// 128-byte lines).  No LDS: nothing is reused, the permutation is pure address arithmetic.
+struct HmArgs {
+    uint32_t n_heads;
+    uint32_t upr;             // 16-byte units per head row (head_bytes / 16)
+    uint32_t ups;             // units one block adds to one head strip (block_tokens * upr)
+    uint32_t pad;
+};
+
+// SRC_ORDER = false (HBM tier): threads walk in destination order, as said above.  SRC_ORDER = true (host tier): threads
+// walk in source order instead, so every wave load is one contiguous kilobyte - PCIe reads of 256-byte pieces reach
+// only 22 GB/s, whole kilobytes 56 GB/s - and the stores, which go to HBM, are the ones cut into head rows.
+template <int UNROLL, bool NT, bool SRC_ORDER = false>
+__global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                                GatherArgs a, HmArgs h, uint32_t *feedback)
+{
+    constexpr uint32_t UNITS = WG * UNROLL;
+    uint32_t tpc = a.tiles_per_chunk;
+    uint64_t t = blockIdx.x;
+    uint32_t idx = (uint32_t)t / tpc;
+    Rec x = recs[idx];                                   // speculative, as in gather
+    uint32_t n_req = *n_req_ptr;
+    uint32_t plane = blockIdx.y;
+    if (feedback && blockIdx.x == 0 && plane == 0 && threadIdx.x == 0) *feedback = n_req;
+    uint64_t n_tiles = (uint64_t)n_req * tpc;
+    uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
+    uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
+    while (t < n_tiles) {
+        uint32_t u0 = ((uint32_t)t - idx * tpc) * UNITS + threadIdx.x;
+        uint64_t cap = x.src >> 48;
+        uint64_t src = src_base_of(a, (uint32_t)(x.src & 3), plane) + (x.src & 0x0000FFFFFFFFFFFCull);
+        uint64_t dst = dst_plane + x.dst;
+        uint64_t head_stride = cap * h.ups * 16;
+        // unit u (in walking order) -> source unit and destination byte offset
+        auto map = [&](uint32_t u, uint32_t &s_unit, uint64_t &d_off) {
+            if (SRC_ORDER) {
+                uint32_t row_units = h.n_heads * h.upr;                 // one token: all heads
+                uint32_t tok = u / row_units, rem = u - tok * row_units;
+                uint32_t head = rem / h.upr, col = rem - head * h.upr;
+                s_unit = u;
+                d_off = head * head_stride + (uint64_t)(tok * h.upr + col) * 16;
+            } else {
+                uint32_t head = u / h.ups, rem = u - head * h.ups;
+                uint32_t tok = rem / h.upr, col = rem - tok * h.upr;
+                s_unit = (tok * h.n_heads + head) * h.upr + col;
+                d_off = head * head_stride + (uint64_t)rem * 16;
+            }
+        };
+        uint32_t tile_first = ((uint32_t)t - idx * tpc) * UNITS;
+        if (tile_first + UNITS <= chunk_units) {
+            // whole tile: no per-element branches, so all loads are in flight before the first store
+            u32x4 v[UNROLL];
+            uint64_t d_off[UNROLL];
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i) {
+                uint32_t s_unit;
+                map(u0 + i * WG, s_unit, d_off[i]);
+                v[i] = ld16<NT>(reinterpret_cast<const u32x4 *>(src) + s_unit);
+            }
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i) st16<true>(reinterpret_cast<u32x4 *>(dst + d_off[i]), v[i]);
+        } else {
+            for (uint32_t u = u0; u < chunk_units; u += WG) {
+                uint32_t s_unit;
+                uint64_t d_off;
+                map(u, s_unit, d_off);
+                st16<true>(reinterpret_cast<u32x4 *>(dst + d_off), ld16<NT>(reinterpret_cast<const u32x4 *>(src) + s_unit));
+            }
+        }
+        t += gridDim.x;
+        if (t >= n_tiles) break;
+        idx = (uint32_t)t / tpc;
+        x = recs[idx];
+    }
+}
+
 // Host tier: the same request list format, read over PCIe from pinned host memory by a few persistent workgroups.
 // Both planes of a tile are loaded before either is stored, so a two-plane class keeps 16 x 16 bytes in flight per
 // thread: the link needs bytes in flight, not workgroups, and every workgroup spared leaves the HBM tier alone.
@@ -411,13 +506,13 @@ __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, 
             u32x4 *d1 = reinterpret_cast<u32x4 *>(a.dst_base[1] + x.dst + off) + tid;
             u32x4 v0[U], v1[U];
 #pragma unroll
-            for (int i = 0; i < U; ++i) v0[i] = s0[i * WG];
+            for (int i = 0; i < U; ++i) v0[i] = ld16<false>(s0 + i * WG);
 #pragma unroll
-            for (int i = 0; i < U; ++i) v1[i] = s1[i * WG];
+            for (int i = 0; i < U; ++i) v1[i] = ld16<false>(s1 + i * WG);
 #pragma unroll
-            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v0[i], d0 + i * WG);
+            for (int i = 0; i < U; ++i) st16<true>(d0 + i * WG, v0[i]);
 #pragma unroll
-            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v1[i], d1 + i * WG);
+            for (int i = 0; i < U; ++i) st16<true>(d1 + i * WG, v1[i]);
         } else {
             for (uint32_t p = 0; p < a.n_planes; ++p)
                 copy_tile<U, false>(src_base_of(a, tier, p) + so, (p ? a.dst_base[1] : a.dst_base[0]) + x.dst + off, len,
@@ -458,9 +553,9 @@ __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ item
         u32x4 *d1 = reinterpret_cast<u32x4 *>(x.dst1 + off);
         uint32_t n_vec = (uint32_t)(len >> 4);
         for (uint32_t i = threadIdx.x; i < n_vec; i += WG) {
-            u32x4 v = s[i];
-            if (x.dst0) d0[i] = v;
-            if (x.dst1) d1[i] = v;
+            u32x4 v = ld16<false>(s + i);
+            if (x.dst0) st16<false>(d0 + i, v);
+            if (x.dst1) st16<false>(d1 + i, v);
         }
     }
 }
@@ -478,7 +573,7 @@ __global__ __launch_bounds__(WG) void fill_items(const Item *__restrict__ items,
         if (len > TILE) len = TILE;
         u32x4 *d = reinterpret_cast<u32x4 *>(items[it].dst + off);
         uint32_t n_vec = (uint32_t)(len >> 4);
-        for (uint32_t i = threadIdx.x; i < n_vec; i += WG) d[i] = v;
+        for (uint32_t i = threadIdx.x; i < n_vec; i += WG) st16<false>(d + i, v);
     }
 }
 

@@ -107,8 +107,9 @@ class HipEngine:
         self.h.fetch_kv(layer, d_table, d_n_blocks, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, cap, stream)
         return dst
 
-    def fetch_kv_begin(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0):
-        """Enqueue only; fetch_end(handle) waits and copies the results back."""
+    def fetch_kv_begin(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0, head_major=None):
+        """Enqueue only; fetch_end(handle) waits and copies the results back.  head_major = (seq_cap_blocks, n_heads,
+        block_tokens) selects the head-major working layout."""
         sp = self.spec[KV]
         table = np.ascontiguousarray(table, dtype=np.int32)
         with self._on(KV):
@@ -117,8 +118,20 @@ class HipEngine:
             d_sdb = torch.from_numpy(np.ascontiguousarray(seq_dst_block, dtype=np.uint64).view(np.int64)).to(self.dev)
             dst = [torch.full((cap * sp.chunk_bytes,), dst_fill, dtype=torch.uint8, device=self.dev)
                    for _ in range(sp.n_planes)]
-            self.h.fetch_kv(layer, d_table, d_nb, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, cap)
-        return ("kv", dst, table.size, (d_table, d_nb, d_sdb))
+            d_cap = None
+            if head_major is None:
+                self.h.fetch_kv(layer, d_table, d_nb, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, cap)
+            else:
+                caps, n_heads, block_tokens = head_major
+                d_cap = torch.from_numpy(np.ascontiguousarray(caps, dtype=np.uint32).view(np.int32)).to(self.dev)
+                self.h.fetch_kv_head_major(layer, d_table, d_nb, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, d_cap,
+                                           cap, n_heads, block_tokens)
+        return ("kv", dst, table.size, (d_table, d_nb, d_sdb, d_cap))
+
+    def fetch_kv_head_major(self, layer, table, n_blocks, seq_dst_block, seq_cap_blocks, cap, n_heads, block_tokens,
+                            dst_fill=0):
+        return self.fetch_end(self.fetch_kv_begin(layer, table, n_blocks, seq_dst_block, cap, dst_fill,
+                                                  head_major=(seq_cap_blocks, n_heads, block_tokens)))
 
     def fetch_kv(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0):
         return self.fetch_end(self.fetch_kv_begin(layer, table, n_blocks, seq_dst_block, cap, dst_fill))

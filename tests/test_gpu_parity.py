@@ -250,6 +250,47 @@ def test_revocation_stress_two_streams(overlap_revoke):
         eh.close(); eo.close()
 
 
+# ---- head-major working layout ----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("heads,dim,tokens,elt", [(8, 128, 16, 2), (8, 128, 16, 1), (3, 24, 4, 2), (1, 8, 1, 2), (5, 104, 48, 2)])
+def test_head_major_fetch(heads, dim, tokens, elt):
+    shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=elt)
+    say(f"head-major: {heads} heads x {dim} x {elt} B, {tokens}-token blocks, chunk {shape.chunk_bytes}")
+    wl = W.kv_decode(seed=12, n_seq=3, min_len=30 * tokens, max_len=90 * tokens, n_steps=tokens + 3, shape=shape,
+                     fill_mode=W.FILL_NORMAL)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
+        caps = np.array(final, np.uint32)
+        for t in range(tokens + 3):
+            table, nb = ro.table_arrays()
+            layer = t % 2
+            a = eo.fetch_kv_head_major(layer, table, nb, ro.seq_dst_block, caps, ro.cap, heads, tokens, dst_fill=0x5A)
+            b = eh.fetch_kv_head_major(layer, table, nb, rh.seq_dst_block, caps, rh.cap, heads, tokens, dst_fill=0x5A)
+            P.assert_kv_equal(a, b, f"head-major step {t}")
+            # and against the token-major fetch of the library itself: a pure transpose per sequence
+            if t == 0:
+                tm = rh.fetch(layer)
+                hb = dim * elt
+                for s in range(3):
+                    lo, hi = int(ro.seq_dst_block[s]) * shape.chunk_bytes, (int(ro.seq_dst_block[s]) + int(nb[s])) * shape.chunk_bytes
+                    x = tm[0][lo:hi].reshape(int(nb[s]) * tokens, heads, hb)
+                    full = b[0][int(ro.seq_dst_block[s]) * shape.chunk_bytes:(int(ro.seq_dst_block[s]) + final[s]) * shape.chunk_bytes]
+                    y = full.reshape(heads, final[s] * tokens, hb)[:, :int(nb[s]) * tokens]
+                    assert np.array_equal(np.transpose(x, (1, 0, 2)), y)
+            ro.append(t); rh.append(t)
+        # capacities that do not fit, and a table longer than a capacity
+        small = caps.copy(); small[1] = 2
+        table, nb = ro.table_arrays()
+        a = eo.fetch_kv_head_major(0, table, nb, ro.seq_dst_block, small, ro.cap - 1, heads, tokens, dst_fill=0x5A)
+        b = eh.fetch_kv_head_major(0, table, nb, rh.seq_dst_block, small, rh.cap - 1, heads, tokens, dst_fill=0x5A)
+        P.assert_kv_equal(a, b, "head-major with short capacities")
+        assert b[3]["n_invalid"] > 0
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- lossy objects ------------------------------------------------------------------------------------------------
 
 def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation():

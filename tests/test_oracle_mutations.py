@@ -62,6 +62,15 @@ MUTATIONS = [
     ("lossy objects demoted to the host tier, where they have no copy",
      "if (to_cache >= 0) { c->tier[id] = T_CACHE; c->slot[id] = to_cache; }\n            else { c->tier[id] = T_HOST; c->slot[id] = -1; }",
      "{ c->tier[id] = T_HOST; c->slot[id] = -1; }"),
+    ("head-major fetch reads the block as if it were head-major already",
+     "src + ((uint64_t)tok * n_heads + h) * head_bytes, head_bytes);",
+     "src + ((uint64_t)h * block_tokens + tok) * head_bytes, head_bytes);"),
+    ("head-major fetch forgets the block's position in the sequence",
+     "memcpy(seq_base + h * strip + ((uint64_t)j * block_tokens + tok) * head_bytes,",
+     "memcpy(seq_base + h * strip + ((uint64_t)tok) * head_bytes,"),
+    ("head strips sized by the current length instead of the capacity",
+     "uint64_t strip = (uint64_t)seq_cap_blocks[s] * block_tokens * head_bytes;",
+     "uint64_t strip = (uint64_t)nb * block_tokens * head_bytes;"),
     ("duplicate ids accepted by the write-back",
      "if (ids[j] == ids[i]) return ORC_EINVAL;\n    }\n    uint32_t free_cache", "if (0) return ORC_EINVAL;\n    }\n    uint32_t free_cache"),
 ]
@@ -91,6 +100,9 @@ def battery():
     pins.test_lossy_object_is_lost_after_revocation_and_leaves_dst_untouched()
     for seed in range(3):
         pins.test_random_operation_sequences_keep_tiered_and_plain_fetch_equal(seed)
+    for heads, bt, hb in ((8, 16, 256), (3, 4, 48), (1, 16, 32), (5, 1, 16)):
+        pins.test_head_major_fetch_is_the_transpose_of_the_token_major_fetch(heads, bt, hb)
+    pins.test_head_major_fetch_rejects_what_does_not_fit()
 
 
 def test_the_unmutated_oracle_passes_the_battery():

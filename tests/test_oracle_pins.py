@@ -526,3 +526,45 @@ def test_threads_do_not_change_the_result():
     a = oc.fetch_kv(0, table, n_blocks, sdb, cap, threads=1)
     b = oc.fetch_kv(0, table, n_blocks, sdb, cap, threads=4)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and list(a[2]) == list(b[2]) and a[3] == b[3]
+
+
+# ---- head-major working layout ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("heads,bt,hb", [(8, 16, 256), (3, 4, 48), (1, 16, 32), (5, 1, 16)])
+def test_head_major_fetch_is_the_transpose_of_the_token_major_fetch(heads, bt, hb):
+    chunk = heads * bt * hb
+    oc, ids, _ = make_kv(n_layers=2, chunk=chunk, n_obj=30, n_cache=20, seed=21, mode=W.FILL_NORMAL)
+    place_fraction(oc, ids, 0.5, 21)
+    g = W.rng(21, 1)
+    n_seq, max_blocks = 3, 6
+    nb = np.array([6, 2, 4], np.int32)
+    table = g.integers(0, 30, size=(n_seq, max_blocks)).astype(np.int32)
+    cap = np.array([7, 2, 5], np.uint32)                   # room beyond the current length stays untouched
+    sdb = np.array([0, 7, 9], np.uint64)
+    total = 14
+    for layer in range(2):
+        k_tm, v_tm, miss_tm, c_tm = oc.fetch_kv(layer, table, nb, sdb, total)
+        k_hm, v_hm, miss_hm, c_hm = oc.fetch_kv_head_major(layer, table, nb, sdb, cap, total, heads, bt)
+        assert list(miss_tm) == list(miss_hm) and c_tm == c_hm
+        for tm, hm in ((k_tm, k_hm), (v_tm, v_hm)):
+            for s in range(n_seq):
+                lo, hi = int(sdb[s]) * chunk, (int(sdb[s]) + int(cap[s])) * chunk
+                a = tm[lo:hi].reshape(int(cap[s]) * bt, heads, hb)            # [token][head][bytes]
+                b = hm[lo:hi].reshape(heads, int(cap[s]) * bt, hb)            # [head][token][bytes]
+                assert np.array_equal(np.transpose(a, (1, 0, 2)), b)
+
+
+def test_head_major_fetch_rejects_what_does_not_fit():
+    heads, bt, hb = 2, 4, 16
+    chunk = heads * bt * hb
+    oc, ids, _ = make_kv(n_layers=1, chunk=chunk, n_obj=10, n_cache=10, seed=22)
+    table = np.array([[0, 1, 2, 3], [4, 5, 6, 99]], np.int32)
+    nb = np.array([4, 4], np.int32)
+    k = np.full(8 * chunk, 0xEE, np.uint8); v = np.full(8 * chunk, 0xEE, np.uint8)
+    # sequence 0 has room for 3 of its 4 blocks; sequence 1's region would end beyond the destination
+    k, v, miss, counts = oc.fetch_kv_head_major(0, table, nb, np.array([0, 5], np.uint64), np.array([3, 4], np.uint32), 8,
+                                                heads, bt, dst_k=k, dst_v=v)
+    assert counts["n_requests"] == 8 and counts["n_invalid"] == 5 and counts["n_host"] == 3
+    assert (k[3 * chunk:] == 0xEE).all()
+    with pytest.raises(OracleError):
+        oc.fetch_kv_head_major(0, table, nb, np.array([0, 4], np.uint64), np.array([4, 4], np.uint32), 8, 3, bt)
