@@ -68,6 +68,11 @@ class DeviceDecode:
         self.local = [eng.h.dev_plane(0, 2, p).view(sh.n_layers, -1, sh.row_bytes) for p in range(2)]
         self.t = 0
         self.head_major = head_major
+        idx = [eng.h.lookup(0, run.tables[s][-1])[1] * sh.block_tokens + run.lens[s] % sh.block_tokens
+               for s in range(wl.n_seq)]
+        self.d_idx = torch.tensor(idx, dtype=torch.int64, device=self.dev)
+        self.roll = torch.zeros((sum(len(f) for f in wl.future_blocks) + 1, 2), dtype=torch.int64).pin_memory()
+        self.n_roll = 0
         final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
         self.d_cap = torch.tensor(final, dtype=torch.int32, device=self.dev)
 
@@ -84,14 +89,11 @@ class DeviceDecode:
         run, wl, sh = self.run, self.wl, self.wl.shape
         t = self.t
         self.fetch(t % sh.n_layers)
-        # append one token per sequence: rows go straight into the open tail blocks in local HBM
-        idx = []
-        for s in range(wl.n_seq):
-            slot = self.eng.h.lookup(0, run.tables[s][-1])[1]
-            idx.append(slot * sh.block_tokens + run.lens[s] % sh.block_tokens)
-        d_idx = torch.tensor(idx, dtype=torch.int64, device=self.dev)
+        # append one token per sequence: rows go straight into the open tail blocks in local HBM.  The row index of every
+        # tail lives on the device and is bumped there, so a step copies nothing from the host unless a tail rolls over.
         for p in range(2):
-            self.local[p].index_copy_(1, d_idx, self.rows[t, p])
+            self.local[p].index_copy_(1, self.d_idx, self.rows[t, p])
+        self.d_idx += 1
         for s in range(wl.n_seq):
             run.lens[s] += 1
             if run.lens[s] % sh.block_tokens == 0:
@@ -104,8 +106,13 @@ class DeviceDecode:
                 got = self.eng.register(0, 1, wl.host_slot[new:new + 1], 2)
                 assert int(got[0]) == new
                 run.tables[s].append(new)
-                self.d_table[s, len(run.tables[s]) - 1] = new
+                k = self.n_roll                       # one pinned row per roll-over: the copy below is asynchronous
+                self.n_roll += 1
+                self.roll[k, 0], self.roll[k, 1] = new, self.eng.h.lookup(0, new)[1] * sh.block_tokens
+                r = self.roll[k].to(self.dev, non_blocking=True)
+                self.d_table[s, len(run.tables[s]) - 1] = r[0].to(torch.int32)
                 self.d_nb[s] += 1
+                self.d_idx[s] = r[1]
         self.t += 1
 
 

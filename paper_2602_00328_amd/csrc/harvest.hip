@@ -90,6 +90,7 @@ struct StreamState {
     uint32_t *miss_idx = nullptr;
     uint32_t *cnt = nullptr;                // [C_N] counters of the last fetch; every fetch overwrites all of them
     bool fetched = false;                   // a fetch has been enqueued on this stream
+    uint64_t seen_seq = 0;                  // directory edits this stream has been ordered after
     // control scratch (host-built lists)
     void *ctl_buf = nullptr;
     size_t ctl_cap = 0;
@@ -108,6 +109,8 @@ struct harvest_ctx {
     uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0;
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
+    hipEvent_t ctl_evt = nullptr;            // recorded after every directory edit on the control stream
+    uint64_t ctl_seq = 0;                    // number of directory edits enqueued so far
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
@@ -273,7 +276,19 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
     hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, ctx->ctl, c.d_dir, d_ids, d_ent,
                        (uint32_t)n);
     HIP_TRY(hipGetLastError());
+    ctx->ctl_seq++;
+    HIP_TRY(hipEventRecord(ctx->ctl_evt, ctx->ctl));
     return release_after(st, ctx->ctl);
+}
+
+// Orders the caller's stream after every directory edit made so far, so that a fetch enqueued after register / place /
+// evict(DEMOTE) returned reads entries at least that new - without the host ever waiting for the control stream.
+int order_after_directory_edits(harvest_ctx *ctx, StreamState *ss)
+{
+    if (ss->seen_seq == ctx->ctl_seq || is_capturing(ss->s)) return HARVEST_OK;
+    HIP_TRY(hipStreamWaitEvent(ss->s, ctx->ctl_evt, 0));
+    ss->seen_seq = ctx->ctl_seq;
+    return HARVEST_OK;
 }
 
 // Remembers the end of this call's work on the stream for the revocation drain.  Work recorded into a HIP graph runs
@@ -398,6 +413,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 8;
     ctx->ctl_grid = 8 * ctx->n_cu;
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->ctl_evt, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
@@ -533,6 +549,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
+        if (ctx->ctl_evt) (void)hipEventDestroy(ctx->ctl_evt);
         (void)hipStreamDestroy(ctx->ctl);
     }
     delete ctx;
@@ -574,7 +591,9 @@ int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_
         if (out_ids) out_ids[i] = id;
     }
     if ((rc = publish(ctx, c, ids, nullptr))) return rc;
-    if (!ctx->no_device) HIP_TRY(hipStreamSynchronize(ctx->ctl));
+    // Later fetches are ordered after this edit on their own streams; only replays of recorded graphs, which the library
+    // does not see, need the entry to be there before this call returns.
+    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
     return HARVEST_OK;
 }
 
@@ -733,6 +752,7 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     if (total == 0) { ss->fetched = false; return HARVEST_OK; }
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
@@ -790,6 +810,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, E))) return rc;
+    if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     uint32_t *cnt = ss->cnt;
     hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
                        (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_recs, ss->host_recs,
