@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
+    ap.add_argument("--workload", default="kv_decode", choices=["kv_decode", "experts_phi", "experts_qwen"],
+                    help="kv_decode = configs[1] (the benchmark line); experts_* = configs[2] / configs[3], extra lines")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     return ap.parse_args()
@@ -123,6 +125,87 @@ def kv_totals(stats):
     return {k: int(getattr(stats.fetch[0], k)) for k in COUNT_KEYS}
 
 
+def bench_experts(args):
+    """configs[2] (Phi-3.5-MoE-shaped, static residency) and configs[3] (Qwen-MoE-shaped, LRU-driven cache tier): one step
+    = the expert fetch of every materialised layer for one batch of routed tokens (plus, for the LRU config, the
+    revocations and placements the policy asks for after each layer)."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from workloads import scenarios as S
+    from paper_2602_00328_amd.engine import HipEngine
+    dev = torch.device("cuda", 0)
+    phi = args.workload == "experts_phi"
+    L = min(args.layers, 32 if phi else 24)
+    if phi:
+        wl = W.expert_offload(seed=args.seed, shape=W.ExpertShape(n_layers=L))
+    else:
+        wl = W.expert_lru(seed=args.seed, shape=W.ExpertShape(n_layers=L, n_experts=60, d_model=2048, d_ff=1408))
+    t0 = time.time()
+    eng = HipEngine(expert=S.expert_spec(wl), profile=True, host_wgs=args.host_wgs)
+    run = S.ExpertRun(eng, wl)
+    torch.cuda.synchronize()
+    sp = eng.spec[1]
+    E = sp.n_experts
+    log(f"[bench] {args.workload}: {L} layers x {E} experts of {sp.chunk_bytes / 2**20:.1f} MiB, host pool "
+        f"{sp.n_host_slots * sp.chunk_bytes / 2**30:.1f} GiB, set up in {time.time() - t0:.1f}s")
+    staging = torch.empty(E * sp.chunk_bytes, dtype=torch.uint8, device=dev)
+    ptrs = torch.zeros(E, dtype=torch.int64, device=dev)
+    n_total = args.warmup + args.steps
+    topk = {(t, l): torch.from_numpy(wl.routing(t, l)).to(dev) for t in range(n_total) for l in range(L)}
+
+    def step(t):
+        for l in range(L):
+            eng.h.fetch_experts(l, topk[(t, l)], staging, E, ptrs)
+            if wl.lru_capacity:
+                run.lru_update(t, l)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    eng.h.profile()
+    f0 = eng.h.stats()
+    c0 = {k: int(getattr(f0.fetch[1], k)) for k in COUNT_KEYS}
+    p0 = int(f0.n_placed[1])
+    a = time.perf_counter()
+    for t in range(args.warmup, n_total):
+        step(t)
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - a
+    pr = eng.h.profile()
+    f1 = eng.h.stats()
+    d = {k: int(getattr(f1.fetch[1], k)) - c0[k] for k in COUNT_KEYS}
+    placed = int(f1.n_placed[1]) - p0
+    chunk = sp.chunk_bytes
+    payload = (d["n_cache"] + d["n_host"]) * chunk
+    hbm_gbs = 2 * d["n_cache"] * chunk / (pr.hbm_ms * 1e-3) / 1e9 if pr.hbm_ms > 0 and d["n_cache"] else 0.0
+    host_gbs = d["n_host"] * chunk / (pr.host_ms * 1e-3) / 1e9 if pr.host_ms > 0 and d["n_host"] else 0.0
+    out = {
+        "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
+        "value": round(2 * payload / sec / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": ("configs[2]: MoE expert fetch, Phi-3.5-MoE-shaped (16 experts/layer of 150 MiB, top-2 "
+                                "Zipf(1.1), 64 tokens, 2 local, 50% of the rest cached)" if phi else
+                                "configs[3]: MoE expert fetch, Qwen-MoE-shaped (60 experts/layer of 16.5 MiB, top-4 "
+                                "Zipf(1.0), 256 tokens, LRU cache tier of 24 experts/layer)"),
+                   "seed": args.seed, "layers_materialised": L},
+        "objects_per_s": round(d["n_requests"] / sec), "bit_exact": None,
+        "served_per_step": {k: round(v / args.steps, 2) for k, v in d.items()},
+        "placed_per_step": round(placed / args.steps, 2),
+        "roofline": {"bound": "hbm", "kernel": "gather<1,true> (HBM-tier gather of whole experts)", "achieved": round(hbm_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches": int(pr.hbm_launches)},
+        "host_tier": {"bound": "pcie", "kernel": "gather_host", "achieved": round(host_gbs, 2), "unit": "GB/s",
+                      "launches": int(pr.host_launches)},
+        "cpu_baseline": None,
+    }
+    log(f"[bench] {args.steps} steps in {sec:.3f}s: {out['ms_per_step']} ms/step; HBM tier {hbm_gbs:.0f} GB/s, host tier "
+        f"{host_gbs:.1f} GB/s; per step {out['served_per_step']}, placed {out['placed_per_step']}")
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -137,6 +220,8 @@ def main():
     from paper_2602_00328_amd.engine import HipEngine
 
     torch.cuda.set_device(0)
+    if args.workload != "kv_decode":
+        return bench_experts(args)
     dev = torch.device("cuda", 0)
     n_total = args.warmup + args.steps
     t0 = time.time()
@@ -258,13 +343,32 @@ def main():
         eo.close()
 
     # ---- isolation points: the same request list with every block in the cache tier, then every block on the host ----
-    iso = {}
+    iso, write_paths = {}, {}
     if not args.no_isolation:
         closed = [b for s in range(wl.n_seq) for b in run.tables[s][:-1]]
         host_only = [b for b in closed if eng.lookup(0, b)[0] == 0]
-        st = eng.place(0, host_only)
-        assert (st == 0).all()
         torch.cuda.synchronize()
+        a = time.perf_counter()
+        st = eng.place(0, host_only)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - a
+        assert (st == 0).all()
+        obj_bytes = 2 * chunk * sh.n_layers
+        write_paths["place"] = {"objects": len(host_only), "gbs_over_pcie": round(len(host_only) * obj_bytes / dt / 1e9, 2),
+                                "ms": round(dt * 1e3, 2)}
+        # write-back of one layer of the longest sequence: fetch it, hand the same bytes back (state stays unchanged)
+        s_long = int(np.argmax([len(t) for t in run.tables]))
+        ev_ids = np.array(run.tables[s_long][:-1], dtype=np.uint32)
+        dd.fetch(0)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        eng.h.evict(0, 0, ev_ids, dd.dst[0], dd.dst[1], int(run.seq_dst_block[s_long]) + np.arange(ev_ids.size),
+                    run.cap, 0)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - a
+        write_paths["evict"] = {"objects": int(ev_ids.size), "gbs_to_host": round(ev_ids.size * 2 * chunk / dt / 1e9, 2),
+                                "ms": round(dt * 1e3, 2), "note": "each block is written to its host slot and its cache slot"}
+        log(f"[bench] write paths: {write_paths}")
         for name, n_it in (("all_cache", args.iso_steps), ("all_host", max(2, args.iso_steps // 4))):
             if name == "all_host":
                 eng.revoke(0, closed)
@@ -325,6 +429,7 @@ def main():
                       "peak_source": "1 GiB pinned->device hipMemcpyAsync, median of 10, same run"},
         "overlap": {"max_kernel_ms_over_step_ms": round(max(hbm_ms, host_ms) / ms_per_step, 4)},
         "isolation": iso,
+        "write_paths": write_paths,
         "cpu_baseline": cpu_baseline,
     }
     eng.close()

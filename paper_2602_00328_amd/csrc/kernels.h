@@ -551,11 +551,25 @@ __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ item
         const u32x4 *s = reinterpret_cast<const u32x4 *>(x.src + off);
         u32x4 *d0 = reinterpret_cast<u32x4 *>(x.dst0 + off);
         u32x4 *d1 = reinterpret_cast<u32x4 *>(x.dst1 + off);
-        uint32_t n_vec = (uint32_t)(len >> 4);
-        for (uint32_t i = threadIdx.x; i < n_vec; i += WG) {
-            u32x4 v = ld16<false>(s + i);
-            if (x.dst0) st16<false>(d0 + i, v);
-            if (x.dst1) st16<false>(d1 + i, v);
+        if (len == TILE) {                       // whole tile: all loads in flight, then the stores
+            u32x4 v[UNROLL_HOST];
+#pragma unroll
+            for (int i = 0; i < UNROLL_HOST; ++i) v[i] = ld16<false>(s + threadIdx.x + i * WG);
+            if (x.dst0) {
+#pragma unroll
+                for (int i = 0; i < UNROLL_HOST; ++i) st16<false>(d0 + threadIdx.x + i * WG, v[i]);
+            }
+            if (x.dst1) {
+#pragma unroll
+                for (int i = 0; i < UNROLL_HOST; ++i) st16<false>(d1 + threadIdx.x + i * WG, v[i]);
+            }
+        } else {
+            uint32_t n_vec = (uint32_t)(len >> 4);
+            for (uint32_t i = threadIdx.x; i < n_vec; i += WG) {
+                u32x4 v = ld16<false>(s + i);
+                if (x.dst0) st16<false>(d0 + i, v);
+                if (x.dst1) st16<false>(d1 + i, v);
+            }
         }
     }
 }
