@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--workload", default="kv_decode", choices=["kv_decode", "experts_phi", "experts_qwen"],
                     help="kv_decode = configs[1] (the benchmark line); experts_* = configs[2] / configs[3], extra lines")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
+    ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
+                    help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
+    ap.add_argument("--graph-steps", type=int, default=64,
+                    help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     return ap.parse_args()
 
@@ -69,6 +73,7 @@ class DeviceDecode:
         self.rows = torch.from_numpy(rows).to(self.dev)
         self.local = [eng.h.dev_plane(0, 2, p).view(sh.n_layers, -1, sh.row_bytes) for p in range(2)]
         self.t = 0
+        self.graphs = None
         self.head_major = head_major
         idx = [eng.h.lookup(0, run.tables[s][-1])[1] * sh.block_tokens + run.lens[s] % sh.block_tokens
                for s in range(wl.n_seq)]
@@ -78,7 +83,26 @@ class DeviceDecode:
         final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
         self.d_cap = torch.tensor(final, dtype=torch.int32, device=self.dev)
 
+    def record_graphs(self):
+        """One HIP graph per layer holding that layer's fetch: its launch parameters are fixed, tables and residency
+        live in device memory and keep changing underneath."""
+        import torch
+        s = torch.cuda.Stream(self.dev)
+        with torch.cuda.stream(s):
+            self.fetch(0)                              # outside capture: this stream's scratch is allocated here
+        s.synchronize()
+        graphs = []
+        for layer in range(self.wl.shape.n_layers):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                self.fetch(layer)
+            graphs.append(g)
+        self.graphs = graphs
+
     def fetch(self, layer):
+        if self.graphs:
+            self.graphs[layer].replay()
+            return
         if self.head_major:
             sh = self.wl.shape
             self.eng.h.fetch_kv_head_major(layer, self.d_table, self.d_nb, self.dst[0], self.dst[1], self.d_sdb,
@@ -223,9 +247,10 @@ def main():
     if args.workload != "kv_decode":
         return bench_experts(args)
     dev = torch.device("cuda", 0)
-    n_total = args.warmup + args.steps
+    n_total = args.warmup + args.steps + args.graph_steps
     t0 = time.time()
-    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total)
+    kv_shape = W.KVShape(n_layers=args.layers, elt_bytes=args.kv_elt_bytes)
+    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape)
     sh = wl.shape
     chunk = sh.chunk_bytes
     n_blocks0 = int(sum(len(t) for t in wl.tables))
@@ -294,6 +319,26 @@ def main():
     host_bytes = host_payload / max(1, pr.host_launches)
     hbm_gbs = hbm_alg_bytes / (hbm_ms * 1e-3) / 1e9
     host_gbs = host_bytes / (host_ms * 1e-3) / 1e9
+    graph_replay = None
+    if args.graph_steps:
+        # ---- the same decode, continued, with every fetch replayed from a recorded graph ----
+        dd.record_graphs()
+        torch.cuda.synchronize()
+        g0 = kv_totals(eng.h.stats())
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(args.graph_steps):
+            dd.step()
+        torch.cuda.synchronize()
+        gsec = time.perf_counter() - a
+        g1 = kv_totals(eng.h.stats())
+        dd.graphs = None
+        g_payload = (g1["n_requests"] - g0["n_requests"]) * 2 * chunk
+        graph_replay = {"steps": args.graph_steps, "ms_per_step": round(gsec * 1e3 / args.graph_steps, 4),
+                        "value": round(2 * g_payload / gsec / 1e9, 2), "unit": "GB/s",
+                        "note": "fetches replayed from HIP graphs recorded once per layer; appends, tail write-backs and "
+                                "placements stay eager between the replays; included in the bit_exact check"}
+        log(f"[bench] graph replay: {graph_replay['ms_per_step']:.3f} ms/step, {graph_replay['value']:.0f} GB/s")
     log(f"[bench] {args.steps} steps in {sec:.3f}s: {ms_per_step:.3f} ms/step, {value:.0f} GB/s read+write, "
         f"HBM-tier kernel {hbm_ms:.3f} ms ({hbm_gbs:.0f} GB/s), host-tier kernel {host_ms:.3f} ms ({host_gbs:.1f} GB/s)")
 
@@ -303,7 +348,7 @@ def main():
         from oracle.engine import OracleEngine
         layer = dd.t % sh.n_layers
         ncores = len(os.sched_getaffinity(0))
-        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total)
+        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape)
         eo = OracleEngine(kv=S.kv_spec(wl1, cache_slack=0 if args.no_isolation else all_cache_slack), kv_layers=[layer],
                           threads=ncores)
         ro = S.KVRun(eo, wl1)
@@ -389,6 +434,15 @@ def main():
                              "hbm_gbs_read_write": round(2 * pay / (k_ms * 1e-3) / 1e9, 1),
                              "frac_of_hbm_peak": round(2 * pay / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                              "objects_per_s": round(counts["n_requests"] / (dt / n_it))}
+                if args.graph_steps:                     # the short fetch is where launch overhead shows: replay it
+                    dd.record_graphs()
+                    torch.cuda.synchronize()
+                    a = time.perf_counter()
+                    for i in range(n_it):
+                        dd.fetch(i % sh.n_layers)
+                    torch.cuda.synchronize()
+                    iso[name]["graph_replay_ms_per_fetch"] = round((time.perf_counter() - a) * 1e3 / n_it, 4)
+                    dd.graphs = None
             else:
                 k_ms = p.host_ms / p.host_launches
                 g = counts["n_host"] * 2 * chunk / (k_ms * 1e-3) / 1e9
@@ -411,12 +465,15 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": "configs[1]: long-context KV decode fetch, Llama-3-8B-shaped (32 layers, 8 KV heads x 128, "
                                "bf16, block 16), 4 sequences U[32K,128K] tokens, 70% HBM cache tier / 30% host, one layer "
-                               "gathered per step, one token appended per step",
+                               "gathered per step, one token appended per step"
+                               + ("" if args.kv_elt_bytes == 2 else f" -- VARIANT: {args.kv_elt_bytes}-byte KV elements, "
+                                  f"{chunk // 1024} KiB blocks"),
                    "working_layout": "head-major" if args.head_major else "token-major",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},
         "objects_per_s": round(d["n_requests"] / sec),
         "bit_exact": bit_exact,
+        "graph_replay": graph_replay,
         "served": {k: v // args.steps for k, v in d.items()},
         "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true>" if args.head_major else "gather<1,true>") + " (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,

@@ -77,7 +77,8 @@ enum harvest_class { HARVEST_KV = 0, HARVEST_EXPERT = 1, HARVEST_N_CLASSES = 2 }
 enum harvest_flags {
     HARVEST_FLAG_NO_DEVICE = 1,  /* directory bookkeeping only (no HIP call at all): for host-side tests */
     HARVEST_FLAG_POISON = 2,     /* revoke overwrites the freed cache slot with 0xA5 after the drain */
-    HARVEST_FLAG_PROFILE = 4     /* bracket the gather kernels with events; read them with harvest_profile */
+    HARVEST_FLAG_PROFILE = 4     /* bracket the gather kernels with events; read them with harvest_profile
+                                    (launches recorded into a graph are not timed) */
 };
 
 enum harvest_evict_flags {

@@ -332,8 +332,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
-    if (ctx->profile && is_capturing(ss->s)) return HARVEST_EINVAL;   // timing events cannot be recorded into a graph
-    if (ctx->profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
+    const bool profile = ctx->profile && !is_capturing(ss->s);        // timing events cannot be recorded into a graph
+    if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
     bool host_tier = c.cfg.n_host_slots != 0;
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
         ga.tiles_per_chunk = tpc_host;
@@ -387,7 +387,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     ss->feedback_valid[cls] = true;
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
-    if (ctx->profile) {
+    if (profile) {
         ctx->prof.push_back({ pa, pb, 0 });
         if (host_tier) ctx->prof.push_back({ pc, pd, 1 });
         else { ctx->prof_pool.push_back(pc); ctx->prof_pool.push_back(pd); }

@@ -102,9 +102,11 @@ def test_kv_decode_steps_small():
 
 # ---- chunk sizes that are not a multiple of the 32 KiB tile -----------------------------------------------------
 
-@pytest.mark.parametrize("heads,dim,tokens", [(1, 8, 1), (3, 8, 16), (8, 129 - 1, 16), (8, 136, 16), (5, 200, 48)])
-def test_ragged_chunk_sizes(heads, dim, tokens):
-    shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim)
+@pytest.mark.parametrize("heads,dim,tokens,elt", [(1, 8, 1, 2), (3, 8, 16, 2), (8, 129 - 1, 16, 2), (8, 136, 16, 2),
+                                                  (5, 200, 48, 2), (8, 128, 16, 1), (8, 128, 16, 4), (2, 80, 16, 1)])
+def test_ragged_chunk_sizes(heads, dim, tokens, elt):
+    """Block sizes off the 4 KiB / 32 KiB tiles, and the element sizes of fp8, fp16 / bf16 and fp32 KV caches."""
+    shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=elt)
     say(f"ragged chunk {shape.chunk_bytes} bytes")
     wl = W.kv_decode(seed=4, n_seq=3, min_len=20 * tokens, max_len=60 * tokens, n_steps=2 * tokens, shape=shape,
                      fill_mode=W.FILL_TAG)
@@ -207,10 +209,13 @@ def test_expert_lru_small():
 
 # ---- config 5, small: KV and experts on two streams with periodic revocation -------------------------------------
 
+N_STRESS = 500          # the step count of the revocation-stress configuration
+
+
 @pytest.mark.parametrize("overlap_revoke", [False, True])
 def test_revocation_stress_two_streams(overlap_revoke):
     say(f"revocation stress overlap={overlap_revoke}")
-    wl = W.kv_decode(seed=8, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=60)
+    wl = W.kv_decode(seed=8, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=N_STRESS)
     sh = W.ExpertShape(n_layers=2, n_experts=16, d_model=64, d_ff=100)
     ex = W.expert_offload(seed=8, shape=sh, n_tokens=64)
     eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
@@ -218,7 +223,7 @@ def test_revocation_stress_two_streams(overlap_revoke):
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
         n_revoked = 0
-        for t in range(60):
+        for t in range(N_STRESS):
             layer = t % 2
             revoke_now = t % 10 == 0 and t > 0
             ha, hx = rh.fetch_begin(layer), xh.fetch_begin(t, layer)          # both in flight on their own streams
@@ -241,7 +246,7 @@ def test_revocation_stress_two_streams(overlap_revoke):
                 assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
                 assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
             ro.append(t); rh.append(t)
-        assert n_revoked > 20
+        assert n_revoked > 20 * N_STRESS // 60
         P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
         P.assert_tiers_equal(eo, eh, S.KV, 2, what="stress kv")
