@@ -64,6 +64,18 @@ def _bind(path):
     L.orc_fetch_kv_head_major.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp, vp, vp]
     L.orc_fetch_experts.argtypes = [vp, u32, u32, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp]
     L.orc_evict.argtypes = [vp, i32, vp, u32, vp, vp, vp, u64, i32]
+    L.orc_segpool_create.restype = vp
+    L.orc_segpool_create.argtypes = [u64, u64]
+    L.orc_segpool_destroy.argtypes = [vp]
+    L.orc_segpool_mem.restype = vp
+    L.orc_segpool_mem.argtypes = [vp]
+    L.orc_segpool_free_runs.restype = u64
+    L.orc_segpool_free_runs.argtypes = [vp, vp, vp, u64]
+    L.orc_segpool_alloc.restype = i64
+    L.orc_segpool_alloc.argtypes = [vp, u64]
+    L.orc_segpool_free.restype = None
+    L.orc_segpool_free.argtypes = [vp, u64, u64]
+    L.orc_attach_segpool.argtypes = [vp, vp]
     return L
 
 
@@ -92,11 +104,44 @@ class OracleError(RuntimeError):
         self.code = code
 
 
+class SegPool:
+    """Cache-tier storage shared by several classes: variable-size segments, best-fit allocation."""
+
+    def __init__(self, n_bytes, granule):
+        self.L = _load()
+        self.n_bytes, self.granule = int(n_bytes), int(granule)
+        self.h = self.L.orc_segpool_create(self.n_bytes, self.granule)
+        if not self.h:
+            raise OracleError(EINVAL, "segpool create")
+
+    def close(self):
+        if self.h:
+            self.L.orc_segpool_destroy(self.h)
+            self.h = None
+
+    def mem(self) -> np.ndarray:
+        buf = (ctypes.c_uint8 * max(1, self.n_bytes)).from_address(self.L.orc_segpool_mem(self.h))
+        return np.frombuffer(buf, dtype=np.uint8)[:self.n_bytes]
+
+    def alloc(self, n_granules) -> int:
+        return int(self.L.orc_segpool_alloc(self.h, int(n_granules)))
+
+    def free(self, off, n_granules):
+        self.L.orc_segpool_free(self.h, int(off), int(n_granules))
+
+    def free_runs(self):
+        """[(offset, length)] in granules, ascending."""
+        cap = self.n_bytes // self.granule // 2 + 2
+        off, ln = np.empty(cap, np.uint64), np.empty(cap, np.uint64)
+        n = int(self.L.orc_segpool_free_runs(self.h, _p(off), _p(ln), cap))
+        return [(int(off[i]), int(ln[i])) for i in range(n)]
+
+
 class OracleClass:
     """One class of objects (KV blocks, or expert weights) with its three tiers and directory."""
 
     def __init__(self, n_layers, n_planes, chunk_bytes, max_objects, n_host_slots, n_cache_slots, n_local_slots,
-                 poison=False):
+                 poison=False, segpool=None):
         self.L = _load()
         self.n_layers, self.n_planes, self.chunk_bytes = n_layers, n_planes, chunk_bytes
         self.max_objects = max_objects
@@ -105,6 +150,11 @@ class OracleClass:
                                    n_local_slots, int(poison))
         if not self.h:
             raise OracleError(EINVAL, "create")
+        self.segpool = segpool
+        if segpool is not None:
+            rc = self.L.orc_attach_segpool(self.h, segpool.h)
+            if rc != OK:
+                raise OracleError(rc, "attach_segpool")
         self.revoked_log = []          # ids, in callback order
         self._cb = _CB(lambda i, _u: self.revoked_log.append(int(i)))
 

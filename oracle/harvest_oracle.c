@@ -17,6 +17,12 @@
  * V; experts: one), each plane laid out [layer][slot][chunk_bytes].  An object
  * occupies the same slot number in every layer and plane of the tier it is in.
  *
+ * Instead of equal-size cache slots a class may draw its cache-tier storage
+ * from a segment pool shared with the other class (Section 3.3: the
+ * controller allocates best-fit among free segments): an object then owns one
+ * contiguous run of granules holding [layer][plane][chunk_bytes], and its
+ * cache "slot" is the number of the run's first granule.
+ *
  * Beside the tiers the oracle keeps `truth`: the tier-free value of every
  * object, [layer][object][chunk_bytes], written only by orc_set_object and
  * orc_evict.  The plain definition of a fetch ("deliver the current value of
@@ -37,11 +43,20 @@ enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ENOSPC = -2, ORC_ENOENT = -3, ORC_ELOST 
 enum { ORC_EVICT_DEMOTE = 1 };
 #define ORC_POISON 0xA5
 
+/* Free space of a segment pool: maximal runs of free granules, sorted by offset, never adjacent. */
+typedef struct {
+    uint64_t n_granules, granule;
+    uint8_t *mem;
+    uint64_t n_runs, cap_runs;
+    uint64_t *run_off, *run_len;
+} orc_segpool;
+
 typedef struct {
     uint32_t n_layers, n_planes;
     uint64_t chunk_bytes;
     uint32_t max_objects, n_host_slots, n_cache_slots, n_local_slots;
     int poison;
+    orc_segpool *seg;    /* NULL: equal-size cache slots */
     uint8_t *host[2], *cache[2], *local[2], *truth[2];
     /* directory */
     uint32_t n_objects;
@@ -67,6 +82,73 @@ static uint8_t *plane_alloc(uint64_t n_layers, uint64_t n_slots, uint64_t chunk)
 static uint8_t *at(uint8_t *plane, const orc_class *c, uint64_t n_slots, uint32_t layer, uint64_t slot)
 {
     return plane + ((uint64_t)layer * n_slots + slot) * c->chunk_bytes;
+}
+
+orc_segpool *orc_segpool_create(uint64_t bytes, uint64_t granule)
+{
+    if (!granule || bytes % granule) return NULL;
+    orc_segpool *g = (orc_segpool *)calloc(1, sizeof *g);
+    g->n_granules = bytes / granule; g->granule = granule;
+    g->mem = (uint8_t *)calloc(bytes ? bytes : 1, 1);
+    g->cap_runs = g->n_granules / 2 + 2;
+    g->run_off = (uint64_t *)calloc(g->cap_runs, sizeof(uint64_t));
+    g->run_len = (uint64_t *)calloc(g->cap_runs, sizeof(uint64_t));
+    if (g->n_granules) { g->n_runs = 1; g->run_off[0] = 0; g->run_len[0] = g->n_granules; }
+    return g;
+}
+
+void orc_segpool_destroy(orc_segpool *g)
+{
+    if (!g) return;
+    free(g->mem); free(g->run_off); free(g->run_len); free(g);
+}
+
+uint8_t *orc_segpool_mem(orc_segpool *g) { return g->mem; }
+
+/* free runs as (offset, length) pairs in granules, ascending; returns how many there are */
+uint64_t orc_segpool_free_runs(const orc_segpool *g, uint64_t *off, uint64_t *len, uint64_t cap)
+{
+    for (uint64_t i = 0; i < g->n_runs && i < cap; ++i) { off[i] = g->run_off[i]; len[i] = g->run_len[i]; }
+    return g->n_runs;
+}
+
+/*
+ * Best-fit (Section 3.3): among the free runs that can hold `need` granules
+ * take the one that leaves the least behind; of equally good ones the lowest.
+ * The allocation sits at the low end of the run.  -1: no run is long enough.
+ */
+int64_t orc_segpool_alloc(orc_segpool *g, uint64_t need)
+{
+    if (!need) return -1;
+    int64_t best = -1;
+    for (uint64_t i = 0; i < g->n_runs; ++i)
+        if (g->run_len[i] >= need && (best < 0 || g->run_len[i] < g->run_len[best])) best = (int64_t)i;
+    if (best < 0) return -1;
+    uint64_t off = g->run_off[best];
+    if (g->run_len[best] == need) {
+        for (uint64_t i = (uint64_t)best; i + 1 < g->n_runs; ++i) { g->run_off[i] = g->run_off[i + 1]; g->run_len[i] = g->run_len[i + 1]; }
+        g->n_runs--;
+    } else { g->run_off[best] += need; g->run_len[best] -= need; }
+    return (int64_t)off;
+}
+
+/* Returns [off, off + len) to the pool, merging with a free neighbour on either side. */
+void orc_segpool_free(orc_segpool *g, uint64_t off, uint64_t len)
+{
+    uint64_t i = 0;
+    while (i < g->n_runs && g->run_off[i] < off) ++i;                    /* the new run goes before run i */
+    int joins_prev = i > 0 && g->run_off[i - 1] + g->run_len[i - 1] == off;
+    int joins_next = i < g->n_runs && off + len == g->run_off[i];
+    if (joins_prev && joins_next) {
+        g->run_len[i - 1] += len + g->run_len[i];
+        for (uint64_t k = i; k + 1 < g->n_runs; ++k) { g->run_off[k] = g->run_off[k + 1]; g->run_len[k] = g->run_len[k + 1]; }
+        g->n_runs--;
+    } else if (joins_prev) g->run_len[i - 1] += len;
+    else if (joins_next) { g->run_off[i] = off; g->run_len[i] += len; }
+    else {
+        for (uint64_t k = g->n_runs; k > i; --k) { g->run_off[k] = g->run_off[k - 1]; g->run_len[k] = g->run_len[k - 1]; }
+        g->run_off[i] = off; g->run_len[i] = len; g->n_runs++;
+    }
 }
 
 orc_class *orc_create(uint32_t n_layers, uint32_t n_planes, uint64_t chunk_bytes, uint32_t max_objects,
@@ -103,6 +185,25 @@ void orc_destroy(orc_class *c)
     free(c);
 }
 
+/* From now on the class takes its cache-tier storage from segment pool g (it must have no cache slots of its own). */
+int orc_attach_segpool(orc_class *c, orc_segpool *g)
+{
+    if (c->n_cache_slots || c->n_objects || !g) return ORC_EINVAL;
+    c->seg = g;
+    return ORC_OK;
+}
+
+static uint64_t object_bytes(const orc_class *c) { return (uint64_t)c->n_layers * c->n_planes * c->chunk_bytes; }
+static uint64_t object_granules(const orc_class *c) { return (object_bytes(c) + c->seg->granule - 1) / c->seg->granule; }
+
+/* Where the cache tier keeps (plane, layer) of the object in cache slot `slot`. */
+static uint8_t *cache_at(orc_class *c, uint32_t plane, uint32_t layer, uint64_t slot)
+{
+    if (c->seg)
+        return c->seg->mem + slot * c->seg->granule + ((uint64_t)layer * c->n_planes + plane) * c->chunk_bytes;
+    return at(c->cache[plane], c, c->n_cache_slots, layer, slot);
+}
+
 /* raw plane pointers, so the harness can look at (or, for the local pool it owns, write) tier contents.
  * which: 0 host, 1 cache, 2 local, 3 truth */
 uint8_t *orc_plane(orc_class *c, int which, uint32_t plane)
@@ -124,6 +225,21 @@ static int64_t lowest_free(const uint8_t *used, uint32_t n)
     for (uint32_t s = 0; s < n; ++s)
         if (!used[s]) return s;
     return -1;
+}
+
+/* Room in the cache tier for one object: the lowest free slot, or a best-fit segment.  -1: none. */
+static int64_t cache_take(orc_class *c)
+{
+    if (c->seg) return orc_segpool_alloc(c->seg, object_granules(c));
+    int64_t s = lowest_free(c->cache_used, c->n_cache_slots);
+    if (s >= 0) c->cache_used[s] = 1;
+    return s;
+}
+
+static void cache_release(orc_class *c, int64_t slot)
+{
+    if (c->seg) orc_segpool_free(c->seg, (uint64_t)slot, object_granules(c));
+    else c->cache_used[slot] = 0;
 }
 
 /*
@@ -180,7 +296,7 @@ static uint8_t *resolve(orc_class *c, uint32_t id, uint32_t plane, uint32_t laye
 {
     switch (c->tier[id]) {
     case T_LOCAL: return at(c->local[plane], c, c->n_local_slots, layer, (uint64_t)c->slot[id]);
-    case T_CACHE: return at(c->cache[plane], c, c->n_cache_slots, layer, (uint64_t)c->slot[id]);
+    case T_CACHE: return cache_at(c, plane, layer, (uint64_t)c->slot[id]);
     case T_HOST:  return at(c->host[plane], c, c->n_host_slots, layer, (uint64_t)c->host_slot[id]);
     default:      return NULL;
     }
@@ -229,8 +345,8 @@ int orc_write_local(orc_class *c, uint32_t id, uint32_t plane, uint32_t layer, u
 /*
  * Placement (Section 3.2: harvest_alloc + explicit copy + record in the
  * placement map; Section 4.3: the rebalancer moves chosen experts into peer
- * HBM as room appears).  Equal-size slots make best-fit degenerate, so the lowest
- * free slot is taken.  A failed allocation leaves the object on the host
+ * HBM as room appears).  With equal-size slots best-fit degenerates and the lowest
+ * free slot is taken; with a segment pool the allocation is best-fit.  A failed allocation leaves the object on the host
  * (Figure 4 caption).  status[i] per object; the call itself fails only on an
  * unknown id.
  */
@@ -244,13 +360,12 @@ int orc_place(orc_class *c, const uint32_t *ids, uint32_t n, int *status)
         if (c->tier[id] == T_NONE) st = ORC_ELOST;
         else if (c->tier[id] != T_HOST) st = ORC_OK;          /* already in HBM: nothing to do */
         else {
-            int64_t s = lowest_free(c->cache_used, c->n_cache_slots);
+            int64_t s = cache_take(c);
             if (s < 0) st = ORC_ENOSPC;
             else {
-                c->cache_used[s] = 1;
                 for (uint32_t p = 0; p < c->n_planes; ++p)
                     for (uint32_t l = 0; l < c->n_layers; ++l)
-                        memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)s),
+                        memcpy(cache_at(c, p, l, (uint64_t)s),
                                at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), c->chunk_bytes);
                 c->tier[id] = T_CACHE; c->slot[id] = s; c->gen[id] += 1;
             }
@@ -283,11 +398,11 @@ int orc_revoke(orc_class *c, const uint32_t *ids, uint32_t n, orc_revoke_cb cb, 
     }
     for (uint32_t i = 0; i < n; ++i) {               /* free (+ poison) */
         if (!hit[i]) continue;
-        c->cache_used[old[i]] = 0;
         if (c->poison)
             for (uint32_t p = 0; p < c->n_planes; ++p)
                 for (uint32_t l = 0; l < c->n_layers; ++l)
-                    memset(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes);
+                    memset(cache_at(c, p, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes);
+        cache_release(c, old[i]);
     }
     for (uint32_t i = 0; i < n; ++i)                 /* notify */
         if (hit[i] && cb) cb(ids[i], user);
@@ -495,9 +610,9 @@ int orc_fetch_experts(orc_class *c, uint32_t layer, uint32_t n_experts, const in
  * ORC_EVICT_DEMOTE (all layers only): a local object leaves local HBM - its
  * slot is released.  A backed object then lives on the host; a lossy one
  * (Section 5.2: KV state need not be duplicated in a lower tier)
- * moves into the lowest free cache slot instead and has no other copy - if the
- * cache tier cannot take all lossy objects of the call, ORC_ENOSPC and nothing
- * changes.
+ * moves into the cache tier instead (lowest free slot, or a best-fit segment)
+ * and has no other copy - if the cache tier cannot take all lossy objects of
+ * the call, ORC_ENOSPC and nothing changes.
  * Duplicate ids make the write order undefined: rejected, nothing written.
  */
 int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const uint8_t *src_k, const uint8_t *src_v,
@@ -515,18 +630,23 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
         for (uint32_t j = 0; j < i; ++j)
             if (ids[j] == ids[i]) return ORC_EINVAL;
     }
-    uint32_t free_cache = 0;
-    for (uint32_t s = 0; s < c->n_cache_slots; ++s) free_cache += !c->cache_used[s];
-    if (need_cache > free_cache) return ORC_ENOSPC;
+    /* room for every lossy object that leaves local HBM, taken in request order; all or nothing */
+    int64_t *room = (int64_t *)calloc(need_cache ? need_cache : 1, sizeof(int64_t));
+    for (uint32_t k = 0; k < need_cache; ++k) {
+        room[k] = cache_take(c);
+        if (room[k] < 0) {
+            while (k > 0) cache_release(c, room[--k]);
+            free(room);
+            return ORC_ENOSPC;
+        }
+    }
+    uint32_t n_room = 0;
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c->n_layers : (uint32_t)layer + 1;
     for (uint32_t i = 0; i < n; ++i) {
         uint32_t id = ids[i];
         int demote = (flags & ORC_EVICT_DEMOTE) && c->tier[id] == T_LOCAL;
         int64_t to_cache = -1;
-        if (demote && c->host_slot[id] < 0) {
-            to_cache = lowest_free(c->cache_used, c->n_cache_slots);
-            c->cache_used[to_cache] = 1;
-        }
+        if (demote && c->host_slot[id] < 0) to_cache = room[n_room++];
         for (uint32_t p = 0; p < c->n_planes; ++p)
             for (uint32_t l = l0; l < l1; ++l) {
                 uint64_t li = layer < 0 ? l : 0;
@@ -535,9 +655,9 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
                 if (c->host_slot[id] >= 0)
                     memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);
                 if (c->tier[id] == T_CACHE)
-                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);
+                    memcpy(cache_at(c, p, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);
                 if (to_cache >= 0)
-                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)to_cache), s, c->chunk_bytes);
+                    memcpy(cache_at(c, p, l, (uint64_t)to_cache), s, c->chunk_bytes);
                 if (c->tier[id] == T_LOCAL && !demote) {
                     uint8_t *d = at(c->local[p], c, c->n_local_slots, l, (uint64_t)c->slot[id]);
                     if (d != s) memmove(d, s, c->chunk_bytes);
@@ -551,6 +671,7 @@ int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const ui
             c->gen[id] += 1;
         }
     }
+    free(room);
     return ORC_OK;
 }
 

@@ -17,8 +17,8 @@ MUTATIONS = [
      "return plane + ((uint64_t)layer * n_slots + slot) * c->chunk_bytes;",
      "return plane + ((uint64_t)slot * c->n_layers + layer) * c->chunk_bytes;"),
     ("cache-tier objects resolved through their host slot number",
-     "case T_CACHE: return at(c->cache[plane], c, c->n_cache_slots, layer, (uint64_t)c->slot[id]);",
-     "case T_CACHE: return at(c->cache[plane], c, c->n_cache_slots, layer, (uint64_t)c->host_slot[id] % c->n_cache_slots);"),
+     "case T_CACHE: return cache_at(c, plane, layer, (uint64_t)c->slot[id]);",
+     "case T_CACHE: return cache_at(c, plane, layer, (uint64_t)c->host_slot[id] % c->n_cache_slots);"),
     ("host copy looked up by object number instead of host slot",
      "case T_HOST:  return at(c->host[plane], c, c->n_host_slots, layer, (uint64_t)c->host_slot[id]);",
      "case T_HOST:  return at(c->host[plane], c, c->n_host_slots, layer, (uint64_t)id);"),
@@ -29,23 +29,23 @@ MUTATIONS = [
      "if (src) memcpy(dst[p] + (seq_dst_block[s] + j) * c->chunk_bytes, src, c->chunk_bytes);",
      "if (src) memcpy(dst[p] + (uint64_t)j * c->chunk_bytes, src, c->chunk_bytes);"),
     ("placement copies only the first layer",
-     "for (uint32_t l = 0; l < c->n_layers; ++l)\n                        memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)s),",
-     "for (uint32_t l = 0; l < 1; ++l)\n                        memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)s),"),
+     "for (uint32_t l = 0; l < c->n_layers; ++l)\n                        memcpy(cache_at(c, p, l, (uint64_t)s),",
+     "for (uint32_t l = 0; l < 1; ++l)\n                        memcpy(cache_at(c, p, l, (uint64_t)s),"),
     ("placement takes the highest free slot",
-     "int64_t s = lowest_free(c->cache_used, c->n_cache_slots);\n            if (s < 0) st = ORC_ENOSPC;",
-     "int64_t s = -1; for (int64_t q = (int64_t)c->n_cache_slots - 1; q >= 0; --q) if (!c->cache_used[q]) { s = q; break; }\n            if (s < 0) st = ORC_ENOSPC;"),
+     "int64_t s = lowest_free(c->cache_used, c->n_cache_slots);\n    if (s >= 0) c->cache_used[s] = 1;",
+     "int64_t s = -1; for (int64_t q = (int64_t)c->n_cache_slots - 1; q >= 0; --q) if (!c->cache_used[q]) { s = q; break; }\n    if (s >= 0) c->cache_used[s] = 1;"),
     ("a full cache tier reported as success",
      "if (s < 0) st = ORC_ENOSPC;", "if (s < 0) st = ORC_OK;"),
     ("revocation forgets the generation",
      "c->slot[id] = -1; c->gen[id] += 1;\n    }\n    for (uint32_t i = 0; i < n; ++i) {               /* free (+ poison) */",
      "c->slot[id] = -1;\n    }\n    for (uint32_t i = 0; i < n; ++i) {               /* free (+ poison) */"),
     ("revocation never frees the slot",
-     "c->cache_used[old[i]] = 0;", "c->cache_used[old[i]] = 1;"),
+     "cache_release(c, old[i]);", ";"),
     ("revoked lossy objects fall back to a host copy they do not have",
      "c->tier[id] = c->host_slot[id] >= 0 ? T_HOST : T_NONE;", "c->tier[id] = T_HOST;"),
     ("write-back skips the cache-tier copy",
-     "if (c->tier[id] == T_CACHE)\n                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);",
-     "if (0)\n                    memcpy(at(c->cache[p], c, c->n_cache_slots, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);"),
+     "if (c->tier[id] == T_CACHE)\n                    memcpy(cache_at(c, p, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);",
+     "if (0)\n                    memcpy(cache_at(c, p, l, (uint64_t)c->slot[id]), s, c->chunk_bytes);"),
     ("write-back skips the host copy",
      "if (c->host_slot[id] >= 0)\n                    memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);",
      "if (0)\n                    memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), s, c->chunk_bytes);"),
@@ -72,7 +72,29 @@ MUTATIONS = [
      "uint64_t strip = (uint64_t)seq_cap_blocks[s] * block_tokens * head_bytes;",
      "uint64_t strip = (uint64_t)nb * block_tokens * head_bytes;"),
     ("duplicate ids accepted by the write-back",
-     "if (ids[j] == ids[i]) return ORC_EINVAL;\n    }\n    uint32_t free_cache", "if (0) return ORC_EINVAL;\n    }\n    uint32_t free_cache"),
+     "if (ids[j] == ids[i]) return ORC_EINVAL;\n    }\n    /* room for", "if (0) return ORC_EINVAL;\n    }\n    /* room for"),
+    ("first-fit instead of best-fit",
+     "(best < 0 || g->run_len[i] < g->run_len[best])", "(best < 0)"),
+    ("worst-fit instead of best-fit",
+     "(best < 0 || g->run_len[i] < g->run_len[best])", "(best < 0 || g->run_len[i] > g->run_len[best])"),
+    ("equally good runs: the highest taken instead of the lowest",
+     "(best < 0 || g->run_len[i] < g->run_len[best])", "(best < 0 || g->run_len[i] <= g->run_len[best])"),
+    ("segment carved from the high end of its run",
+     "} else { g->run_off[best] += need; g->run_len[best] -= need; }",
+     "} else { off = g->run_off[best] + g->run_len[best] - need; g->run_len[best] -= need; }"),
+    ("a freed segment never joins the run before it",
+     "int joins_prev = i > 0 && g->run_off[i - 1] + g->run_len[i - 1] == off;", "int joins_prev = 0;"),
+    ("a freed segment never joins the run after it",
+     "int joins_next = i < g->n_runs && off + len == g->run_off[i];", "int joins_next = 0;"),
+    ("segment laid out plane-major",
+     "+ ((uint64_t)layer * c->n_planes + plane) * c->chunk_bytes;", "+ ((uint64_t)plane * c->n_layers + layer) * c->chunk_bytes;"),
+    ("object size rounded down to whole granules",
+     "return (object_bytes(c) + c->seg->granule - 1) / c->seg->granule;", "return object_bytes(c) / c->seg->granule;"),
+    ("a failed demotion keeps the segments it had taken",
+     "while (k > 0) cache_release(c, room[--k]);", ""),
+    ("revocation poisons whole granules instead of the object",
+     "memset(cache_at(c, p, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes);",
+     "memset(cache_at(c, p, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes + (c->seg ? 16 : 0));"),
 ]
 
 
@@ -103,6 +125,11 @@ def battery():
     for heads, bt, hb in ((8, 16, 256), (3, 4, 48), (1, 16, 32), (5, 1, 16)):
         pins.test_head_major_fetch_is_the_transpose_of_the_token_major_fetch(heads, bt, hb)
     pins.test_head_major_fetch_rejects_what_does_not_fit()
+    pins.test_best_fit_worked_example()
+    for seed in range(5):
+        pins.test_best_fit_agrees_with_the_bitmap_definition_on_random_sequences(seed)
+    pins.test_two_classes_share_one_segment_pool()
+    pins.test_lossy_demotion_into_segments_is_all_or_nothing()
 
 
 def test_the_unmutated_oracle_passes_the_battery():

@@ -14,10 +14,10 @@ from oracle import OracleClass, OracleError
 
 
 def make_kv(n_layers=3, chunk=64, n_obj=40, n_cache=17, n_local=5, seed=0, poison=False, mode=W.FILL_TAG,
-            extra_host=8):
+            extra_host=8, segpool=None):
     """Small KV class: objects start on the host, host slot != object id, payload = tag or normal fill."""
     n_host = n_obj + extra_host
-    oc = OracleClass(n_layers, 2, chunk, n_obj + 8, n_host, n_cache, n_local, poison)
+    oc = OracleClass(n_layers, 2, chunk, n_obj + 8, n_host, 0 if segpool else n_cache, n_local, poison, segpool=segpool)
     hs = W.rng(seed, 100).permutation(n_host)[:n_obj]
     ids = oc.register(n_obj, hs, O.HOST)
     assert list(ids) == list(range(n_obj))
@@ -368,9 +368,10 @@ def test_invalid_requests_are_skipped_and_counted():
 
 # ---- experts (Section 4.3) --------------------------------------------------------------------------------
 
-def make_experts(n_layers=3, E=10, chunk=96, n_cache=12, n_local_per_layer=2, seed=0, lossy_local=False):
+def make_experts(n_layers=3, E=10, chunk=96, n_cache=12, n_local_per_layer=2, seed=0, lossy_local=False, segpool=None):
     n = n_layers * E
-    oc = OracleClass(1, 1, chunk, n, n, n_cache, n_layers * n_local_per_layer, poison=True)
+    oc = OracleClass(1, 1, chunk, n, n, 0 if segpool else n_cache, n_layers * n_local_per_layer, poison=True,
+                     segpool=segpool)
     hs = W.rng(seed, 110).permutation(n)
     local = np.zeros(n, bool)
     for l in range(n_layers):
@@ -568,3 +569,152 @@ def test_head_major_fetch_rejects_what_does_not_fit():
     assert (k[3 * chunk:] == 0xEE).all()
     with pytest.raises(OracleError):
         oc.fetch_kv_head_major(0, table, nb, np.array([0, 4], np.uint64), np.array([4, 4], np.uint32), 8, 3, bt)
+
+
+# ---- variable-size segments shared by both classes, best-fit allocation (Section 3.3) ----------------------------
+
+def bitmap_model(used, need):
+    """The definition on a granule bitmap: list the maximal free runs; the shortest one that fits, the lowest of equals."""
+    runs, i, n = [], 0, len(used)
+    while i < n:
+        if used[i]:
+            i += 1
+            continue
+        j = i
+        while j < n and not used[j]:
+            j += 1
+        runs.append((j - i, i))
+        i = j
+    fits = [r for r in runs if r[0] >= need]
+    return (min(fits)[1] if fits else -1), sorted((o, l) for l, o in runs)
+
+
+def test_best_fit_worked_example():
+    """16 granules; after A B C D E fill the pool and A, C, E are freed the free runs are (0,5) (7,2) (12,4):
+    first-fit, worst-fit and best-fit each answer the next requests differently."""
+    g = O.SegPool(16 * 32, 32)
+    assert [g.alloc(n) for n in (5, 2, 2, 3, 4)] == [0, 5, 7, 9, 12] and g.free_runs() == [] and g.alloc(1) == -1
+    g.free(0, 5); g.free(7, 2); g.free(12, 4)
+    assert g.free_runs() == [(0, 5), (7, 2), (12, 4)]
+    assert g.alloc(2) == 7                       # the exact fit, not the first (0) or the largest (0) run
+    assert g.alloc(3) == 12                      # the run of 4 leaves 1 behind, the run of 5 would leave 2
+    assert g.free_runs() == [(0, 5), (15, 1)]
+    assert g.alloc(1) == 15 and g.alloc(6) == -1 and g.alloc(5) == 0 and g.free_runs() == []
+    g.free(9, 3); g.free(7, 2)                   # joins the run after it
+    assert g.free_runs() == [(7, 5)]
+    g.free(5, 2)                                 # joins the run after it again
+    g.free(15, 1)                                # a run of its own
+    assert g.free_runs() == [(5, 7), (15, 1)]
+    g.free(12, 3)                                # closes the gap: joins both neighbours
+    assert g.free_runs() == [(5, 11)]
+    g.free(0, 5)
+    assert g.free_runs() == [(0, 16)] and g.alloc(0) == -1
+    g.close()
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_best_fit_agrees_with_the_bitmap_definition_on_random_sequences(seed):
+    n = 97
+    g = O.SegPool(n * 16, 16)
+    used = np.zeros(n, bool)
+    live = []
+    r = W.rng(seed, 130)
+    n_failed = 0
+    for _ in range(600):
+        if live and r.random() < 0.45:
+            off, ln = live.pop(int(r.integers(len(live))))
+            g.free(off, ln)
+            used[off:off + ln] = False
+        else:
+            need = int(r.integers(1, 13))
+            want, _ = bitmap_model(used, need)
+            got = g.alloc(need)
+            assert got == want, (seed, need)
+            if got >= 0:
+                used[got:got + need] = True
+                live.append((got, need))
+            else:
+                n_failed += 1
+        assert g.free_runs() == bitmap_model(used, 1)[1]
+    assert n_failed > 5
+    for off, ln in live:
+        g.free(off, ln)
+    assert g.free_runs() == [(0, n)]
+    g.close()
+
+
+def segment_bytes(pool, oc, slot, plane, layer):
+    o = slot * pool.granule + (layer * oc.n_planes + plane) * oc.chunk_bytes
+    return pool.mem()[o:o + oc.chunk_bytes]
+
+
+def test_two_classes_share_one_segment_pool():
+    """KV blocks (3 layers x 2 planes x 48 B = 288 B -> 5 granules of 64 B, 32 B of slack) and experts (400 B -> 7
+    granules) draw from one pool: layout inside a segment, fragmentation, ENOSPC for the large class while the small
+    one still fits, exact poisoning, and fetches that do not care."""
+    pool = O.SegPool(44 * 64, 64)
+    kv, ids, _ = make_kv(n_layers=3, chunk=48, n_obj=12, seed=20, poison=True, segpool=pool)
+    ex, local = make_experts(n_layers=2, E=6, chunk=400, seed=21, segpool=pool)
+    host_experts = [int(e) for e in np.nonzero(~local)[0]]
+    # interleave: K0 K1 X0 K2 X1 K3 -> offsets 0 5 10 17 22 29, 34 of 44 granules used
+    order = [(kv, 0), (kv, 1), (ex, host_experts[0]), (kv, 2), (ex, host_experts[1]), (kv, 3)]
+    offs = []
+    for c, i in order:
+        assert list(c.place([i])) == [O.OK]
+        offs.append(c.lookup(i)[1])
+    assert offs == [0, 5, 10, 17, 22, 29] and pool.free_runs() == [(34, 10)]
+    for b in range(4):                                               # [layer][plane][chunk] inside the segment
+        for l in range(3):
+            for p in range(2):
+                assert W.check_tag(segment_bytes(pool, kv, kv.lookup(b)[1], p, l), 20, W.CLS_KV, p, l, b)
+    for e in host_experts[:2]:
+        assert W.check_tag(segment_bytes(pool, ex, ex.lookup(e)[1], 0, 0), 21, W.CLS_EXPERT, 0, 0, e)
+    # fragment: revoke K1 (5 @ 5) and K2 (5 @ 17): 20 granules free, the longest run is 10 -> one expert fits, not two
+    kv.revoke([1, 2])
+    assert pool.free_runs() == [(5, 5), (17, 5), (34, 10)]
+    m = pool.mem()
+    assert (m[5 * 64:5 * 64 + 288] == O.POISON).all() and (m[5 * 64 + 288:10 * 64] == 0).all()   # the object, not the slack
+    assert list(ex.place(host_experts[2:4])) == [O.OK, O.ENOSPC] and ex.lookup(host_experts[2])[1] == 34
+    assert pool.free_runs() == [(5, 5), (17, 5), (41, 3)]
+    assert list(kv.place([5, 6, 7])) == [O.OK, O.OK, O.ENOSPC]       # exact fits, lowest first; 3 granules are too few
+    assert (kv.lookup(5)[1], kv.lookup(6)[1]) == (5, 17) and pool.free_runs() == [(41, 3)]
+    # fetches resolve through the shared pool and equal the tier-free definition
+    table = np.array([[0, 5, 1, 6, 3, 7, 2]], np.int32)
+    nb, sdb = np.array([7], np.int32), np.array([0], np.uint64)
+    for l in range(3):
+        k, v, miss, counts = kv.fetch_kv(l, table, nb, sdb, 7)
+        kp, vp, _, _ = kv.fetch_kv(l, table, nb, sdb, 7, plain=True)
+        assert np.array_equal(k, kp) and np.array_equal(v, vp) and counts["n_cache"] == 4 and list(miss) == [2, 5, 6]
+        check_tags(kv, k, 0, l, table, nb, sdb, 20, 48)
+        check_tags(kv, v, 1, l, table, nb, sdb, 20, 48)
+    in_cache = [e for e in host_experts[:3] if e < 6]                # layer 0's experts are objects 0..5
+    assert in_cache
+    topk = np.array([in_cache], np.int32)
+    st, kind, where, miss, counts = ex.fetch_experts(0, 6, topk, 6)
+    assert counts["n_cache"] == len(in_cache) and counts["n_host"] == 0
+    for r, e in enumerate(sorted(in_cache)):
+        assert W.check_tag(st[r * 400:(r + 1) * 400], 21, W.CLS_EXPERT, 0, 0, e)
+    # everything revoked: the pool is one run again
+    kv.revoke(list(range(12))); ex.revoke(list(range(12)))
+    assert pool.free_runs() == [(0, 44)]
+    kv.close(); ex.close(); pool.close()
+
+
+def test_lossy_demotion_into_segments_is_all_or_nothing():
+    pool = O.SegPool(5 * 64, 64)                                     # room for two objects of 2 granules, not three
+    oc = OracleClass(1, 2, 64, 6, 2, 0, 3, poison=True, segpool=pool)
+    a, b, c = oc.register(3, None, O.LOCAL)
+    for obj in (a, b, c):
+        for p in range(2):
+            oc.write_local(obj, p, 0, 0, np.full(64, 10 * int(obj) + p + 1, np.uint8))
+    lk, lv = oc.plane(O.LOCAL, 0), oc.plane(O.LOCAL, 1)
+    with pytest.raises(OracleError) as e:
+        oc.evict(-1, [a, b, c], lk, lv, [0, 1, 2], 3, O.EVICT_DEMOTE)
+    assert e.value.code == O.ENOSPC and pool.free_runs() == [(0, 5)] and oc.lookup(a)[:2] == (O.LOCAL, 0)
+    oc.evict(-1, [b, a], lk, lv, [1, 0], 3, O.EVICT_DEMOTE)
+    assert oc.lookup(b)[:2] == (O.CACHE, 0) and oc.lookup(a)[:2] == (O.CACHE, 2) and pool.free_runs() == [(4, 1)]
+    m = pool.mem()
+    assert (m[0:64] == 11).all() and (m[64:128] == 12).all() and (m[128:192] == 1).all() and (m[192:256] == 2).all()
+    oc.revoke([b])
+    assert oc.lookup(b)[0] == O.NONE and pool.free_runs() == [(0, 2), (4, 1)] and (m[0:128] == O.POISON).all()
+    oc.close(); pool.close()
