@@ -41,6 +41,20 @@
  *   - A context is not thread safe; operations that touch the same object from
  *     different streams must be ordered by the caller.
  *
+ * Shared cache pool (Section 3.3: the controller allocates best-fit among free
+ * segments).  When harvest_config.d_shared_cache is set, every class whose
+ * n_cache_slots is 0 takes its cache-tier storage from that one pool instead
+ * of from equal-size slots of its own, so objects of different sizes (KV
+ * blocks, experts) compete for the same spare HBM.  An object then owns one
+ * contiguous segment of ceil(n_layers * n_planes * chunk_bytes / granule)
+ * granules laid out [layer][plane][chunk_bytes]; the cache "slot" that
+ * harvest_lookup reports is the index of the segment's first granule.  A
+ * segment is taken best-fit: from the free run that leaves the fewest granules
+ * behind (the lowest of equally good runs), at the low end of that run; freed
+ * segments merge with free neighbours.  HARVEST_ENOSPC therefore means "no free
+ * run is long enough", which fragmentation can cause while enough granules are
+ * free in total.
+ *
  * Pool layout (per class, per plane):  [layer][slot][chunk_bytes]  - an object
  * occupies the same slot number in every layer and plane of its tier.  KV
  * objects are logical blocks with planes K and V and one chunk per model layer;
@@ -109,7 +123,11 @@ typedef struct harvest_config {
     uint32_t gather_wg_per_cu;      /* tuning: cap the HBM-tier gather at this many workgroups per CU (they then loop
                                        over tiles); 0 = default, one workgroup per 4 KiB tile */
     uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (8) */
-    uint32_t reserved[6];           /* must be 0 */
+    uint32_t shared_granule;        /* segment granule of the shared cache pool in bytes: a power of two >= 256;
+                                       0 = 4096 */
+    uint32_t reserved[5];           /* must be 0 */
+    void *d_shared_cache;           /* optional shared cache pool (device memory, 256-byte aligned), see below */
+    uint64_t shared_cache_bytes;    /* its size: a multiple of the granule, at most 2^30 granules */
 } harvest_config;
 
 typedef struct harvest_fetch_counts {
@@ -126,6 +144,8 @@ typedef struct harvest_stats_t {
     uint64_t n_placed[HARVEST_N_CLASSES], n_place_enospc[HARVEST_N_CLASSES];
     uint64_t n_revoked[HARVEST_N_CLASSES], n_evicted[HARVEST_N_CLASSES], n_demoted[HARVEST_N_CLASSES];
     uint64_t cache_slots_in_use[HARVEST_N_CLASSES], local_slots_in_use[HARVEST_N_CLASSES];
+    /* shared cache pool (all 0 without one): free granules, number of free runs, length of the longest */
+    uint64_t shared_granules_free, shared_free_runs, shared_longest_free_run;
 } harvest_stats_t;
 
 typedef struct harvest_profile_t {

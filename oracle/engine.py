@@ -9,7 +9,7 @@ from __future__ import annotations
 import numpy as np
 
 import workloads as W
-from . import OracleClass, HOST, CACHE, LOCAL, NONE, EVICT_DEMOTE, IN_PLACE, STAGED  # noqa: F401
+from . import OracleClass, SegPool, HOST, CACHE, LOCAL, NONE, EVICT_DEMOTE, IN_PLACE, STAGED  # noqa: F401
 
 KV, EXPERT = 0, 1
 
@@ -17,10 +17,15 @@ KV, EXPERT = 0, 1
 class OracleEngine:
     name = "oracle"
 
-    def __init__(self, kv=None, expert=None, poison=False, kv_layers=None, threads=1):
+    def __init__(self, kv=None, expert=None, poison=False, kv_layers=None, threads=1, shared_cache_bytes=0,
+                 shared_granule=0):
         """kv / expert: objects with n_layers, n_planes, chunk_bytes, max_objects, n_host_slots, n_cache_slots,
-        n_local_slots (and n_experts)."""
+        n_local_slots (and n_experts).  shared_cache_bytes: a segment pool from which every class without cache slots
+        of its own takes its cache-tier storage."""
         self.spec = {KV: kv, EXPERT: expert}
+        self.pool = SegPool(shared_cache_bytes, shared_granule or 4096) if shared_cache_bytes else None
+        # an object's segment holds all its layers: a layer subset would change every allocation
+        assert not (self.pool and kv is not None and kv_layers is not None and kv.n_cache_slots == 0)
         self.threads = threads
         self.kv_layers = list(range(kv.n_layers)) if (kv is not None and kv_layers is None) else kv_layers
         self.c = {}
@@ -29,11 +34,21 @@ class OracleEngine:
                 continue
             nl = len(self.kv_layers) if k == KV else sp.n_layers
             self.c[k] = OracleClass(nl, sp.n_planes, sp.chunk_bytes, sp.max_objects, sp.n_host_slots,
-                                    sp.n_cache_slots, sp.n_local_slots, poison)
+                                    sp.n_cache_slots, sp.n_local_slots, poison,
+                                    segpool=self.pool if sp.n_cache_slots == 0 else None)
 
     def close(self):
         for c in self.c.values():
             c.close()
+        if self.pool:
+            self.pool.close()
+            self.pool = None
+
+    def shared_plane(self):
+        return self.pool.mem()
+
+    def shared_free_runs(self):
+        return self.pool.free_runs()
 
     def _layers(self, cls):
         return self.kv_layers if cls == KV else list(range(self.spec[cls].n_layers))
@@ -141,4 +156,6 @@ class OracleEngine:
                 flags)
 
     def tier_plane(self, cls, tier, plane=0):
+        if tier == CACHE and self.c[cls].segpool is not None:
+            return np.zeros((self.c[cls].n_layers, 0, self.c[cls].chunk_bytes), np.uint8)
         return self.c[cls].plane(tier, plane)

@@ -35,7 +35,8 @@ class harvest_class_config(ctypes.Structure):
 
 class harvest_config(ctypes.Structure):
     _fields_ = [("flags", u32), ("device", i32), ("cls", harvest_class_config * 2),
-                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("reserved", u32 * 6)]
+                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("reserved", u32 * 5),
+                ("d_shared_cache", vp), ("shared_cache_bytes", u64)]
 
 
 class harvest_fetch_counts(ctypes.Structure):
@@ -48,7 +49,8 @@ class harvest_fetch_counts(ctypes.Structure):
 class harvest_stats_t(ctypes.Structure):
     _fields_ = [("fetch", harvest_fetch_counts * 2), ("n_placed", u64 * 2), ("n_place_enospc", u64 * 2),
                 ("n_revoked", u64 * 2), ("n_evicted", u64 * 2), ("n_demoted", u64 * 2),
-                ("cache_slots_in_use", u64 * 2), ("local_slots_in_use", u64 * 2)]
+                ("cache_slots_in_use", u64 * 2), ("local_slots_in_use", u64 * 2),
+                ("shared_granules_free", u64), ("shared_free_runs", u64), ("shared_longest_free_run", u64)]
 
 
 class harvest_profile_t(ctypes.Structure):
@@ -141,7 +143,9 @@ class Harvest:
     """A library context plus the pools it borrows (allocated here with torch / harvest_pinned_alloc)."""
 
     def __init__(self, kv: ClassSpec | None = None, expert: ClassSpec | None = None, flags: int = 0, device: int = 0,
-                 gather_wg_per_cu: int = 0, host_wgs: int = 0):
+                 gather_wg_per_cu: int = 0, host_wgs: int = 0, shared_cache_bytes: int = 0, shared_granule: int = 0):
+        """shared_cache_bytes > 0: one device pool of that size from which every class with n_cache_slots == 0 carves
+        its cache-tier segments (best-fit)."""
         self.flags, self.device = flags, device
         self.spec = {KV: kv, EXPERT: expert}
         self.no_device = bool(flags & FLAG_NO_DEVICE)
@@ -153,6 +157,11 @@ class Harvest:
         cfg = harvest_config()
         cfg.flags, cfg.device = flags, device
         cfg.gather_wg_per_cu, cfg.host_wgs = gather_wg_per_cu, host_wgs
+        cfg.shared_cache_bytes, cfg.shared_granule = shared_cache_bytes, shared_granule
+        self.shared_cache = None
+        if shared_cache_bytes and not self.no_device:
+            self.shared_cache = torch.zeros(shared_cache_bytes, dtype=torch.uint8, device=torch.device("cuda", device))
+            cfg.d_shared_cache = self.shared_cache.data_ptr()
         for k, sp in self.spec.items():
             if sp is None:
                 continue
@@ -203,6 +212,7 @@ class Harvest:
                 lib.harvest_pinned_free(ptr)
             self._host_ptr.clear()
             self._dev.clear()
+            self.shared_cache = None
 
     def __del__(self):
         try:

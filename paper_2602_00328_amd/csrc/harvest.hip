@@ -36,6 +36,54 @@ using namespace hv;
 
 namespace {
 
+// Free space of the shared cache pool, in granules: maximal free runs, indexed by offset (to merge neighbours on free)
+// and by (length, offset) (to find the best fit: the shortest run that is long enough, the lowest of equals).
+struct SegAlloc {
+    std::map<uint64_t, uint64_t> by_off;                  // offset -> length
+    std::set<std::pair<uint64_t, uint64_t>> by_len;       // (length, offset)
+    uint64_t n_free = 0;
+
+    void add(uint64_t off, uint64_t len) { by_off[off] = len; by_len.insert({ len, off }); }
+    void drop(uint64_t off, uint64_t len) { by_off.erase(off); by_len.erase({ len, off }); }
+    void reset(uint64_t n_granules)
+    {
+        by_off.clear(); by_len.clear();
+        n_free = n_granules;
+        if (n_granules) add(0, n_granules);
+    }
+    int64_t take(uint64_t need)
+    {
+        if (!need) return -1;
+        auto it = by_len.lower_bound({ need, 0 });
+        if (it == by_len.end()) return -1;
+        uint64_t len = it->first, off = it->second;
+        drop(off, len);
+        if (len > need) add(off + need, len - need);       // the segment sits at the low end of the run
+        n_free -= need;
+        return (int64_t)off;
+    }
+    void give(uint64_t off, uint64_t len)
+    {
+        n_free += len;
+        auto next = by_off.lower_bound(off);
+        if (next != by_off.begin()) {
+            auto prev = std::prev(next);
+            if (prev->first + prev->second == off) {
+                off = prev->first; len += prev->second;
+                uint64_t po = prev->first, pl = prev->second;
+                drop(po, pl);
+            }
+        }
+        next = by_off.lower_bound(off + 1);
+        if (next != by_off.end() && next->first == off + len) {
+            uint64_t no = next->first, nl = next->second;
+            len += nl;
+            drop(no, nl);
+        }
+        add(off, len);
+    }
+};
+
 struct ClassState {
     harvest_class_config cfg{};
     bool used = false;
@@ -49,6 +97,11 @@ struct ClassState {
     std::vector<void *> cb_user;
     std::vector<uint8_t> host_used;
     std::set<uint32_t> cache_free, local_free;   // begin() = lowest free slot
+    // cache tier carved from the context's shared pool instead of equal-size slots: an object owns obj_granules
+    // granules from granule number `slot` on, laid out [layer][plane][chunk]
+    SegAlloc *seg = nullptr;
+    uint64_t seg_base = 0, granule = 0, obj_granules = 0, n_granules = 0;
+    uint64_t cache_in_use = 0;
     uint64_t *d_dir = nullptr;
     // host-side statistics
     uint64_t n_placed = 0, n_enospc = 0, n_revoked = 0, n_evicted = 0, n_demoted = 0;
@@ -59,8 +112,31 @@ struct ClassState {
         uint32_t s = t == T_HOST ? (uint32_t)host_slot[id] : (t == T_NONE ? 0u : (uint32_t)slot[id]);
         return make_entry(t, s, gen[id]);
     }
+    // Room in the cache tier for one object: the lowest free slot, or a best-fit segment.  -1: none.
+    int64_t cache_take()
+    {
+        int64_t s = -1;
+        if (seg) s = seg->take(obj_granules);
+        else if (!cache_free.empty()) {
+            s = *cache_free.begin();
+            cache_free.erase(cache_free.begin());
+        }
+        if (s >= 0) cache_in_use++;
+        return s;
+    }
+    void cache_release(int64_t s)
+    {
+        if (seg) seg->give((uint64_t)s, obj_granules);
+        else cache_free.insert((uint32_t)s);
+        cache_in_use--;
+    }
+    uint64_t cache_base(uint32_t plane) const
+    {
+        return seg ? seg_base + plane * cfg.chunk_bytes : (uint64_t)cfg.d_cache_pool[plane];
+    }
     uint64_t addr(int t, uint32_t plane, uint32_t layer, uint64_t s) const
     {
+        if (t == T_CACHE && seg) return cache_base(plane) + s * granule + (uint64_t)layer * cfg.n_planes * cfg.chunk_bytes;
         uint64_t base = t == T_HOST ? host_dev[plane]
                                     : (t == T_CACHE ? (uint64_t)cfg.d_cache_pool[plane] : (uint64_t)cfg.d_local_pool[plane]);
         uint64_t ns = t == T_HOST ? cfg.n_host_slots : (t == T_CACHE ? cfg.n_cache_slots : cfg.n_local_slots);
@@ -117,6 +193,7 @@ struct harvest_ctx {
     std::vector<ProfPair> prof;
     std::vector<hipEvent_t> prof_pool;
     bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
+    SegAlloc shared;                      // free space of cfg.d_shared_cache
     std::mutex mu;
 };
 
@@ -246,12 +323,20 @@ ClassDev class_dev(const ClassState &c)
     d.chunk_bytes = c.cfg.chunk_bytes;
     for (uint32_t p = 0; p < 2; ++p) {
         d.pool[T_HOST][p] = c.host_dev[p];
-        d.pool[T_CACHE][p] = (uint64_t)c.cfg.d_cache_pool[p];
+        d.pool[T_CACHE][p] = c.cache_base(p);
         d.pool[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p];
     }
     d.n_slots[T_HOST] = c.cfg.n_host_slots;
-    d.n_slots[T_CACHE] = c.cfg.n_cache_slots;
+    d.n_slots[T_CACHE] = c.seg ? (uint32_t)c.n_granules : c.cfg.n_cache_slots;
     d.n_slots[T_LOCAL] = c.cfg.n_local_slots;
+    for (int t = 0; t < 3; ++t) {
+        d.slot_stride[t] = c.cfg.chunk_bytes;
+        d.layer_stride[t] = (uint64_t)d.n_slots[t] * c.cfg.chunk_bytes;
+    }
+    if (c.seg) {
+        d.slot_stride[T_CACHE] = c.granule;
+        d.layer_stride[T_CACHE] = (uint64_t)c.cfg.n_planes * c.cfg.chunk_bytes;
+    }
     return d;
 }
 
@@ -320,7 +405,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     GatherArgs ga{};
     for (uint32_t p = 0; p < 2; ++p) {
         ga.src_base[T_HOST][p] = c.host_dev[p];
-        ga.src_base[T_CACHE][p] = (uint64_t)c.cfg.d_cache_pool[p];
+        ga.src_base[T_CACHE][p] = c.cache_base(p);
         ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p];
     }
     ga.dst_base[0] = dst_base0;
@@ -482,6 +567,15 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
     ctx->no_device = cfg->flags & HARVEST_FLAG_NO_DEVICE;
     ctx->poison = cfg->flags & HARVEST_FLAG_POISON;
     ctx->profile = cfg->flags & HARVEST_FLAG_PROFILE;
+    const uint64_t granule = cfg->shared_granule ? cfg->shared_granule : 4096;
+    const bool shared = cfg->d_shared_cache != nullptr || ((cfg->flags & HARVEST_FLAG_NO_DEVICE) && cfg->shared_cache_bytes);
+    if (shared) {
+        if (granule < 256 || (granule & (granule - 1)) || cfg->shared_cache_bytes % granule ||
+            cfg->shared_cache_bytes / granule > 0x3FFFFFFFull || cfg->shared_cache_bytes >= (1ull << 47) ||
+            ((uint64_t)cfg->d_shared_cache & 255))
+            return HARVEST_EINVAL;
+        ctx->shared.reset(cfg->shared_cache_bytes / granule);
+    } else if (cfg->shared_cache_bytes || cfg->shared_granule) return HARVEST_EINVAL;
     bool any = false;
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
         const harvest_class_config &cc = cfg->cls[k];
@@ -508,6 +602,13 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
         c.used = true;
         any = true;
         c.host_used.assign(cc.n_host_slots, 0);
+        if (shared && cc.n_cache_slots == 0) {
+            c.seg = &ctx->shared;
+            c.seg_base = (uint64_t)cfg->d_shared_cache;
+            c.granule = granule;
+            c.n_granules = cfg->shared_cache_bytes / granule;
+            c.obj_granules = ((uint64_t)cc.n_layers * cc.n_planes * cc.chunk_bytes + granule - 1) / granule;
+        }
         for (uint32_t s = 0; s < cc.n_cache_slots; ++s) c.cache_free.insert(c.cache_free.end(), s);
         for (uint32_t s = 0; s < cc.n_local_slots; ++s) c.local_free.insert(c.local_free.end(), s);
     }
@@ -629,13 +730,11 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
         if (c.tier[id] == T_NONE) st = HARVEST_ELOST;
         else if (c.tier[id] != T_HOST) st = HARVEST_OK;
         else if (c.host_slot[id] < 0) st = HARVEST_EINVAL;
-        else if (c.cache_free.empty()) { st = HARVEST_ENOSPC; c.n_enospc++; }
+        else if (int64_t s = c.cache_take(); s < 0) { st = HARVEST_ENOSPC; c.n_enospc++; }
         else {
-            uint32_t s = *c.cache_free.begin();
-            c.cache_free.erase(c.cache_free.begin());
             for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
                 for (uint32_t l = 0; l < c.cfg.n_layers; ++l)
-                    items.push_back({ c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]), c.addr(T_CACHE, p, l, s) });
+                    items.push_back({ c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]), c.addr(T_CACHE, p, l, (uint64_t)s) });
             c.tier[id] = T_CACHE; c.slot[id] = s; c.gen[id] += 1;
             c.n_placed++;
             moved.push_back(id);
@@ -718,7 +817,7 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
                 HIP_TRY(hipStreamSynchronize(ctx->ctl));
             }
         }
-        for (uint32_t s : old_slot) c.cache_free.insert(s);
+        for (uint32_t s : old_slot) c.cache_release(s);
     }
     // 4. notify (outside the lock: a callback may call back into the library)
     for (size_t i = 0; i < hit.size(); ++i)
@@ -865,7 +964,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
             if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) need_cache++;
             if (!seen.insert(ids[i]).second) return HARVEST_EINVAL;
         }
-        if (need_cache > c.cache_free.size()) return HARVEST_ENOSPC;
+        if (!c.seg && need_cache > c.cache_free.size()) return HARVEST_ENOSPC;
     }
     if (n == 0) return HARVEST_OK;
     if (!ctx->no_device) {
@@ -877,14 +976,24 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     std::vector<Item2> items;
     std::vector<uint32_t> demoted;
+    // room for every lossy object that leaves local HBM, taken in request order before anything changes: all or nothing
+    std::vector<int64_t> room;
+    if (demote_flag)
+        for (uint32_t i = 0; i < n; ++i)
+            if (c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) {
+                int64_t s = c.cache_take();
+                if (s < 0) {
+                    while (!room.empty()) { c.cache_release(room.back()); room.pop_back(); }
+                    return HARVEST_ENOSPC;
+                }
+                room.push_back(s);
+            }
+    size_t n_room = 0;
     for (uint32_t i = 0; i < n; ++i) {
         uint32_t id = ids[i];
         bool demote = demote_flag && c.tier[id] == T_LOCAL;
         int64_t to_cache = -1;                  // a lossy object leaves local HBM for the cache tier: it has no host copy
-        if (demote && c.host_slot[id] < 0) {
-            to_cache = *c.cache_free.begin();
-            c.cache_free.erase(c.cache_free.begin());
-        }
+        if (demote && c.host_slot[id] < 0) to_cache = room[n_room++];
         for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
             for (uint32_t l = l0; l < l1; ++l) {
                 uint64_t li = layer < 0 ? l : 0;
@@ -955,9 +1064,12 @@ int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out)
         out->fetch[k].n_host = t[C_HOST]; out->fetch[k].n_lost = t[C_LOST]; out->fetch[k].n_invalid = t[C_INVALID];
         out->n_placed[k] = c.n_placed; out->n_place_enospc[k] = c.n_enospc; out->n_revoked[k] = c.n_revoked;
         out->n_evicted[k] = c.n_evicted; out->n_demoted[k] = c.n_demoted;
-        out->cache_slots_in_use[k] = c.cfg.n_cache_slots - c.cache_free.size();
+        out->cache_slots_in_use[k] = c.cache_in_use;
         out->local_slots_in_use[k] = c.cfg.n_local_slots - c.local_free.size();
     }
+    out->shared_granules_free = ctx->shared.n_free;
+    out->shared_free_runs = ctx->shared.by_off.size();
+    out->shared_longest_free_run = ctx->shared.by_len.empty() ? 0 : ctx->shared.by_len.rbegin()->first;
     return HARVEST_OK;
 }
 

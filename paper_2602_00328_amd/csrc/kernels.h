@@ -60,8 +60,13 @@ struct ClassDev {
     uint32_t n_objects, n_planes;
     uint64_t chunk_bytes;
     uint64_t pool[3][2];      // [tier HOST/CACHE/LOCAL][plane] base address as the GPU sees it
-    uint32_t n_slots[3];
+    uint32_t n_slots[3];      // slot numbers a directory entry may carry, per tier
     uint32_t pad;
+    // chunk (layer, slot) of a tier's plane sits at  layer * layer_stride + slot * slot_stride  from the plane's base:
+    // [layer][slot][chunk] pools have (n_slots * chunk, chunk); segments of the shared cache pool, [layer][plane][chunk]
+    // from granule number `slot` on, have (n_planes * chunk, granule)
+    uint64_t layer_stride[3];
+    uint64_t slot_stride[3];
 };
 
 struct GatherArgs {
@@ -78,6 +83,12 @@ __device__ inline uint32_t lane_id() { return __lane_id(); }
 __device__ inline uint32_t slots_of(const ClassDev &c, int tier)
 {
     return tier == T_HOST ? c.n_slots[T_HOST] : (tier == T_CACHE ? c.n_slots[T_CACHE] : c.n_slots[T_LOCAL]);
+}
+__device__ inline uint64_t chunk_offset(const ClassDev &c, int tier, uint32_t layer, uint32_t slot)
+{
+    uint64_t ls = tier == T_HOST ? c.layer_stride[T_HOST] : (tier == T_CACHE ? c.layer_stride[T_CACHE] : c.layer_stride[T_LOCAL]);
+    uint64_t ss = tier == T_HOST ? c.slot_stride[T_HOST] : (tier == T_CACHE ? c.slot_stride[T_CACHE] : c.slot_stride[T_LOCAL]);
+    return (uint64_t)layer * ls + (uint64_t)slot * ss;
 }
 __device__ inline uint64_t src_base_of(const GatherArgs &a, uint32_t tier, uint32_t plane)
 {
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
                 rec.dst = seq_cap_blocks ? first * c.chunk_bytes + (uint64_t)j * strip_bytes : dst_chunk * c.chunk_bytes;
                 if (tier != T_NONE) {
                     if (slot >= slots_of(c, tier)) tier = 4;        // never true for a directory the library wrote
-                    else rec.src = (((uint64_t)layer * slots_of(c, tier) + slot) * c.chunk_bytes) | (uint64_t)tier | (cap << 48);
+                    else rec.src = chunk_offset(c, tier, layer, slot) | (uint64_t)tier | (cap << 48);
                 }
             }
         }
@@ -296,7 +307,7 @@ __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer
                 } else {
                     ptr = staging + (uint64_t)rank * c.chunk_bytes;
                     Rec it;                 // few, large objects: their order in the lists does not matter
-                    it.src = ((uint64_t)slot * c.chunk_bytes) | (uint64_t)tier;
+                    it.src = chunk_offset(c, tier, 0, slot) | (uint64_t)tier;
                     it.dst = (uint64_t)rank * c.chunk_bytes;
                     if (tier == T_CACHE) {
                         hbm_recs[atomicAdd(&s_cnt[C_HBM_REQ], 1u)] = it;

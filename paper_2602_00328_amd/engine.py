@@ -20,15 +20,16 @@ class HipEngine:
     name = "hip"
 
     def __init__(self, kv=None, expert=None, poison=False, device=0, profile=False, gather_wg_per_cu=0, host_wgs=0,
-                 two_streams=False):
-        """two_streams: KV work and expert work are enqueued on two HIP streams of their own (default priority)."""
+                 two_streams=False, shared_cache_bytes=0, shared_granule=0):
+        """two_streams: KV work and expert work are enqueued on two HIP streams of their own (default priority).
+        shared_cache_bytes: one cache pool for every class that has no cache slots of its own."""
         flags = (B.FLAG_POISON if poison else 0) | (B.FLAG_PROFILE if profile else 0)
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
         self.spec = {KV: kv, EXPERT: expert}
         self.streams = {k: (torch.cuda.Stream(self.dev) if two_streams else None) for k in (KV, EXPERT)}
         self.h = B.Harvest(kv=kv, expert=expert, flags=flags, device=device, gather_wg_per_cu=gather_wg_per_cu,
-                           host_wgs=host_wgs)
+                           host_wgs=host_wgs, shared_cache_bytes=shared_cache_bytes, shared_granule=shared_granule)
         self._dst = {}
 
     def _on(self, cls):
@@ -203,4 +204,10 @@ class HipEngine:
         if tier == HOST:
             torch.cuda.synchronize(self.dev)
             return self.h.host_plane(cls, plane)
+        if tier == CACHE and self.spec[cls].n_cache_slots == 0:
+            return np.zeros((self.spec[cls].n_layers, 0, self.spec[cls].chunk_bytes), np.uint8)
         return self.h.dev_plane(cls, tier, plane).cpu().numpy()
+
+    def shared_plane(self):
+        torch.cuda.synchronize(self.dev)
+        return self.h.shared_cache.cpu().numpy()

@@ -7,14 +7,28 @@ from workloads import scenarios as S
 
 
 def make_engines(kv_wl=None, ex_wl=None, poison=False, two_streams=False, kv_layers=None, cache_slack=0,
-                 local_slack=0, hip_kwargs=None, kv_spec=None, ex_spec=None):
+                 local_slack=0, hip_kwargs=None, kv_spec=None, ex_spec=None, shared_cache_bytes=0, shared_granule=0):
+    """shared_cache_bytes > 0: both classes carve their cache tier from one pool of that size (best-fit segments)."""
     from oracle.engine import OracleEngine
     from paper_2602_00328_amd.engine import HipEngine
-    kv = kv_spec or (S.kv_spec(kv_wl, cache_slack, local_slack) if kv_wl is not None else None)
-    ex = ex_spec or (S.expert_spec(ex_wl) if ex_wl is not None else None)
-    eo = OracleEngine(kv=kv, expert=ex, poison=poison, kv_layers=kv_layers)
-    eh = HipEngine(kv=kv, expert=ex, poison=poison, two_streams=two_streams, **(hip_kwargs or {}))
+    shared = shared_cache_bytes > 0
+    kv = kv_spec or (S.kv_spec(kv_wl, cache_slack, local_slack, shared=shared) if kv_wl is not None else None)
+    ex = ex_spec or (S.expert_spec(ex_wl, shared=shared) if ex_wl is not None else None)
+    eo = OracleEngine(kv=kv, expert=ex, poison=poison, kv_layers=kv_layers, shared_cache_bytes=shared_cache_bytes,
+                      shared_granule=shared_granule)
+    eh = HipEngine(kv=kv, expert=ex, poison=poison, two_streams=two_streams, shared_cache_bytes=shared_cache_bytes,
+                   shared_granule=shared_granule, **(hip_kwargs or {}))
     return eo, eh
+
+
+def assert_shared_pools_equal(eo, eh, what=""):
+    a, b = eo.shared_plane(), eh.shared_plane()
+    assert a.shape == b.shape
+    assert np.array_equal(a, b), f"{what}: shared cache pool differs: {first_diff(a, b)}"
+    st = eh.h.stats()
+    runs = eo.shared_free_runs()
+    assert st.shared_free_runs == len(runs) and st.shared_granules_free == sum(l for _, l in runs), what
+    assert st.shared_longest_free_run == max([l for _, l in runs], default=0), what
 
 
 def first_diff(a, b):

@@ -171,3 +171,94 @@ def test_lossy_objects_host_logic():
         h.evict(B.KV, 0, [a], None, None, [0], 4)
     assert e.value.code == B.ELOST
     h.close()
+
+
+# ---- shared cache pool: best-fit segments for both classes (Section 3.3) -----------------------------------------
+
+def test_create_rejects_bad_shared_pools():
+    kv = spec(n_cache=0)
+    for kw in (dict(shared_cache_bytes=4096, shared_granule=100), dict(shared_cache_bytes=4096, shared_granule=128),
+               dict(shared_cache_bytes=4096 + 256, shared_granule=512), dict(shared_cache_bytes=0, shared_granule=512)):
+        with pytest.raises(B.HarvestError) as e:
+            B.Harvest(kv=kv, flags=B.FLAG_NO_DEVICE, **kw)
+        assert e.value.code == B.EINVAL, kw
+    h = B.Harvest(kv=kv, flags=B.FLAG_NO_DEVICE, shared_cache_bytes=8192)        # default granule: 4096
+    st = h.stats()
+    assert (st.shared_granules_free, st.shared_free_runs, st.shared_longest_free_run) == (2, 1, 2)
+    h.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_shared_pool_host_logic_matches_the_oracle_under_random_operations(seed):
+    """KV objects of 3 granules (some of them lossy) and expert objects of 5 compete for 41 granules: every status, every
+    directory entry and the free runs must agree with the oracle after every operation."""
+    G = 256
+    kv = spec(n_layers=3, chunk=128, max_objects=30, n_host=30, n_cache=0, n_local=5)
+    ex = spec(n_layers=1, n_planes=1, chunk=5 * G - 16, max_objects=16, n_host=16, n_cache=0, n_local=0, n_experts=8)
+    h = B.Harvest(kv=kv, expert=ex, flags=B.FLAG_NO_DEVICE, shared_cache_bytes=41 * G, shared_granule=G)
+    pool = O.SegPool(41 * G, G)
+    oc = {B.KV: O.OracleClass(3, 2, 128, 30, 30, 0, 5, segpool=pool),
+          B.EXPERT: O.OracleClass(1, 1, 5 * G - 16, 16, 16, 0, 0, segpool=pool)}
+    g = W.rng(seed, 310)
+    free_host = {B.KV: list(g.permutation(30)), B.EXPERT: list(g.permutation(16))}
+    dummy = np.zeros(3 * 8 * 5 * G, np.uint8)
+    n_enospc = 0
+
+    def both(fo, fh):
+        eo = eh = None
+        try:
+            ro = fo()
+        except O.OracleError as e:
+            ro, eo = None, e.code
+        try:
+            rh = fh()
+        except B.HarvestError as e:
+            rh, eh = None, e.code
+        assert eo == eh, (eo, eh)
+        return ro, rh, eo
+
+    for step in range(260):
+        cls = B.KV if g.random() < 0.6 else B.EXPERT
+        c = oc[cls]
+        n = c.n_objects
+        op = int(g.integers(0, 5))
+        if op == 0 and (free_host[cls] or cls == B.KV):
+            if cls == B.KV and g.random() < 0.35:                            # a lossy block in local HBM
+                ro, rh, _ = both(lambda: c.register(1, None, O.LOCAL), lambda: h.register(cls, 1, None, B.LOCAL))
+            elif free_host[cls]:
+                hs = [int(free_host[cls].pop())]
+                ro, rh, _ = both(lambda: c.register(1, hs, O.HOST), lambda: h.register(cls, 1, hs, B.HOST))
+            else:
+                continue
+            if ro is not None:
+                assert np.array_equal(ro, rh)
+        elif n:
+            ids = np.unique(g.integers(0, n, size=int(g.integers(1, 5)))).astype(np.uint32)
+            g.shuffle(ids)
+            if op in (1, 2):
+                ro, rh, _ = both(lambda: c.place(ids), lambda: h.place(cls, ids))
+                assert np.array_equal(ro, rh)
+                n_enospc += int((ro == O.ENOSPC).sum())
+            elif op == 3:
+                n0, m0 = len(c.revoked_log), len(h.revoked_log)
+                both(lambda: c.revoke(ids), lambda: h.revoke(cls, ids))
+                assert c.revoked_log[n0:] == [i for k, i in h.revoked_log[m0:] if k == cls]
+            else:
+                sb = np.arange(ids.size, dtype=np.uint64)
+                _, _, err = both(lambda: c.evict(-1, ids, dummy, dummy, sb, 8, O.EVICT_DEMOTE),
+                                 lambda: h.evict(cls, -1, ids, None, None, sb, 8, B.EVICT_DEMOTE))
+                n_enospc += err == O.ENOSPC
+        for k in oc:
+            for i in range(oc[k].n_objects):
+                assert oc[k].lookup(i) == h.lookup(k, i), (step, k, i)
+        runs = pool.free_runs()
+        st = h.stats()
+        assert (st.shared_free_runs, st.shared_granules_free) == (len(runs), sum(l for _, l in runs)), step
+        assert st.shared_longest_free_run == max([l for _, l in runs], default=0)
+    assert n_enospc > 0
+    in_cache = {k: sum(1 for i in range(oc[k].n_objects) if oc[k].lookup(i)[0] == O.CACHE) for k in oc}
+    assert [st.cache_slots_in_use[k] for k in (B.KV, B.EXPERT)] == [in_cache[B.KV], in_cache[B.EXPERT]]
+    h.close()
+    for c in oc.values():
+        c.close()
+    pool.close()

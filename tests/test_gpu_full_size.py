@@ -141,3 +141,49 @@ def test_revocation_drains_fetches_that_are_still_queued():
             assert np.array_equal(a[0], want[layer][0]) and np.array_equal(a[1], want[layer][1])
     finally:
         eh.close(); eo.close()
+
+
+def test_shared_cache_pool_real_shapes():
+    """32 KiB KV chunks (2 layers materialised: 128 KiB objects) and 150 MiB experts carved best-fit from one pool that
+    holds 80 % of what the placement draw asks for; a revocation round, other objects into the holes, re-placement."""
+    say("shared cache pool at real shapes")
+    wl = W.kv_decode(seed=0, n_layers=2, n_steps=12)
+    ex = W.expert_offload(seed=0, shape=W.ExpertShape(n_layers=1))
+    kv_obj = 2 * 2 * wl.shape.chunk_bytes
+    demand = int(wl.resident.sum()) * kv_obj + int((ex.tier0 == 1).sum()) * ex.shape.chunk_bytes
+    pool = int(0.8 * demand) // 4096 * 4096
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True, shared_cache_bytes=pool)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        assert np.array_equal(ro.place_status, rh.place_status) and np.array_equal(xo.place_status, xh.place_status)
+        assert (xh.place_status == 0).all() and (rh.place_status != 0).any()
+        for t in range(12):
+            layer = t % 2
+            say(f"  step {t}")
+            ha, hx = rh.fetch_begin(layer), xh.fetch_begin(t, 0)
+            P.assert_kv_equal(ro.fetch(layer), eh.fetch_end(ha), f"shared real kv step {t}")
+            P.assert_experts_equal(xo.fetch(t, 0), eh.fetch_end(hx), f"shared real experts step {t}")
+            if t == 4:
+                a, b = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+                a, b = xo.revoke_quarter(t), xh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+                other = [b for b in range(wl.n_closed)
+                         if eo.lookup(S.KV, b)[0] == S.HOST and b not in ro.pending_replace][:1500]
+                st_o, st_h = eo.place(S.KV, other), eh.place(S.KV, other)      # blocks move into the experts' holes
+                assert np.array_equal(st_o, st_h) and (st_h == 0).sum() > 1000
+                for r in (ro, rh):
+                    r.live |= {int(i) for i, st in zip(other, st_o) if st == 0}
+            if t == 8:
+                st_x = xo.replace_revoked()
+                assert np.array_equal(st_x, xh.replace_revoked()) and np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                say(f"  re-placement statuses of the experts: {list(st_x)}")
+            ro.append(t); rh.append(t)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+        st = eh.h.stats()
+        runs = eo.shared_free_runs()
+        assert st.shared_free_runs == len(runs) and st.shared_granules_free == sum(l for _, l in runs)
+    finally:
+        eh.close(); eo.close()

@@ -296,6 +296,136 @@ def test_head_major_fetch(heads, dim, tokens, elt):
         eh.close(); eo.close()
 
 
+# ---- one cache pool shared by both classes: variable-size segments, best-fit (Section 3.3) ----------------------
+
+def shared_pool_bytes(wl, ex, frac, G):
+    kv_bytes = wl.shape.n_layers * 2 * wl.shape.chunk_bytes
+    demand = int(wl.resident.sum()) * kv_bytes + int((ex.tier0 == 1).sum()) * ex.shape.chunk_bytes
+    return (int(frac * demand) // G) * G
+
+
+@pytest.mark.parametrize("frac,granule", [(0.7, 1024), (1.5, 4096), (0.4, 256)])
+def test_both_classes_share_one_cache_pool(frac, granule):
+    say(f"shared cache pool: {frac} of the demand, granule {granule}")
+    wl = W.kv_decode(seed=21, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=60)
+    sh = W.ExpertShape(n_layers=2, n_experts=16, d_model=96, d_ff=100)
+    ex = W.expert_offload(seed=21, shape=sh, n_tokens=64)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True,
+                            shared_cache_bytes=shared_pool_bytes(wl, ex, frac, granule), shared_granule=granule)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)          # experts first, or the blocks take the whole pool
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        assert np.array_equal(ro.place_status, rh.place_status) and np.array_equal(xo.place_status, xh.place_status)
+        enospc = int((ro.place_status != 0).sum() + (xo.place_status != 0).sum())
+        assert (enospc > 0) == (frac < 1)
+        P.assert_shared_pools_equal(eo, eh, "after the first placements")
+        n_refused, most_runs = 0, 0
+        for t in range(60):
+            layer = t % 2
+            P.assert_kv_equal(ro.fetch(layer), rh.fetch(layer), f"shared kv step {t}")
+            P.assert_experts_equal(xo.fetch(t, layer), xh.fetch(t, layer), f"shared experts step {t}")
+            if t % 10 == 0 and t:
+                a, b = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+                a, b = xo.revoke_quarter(t), xh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+                P.assert_shared_pools_equal(eo, eh, f"after the revocations of step {t}")
+                # other objects move into the holes (experts into the holes blocks left, and so on): the pool fragments
+                other_kv = [b for b in range(wl.n_closed)
+                            if eo.lookup(S.KV, b)[0] == S.HOST and b not in ro.pending_replace][:6]
+                other_ex = [e for e in range(ex.n_objects)
+                            if eo.lookup(S.EXPERT, e)[0] == S.HOST and e not in xo.pending_replace][:3]
+                for cls, ids, runs in ((S.EXPERT, other_ex, (xo, xh)), (S.KV, other_kv, (ro, rh))):
+                    if ids:
+                        st_o, st_h = eo.place(cls, ids), eh.place(cls, ids)
+                        assert np.array_equal(st_o, st_h)
+                        for r in runs:
+                            r.live |= {int(i) for i, st in zip(ids, st_o) if st == 0}
+                most_runs = max(most_runs, len(eo.shared_free_runs()))
+                P.assert_shared_pools_equal(eo, eh, f"after filling the holes of step {t}")
+            if t % 10 == 5:
+                st_x, st_k = xo.replace_revoked(), ro.replace_revoked()
+                assert np.array_equal(st_x, xh.replace_revoked()) and np.array_equal(st_k, rh.replace_revoked())
+                n_refused += int((st_x != 0).sum() + (st_k != 0).sum())
+            ro.append(t); rh.append(t)
+        assert most_runs > 4 and (n_refused > 0) == (frac < 1)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="shared kv")
+        P.assert_tiers_equal(eo, eh, S.EXPERT, 1, what="shared experts")
+        P.assert_shared_pools_equal(eo, eh, "at the end")
+        st = eh.h.stats()
+        assert st.cache_slots_in_use[S.KV] == len(rh.live) and st.cache_slots_in_use[S.EXPERT] == len(xh.live)
+    finally:
+        eh.close(); eo.close()
+
+
+def test_head_major_fetch_from_the_shared_pool():
+    say("head-major from shared segments")
+    shape = W.KVShape(n_layers=3, block_tokens=16, n_kv_heads=4, head_dim=64, elt_bytes=1)
+    wl = W.kv_decode(seed=22, n_seq=3, min_len=300, max_len=900, n_steps=4, shape=shape)
+    n_res = int(wl.resident.sum())
+    G = 512
+    pool = -(-(3 * 2 * shape.chunk_bytes) // G) * G * (n_res - 5)          # five blocks too few
+    eo, eh = P.make_engines(wl, shared_cache_bytes=pool, shared_granule=G)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        assert np.array_equal(ro.place_status, rh.place_status) and (rh.place_status != 0).sum() > 0
+        final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
+        caps = np.array(final, np.uint32)
+        for t in range(4):
+            table, nb = ro.table_arrays()
+            layer = t % 3
+            a = eo.fetch_kv_head_major(layer, table, nb, ro.seq_dst_block, caps, ro.cap, 4, 16, dst_fill=0x5A)
+            b = eh.fetch_kv_head_major(layer, table, nb, rh.seq_dst_block, caps, rh.cap, 4, 16, dst_fill=0x5A)
+            P.assert_kv_equal(a, b, f"head-major shared step {t}")
+            P.assert_kv_equal(ro.fetch(layer), rh.fetch(layer), f"token-major shared step {t}")
+            ro.append(t); rh.append(t)
+        P.assert_shared_pools_equal(eo, eh)
+    finally:
+        eh.close(); eo.close()
+
+
+def test_lossy_objects_demote_into_shared_segments():
+    from types import SimpleNamespace
+    say("lossy objects into shared segments")
+    chunk, G = 4096 + 48, 256
+    spec = SimpleNamespace(n_layers=2, n_planes=2, chunk_bytes=chunk, max_objects=8, n_host_slots=4, n_cache_slots=0,
+                           n_local_slots=4, n_experts=0)
+    obj_g = -(-(2 * 2 * chunk) // G)
+    eo, eh = P.make_engines(kv_spec=spec, poison=True, shared_cache_bytes=(2 * obj_g + 3) * G, shared_granule=G)
+    try:
+        for e in (eo, eh):
+            ids = e.register(S.KV, 3, None, S.LOCAL)
+            assert list(ids) == [0, 1, 2]
+            for obj in range(3):
+                for p in range(2):
+                    for l in range(2):
+                        e.write_local(S.KV, obj, p, l, 0, W.rng(23, obj, p, l).integers(0, 256, size=chunk, dtype=np.uint8))
+        for e in (eo, eh):
+            with pytest.raises(Exception):                   # three segments do not fit: nothing may change
+                e.evict_from_local(S.KV, [0, 1, 2], S.EVICT_DEMOTE)
+            assert e.lookup(S.KV, 0)[:2] == (S.LOCAL, 0)
+        P.assert_shared_pools_equal(eo, eh, "after the refused demotion")
+        for e in (eo, eh):
+            e.evict_from_local(S.KV, [2, 0], S.EVICT_DEMOTE)
+            assert e.lookup(S.KV, 2)[:2] == (S.CACHE, 0) and e.lookup(S.KV, 0)[:2] == (S.CACHE, obj_g)
+        table = np.array([[0, 1, 2]], np.int32)
+        nb, sdb = np.array([3], np.int32), np.array([0], np.uint64)
+        for layer in range(2):
+            P.assert_kv_equal(eo.fetch_kv(layer, table, nb, sdb, 3), eh.fetch_kv(layer, table, nb, sdb, 3), "lossy shared")
+        for e in (eo, eh):
+            e.revoke(S.KV, [2])
+        P.assert_shared_pools_equal(eo, eh, "after revoking a lossy object")
+        a = eo.c[S.KV].fetch_kv(0, table, nb, sdb, 3, dst_k=np.full(3 * chunk, 0xEE, np.uint8),
+                                dst_v=np.full(3 * chunk, 0xEE, np.uint8))
+        b = eh.fetch_kv(0, table, nb, sdb, 3, dst_fill=0xEE)
+        P.assert_kv_equal((a[0], a[1], np.sort(a[2]), a[3]), b, "lossy shared after revocation")
+        assert b[3]["n_lost"] == 1 and (b[0][2 * chunk:] == 0xEE).all()
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- lossy objects ------------------------------------------------------------------------------------------------
 
 def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation():

@@ -121,3 +121,34 @@ def test_revocation_schedule_on_the_oracle():
         out = run.step(t)
         check_kv_tags(wl, run, (out[0], out[1], None, None), 0) if t == 0 else None
     e.close()
+
+
+def test_both_classes_in_one_shared_cache_pool_on_the_oracle():
+    """KV blocks and experts compete for one tight segment pool: some placements fail, revocations fragment it,
+    and every fetched chunk still names its block (Section 3.1: what the cache tier holds changes no result)."""
+    wl = W.kv_decode(seed=6, n_layers=2, n_seq=3, min_len=200, max_len=500, n_steps=40, fill_mode=W.FILL_TAG)
+    ex = W.expert_offload(seed=6, shape=W.ExpertShape(n_layers=2, n_experts=8, d_model=32, d_ff=50), n_tokens=8,
+                          fill_mode=W.FILL_TAG)
+    kv_bytes = 2 * 2 * wl.shape.chunk_bytes
+    demand = int(wl.resident.sum()) * kv_bytes + int((ex.tier0 == 1).sum()) * ex.shape.chunk_bytes
+    G = 1024
+    pool_bytes = (int(0.7 * demand) // G) * G
+    e = OracleEngine(kv=S.kv_spec(wl, shared=True), expert=S.expert_spec(ex, shared=True), poison=True,
+                     shared_cache_bytes=pool_bytes, shared_granule=G)
+    run, xr = S.KVRun(e, wl), S.ExpertRun(e, ex)
+    assert (run.place_status == 0).sum() > 10
+    assert (np.concatenate([run.place_status, xr.place_status]) == -2).any()        # the pool is too small for all
+    for t in range(40):
+        layer = t % 2
+        check_kv_tags(wl, run, run.fetch(layer), layer)
+        st, kind, where, miss, counts = xr.fetch(t, layer)
+        assert counts["n_invalid"] == 0 and counts["n_lost"] == 0
+        if t % 10 == 0 and t:
+            run.revoke_quarter(t); xr.revoke_quarter(t)
+        if t % 10 == 5:
+            xr.replace_revoked(); run.replace_revoked()
+    runs = e.shared_free_runs()
+    used = pool_bytes // G - sum(l for _, l in runs)
+    kv_g, ex_g = -(-kv_bytes // G), -(-ex.shape.chunk_bytes // G)
+    assert used == len(run.live) * kv_g + len(xr.live) * ex_g
+    e.close()

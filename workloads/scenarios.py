@@ -18,20 +18,22 @@ OK, ENOSPC = 0, -2
 EVICT_DEMOTE = 1
 
 
-def kv_spec(wl: KVWorkload, cache_slack: int = 0, local_slack: int = 0):
-    """Pool sizes for a KV workload: a host slot for every block, cache slots for every resident block."""
+def kv_spec(wl: KVWorkload, cache_slack: int = 0, local_slack: int = 0, shared: bool = False):
+    """Pool sizes for a KV workload: a host slot for every block, cache slots for every resident block (none when the
+    cache tier is carved from a pool shared with the other class)."""
     return SimpleNamespace(n_layers=wl.shape.n_layers, n_planes=2, chunk_bytes=wl.shape.chunk_bytes,
                            max_objects=wl.n_objects, n_host_slots=wl.n_objects,
-                           n_cache_slots=int(wl.resident.sum()) + cache_slack,
+                           n_cache_slots=0 if shared else int(wl.resident.sum()) + cache_slack,
                            n_local_slots=(wl.n_seq if wl.has_tails else 0) + local_slack, n_experts=0)
 
 
-def expert_spec(wl: ExpertWorkload):
+def expert_spec(wl: ExpertWorkload, shared: bool = False):
     sh = wl.shape
     n = wl.n_objects
     n_cache = sh.n_layers * wl.lru_capacity if wl.lru_capacity else int((wl.tier0 == 1).sum())
     return SimpleNamespace(n_layers=1, n_planes=1, chunk_bytes=sh.chunk_bytes, max_objects=n, n_host_slots=n,
-                           n_cache_slots=max(1, n_cache), n_local_slots=int((wl.tier0 == 2).sum()), n_experts=sh.n_experts)
+                           n_cache_slots=0 if shared else max(1, n_cache), n_local_slots=int((wl.tier0 == 2).sum()),
+                           n_experts=sh.n_experts)
 
 
 class KVRun:
