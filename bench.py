@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
+    ap.add_argument("--shared-cache", action="store_true",
+                    help="variant: the cache tier is one pool of best-fit segments (an object's layers and planes are "
+                         "contiguous) instead of equal-size slots per layer and plane")
     ap.add_argument("--graph-steps", type=int, default=64,
                     help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
@@ -257,8 +260,10 @@ def main():
     log(f"[bench] workload: {wl.n_seq} sequences, lengths {wl.seq_lens.tolist()}, {n_blocks0} blocks, "
         f"{args.layers} layers materialised, host pool {wl.n_objects * 2 * chunk * args.layers / 2**30:.1f} GiB")
     all_cache_slack = int(wl.n_objects - wl.resident.sum())
-    eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack), profile=True,
-                    host_wgs=args.host_wgs)
+    n_cache_slots = int(wl.resident.sum()) + (0 if args.no_isolation else all_cache_slack)
+    shared_bytes = n_cache_slots * (-(-(2 * chunk * args.layers) // 4096) * 4096) if args.shared_cache else 0
+    eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack, shared=args.shared_cache),
+                    profile=True, host_wgs=args.host_wgs, shared_cache_bytes=shared_bytes)
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
@@ -469,6 +474,7 @@ def main():
                                + ("" if args.kv_elt_bytes == 2 else f" -- VARIANT: {args.kv_elt_bytes}-byte KV elements, "
                                   f"{chunk // 1024} KiB blocks"),
                    "working_layout": "head-major" if args.head_major else "token-major",
+                   "cache_tier": "shared pool of best-fit segments" if args.shared_cache else "equal-size slots",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},
         "objects_per_s": round(d["n_requests"] / sec),
