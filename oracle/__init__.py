@@ -54,6 +54,7 @@ def _bind(path):
     L.orc_n_objects.argtypes = [vp]
     L.orc_register.argtypes = [vp, u32, vp, i32, vp]
     L.orc_lookup.argtypes = [vp, u32, vp, vp, vp, vp]
+    L.orc_restore.argtypes = [vp, vp, u32]
     L.orc_set_object.argtypes = [vp, u32, vp, vp]
     L.orc_adopt.argtypes = [vp, u32]
     L.orc_write_local.argtypes = [vp, u32, u32, u32, u64, vp, u64]
@@ -305,6 +306,13 @@ class OracleClass:
         if rc != OK:
             raise OracleError(rc, "fetch_experts")
         return staging, kind, where, miss[:n_miss.value].copy(), counts.as_dict()
+
+    def restore(self, ids):
+        """Lost objects come back into local HBM (their bytes are then written by the caller)."""
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        rc = self.L.orc_restore(self.h, _p(ids), ids.size)
+        if rc != OK:
+            raise OracleError(rc, "restore")
 
     def evict(self, layer, ids, src_k, src_v, src_block, src_layer_stride, flags=0):
         ids = np.ascontiguousarray(ids, dtype=np.uint32)

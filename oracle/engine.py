@@ -148,6 +148,9 @@ class OracleEngine:
             np.asarray(a, dtype=np.uint8).reshape(self.spec[cls].n_layers, stride, chunk)[layers])
         c.evict(-1, ids, sel(src0), sel(src1), src_block, stride, flags)
 
+    def restore(self, cls, ids):
+        self.c[cls].restore(ids)
+
     def evict_from_local(self, cls, ids, flags=0):
         """Write back local objects, the source being their own local slots (all layers)."""
         c = self.c[cls]

@@ -284,6 +284,32 @@ int orc_register(orc_class *c, uint32_t n, const int64_t *host_slot, int tier, u
     return ORC_OK;
 }
 
+/*
+ * Reconstruction (Section 3.1: a lossy object that was revoked is lost and
+ * the application rebuilds it later; Section 3.2: the callback starts that).
+ * Every listed object must be lost; each gets the lowest free local slot and a
+ * new generation, and the harness then writes the rebuilt bytes there.
+ * All or nothing.
+ */
+int orc_restore(orc_class *c, const uint32_t *ids, uint32_t n)
+{
+    uint32_t free_local = 0;
+    for (uint32_t s = 0; s < c->n_local_slots; ++s) free_local += !c->local_used[s];
+    for (uint32_t i = 0; i < n; ++i) {
+        if (ids[i] >= c->n_objects) return ORC_ENOENT;
+        if (c->tier[ids[i]] != T_NONE) return ORC_EINVAL;
+        for (uint32_t j = 0; j < i; ++j)
+            if (ids[j] == ids[i]) return ORC_EINVAL;
+    }
+    if (free_local < n) return ORC_ENOSPC;
+    for (uint32_t i = 0; i < n; ++i) {
+        int64_t s = lowest_free(c->local_used, c->n_local_slots);
+        c->local_used[s] = 1;
+        c->tier[ids[i]] = T_LOCAL; c->slot[ids[i]] = s; c->gen[ids[i]] += 1;
+    }
+    return ORC_OK;
+}
+
 int orc_lookup(const orc_class *c, uint32_t id, int *tier, int64_t *slot, uint32_t *gen, int64_t *host_slot)
 {
     if (id >= c->n_objects) return ORC_ENOENT;

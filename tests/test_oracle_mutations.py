@@ -73,6 +73,12 @@ MUTATIONS = [
      "uint64_t strip = (uint64_t)nb * block_tokens * head_bytes;"),
     ("duplicate ids accepted by the write-back",
      "if (ids[j] == ids[i]) return ORC_EINVAL;\n    }\n    /* room for", "if (0) return ORC_EINVAL;\n    }\n    /* room for"),
+    ("a restored object keeps its old generation",
+     "c->tier[ids[i]] = T_LOCAL; c->slot[ids[i]] = s; c->gen[ids[i]] += 1;", "c->tier[ids[i]] = T_LOCAL; c->slot[ids[i]] = s;"),
+    ("restore accepts objects that are not lost",
+     "if (c->tier[ids[i]] != T_NONE) return ORC_EINVAL;", ""),
+    ("restore does not claim the local slot it hands out",
+     "c->local_used[s] = 1;\n        c->tier[ids[i]] = T_LOCAL;", "c->tier[ids[i]] = T_LOCAL;"),
     ("first-fit instead of best-fit",
      "(best < 0 || g->run_len[i] < g->run_len[best])", "(best < 0)"),
     ("worst-fit instead of best-fit",
@@ -125,6 +131,7 @@ def battery():
     for heads, bt, hb in ((8, 16, 256), (3, 4, 48), (1, 16, 32), (5, 1, 16)):
         pins.test_head_major_fetch_is_the_transpose_of_the_token_major_fetch(heads, bt, hb)
     pins.test_head_major_fetch_rejects_what_does_not_fit()
+    pins.test_restore_is_all_or_nothing_when_local_hbm_is_full()
     pins.test_best_fit_worked_example()
     for seed in range(5):
         pins.test_best_fit_agrees_with_the_bitmap_definition_on_random_sequences(seed)

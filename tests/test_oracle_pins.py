@@ -481,6 +481,39 @@ def test_lossy_object_is_lost_after_revocation_and_leaves_dst_untouched():
     with pytest.raises(OracleError) as e:
         oc.evict(0, [a], k, v, [0], 3)
     assert e.value.code == O.ELOST
+    # reconstruction: the lost object comes back into the lowest free local slot (a left slot 0 when it was demoted)
+    for bad, code in (([b], O.EINVAL), ([a2], O.EINVAL), ([a, a], O.EINVAL), ([77], O.ENOENT)):
+        with pytest.raises(OracleError) as e:
+            oc.restore(bad)
+        assert e.value.code == code and oc.lookup(a)[:3] == (O.NONE, -1, 2)
+    oc.restore([a])
+    assert oc.lookup(a) == (O.LOCAL, 0, 3, -1)
+    rebuilt = {(p, l): W.rng(16, p, l).integers(0, 256, size=chunk, dtype=np.uint8) for p in range(2) for l in range(2)}
+    for (p, l), row in rebuilt.items():
+        oc.write_local(a, p, l, 0, row)
+    for l in range(2):
+        k, v, miss, counts = oc.fetch_kv(l, table, nb, sdb, 3)
+        kp, vp, _, _ = oc.fetch_kv(l, table, nb, sdb, 3, plain=True)
+        assert np.array_equal(k[:chunk], rebuilt[(0, l)]) and np.array_equal(v[:chunk], rebuilt[(1, l)])
+        assert np.array_equal(k, kp) and np.array_equal(v, vp) and counts["n_lost"] == 0 and counts["n_local"] == 2
+
+
+def test_restore_is_all_or_nothing_when_local_hbm_is_full():
+    oc = OracleClass(1, 1, 16, 6, 1, 4, 2, poison=False)
+    x, y = oc.register(2, None, O.LOCAL)
+    for obj in (x, y):
+        oc.write_local(obj, 0, 0, 0, np.full(16, int(obj) + 1, np.uint8))
+    oc.evict(-1, [x, y], oc.plane(O.LOCAL, 0), None, [0, 1], 2, O.EVICT_DEMOTE)
+    oc.revoke([x, y])
+    z = oc.register(1, None, O.LOCAL)[0]                        # takes local slot 0: one slot left for two lost objects
+    with pytest.raises(OracleError) as e:
+        oc.restore([x, y])
+    assert e.value.code == O.ENOSPC and oc.lookup(x)[0] == O.NONE and oc.lookup(y)[0] == O.NONE
+    oc.restore([y])
+    assert oc.lookup(y)[:3] == (O.LOCAL, 1, 3) and oc.lookup(z)[:2] == (O.LOCAL, 0)
+    with pytest.raises(OracleError) as e:                       # the restored object owns its slot: local HBM is full
+        oc.register(1, None, O.LOCAL)
+    assert e.value.code == O.ENOSPC
 
 
 # ---- random operation sequences: the invariants hold after every step ------------------------------------
