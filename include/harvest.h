@@ -83,7 +83,8 @@ enum harvest_status {
     HARVEST_ENOENT = -3,   /* unknown object / class */
     HARVEST_EHIP = -4,     /* a HIP runtime call failed */
     HARVEST_ELOST = -5,    /* lossy object whose cache copy was revoked (Section 3.1) */
-    HARVEST_ENODEV = -6    /* data-moving call on a context created with HARVEST_FLAG_NO_DEVICE */
+    HARVEST_ENODEV = -6,   /* data-moving call on a context created with HARVEST_FLAG_NO_DEVICE */
+    HARVEST_EBUSY = -7     /* prefetcher: both buffers are in use (issue), or no issued fetch is left (acquire) */
 };
 
 enum harvest_class { HARVEST_KV = 0, HARVEST_EXPERT = 1, HARVEST_N_CLASSES = 2 };
@@ -175,6 +176,14 @@ int harvest_destroy(harvest_ctx *ctx);
 int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_slot, int tier,
                      harvest_revoke_cb cb, void *user, harvest_obj *out_ids);
 
+/* Reconstruction of lost objects (Section 3.1: a lossy object that is revoked is lost and rebuilt later; Section 3.2:
+ * the revocation callback is where the application starts that).  Each listed object must be lost (tier
+ * HARVEST_NONE); it gets the lowest free local slot and a new generation, and the caller then writes the rebuilt
+ * bytes into that slot (see harvest_lookup), as it does after registering a local object.  ids: host pointer.
+ * All-or-nothing: ENOENT (unknown id), EINVAL (an object that is not lost, or a repeated id), ENOSPC (local pool
+ * exhausted).  Synchronous like harvest_register. */
+int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n);
+
 /* Host-side copy of one directory entry.  slot = cache / local slot, or -1.  ENOENT for unknown ids. */
 int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t *slot, uint32_t *gen,
                    int64_t *host_slot);
@@ -226,6 +235,29 @@ int harvest_fetch_kv_head_major(harvest_ctx *ctx, uint32_t layer, const int32_t 
  * NULL.  d_expert_ptr has n_experts entries. */
 int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens, uint32_t k,
                           void *d_staging, uint32_t n_staging_slots, void **d_expert_ptr, void *stream);
+
+/* Double-buffered expert prefetch (Section 4.3: the transfers of expert weights for the next micro-batch overlap the
+ * computation of the current one).  A prefetcher owns a fetch stream (default priority) and borrows two staging
+ * buffers (n_staging_slots * chunk_bytes each, device memory) and two pointer tables (n_experts entries each, device
+ * memory) from the caller; they must outlive it.  The three calls form a ring of two:
+ *   issue   - harvest_fetch_experts for `layer` into the next buffer, on the fetch stream, after (a) the work enqueued
+ *             so far on topk_stream, which produces d_topk_ids, and (b) the release of that buffer's previous use.
+ *             EBUSY when two issued fetches are not released yet.
+ *   acquire - makes compute_stream wait for the oldest fetch not acquired yet and returns its staging buffer and
+ *             pointer table.  EBUSY when every issued fetch has been acquired.
+ *   release - the work enqueued so far on compute_stream is the last use of the oldest acquired buffer.  EINVAL when
+ *             nothing is acquired.
+ * All three only enqueue.  harvest_prefetcher_stream returns the fetch stream (for harvest_fetch_info); destroy waits
+ * for it.  Destroy every prefetcher before its context. */
+typedef struct harvest_prefetcher harvest_prefetcher;
+int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32_t n_staging_slots,
+                              void **const d_expert_ptr[2], harvest_prefetcher **out);
+int harvest_prefetcher_destroy(harvest_prefetcher *pf);
+void *harvest_prefetcher_stream(harvest_prefetcher *pf);
+int harvest_prefetch_issue(harvest_prefetcher *pf, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens,
+                           uint32_t k, void *topk_stream);
+int harvest_prefetch_acquire(harvest_prefetcher *pf, void *compute_stream, void **d_staging, void ***d_expert_ptr);
+int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream);
 
 /* Synchronises `stream` and reports the last fetch enqueued on it: its counts and its miss list (requests served
  * from host or lost: KV request numbers r, or expert numbers e; order unspecified).  miss_idx may be NULL; at most

@@ -19,7 +19,7 @@ import torch  # noqa: F401  - must be imported BEFORE the library is loaded: PyT
 from . import _build
 
 HOST, CACHE, LOCAL, NONE = 0, 1, 2, 3
-OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV, EBUSY = 0, -1, -2, -3, -4, -5, -6, -7
 KV, EXPERT = 0, 1
 FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE = 1, 2, 4
 EVICT_DEMOTE = 1
@@ -65,11 +65,18 @@ SYMBOLS = {
     "harvest_destroy": (ctypes.c_int, [vp]),
     "harvest_register": (ctypes.c_int, [vp, ctypes.c_int, u32, vp, ctypes.c_int, REVOKE_CB, vp, vp]),
     "harvest_lookup": (ctypes.c_int, [vp, ctypes.c_int, u32, vp, vp, vp, vp]),
+    "harvest_restore": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
     "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
     "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
     "harvest_fetch_experts": (ctypes.c_int, [vp, u32, vp, u32, u32, vp, u32, vp, vp]),
+    "harvest_prefetcher_create": (ctypes.c_int, [vp, vp * 2, u32, vp * 2, ctypes.POINTER(vp)]),
+    "harvest_prefetcher_destroy": (ctypes.c_int, [vp]),
+    "harvest_prefetcher_stream": (vp, [vp]),
+    "harvest_prefetch_issue": (ctypes.c_int, [vp, u32, vp, u32, u32, vp]),
+    "harvest_prefetch_acquire": (ctypes.c_int, [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]),
+    "harvest_prefetch_release": (ctypes.c_int, [vp, vp]),
     "harvest_fetch_info": (ctypes.c_int, [vp, vp, ctypes.POINTER(harvest_fetch_counts), vp, u32, vp]),
     "harvest_evict": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, vp, u32, vp, vp, vp, u64, ctypes.c_int, vp]),
     "harvest_stats": (ctypes.c_int, [vp, ctypes.POINTER(harvest_stats_t)]),
@@ -233,6 +240,10 @@ class Harvest:
                                 ctypes.byref(hs)), "harvest_lookup")
         return t.value, s.value, g.value, hs.value
 
+    def restore(self, cls, ids):
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        _chk(lib.harvest_restore(self.h, cls, _np_ptr(ids), ids.size), "harvest_restore")
+
     def place(self, cls, ids, stream=None) -> np.ndarray:
         ids = np.ascontiguousarray(ids, dtype=np.uint32)
         st = np.zeros(ids.size, dtype=np.int32)
@@ -294,6 +305,59 @@ class Harvest:
         out = harvest_profile_t()
         _chk(lib.harvest_profile(self.h, ctypes.byref(out)), "harvest_profile")
         return out
+
+
+class Prefetcher:
+    """harvest_prefetcher_*: a ring of two staging buffers filled on the library's fetch stream while the caller's
+    compute stream uses the other one.  The buffers (torch tensors) are allocated here and lent to the library."""
+
+    def __init__(self, h: Harvest, n_staging_slots: int):
+        sp = h.spec[EXPERT]
+        dev = torch.device("cuda", h.device)
+        self.h = h
+        self.staging = [torch.empty(max(1, n_staging_slots) * sp.chunk_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+        self.ptrs = [torch.zeros(sp.n_experts, dtype=torch.int64, device=dev) for _ in range(2)]
+        self.n_staging_slots = n_staging_slots
+        st = (vp * 2)(self.staging[0].data_ptr(), self.staging[1].data_ptr())
+        pt = (vp * 2)(self.ptrs[0].data_ptr(), self.ptrs[1].data_ptr())
+        pf = vp()
+        _chk(lib.harvest_prefetcher_create(h.h, st, n_staging_slots, pt, ctypes.byref(pf)), "harvest_prefetcher_create")
+        self.pf = pf
+
+    def close(self):
+        if getattr(self, "pf", None):
+            _chk(lib.harvest_prefetcher_destroy(self.pf), "harvest_prefetcher_destroy")
+            self.pf = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def stream(self) -> int:
+        return int(lib.harvest_prefetcher_stream(self.pf) or 0)
+
+    def issue(self, layer, d_topk, topk_stream=None):
+        n_tokens, k = d_topk.shape
+        _chk(lib.harvest_prefetch_issue(self.pf, layer, _dev_ptr(d_topk), n_tokens, k, _stream_ptr(topk_stream)),
+             "harvest_prefetch_issue")
+
+    def acquire(self, compute_stream=None):
+        """-> (staging tensor, pointer-table tensor) of the oldest issued fetch; compute_stream waits for it."""
+        st, pt = vp(), vp()
+        _chk(lib.harvest_prefetch_acquire(self.pf, _stream_ptr(compute_stream), ctypes.byref(st), ctypes.byref(pt)),
+             "harvest_prefetch_acquire")
+        b = 0 if st.value == self.staging[0].data_ptr() else 1
+        assert st.value == self.staging[b].data_ptr() and pt.value == self.ptrs[b].data_ptr()
+        return self.staging[b], self.ptrs[b]
+
+    def release(self, compute_stream=None):
+        _chk(lib.harvest_prefetch_release(self.pf, _stream_ptr(compute_stream)), "harvest_prefetch_release")
+
+    def fetch_info(self, miss_cap=0):
+        return self.h.fetch_info(stream=self.stream, miss_cap=miss_cap)
 
 
 def plain_copy(d_dst, d_src, nbytes, stream=None):

@@ -197,6 +197,19 @@ struct harvest_ctx {
     std::mutex mu;
 };
 
+struct harvest_prefetcher {
+    harvest_ctx *ctx = nullptr;
+    hipStream_t fetch = nullptr;                 // library-owned, default priority
+    void *staging[2] = { nullptr, nullptr };
+    void **ptrs[2] = { nullptr, nullptr };
+    uint32_t n_slots = 0;
+    hipEvent_t ready[2] = { nullptr, nullptr };  // the fetch into buffer b has finished
+    hipEvent_t freed[2] = { nullptr, nullptr };  // the consumer of buffer b has finished
+    hipEvent_t dep = nullptr;                    // the routing ids of the next fetch exist
+    bool freed_valid[2] = { false, false };
+    uint64_t n_issued = 0, n_acquired = 0, n_released = 0;
+};
+
 namespace {
 
 int device_guard(harvest_ctx *ctx)
@@ -480,6 +493,17 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     return mark_last(ctx, ss);
 }
 
+// Releases what a caller stream's state owns; the stream's work must have finished.
+void free_stream_state(StreamState *ss)
+{
+    (void)hipStreamDestroy(ss->side);
+    for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
+    (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
+    (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
+    (void)hipFree(ss->ctl_buf);
+    (void)hipHostFree(ss->h_feedback);
+}
+
 int check_class(harvest_ctx *ctx, int cls)
 {
     if (!ctx) return HARVEST_EINVAL;
@@ -535,6 +559,7 @@ const char *harvest_strerror(int status)
     case HARVEST_EHIP: return "HIP runtime error";
     case HARVEST_ELOST: return "lossy object was revoked";
     case HARVEST_ENODEV: return "context has no device";
+    case HARVEST_EBUSY: return "both prefetch buffers are in use, or none is ready";
     }
     return "unknown status";
 }
@@ -636,15 +661,7 @@ int harvest_destroy(harvest_ctx *ctx)
             (void)hipStreamSynchronize(ss->side);
         }
         (void)hipStreamSynchronize(ctx->ctl);
-        for (auto &kv : ctx->streams) {
-            StreamState *ss = kv.second.get();
-            (void)hipStreamDestroy(ss->side);
-            for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
-            (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
-            (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
-            (void)hipFree(ss->ctl_buf);
-            (void)hipHostFree(ss->h_feedback);
-        }
+        for (auto &kv : ctx->streams) free_stream_state(kv.second.get());
         for (auto &st : ctx->staging) { (void)hipEventDestroy(st.done); (void)hipHostFree(st.h); }
         for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
@@ -694,6 +711,32 @@ int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_
     if ((rc = publish(ctx, c, ids, nullptr))) return rc;
     // Later fetches are ordered after this edit on their own streams; only replays of recorded graphs, which the library
     // does not see, need the entry to be there before this call returns.
+    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
+    return HARVEST_OK;
+}
+
+int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    if (n && !ids) return HARVEST_EINVAL;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    std::unordered_set<uint32_t> seen;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+        if (c.tier[ids[i]] != T_NONE || !seen.insert(ids[i]).second) return HARVEST_EINVAL;
+    }
+    if (c.local_free.size() < n) return HARVEST_ENOSPC;
+    if ((rc = device_guard(ctx))) return rc;
+    std::vector<uint32_t> changed(ids, ids + n);
+    for (uint32_t id : changed) {
+        c.slot[id] = *c.local_free.begin();
+        c.local_free.erase(c.local_free.begin());
+        c.tier[id] = T_LOCAL;
+        c.gen[id] += 1;
+    }
+    if ((rc = publish(ctx, c, changed, nullptr))) return rc;
     if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
     return HARVEST_OK;
 }
@@ -917,6 +960,107 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_EXPERT, cnt, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
+}
+
+int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32_t n_staging_slots,
+                              void **const d_expert_ptr[2], harvest_prefetcher **out)
+{
+    if (!out) return HARVEST_EINVAL;
+    *out = nullptr;
+    int rc = check_class(ctx, HARVEST_EXPERT);
+    if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    if (!d_staging || !d_expert_ptr) return HARVEST_EINVAL;
+    for (int b = 0; b < 2; ++b) {
+        if (!d_expert_ptr[b] || (n_staging_slots && (!d_staging[b] || ((uint64_t)d_staging[b] & 15)))) return HARVEST_EINVAL;
+    }
+    if (d_staging[0] == d_staging[1] && n_staging_slots) return HARVEST_EINVAL;
+    if (d_expert_ptr[0] == d_expert_ptr[1]) return HARVEST_EINVAL;
+    if ((rc = device_guard(ctx))) return rc;
+    auto pf = std::make_unique<harvest_prefetcher>();
+    pf->ctx = ctx;
+    pf->n_slots = n_staging_slots;
+    for (int b = 0; b < 2; ++b) { pf->staging[b] = d_staging[b]; pf->ptrs[b] = d_expert_ptr[b]; }
+    auto fail = [&](void) {
+        for (hipEvent_t e : { pf->ready[0], pf->ready[1], pf->freed[0], pf->freed[1], pf->dep }) if (e) (void)hipEventDestroy(e);
+        if (pf->fetch) (void)hipStreamDestroy(pf->fetch);
+        return HARVEST_EHIP;
+    };
+    if (hipStreamCreateWithFlags(&pf->fetch, hipStreamNonBlocking) != hipSuccess) return fail();
+    for (hipEvent_t *e : { &pf->ready[0], &pf->ready[1], &pf->freed[0], &pf->freed[1], &pf->dep })
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return fail();
+    *out = pf.release();
+    return HARVEST_OK;
+}
+
+int harvest_prefetcher_destroy(harvest_prefetcher *pf)
+{
+    if (!pf) return HARVEST_OK;
+    harvest_ctx *ctx = pf->ctx;
+    int rc = device_guard(ctx);
+    if (rc) return rc;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        (void)hipStreamSynchronize(pf->fetch);
+        auto it = ctx->streams.find(pf->fetch);
+        if (it != ctx->streams.end()) {
+            (void)hipStreamSynchronize(it->second->side);
+            free_stream_state(it->second.get());
+            ctx->streams.erase(it);
+        }
+    }
+    for (hipEvent_t e : { pf->ready[0], pf->ready[1], pf->freed[0], pf->freed[1], pf->dep }) (void)hipEventDestroy(e);
+    (void)hipStreamDestroy(pf->fetch);
+    delete pf;
+    return HARVEST_OK;
+}
+
+void *harvest_prefetcher_stream(harvest_prefetcher *pf) { return pf ? (void *)pf->fetch : nullptr; }
+
+int harvest_prefetch_issue(harvest_prefetcher *pf, uint32_t layer, const int32_t *d_topk_ids, uint32_t n_tokens,
+                           uint32_t k, void *topk_stream)
+{
+    if (!pf) return HARVEST_EINVAL;
+    if (pf->n_issued - pf->n_released >= 2) return HARVEST_EBUSY;
+    int rc = device_guard(pf->ctx);
+    if (rc) return rc;
+    int b = (int)(pf->n_issued & 1);
+    // the fetch starts once the routing ids exist and the last consumer of this buffer is done with it
+    HIP_TRY(hipEventRecord(pf->dep, (hipStream_t)topk_stream));
+    HIP_TRY(hipStreamWaitEvent(pf->fetch, pf->dep, 0));
+    if (pf->freed_valid[b]) HIP_TRY(hipStreamWaitEvent(pf->fetch, pf->freed[b], 0));
+    rc = harvest_fetch_experts(pf->ctx, layer, d_topk_ids, n_tokens, k, pf->staging[b], pf->n_slots, pf->ptrs[b], pf->fetch);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(pf->ready[b], pf->fetch));
+    pf->n_issued++;
+    return HARVEST_OK;
+}
+
+int harvest_prefetch_acquire(harvest_prefetcher *pf, void *compute_stream, void **d_staging, void ***d_expert_ptr)
+{
+    if (!pf) return HARVEST_EINVAL;
+    if (pf->n_acquired >= pf->n_issued) return HARVEST_EBUSY;
+    int rc = device_guard(pf->ctx);
+    if (rc) return rc;
+    int b = (int)(pf->n_acquired & 1);
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)compute_stream, pf->ready[b], 0));
+    if (d_staging) *d_staging = pf->staging[b];
+    if (d_expert_ptr) *d_expert_ptr = pf->ptrs[b];
+    pf->n_acquired++;
+    return HARVEST_OK;
+}
+
+int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream)
+{
+    if (!pf) return HARVEST_EINVAL;
+    if (pf->n_released >= pf->n_acquired) return HARVEST_EINVAL;
+    int rc = device_guard(pf->ctx);
+    if (rc) return rc;
+    int b = (int)(pf->n_released & 1);
+    HIP_TRY(hipEventRecord(pf->freed[b], (hipStream_t)compute_stream));
+    pf->freed_valid[b] = true;
+    pf->n_released++;
+    return HARVEST_OK;
 }
 
 int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,

@@ -78,6 +78,9 @@ class HipEngine:
     def lookup(self, cls, obj):
         return self.h.lookup(cls, obj)
 
+    def restore(self, cls, ids):
+        self.h.restore(cls, ids)
+
     def place(self, cls, ids):
         with self._on(cls):
             return self.h.place(cls, ids)

@@ -141,6 +141,11 @@ def test_host_logic_matches_the_oracle_directory_under_random_operations(seed):
                 sb = g.integers(0, 8 + (1 if g.random() < 0.05 else 0), size=ids.size).astype(np.uint64)
                 both(lambda: oc.evict(layer, ids, dummy, dummy, sb, 8, flags),
                      lambda: h.evict(B.KV, layer, ids, None, None, sb, 8, flags))
+            elif g.random() < 0.7:
+                both(lambda: oc.restore(ids[:2]), lambda: h.restore(B.KV, ids[:2]))       # mostly EINVAL: rarely all lost
+                lost = [i for i in range(n) if oc.lookup(i)[0] == O.NONE][:2]
+                if lost:
+                    both(lambda: oc.restore(lost), lambda: h.restore(B.KV, lost))
             else:
                 bad = int(n + 3)
                 both(lambda: oc.lookup(bad), lambda: h.lookup(B.KV, bad))

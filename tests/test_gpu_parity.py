@@ -463,6 +463,19 @@ def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation():
         P.assert_kv_equal((a[0], a[1], np.sort(a[2]), a[3]), b, "after revocation")
         assert b[3]["n_lost"] == 1 and (b[0][:chunk] == 0xEE).all() and list(b[2]) == [0, 1, 4]
         P.assert_tiers_equal(eo, eh, S.KV, 2, what="lossy")
+        # reconstruction: the lost block returns to local HBM, is rebuilt there and served again
+        for e in (eo, eh):
+            e.restore(S.KV, [0])
+            for p in range(2):
+                for l in range(2):
+                    e.write_local(S.KV, 0, p, l, 0, W.chunk(10, W.CLS_APPEND, p, l, 0, chunk, W.FILL_TAG))
+        P.assert_dirs_equal(eo, eh, S.KV, 5)
+        assert eh.lookup(S.KV, 0)[0] == S.LOCAL
+        for layer in range(2):
+            a, b = eo.fetch_kv(layer, table, nb, sdb, 5), eh.fetch_kv(layer, table, nb, sdb, 5)
+            P.assert_kv_equal(a, b, f"rebuilt {layer}")
+            assert b[3]["n_lost"] == 0 and W.check_tag(b[0][:chunk], 10, W.CLS_APPEND, 0, layer, 0)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="rebuilt")
     finally:
         eh.close(); eo.close()
 
