@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--shared-cache", action="store_true",
                     help="variant: the cache tier is one pool of best-fit segments (an object's layers and planes are "
                          "contiguous) instead of equal-size slots per layer and plane")
+    ap.add_argument("--prefetch", action="store_true",
+                    help="experts_phi only: also time the double-buffered prefetch ring against fetch-then-use")
     ap.add_argument("--graph-steps", type=int, default=64,
                     help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
@@ -229,8 +231,67 @@ def bench_experts(args):
     }
     log(f"[bench] {args.steps} steps in {sec:.3f}s: {out['ms_per_step']} ms/step; HBM tier {hbm_gbs:.0f} GB/s, host tier "
         f"{host_gbs:.1f} GB/s; per step {out['served_per_step']}, placed {out['placed_per_step']}")
+    if args.prefetch and not wl.lru_capacity:
+        out["prefetch"] = bench_prefetch(eng, wl, topk, staging, ptrs, L, E, sp.chunk_bytes, sec / (args.steps * L),
+                                         range(args.warmup, n_total))
     eng.close()
     print(json.dumps(out), flush=True)
+
+
+def bench_prefetch(eng, wl, topk, staging, ptrs, L, E, chunk, fetch_s_per_layer, steps):
+    """Fetch-then-use on one stream against the prefetch ring (layer l+1 fetched while layer l is in use).  The stand-in
+    for the FFN is a reader of the staging buffer (harvest_plain_copy into a sink), repeated so that one layer's use
+    takes about 0.8 of one layer's fetch - the regime in which overlapping matters."""
+    import torch
+    from paper_2602_00328_amd import binding as B
+    sink = torch.empty_like(staging)
+    nbytes = staging.numel()
+
+    def use(buf, passes):
+        for _ in range(passes):
+            B.plain_copy(sink, buf, nbytes)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - a
+
+    one_pass = timed(lambda: use(staging, 8)) / 8
+    passes = max(1, round(0.8 * fetch_s_per_layer / one_pass))
+    work = [(t, l) for t in steps for l in range(L)]
+
+    def use_only():
+        for _ in work:
+            use(staging, passes)
+
+    def serial():
+        for w in work:
+            eng.h.fetch_experts(w[1], topk[w], staging, E, ptrs)
+            use(staging, passes)
+
+    pf = B.Prefetcher(eng.h, E)
+
+    def pipelined():
+        pf.issue(work[0][1], topk[work[0]])
+        for i, w in enumerate(work):
+            if i + 1 < len(work):
+                pf.issue(work[i + 1][1], topk[work[i + 1]])
+            buf, _ = pf.acquire()
+            use(buf, passes)
+            pf.release()
+
+    pipelined()                                           # warm-up: scratch of the fetch stream
+    n = len(work)
+    t_use, t_serial, t_pipe = timed(use_only) / n, timed(serial) / n, timed(pipelined) / n
+    pf.close()
+    res = {"use": f"{passes} read passes over the staging buffer ({nbytes / 2**30:.2f} GiB each)",
+           "fetch_only_ms_per_layer": round(fetch_s_per_layer * 1e3, 3), "use_only_ms_per_layer": round(t_use * 1e3, 3),
+           "fetch_then_use_ms_per_layer": round(t_serial * 1e3, 3), "prefetch_ring_ms_per_layer": round(t_pipe * 1e3, 3),
+           "ring_over_longer_leg": round(t_pipe / max(fetch_s_per_layer, t_use), 4)}
+    log(f"[bench] prefetch: {res}")
+    return res
 
 
 def main():
