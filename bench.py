@@ -355,8 +355,17 @@ def main():
         torch.cuda.synchronize()
         ts.append(time.perf_counter() - a)
     pcie_peak_gbs = (1 << 30) / float(np.median(ts[1:])) / 1e9
+    ts = []
+    for _ in range(6):                                   # and device -> pinned host, for the write-back path
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        pin.copy_(dbuf, non_blocking=True)
+        torch.cuda.synchronize()
+        ts.append(time.perf_counter() - a)
+    d2h_peak_gbs = (1 << 30) / float(np.median(ts[1:])) / 1e9
     del pin, dbuf
-    log(f"[bench] plain copy {plain_gbs:.0f} GB/s read+write; PCIe H2D DMA peak {pcie_peak_gbs:.1f} GB/s")
+    log(f"[bench] plain copy {plain_gbs:.0f} GB/s read+write; PCIe DMA peak {pcie_peak_gbs:.1f} GB/s to the device, "
+        f"{d2h_peak_gbs:.1f} GB/s to the host")
 
     # ---- warm-up, then the timed region ----
     for _ in range(args.warmup):
@@ -465,8 +474,9 @@ def main():
         dt = time.perf_counter() - a
         assert (st == 0).all()
         obj_bytes = 2 * chunk * sh.n_layers
-        write_paths["place"] = {"objects": len(host_only), "gbs_over_pcie": round(len(host_only) * obj_bytes / dt / 1e9, 2),
-                                "ms": round(dt * 1e3, 2)}
+        g = len(host_only) * obj_bytes / dt / 1e9
+        write_paths["place"] = {"objects": len(host_only), "gbs_over_pcie": round(g, 2), "ms": round(dt * 1e3, 2),
+                                "frac_of_pcie_peak": round(g / pcie_peak_gbs, 4)}
         # write-back of one layer of the longest sequence: fetch it, hand the same bytes back (state stays unchanged)
         s_long = int(np.argmax([len(t) for t in run.tables]))
         ev_ids = np.array(run.tables[s_long][:-1], dtype=np.uint32)
@@ -477,8 +487,10 @@ def main():
                     run.cap, 0)
         torch.cuda.synchronize()
         dt = time.perf_counter() - a
-        write_paths["evict"] = {"objects": int(ev_ids.size), "gbs_to_host": round(ev_ids.size * 2 * chunk / dt / 1e9, 2),
-                                "ms": round(dt * 1e3, 2), "note": "each block is written to its host slot and its cache slot"}
+        g = ev_ids.size * 2 * chunk / dt / 1e9
+        write_paths["evict"] = {"objects": int(ev_ids.size), "gbs_to_host": round(g, 2), "ms": round(dt * 1e3, 2),
+                                "frac_of_pcie_peak_to_host": round(g / d2h_peak_gbs, 4),
+                                "note": "each block is written to its host slot and its cache slot"}
         log(f"[bench] write paths: {write_paths}")
         for name, n_it in (("all_cache", args.iso_steps), ("all_host", max(2, args.iso_steps // 4))):
             if name == "all_host":
