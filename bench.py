@@ -558,7 +558,7 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
                      "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1)},
-        "host_tier": {"bound": "pcie", "kernel": "gather_host (host-tier gather, zero-copy over PCIe)",
+        "host_tier": {"bound": "pcie", "kernel": ("gather_hm<8,false,true>" if args.head_major else "gather_host") + " (host-tier gather, zero-copy over PCIe)",
                       "achieved": round(host_gbs, 2), "peak": round(pcie_peak_gbs, 2), "unit": "GB/s",
                       "frac": round(host_gbs / pcie_peak_gbs, 4), "launches": int(pr.host_launches),
                       "avg_launch_ms": round(host_ms, 5), "bytes_per_launch": round(host_bytes),
