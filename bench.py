@@ -171,7 +171,10 @@ def bench_experts(args):
     else:
         wl = W.expert_lru(seed=args.seed, shape=W.ExpertShape(n_layers=L, n_experts=60, d_model=2048, d_ff=1408))
     t0 = time.time()
-    eng = HipEngine(expert=S.expert_spec(wl), profile=True, host_wgs=args.host_wgs)
+    spec = S.expert_spec(wl)
+    if not args.no_isolation:
+        spec.n_cache_slots = wl.n_objects              # room for the all-cache isolation point
+    eng = HipEngine(expert=spec, profile=True, host_wgs=args.host_wgs)
     run = S.ExpertRun(eng, wl)
     torch.cuda.synchronize()
     sp = eng.spec[1]
@@ -231,6 +234,39 @@ def bench_experts(args):
     }
     log(f"[bench] {args.steps} steps in {sec:.3f}s: {out['ms_per_step']} ms/step; HBM tier {hbm_gbs:.0f} GB/s, host tier "
         f"{host_gbs:.1f} GB/s; per step {out['served_per_step']}, placed {out['placed_per_step']}")
+    if not args.no_isolation:
+        # ---- isolation points: the same routing with every non-local expert in the cache tier, then on the host ----
+        iso = {}
+        everything = [i for i in range(wl.n_objects) if eng.lookup(1, i)[0] != 2]
+        for name in ("all_cache", "all_host"):
+            if name == "all_cache":
+                st_all = eng.place(1, everything)
+                assert (st_all == 0).all()
+            else:
+                eng.revoke(1, everything)
+            torch.cuda.synchronize()
+            eng.h.profile()
+            s0 = eng.h.stats()
+            a = time.perf_counter()
+            for l in range(L):
+                eng.h.fetch_experts(l, topk[(args.warmup, l)], staging, E, ptrs)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - a
+            p, s1 = eng.h.profile(), eng.h.stats()
+            n_c = int(s1.fetch[1].n_cache) - int(s0.fetch[1].n_cache)
+            n_h = int(s1.fetch[1].n_host) - int(s0.fetch[1].n_host)
+            if name == "all_cache":
+                g = 2 * n_c * chunk / (p.hbm_ms * 1e-3) / 1e9
+                iso[name] = {"experts": n_c, "ms_per_layer": round(dt * 1e3 / L, 3), "kernel_ms_per_layer": round(p.hbm_ms / L, 3),
+                             "hbm_gbs_read_write": round(g, 1), "frac_of_hbm_peak": round(g / HBM_PEAK_GBS, 4)}
+            else:
+                g = n_h * chunk / (p.host_ms * 1e-3) / 1e9
+                iso[name] = {"experts": n_h, "ms_per_layer": round(dt * 1e3 / L, 3), "kernel_ms_per_layer": round(p.host_ms / L, 3),
+                             "pcie_gbs": round(g, 2)}
+            log(f"[bench] isolation {name}: {iso[name]}")
+        out["isolation"] = iso
+        if not wl.lru_capacity:                          # back to the configured residency for the prefetch leg
+            eng.place(1, [int(i) for i in wl.place_order])
     if args.prefetch and not wl.lru_capacity:
         out["prefetch"] = bench_prefetch(eng, wl, topk, staging, ptrs, L, E, sp.chunk_bytes, sec / (args.steps * L),
                                          range(args.warmup, n_total))

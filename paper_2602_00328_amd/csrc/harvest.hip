@@ -434,24 +434,34 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
     bool host_tier = c.cfg.n_host_slots != 0;
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
-        ga.tiles_per_chunk = tpc_host;
+        // chunks that are whole 32 KiB tiles take the tile kernels; other sizes the kernels that batch 4 KiB sub-tiles
+        // across requests.  With profiling on, the events are attached to the dispatch itself and read the kernel's
+        // own begin and end.
+        const bool whole_tiles = c.cfg.chunk_bytes % TILE_HOST == 0;
+        ga.tiles_per_chunk = whole_tiles ? tpc_host : tpc_hbm;
         ga.n_planes = planes;
-        // with profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end
+        const Rec *recs = (const Rec *)ss->host_recs;
+        const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
         if (hm) {
             dim3 g(std::max(1u, ctx->host_grid / planes), planes);
-            if (pc)
-                hipExtLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, pc, pd, 0,
-                                      (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga, *hm,
-                                      (uint32_t *)nullptr);
+            if (whole_tiles) {
+                if (pc)
+                    hipExtLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, pc, pd, 0, recs,
+                                          n_req, ga, *hm, (uint32_t *)nullptr);
+                else
+                    hipLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm,
+                                       (uint32_t *)nullptr);
+            } else if (pc)
+                hipExtLaunchKernelGGL(gather_hm_host_batches, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
             else
-                hipLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
-                                   (const uint32_t *)(cnt + C_HOST_REQ), ga, *hm, (uint32_t *)nullptr);
-        } else if (pc)
-            hipExtLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0,
-                                  (const Rec *)ss->host_recs, (const uint32_t *)(cnt + C_HOST_REQ), ga);
-        else
-            hipLaunchKernelGGL(gather_host, dim3(ctx->host_grid), dim3(WG), 0, ss->side, (const Rec *)ss->host_recs,
-                               (const uint32_t *)(cnt + C_HOST_REQ), ga);
+                hipLaunchKernelGGL(gather_hm_host_batches, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
+        } else {
+            auto kernel = whole_tiles ? gather_host : (planes == 2 ? gather_host_batches<2> : gather_host_batches<1>);
+            if (pc)
+                hipExtLaunchKernelGGL(kernel, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
+            else
+                hipLaunchKernelGGL(kernel, dim3(ctx->host_grid), dim3(WG), 0, ss->side, recs, n_req, ga);
+        }
         HIP_TRY(hipGetLastError());
     }
     // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the

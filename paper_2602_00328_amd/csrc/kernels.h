@@ -496,6 +496,9 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
 // Host tier: the same request list format, read over PCIe from pinned host memory by a few persistent workgroups.
 // Both planes of a tile are loaded before either is stored, so a two-plane class keeps 16 x 16 bytes in flight per
 // thread: the link needs bytes in flight, not workgroups, and every workgroup spared leaves the HBM tier alone.
+// This kernel walks 32 KiB tiles inside a chunk and is the one launched for chunk sizes that are whole tiles (32 KiB KV
+// blocks, experts); a chunk that ends inside a tile would leave that tile's loads half empty - gather_host_batches
+// below serves those sizes.
 __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
                                                   GatherArgs a)
 {
@@ -528,6 +531,100 @@ __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, 
             for (uint32_t p = 0; p < a.n_planes; ++p)
                 copy_tile<U, false>(src_base_of(a, tier, p) + so, (p ? a.dst_base[1] : a.dst_base[0]) + x.dst + off, len,
                                     tid);
+        }
+    }
+}
+
+// Host tier for chunk sizes that are not whole 32 KiB tiles (16 KiB blocks of an fp8 KV cache, ragged sizes).  Work is
+// cut into 4 KiB sub-tiles numbered through the whole list (request * sub-tiles per chunk + position); a workgroup takes
+// UNROLL_HOST consecutive ones at a time, across request boundaries, and loads all of them (for both planes) before it
+// stores any, so the bytes in flight per thread do not depend on the chunk size.  Each load is issued as soon as its list
+// entry has arrived - computing all addresses first leaves the link idle meanwhile and costs a fifth of the rate.  Lanes
+// beyond a chunk's end re-read the chunk's first bytes and store nothing: loads stay free of branches.
+struct HostSub {
+    uint64_t src;      // offset of this lane's 16 bytes inside the tier's plane pool
+    uint64_t dst;      // offset of the chunk inside the destination plane (head-major: of the sequence's region)
+    uint32_t tier;
+    uint32_t unit;     // this lane's 16-byte unit inside the chunk (0 when inactive)
+    uint64_t cap;      // head-major only: the sequence's capacity in blocks
+    bool act;
+};
+
+__device__ inline HostSub host_sub(const Rec *__restrict__ recs, uint64_t g, uint64_t n_sub, uint32_t spc,
+                                   uint32_t chunk_units, uint32_t tid)
+{
+    HostSub r;
+    bool valid = g < n_sub;
+    uint32_t idx = valid ? (uint32_t)g / spc : 0;             // a batch exists only when the list is not empty
+    Rec x = recs[idx];
+    uint32_t j = valid ? (uint32_t)g - idx * spc : 0;
+    uint32_t u = j * WG + tid;
+    r.act = valid && u < chunk_units;
+    r.unit = r.act ? u : 0;
+    r.src = (x.src & 0x0000FFFFFFFFFFFCull) + (uint64_t)r.unit * 16;
+    r.dst = x.dst;
+    r.tier = (uint32_t)(x.src & 3);
+    r.cap = x.src >> 48;
+    return r;
+}
+
+template <int PLANES>
+__global__ __launch_bounds__(WG) void gather_host_batches(const Rec *__restrict__ recs,
+                                                          const uint32_t *__restrict__ n_req_ptr, GatherArgs a)
+{
+    constexpr int U = PLANES == 2 ? UNROLL_HOST : 2 * UNROLL_HOST;       // 16 loads of 16 bytes per thread either way
+    uint32_t spc = a.tiles_per_chunk;                          // 4 KiB sub-tiles per chunk
+    uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
+    uint64_t n_batches = (n_sub + U - 1) / U;
+    uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
+    uint32_t tid = threadIdx.x;
+    for (uint64_t b = blockIdx.x; b < n_batches; b += gridDim.x) {
+        HostSub q[U];
+        u32x4 v0[U], v1[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            q[i] = host_sub(recs, b * U + i, n_sub, spc, chunk_units, tid);
+            v0[i] = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q[i].tier, 0) + q[i].src));
+            if (PLANES == 2) v1[i] = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q[i].tier, 1) + q[i].src));
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+            if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[0] + q[i].dst + (uint64_t)q[i].unit * 16), v0[i]);
+        if (PLANES == 2) {
+#pragma unroll
+            for (int i = 0; i < U; ++i)
+                if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[1] + q[i].dst + (uint64_t)q[i].unit * 16), v1[i]);
+        }
+    }
+}
+
+// The same for the head-major layout, walked in source order like gather_hm<.., true>; blockIdx.y is the plane.
+__global__ __launch_bounds__(WG) void gather_hm_host_batches(const Rec *__restrict__ recs,
+                                                             const uint32_t *__restrict__ n_req_ptr, GatherArgs a, HmArgs h)
+{
+    constexpr int U = UNROLL_HOST;
+    uint32_t spc = a.tiles_per_chunk;
+    uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
+    uint64_t n_batches = (n_sub + U - 1) / U;
+    uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
+    uint32_t tid = threadIdx.x, plane = blockIdx.y;
+    uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
+    uint32_t row_units = h.n_heads * h.upr;                    // one token: all heads
+    for (uint64_t b = blockIdx.x; b < n_batches; b += gridDim.x) {
+        HostSub q[U];
+        u32x4 v[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            q[i] = host_sub(recs, b * U + i, n_sub, spc, chunk_units, tid);
+            v[i] = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q[i].tier, plane) + q[i].src));
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            uint32_t u = q[i].unit;
+            uint32_t tok = u / row_units, rem = u - tok * row_units;
+            uint32_t head = rem / h.upr, col = rem - head * h.upr;
+            uint64_t d_off = head * (q[i].cap * h.ups * 16) + (uint64_t)(tok * h.upr + col) * 16;
+            if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(dst_plane + q[i].dst + d_off), v[i]);
         }
     }
 }
