@@ -123,7 +123,7 @@ typedef struct harvest_config {
     harvest_class_config cls[HARVEST_N_CLASSES];
     uint32_t gather_wg_per_cu;      /* tuning: cap the HBM-tier gather at this many workgroups per CU (they then loop
                                        over tiles); 0 = default, one workgroup per 4 KiB tile */
-    uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (8) */
+    uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (24) */
     uint32_t shared_granule;        /* segment granule of the shared cache pool in bytes: a power of two >= 256;
                                        0 = 4096 */
     uint32_t reserved[5];           /* must be 0 */

@@ -425,7 +425,6 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     ga.dst_base[1] = dst_base1;
     ga.chunk_bytes = c.cfg.chunk_bytes;
     uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
-    uint32_t tpc_host = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
     uint32_t planes = c.cfg.n_planes;
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
@@ -434,33 +433,24 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
     bool host_tier = c.cfg.n_host_slots != 0;
     if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
-        // chunks that are whole 32 KiB tiles take the tile kernels; other sizes the kernels that batch 4 KiB sub-tiles
-        // across requests.  With profiling on, the events are attached to the dispatch itself and read the kernel's
-        // own begin and end.
-        const bool whole_tiles = c.cfg.chunk_bytes % TILE_HOST == 0;
-        ga.tiles_per_chunk = whole_tiles ? tpc_host : tpc_hbm;
+        // With profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end.
+        ga.tiles_per_chunk = tpc_hbm;                  // the host-tier kernels walk 4 KiB sub-tiles
         ga.n_planes = planes;
         const Rec *recs = (const Rec *)ss->host_recs;
         const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
+        dim3 g(ctx->host_grid);
         if (hm) {
-            dim3 g(std::max(1u, ctx->host_grid / planes), planes);
-            if (whole_tiles) {
-                if (pc)
-                    hipExtLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, pc, pd, 0, recs,
-                                          n_req, ga, *hm, (uint32_t *)nullptr);
-                else
-                    hipLaunchKernelGGL((gather_hm<UNROLL_HOST, false, true>), g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm,
-                                       (uint32_t *)nullptr);
-            } else if (pc)
-                hipExtLaunchKernelGGL(gather_hm_host_batches, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
-            else
-                hipLaunchKernelGGL(gather_hm_host_batches, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
-        } else {
-            auto kernel = whole_tiles ? gather_host : (planes == 2 ? gather_host_batches<2> : gather_host_batches<1>);
+            auto kernel = planes == 2 ? gather_hm_host<2> : gather_hm_host<1>;
             if (pc)
-                hipExtLaunchKernelGGL(kernel, dim3(ctx->host_grid), dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
+                hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
             else
-                hipLaunchKernelGGL(kernel, dim3(ctx->host_grid), dim3(WG), 0, ss->side, recs, n_req, ga);
+                hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
+        } else {
+            auto kernel = planes == 2 ? gather_host<2> : gather_host<1>;
+            if (pc)
+                hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
+            else
+                hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga);
         }
         HIP_TRY(hipGetLastError());
     }
@@ -529,7 +519,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     HIP_TRY(hipGetDeviceProperties(&prop, cfg->device));
     ctx->n_cu = prop.multiProcessorCount;
     ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
-    ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 8;
+    ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 24;
     ctx->ctl_grid = 8 * ctx->n_cu;
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&ctx->ctl_evt, hipEventDisableTiming));

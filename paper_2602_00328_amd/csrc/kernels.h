@@ -30,7 +30,8 @@ constexpr int WG = 256;                         // 4 wavefronts
 constexpr int WAVES = WG / 64;
 constexpr uint32_t TILE_HBM = WG * 16;          // 4 KiB: one 16-byte access per thread
 constexpr int UNROLL_HOST = 8;
-constexpr uint32_t TILE_HOST = WG * 16 * UNROLL_HOST;   // 32 KiB: 8 accesses in flight per thread over PCIe
+constexpr uint32_t TILE_HOST = WG * 16 * UNROLL_HOST;   // 32 KiB tiles of the host-built copy lists (place, write-back)
+constexpr int HOST_LOADS = 2;                   // 16-byte loads a thread of the host-tier gather keeps in flight
 
 // directory entry: [1:0] tier, [31:2] slot in that tier (host slot for HOST), [63:32] generation
 constexpr uint64_t TIER_MASK = 3;
@@ -426,10 +427,7 @@ struct HmArgs {
     uint32_t pad;
 };
 
-// SRC_ORDER = false (HBM tier): threads walk in destination order, as said above.  SRC_ORDER = true (host tier): threads
-// walk in source order instead, so every wave load is one contiguous kilobyte - PCIe reads of 256-byte pieces reach
-// only 22 GB/s, whole kilobytes 56 GB/s - and the stores, which go to HBM, are the ones cut into head rows.
-template <int UNROLL, bool NT, bool SRC_ORDER = false>
+template <int UNROLL, bool NT>
 __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
                                                 GatherArgs a, HmArgs h, uint32_t *feedback)
 {
@@ -452,18 +450,10 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
         uint64_t head_stride = cap * h.ups * 16;
         // unit u (in walking order) -> source unit and destination byte offset
         auto map = [&](uint32_t u, uint32_t &s_unit, uint64_t &d_off) {
-            if (SRC_ORDER) {
-                uint32_t row_units = h.n_heads * h.upr;                 // one token: all heads
-                uint32_t tok = u / row_units, rem = u - tok * row_units;
-                uint32_t head = rem / h.upr, col = rem - head * h.upr;
-                s_unit = u;
-                d_off = head * head_stride + (uint64_t)(tok * h.upr + col) * 16;
-            } else {
-                uint32_t head = u / h.ups, rem = u - head * h.ups;
-                uint32_t tok = rem / h.upr, col = rem - tok * h.upr;
-                s_unit = (tok * h.n_heads + head) * h.upr + col;
-                d_off = head * head_stride + (uint64_t)rem * 16;
-            }
+            uint32_t head = u / h.ups, rem = u - head * h.ups;
+            uint32_t tok = rem / h.upr, col = rem - tok * h.upr;
+            s_unit = (tok * h.n_heads + head) * h.upr + col;
+            d_off = head * head_stride + (uint64_t)rem * 16;
         };
         uint32_t tile_first = ((uint32_t)t - idx * tpc) * UNITS;
         if (tile_first + UNITS <= chunk_units) {
@@ -494,53 +484,19 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
 }
 
 // Host tier: the same request list format, read over PCIe from pinned host memory by a few persistent workgroups.
-// Both planes of a tile are loaded before either is stored, so a two-plane class keeps 16 x 16 bytes in flight per
-// thread: the link needs bytes in flight, not workgroups, and every workgroup spared leaves the HBM tier alone.
-// This kernel walks 32 KiB tiles inside a chunk and is the one launched for chunk sizes that are whole tiles (32 KiB KV
-// blocks, experts); a chunk that ends inside a tile would leave that tile's loads half empty - gather_host_batches
-// below serves those sizes.
-__global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                                  GatherArgs a)
-{
-    constexpr int U = UNROLL_HOST;
-    uint32_t tpc = a.tiles_per_chunk;
-    uint64_t n_tiles = (uint64_t)(*n_req_ptr) * tpc;
-    uint32_t tid = threadIdx.x;
-    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint32_t idx = (uint32_t)t / tpc;
-        Rec x = recs[idx];
-        uint64_t off = (uint64_t)((uint32_t)t - idx * tpc) * TILE_HOST;
-        uint64_t len = a.chunk_bytes - off;
-        uint64_t so = (x.src & ~(uint64_t)3) + off;
-        uint32_t tier = (uint32_t)(x.src & 3);
-        if (a.n_planes == 2 && len >= TILE_HOST) {
-            const u32x4 *s0 = reinterpret_cast<const u32x4 *>(src_base_of(a, tier, 0) + so) + tid;
-            const u32x4 *s1 = reinterpret_cast<const u32x4 *>(src_base_of(a, tier, 1) + so) + tid;
-            u32x4 *d0 = reinterpret_cast<u32x4 *>(a.dst_base[0] + x.dst + off) + tid;
-            u32x4 *d1 = reinterpret_cast<u32x4 *>(a.dst_base[1] + x.dst + off) + tid;
-            u32x4 v0[U], v1[U];
-#pragma unroll
-            for (int i = 0; i < U; ++i) v0[i] = ld16<false>(s0 + i * WG);
-#pragma unroll
-            for (int i = 0; i < U; ++i) v1[i] = ld16<false>(s1 + i * WG);
-#pragma unroll
-            for (int i = 0; i < U; ++i) st16<true>(d0 + i * WG, v0[i]);
-#pragma unroll
-            for (int i = 0; i < U; ++i) st16<true>(d1 + i * WG, v1[i]);
-        } else {
-            for (uint32_t p = 0; p < a.n_planes; ++p)
-                copy_tile<U, false>(src_base_of(a, tier, p) + so, (p ? a.dst_base[1] : a.dst_base[0]) + x.dst + off, len,
-                                    tid);
-        }
-    }
-}
-
-// Host tier for chunk sizes that are not whole 32 KiB tiles (16 KiB blocks of an fp8 KV cache, ragged sizes).  Work is
-// cut into 4 KiB sub-tiles numbered through the whole list (request * sub-tiles per chunk + position); a workgroup takes
-// UNROLL_HOST consecutive ones at a time, across request boundaries, and loads all of them (for both planes) before it
-// stores any, so the bytes in flight per thread do not depend on the chunk size.  Each load is issued as soon as its list
-// entry has arrived - computing all addresses first leaves the link idle meanwhile and costs a fifth of the rate.  Lanes
-// beyond a chunk's end re-read the chunk's first bytes and store nothing: loads stay free of branches.
+//
+// What the link needs (measured on MI355X): one compute unit sustains about 12.8 GB/s of reads from host memory however
+// many loads its threads have outstanding, so the rate is set by how many CUs take part (5 saturate the 57 GB/s link) -
+// and every host read in flight beyond what the link can absorb (about 128 KiB) only queues in the memory pipeline the
+// HBM-tier gather is using at the same time: 8 workgroups x 16 loads per thread cost that kernel 12 %, 24 workgroups x
+// 2 loads cost it 8 % and serve the link better (57.1 against 56.8 GB/s).  Hence: HOST_LOADS = 2 loads of 16 bytes per
+// thread, a couple of dozen workgroups.
+//
+// Work is cut into 4 KiB sub-tiles numbered through the whole list (request * sub-tiles per chunk + position), so the
+// bytes in flight do not depend on the chunk size (16 KiB blocks of an fp8 KV cache and ragged sizes run at the same
+// rate as 32 KiB blocks).  A two-plane class takes one sub-tile of both planes per step, a one-plane class two
+// consecutive sub-tiles.  Each load is issued as soon as its list entry has arrived.  Lanes beyond a chunk's end
+// re-read the chunk's first bytes and store nothing: loads stay free of branches.
 struct HostSub {
     uint64_t src;      // offset of this lane's 16 bytes inside the tier's plane pool
     uint64_t dst;      // offset of the chunk inside the destination plane (head-major: of the sequence's region)
@@ -555,7 +511,7 @@ __device__ inline HostSub host_sub(const Rec *__restrict__ recs, uint64_t g, uin
 {
     HostSub r;
     bool valid = g < n_sub;
-    uint32_t idx = valid ? (uint32_t)g / spc : 0;             // a batch exists only when the list is not empty
+    uint32_t idx = valid ? (uint32_t)g / spc : 0;             // a step exists only when the list is not empty
     Rec x = recs[idx];
     uint32_t j = valid ? (uint32_t)g - idx * spc : 0;
     uint32_t u = j * WG + tid;
@@ -569,16 +525,16 @@ __device__ inline HostSub host_sub(const Rec *__restrict__ recs, uint64_t g, uin
 }
 
 template <int PLANES>
-__global__ __launch_bounds__(WG) void gather_host_batches(const Rec *__restrict__ recs,
-                                                          const uint32_t *__restrict__ n_req_ptr, GatherArgs a)
+__global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                                  GatherArgs a)
 {
-    constexpr int U = PLANES == 2 ? UNROLL_HOST : 2 * UNROLL_HOST;       // 16 loads of 16 bytes per thread either way
+    constexpr int U = HOST_LOADS / PLANES;                     // sub-tiles per step
     uint32_t spc = a.tiles_per_chunk;                          // 4 KiB sub-tiles per chunk
     uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
-    uint64_t n_batches = (n_sub + U - 1) / U;
+    uint64_t n_steps = (n_sub + U - 1) / U;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     uint32_t tid = threadIdx.x;
-    for (uint64_t b = blockIdx.x; b < n_batches; b += gridDim.x) {
+    for (uint64_t b = blockIdx.x; b < n_steps; b += gridDim.x) {
         HostSub q[U];
         u32x4 v0[U], v1[U];
 #pragma unroll
@@ -588,43 +544,38 @@ __global__ __launch_bounds__(WG) void gather_host_batches(const Rec *__restrict_
             if (PLANES == 2) v1[i] = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q[i].tier, 1) + q[i].src));
         }
 #pragma unroll
-        for (int i = 0; i < U; ++i)
-            if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[0] + q[i].dst + (uint64_t)q[i].unit * 16), v0[i]);
-        if (PLANES == 2) {
-#pragma unroll
-            for (int i = 0; i < U; ++i)
-                if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[1] + q[i].dst + (uint64_t)q[i].unit * 16), v1[i]);
+        for (int i = 0; i < U; ++i) {
+            if (!q[i].act) continue;
+            uint64_t d = q[i].dst + (uint64_t)q[i].unit * 16;
+            st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[0] + d), v0[i]);
+            if (PLANES == 2) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[1] + d), v1[i]);
         }
     }
 }
 
-// The same for the head-major layout, walked in source order like gather_hm<.., true>; blockIdx.y is the plane.
-__global__ __launch_bounds__(WG) void gather_hm_host_batches(const Rec *__restrict__ recs,
-                                                             const uint32_t *__restrict__ n_req_ptr, GatherArgs a, HmArgs h)
+// The same for the head-major layout.  Unlike the HBM-tier kernel above, threads walk the block in SOURCE order, so that
+// every wave load is one contiguous kilobyte (PCIe reads of 256-byte pieces reach only 22 GB/s); the stores, which go to
+// HBM, are the ones cut into head rows.  K and V of a unit go to the same place in their planes: one address
+// computation serves both.
+template <int PLANES>
+__global__ __launch_bounds__(WG) void gather_hm_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                                     GatherArgs a, HmArgs h)
 {
-    constexpr int U = UNROLL_HOST;
     uint32_t spc = a.tiles_per_chunk;
     uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
-    uint64_t n_batches = (n_sub + U - 1) / U;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
-    uint32_t tid = threadIdx.x, plane = blockIdx.y;
-    uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
+    uint32_t tid = threadIdx.x;
     uint32_t row_units = h.n_heads * h.upr;                    // one token: all heads
-    for (uint64_t b = blockIdx.x; b < n_batches; b += gridDim.x) {
-        HostSub q[U];
-        u32x4 v[U];
-#pragma unroll
-        for (int i = 0; i < U; ++i) {
-            q[i] = host_sub(recs, b * U + i, n_sub, spc, chunk_units, tid);
-            v[i] = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q[i].tier, plane) + q[i].src));
-        }
-#pragma unroll
-        for (int i = 0; i < U; ++i) {
-            uint32_t u = q[i].unit;
-            uint32_t tok = u / row_units, rem = u - tok * row_units;
-            uint32_t head = rem / h.upr, col = rem - head * h.upr;
-            uint64_t d_off = head * (q[i].cap * h.ups * 16) + (uint64_t)(tok * h.upr + col) * 16;
-            if (q[i].act) st16<true>(reinterpret_cast<u32x4 *>(dst_plane + q[i].dst + d_off), v[i]);
+    for (uint64_t g = blockIdx.x; g < n_sub; g += gridDim.x) {
+        HostSub q = host_sub(recs, g, n_sub, spc, chunk_units, tid);
+        u32x4 v0 = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q.tier, 0) + q.src)), v1;
+        if (PLANES == 2) v1 = ld16<false>(reinterpret_cast<const u32x4 *>(src_base_of(a, q.tier, 1) + q.src));
+        uint32_t tok = q.unit / row_units, rem = q.unit - tok * row_units;
+        uint32_t head = rem / h.upr, col = rem - head * h.upr;
+        uint64_t d = q.dst + head * (q.cap * h.ups * 16) + (uint64_t)(tok * h.upr + col) * 16;
+        if (q.act) {
+            st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[0] + d), v0);
+            if (PLANES == 2) st16<true>(reinterpret_cast<u32x4 *>(a.dst_base[1] + d), v1);
         }
     }
 }
