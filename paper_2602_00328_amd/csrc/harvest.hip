@@ -182,7 +182,7 @@ struct harvest_ctx {
     harvest_config cfg{};
     bool no_device = false, poison = false, profile = false;
     int n_cu = 256;
-    uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0;
+    uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0, pcie_grid = 0;
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
     hipEvent_t ctl_evt = nullptr;            // recorded after every directory edit on the control stream
@@ -520,7 +520,9 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->n_cu = prop.multiProcessorCount;
     ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
     ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 24;
-    ctx->ctl_grid = 8 * ctx->n_cu;
+    ctx->ctl_grid = 8 * ctx->n_cu;                 // HBM-bound fills
+    ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
+                                                   // GB/s against 55.2 with 2048 workgroups)
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&ctx->ctl_evt, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
@@ -795,7 +797,7 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
     if ((rc = release_after(st, ss->s))) return rc;
     uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
+    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->pcie_grid);
     hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
                        c.cfg.chunk_bytes, tpc);
     HIP_TRY(hipGetLastError());
@@ -1174,7 +1176,9 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
         if ((rc = release_after(st, ss->s))) return rc;
         uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-        uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
+        bool to_host = false;                          // lossy objects move between HBM pools only
+        for (const Item2 &it : items) to_host |= it.dst0 != 0;
+        uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
         hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
                            (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
         HIP_TRY(hipGetLastError());
