@@ -13,9 +13,12 @@
 //   gather                   : the copy itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte non-temporal
 //                              load and store per thread, as many workgroups as tiles, plane K before plane V
 //                              (measured on MI355X: short workgroups beat deep unrolling and persistent grids by
-//                              ~15%, non-temporal accesses are worth ~11%, one plane at a time ~2%).  Host tier: a
-//                              few persistent workgroups with 8 loads in flight per thread - enough to keep the PCIe
-//                              link full while leaving the CUs to the HBM tier.
+//                              ~15%, non-temporal accesses are worth ~11%, one plane at a time ~2%).
+//   gather_host              : host tier - a couple of dozen persistent workgroups with two loads in flight per
+//                              thread over 4 KiB sub-tiles: enough compute units to keep the PCIe link full, and no
+//                              more host reads in flight than the link absorbs, because the rest would only stand in
+//                              the HBM tier's way.
+//   gather_hm, gather_hm_host: the same two into a head-major working layout.
 //   copy_items, copy_items2, fill_items, dir_write : host-built lists - placement, write-back (one source, up to two
 //                              destinations), slot poisoning after revocation, directory publication.
 #pragma once
