@@ -26,7 +26,9 @@
  *     harvest_fetch_experts may be recorded into a HIP graph (stream capture)
  *     once such a call has run on that stream outside capture: they use no
  *     memset and read residency from device memory, so a replay follows every
- *     place / revoke made since.  While a context has recorded work,
+ *     place / revoke made since.  harvest_place and harvest_evict refuse a
+ *     capturing stream, harvest_revoke refuses while any stream the context
+ *     knows is capturing (EINVAL, nothing changed).  While a context has recorded work,
  *     harvest_revoke drains by waiting for the whole device.  Directory edits made by place /
  *     revoke / evict(DEMOTE) / register are visible to every fetch enqueued
  *     after the call returns (place: on the same stream; other streams may

@@ -767,6 +767,8 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     ClassState &c = ctx->cls[cls];
     for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
     if ((rc = device_guard(ctx))) return rc;
+    // directory edits go through the control stream and pinned staging: they cannot be recorded into a graph
+    if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;
     std::vector<uint32_t> moved;
     std::vector<Item> items;
     for (uint32_t i = 0; i < n; ++i) {
@@ -822,6 +824,10 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
         ClassState &c = ctx->cls[cls];
         for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
         if ((rc = device_guard(ctx))) return rc;
+        // the drain waits for streams: impossible while one of them is being recorded into a graph
+        if (!ctx->no_device)
+            for (auto &kv : ctx->streams)
+                if (is_capturing(kv.first)) return HARVEST_EINVAL;
         // 1. invalidate
         for (uint32_t i = 0; i < n; ++i) {
             uint32_t id = ids[i];
@@ -1118,6 +1124,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         if (((uint64_t)d_src0 | (uint64_t)d_src1) & 15) return HARVEST_EINVAL;
     }
     if ((rc = device_guard(ctx))) return rc;
+    if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;     // as for harvest_place
     const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     std::vector<Item2> items;

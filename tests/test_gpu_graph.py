@@ -32,8 +32,17 @@ def test_captured_fetch_follows_residency_changes_across_replays():
             eh.h.fetch_kv(1, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
         s.synchronize()
         g = torch.cuda.CUDAGraph()
+        some_host_block = next(b for b in range(wl.n_closed) if eh.lookup(S.KV, b)[0] == S.HOST)
+        before = eh.lookup(S.KV, some_host_block)
         with torch.cuda.graph(g, stream=s):
+            with pytest.raises(Exception) as e:            # directory edits cannot be recorded: refused, nothing changes
+                eh.h.place(S.KV, [some_host_block])
+            assert e.value.code == -1
+            with pytest.raises(Exception) as e:            # and a revocation could not drain
+                eh.h.revoke(S.KV, [int(next(iter(rh.live)))])
+            assert e.value.code == -1
             eh.h.fetch_kv(1, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+        assert eh.lookup(S.KV, some_host_block) == before
 
         def replay_and_check(what):
             for t in dst:
