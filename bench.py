@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
+    ap.add_argument("--fetch-layers", type=int, default=1,
+                    help="variant: every step fetches this many consecutive layers with one harvest_fetch_kv_layers call "
+                         "(must divide --layers); isolation and graph legs are skipped")
     ap.add_argument("--shared-cache", action="store_true",
                     help="variant: the cache tier is one pool of best-fit segments (an object's layers and planes are "
                          "contiguous) instead of equal-size slots per layer and plane")
@@ -51,14 +54,19 @@ def parse():
     ap.add_argument("--graph-steps", type=int, default=64,
                     help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.fetch_layers > 1:
+        if args.layers % args.fetch_layers or args.head_major:
+            ap.error("--fetch-layers must divide --layers and excludes --head-major")
+        args.no_isolation, args.graph_steps = True, 0
+    return args
 
 
 class DeviceDecode:
     """Keeps the decode state of workloads.scenarios.KVRun on the device so that a timed step moves no table or
     payload over PCIe except what the method itself moves."""
 
-    def __init__(self, run, eng, wl, n_steps, head_major=False):
+    def __init__(self, run, eng, wl, n_steps, head_major=False, fetch_layers=1):
         import numpy as np
         import torch
         import workloads as W
@@ -69,7 +77,10 @@ class DeviceDecode:
         self.d_table = torch.from_numpy(table).to(self.dev)
         self.d_nb = torch.from_numpy(nb).to(self.dev)
         self.d_sdb = torch.from_numpy(run.seq_dst_block.view(np.int64)).to(self.dev)
-        self.dst = [torch.zeros(run.cap * sh.chunk_bytes, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        self.fetch_layers = fetch_layers
+        self.layer_bytes = run.cap * sh.chunk_bytes
+        self.dst_all = [torch.zeros(fetch_layers * self.layer_bytes, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        self.dst = [t[:self.layer_bytes] for t in self.dst_all]            # the first fetched layer
         # the rows every step appends, generated up front: [step][plane][layer][seq][row_bytes]
         rows = np.empty((n_steps, 2, sh.n_layers, wl.n_seq, sh.row_bytes), dtype=np.uint8)
         for t in range(n_steps):
@@ -104,7 +115,14 @@ class DeviceDecode:
             graphs.append(g)
         self.graphs = graphs
 
+    def first_layer(self, t):
+        return (t * self.fetch_layers) % self.wl.shape.n_layers
+
     def fetch(self, layer):
+        if self.fetch_layers > 1:
+            self.eng.h.fetch_kv_layers(layer, self.fetch_layers, self.d_table, self.d_nb, self.dst_all[0], self.dst_all[1],
+                                       self.layer_bytes, self.d_sdb, self.run.cap)
+            return
         if self.graphs:
             self.graphs[layer].replay()
             return
@@ -119,7 +137,7 @@ class DeviceDecode:
         import torch
         run, wl, sh = self.run, self.wl, self.wl.shape
         t = self.t
-        self.fetch(t % sh.n_layers)
+        self.fetch(self.first_layer(t))
         # append one token per sequence: rows go straight into the open tail blocks in local HBM.  The row index of every
         # tail lives on the device and is bumped there, so a step copies nothing from the host unless a tail rolls over.
         for p in range(2):
@@ -364,7 +382,7 @@ def main():
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
-    dd = DeviceDecode(run, eng, wl, n_total, head_major=args.head_major)
+    dd = DeviceDecode(run, eng, wl, n_total, head_major=args.head_major, fetch_layers=args.fetch_layers)
 
     # ---- calibration kernel of known size (for hardware byte counters) + achievable-copy ceiling ----
     cal_bytes = 2 << 30
@@ -420,9 +438,10 @@ def main():
     d = {k: c1[k] - c0[k] for k in COUNT_KEYS}
     sec = t_end - t_start
     ms_per_step = sec * 1e3 / args.steps
-    payload = d["n_requests"] * 2 * chunk                   # bytes delivered into the working layout
-    hbm_payload = (d["n_local"] + d["n_cache"]) * 2 * chunk
-    host_payload = d["n_host"] * 2 * chunk
+    FL = args.fetch_layers                                  # requests are counted once per call, bytes move per layer
+    payload = d["n_requests"] * 2 * chunk * FL              # bytes delivered into the working layout
+    hbm_payload = (d["n_local"] + d["n_cache"]) * 2 * chunk * FL
+    host_payload = d["n_host"] * 2 * chunk * FL
     value = 2 * payload / sec / 1e9
     hbm_ms = pr.hbm_ms / max(1, pr.hbm_launches)
     host_ms = pr.host_ms / max(1, pr.host_launches)
@@ -457,7 +476,7 @@ def main():
     bit_exact, cpu_baseline = None, None
     if not args.no_cpu_baseline:
         from oracle.engine import OracleEngine
-        layer = dd.t % sh.n_layers
+        layer = dd.first_layer(dd.t)
         ncores = len(os.sched_getaffinity(0))
         wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape)
         eo = OracleEngine(kv=S.kv_spec(wl1, cache_slack=0 if args.no_isolation else all_cache_slack), kv_layers=[layer],
@@ -583,10 +602,11 @@ def main():
                                + ("" if args.kv_elt_bytes == 2 else f" -- VARIANT: {args.kv_elt_bytes}-byte KV elements, "
                                   f"{chunk // 1024} KiB blocks"),
                    "working_layout": "head-major" if args.head_major else "token-major",
+                   "layers_per_fetch": args.fetch_layers,
                    "cache_tier": "shared pool of best-fit segments" if args.shared_cache else "equal-size slots",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},
-        "objects_per_s": round(d["n_requests"] / sec),
+        "objects_per_s": round(d["n_requests"] * args.fetch_layers / sec),
         "bit_exact": bit_exact,
         "graph_replay": graph_replay,
         "served": {k: v // args.steps for k, v in d.items()},

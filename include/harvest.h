@@ -217,6 +217,17 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
                      uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                      const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, void *stream);
 
+/* The same fetch for n_layers consecutive layers in one call (Section 5.2 moves whole blocks; an engine that reloads a
+ * block needs it in every layer).  The block table is resolved once - an object has the same slot in every layer -
+ * and layer layer_first + r lands d_dst + r * dst_layer_stride_bytes (a multiple of 16, at least dst_capacity_blocks *
+ * chunk_bytes).  The host-tier copies of all layers follow each other without a join in between.  Counts and miss
+ * list are per request (block), not per layer.  Nothing can change residency inside one call, and a revocation made
+ * after it returns drains all of its layers. */
+int harvest_fetch_kv_layers(harvest_ctx *ctx, uint32_t layer_first, uint32_t n_layers, const int32_t *d_block_table,
+                            const int32_t *d_n_blocks, uint32_t n_seq, uint32_t max_blocks, void *d_dst_k,
+                            void *d_dst_v, uint64_t dst_layer_stride_bytes, const uint64_t *d_seq_dst_block,
+                            uint64_t dst_capacity_blocks, void *stream);
+
 /* The same fetch into a head-major working layout (the paper leaves layouts open; attention kernels that walk one head at
  * a time want this one).  A pool block is [block_tokens][n_heads][head_bytes] with head_bytes = chunk_bytes /
  * (block_tokens * n_heads), a multiple of 16.  Sequence s owns d_seq_cap_blocks[s] (< 65536) destination blocks starting at

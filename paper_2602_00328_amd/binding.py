@@ -69,6 +69,7 @@ SYMBOLS = {
     "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
     "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
+    "harvest_fetch_kv_layers": (ctypes.c_int, [vp, u32, u32, vp, vp, u32, u32, vp, vp, u64, vp, u64, vp]),
     "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
     "harvest_fetch_experts": (ctypes.c_int, [vp, u32, vp, u32, u32, vp, u32, vp, vp]),
     "harvest_prefetcher_create": (ctypes.c_int, [vp, vp * 2, u32, vp * 2, ctypes.POINTER(vp)]),
@@ -263,6 +264,14 @@ class Harvest:
         _chk(lib.harvest_fetch_kv(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
                                   _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block), dst_capacity_blocks,
                                   _stream_ptr(stream)), "harvest_fetch_kv")
+
+    def fetch_kv_layers(self, layer_first, n_layers, d_table, d_n_blocks, d_dst_k, d_dst_v, dst_layer_stride_bytes,
+                        d_seq_dst_block, cap_blocks, stream=None):
+        n_seq, max_blocks = d_table.shape
+        _chk(lib.harvest_fetch_kv_layers(self.h, layer_first, n_layers, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq,
+                                         max_blocks, _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), dst_layer_stride_bytes,
+                                         _dev_ptr(d_seq_dst_block), cap_blocks, _stream_ptr(stream)),
+             "harvest_fetch_kv_layers")
 
     def fetch_kv_head_major(self, layer, d_table, d_n_blocks, d_dst_k, d_dst_v, d_seq_dst_block, d_seq_cap_blocks,
                             dst_capacity_blocks, n_heads, block_tokens, stream=None):

@@ -412,51 +412,28 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 
 // Launches the HBM-tier gather on the caller's stream and the host-tier gather on the side stream, joined back.
 // max_req bounds the number of requests either list can hold; dst_base: where plane p of the working layout starts.
+// n_rep > 1 gathers n_rep consecutive layers from the same two lists (they name slots, and an object has the same slot
+// in every layer): repetition r reads layer_stride(tier) * r further into every pool and writes dst_step * r further
+// into the destination.  The host-tier gathers of all repetitions queue up behind each other on the side stream, so
+// the link never waits for a join between layers.
 int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
-                   uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr)
+                   uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr, uint32_t n_rep = 1,
+                   uint64_t dst_step = 0)
 {
+    const ClassDev cd = class_dev(c);
     GatherArgs ga{};
-    for (uint32_t p = 0; p < 2; ++p) {
-        ga.src_base[T_HOST][p] = c.host_dev[p];
-        ga.src_base[T_CACHE][p] = c.cache_base(p);
-        ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p];
-    }
-    ga.dst_base[0] = dst_base0;
-    ga.dst_base[1] = dst_base1;
     ga.chunk_bytes = c.cfg.chunk_bytes;
     uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
     uint32_t planes = c.cfg.n_planes;
+    ga.tiles_per_chunk = tpc_hbm;                      // both tiers walk 4 KiB tiles
+    ga.n_planes = planes;
     HIP_TRY(hipEventRecord(ss->fork, ss->s));
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
-    hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
     const bool profile = ctx->profile && !is_capturing(ss->s);        // timing events cannot be recorded into a graph
-    if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); pc = prof_event(ctx); pd = prof_event(ctx); }
-    bool host_tier = c.cfg.n_host_slots != 0;
-    if (host_tier) {                 // first, so that the long PCIe transfer starts before the CUs fill up
-        // With profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end.
-        ga.tiles_per_chunk = tpc_hbm;                  // the host-tier kernels walk 4 KiB sub-tiles
-        ga.n_planes = planes;
-        const Rec *recs = (const Rec *)ss->host_recs;
-        const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
-        dim3 g(ctx->host_grid);
-        if (hm) {
-            auto kernel = planes == 2 ? gather_hm_host<2> : gather_hm_host<1>;
-            if (pc)
-                hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
-            else
-                hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
-        } else {
-            auto kernel = planes == 2 ? gather_host<2> : gather_host<1>;
-            if (pc)
-                hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
-            else
-                hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga);
-        }
-        HIP_TRY(hipGetLastError());
-    }
-    // Grid: one workgroup per tile.  The request count lives on the device, so the grid is sized from what the
-    // previous gather of this class on this stream reported (plus slack), never below a floor that still fills the
-    // chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
+    const bool host_tier = c.cfg.n_host_slots != 0;
+    // Grid of the HBM-tier gather: one workgroup per tile.  The request count lives on the device, so the grid is sized
+    // from what the previous gather of this class on this stream reported (plus slack), never below a floor that still
+    // fills the chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
     uint64_t max_tiles = max_req * tpc_hbm;
     uint64_t want = max_tiles;
     if (ss->feedback_valid[cls]) {
@@ -465,31 +442,61 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
     }
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
-    ga.tiles_per_chunk = tpc_hbm;
-    ga.n_planes = planes;
-    if (hm) {
-        if (pa)
-            hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
-                                  (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, *hm,
+    for (uint32_t r = 0; r < n_rep; ++r) {
+        for (uint32_t p = 0; p < 2; ++p) {
+            ga.src_base[T_HOST][p] = c.host_dev[p] + r * cd.layer_stride[T_HOST];
+            ga.src_base[T_CACHE][p] = c.cache_base(p) + r * cd.layer_stride[T_CACHE];
+            ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p] + r * cd.layer_stride[T_LOCAL];
+        }
+        ga.dst_base[0] = dst_base0 + r * dst_step;
+        ga.dst_base[1] = dst_base1 + r * dst_step;
+        // With profiling on, the events are attached to the dispatch itself and read the kernel's own begin and end.
+        hipEvent_t pa = nullptr, pb = nullptr, pc = nullptr, pd = nullptr;
+        if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); }
+        if (profile && host_tier) { pc = prof_event(ctx); pd = prof_event(ctx); }
+        if (host_tier) {             // first, so that the long PCIe transfer starts before the CUs fill up
+            const Rec *recs = (const Rec *)ss->host_recs;
+            const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
+            dim3 g(ctx->host_grid);
+            if (hm) {
+                auto kernel = planes == 2 ? gather_hm_host<2> : gather_hm_host<1>;
+                if (pc)
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
+                else
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
+            } else {
+                auto kernel = planes == 2 ? gather_host<2> : gather_host<1>;
+                if (pc)
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
+                else
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga);
+            }
+            HIP_TRY(hipGetLastError());
+        }
+        const Rec *recs = (const Rec *)ss->hbm_recs;
+        const uint32_t *n_req = (const uint32_t *)(cnt + C_HBM_REQ);
+        if (hm) {
+            if (pa)
+                hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0, recs, n_req,
+                                      ga, *hm, ss->d_feedback + cls);
+            else
+                hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, recs, n_req, ga, *hm,
+                                   ss->d_feedback + cls);
+        } else if (pa)
+            hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0, recs, n_req, ga,
                                   ss->d_feedback + cls);
         else
-            hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
-                               (const uint32_t *)(cnt + C_HBM_REQ), ga, *hm, ss->d_feedback + cls);
-    } else if (pa)
-        hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0,
-                              (const Rec *)ss->hbm_recs, (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
-    else
-        hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, (const Rec *)ss->hbm_recs,
-                           (const uint32_t *)(cnt + C_HBM_REQ), ga, ss->d_feedback + cls);
-    HIP_TRY(hipGetLastError());
+            hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, recs, n_req, ga,
+                               ss->d_feedback + cls);
+        HIP_TRY(hipGetLastError());
+        if (profile) {
+            ctx->prof.push_back({ pa, pb, 0 });
+            if (host_tier) ctx->prof.push_back({ pc, pd, 1 });
+        }
+    }
     ss->feedback_valid[cls] = true;
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
-    if (profile) {
-        ctx->prof.push_back({ pa, pb, 0 });
-        if (host_tier) ctx->prof.push_back({ pc, pd, 1 });
-        else { ctx->prof_pool.push_back(pc); ctx->prof_pool.push_back(pd); }
-    }
     return mark_last(ctx, ss);
 }
 
@@ -879,14 +886,17 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
 static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
                          uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                          const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
-                         uint32_t n_heads, uint32_t block_tokens, void *stream)
+                         uint32_t n_heads, uint32_t block_tokens, void *stream, uint32_t n_layers = 1,
+                         uint64_t dst_layer_stride = 0)
 {
     int rc = check_class(ctx, HARVEST_KV);
     if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
     if (ctx->no_device) return HARVEST_ENODEV;
     std::lock_guard<std::mutex> lk(ctx->mu);
     ClassState &c = ctx->cls[HARVEST_KV];
-    if (layer >= c.cfg.n_layers) return HARVEST_EINVAL;
+    if (n_layers == 0 || (uint64_t)layer + n_layers > c.cfg.n_layers) return HARVEST_EINVAL;
+    if (n_layers > 1 && (dst_layer_stride % 16 || dst_layer_stride < dst_capacity_blocks * c.cfg.chunk_bytes))
+        return HARVEST_EINVAL;
     uint64_t total = (uint64_t)n_seq * max_blocks;
     if (total >= (1ull << 31)) return HARVEST_EINVAL;
     HmArgs hm{};
@@ -921,7 +931,7 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
-                          head_major ? &hm : nullptr);
+                          head_major ? &hm : nullptr, n_layers, dst_layer_stride);
 }
 
 int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
@@ -930,6 +940,15 @@ int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_ta
 {
     return fetch_kv_impl(ctx, layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v, d_seq_dst_block,
                          nullptr, dst_capacity_blocks, 0, 0, stream);
+}
+
+int harvest_fetch_kv_layers(harvest_ctx *ctx, uint32_t layer_first, uint32_t n_layers, const int32_t *d_block_table,
+                            const int32_t *d_n_blocks, uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                            uint64_t dst_layer_stride_bytes, const uint64_t *d_seq_dst_block,
+                            uint64_t dst_capacity_blocks, void *stream)
+{
+    return fetch_kv_impl(ctx, layer_first, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v,
+                         d_seq_dst_block, nullptr, dst_capacity_blocks, 0, 0, stream, n_layers, dst_layer_stride_bytes);
 }
 
 int harvest_fetch_kv_head_major(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,

@@ -140,6 +140,29 @@ class HipEngine:
     def fetch_kv(self, layer, table, n_blocks, seq_dst_block, cap, dst_fill=0):
         return self.fetch_end(self.fetch_kv_begin(layer, table, n_blocks, seq_dst_block, cap, dst_fill))
 
+    def fetch_kv_layers(self, layer_first, n_layers, table, n_blocks, seq_dst_block, cap, dst_fill=0):
+        """One call for n_layers consecutive layers -> ([(k, v) per layer], sorted miss list, counts)."""
+        sp = self.spec[KV]
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        with self._on(KV):
+            d_table = torch.from_numpy(table).to(self.dev)
+            d_nb = torch.from_numpy(np.ascontiguousarray(n_blocks, dtype=np.int32)).to(self.dev)
+            d_sdb = torch.from_numpy(np.ascontiguousarray(seq_dst_block, dtype=np.uint64).view(np.int64)).to(self.dev)
+            stride = cap * sp.chunk_bytes + 256               # not a multiple of the chunk size: strides are in bytes
+            dst = [torch.full((n_layers * stride,), dst_fill, dtype=torch.uint8, device=self.dev)
+                   for _ in range(sp.n_planes)]
+            self.h.fetch_kv_layers(layer_first, n_layers, d_table, d_nb, dst[0], dst[1] if sp.n_planes == 2 else None,
+                                   stride, d_sdb, cap)
+            counts, miss, n_miss = self.h.fetch_info(miss_cap=table.size)
+            out = []
+            for r in range(n_layers):
+                k = dst[0][r * stride:r * stride + cap * sp.chunk_bytes].cpu().numpy()
+                v = dst[1][r * stride:r * stride + cap * sp.chunk_bytes].cpu().numpy() if sp.n_planes == 2 else None
+                gap = dst[0][r * stride + cap * sp.chunk_bytes:(r + 1) * stride]
+                assert bool((gap == dst_fill).all()), "bytes between two layers' destinations were written"
+                out.append((k, v))
+        return out, np.sort(miss), counts
+
     def fetch_experts_begin(self, layer, topk, n_staging, staging_fill=0):
         sp = self.spec[EXPERT]
         with self._on(EXPERT):

@@ -296,6 +296,40 @@ def test_head_major_fetch(heads, dim, tokens, elt):
         eh.close(); eo.close()
 
 
+# ---- several layers in one call --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_fetch_of_several_layers_in_one_call(shared):
+    say(f"multi-layer fetch, shared pool {shared}")
+    wl = W.kv_decode(seed=24, n_layers=5, n_seq=3, min_len=300, max_len=900, n_steps=20)
+    kw = {}
+    if shared:
+        obj = 5 * 2 * wl.shape.chunk_bytes
+        kw = dict(shared_cache_bytes=(int(wl.resident.sum()) - 3) * obj, shared_granule=4096)
+    eo, eh = P.make_engines(wl, poison=True, **kw)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(20):
+            first, n = [(0, 5), (1, 3), (4, 1), (2, 2)][t % 4]
+            table, nb = rh.table_arrays()
+            layers, miss, counts = eh.fetch_kv_layers(first, n, table, nb, rh.seq_dst_block, rh.cap)
+            assert len(layers) == n
+            for r, (k, v) in enumerate(layers):
+                want = eo.fetch_kv(first + r, table, nb, ro.seq_dst_block, ro.cap)
+                P.assert_kv_equal(want, (k, v, miss, counts), f"step {t} layer {first + r}")
+            if t == 7:
+                a, b = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0])
+            if t == 12:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+            ro.append(t); rh.append(t)
+        with pytest.raises(Exception):                         # layers beyond the pool
+            eh.fetch_kv_layers(3, 3, table, nb, rh.seq_dst_block, rh.cap)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- one cache pool shared by both classes: variable-size segments, best-fit (Section 3.3) ----------------------
 
 def shared_pool_bytes(wl, ex, frac, G):
