@@ -108,7 +108,7 @@ class OracleEngine:
         k, v, miss, counts = c.fetch_kv_head_major(self.kv_layers.index(layer), table, n_blocks, seq_dst_block,
                                                    seq_cap_blocks, cap, n_heads, block_tokens,
                                                    dst_k=np.full(n, dst_fill, np.uint8), dst_v=np.full(n, dst_fill, np.uint8))
-        return k, v, np.sort(miss), counts
+        return k, (v if c.n_planes == 2 else None), np.sort(miss), counts
 
     def fetch_experts(self, layer, topk, n_staging):
         """-> (list over experts: None or the expert's bytes as the FFN would see them, kinds, sorted miss, counts)."""

@@ -296,6 +296,42 @@ def test_head_major_fetch(heads, dim, tokens, elt):
         eh.close(); eo.close()
 
 
+# ---- a one-plane KV class (a latent cache, say): every kernel's one-plane instantiation -------------------------
+
+def test_one_plane_kv_class():
+    say("one-plane KV class")
+    shape = W.KVShape(n_layers=3, block_tokens=16, n_kv_heads=4, head_dim=72, elt_bytes=2)       # 9 216-byte chunks
+    wl = W.kv_decode(seed=25, n_seq=3, min_len=300, max_len=900, n_steps=20, shape=shape)
+    kv = S.kv_spec(wl, n_planes=1)
+    eo, eh = P.make_engines(kv_spec=kv, poison=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        caps = np.array([len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)], np.uint32)
+        for t in range(20):
+            layer = t % 3
+            a, b = ro.fetch(layer), rh.fetch(layer)
+            assert b[1] is None
+            P.assert_kv_equal(a, b, f"one plane step {t}")
+            table, nb = rh.table_arrays()
+            a = eo.fetch_kv_head_major(layer, table, nb, ro.seq_dst_block, caps, ro.cap, 4, 16)
+            b = eh.fetch_kv_head_major(layer, table, nb, rh.seq_dst_block, caps, rh.cap, 4, 16)
+            P.assert_kv_equal(a, b, f"one plane head-major step {t}")
+            if t % 5 == 0:
+                layers, miss, counts = eh.fetch_kv_layers(0, 3, table, nb, rh.seq_dst_block, rh.cap)
+                for r, (k, v) in enumerate(layers):
+                    P.assert_kv_equal(eo.fetch_kv(r, table, nb, ro.seq_dst_block, ro.cap), (k, v, miss, counts), f"layers {t}.{r}")
+            if t == 8:
+                x, y = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                assert np.array_equal(x[0], y[0])
+            if t == 14:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+            ro.append(t); rh.append(t)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 1, what="one plane")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- several layers in one call --------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("shared", [False, True])

@@ -18,10 +18,10 @@ OK, ENOSPC = 0, -2
 EVICT_DEMOTE = 1
 
 
-def kv_spec(wl: KVWorkload, cache_slack: int = 0, local_slack: int = 0, shared: bool = False):
+def kv_spec(wl: KVWorkload, cache_slack: int = 0, local_slack: int = 0, shared: bool = False, n_planes: int = 2):
     """Pool sizes for a KV workload: a host slot for every block, cache slots for every resident block (none when the
     cache tier is carved from a pool shared with the other class)."""
-    return SimpleNamespace(n_layers=wl.shape.n_layers, n_planes=2, chunk_bytes=wl.shape.chunk_bytes,
+    return SimpleNamespace(n_layers=wl.shape.n_layers, n_planes=n_planes, chunk_bytes=wl.shape.chunk_bytes,
                            max_objects=wl.n_objects, n_host_slots=wl.n_objects,
                            n_cache_slots=0 if shared else int(wl.resident.sum()) + cache_slack,
                            n_local_slots=(wl.n_seq if wl.has_tails else 0) + local_slack, n_experts=0)
@@ -91,7 +91,7 @@ class KVRun:
             tail = self.tables[s][-1]
             rows = append_rows(wl, t, s)
             off = (self.lens[s] % sh.block_tokens) * sh.row_bytes
-            for p in range(2):
+            for p in range(self.e.spec[KV].n_planes):
                 for l in range(sh.n_layers):
                     self.e.write_local(KV, tail, p, l, off, rows[p, l])
             self.lens[s] += 1
