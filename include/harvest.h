@@ -261,7 +261,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
  *   release - the work enqueued so far on compute_stream is the last use of the oldest acquired buffer.  EINVAL when
  *             nothing is acquired.
  * All three only enqueue.  harvest_prefetcher_stream returns the fetch stream (for harvest_fetch_info); destroy waits
- * for it.  Destroy every prefetcher before its context. */
+ * for it.  harvest_destroy destroys the prefetchers its context still has; their handles are dead afterwards. */
 typedef struct harvest_prefetcher harvest_prefetcher;
 int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32_t n_staging_slots,
                               void **const d_expert_ptr[2], harvest_prefetcher **out);

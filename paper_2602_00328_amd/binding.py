@@ -7,6 +7,7 @@ the import of this module fails loudly - there is no fallback path.
 from __future__ import annotations
 
 import ctypes
+import weakref
 import os
 from dataclasses import dataclass
 
@@ -161,6 +162,7 @@ class Harvest:
         self._host_np = {}
         self._dev = {}             # (cls, tier, plane) -> torch tensor
         self.revoked_log = []      # (cls, id) in callback order
+        self._prefetchers = []     # weak references: closed with the context, their handles die with it
         self._cb = REVOKE_CB(lambda c, i, _u: self.revoked_log.append((int(c), int(i))))
         cfg = harvest_config()
         cfg.flags, cfg.device = flags, device
@@ -213,6 +215,11 @@ class Harvest:
 
     def close(self):
         if getattr(self, "h", None):
+            for ref in self._prefetchers:
+                pf = ref()
+                if pf is not None:
+                    pf.close()
+            self._prefetchers.clear()
             _chk(lib.harvest_destroy(self.h), "harvest_destroy")
             self.h = None
             self._host_np.clear()
@@ -332,6 +339,7 @@ class Prefetcher:
         pf = vp()
         _chk(lib.harvest_prefetcher_create(h.h, st, n_staging_slots, pt, ctypes.byref(pf)), "harvest_prefetcher_create")
         self.pf = pf
+        h._prefetchers.append(weakref.ref(self))
 
     def close(self):
         if getattr(self, "pf", None):

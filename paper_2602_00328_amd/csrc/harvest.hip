@@ -178,6 +178,8 @@ struct StreamState {
 
 }  // namespace
 
+struct harvest_prefetcher;
+
 struct harvest_ctx {
     harvest_config cfg{};
     bool no_device = false, poison = false, profile = false;
@@ -194,6 +196,7 @@ struct harvest_ctx {
     std::vector<hipEvent_t> prof_pool;
     bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
     SegAlloc shared;                      // free space of cfg.d_shared_cache
+    std::vector<harvest_prefetcher *> prefetchers;   // live ones: destroyed with the context if the caller did not
     std::mutex mu;
 };
 
@@ -664,6 +667,7 @@ int harvest_destroy(harvest_ctx *ctx)
     if (!ctx->no_device) {
         int rc = device_guard(ctx);
         if (rc) return rc;
+        while (!ctx->prefetchers.empty()) (void)harvest_prefetcher_destroy(ctx->prefetchers.back());
         for (auto &kv : ctx->streams) {
             StreamState *ss = kv.second.get();
             (void)hipStreamSynchronize(ss->s);
@@ -1016,6 +1020,7 @@ int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32
     if (hipStreamCreateWithFlags(&pf->fetch, hipStreamNonBlocking) != hipSuccess) return fail();
     for (hipEvent_t *e : { &pf->ready[0], &pf->ready[1], &pf->freed[0], &pf->freed[1], &pf->dep })
         if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return fail();
+    ctx->prefetchers.push_back(pf.get());
     *out = pf.release();
     return HARVEST_OK;
 }
@@ -1029,6 +1034,7 @@ int harvest_prefetcher_destroy(harvest_prefetcher *pf)
     {
         std::lock_guard<std::mutex> lk(ctx->mu);
         (void)hipStreamSynchronize(pf->fetch);
+        ctx->prefetchers.erase(std::remove(ctx->prefetchers.begin(), ctx->prefetchers.end(), pf), ctx->prefetchers.end());
         auto it = ctx->streams.find(pf->fetch);
         if (it != ctx->streams.end()) {
             (void)hipStreamSynchronize(it->second->side);

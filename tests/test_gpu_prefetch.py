@@ -76,6 +76,8 @@ def test_double_buffered_prefetch_against_layer_by_layer_oracle_fetches():
             if i == len(work) - 1:
                 assert counts == counts_o and np.array_equal(np.sort(miss), miss_o)
         assert {c[2] for c in consumed} == {pf.staging[0].data_ptr(), pf.staging[1].data_ptr()}
+        left_open = B.Prefetcher(eh.h, n_staging_slots=2)          # never closed: the context takes it down with it
+        left_open.issue(0, topk[work[0]])
     finally:
         if pf is not None:
             pf.close()
