@@ -23,10 +23,10 @@ def test_host_logic_and_oracle_under_sanitizers(tmp_path):
     orc = tmp_path / "liboracle_san.so"
     # the same compiler family for everything: one sanitizer runtime serves the whole process (OpenMP pragmas are left
     # out of this build: the loops they mark run serially)
-    subprocess.check_call(["hipcc", "-x", "c", "-O1", "-std=c99", "-Wno-unknown-pragmas", "-shared", "-fPIC", *SAN, "-o", str(orc),
+    subprocess.check_call(["hipcc", "-x", "c", "-fno-gpu-sanitize", "-O1", "-std=c99", "-Wno-unknown-pragmas", "-shared", "-fPIC", *SAN, "-o", str(orc),
                            os.path.join(ROOT, "oracle", "harvest_oracle.c")])
     exe = tmp_path / "driver"
-    subprocess.check_call(["hipcc", "-x", "c", "-O1", "-g", *SAN, "-I", os.path.join(ROOT, "include"),
+    subprocess.check_call(["hipcc", "-x", "c", "-fno-gpu-sanitize", "-O1", "-g", *SAN, "-I", os.path.join(ROOT, "include"),
                            os.path.join(ROOT, "tests", "sanitize", "driver.c"), "-x", "none", "-o", str(exe), str(lib), str(orc),
                            f"-Wl,-rpath,{tmp_path}"])
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
