@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
+    ap.add_argument("--no-profile", action="store_true",
+                    help="kv_decode only: no timing events on the gather launches (per-kernel figures are then absent)")
     ap.add_argument("--fetch-layers", type=int, default=1,
                     help="variant: every step fetches this many consecutive layers with one harvest_fetch_kv_layers call "
                          "(must divide --layers); isolation and graph legs are skipped")
@@ -55,6 +57,8 @@ def parse():
                     help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     args = ap.parse_args()
+    if args.no_profile:
+        args.no_isolation = True
     if args.fetch_layers > 1:
         if args.layers % args.fetch_layers or args.head_major:
             ap.error("--fetch-layers must divide --layers and excludes --head-major")
@@ -348,6 +352,15 @@ def bench_prefetch(eng, wl, topk, staging, ptrs, L, E, chunk, fetch_s_per_layer,
     return res
 
 
+def no_nan(x):
+    """JSON has no NaN: figures that were not measured (--no-profile) are reported as null."""
+    if isinstance(x, dict):
+        return {k: no_nan(v) for k, v in x.items()}
+    if isinstance(x, list):
+        return [no_nan(v) for v in x]
+    return None if isinstance(x, float) and x != x else x
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -378,7 +391,7 @@ def main():
     n_cache_slots = int(wl.resident.sum()) + (0 if args.no_isolation else all_cache_slack)
     shared_bytes = n_cache_slots * (-(-(2 * chunk * args.layers) // 4096) * 4096) if args.shared_cache else 0
     eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack, shared=args.shared_cache),
-                    profile=True, host_wgs=args.host_wgs, shared_cache_bytes=shared_bytes)
+                    profile=not args.no_profile, host_wgs=args.host_wgs, shared_cache_bytes=shared_bytes)
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
@@ -443,8 +456,8 @@ def main():
     hbm_payload = (d["n_local"] + d["n_cache"]) * 2 * chunk * FL
     host_payload = d["n_host"] * 2 * chunk * FL
     value = 2 * payload / sec / 1e9
-    hbm_ms = pr.hbm_ms / max(1, pr.hbm_launches)
-    host_ms = pr.host_ms / max(1, pr.host_launches)
+    hbm_ms = pr.hbm_ms / max(1, pr.hbm_launches) if pr.hbm_launches else float("nan")
+    host_ms = pr.host_ms / max(1, pr.host_launches) if pr.host_launches else float("nan")
     hbm_alg_bytes = 2 * hbm_payload / max(1, pr.hbm_launches)     # read + write, per launch
     host_bytes = host_payload / max(1, pr.host_launches)
     hbm_gbs = hbm_alg_bytes / (hbm_ms * 1e-3) / 1e9
@@ -625,7 +638,7 @@ def main():
         "cpu_baseline": cpu_baseline,
     }
     eng.close()
-    print(json.dumps(out), flush=True)
+    print(json.dumps(no_nan(out)), flush=True)
 
 
 if __name__ == "__main__":
