@@ -417,7 +417,7 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 // max_req bounds the number of requests either list can hold; dst_base: where plane p of the working layout starts.
 // n_rep > 1 gathers n_rep consecutive layers from the same two lists (they name slots, and an object has the same slot
 // in every layer): repetition r reads layer_stride(tier) * r further into every pool and writes dst_step * r further
-// into the destination.  The host-tier gathers of all repetitions queue up behind each other on the side stream, so
+// into the destination.  The host-tier gathers of all repetitions queue up behind each other on one stream, so
 // the link never waits for a join between layers.
 int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
                    uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr, uint32_t n_rep = 1,
@@ -439,11 +439,18 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     // fills the chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
     uint64_t max_tiles = max_req * tpc_hbm;
     uint64_t want = max_tiles;
+    // Which of the two gathers stays on the caller's stream: crossing to the side stream and back costs some 15 us each
+    // way, so the one that takes longer - by the same report: host bytes at PCIe rate against HBM bytes at HBM rate,
+    // about 1 : 48 per request - stays, and the short one takes the detour inside the long one's shadow.
+    bool host_stays = host_tier;
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
+        uint64_t seen_host = *(volatile uint32_t *)&ss->h_feedback[HARVEST_N_CLASSES + cls];
         uint64_t guess = (seen + seen / 16 + 8) * tpc_hbm;
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
+        host_stays = host_tier && seen_host * 48 > seen;
     }
+    hipStream_t s_host = host_stays ? ss->s : ss->side, s_hbm = host_stays ? ss->side : ss->s;
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     for (uint32_t r = 0; r < n_rep; ++r) {
         for (uint32_t p = 0; p < 2; ++p) {
@@ -460,19 +467,20 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         if (host_tier) {             // first, so that the long PCIe transfer starts before the CUs fill up
             const Rec *recs = (const Rec *)ss->host_recs;
             const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
+            uint32_t *fb = ss->d_feedback + HARVEST_N_CLASSES + cls;
             dim3 g(ctx->host_grid);
             if (hm) {
                 auto kernel = planes == 2 ? gather_hm_host<2> : gather_hm_host<1>;
                 if (pc)
-                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga, *hm);
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, *hm, fb);
                 else
-                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga, *hm);
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, *hm, fb);
             } else {
                 auto kernel = planes == 2 ? gather_host<2> : gather_host<1>;
                 if (pc)
-                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, pc, pd, 0, recs, n_req, ga);
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, fb);
                 else
-                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, ss->side, recs, n_req, ga);
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, fb);
             }
             HIP_TRY(hipGetLastError());
         }
@@ -480,16 +488,16 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         const uint32_t *n_req = (const uint32_t *)(cnt + C_HBM_REQ);
         if (hm) {
             if (pa)
-                hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0, recs, n_req,
+                hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req,
                                       ga, *hm, ss->d_feedback + cls);
             else
-                hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, recs, n_req, ga, *hm,
+                hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, recs, n_req, ga, *hm,
                                    ss->d_feedback + cls);
         } else if (pa)
-            hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, pa, pb, 0, recs, n_req, ga,
+            hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req, ga,
                                   ss->d_feedback + cls);
         else
-            hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, ss->s, recs, n_req, ga,
+            hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, recs, n_req, ga,
                                ss->d_feedback + cls);
         HIP_TRY(hipGetLastError());
         if (profile) {

@@ -529,11 +529,13 @@ __device__ inline HostSub host_sub(const Rec *__restrict__ recs, uint64_t g, uin
 
 template <int PLANES>
 __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                                  GatherArgs a)
+                                                  GatherArgs a, uint32_t *feedback)
 {
     constexpr int U = HOST_LOADS / PLANES;                     // sub-tiles per step
     uint32_t spc = a.tiles_per_chunk;                          // 4 KiB sub-tiles per chunk
-    uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
+    uint32_t n_req = *n_req_ptr;
+    if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = n_req;      // as in gather: a hint for the host
+    uint64_t n_sub = (uint64_t)n_req * spc;
     uint64_t n_steps = (n_sub + U - 1) / U;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     uint32_t tid = threadIdx.x;
@@ -562,10 +564,12 @@ __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, 
 // computation serves both.
 template <int PLANES>
 __global__ __launch_bounds__(WG) void gather_hm_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                                     GatherArgs a, HmArgs h)
+                                                     GatherArgs a, HmArgs h, uint32_t *feedback)
 {
     uint32_t spc = a.tiles_per_chunk;
-    uint64_t n_sub = (uint64_t)(*n_req_ptr) * spc;
+    uint32_t n_req = *n_req_ptr;
+    if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = n_req;
+    uint64_t n_sub = (uint64_t)n_req * spc;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     uint32_t tid = threadIdx.x;
     uint32_t row_units = h.n_heads * h.upr;                    // one token: all heads
