@@ -187,3 +187,22 @@ def test_shared_cache_pool_real_shapes():
         assert st.shared_free_runs == len(runs) and st.shared_granules_free == sum(l for _, l in runs)
     finally:
         eh.close(); eo.close()
+
+
+def test_config2_at_its_maximum_lengths():
+    """All four sequences at the upper end of the length range (131 072 tokens): 32 768 blocks, 2 GiB of payload per
+    fetch - the largest single fetch the configuration can ask for."""
+    say("config 2, maximum lengths")
+    wl = W.kv_decode(seed=1, n_layers=1, min_len=131072, max_len=131072, n_steps=2)
+    assert int(sum(len(t) for t in wl.tables)) == 4 * 8192 + 4
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(2):
+            got = rh.fetch(0)
+            say(f"  step {t}: comparing {got[3]['n_requests']} blocks")
+            P.assert_kv_equal(ro.fetch(0), got, f"maximum lengths step {t}")
+            ro.append(t); rh.append(t)
+        assert got[3]["n_requests"] == 32772 and got[3]["n_cache"] > 20000 and got[3]["n_host"] > 8000
+    finally:
+        eh.close(); eo.close()
