@@ -1,0 +1,46 @@
+"""bench.py's command line: what can be checked without a GPU (CPU), and the shape of its one JSON line (GPU)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BENCH = os.path.join(ROOT, "bench.py")
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, BENCH, "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_help_lists_the_contract_flags():
+    r = subprocess.run([sys.executable, BENCH, "--help"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0
+    for flag in ("--gpus", "--steps", "--warmup"):
+        assert flag in r.stdout
+
+
+@pytest.mark.gpu
+def test_one_json_line_with_roofline_and_cpu_baseline():
+    print("bench contract", flush=True)
+    r = subprocess.run([sys.executable, BENCH, "--steps", "12", "--warmup", "2", "--layers", "2", "--iso-steps", "4",
+                        "--graph-steps", "4"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 12 and out["warmup"] == 2 and out["unit"] == "GB/s" and out["dtype"] == "u8"
+    assert out["vs_baseline"] is None and out["data"] == "synthetic" and "workload" in out["config"]
+    rf = out["roofline"]
+    assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert rf["launches"] == 12 and 0 < rf["frac"] < 1
+    cb = out["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
+    assert out["bit_exact"] is True
+    assert out["value"] > 0 and abs(out["ms_per_step"] - 2 * out["config"]["payload_bytes_per_step"] / out["value"] / 1e6) \
+        < 0.02 * out["ms_per_step"]
