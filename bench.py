@@ -365,7 +365,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         log(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); the path has no collectives - "
-            "see DESIGN.md for how it would shard.")
+            "objects are independent, so several GPUs would each run this same fetch over their own share.")
         sys.exit(2)
     import numpy as np
     import torch
