@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
+    ap.add_argument("--placement", default="shuffled", choices=["shuffled", "in_sequence_order"],
+                    help="kv_decode: order in which the resident blocks were placed (shuffled = scattered over the cache "
+                         "tier, the default; in_sequence_order = a sequence's blocks are neighbours)")
     ap.add_argument("--no-profile", action="store_true",
                     help="kv_decode only: no timing events on the gather launches (per-kernel figures are then absent)")
     ap.add_argument("--fetch-layers", type=int, default=1,
@@ -381,7 +384,7 @@ def main():
     n_total = args.warmup + args.steps + args.graph_steps
     t0 = time.time()
     kv_shape = W.KVShape(n_layers=args.layers, elt_bytes=args.kv_elt_bytes)
-    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape)
+    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
     sh = wl.shape
     chunk = sh.chunk_bytes
     n_blocks0 = int(sum(len(t) for t in wl.tables))
@@ -491,7 +494,7 @@ def main():
         from oracle.engine import OracleEngine
         layer = dd.first_layer(dd.t)
         ncores = len(os.sched_getaffinity(0))
-        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape)
+        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
         eo = OracleEngine(kv=S.kv_spec(wl1, cache_slack=0 if args.no_isolation else all_cache_slack), kv_layers=[layer],
                           threads=ncores)
         ro = S.KVRun(eo, wl1)
@@ -615,7 +618,7 @@ def main():
                                + ("" if args.kv_elt_bytes == 2 else f" -- VARIANT: {args.kv_elt_bytes}-byte KV elements, "
                                   f"{chunk // 1024} KiB blocks"),
                    "working_layout": "head-major" if args.head_major else "token-major",
-                   "layers_per_fetch": args.fetch_layers,
+                   "layers_per_fetch": args.fetch_layers, "placement": args.placement,
                    "cache_tier": "shared pool of best-fit segments" if args.shared_cache else "equal-size slots",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},

@@ -200,8 +200,13 @@ def kv_tiny(seed: int = 0, fill_mode: int = FILL_NORMAL) -> KVWorkload:
 
 def kv_decode(seed: int = 0, n_layers: int = 32, n_seq: int = 4, min_len: int = 32768, max_len: int = 131072,
               p_cache: float = 0.7, n_steps: int = 200, fill_mode: int = FILL_NORMAL,
-              shape: KVShape | None = None) -> KVWorkload:
+              shape: KVShape | None = None, placement: str = "shuffled") -> KVWorkload:
     """Long-context decode: sequence lengths ~U[min_len, max_len], blocks i.i.d. Bernoulli(p_cache) in the cache tier.
+
+    ``placement``: the order in which the resident blocks are placed at start, which (slots being handed out lowest
+    first) decides where they sit in the cache tier - "shuffled" (default: a seeded permutation, so a sequence's blocks
+    are scattered over the pool) or "in_sequence_order" (sequence after sequence in block order, as a prefill that
+    offloads one prompt after the other would leave them: a sequence's blocks are neighbours).
 
     Every sequence ends in an open tail block (local tier) that decode steps append to.  A step appends one token
     per sequence; a tail that becomes full is closed and a new one opened, so the blocks opened during ``n_steps``
@@ -224,7 +229,12 @@ def kv_decode(seed: int = 0, n_layers: int = 32, n_seq: int = 4, min_len: int = 
                 future[s].append(nxt); nxt += 1
     total = nxt
     resident = rng(seed, 12).random(total) < p_cache
-    order = rng(seed, 13).permutation(C).astype(np.int32)
+    if placement == "shuffled":
+        order = rng(seed, 13).permutation(C).astype(np.int32)
+    elif placement == "in_sequence_order":
+        order = np.concatenate([t[:-1] for t in tables]).astype(np.int32)
+    else:
+        raise ValueError(placement)
     place_order = order[resident[order]]
     return KVWorkload(shape=shape, seed=seed, seq_lens=lens, n_objects=total, tables=tables, has_tails=True,
                       future_blocks=[np.array(f, np.int32) for f in future],
