@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """The native libraries are loaded as built; only when none is there at all (a fresh checkout) are they built here."""
+    from paper_2602_00328_amd import _build
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library(verbose=False)
+
+
 def _has_gpu():
     try:
         import torch
