@@ -34,12 +34,13 @@
  *     after the call returns (place: on the same stream; other streams may
  *     still see the older, equally correct, host entry for a while).
  *   - Return value: HARVEST_OK (0) or a negative harvest_status.  A fetch never
- *     fails because of residency (Section 3.1: correctness never depends on
- *     the cache tier).
+ *     fails because of residency (Section 3.1: what the cache tier holds or
+ *     has lost changes no result).
  *   - No call mutates the directory except register / place / revoke /
  *     evict(DEMOTE).  In particular a fetch never promotes an object (Section
- *     4.3: on a miss the runtime does not fetch into the cache tier), and the
- *     library never writes back on its own (Section 3.1: no dirty tracking).
+ *     4.3: a miss leaves the object where it is), and the library never writes
+ *     back on its own (Section 3.1: which copies are stale is the application's
+ *     business).
  *   - A context is not thread safe; operations that touch the same object from
  *     different streams must be ordered by the caller.
  *
