@@ -179,6 +179,18 @@ int harvest_destroy(harvest_ctx *ctx);
 int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_slot, int tier,
                      harvest_revoke_cb cb, void *user, harvest_obj *out_ids);
 
+/* The paper's own three calls (Section 3.2: an allocation in the cache tier that may fail, its release, and a callback
+ * per allocation), for one object each, expressed through the calls above:
+ *   harvest_alloc       = harvest_place of one object; returns its status (ENOSPC: no room, the object stays on the
+ *                         host; ELOST; OK also when the object already is in HBM).  The size is the class's object size;
+ *                         there are no peers to choose between, so the paper's hints have no counterpart.
+ *   harvest_free        = the application gives the object's cache-tier copy back: exactly harvest_revoke (invalidate,
+ *                         drain, free), except that no callback is invoked - nobody needs telling.
+ *   harvest_register_cb = sets (or, with cb == NULL, clears) the callback harvest_revoke invokes for this object. */
+int harvest_alloc(harvest_ctx *ctx, int cls, harvest_obj id, void *stream);
+int harvest_free(harvest_ctx *ctx, int cls, harvest_obj id);
+int harvest_register_cb(harvest_ctx *ctx, int cls, harvest_obj id, harvest_revoke_cb cb, void *user);
+
 /* Reconstruction of lost objects (Section 3.1: a lossy object that is revoked is lost and rebuilt later; Section 3.2:
  * the revocation callback is where the application starts that).  Each listed object must be lost (tier
  * HARVEST_NONE); it gets the lowest free local slot and a new generation, and the caller then writes the rebuilt

@@ -69,6 +69,9 @@ SYMBOLS = {
     "harvest_restore": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
     "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
+    "harvest_alloc": (ctypes.c_int, [vp, ctypes.c_int, u32, vp]),
+    "harvest_free": (ctypes.c_int, [vp, ctypes.c_int, u32]),
+    "harvest_register_cb": (ctypes.c_int, [vp, ctypes.c_int, u32, REVOKE_CB, vp]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
     "harvest_fetch_kv_layers": (ctypes.c_int, [vp, u32, u32, vp, vp, u32, u32, vp, vp, u64, vp, u64, vp]),
     "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
@@ -247,6 +250,22 @@ class Harvest:
         _chk(lib.harvest_lookup(self.h, cls, int(obj), ctypes.byref(t), ctypes.byref(s), ctypes.byref(g),
                                 ctypes.byref(hs)), "harvest_lookup")
         return t.value, s.value, g.value, hs.value
+
+    def alloc(self, cls, obj, stream=None) -> int:
+        """harvest_alloc: the status (OK, ENOSPC, ELOST) rather than an exception - a full cache tier is no error."""
+        sp = vp(0) if self.no_device else _stream_ptr(stream)
+        rc = lib.harvest_alloc(self.h, cls, int(obj), sp)
+        if rc not in (OK, ENOSPC, ELOST):
+            raise HarvestError(rc, "harvest_alloc")
+        return rc
+
+    def free(self, cls, obj):
+        _chk(lib.harvest_free(self.h, cls, int(obj)), "harvest_free")
+
+    def register_cb(self, cls, obj, enabled=True):
+        """Attach the context's logging callback to the object, or (enabled=False) clear its callback."""
+        cb = self._cb if enabled else ctypes.cast(None, REVOKE_CB)
+        _chk(lib.harvest_register_cb(self.h, cls, int(obj), cb, None), "harvest_register_cb")
 
     def restore(self, cls, ids):
         ids = np.ascontiguousarray(ids, dtype=np.uint32)

@@ -830,7 +830,7 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     return mark_last(ctx, ss);
 }
 
-int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n)
+static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, bool notify)
 {
     int rc = check_class(ctx, cls);
     if (rc) return rc;
@@ -891,7 +891,37 @@ int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n
     }
     // 4. notify (outside the lock: a callback may call back into the library)
     for (size_t i = 0; i < hit.size(); ++i)
-        if (cbs[i].first) cbs[i].first(cls, hit[i], cbs[i].second);
+        if (notify && cbs[i].first) cbs[i].first(cls, hit[i], cbs[i].second);
+    return HARVEST_OK;
+}
+
+int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n)
+{
+    return revoke_impl(ctx, cls, ids, n, true);
+}
+
+// The three calls of the paper's API (Section 3.2), one object each, on top of the calls above.
+int harvest_alloc(harvest_ctx *ctx, int cls, harvest_obj id, void *stream)
+{
+    int status = HARVEST_OK;
+    int rc = harvest_place(ctx, cls, &id, 1, stream, &status);
+    return rc ? rc : status;
+}
+
+int harvest_free(harvest_ctx *ctx, int cls, harvest_obj id)
+{
+    return revoke_impl(ctx, cls, &id, 1, false);       // the application's own decision: nobody to notify
+}
+
+int harvest_register_cb(harvest_ctx *ctx, int cls, harvest_obj id, harvest_revoke_cb cb, void *user)
+{
+    int rc = check_class(ctx, cls);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[cls];
+    if (id >= c.n_objects) return HARVEST_ENOENT;
+    c.cb[id] = cb;
+    c.cb_user[id] = user;
     return HARVEST_OK;
 }
 

@@ -267,3 +267,37 @@ def test_shared_pool_host_logic_matches_the_oracle_under_random_operations(seed)
     for c in oc.values():
         c.close()
     pool.close()
+
+
+def test_the_papers_three_calls():
+    """harvest_alloc / harvest_free / harvest_register_cb (Section 3.2) against the oracle's place and revoke."""
+    sp = spec(n_cache=2)
+    h = B.Harvest(kv=sp, flags=B.FLAG_NO_DEVICE)
+    oc = O.OracleClass(sp.n_layers, sp.n_planes, sp.chunk_bytes, sp.max_objects, sp.n_host_slots, 2, sp.n_local_slots)
+    ids = h.register(B.KV, 4, [5, 6, 7, 8], B.HOST)
+    oc.register(4, [5, 6, 7, 8], O.HOST)
+    want = [int(oc.place([i])[0]) for i in ids]
+    got = [h.alloc(B.KV, i) for i in ids]
+    assert got == want == [B.OK, B.OK, B.ENOSPC, B.ENOSPC]
+    for i in ids:
+        assert oc.lookup(i) == h.lookup(B.KV, i)
+    h.register_cb(B.KV, ids[1], enabled=False)                  # object 1 loses its callback
+    h.free(B.KV, ids[0])                                        # given back by the application: no callback
+    oc.revoke([ids[0]])
+    assert h.revoked_log == [] and oc.lookup(ids[0]) == h.lookup(B.KV, ids[0]) == (O.HOST, -1, 2, 5)
+    h.revoke(B.KV, [ids[1]]); oc.revoke([ids[1]])
+    assert h.revoked_log == [] and oc.lookup(ids[1]) == h.lookup(B.KV, ids[1])
+    assert h.alloc(B.KV, ids[2]) == B.OK and h.alloc(B.KV, ids[3]) == B.OK      # the freed slots are taken again
+    oc.place([ids[2], ids[3]])
+    h.register_cb(B.KV, ids[2])
+    h.revoke(B.KV, [ids[2], ids[3]]); oc.revoke([ids[2], ids[3]])
+    assert h.revoked_log == [(B.KV, int(ids[2])), (B.KV, int(ids[3]))]
+    for i in ids:
+        assert oc.lookup(i) == h.lookup(B.KV, i)
+    with pytest.raises(B.HarvestError) as e:
+        h.free(B.KV, 99)
+    assert e.value.code == B.ENOENT
+    with pytest.raises(B.HarvestError) as e:
+        h.register_cb(B.KV, 99)
+    assert e.value.code == B.ENOENT
+    h.close(); oc.close()

@@ -296,6 +296,31 @@ def test_head_major_fetch(heads, dim, tokens, elt):
         eh.close(); eo.close()
 
 
+# ---- the paper's own three calls ---------------------------------------------------------------------------------
+
+def test_alloc_and_free_by_their_paper_names():
+    say("harvest_alloc / harvest_free / harvest_register_cb")
+    wl = W.kv_decode(seed=26, n_layers=2, n_seq=2, min_len=200, max_len=400, p_cache=0.0, n_steps=1, fill_mode=W.FILL_TAG)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=5)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        blocks = rh.tables[0][:7]
+        st = [eh.h.alloc(S.KV, b) for b in blocks]                 # five cache slots: the last two stay on the host
+        assert st == [0, 0, 0, 0, 0, -2, -2] and list(eo.place(S.KV, blocks)) == st
+        P.assert_kv_equal(ro.fetch(1), rh.fetch(1), "after harvest_alloc")
+        eh.h.register_cb(S.KV, blocks[1], enabled=False)
+        eh.h.free(S.KV, blocks[0]); eo.revoke(S.KV, [blocks[0]])
+        eh.revoke(S.KV, [blocks[1], blocks[2]]); eo.revoke(S.KV, [blocks[1], blocks[2]])
+        assert [i for _c, i in eh.h.revoked_log] == [int(blocks[2])]      # freed: no callback; cleared: no callback
+        a, b = ro.fetch(0), rh.fetch(0)
+        P.assert_kv_equal(a, b, "after harvest_free")
+        assert b[3]["n_cache"] == 2
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="alloc / free")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- a one-plane KV class (a latent cache, say): every kernel's one-plane instantiation -------------------------
 
 def test_one_plane_kv_class():
