@@ -323,7 +323,8 @@ int release_after(Staging *st, hipStream_t s)
 
 uint32_t tiles_per_chunk(uint64_t chunk_bytes, uint32_t tile) { return (uint32_t)((chunk_bytes + tile - 1) / tile); }
 
-constexpr uint32_t MAX_GRID = 0x7FFFFFFFu;
+// one workgroup per tile up to here; beyond, the kernels loop.  Kept below 2^32 threads per launch dimension.
+constexpr uint32_t MAX_GRID = 0xFFFFFFFFu / WG;
 
 uint32_t grid_for(uint64_t n_tiles, uint32_t max_grid)
 {
