@@ -34,3 +34,19 @@ def library_is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB_PATH)
     return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+EXAMPLE_SRC = os.path.join(HERE, "examples", "kv_fetch.c")
+EXAMPLE_BIN = os.path.join(HERE, "examples", "kv_fetch")
+
+
+def build_example() -> str:
+    """The plain-C user of the ABI (no Python in its process); links the library built above."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-x", "hip", "--offload-arch=gfx950", "-O1", "-Wno-unused-command-line-argument", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", "-I", os.path.join(os.path.dirname(HERE), "include"), EXAMPLE_SRC, "-x", "none",
+           "-o", EXAMPLE_BIN, "-L", HERE, "-l:libharvest.so", "-Wl,-rpath,$ORIGIN/.."]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on the example ({res.returncode}):\n{res.stderr}")
+    return EXAMPLE_BIN

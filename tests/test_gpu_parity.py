@@ -592,3 +592,15 @@ def test_plain_copy_and_profile_counters():
 def test_smoke_entry():
     say("smoke")
     P.smoke()
+
+
+# ---- the ABI from plain C, no Python in the process ---------------------------------------------------------------
+
+def test_plain_c_example_runs():
+    import os
+    import subprocess
+    say("plain-C example")
+    exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2602_00328_amd", "examples", "kv_fetch")
+    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0 and "kv_fetch example: ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
