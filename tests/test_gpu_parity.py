@@ -601,6 +601,8 @@ def test_plain_c_example_runs():
     import subprocess
     say("plain-C example")
     exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2602_00328_amd", "examples", "kv_fetch")
-    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    if not os.path.exists(exe):                          # a fresh checkout: built here, otherwise used as built
+        from paper_2602_00328_amd import _build
+        _build.build_example()
     r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0 and "kv_fetch example: ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
