@@ -178,6 +178,10 @@ def test_expert_fetch_small():
             a = eo.fetch_experts(1, topk, n_staging)
             b = eh.fetch_experts(1, topk, n_staging)
             P.assert_experts_equal(a, b, f"staging {n_staging}")
+        none = np.zeros((0, 2), np.int32)                                      # a batch without tokens: nothing is routed
+        a, b = eo.fetch_experts(2, none, 16), eh.fetch_experts(2, none, 16)
+        P.assert_experts_equal(a, b, "no tokens")
+        assert b[4]["n_requests"] == 0 and all(x is None for x in b[0])
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
     finally:
         eh.close(); eo.close()
@@ -294,6 +298,31 @@ def test_head_major_fetch(heads, dim, tokens, elt):
         assert b[3]["n_invalid"] > 0
     finally:
         eh.close(); eo.close()
+
+
+# ---- two contexts alive on the device at once --------------------------------------------------------------------
+
+def test_two_contexts_side_by_side():
+    say("two contexts")
+    wl_a = W.kv_decode(seed=27, n_layers=2, n_seq=2, min_len=300, max_len=700, n_steps=6)
+    wl_b = W.kv_decode(seed=28, n_layers=3, n_seq=3, min_len=200, max_len=500, n_steps=6,
+                       shape=W.KVShape(n_layers=3, n_kv_heads=4, head_dim=64))
+    eo_a, eh_a = P.make_engines(wl_a, poison=True)
+    eo_b, eh_b = P.make_engines(wl_b, poison=True)
+    try:
+        ra_o, ra_h, rb_o, rb_h = S.KVRun(eo_a, wl_a), S.KVRun(eh_a, wl_a), S.KVRun(eo_b, wl_b), S.KVRun(eh_b, wl_b)
+        for t in range(6):
+            ha, hb = ra_h.fetch_begin(t % 2), rb_h.fetch_begin(t % 3)            # both contexts have work in flight
+            if t == 3:
+                x, y = ra_o.revoke_quarter(t), ra_h.revoke_quarter(t)            # a revocation in one of them
+                assert np.array_equal(x[0], y[0])
+            P.assert_kv_equal(ra_o.fetch(t % 2), eh_a.fetch_end(ha), f"context a step {t}", counts=t != 3)
+            P.assert_kv_equal(rb_o.fetch(t % 3), eh_b.fetch_end(hb), f"context b step {t}")
+            ra_o.append(t); ra_h.append(t); rb_o.append(t); rb_h.append(t)
+        P.assert_dirs_equal(eo_a, eh_a, S.KV, wl_a.n_objects)
+        P.assert_dirs_equal(eo_b, eh_b, S.KV, wl_b.n_objects)
+    finally:
+        eh_a.close(); eo_a.close(); eh_b.close(); eo_b.close()
 
 
 # ---- the paper's own three calls ---------------------------------------------------------------------------------
