@@ -41,8 +41,10 @@
  *     4.3: a miss leaves the object where it is), and the library never writes
  *     back on its own (Section 3.1: which copies are stale is the application's
  *     business).
- *   - A context is not thread safe; operations that touch the same object from
- *     different streams must be ordered by the caller.
+ *   - Calls on one context may come from several threads: each call runs under
+ *     the context's lock.  A prefetcher belongs to one thread at a time.
+ *     Operations that touch the same object from different streams must be
+ *     ordered by the caller.
  *
  * Shared cache pool (Section 3.3: the controller allocates best-fit among free
  * segments).  When harvest_config.d_shared_cache is set, every class whose

@@ -229,6 +229,30 @@ bool is_capturing(hipStream_t s)
     return st != hipStreamCaptureStatusNone;
 }
 
+// Releases what a caller stream's state owns (any part of it may be missing); the stream's work must have finished.
+void free_stream_state(StreamState *ss)
+{
+    if (ss->side) (void)hipStreamDestroy(ss->side);
+    for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) if (e) (void)hipEventDestroy(e);
+    (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
+    (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
+    (void)hipFree(ss->ctl_buf);
+    if (ss->h_feedback) (void)hipHostFree(ss->h_feedback);
+}
+
+int init_stream_state(StreamState *ss)
+{
+    HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
+    for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last, &ss->ctl_done, &ss->pre_ctl })
+        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
+    HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
+    memset(ss->h_feedback, 0, 64);
+    HIP_TRY(hipHostGetDevicePointer((void **)&ss->d_feedback, ss->h_feedback, 0));
+    return HARVEST_OK;
+}
+
 int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
 {
     hipStream_t s = (hipStream_t)stream;
@@ -240,14 +264,10 @@ int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
     }
     auto ss = std::make_unique<StreamState>();
     ss->s = s;
-    HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
-    for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last, &ss->ctl_done, &ss->pre_ctl })
-        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
-    HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
-    HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
-    HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
-    memset(ss->h_feedback, 0, 64);
-    HIP_TRY(hipHostGetDevicePointer((void **)&ss->d_feedback, ss->h_feedback, 0));
+    if (int rc = init_stream_state(ss.get())) {
+        free_stream_state(ss.get());
+        return rc;
+    }
     *out = ss.get();
     ctx->streams[s] = std::move(ss);
     return HARVEST_OK;
@@ -510,17 +530,6 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     HIP_TRY(hipEventRecord(ss->join, ss->side));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
     return mark_last(ctx, ss);
-}
-
-// Releases what a caller stream's state owns; the stream's work must have finished.
-void free_stream_state(StreamState *ss)
-{
-    (void)hipStreamDestroy(ss->side);
-    for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) (void)hipEventDestroy(e);
-    (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
-    (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
-    (void)hipFree(ss->ctl_buf);
-    (void)hipHostFree(ss->h_feedback);
 }
 
 int check_class(harvest_ctx *ctx, int cls)
@@ -789,6 +798,8 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     if ((rc = device_guard(ctx))) return rc;
     // directory edits go through the control stream and pinned staging: they cannot be recorded into a graph
     if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;
+    StreamState *ss = nullptr;                     // before the mirror changes: a failure here leaves nothing half done
+    if (!ctx->no_device && (rc = get_stream(ctx, stream, &ss))) return rc;
     std::vector<uint32_t> moved;
     std::vector<Item> items;
     for (uint32_t i = 0; i < n; ++i) {
@@ -809,8 +820,6 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
         if (status) status[i] = st;
     }
     if (ctx->no_device || moved.empty()) return HARVEST_OK;
-    StreamState *ss;
-    if ((rc = get_stream(ctx, stream, &ss))) return rc;
     size_t bytes = items.size() * sizeof(Item);
     if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
     Staging *st;
@@ -1059,7 +1068,10 @@ int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32
     if (hipStreamCreateWithFlags(&pf->fetch, hipStreamNonBlocking) != hipSuccess) return fail();
     for (hipEvent_t *e : { &pf->ready[0], &pf->ready[1], &pf->freed[0], &pf->freed[1], &pf->dep })
         if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return fail();
-    ctx->prefetchers.push_back(pf.get());
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        ctx->prefetchers.push_back(pf.get());
+    }
     *out = pf.release();
     return HARVEST_OK;
 }
@@ -1189,6 +1201,8 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     }
     if ((rc = device_guard(ctx))) return rc;
     if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;     // as for harvest_place
+    StreamState *ss = nullptr;
+    if (!ctx->no_device && (rc = get_stream(ctx, stream, &ss))) return rc;
     const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     std::vector<Item2> items;
@@ -1236,8 +1250,6 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         }
     }
     if (ctx->no_device) return HARVEST_OK;
-    StreamState *ss;
-    if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if (!items.empty()) {
         size_t bytes = items.size() * sizeof(Item2);
         if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
@@ -1320,11 +1332,6 @@ int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *str
 {
     if (!d_dst || !d_src || bytes % 16 || (((uint64_t)d_dst | (uint64_t)d_src) & 15)) return HARVEST_EINVAL;
     if (bytes == 0) return HARVEST_OK;
-    int dev = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    int n_cu = 0;
-    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    (void)n_cu;
     uint64_t n_tiles = (bytes + TILE_HBM - 1) / TILE_HBM;
     uint32_t grid = grid_for(n_tiles, MAX_GRID);
     hipLaunchKernelGGL(plain_copy, dim3(grid), dim3(WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,

@@ -88,7 +88,7 @@ class HipEngine:
     def revoke(self, cls, ids):
         n0 = len(self.h.revoked_log)
         self.h.revoke(cls, ids)
-        return [i for _c, i in self.h.revoked_log[n0:]]
+        return [i for c, i in self.h.revoked_log[n0:] if c == cls]      # another thread may be revoking the other class
 
     # ---- data path -------------------------------------------------------------------------------------------
     def has_layer(self, layer):

@@ -259,6 +259,63 @@ def test_revocation_stress_two_streams(overlap_revoke):
         eh.close(); eo.close()
 
 
+def test_two_threads_drive_one_context():
+    """One host thread per class, each on its own stream, revoking and re-placing as it goes: every call runs under the
+    context's lock, a revocation of one class drains the other class's stream too, and no result changes."""
+    import threading
+    say("two threads")
+    n_steps = 120
+    wl = W.kv_decode(seed=29, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=n_steps)
+    ex = W.expert_offload(seed=29, shape=W.ExpertShape(n_layers=2, n_experts=16, d_model=64, d_ff=100), n_tokens=64)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    errors = []
+
+    def kv_side():
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(n_steps):
+            P.assert_kv_equal(ro.fetch(t % 2), rh.fetch(t % 2), f"threads kv step {t}")
+            if t % 10 == 0 and t > 0:
+                a, b = ro.revoke_quarter(t), rh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+            if t % 10 == 5:
+                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+            ro.append(t); rh.append(t)
+
+    def expert_side():
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        for t in range(n_steps):
+            P.assert_experts_equal(xo.fetch(t, t % 2), xh.fetch(t, t % 2), f"threads experts step {t}")
+            if t % 7 == 0 and t > 0:
+                a, b = xo.revoke_quarter(t), xh.revoke_quarter(t)
+                assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+            if t % 7 == 3:
+                assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
+
+    def guarded(f):
+        def run():
+            try:
+                f()
+            except BaseException as e:                                     # reported by the main thread
+                errors.append(e)
+        return run
+
+    try:
+        threads = [threading.Thread(target=guarded(f)) for f in (kv_side, expert_side)]
+        for th in threads:
+            th.start()
+        for th in threads:
+            th.join(100)
+            assert not th.is_alive(), "a thread did not finish"
+        if errors:
+            raise errors[0]
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what="threads kv")
+        P.assert_tiers_equal(eo, eh, S.EXPERT, 1, what="threads experts")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- head-major working layout ----------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("heads,dim,tokens,elt", [(8, 128, 16, 2), (8, 128, 16, 1), (3, 24, 4, 2), (1, 8, 1, 2), (5, 104, 48, 2)])
