@@ -103,6 +103,22 @@ struct ClassState {
     uint64_t seg_base = 0, granule = 0, obj_granules = 0, n_granules = 0;
     uint64_t cache_in_use = 0;
     uint64_t *d_dir = nullptr;
+    // duplicate detection within one call without hashing: an object is marked with the number of the call
+    std::vector<uint32_t> stamp;
+    uint32_t epoch = 0;
+
+    void new_call()
+    {
+        if (++epoch == 0) { std::fill(stamp.begin(), stamp.end(), 0u); epoch = 1; }
+        if (stamp.size() < n_objects) stamp.resize(n_objects, 0u);
+    }
+    bool first_time(uint32_t id)               // false: this call has named the object before
+    {
+        if (stamp[id] == epoch) return false;
+        stamp[id] = epoch;
+        return true;
+    }
+
     // host-side statistics
     uint64_t n_placed = 0, n_enospc = 0, n_revoked = 0, n_evicted = 0, n_demoted = 0;
 
@@ -753,10 +769,10 @@ int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t 
     if (n && !ids) return HARVEST_EINVAL;
     std::lock_guard<std::mutex> lk(ctx->mu);
     ClassState &c = ctx->cls[cls];
-    std::unordered_set<uint32_t> seen;
+    c.new_call();
     for (uint32_t i = 0; i < n; ++i) {
         if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
-        if (c.tier[ids[i]] != T_NONE || !seen.insert(ids[i]).second) return HARVEST_EINVAL;
+        if (c.tier[ids[i]] != T_NONE || !c.first_time(ids[i])) return HARVEST_EINVAL;
     }
     if (c.local_free.size() < n) return HARVEST_ENOSPC;
     if ((rc = device_guard(ctx))) return rc;
@@ -1183,14 +1199,14 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     bool demote_flag = flags & HARVEST_EVICT_DEMOTE;
     if (demote_flag && layer >= 0 && c.cfg.n_layers != 1) return HARVEST_EINVAL;
     {
-        std::unordered_set<uint32_t> seen;
+        c.new_call();
         size_t need_cache = 0;
         for (uint32_t i = 0; i < n; ++i) {
             if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
             if (src_block[i] >= src_layer_stride) return HARVEST_EINVAL;
             if (c.tier[ids[i]] == T_NONE) return HARVEST_ELOST;
             if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) need_cache++;
-            if (!seen.insert(ids[i]).second) return HARVEST_EINVAL;
+            if (!c.first_time(ids[i])) return HARVEST_EINVAL;
         }
         if (!c.seg && need_cache > c.cache_free.size()) return HARVEST_ENOSPC;
     }
@@ -1206,6 +1222,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
     uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     std::vector<Item2> items;
+    items.reserve((size_t)n * c.cfg.n_planes * (l1 - l0));
     std::vector<uint32_t> demoted;
     // room for every lossy object that leaves local HBM, taken in request order before anything changes: all or nothing
     std::vector<int64_t> room;
