@@ -471,9 +471,11 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     const bool profile = ctx->profile && !is_capturing(ss->s);        // timing events cannot be recorded into a graph
     const bool host_tier = c.cfg.n_host_slots != 0;
-    // Grid of the HBM-tier gather: one workgroup per tile.  The request count lives on the device, so the grid is sized
-    // from what the previous gather of this class on this stream reported (plus slack), never below a floor that still
-    // fills the chip, never above the bound; the kernel loops if the guess was short, so any size is correct.
+    // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
+    // sized from what the previous gather of this class on this stream reported, never below a floor that still fills the
+    // chip, never above the bound; the kernel loops where the grid is short, so any size is correct.  The guess is
+    // biased low on purpose: surplus workgroups at the end of the grid cost time (6 % of them 1 %, 23 % of them 3.5 %),
+    // a grid 10 to 25 % short costs nothing (the first workgroups take a second tile while the rest still run).
     uint64_t max_tiles = max_req * tpc_hbm;
     uint64_t want = max_tiles;
     // Which of the two gathers stays on the caller's stream: crossing to the side stream and back costs some 15 us each
@@ -483,7 +485,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
         uint64_t seen_host = *(volatile uint32_t *)&ss->h_feedback[HARVEST_N_CLASSES + cls];
-        uint64_t guess = (seen + seen / 16 + 8) * tpc_hbm;
+        uint64_t guess = std::max<uint64_t>(1, seen - seen / 8) * tpc_hbm;
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
         host_stays = host_tier && seen_host * 48 > seen;
     }

@@ -388,7 +388,7 @@ __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint3
 // two-plane class is gathered plane after plane.  The grid's x size is free: with one workgroup per tile the loop body
 // runs once; a smaller grid loops.  `feedback`, when given, is a word of pinned host memory that receives the list
 // length: the host sizes the next launch from it, because workgroups that find no tile are not free (about 0.2 ns
-// each on MI355X).
+// each on MI355X) while a grid somewhat short of the tile count is.
 template <int UNROLL, bool NT>
 __global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
                                              GatherArgs a, uint32_t *feedback)
