@@ -80,3 +80,51 @@ def test_captured_fetch_follows_residency_changes_across_replays():
         replay_and_check("replay 6 (revoked blocks placed again)")
     finally:
         eh.close(); eo.close()
+
+
+def test_captured_expert_fetch_follows_residency_changes_across_replays():
+    """The same for the expert fetch: routing ids, staging buffer and pointer table are fixed in the graph; which experts
+    come from the cache tier and which from the host is read from the directory at every replay."""
+    print("graph capture, experts", flush=True)
+    ex = W.expert_offload(seed=12, shape=W.ExpertShape(n_layers=3, n_experts=16, d_model=64, d_ff=100), n_tokens=64)
+    eo, eh = P.make_engines(None, ex, poison=True)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        dev, sp, layer, n_staging = eh.dev, eh.spec[S.EXPERT], 1, 16
+        topk = ex.routing(0, layer)
+        d_topk = torch.from_numpy(np.ascontiguousarray(topk, dtype=np.int32)).to(dev)
+        staging = torch.zeros(n_staging * sp.chunk_bytes, dtype=torch.uint8, device=dev)
+        ptrs = torch.zeros(sp.n_experts, dtype=torch.int64, device=dev)
+        s = torch.cuda.Stream(dev)
+        with torch.cuda.stream(s):                     # once outside capture: allocates this stream's scratch
+            eh.h.fetch_experts(layer, d_topk, staging, n_staging, ptrs)
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            eh.h.fetch_experts(layer, d_topk, staging, n_staging, ptrs)
+
+        def replay_and_check(what):
+            staging.fill_(0x5A)
+            ptrs.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s):
+                got = eh.fetch_end(("experts", staging, n_staging, ptrs, d_topk))
+            P.assert_experts_equal(eo.fetch_experts(layer, topk, n_staging), got, what)
+            P.assert_experts_equal(eh.fetch_experts(layer, topk, n_staging), got, what + " (eager)")
+            return got[4]
+
+        c1 = replay_and_check("replay 1")
+        in_cache = [i for i in range(layer * 16, layer * 16 + 16) if eh.lookup(S.EXPERT, i)[0] == S.CACHE]
+        assert len(in_cache) >= 2
+        gone = in_cache[:len(in_cache) // 2 + 1]
+        assert eo.revoke(S.EXPERT, gone) == eh.revoke(S.EXPERT, gone) == gone
+        c2 = replay_and_check("replay 2 (cached experts revoked, slots poisoned)")
+        assert c2["n_host"] > c1["n_host"] or not set(gone) & {layer * 16 + int(e) for e in np.unique(topk)}
+        on_host = [i for i in range(layer * 16, layer * 16 + 16) if eh.lookup(S.EXPERT, i)[0] == S.HOST]
+        assert np.array_equal(eo.place(S.EXPERT, on_host), eh.place(S.EXPERT, on_host))
+        replay_and_check("replay 3 (every host expert of the layer placed, as far as slots last)")
+        replay_and_check("replay 4 (unchanged)")
+    finally:
+        eh.close(); eo.close()
