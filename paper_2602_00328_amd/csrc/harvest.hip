@@ -1170,13 +1170,19 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
 {
     if (!ctx) return HARVEST_EINVAL;
     if (ctx->no_device) return HARVEST_ENODEV;
-    std::lock_guard<std::mutex> lk(ctx->mu);
     int rc = device_guard(ctx);
     if (rc) return rc;
-    auto it = ctx->streams.find((hipStream_t)stream);
-    if (it == ctx->streams.end()) return HARVEST_ENOENT;
-    StreamState *ss = it->second.get();
+    StreamState *ss = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        auto it = ctx->streams.find((hipStream_t)stream);
+        if (it == ctx->streams.end()) return HARVEST_ENOENT;
+        ss = it->second.get();
+    }
+    // the wait runs outside the lock, so that another thread can enqueue on its own stream meanwhile; the stream's
+    // state stays where it is until the context (or the prefetcher that owns the stream) is destroyed
     HIP_TRY(hipStreamSynchronize(ss->s));
+    std::lock_guard<std::mutex> lk(ctx->mu);
     uint32_t h[C_N] = { 0 };
     if (ss->fetched) HIP_TRY(hipMemcpy(h, ss->cnt, sizeof h, hipMemcpyDeviceToHost));
     if (counts) {
