@@ -100,6 +100,29 @@ def test_kv_decode_steps_small():
         eh.close(); eo.close()
 
 
+def test_fetch_sizes_that_jump_between_calls():
+    """The gather's grid is sized from what the previous fetch on the stream reported: a fetch far larger than the one
+    before runs on a grid far too short and has to loop, one far smaller finds most of its grid empty."""
+    say("jumping fetch sizes")
+    wl = W.kv_decode(seed=31, n_layers=2, n_seq=3, min_len=12000, max_len=24000, p_cache=0.8, n_steps=1)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        table, nb = rh.table_arrays()
+        assert int(nb.sum()) * wl.shape.chunk_bytes // 4096 > 5 * 16 * 256          # several times the grid's floor
+        tiny = np.minimum(nb, [2, 0, 1]).astype(np.int32)
+        heads, tokens = wl.shape.n_kv_heads, wl.shape.block_tokens
+        caps = np.diff(np.append(rh.seq_dst_block, rh.cap).astype(np.int64)).astype(np.uint32)   # blocks per sequence
+        for i, n in enumerate((tiny, nb, tiny, nb // 2, nb, tiny)):
+            P.assert_kv_equal(eo.fetch_kv(i % 2, table, n, ro.seq_dst_block, ro.cap),
+                              eh.fetch_kv(i % 2, table, n, rh.seq_dst_block, rh.cap), f"token-major call {i}")
+            P.assert_kv_equal(eo.fetch_kv_head_major(i % 2, table, n, ro.seq_dst_block, caps, ro.cap, heads, tokens),
+                              eh.fetch_kv_head_major(i % 2, table, n, rh.seq_dst_block, caps, rh.cap, heads, tokens),
+                              f"head-major call {i}")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- chunk sizes that are not a multiple of the 32 KiB tile -----------------------------------------------------
 
 @pytest.mark.parametrize("heads,dim,tokens,elt", [(1, 8, 1, 2), (3, 8, 16, 2), (8, 129 - 1, 16, 2), (8, 136, 16, 2),
