@@ -59,6 +59,7 @@ def _bind(path):
     L.orc_adopt.argtypes = [vp, u32]
     L.orc_write_local.argtypes = [vp, u32, u32, u32, u64, vp, u64]
     L.orc_place.argtypes = [vp, vp, u32, vp]
+    L.orc_place_from.argtypes = [vp, vp, u32, vp, vp, vp, u64, vp]
     L.orc_revoke.argtypes = [vp, vp, u32, _CB, vp]
     L.orc_fetch_kv.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp, i32]
     L.orc_fetch_kv_plain.argtypes = [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64]
@@ -227,6 +228,23 @@ class OracleClass:
         rc = self.L.orc_place(self.h, _p(ids), ids.size, _p(st))
         if rc != OK:
             raise OracleError(rc, "place")
+        return st
+
+    def place_from(self, ids, src0, src1, src_block, src_layer_stride) -> np.ndarray:
+        """Placement from bytes held elsewhere than the host copy: planes laid out [layer][src_layer_stride][chunk]."""
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        sb = np.ascontiguousarray(src_block, dtype=np.uint64)
+        assert sb.shape == ids.shape
+        need = self.n_layers * src_layer_stride * self.chunk_bytes
+        src0 = np.ascontiguousarray(src0, dtype=np.uint8)
+        assert src0.size >= need
+        if self.n_planes == 2:
+            src1 = np.ascontiguousarray(src1, dtype=np.uint8)
+            assert src1.size >= need
+        st = np.zeros(ids.size, dtype=np.int32)
+        rc = self.L.orc_place_from(self.h, _p(ids), ids.size, _p(src0), _p(src1), _p(sb), src_layer_stride, _p(st))
+        if rc != OK:
+            raise OracleError(rc, "place_from")
         return st
 
     def revoke(self, ids):

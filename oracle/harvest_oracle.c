@@ -402,6 +402,50 @@ int orc_place(orc_class *c, const uint32_t *ids, uint32_t n, int *status)
 }
 
 /*
+ * Placement from a copy the application already holds in GPU memory.  Section
+ * 3.2: the allocation call only allocates and every copy stays explicit, so
+ * the bytes of a new cache-tier object may come from wherever the application
+ * has them - after a miss an expert sits complete in local staging memory
+ * (Section 4.3), and moving it to the cache tier from there saves the second
+ * trip over PCIe.  Object i is read from plane p at
+ * src[p] + (layer * src_layer_stride + src_block[i]) * chunk_bytes, all
+ * layers, as orc_evict reads its source.  Everything else is orc_place: only
+ * an object on the host moves, the lowest free slot (or a best-fit segment)
+ * is taken, a failed allocation leaves the object where it is.  The host copy
+ * is neither read nor written; that the source equals it is the
+ * application's business (Section 3.1: the runtime keeps no tier coherent).
+ */
+int orc_place_from(orc_class *c, const uint32_t *ids, uint32_t n, const uint8_t *src0, const uint8_t *src1,
+                   const uint64_t *src_block, uint64_t src_layer_stride, int *status)
+{
+    const uint8_t *src[2] = { src0, src1 };
+    for (uint32_t i = 0; i < n; ++i) {
+        if (ids[i] >= c->n_objects) return ORC_ENOENT;
+        if (src_block[i] >= src_layer_stride) return ORC_EINVAL;
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t id = ids[i];
+        int st = ORC_OK;
+        if (c->tier[id] == T_NONE) st = ORC_ELOST;
+        else if (c->tier[id] == T_CACHE || c->tier[id] == T_LOCAL) st = ORC_OK;      /* in HBM already: not written */
+        else {
+            int64_t room = cache_take(c);
+            if (room < 0) st = ORC_ENOSPC;
+            else {
+                for (uint32_t p = 0; p < c->n_planes; ++p)
+                    for (uint32_t l = 0; l < c->n_layers; ++l) {
+                        const uint8_t *from = src[p] + ((uint64_t)l * src_layer_stride + src_block[i]) * c->chunk_bytes;
+                        memcpy(cache_at(c, p, l, (uint64_t)room), from, c->chunk_bytes);
+                    }
+                c->tier[id] = T_CACHE; c->slot[id] = room; c->gen[id] = c->gen[id] + 1;
+            }
+        }
+        if (status) status[i] = st;
+    }
+    return ORC_OK;
+}
+
+/*
  * Revocation (Section 3.2: an explicit call whose steps come in a fixed
  * order): invalidate the entry, (drain - nothing is in flight on a CPU),
  * free the slot, then invoke the callback.  Backed objects fall back to their

@@ -98,6 +98,25 @@ MUTATIONS = [
      "return (object_bytes(c) + c->seg->granule - 1) / c->seg->granule;", "return object_bytes(c) / c->seg->granule;"),
     ("a failed demotion keeps the segments it had taken",
      "while (k > 0) cache_release(c, room[--k]);", ""),
+    ("placement from a device copy reads the host copy instead",
+     "const uint8_t *from = src[p] + ((uint64_t)l * src_layer_stride + src_block[i]) * c->chunk_bytes;",
+     "const uint8_t *from = at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]);"),
+    ("placement from a device copy takes the i-th source block instead of the named one",
+     "const uint8_t *from = src[p] + ((uint64_t)l * src_layer_stride + src_block[i]) * c->chunk_bytes;",
+     "const uint8_t *from = src[p] + ((uint64_t)l * src_layer_stride + i) * c->chunk_bytes;"),
+    ("placement from a device copy reads every layer from the first source layer",
+     "const uint8_t *from = src[p] + ((uint64_t)l * src_layer_stride + src_block[i]) * c->chunk_bytes;",
+     "const uint8_t *from = src[p] + ((uint64_t)0 * src_layer_stride + src_block[i]) * c->chunk_bytes;"),
+    ("placement from a device copy forgets the generation",
+     "c->slot[id] = room; c->gen[id] = c->gen[id] + 1;", "c->slot[id] = room;"),
+    ("placement from a device copy overwrites objects that are in HBM already",
+     "else if (c->tier[id] == T_CACHE || c->tier[id] == T_LOCAL) st = ORC_OK;      /* in HBM already: not written */",
+     "else if (c->tier[id] == T_LOCAL) st = ORC_OK;"),
+    ("placement from a device copy reports a full cache tier as success",
+     "if (room < 0) st = ORC_ENOSPC;", "if (room < 0) st = ORC_OK;"),
+    ("placement from a device copy also rewrites the host copy",
+     "memcpy(cache_at(c, p, l, (uint64_t)room), from, c->chunk_bytes);",
+     "memcpy(cache_at(c, p, l, (uint64_t)room), from, c->chunk_bytes); memcpy(at(c->host[p], c, c->n_host_slots, l, (uint64_t)c->host_slot[id]), from, c->chunk_bytes);"),
     ("revocation poisons whole granules instead of the object",
      "memset(cache_at(c, p, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes);",
      "memset(cache_at(c, p, l, (uint64_t)old[i]), ORC_POISON, c->chunk_bytes + (c->seg ? 16 : 0));"),
@@ -120,6 +139,8 @@ def battery():
         pins.test_revocation_falls_back_to_host_and_grows_the_miss_set_exactly(poison)
     pins.test_miss_list_is_exactly_the_host_and_lost_requests_in_request_order()
     pins.test_place_takes_lowest_free_slot_copies_the_host_bytes_and_reports_enospc()
+    pins.test_place_from_a_copy_in_device_memory_writes_those_bytes_and_never_touches_the_host()
+    pins.test_place_from_the_host_bytes_is_place()
     pins.test_fetch_never_changes_the_directory_or_any_tier()
     pins.test_local_objects_append_evict_demote_then_place()
     pins.test_invalid_requests_are_skipped_and_counted()

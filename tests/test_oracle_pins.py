@@ -298,6 +298,71 @@ def test_place_takes_lowest_free_slot_copies_the_host_bytes_and_reports_enospc()
     assert e.value.code == O.ENOENT and oc.lookup(0)[0] == O.HOST
 
 
+def test_place_from_a_copy_in_device_memory_writes_those_bytes_and_never_touches_the_host():
+    """Section 3.2: the allocation only allocates, every copy is explicit - so the new cache-tier copy may be filled from
+    wherever the application holds the bytes.  Closed form: slot bytes == the named source bytes, layer by layer."""
+    oc, ids, hs = make_kv(n_layers=2, chunk=32, n_obj=12, n_cache=4, seed=13, mode=W.FILL_NORMAL)
+    stride = 5
+    g = W.rng(13, 200)
+    src = [g.integers(0, 256, size=(2, stride, 32), dtype=np.uint8) for _ in range(2)]      # unlike any host bytes
+    host_before = [oc.plane(O.HOST, p).copy() for p in range(2)]
+    st = oc.place_from([7, 3, 9], src[0], src[1], [4, 0, 2], stride)
+    assert list(st) == [O.OK] * 3
+    assert [oc.lookup(b)[:3] for b in (7, 3, 9)] == [(O.CACHE, 0, 1), (O.CACHE, 1, 1), (O.CACHE, 2, 1)]
+    for b, blk in ((7, 4), (3, 0), (9, 2)):
+        for p in range(2):
+            for l in range(2):
+                assert np.array_equal(oc.plane(O.CACHE, p)[l, oc.lookup(b)[1]], src[p][l, blk]), (b, p, l)
+    assert all(np.array_equal(oc.plane(O.HOST, p), host_before[p]) for p in range(2))
+    # a fetch is served from the cache-tier copy while it exists, and from the host copy after revocation
+    table, nb, sdb = np.array([[3, 7, 5]], np.int32), np.array([3], np.int32), np.array([0], np.uint64)
+    k, v, miss, counts = oc.fetch_kv(1, table, nb, sdb, 3)
+    assert np.array_equal(k[:32], src[0][1, 0]) and np.array_equal(v[32:64], src[1][1, 4]) and list(miss) == [2]
+    assert np.array_equal(k[64:], host_before[0][1, hs[5]])
+    oc.revoke([3, 7])
+    k, v, miss, counts = oc.fetch_kv(1, table, nb, sdb, 3)
+    assert np.array_equal(k[:32], host_before[0][1, hs[3]]) and np.array_equal(v[32:64], host_before[1][1, hs[7]])
+    # statuses as for place: no-op for what is already in HBM (nothing written), one slot... then full; errors change nothing
+    cache_before = [oc.plane(O.CACHE, p).copy() for p in range(2)]
+    st = oc.place_from([9, 5, 6, 1, 2], src[0], src[1], [1, 1, 3, 0, 4], stride)
+    assert list(st) == [O.OK, O.OK, O.OK, O.OK, O.ENOSPC]
+    assert oc.lookup(9)[:3] == (O.CACHE, 2, 1) and np.array_equal(oc.plane(O.CACHE, 0)[:, 2], cache_before[0][:, 2])
+    assert [oc.lookup(b)[:2] for b in (5, 6, 1)] == [(O.CACHE, 0), (O.CACHE, 1), (O.CACHE, 3)]
+    assert np.array_equal(oc.plane(O.CACHE, 1)[0, 3], src[1][0, 0]) and oc.lookup(2)[:3] == (O.HOST, -1, 0)
+    for bad_ids, bad_blk, code in (([0, 500], [0, 0], O.ENOENT), ([0, 4], [0, stride], O.EINVAL)):
+        with pytest.raises(OracleError) as e:
+            oc.place_from(bad_ids, src[0], src[1], bad_blk, stride)
+        assert e.value.code == code and oc.lookup(0)[0] == O.HOST
+    oc.close()
+
+
+def test_place_from_the_host_bytes_is_place():
+    """Special case that reduces to the pinned routine: a source holding exactly the host copies leaves the same
+    directory and the same cache tier as orc_place - with equal-size slots and with best-fit segments."""
+    for shared in (False, True):
+        pools = [O.SegPool(22 * 64, 64) if shared else None for _ in range(2)]       # four objects of 5 granules, 2 to spare
+        a, ids, hs = make_kv(n_layers=3, chunk=48, n_obj=10, n_cache=3, seed=14, segpool=pools[0])
+        b, _, _ = make_kv(n_layers=3, chunk=48, n_obj=10, n_cache=3, seed=14, segpool=pools[1])
+        order = [4, 8, 1, 4, 6, 0]                                    # a repeat; more than fits either way
+        st_a = a.place(order)
+        blk = W.rng(14, 201).permutation(12)[:len(order)]
+        src = [np.zeros((3, 12, 48), np.uint8) for _ in range(2)]
+        for i, obj in enumerate(order):
+            for p in range(2):
+                src[p][:, blk[i]] = b.plane(O.HOST, p)[:, hs[obj]]
+        st_b = b.place_from(order, src[0], src[1], blk, 12)
+        assert list(st_a) == list(st_b) and O.ENOSPC in st_a and list(st_a).count(O.OK) >= 4
+        assert [a.lookup(i) for i in ids] == [b.lookup(i) for i in ids]
+        if shared:
+            assert np.array_equal(pools[0].mem(), pools[1].mem()) and pools[0].free_runs() == pools[1].free_runs()
+        else:
+            assert all(np.array_equal(a.plane(O.CACHE, p), b.plane(O.CACHE, p)) for p in range(2))
+        a.close(); b.close()
+        for g in pools:
+            if g:
+                g.close()
+
+
 def test_fetch_never_changes_the_directory_or_any_tier():
     oc, ids, _ = make_kv(n_layers=2, chunk=32, n_obj=20, n_cache=8, n_local=3, seed=11)
     place_fraction(oc, ids, 0.4, 11)

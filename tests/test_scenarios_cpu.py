@@ -1,6 +1,7 @@
 """The harness drivers run against the oracle alone (no GPU): with the self-describing tag payload every fetched
 chunk names the block it must be, so these runs check drivers and oracle together against the workload definition."""
 import numpy as np
+import pytest
 
 import workloads as W
 from workloads import scenarios as S
@@ -85,7 +86,8 @@ def test_expert_configs_on_the_oracle():
     e.close()
 
 
-def test_lru_policy_keeps_capacity_and_hits_after_warm_up():
+@pytest.mark.parametrize("from_staging", [False, True])
+def test_lru_policy_keeps_capacity_and_hits_after_warm_up(from_staging):
     sh = W.ExpertShape(n_layers=2, n_experts=60, d_model=16, d_ff=12)
     ex = W.expert_lru(seed=1, shape=sh, n_tokens=32, top_k=4, fill_mode=W.FILL_TAG)
     e = OracleEngine(expert=S.expert_spec(ex), poison=True)
@@ -98,11 +100,31 @@ def test_lru_policy_keeps_capacity_and_hits_after_warm_up():
                 if out[i] is not None:
                     assert W.check_tag(out[i], ex.seed, W.CLS_EXPERT, 0, 0, layer * 60 + i)
             hits.append(counts["n_cache"])
-            run.lru_update(t, layer)
+            run.lru_update(t, layer, from_staging=from_staging)
             in_cache = [i for i in range(60) if e.lookup(S.EXPERT, layer * 60 + i)[0] == S.CACHE]
             assert len(in_cache) == min(24, len(run.lru[layer].members())) and set(in_cache) == run.lru[layer].members()
     assert hits[0] == 0 and hits[1] == 0 and sum(hits[2:]) > 0
     e.close()
+
+
+def test_placing_from_the_staging_buffer_leaves_the_state_placing_from_the_host_leaves():
+    """An expert the fetch has just staged holds its host bytes, so filling the cache tier from the staging buffer must
+    end in the same directory and the same cache-tier bytes as filling it over PCIe."""
+    sh = W.ExpertShape(n_layers=2, n_experts=60, d_model=16, d_ff=12)
+    ex = W.expert_lru(seed=2, shape=sh, n_tokens=32, top_k=4)
+    engines = [OracleEngine(expert=S.expert_spec(ex), poison=True) for _ in range(2)]
+    runs = [S.ExpertRun(e, ex, n_staging=40) for e in engines]                 # 40 slots: some steps overflow the staging buffer
+    for t in range(4):
+        for layer in range(2):
+            outs = [r.fetch(t, layer) for r in runs]
+            assert all((a is None) == (b is None) and (a is None or np.array_equal(a, b)) for a, b in zip(*[o[0] for o in outs]))
+            ups = [r.lru_update(t, layer, from_staging=k == 1) for k, r in enumerate(runs)]
+            assert ups[0][0] == ups[1][0] and ups[0][2] == ups[1][2] and np.array_equal(ups[0][3], ups[1][3])
+    a, b = engines
+    assert [a.lookup(S.EXPERT, i) for i in range(ex.n_objects)] == [b.lookup(S.EXPERT, i) for i in range(ex.n_objects)]
+    assert np.array_equal(a.tier_plane(S.EXPERT, S.CACHE), b.tier_plane(S.EXPERT, S.CACHE))
+    for e in engines:
+        e.close()
 
 
 def test_revocation_schedule_on_the_oracle():

@@ -165,9 +165,10 @@ class ExpertRun:
     def fetch_begin(self, t, layer):
         return self.e.fetch_experts_begin(layer, self.wl.routing(t, layer), self.n_staging)
 
-    def lru_update(self, t, layer):
+    def lru_update(self, t, layer, from_staging=False):
         """After the fetch of (t, layer): run the LRU over this step's token-ordered trace and apply the net change
-        as revocations followed by placements."""
+        as revocations followed by placements.  from_staging: an expert that enters the cache tier was routed in this
+        very step, so the fetch has just left it in the staging buffer - it is placed from there, not from the host."""
         E = self.wl.shape.n_experts
         lru = self.lru[layer]
         before = lru.members()
@@ -178,7 +179,10 @@ class ExpertRun:
         out_ids = sorted(layer * E + e for e in before - after)
         in_ids = sorted(layer * E + e for e in after - before)
         called = self.e.revoke(EXPERT, out_ids) if out_ids else []
-        st = self.e.place(EXPERT, in_ids) if in_ids else np.zeros(0, np.int32)
+        if not in_ids:
+            st = np.zeros(0, np.int32)
+        else:
+            st = self.e.place_staged(in_ids) if from_staging else self.e.place(EXPERT, in_ids)
         self.live -= set(out_ids)
         self.live |= {i for i, s in zip(in_ids, st) if s == OK}
         return out_ids, called, in_ids, st
