@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--shared-cache", action="store_true",
                     help="variant: the cache tier is one pool of best-fit segments (an object's layers and planes are "
                          "contiguous) instead of equal-size slots per layer and plane")
+    ap.add_argument("--place-from-host", action="store_true",
+                    help="experts_qwen only: the LRU's placements read the host copies over PCIe (harvest_place) instead of "
+                         "the staging buffer the fetch has just filled (harvest_place_from)")
     ap.add_argument("--prefetch", action="store_true",
                     help="experts_phi only: also time the double-buffered prefetch ring against fetch-then-use")
     ap.add_argument("--graph-steps", type=int, default=64,
@@ -211,11 +214,13 @@ def bench_experts(args):
     n_total = args.warmup + args.steps
     topk = {(t, l): torch.from_numpy(wl.routing(t, l)).to(dev) for t in range(n_total) for l in range(L)}
 
+    eng._last_staging = staging                        # what the LRU's placements copy from (harvest_place_from)
+
     def step(t):
         for l in range(L):
             eng.h.fetch_experts(l, topk[(t, l)], staging, E, ptrs)
             if wl.lru_capacity:
-                run.lru_update(t, l)
+                run.lru_update(t, l, from_staging=not args.place_from_host)
 
     for t in range(args.warmup):
         step(t)
@@ -246,7 +251,9 @@ def bench_experts(args):
                                 "Zipf(1.1), 64 tokens, 2 local, 50% of the rest cached)" if phi else
                                 "configs[3]: MoE expert fetch, Qwen-MoE-shaped (60 experts/layer of 16.5 MiB, top-4 "
                                 "Zipf(1.0), 256 tokens, LRU cache tier of 24 experts/layer)"),
-                   "seed": args.seed, "layers_materialised": L},
+                   "seed": args.seed, "layers_materialised": L,
+                   **({"placements_read": "host copies" if args.place_from_host else "the staging buffer of the fetch"}
+                      if wl.lru_capacity else {})},
         "objects_per_s": round(d["n_requests"] / sec), "bit_exact": None,
         "served_per_step": {k: round(v / args.steps, 2) for k, v in d.items()},
         "placed_per_step": round(placed / args.steps, 2),

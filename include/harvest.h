@@ -212,6 +212,21 @@ int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t
  * nothing, only for unknown ids (ENOENT). */
 int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *per_obj_status);
 
+/* Placement from a copy the application already holds in device memory (Section 3.2: the allocation only allocates
+ * and every copy stays explicit, so a new cache-tier object may be filled from wherever its bytes are; Section 4.3:
+ * after a miss the whole expert sits in local staging memory).  Exactly harvest_place, except that object i is read,
+ * in every layer l and plane p, from d_src{p} + (l * src_layer_stride + src_block[i]) * chunk_bytes - the source
+ * addressing of harvest_evict with layer < 0 - instead of from its host copy, so nothing crosses PCIe.  For experts
+ * (one storage layer) d_src0 is the staging buffer of the fetch, src_block[i] the staging slot and src_layer_stride
+ * the number of staging slots.  The host copy is neither read nor written: that the source holds the same bytes is
+ * the caller's business (Section 3.1: the runtime keeps no tier coherent).  ids, src_block: host pointers.  The
+ * copy is enqueued on `stream`; whatever wrote the source must precede it in stream order.  Statuses and errors as
+ * for harvest_place, plus EINVAL (nothing changed) for src_block[i] >= src_layer_stride or a missing / misaligned
+ * source plane.  Refuses a capturing stream like harvest_place. */
+int harvest_place_from(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, const void *d_src0,
+                       const void *d_src1, const uint64_t *src_block, uint64_t src_layer_stride, void *stream,
+                       int *per_obj_status);
+
 /* Revocation (Section 3.2: an explicit call whose steps come in a fixed order): for each id in the cache tier: publish (HOST, gen+1) - or
  * (NONE) for a lossy object -, wait until every fetch / evict / place enqueued so far on any stream this context
  * has seen has completed (the drain), free the slot (poison it if asked), then invoke the callback.  Ids not in the

@@ -89,19 +89,9 @@ class OracleEngine:
         assert cls != KV or self.kv_layers == list(range(self.spec[KV].n_layers))
         return self.c[cls].place_from(ids, src0, src1, src_block, stride)
 
-    def place_staged(self, ids):
-        """Experts the last fetch_experts call left in its staging buffer move into the cache tier from there; the
-        others are placed from their host copies."""
-        staging, where, kind, layer = self._last_expert_fetch
-        E = self.spec[EXPERT].n_experts
-        ids = [int(i) for i in ids]
-        staged = [i for i in ids if i // E == layer and kind[i % E] == STAGED]
-        st = dict(zip(staged, self.c[EXPERT].place_from(staged, staging, None, [int(where[i % E]) for i in staged],
-                                                        max(1, staging.size // self.c[EXPERT].chunk_bytes))
-                      if staged else []))
-        rest = [i for i in ids if i not in st]
-        st.update(zip(rest, self.c[EXPERT].place(rest) if rest else []))
-        return np.array([st[i] for i in ids], dtype=np.int32)
+    def last_staging(self):
+        """The staging buffer of the latest expert fetch."""
+        return self._last_expert_fetch[0]
 
     def revoke(self, cls, ids):
         c = self.c[cls]

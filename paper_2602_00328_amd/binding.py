@@ -68,6 +68,7 @@ SYMBOLS = {
     "harvest_lookup": (ctypes.c_int, [vp, ctypes.c_int, u32, vp, vp, vp, vp]),
     "harvest_restore": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_place": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp]),
+    "harvest_place_from": (ctypes.c_int, [vp, ctypes.c_int, vp, u32, vp, vp, vp, u64, vp, vp]),
     "harvest_revoke": (ctypes.c_int, [vp, ctypes.c_int, vp, u32]),
     "harvest_alloc": (ctypes.c_int, [vp, ctypes.c_int, u32, vp]),
     "harvest_free": (ctypes.c_int, [vp, ctypes.c_int, u32]),
@@ -276,6 +277,16 @@ class Harvest:
         st = np.zeros(ids.size, dtype=np.int32)
         sp = vp(0) if self.no_device else _stream_ptr(stream)
         _chk(lib.harvest_place(self.h, cls, _np_ptr(ids), ids.size, sp, _np_ptr(st)), "harvest_place")
+        return st
+
+    def place_from(self, cls, ids, d_src0, d_src1, src_block, src_layer_stride, stream=None) -> np.ndarray:
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        sb = np.ascontiguousarray(src_block, dtype=np.uint64)
+        assert sb.shape == ids.shape
+        st = np.zeros(ids.size, dtype=np.int32)
+        sp = vp(0) if self.no_device else _stream_ptr(stream)
+        _chk(lib.harvest_place_from(self.h, cls, _np_ptr(ids), ids.size, _dev_ptr(d_src0), _dev_ptr(d_src1), _np_ptr(sb),
+                                    src_layer_stride, sp, _np_ptr(st)), "harvest_place_from")
         return st
 
     def revoke(self, cls, ids):

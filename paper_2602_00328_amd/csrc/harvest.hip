@@ -805,14 +805,25 @@ int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t
     return HARVEST_OK;
 }
 
-int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *status)
+// Source of a placement that does not read the host copies: planes laid out [layer][stride][chunk], object i at block[i].
+struct PlaceSource { uint64_t plane[2]; const uint64_t *block; uint64_t stride; };
+
+static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, const PlaceSource *from, void *stream,
+                      int *status)
 {
     int rc = check_class(ctx, cls);
     if (rc) return rc;
     if (n && !ids) return HARVEST_EINVAL;
     std::lock_guard<std::mutex> lk(ctx->mu);
     ClassState &c = ctx->cls[cls];
-    for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
+        if (from && from->block[i] >= from->stride) return HARVEST_EINVAL;
+    }
+    if (from && n && !ctx->no_device) {
+        if (!from->plane[0] || (c.cfg.n_planes == 2 && !from->plane[1])) return HARVEST_EINVAL;
+        if ((from->plane[0] | from->plane[1]) & 15) return HARVEST_EINVAL;
+    }
     if ((rc = device_guard(ctx))) return rc;
     // directory edits go through the control stream and pinned staging: they cannot be recorded into a graph
     if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;
@@ -829,8 +840,11 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
         else if (int64_t s = c.cache_take(); s < 0) { st = HARVEST_ENOSPC; c.n_enospc++; }
         else {
             for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
-                for (uint32_t l = 0; l < c.cfg.n_layers; ++l)
-                    items.push_back({ c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]), c.addr(T_CACHE, p, l, (uint64_t)s) });
+                for (uint32_t l = 0; l < c.cfg.n_layers; ++l) {
+                    uint64_t src = from ? from->plane[p] + ((uint64_t)l * from->stride + from->block[i]) * c.cfg.chunk_bytes
+                                        : c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]);
+                    items.push_back({ src, c.addr(T_CACHE, p, l, (uint64_t)s) });
+                }
             c.tier[id] = T_CACHE; c.slot[id] = s; c.gen[id] += 1;
             c.n_placed++;
             moved.push_back(id);
@@ -846,7 +860,7 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
     if ((rc = release_after(st, ss->s))) return rc;
     uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->pcie_grid);
+    uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);   // HBM to HBM, or over PCIe
     hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
                        c.cfg.chunk_bytes, tpc);
     HIP_TRY(hipGetLastError());
@@ -856,6 +870,19 @@ int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n,
     HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
     HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
     return mark_last(ctx, ss);
+}
+
+int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *status)
+{
+    return place_impl(ctx, cls, ids, n, nullptr, stream, status);
+}
+
+int harvest_place_from(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, const void *d_src0, const void *d_src1,
+                       const uint64_t *src_block, uint64_t src_layer_stride, void *stream, int *status)
+{
+    if (n && !src_block) return HARVEST_EINVAL;
+    PlaceSource from{ { (uint64_t)d_src0, (uint64_t)d_src1 }, src_block, src_layer_stride };
+    return place_impl(ctx, cls, ids, n, &from, stream, status);
 }
 
 static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, bool notify)

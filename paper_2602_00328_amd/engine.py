@@ -85,6 +85,21 @@ class HipEngine:
         with self._on(cls):
             return self.h.place(cls, ids)
 
+    def place_from(self, cls, ids, src0, src1, src_block, stride):
+        """src planes: device tensors, or numpy arrays that are copied to the device first; [n_layers][stride][chunk]."""
+        with self._on(cls):
+            up = lambda a: a if a is None or torch.is_tensor(a) else torch.from_numpy(
+                np.ascontiguousarray(a, dtype=np.uint8)).to(self.dev)
+            d0, d1 = up(src0), up(src1)
+            st = self.h.place_from(cls, ids, d0, d1, src_block, stride)
+            if d0 is not src0:
+                torch.cuda.current_stream().synchronize()       # the uploaded copies are freed when this returns
+            return st
+
+    def last_staging(self):
+        """The staging buffer of the latest expert fetch (device tensor)."""
+        return self._last_staging
+
     def revoke(self, cls, ids):
         n0 = len(self.h.revoked_log)
         self.h.revoke(cls, ids)
@@ -171,6 +186,7 @@ class HipEngine:
                                  device=self.dev)
             ptrs = torch.zeros(sp.n_experts, dtype=torch.int64, device=self.dev)
             self.h.fetch_experts(layer, d_topk, staging, n_staging, ptrs)
+            self._last_staging = staging
         return ("experts", staging, n_staging, ptrs, d_topk)
 
     def fetch_experts(self, layer, topk, n_staging, staging_fill=0):
@@ -209,7 +225,6 @@ class HipEngine:
                     slot = (p - l0) // sp.chunk_bytes
                     kind[e], where[e] = IN_PLACE, slot
                     out.append(local[0, slot].cpu().numpy())
-        self.last_staging = staging
         return out, kind, where, np.sort(miss), counts
 
     def evict(self, cls, layer, ids, src0, src1, src_block, stride, flags=0):

@@ -127,8 +127,13 @@ def test_host_logic_matches_the_oracle_directory_under_random_operations(seed):
                 free_host.extend(hs[1:])
         elif n:
             ids = g.integers(0, n + (1 if g.random() < 0.05 else 0), size=int(g.integers(1, 6))).astype(np.uint32)
-            if op == 1:
+            if op == 1 and g.random() < 0.5:
                 ro, rh = both(lambda: oc.place(ids), lambda: h.place(B.KV, ids))
+                if ro is not None:
+                    assert np.array_equal(ro, rh)
+            elif op == 1:                                                   # the same decisions when the bytes come from a device copy
+                sb = g.integers(0, 8 + (1 if g.random() < 0.1 else 0), size=ids.size).astype(np.uint64)
+                ro, rh = both(lambda: oc.place_from(ids, dummy, dummy, sb, 8), lambda: h.place_from(B.KV, ids, None, None, sb, 8))
                 if ro is not None:
                     assert np.array_equal(ro, rh)
             elif op == 2:
@@ -241,7 +246,12 @@ def test_shared_pool_host_logic_matches_the_oracle_under_random_operations(seed)
             ids = np.unique(g.integers(0, n, size=int(g.integers(1, 5)))).astype(np.uint32)
             g.shuffle(ids)
             if op in (1, 2):
-                ro, rh, _ = both(lambda: c.place(ids), lambda: h.place(cls, ids))
+                if g.random() < 0.5:
+                    ro, rh, _ = both(lambda: c.place(ids), lambda: h.place(cls, ids))
+                else:
+                    sb = g.integers(0, 8, size=ids.size).astype(np.uint64)
+                    ro, rh, _ = both(lambda: c.place_from(ids, dummy, dummy, sb, 8),
+                                     lambda: h.place_from(cls, ids, None, None, sb, 8))
                 assert np.array_equal(ro, rh)
                 n_enospc += int((ro == O.ENOSPC).sum())
             elif op == 3:

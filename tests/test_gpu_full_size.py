@@ -73,7 +73,8 @@ def test_config4_qwen_shaped_experts_lru_real_size():
                 a, b = xo.fetch(t, layer), xh.fetch(t, layer)
                 P.assert_experts_equal(a, b, f"config 4 step {t} layer {layer}")
                 hits += b[4]["n_cache"]
-                ua, ub = xo.lru_update(t, layer), xh.lru_update(t, layer)
+                from_staging = t >= 1                    # the second half fills the cache tier from the staging buffer
+                ua, ub = xo.lru_update(t, layer, from_staging), xh.lru_update(t, layer, from_staging)
                 assert ua[0] == ub[0] and ua[1] == ub[1] and ua[2] == ub[2] and np.array_equal(ua[3], ub[3])
         assert hits >= 2 * 2 * 20
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)

@@ -212,26 +212,68 @@ def test_expert_fetch_small():
 
 # ---- config 4, small: cache tier driven by an LRU policy --------------------------------------------------------
 
-def test_expert_lru_small():
-    say("experts lru small")
+@pytest.mark.parametrize("from_staging", [False, True])
+def test_expert_lru_small(from_staging):
+    """from_staging: experts that enter the cache tier are copied from the staging buffer the fetch has just filled
+    (harvest_place_from), those the buffer had no room for from their host copies; 30 staging slots force both."""
+    say(f"experts lru small, from_staging={from_staging}")
     sh = W.ExpertShape(n_layers=3, n_experts=60, d_model=32, d_ff=44)
     ex = W.expert_lru(seed=7, shape=sh, n_tokens=24, top_k=4)
     eo, eh = P.make_engines(ex_wl=ex, poison=True)
     try:
-        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        n_staging = 30 if from_staging else None
+        xo, xh = S.ExpertRun(eo, ex, n_staging=n_staging), S.ExpertRun(eh, ex, n_staging=n_staging)
         hits = 0
         for t in range(6):
             for layer in range(3):
                 a, b = xo.fetch(t, layer), xh.fetch(t, layer)
                 P.assert_experts_equal(a, b, f"lru step {t} layer {layer}")
                 hits += b[4]["n_cache"]
-                ua, ub = xo.lru_update(t, layer), xh.lru_update(t, layer)
+                ua, ub = xo.lru_update(t, layer, from_staging), xh.lru_update(t, layer, from_staging)
                 assert ua[0] == ub[0] and ua[1] == ub[1] and ua[2] == ub[2] and np.array_equal(ua[3], ub[3])
         assert hits > 0
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
         P.assert_tiers_equal(eo, eh, S.EXPERT, 1, tiers=(S.CACHE,), what="lru cache pool (poisoned slots included)")
     finally:
         eh.close(); eo.close()
+
+
+def test_place_from_device_memory_kv_all_layers():
+    """harvest_place_from on a two-plane, three-layer class, with source bytes unlike any host copy: the cache tier must
+    hold exactly the named source blocks, the host pool must stay as it was, fetches serve the new bytes until the
+    objects are revoked and the host bytes afterwards.  Equal-size slots and best-fit segments."""
+    say("place_from, kv")
+    for shared in (0, 1):
+        wl = W.kv_decode(seed=33, n_layers=3, n_seq=2, min_len=200, max_len=400, p_cache=0.0, n_steps=1)
+        nbytes = 64 * 256 * 3 * 2 * wl.shape.chunk_bytes // 64 if shared else 0
+        eo, eh = P.make_engines(wl, poison=True, cache_slack=16, shared_cache_bytes=nbytes, shared_granule=256 if shared else 0)
+        try:
+            ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+            chunk, stride = wl.shape.chunk_bytes, 7
+            g = W.rng(33, 5)
+            src = [g.integers(0, 256, size=3 * stride * chunk, dtype=np.uint8) for _ in range(2)]
+            host_before = [eh.tier_plane(S.KV, S.HOST, p).copy() for p in range(2)]
+            ids, blk = [5, 2, 9, 2, 11], [6, 0, 3, 1, 3]                     # a repeat: the second mention is a no-op
+            a = eo.place_from(S.KV, ids, src[0], src[1], blk, stride)
+            b = eh.place_from(S.KV, ids, src[0], src[1], blk, stride)
+            assert np.array_equal(a, b) and list(b) == [0] * 5
+            P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+            if shared:
+                P.assert_shared_pools_equal(eo, eh, "after place_from")
+            else:
+                P.assert_tiers_equal(eo, eh, S.KV, 2, tiers=(S.CACHE,), what="after place_from")
+            assert all(np.array_equal(eh.tier_plane(S.KV, S.HOST, p), host_before[p]) for p in range(2))
+            for layer in range(3):
+                P.assert_kv_equal(ro.fetch(layer), rh.fetch(layer), f"after place_from, layer {layer}")
+            assert eo.revoke(S.KV, [5, 9]) == eh.revoke(S.KV, [5, 9]) == [5, 9]
+            for layer in range(3):
+                P.assert_kv_equal(ro.fetch(layer), rh.fetch(layer), f"after revocation, layer {layer}")
+            for bad_ids, bad_blk in (([0, 10 ** 6], [0, 0]), ([0, 1], [0, stride])):
+                with pytest.raises(Exception):
+                    eh.place_from(S.KV, bad_ids, src[0], src[1], bad_blk, stride)
+                assert eh.lookup(S.KV, 0)[0] == S.HOST
+        finally:
+            eh.close(); eo.close()
 
 
 # ---- config 5, small: KV and experts on two streams with periodic revocation -------------------------------------

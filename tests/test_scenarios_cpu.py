@@ -117,6 +117,9 @@ def test_placing_from_the_staging_buffer_leaves_the_state_placing_from_the_host_
     for t in range(4):
         for layer in range(2):
             outs = [r.fetch(t, layer) for r in runs]
+            ranks = runs[1].staged_ranks(t, layer)                             # what the harness works out on the host ...
+            kind, where = outs[1][1], outs[1][2]                               # ... is what the fetch did
+            assert ranks == {e: int(where[e]) for e in range(60) if kind[e] == 2}
             assert all((a is None) == (b is None) and (a is None or np.array_equal(a, b)) for a, b in zip(*[o[0] for o in outs]))
             ups = [r.lru_update(t, layer, from_staging=k == 1) for k, r in enumerate(runs)]
             assert ups[0][0] == ups[1][0] and ups[0][2] == ups[1][2] and np.array_equal(ups[0][3], ups[1][3])

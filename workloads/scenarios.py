@@ -165,11 +165,20 @@ class ExpertRun:
     def fetch_begin(self, t, layer):
         return self.e.fetch_experts_begin(layer, self.wl.routing(t, layer), self.n_staging)
 
+    def staged_ranks(self, t, layer):
+        """expert -> staging slot of the fetch of (t, layer), from what the host knows: routed experts that are not local,
+        in ascending order, as far as the staging buffer has room (Section 4.3: whole experts, one staging slot each)."""
+        E = self.wl.shape.n_experts
+        routed = sorted(set(int(e) for e in self.wl.routing(t, layer).reshape(-1)))
+        staged = [e for e in routed if self.e.lookup(EXPERT, layer * E + e)[0] in (HOST, CACHE)]
+        return {e: r for r, e in enumerate(staged) if r < self.n_staging}
+
     def lru_update(self, t, layer, from_staging=False):
         """After the fetch of (t, layer): run the LRU over this step's token-ordered trace and apply the net change
         as revocations followed by placements.  from_staging: an expert that enters the cache tier was routed in this
         very step, so the fetch has just left it in the staging buffer - it is placed from there, not from the host."""
         E = self.wl.shape.n_experts
+        ranks = self.staged_ranks(t, layer) if from_staging else {}      # as the fetch saw residency: before any change
         lru = self.lru[layer]
         before = lru.members()
         for row in self.wl.routing(t, layer):
@@ -181,8 +190,18 @@ class ExpertRun:
         called = self.e.revoke(EXPERT, out_ids) if out_ids else []
         if not in_ids:
             st = np.zeros(0, np.int32)
+        elif not from_staging:
+            st = self.e.place(EXPERT, in_ids)
         else:
-            st = self.e.place_staged(in_ids) if from_staging else self.e.place(EXPERT, in_ids)
+            staged = [i for i in in_ids if i - layer * E in ranks]
+            rest = [i for i in in_ids if i - layer * E not in ranks]
+            got = {}
+            if staged:
+                got.update(zip(staged, self.e.place_from(EXPERT, staged, self.e.last_staging(), None,
+                                                         [ranks[i - layer * E] for i in staged], max(1, self.n_staging))))
+            if rest:
+                got.update(zip(rest, self.e.place(EXPERT, rest)))
+            st = np.array([got[i] for i in in_ids], dtype=np.int32)
         self.live -= set(out_ids)
         self.live |= {i for i, s in zip(in_ids, st) if s == OK}
         return out_ids, called, in_ids, st
