@@ -572,7 +572,15 @@ def main():
         log(f"[bench] write paths: {write_paths}")
         for name, n_it in (("all_cache", args.iso_steps), ("all_host", max(2, args.iso_steps // 4))):
             if name == "all_host":
-                eng.revoke(0, closed)
+                torch.cuda.synchronize()
+                n_live = int(eng.h.stats().cache_slots_in_use[0])
+                a = time.perf_counter()
+                eng.revoke(0, closed)                    # nothing in flight: invalidate, publish, (empty) drain, free, callbacks
+                dt = time.perf_counter() - a
+                write_paths["revoke"] = {"objects": n_live, "ms": round(dt * 1e3, 3),
+                                         "us_per_object": round(dt * 1e6 / max(1, n_live), 3),
+                                         "note": "every cache-tier block revoked in one call, callbacks into Python included"}
+                log(f"[bench] revoke: {write_paths['revoke']}")
             dd.fetch(0)
             torch.cuda.synchronize()
             counts, _, _ = eng.h.fetch_info()
