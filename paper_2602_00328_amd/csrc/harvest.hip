@@ -179,6 +179,7 @@ struct StreamState {
     Rec *hbm_recs = nullptr, *host_recs = nullptr, *tmp_recs = nullptr;
     uint8_t *kind = nullptr;
     uint32_t *blk_counts = nullptr;
+    uint32_t *grp_totals = nullptr, *row_prefix = nullptr;     // large tables: the middle pass of the compaction
     uint32_t *miss_idx = nullptr;
     uint32_t *cnt = nullptr;                // [C_N] counters of the last fetch; every fetch overwrites all of them
     bool fetched = false;                   // a fetch has been enqueued on this stream
@@ -252,6 +253,7 @@ void free_stream_state(StreamState *ss)
     for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) if (e) (void)hipEventDestroy(e);
     (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
     (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
+    (void)hipFree(ss->grp_totals); (void)hipFree(ss->row_prefix);
     (void)hipFree(ss->ctl_buf);
     if (ss->h_feedback) (void)hipHostFree(ss->h_feedback);
 }
@@ -300,16 +302,19 @@ int ensure_req_cap(StreamState *ss, uint32_t n_req)
     HIP_TRY(hipStreamSynchronize(ss->s));
     HIP_TRY(hipStreamSynchronize(ss->side));
     for (void *p : { (void *)ss->hbm_recs, (void *)ss->host_recs, (void *)ss->tmp_recs, (void *)ss->kind,
-                     (void *)ss->blk_counts, (void *)ss->miss_idx })
+                     (void *)ss->blk_counts, (void *)ss->grp_totals, (void *)ss->row_prefix, (void *)ss->miss_idx })
         if (p) HIP_TRY(hipFree(p));
     ss->hbm_recs = ss->host_recs = ss->tmp_recs = nullptr;
-    ss->kind = nullptr; ss->blk_counts = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
+    ss->kind = nullptr; ss->blk_counts = ss->grp_totals = ss->row_prefix = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
     uint32_t cap = std::max<uint32_t>(1024, n_req + n_req / 4);
     HIP_TRY(hipMalloc(&ss->hbm_recs, (size_t)cap * sizeof(Rec)));
     HIP_TRY(hipMalloc(&ss->host_recs, (size_t)cap * sizeof(Rec)));
     HIP_TRY(hipMalloc(&ss->tmp_recs, (size_t)cap * sizeof(Rec)));
     HIP_TRY(hipMalloc(&ss->kind, (size_t)cap));
-    HIP_TRY(hipMalloc(&ss->blk_counts, (size_t)((cap + WG - 1) / WG) * BC_N * sizeof(uint32_t)));
+    size_t n_rows = (cap + WG - 1) / WG;
+    HIP_TRY(hipMalloc(&ss->blk_counts, n_rows * BC_N * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->grp_totals, ((n_rows + WG - 1) / WG) * BC_N * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->row_prefix, n_rows * 3 * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ss->miss_idx, (size_t)cap * sizeof(uint32_t)));
     ss->req_cap = cap;
     return HARVEST_OK;
@@ -356,6 +361,8 @@ int release_after(Staging *st, hipStream_t s)
     st->busy = true;
     return HARVEST_OK;
 }
+
+constexpr uint32_t GROUPED_SCAN_ROWS = 1024;      // block tables of more than 262 144 cells take the three-kernel compaction
 
 uint32_t tiles_per_chunk(uint64_t chunk_bytes, uint32_t tile) { return (uint32_t)((chunk_bytes + tile - 1) / tile); }
 
@@ -1022,9 +1029,19 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
                        max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts,
                        d_seq_cap_blocks, (uint64_t)hm.ups * 16);
     HIP_TRY(hipGetLastError());
+    // Beyond this many rows of workgroup totals the compaction's own adding-up of all earlier rows (quadratic) costs more
+    // than one more small kernel that groups them first (2 M cells: 70 us against about 10).
+    const bool grouped = n_wg > GROUPED_SCAN_ROWS;
+    if (grouped) {
+        hipLaunchKernelGGL(scan_groups, dim3((n_wg + WG - 1) / WG), dim3(WG), 0, ss->s, (const uint32_t *)ss->blk_counts, n_wg,
+                           ss->grp_totals, ss->row_prefix);
+        HIP_TRY(hipGetLastError());
+    }
     hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)ss->tmp_recs,
                        (const uint8_t *)ss->kind, (const uint32_t *)ss->blk_counts, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N);
+                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
+                       grouped ? (const uint32_t *)ss->grp_totals : (const uint32_t *)nullptr,
+                       grouped ? (const uint32_t *)ss->row_prefix : (const uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,

@@ -189,6 +189,53 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
     if (tid < BC_N) blk_counts[blockIdx.x * BC_N + tid] = s_cnt[tid];
 }
 
+// KV, middle pass for large tables only.  In pass 2 every workgroup adds up the rows of all workgroups before it: fine for
+// a few hundred rows, quadratic beyond (a table of 8 M cells has 32 768 rows: 17 GB of reads).  This pass makes groups of
+// WG rows: workgroup g leaves the totals of its group in grp_totals[g] and, for each of its rows, the list counters of the
+// group's earlier rows in row_prefix[row] - pass 2 then adds up whole groups only.
+__global__ __launch_bounds__(WG) void scan_groups(const uint32_t *__restrict__ blk_counts, uint32_t n_rows,
+                                                  uint32_t *__restrict__ grp_totals, uint32_t *__restrict__ row_prefix)
+{
+    __shared__ uint32_t s_wave[WAVES][BC_N];
+    uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    uint32_t row = blockIdx.x * WG + tid;
+    uint32_t v[BC_N], incl[3];
+#pragma unroll
+    for (int i = 0; i < BC_N; ++i) v[i] = row < n_rows ? blk_counts[row * BC_N + i] : 0u;
+    // inclusive scan of the three list counters (BC_HBM, BC_HOST, BC_MISS are 0, 1, 2) within the wavefront
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        uint32_t x = v[k];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t y = __shfl_up(x, o);
+            if (lane >= (uint32_t)o) x += y;
+        }
+        incl[k] = x;
+    }
+    uint32_t tot[BC_N];
+#pragma unroll
+    for (int i = 0; i < BC_N; ++i) tot[i] = wave_sum(v[i]);
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < BC_N; ++i) s_wave[wave][i] = tot[i];
+    }
+    __syncthreads();
+    if (row < n_rows) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            uint32_t before = 0;
+            for (uint32_t w = 0; w < wave; ++w) before += s_wave[w][k];
+            row_prefix[row * 3 + k] = before + incl[k] - v[k];
+        }
+    }
+    if (tid < BC_N) {
+        uint32_t t = 0;
+        for (int w = 0; w < WAVES; ++w) t += s_wave[w][tid];
+        grp_totals[blockIdx.x * BC_N + tid] = t;
+    }
+}
+
 // KV, pass 2: list position = (totals of the workgroups before mine) + (totals of the waves before mine in the
 // workgroup) + (rank in my wave), so the lists come out in request order.  The last workgroup has seen every
 // total: it writes the counters of this fetch and adds them to the running totals.
@@ -196,8 +243,10 @@ __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__re
                                                  const uint8_t *__restrict__ kind, const uint32_t *__restrict__ blk_counts,
                                                  Rec *__restrict__ hbm_recs, Rec *__restrict__ host_recs,
                                                  uint32_t *__restrict__ miss_idx, uint32_t *cnt,
-                                                 unsigned long long *totals)
+                                                 unsigned long long *totals, const uint32_t *__restrict__ grp_totals,
+                                                 const uint32_t *__restrict__ row_prefix)
 {
+    // grp_totals / row_prefix: what scan_groups left (large tables), or null - then the rows themselves are added up.
     __shared__ uint32_t s_pre[BC_N];
     __shared__ uint32_t s_wave[WAVES][3];
     uint32_t tid = threadIdx.x, wave = tid >> 6;
@@ -207,10 +256,13 @@ __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__re
         uint32_t a[BC_N];
 #pragma unroll
         for (int i = 0; i < BC_N; ++i) a[i] = 0;
-        uint32_t upto = last ? gridDim.x : blockIdx.x;          // the last workgroup sums everybody, itself included
+        const uint32_t *rows = grp_totals ? grp_totals : blk_counts;
+        uint32_t n_all = grp_totals ? (gridDim.x + WG - 1) / WG : gridDim.x;
+        uint32_t mine = grp_totals ? blockIdx.x / WG : blockIdx.x;
+        uint32_t upto = last ? n_all : mine;                    // the last workgroup sums everybody, itself included
         for (uint32_t b = lane_id(); b < upto; b += 64) {
 #pragma unroll
-            for (int i = 0; i < BC_N; ++i) a[i] += blk_counts[b * BC_N + i];
+            for (int i = 0; i < BC_N; ++i) a[i] += rows[b * BC_N + i];
         }
 #pragma unroll
         for (int i = 0; i < BC_N; ++i) a[i] = wave_sum(a[i]);
@@ -227,10 +279,16 @@ __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__re
     if (lane_id() == 0) { s_wave[wave][0] = n_hbm; s_wave[wave][1] = n_host; s_wave[wave][2] = n_miss; }
     __syncthreads();
     uint32_t b_hbm = s_pre[BC_HBM], b_host = s_pre[BC_HOST], b_miss = s_pre[BC_MISS];
-    if (last) {                                                  // its prefix sums included its own row: take it out
-        b_hbm -= blk_counts[blockIdx.x * BC_N + BC_HBM];
-        b_host -= blk_counts[blockIdx.x * BC_N + BC_HOST];
-        b_miss -= blk_counts[blockIdx.x * BC_N + BC_MISS];
+    if (last) {                                  // its sums included its own row (its whole group): take that out
+        const uint32_t *own = grp_totals ? grp_totals + (blockIdx.x / WG) * BC_N : blk_counts + blockIdx.x * BC_N;
+        b_hbm -= own[BC_HBM];
+        b_host -= own[BC_HOST];
+        b_miss -= own[BC_MISS];
+    }
+    if (row_prefix) {                            // the rows of my group before mine
+        b_hbm += row_prefix[blockIdx.x * 3 + BC_HBM];
+        b_host += row_prefix[blockIdx.x * 3 + BC_HOST];
+        b_miss += row_prefix[blockIdx.x * 3 + BC_MISS];
     }
     for (uint32_t w = 0; w < wave; ++w) { b_hbm += s_wave[w][0]; b_host += s_wave[w][1]; b_miss += s_wave[w][2]; }
     if (k == K_HBM) hbm_recs[b_hbm + p_hbm] = tmp[r];

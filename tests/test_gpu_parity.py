@@ -123,6 +123,37 @@ def test_fetch_sizes_that_jump_between_calls():
         eh.close(); eo.close()
 
 
+def test_block_table_large_enough_for_the_grouped_compaction():
+    """More than 262 144 table cells: the compaction takes its three-kernel form (workgroup totals are grouped before they
+    are added up).  Sparse rows, empty rows, one full row, invalid ids and a row that runs past the destination."""
+    say("large block table")
+    wl = W.kv_decode(seed=35, n_layers=2, n_seq=3, min_len=3000, max_len=6000, p_cache=0.6, n_steps=1)
+    eo, eh = P.make_engines(wl)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        g = W.rng(35, 9)
+        n_seq, max_blocks = 41, 8192
+        assert n_seq * max_blocks > 1024 * 256
+        table = g.integers(0, wl.n_closed, size=(n_seq, max_blocks)).astype(np.int32)
+        table[g.random(table.shape) < 0.001] = -7                                # unknown ids here and there
+        table[5, 17] = wl.n_objects + 100
+        nb = g.integers(0, 300, size=n_seq).astype(np.int32)
+        nb[3], nb[11], nb[29], nb[40] = 0, max_blocks, 0, 1
+        sdb = np.concatenate([[0], np.cumsum(nb)[:-1]]).astype(np.uint64)
+        cap = int(nb.sum()) - 40                                                 # the last rows do not fit entirely
+        for layer in range(2):
+            a = eo.fetch_kv(layer, table, nb, sdb, cap)
+            b = eh.fetch_kv(layer, table, nb, sdb, cap)
+            P.assert_kv_equal(a, b, f"large table, layer {layer}")
+            assert b[3]["n_invalid"] > 40 and b[3]["n_requests"] == int(nb.sum())
+        caps = nb.astype(np.uint32)
+        a = eo.fetch_kv_head_major(0, table, nb, sdb, caps, int(nb.sum()), wl.shape.n_kv_heads, wl.shape.block_tokens)
+        b = eh.fetch_kv_head_major(0, table, nb, sdb, caps, int(nb.sum()), wl.shape.n_kv_heads, wl.shape.block_tokens)
+        P.assert_kv_equal(a, b, "large table, head-major")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- chunk sizes that are not a multiple of the 32 KiB tile -----------------------------------------------------
 
 @pytest.mark.parametrize("heads,dim,tokens,elt", [(1, 8, 1, 2), (3, 8, 16, 2), (8, 129 - 1, 16, 2), (8, 136, 16, 2),
