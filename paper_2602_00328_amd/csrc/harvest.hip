@@ -182,6 +182,8 @@ struct StreamState {
     uint32_t *grp_totals = nullptr, *row_prefix = nullptr;     // large tables: the middle pass of the compaction
     uint32_t *miss_idx = nullptr;
     uint32_t *cnt = nullptr;                // [C_N] counters of the last fetch; every fetch overwrites all of them
+    uint32_t *mark = nullptr;               // [MAX_EXPERTS / 32 + 1] routed-set bitmap and invalid-id count of large batches;
+                                            // zero between fetches
     bool fetched = false;                   // a fetch has been enqueued on this stream
     uint64_t seen_seq = 0;                  // directory edits this stream has been ordered after
     // control scratch (host-built lists)
@@ -253,7 +255,7 @@ void free_stream_state(StreamState *ss)
     for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) if (e) (void)hipEventDestroy(e);
     (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
     (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
-    (void)hipFree(ss->grp_totals); (void)hipFree(ss->row_prefix);
+    (void)hipFree(ss->grp_totals); (void)hipFree(ss->row_prefix); (void)hipFree(ss->mark);
     (void)hipFree(ss->ctl_buf);
     if (ss->h_feedback) (void)hipHostFree(ss->h_feedback);
 }
@@ -265,6 +267,8 @@ int init_stream_state(StreamState *ss)
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
     HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->mark, (MAX_EXPERTS / 32 + 1) * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(ss->mark, 0, (MAX_EXPERTS / 32 + 1) * sizeof(uint32_t)));
     HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
     memset(ss->h_feedback, 0, 64);
     HIP_TRY(hipHostGetDevicePointer((void **)&ss->d_feedback, ss->h_feedback, 0));
@@ -362,6 +366,7 @@ int release_after(Staging *st, hipStream_t s)
     return HARVEST_OK;
 }
 
+constexpr uint32_t MARKED_BATCH_IDS = 32768;      // routing-id batches beyond this take the two-kernel resolve
 constexpr uint32_t GROUPED_SCAN_ROWS = 1024;      // block tables of more than 262 144 cells take the three-kernel compaction
 
 uint32_t tiles_per_chunk(uint64_t chunk_bytes, uint32_t tile) { return (uint32_t)((chunk_bytes + tile - 1) / tile); }
@@ -1095,9 +1100,18 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = ensure_req_cap(ss, E))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     uint32_t *cnt = ss->cnt;
+    // a large batch of routing ids is marked by many workgroups first; the single resolving workgroup reads the bitmap
+    const bool marked = n_ids > MARKED_BATCH_IDS;
+    if (marked) {
+        uint32_t grid = (uint32_t)std::min<uint64_t>(1024, (n_ids + WG * 8 - 1) / (WG * 8));
+        hipLaunchKernelGGL(mark_experts, dim3(grid), dim3(WG), 0, ss->s, d_topk_ids, (uint32_t)n_ids, E, ss->mark,
+                           ss->mark + MAX_EXPERTS / 32);
+        HIP_TRY(hipGetLastError());
+    }
     hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
                        (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_EXPERT * C_N);
+                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_EXPERT * C_N, marked ? ss->mark : (uint32_t *)nullptr,
+                       marked ? ss->mark + MAX_EXPERTS / 32 : (uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
     return launch_gathers(ctx, ss, c, HARVEST_EXPERT, cnt, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);

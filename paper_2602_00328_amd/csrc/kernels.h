@@ -312,26 +312,60 @@ __global__ __launch_bounds__(WG) void compact_kv(uint32_t total, const Rec *__re
 // ---------------------------------------------------------------------------------------------------------
 constexpr uint32_t MAX_EXPERTS = 8192;
 
+// Large batches only: many workgroups mark the routed experts - each in a bitmap of its own in LDS, merged into
+// g_bitmap with one atomic per non-zero word - so that the single workgroup of resolve_experts need not read every
+// routing id itself (half a million ids cost it 0.4 ms).  g_bitmap and g_invalid are zero on entry; resolve_experts
+// takes their contents and leaves them zero again, so nothing has to be cleared between fetches or graph replays.
+__global__ __launch_bounds__(WG) void mark_experts(const int32_t *__restrict__ topk, uint32_t n_ids, uint32_t n_experts,
+                                                   uint32_t *g_bitmap, uint32_t *g_invalid)
+{
+    __shared__ uint32_t bm[MAX_EXPERTS / 32];
+    __shared__ uint32_t inval;
+    uint32_t tid = threadIdx.x, words = (n_experts + 31) / 32;
+    for (uint32_t i = tid; i < words; i += WG) bm[i] = 0;
+    if (tid == 0) inval = 0;
+    __syncthreads();
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + tid; i < n_ids; i += (uint64_t)gridDim.x * WG) {
+        int32_t e = topk[i];
+        if (e < 0 || (uint32_t)e >= n_experts) atomicAdd(&inval, 1u);
+        else atomicOr(&bm[e >> 5], 1u << (e & 31));
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < words; i += WG)
+        if (bm[i]) atomicOr(&g_bitmap[i], bm[i]);
+    if (tid == 0 && inval) atomicAdd(g_invalid, inval);
+}
+
 __global__ __launch_bounds__(WG) void resolve_experts(ClassDev c, uint32_t layer, uint32_t n_experts,
                                                       const int32_t *__restrict__ topk, uint32_t n_ids,
                                                       uint64_t staging, uint32_t n_staging,
                                                       uint64_t *__restrict__ expert_ptr, Rec *__restrict__ hbm_recs,
                                                       Rec *__restrict__ host_recs, uint32_t *__restrict__ miss_idx,
-                                                      uint32_t *cnt, unsigned long long *totals)
+                                                      uint32_t *cnt, unsigned long long *totals, uint32_t *g_bitmap,
+                                                      uint32_t *g_invalid)
 {
+    // g_bitmap != nullptr: mark_experts has already formed the routed set; it is taken from there (and cleared).
     __shared__ uint32_t bitmap[MAX_EXPERTS / 32];
     __shared__ uint32_t s_cnt[C_N];
     __shared__ uint32_t wave_tot[WG / 64];
     __shared__ uint32_t running;
     uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < MAX_EXPERTS / 32; i += WG) bitmap[i] = 0;
+    for (uint32_t i = tid; i < MAX_EXPERTS / 32; i += WG) {
+        uint32_t w = 0;
+        if (g_bitmap && i < (n_experts + 31) / 32) { w = g_bitmap[i]; g_bitmap[i] = 0; }
+        bitmap[i] = w;
+    }
     if (tid < C_N) s_cnt[tid] = 0;
     if (tid == 0) running = 0;
     __syncthreads();
-    for (uint32_t i = tid; i < n_ids; i += WG) {
-        int32_t e = topk[i];
-        if (e < 0 || (uint32_t)e >= n_experts) atomicAdd(&s_cnt[C_INVALID], 1u);
-        else atomicOr(&bitmap[e >> 5], 1u << (e & 31));
+    if (g_bitmap) {
+        if (tid == 0) { s_cnt[C_INVALID] = *g_invalid; *g_invalid = 0; }
+    } else {
+        for (uint32_t i = tid; i < n_ids; i += WG) {
+            int32_t e = topk[i];
+            if (e < 0 || (uint32_t)e >= n_experts) atomicAdd(&s_cnt[C_INVALID], 1u);
+            else atomicOr(&bitmap[e >> 5], 1u << (e & 31));
+        }
     }
     __syncthreads();
     for (uint32_t base = 0; base < n_experts; base += WG) {

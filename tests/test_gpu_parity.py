@@ -243,6 +243,29 @@ def test_expert_fetch_small():
 
 # ---- config 4, small: cache tier driven by an LRU policy --------------------------------------------------------
 
+def test_expert_fetch_with_a_very_large_batch_of_routing_ids():
+    """More than 32 768 routing ids: the routed set is marked by many workgroups before the resolving workgroup runs.
+    Every call must see its own routing only (the marks are cleared on the way), invalid ids are counted."""
+    say("experts, large batch")
+    ex = W.expert_offload(seed=37, shape=W.ExpertShape(n_layers=2, n_experts=48, d_model=64, d_ff=100), n_tokens=64)
+    eo, eh = P.make_engines(ex_wl=ex, poison=True)
+    try:
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        g = W.rng(37, 3)
+        everything = g.integers(0, 48, size=(30000, 4)).astype(np.int32)
+        everything[g.random(everything.shape) < 0.0005] = 48 + 5                      # a few ids no expert has
+        everything[17, 2] = -1
+        few = g.choice(np.arange(0, 48, 3), size=(20000, 2)).astype(np.int32)         # every third expert only
+        small = ex.routing(0, 1)
+        for i, (layer, topk) in enumerate(((0, everything), (1, few), (1, small), (0, few), (1, everything))):
+            a, b = eo.fetch_experts(layer, topk, 48), eh.fetch_experts(layer, topk, 48)
+            P.assert_experts_equal(a, b, f"large batch, call {i}")
+            assert b[4]["n_invalid"] == int(((topk < 0) | (topk >= 48)).sum())
+        assert eh.fetch_experts(1, few, 48)[4]["n_requests"] == len(np.unique(few))
+    finally:
+        eh.close(); eo.close()
+
+
 @pytest.mark.parametrize("from_staging", [False, True])
 def test_expert_lru_small(from_staging):
     """from_staging: experts that enter the cache tier are copied from the staging buffer the fetch has just filled
