@@ -479,8 +479,6 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     uint32_t planes = c.cfg.n_planes;
     ga.tiles_per_chunk = tpc_hbm;                      // both tiers walk 4 KiB tiles
     ga.n_planes = planes;
-    HIP_TRY(hipEventRecord(ss->fork, ss->s));
-    HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
     const bool profile = ctx->profile && !is_capturing(ss->s);        // timing events cannot be recorded into a graph
     const bool host_tier = c.cfg.n_host_slots != 0;
     // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
@@ -493,15 +491,25 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     // Which of the two gathers stays on the caller's stream: crossing to the side stream and back costs some 15 us each
     // way, so the one that takes longer - by the same report: host bytes at PCIe rate against HBM bytes at HBM rate,
     // about 1 : 48 per request - stays, and the short one takes the detour inside the long one's shadow.
-    bool host_stays = host_tier;
+    // And whether there is a detour at all: when even the longer of the two is expected to be over in less time than the
+    // two crossings take (a small fetch: a few dozen blocks from the host, or some tens of MiB from HBM), both run on the
+    // caller's stream one after the other, and so they do when the class has no host tier.
+    bool host_stays = host_tier, serial = !host_tier;
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
         uint64_t seen_host = *(volatile uint32_t *)&ss->h_feedback[HARVEST_N_CLASSES + cls];
         uint64_t guess = std::max<uint64_t>(1, seen - seen / 8) * tpc_hbm;
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
         host_stays = host_tier && seen_host * 48 > seen;
+        double bytes = (double)planes * c.cfg.chunk_bytes * n_rep;
+        double us_hbm = 2.0 * seen * bytes / 6.0e6, us_host = seen_host * bytes / 57.0e3;     // at 6 TB/s and 57 GB/s
+        serial = serial || std::max(us_hbm, us_host) < 35.0;
     }
-    hipStream_t s_host = host_stays ? ss->s : ss->side, s_hbm = host_stays ? ss->side : ss->s;
+    if (!serial) {
+        HIP_TRY(hipEventRecord(ss->fork, ss->s));
+        HIP_TRY(hipStreamWaitEvent(ss->side, ss->fork, 0));
+    }
+    hipStream_t s_host = (host_stays || serial) ? ss->s : ss->side, s_hbm = (host_stays && !serial) ? ss->side : ss->s;
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     for (uint32_t r = 0; r < n_rep; ++r) {
         for (uint32_t p = 0; p < 2; ++p) {
@@ -557,8 +565,10 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         }
     }
     ss->feedback_valid[cls] = true;
-    HIP_TRY(hipEventRecord(ss->join, ss->side));
-    HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
+    if (!serial) {
+        HIP_TRY(hipEventRecord(ss->join, ss->side));
+        HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
+    }
     return mark_last(ctx, ss);
 }
 
