@@ -97,8 +97,11 @@ enum harvest_class { HARVEST_KV = 0, HARVEST_EXPERT = 1, HARVEST_N_CLASSES = 2 }
 enum harvest_flags {
     HARVEST_FLAG_NO_DEVICE = 1,  /* directory bookkeeping only (no HIP call at all): for host-side tests */
     HARVEST_FLAG_POISON = 2,     /* revoke overwrites the freed cache slot with 0xA5 after the drain */
-    HARVEST_FLAG_PROFILE = 4     /* bracket the gather kernels with events; read them with harvest_profile
+    HARVEST_FLAG_PROFILE = 4,    /* bracket the gather kernels with events; read them with harvest_profile
                                     (launches recorded into a graph are not timed) */
+    HARVEST_FLAG_GENERAL_FETCH = 8 /* harvest_fetch_kv never takes its one-kernel form for small block tables (up to
+                                    1024 cells): every fetch runs resolve, compaction and the two gathers - for
+                                    measurements and tests of that path; results are the same either way */
 };
 
 enum harvest_evict_flags {

@@ -22,7 +22,7 @@ from . import _build
 HOST, CACHE, LOCAL, NONE = 0, 1, 2, 3
 OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV, EBUSY = 0, -1, -2, -3, -4, -5, -6, -7
 KV, EXPERT = 0, 1
-FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE = 1, 2, 4
+FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE, FLAG_GENERAL_FETCH = 1, 2, 4, 8
 EVICT_DEMOTE = 1
 
 u32, u64, i32, i64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p

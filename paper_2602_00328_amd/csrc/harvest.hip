@@ -201,7 +201,7 @@ struct harvest_prefetcher;
 
 struct harvest_ctx {
     harvest_config cfg{};
-    bool no_device = false, poison = false, profile = false;
+    bool no_device = false, poison = false, profile = false, general_fetch = false;
     int n_cu = 256;
     uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0, pcie_grid = 0;
     ClassState cls[HARVEST_N_CLASSES];
@@ -366,6 +366,8 @@ int release_after(Staging *st, hipStream_t s)
     return HARVEST_OK;
 }
 
+constexpr uint64_t SMALL_FETCH_CELLS = 1024;      // block tables up to this many cells (and tiles) are fetched by one kernel
+constexpr uint64_t SMALL_FETCH_TILES = 65535;
 constexpr uint32_t MARKED_BATCH_IDS = 32768;      // routing-id batches beyond this take the two-kernel resolve
 constexpr uint32_t GROUPED_SCAN_ROWS = 1024;      // block tables of more than 262 144 cells take the three-kernel compaction
 
@@ -662,6 +664,7 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
     ctx->no_device = cfg->flags & HARVEST_FLAG_NO_DEVICE;
     ctx->poison = cfg->flags & HARVEST_FLAG_POISON;
     ctx->profile = cfg->flags & HARVEST_FLAG_PROFILE;
+    ctx->general_fetch = cfg->flags & HARVEST_FLAG_GENERAL_FETCH;
     const uint64_t granule = cfg->shared_granule ? cfg->shared_granule : 4096;
     const bool shared = cfg->d_shared_cache != nullptr || ((cfg->flags & HARVEST_FLAG_NO_DEVICE) && cfg->shared_cache_bytes);
     if (shared) {
@@ -1039,6 +1042,27 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     if ((rc = ensure_req_cap(ss, (uint32_t)total))) return rc;
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     uint32_t *cnt = ss->cnt;
+    const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
+    if (!ctx->general_fetch && !head_major && n_layers == 1 && total <= SMALL_FETCH_CELLS && total * tpc <= SMALL_FETCH_TILES) {
+        // a small table: the whole fetch is one kernel (no compaction, no second stream) - see fetch_kv_small
+        GatherArgs ga{};
+        const ClassDev cd = class_dev(c);
+        for (uint32_t p = 0; p < 2; ++p) {
+            ga.src_base[T_HOST][p] = cd.pool[T_HOST][p];
+            ga.src_base[T_CACHE][p] = cd.pool[T_CACHE][p];
+            ga.src_base[T_LOCAL][p] = cd.pool[T_LOCAL][p];
+        }
+        ga.dst_base[0] = (uint64_t)d_dst_k; ga.dst_base[1] = (uint64_t)d_dst_v;
+        ga.chunk_bytes = c.cfg.chunk_bytes; ga.tiles_per_chunk = tpc; ga.n_planes = c.cfg.n_planes;
+        hipLaunchKernelGGL(fetch_kv_small, dim3((uint32_t)(total * tpc), c.cfg.n_planes), dim3(WG), 0, ss->s, cd, layer,
+                           d_block_table, d_n_blocks, n_seq, max_blocks, d_seq_dst_block, dst_capacity_blocks, ga,
+                           ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
+                           ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV);
+        HIP_TRY(hipGetLastError());
+        ss->fetched = true;
+        ss->feedback_valid[HARVEST_KV] = true;
+        return mark_last(ctx, ss);
+    }
     uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
     hipLaunchKernelGGL(classify_kv, dim3(n_wg), dim3(WG), 0, ss->s, class_dev(c), layer, d_block_table, d_n_blocks, n_seq,
                        max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts,

@@ -124,6 +124,38 @@ __device__ inline uint32_t wave_sum(uint32_t v)
 // ---------------------------------------------------------------------------------------------------------
 enum { BC_HBM = 0, BC_HOST, BC_MISS, BC_REQ, BC_LOCAL, BC_CACHE, BC_LOST, BC_INVALID, BC_N = 8 };
 
+// What cell r of the block table asks for: -1 nothing (beyond the row's length), 0..3 the tier of its block, 4 an invalid
+// request (unknown block, or a destination that does not fit).  For tiers 0..2 rec names source and destination.
+__device__ inline int resolve_cell(const ClassDev &c, uint32_t layer, const int32_t *__restrict__ table,
+                                   const int32_t *__restrict__ n_blocks, uint32_t max_blocks,
+                                   const uint64_t *__restrict__ seq_dst_block, uint64_t dst_cap,
+                                   const uint32_t *__restrict__ seq_cap_blocks, uint64_t strip_bytes, uint32_t r, Rec &rec)
+{
+    uint32_t s = r / max_blocks, j = r - s * max_blocks;
+    int32_t nb = n_blocks[s];
+    nb = nb < 0 ? 0 : (nb > (int32_t)max_blocks ? (int32_t)max_blocks : nb);
+    if (j >= (uint32_t)nb) return -1;
+    int32_t b = table[r];
+    uint64_t first = seq_dst_block[s];
+    uint64_t dst_chunk = first + j;
+    bool fits = dst_chunk < dst_cap;
+    uint64_t cap = 0;
+    if (seq_cap_blocks) {
+        cap = seq_cap_blocks[s];
+        fits = first + cap <= dst_cap && j < cap && cap < 65536;
+    }
+    if (b < 0 || (uint32_t)b >= c.n_objects || !fits) return 4;
+    uint64_t e = c.dir[b];
+    int tier = (int)entry_tier(e);
+    uint32_t slot = entry_slot(e);
+    rec.dst = seq_cap_blocks ? first * c.chunk_bytes + (uint64_t)j * strip_bytes : dst_chunk * c.chunk_bytes;
+    if (tier != T_NONE) {
+        if (slot >= slots_of(c, tier)) return 4;                // never true for a directory the library wrote
+        rec.src = chunk_offset(c, tier, layer, slot) | (uint64_t)tier | (cap << 48);
+    }
+    return tier;
+}
+
 __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
                                                   const int32_t *__restrict__ n_blocks, uint32_t n_seq,
                                                   uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
@@ -142,34 +174,8 @@ __global__ __launch_bounds__(WG) void classify_kv(ClassDev c, uint32_t layer, co
     uint32_t total = n_seq * max_blocks;
     int tier = -1;                       // -1 no request, 0..3 tier, 4 invalid
     Rec rec = { 0, 0 };
-    if (r < total) {
-        uint32_t s = r / max_blocks, j = r - s * max_blocks;
-        int32_t nb = n_blocks[s];
-        nb = nb < 0 ? 0 : (nb > (int32_t)max_blocks ? (int32_t)max_blocks : nb);
-        if (j < (uint32_t)nb) {
-            int32_t b = table[r];
-            uint64_t first = seq_dst_block[s];
-            uint64_t dst_chunk = first + j;
-            bool fits = dst_chunk < dst_cap;
-            uint64_t cap = 0;
-            if (seq_cap_blocks) {
-                cap = seq_cap_blocks[s];
-                fits = first + cap <= dst_cap && j < cap && cap < 65536;
-            }
-            if (b < 0 || (uint32_t)b >= c.n_objects || !fits) {
-                tier = 4;
-            } else {
-                uint64_t e = c.dir[b];
-                tier = (int)entry_tier(e);
-                uint32_t slot = entry_slot(e);
-                rec.dst = seq_cap_blocks ? first * c.chunk_bytes + (uint64_t)j * strip_bytes : dst_chunk * c.chunk_bytes;
-                if (tier != T_NONE) {
-                    if (slot >= slots_of(c, tier)) tier = 4;        // never true for a directory the library wrote
-                    else rec.src = chunk_offset(c, tier, layer, slot) | (uint64_t)tier | (cap << 48);
-                }
-            }
-        }
-    }
+    if (r < total)
+        tier = resolve_cell(c, layer, table, n_blocks, max_blocks, seq_dst_block, dst_cap, seq_cap_blocks, strip_bytes, r, rec);
     uint32_t k = (tier == T_LOCAL || tier == T_CACHE) ? K_HBM
                                                       : (tier == T_HOST ? K_HOST : (tier == T_NONE ? K_LOST : K_NONE));
     if (r < total) {
@@ -508,6 +514,84 @@ __global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const
         if (t >= n_tiles) break;
         idx = (uint32_t)t / tpc;
         x = recs[idx];
+    }
+}
+
+// The whole KV fetch in one kernel, for small block tables (token-major layout, one layer).  A fetch of a few blocks is
+// made of launch gaps, not of bytes: resolve, compaction and the two gathers are four dependent kernels of a few
+// microseconds each.  Here workgroup (cell r, tile k, plane p) resolves cell r by itself and copies its tile from whichever
+// tier holds the block (a host-tier tile is read over PCIe by the same 16-byte loads); nothing is compacted, so the grid
+// covers the padded table - which is why this is for small tables only.  The books (counters, miss list in request
+// order) are kept by the first workgroup alone, which walks the whole table once more, a cell per thread: no atomics on
+// shared counters (a thousand of them on one address take longer than the copy), nothing to zero.
+__global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
+                                                     const int32_t *__restrict__ n_blocks, uint32_t n_seq,
+                                                     uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
+                                                     uint64_t dst_cap, GatherArgs a, uint32_t *__restrict__ miss_idx,
+                                                     uint32_t *cnt, unsigned long long *totals, uint32_t *feedback_hbm,
+                                                     uint32_t *feedback_host)
+{
+    uint32_t tpc = a.tiles_per_chunk;
+    uint32_t r = blockIdx.x / tpc, k = blockIdx.x - r * tpc, plane = blockIdx.y;
+    uint32_t total = n_seq * max_blocks;                       // the host launches exactly total * tpc workgroups in x
+    {
+        Rec rec = { 0, 0 };
+        int tier = resolve_cell(c, layer, table, n_blocks, max_blocks, seq_dst_block, dst_cap, nullptr, 0, r, rec);
+        if (tier == T_HOST || tier == T_CACHE || tier == T_LOCAL) {
+            uint64_t off = (uint64_t)k * TILE_HBM;
+            uint64_t src = src_base_of(a, (uint32_t)tier, plane) + (rec.src & 0x0000FFFFFFFFFFFCull) + off;
+            uint64_t dst = (plane ? a.dst_base[1] : a.dst_base[0]) + rec.dst + off;
+            if (tier == T_HOST) copy_tile<1, false>(src, dst, a.chunk_bytes - off, threadIdx.x);
+            else copy_tile<1, true>(src, dst, a.chunk_bytes - off, threadIdx.x);
+        }
+    }
+    if (blockIdx.x != 0 || plane != 0) return;
+    // ---- the books: every cell once more, one per thread ----
+    __shared__ uint32_t s_cnt[C_N];
+    __shared__ uint32_t s_wave[WAVES];
+    __shared__ uint32_t s_base;
+    uint32_t tid = threadIdx.x, wave = tid >> 6;
+    if (tid < C_N) s_cnt[tid] = 0;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    for (uint32_t first = 0; first < total; first += WG) {
+        uint32_t q = first + tid;
+        Rec rec = { 0, 0 };
+        int tier = q < total ? resolve_cell(c, layer, table, n_blocks, max_blocks, seq_dst_block, dst_cap, nullptr, 0, q, rec) : -1;
+        bool miss = tier == T_HOST || tier == T_NONE;
+        uint32_t n_miss;
+        uint32_t rank = wave_rank(miss, n_miss);
+        if (lane_id() == 0) s_wave[wave] = n_miss;
+        const int which[6] = { C_REQ, C_LOCAL, C_CACHE, C_HOST, C_LOST, C_INVALID };
+        const bool pred[6] = { tier >= 0, tier == T_LOCAL, tier == T_CACHE, tier == T_HOST, tier == T_NONE, tier == 4 };
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            uint32_t n = (uint32_t)__popcll(__ballot(pred[i]));
+            if (lane_id() == 0 && n) atomicAdd(&s_cnt[which[i]], n);
+        }
+        __syncthreads();
+        uint32_t before = s_base;
+        for (uint32_t w = 0; w < wave; ++w) before += s_wave[w];
+        if (miss) miss_idx[before + rank] = q;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t t = 0;
+            for (int w = 0; w < WAVES; ++w) t += s_wave[w];
+            s_base += t;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        uint32_t hbm = s_cnt[C_LOCAL] + s_cnt[C_CACHE], host = s_cnt[C_HOST];
+        for (int i = 0; i <= C_INVALID; ++i) {
+            cnt[i] = s_cnt[i];
+            if (s_cnt[i]) atomicAdd(&totals[i], (unsigned long long)s_cnt[i]);
+        }
+        cnt[C_HBM_REQ] = hbm;
+        cnt[C_HOST_REQ] = host;
+        cnt[C_MISS] = s_base;
+        *feedback_hbm = hbm;
+        *feedback_host = host;
     }
 }
 

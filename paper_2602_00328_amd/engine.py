@@ -20,10 +20,11 @@ class HipEngine:
     name = "hip"
 
     def __init__(self, kv=None, expert=None, poison=False, device=0, profile=False, gather_wg_per_cu=0, host_wgs=0,
-                 two_streams=False, shared_cache_bytes=0, shared_granule=0):
+                 two_streams=False, shared_cache_bytes=0, shared_granule=0, general_fetch=False):
         """two_streams: KV work and expert work are enqueued on two HIP streams of their own (default priority).
         shared_cache_bytes: one cache pool for every class that has no cache slots of its own."""
-        flags = (B.FLAG_POISON if poison else 0) | (B.FLAG_PROFILE if profile else 0)
+        flags = (B.FLAG_POISON if poison else 0) | (B.FLAG_PROFILE if profile else 0) | \
+            (B.FLAG_GENERAL_FETCH if general_fetch else 0)
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
         self.spec = {KV: kv, EXPERT: expert}

@@ -20,11 +20,12 @@ def say(msg):
 
 # ---- config 1: tiny KV fetch, scatter back, round trip ------------------------------------------------------
 
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("fill", [W.FILL_NORMAL, W.FILL_TAG])
-def test_config1_tiny_kv_fetch_and_round_trip(fill):
+def test_config1_tiny_kv_fetch_and_round_trip(fill, general):
     say(f"config1 fill={fill}")
     wl = W.kv_tiny(0, fill_mode=fill)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         assert np.array_equal(ro.place_status, rh.place_status) and (rh.place_status == 0).all()
@@ -61,12 +62,13 @@ def test_config1_tiny_kv_fetch_and_round_trip(fill):
 
 # ---- tier independence on the GPU -----------------------------------------------------------------------------
 
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("p_cache", [0.0, 0.35, 1.0])
-def test_fetch_is_the_same_for_every_residency(p_cache):
+def test_fetch_is_the_same_for_every_residency(p_cache, general):
     say(f"residency p={p_cache}")
     wl = W.kv_decode(seed=1, n_layers=2, n_seq=3, min_len=300, max_len=900, p_cache=p_cache, n_steps=1)
     ref = W.kv_decode(seed=1, n_layers=2, n_seq=3, min_len=300, max_len=900, p_cache=0.5, n_steps=1)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
     eo2, _unused = None, None
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
@@ -84,10 +86,11 @@ def test_fetch_is_the_same_for_every_residency(p_cache):
 
 # ---- config 2, small: decode steps with append, write-back, demotion, placement -------------------------------
 
-def test_kv_decode_steps_small():
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
+def test_kv_decode_steps_small(general):
     say("kv decode small")
     wl = W.kv_decode(seed=2, n_layers=3, n_seq=4, min_len=500, max_len=2000, n_steps=40)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(40):
@@ -158,13 +161,14 @@ def test_block_table_large_enough_for_the_grouped_compaction():
 
 @pytest.mark.parametrize("heads,dim,tokens,elt", [(1, 8, 1, 2), (3, 8, 16, 2), (8, 129 - 1, 16, 2), (8, 136, 16, 2),
                                                   (5, 200, 48, 2), (8, 128, 16, 1), (8, 128, 16, 4), (2, 80, 16, 1)])
-def test_ragged_chunk_sizes(heads, dim, tokens, elt):
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
+def test_ragged_chunk_sizes(heads, dim, tokens, elt, general):
     """Block sizes off the 4 KiB / 32 KiB tiles, and the element sizes of fp8, fp16 / bf16 and fp32 KV caches."""
     shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=elt)
     say(f"ragged chunk {shape.chunk_bytes} bytes")
     wl = W.kv_decode(seed=4, n_seq=3, min_len=20 * tokens, max_len=60 * tokens, n_steps=2 * tokens, shape=shape,
                      fill_mode=W.FILL_TAG)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(2 * tokens):
@@ -176,10 +180,11 @@ def test_ragged_chunk_sizes(heads, dim, tokens, elt):
 
 # ---- degenerate requests ----------------------------------------------------------------------------------------
 
-def test_empty_invalid_duplicate_and_overflowing_requests():
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
+def test_empty_invalid_duplicate_and_overflowing_requests(general):
     say("edge cases")
     wl = W.kv_decode(seed=5, n_layers=1, n_seq=2, min_len=64, max_len=128, n_steps=1, fill_mode=W.FILL_TAG)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         n = wl.n_closed
@@ -335,13 +340,14 @@ def test_place_from_device_memory_kv_all_layers():
 N_STRESS = 500          # the step count of the revocation-stress configuration
 
 
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("overlap_revoke", [False, True])
-def test_revocation_stress_two_streams(overlap_revoke):
+def test_revocation_stress_two_streams(overlap_revoke, general):
     say(f"revocation stress overlap={overlap_revoke}")
     wl = W.kv_decode(seed=8, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=N_STRESS)
     sh = W.ExpertShape(n_layers=2, n_experts=16, d_model=64, d_ff=100)
     ex = W.expert_offload(seed=8, shape=sh, n_tokens=64)
-    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
