@@ -8,8 +8,11 @@
 //                              workgroup totals of the first kernel become the offsets of the second.  Keeping the
 //                              lists in request order makes the gather's writes one ascending stream, worth ~6% of
 //                              HBM bandwidth over lists ordered by racing atomics.
+//                              Very large tables get a middle pass (scan_groups) that groups the workgroup totals.
+//   fetch_kv_small           : small block tables - the whole fetch in one launch, every workgroup resolving its own cell.
 //   resolve_experts          : the same for expert weights (Section 4.3: residency map) - one workgroup forms the
-//                              distinct set of routed experts and walks it in ascending order.
+//                              distinct set of routed experts and walks it in ascending order (very large batches of
+//                              routing ids are marked by many workgroups first: mark_experts).
 //   gather                   : the copy itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte non-temporal
 //                              load and store per thread, as many workgroups as tiles, plane K before plane V
 //                              (measured on MI355X: short workgroups beat deep unrolling and persistent grids by
