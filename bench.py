@@ -38,8 +38,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
-    ap.add_argument("--workload", default="kv_decode", choices=["kv_decode", "experts_phi", "experts_qwen"],
-                    help="kv_decode = configs[1] (the benchmark line); experts_* = configs[2] / configs[3], extra lines")
+    ap.add_argument("--workload", default="kv_decode", choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen"],
+                    help="kv_decode = configs[1] (the benchmark line); kv_tiny = configs[0] (fetch latency, both forms of the "
+                         "fetch); experts_* = configs[2] / configs[3], extra lines")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
@@ -180,6 +181,79 @@ COUNT_KEYS = ("n_requests", "n_local", "n_cache", "n_host", "n_lost", "n_invalid
 
 def kv_totals(stats):
     return {k: int(getattr(stats.fetch[0], k)) for k in COUNT_KEYS}
+
+
+def bench_tiny(args):
+    """configs[0]: the tiny KV fetch (16 sequences x 16 blocks, 60 % in the cache tier), its write-back and the fetch
+    again, checked against the oracle.  Its size says nothing about bandwidth; what it shows is the latency floor of a
+    fetch, for the one-kernel form small tables take and for the general path."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from workloads import scenarios as S
+    from oracle.engine import OracleEngine
+    from paper_2602_00328_amd.engine import HipEngine
+    wl = W.kv_tiny(args.seed)
+    chunk = wl.shape.chunk_bytes
+    eo = OracleEngine(kv=S.kv_spec(wl))
+    ro = S.KVRun(eo, wl)
+    want = ro.fetch(0)
+    res, exact = {}, True
+    for name, general in (("one_kernel", False), ("general_path", True)):
+        eng = HipEngine(kv=S.kv_spec(wl), general_fetch=general)
+        run = S.KVRun(eng, wl)
+        table, nb = run.table_arrays()
+        dev = eng.dev
+        d_table, d_nb = torch.from_numpy(table).to(dev), torch.from_numpy(nb).to(dev)
+        d_sdb = torch.from_numpy(run.seq_dst_block.view(np.int64)).to(dev)
+        dst = [torch.zeros(run.cap * chunk, dtype=torch.uint8, device=dev) for _ in range(2)]
+        ids = np.concatenate(wl.tables).astype(np.uint32)
+        blk = np.arange(ids.size)
+
+        def fetch():
+            eng.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, run.cap)
+
+        for _ in range(args.warmup):
+            fetch()
+        torch.cuda.synchronize()
+        lat = []
+        for _ in range(args.steps):
+            a = time.perf_counter()
+            fetch()
+            torch.cuda.synchronize()
+            lat.append(time.perf_counter() - a)
+        a = time.perf_counter()
+        for _ in range(args.steps):
+            fetch()
+        torch.cuda.synchronize()
+        b2b = (time.perf_counter() - a) / args.steps
+        a = time.perf_counter()
+        for _ in range(args.steps):                      # the round trip: gather, scatter the same bytes back, gather again
+            fetch()
+            eng.h.evict(0, 0, ids, dst[0], dst[1], blk, run.cap, 0)
+        fetch()
+        torch.cuda.synchronize()
+        trip = (time.perf_counter() - a) / args.steps
+        counts, _, _ = eng.h.fetch_info()
+        exact &= bool(np.array_equal(dst[0].cpu().numpy(), want[0]) and np.array_equal(dst[1].cpu().numpy(), want[1])
+                      and counts == want[3])
+        res[name] = {"latency_us": round(float(np.median(lat)) * 1e6, 1), "back_to_back_us": round(b2b * 1e6, 1),
+                     "fetch_plus_write_back_us": round(trip * 1e6, 1)}
+        log(f"[bench] kv_tiny {name}: {res[name]}")
+        eng.close()
+    eo.close()
+    payload = ids.size * 2 * chunk
+    best = res["one_kernel"]["back_to_back_us"] * 1e-6
+    print(json.dumps({
+        "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
+        "value": round(2 * payload / best / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(best * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": "configs[0]: tiny KV fetch, 16 sequences x 16 blocks of 2 x 32 KiB, 60% in the cache tier / 40% "
+                               "on the host, one layer; a latency case - too small to say anything about bandwidth",
+                   "seed": args.seed},
+        "objects_per_s": round(ids.size / best), "bit_exact": exact, "served": want[3], "latency": res,
+        "roofline": None, "cpu_baseline": None}), flush=True)
 
 
 def bench_experts(args):
@@ -385,6 +459,8 @@ def main():
     from paper_2602_00328_amd.engine import HipEngine
 
     torch.cuda.set_device(0)
+    if args.workload == "kv_tiny":
+        return bench_tiny(args)
     if args.workload != "kv_decode":
         return bench_experts(args)
     dev = torch.device("cuda", 0)
