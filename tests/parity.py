@@ -85,21 +85,22 @@ def smoke():
     wl = W.kv_decode(seed=3, n_layers=2, n_seq=3, min_len=40, max_len=90, n_steps=20, fill_mode=W.FILL_TAG)
     ex = W.expert_offload(seed=3, shape=W.ExpertShape(n_layers=2, n_experts=8, d_model=32, d_ff=50), n_tokens=6,
                           fill_mode=W.FILL_TAG)
-    eo, eh = make_engines(wl, ex, poison=True)
-    try:
-        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
-        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
-        for t in range(20):
-            assert_kv_equal(ro.step(t), rh.step(t), f"smoke kv step {t}")
-            assert_experts_equal(xo.fetch(t, t % 2), xh.fetch(t, t % 2), f"smoke experts step {t}")
-            if t == 10:
-                assert ro.revoke_quarter(t)[1] == rh.revoke_quarter(t)[1]
-                assert xo.revoke_quarter(t)[1] == xh.revoke_quarter(t)[1]
-            if t == 15:
-                assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
-                assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
-        assert_dirs_equal(eo, eh, S.KV, wl.n_objects, "smoke")
-        assert_tiers_equal(eo, eh, S.KV, 2, what="smoke")
-    finally:
-        eh.close()
-        eo.close()
+    for general in (False, True):              # the one-kernel form small tables take, then the general path
+        eo, eh = make_engines(wl, ex, poison=True, hip_kwargs=dict(general_fetch=general))
+        try:
+            ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+            xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+            for t in range(20):
+                assert_kv_equal(ro.step(t), rh.step(t), f"smoke kv step {t}")
+                assert_experts_equal(xo.fetch(t, t % 2), xh.fetch(t, t % 2), f"smoke experts step {t}")
+                if t == 10:
+                    assert ro.revoke_quarter(t)[1] == rh.revoke_quarter(t)[1]
+                    assert xo.revoke_quarter(t)[1] == xh.revoke_quarter(t)[1]
+                if t == 15:
+                    assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                    assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
+            assert_dirs_equal(eo, eh, S.KV, wl.n_objects, "smoke")
+            assert_tiers_equal(eo, eh, S.KV, 2, what="smoke")
+        finally:
+            eh.close()
+            eo.close()
