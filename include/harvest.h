@@ -100,7 +100,7 @@ enum harvest_flags {
     HARVEST_FLAG_PROFILE = 4,    /* bracket the gather kernels with events; read them with harvest_profile
                                     (launches recorded into a graph are not timed) */
     HARVEST_FLAG_GENERAL_FETCH = 8 /* harvest_fetch_kv never takes its one-kernel form for small block tables (up to
-                                    1024 cells): every fetch runs resolve, compaction and the two gathers - for
+                                    4096 cells): every fetch runs resolve, compaction and the two gathers - for
                                     measurements and tests of that path; results are the same either way */
 };
 
@@ -134,7 +134,9 @@ typedef struct harvest_config {
     uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (24) */
     uint32_t shared_granule;        /* segment granule of the shared cache pool in bytes: a power of two >= 256;
                                        0 = 4096 */
-    uint32_t reserved[5];           /* must be 0 */
+    uint32_t small_fetch_cells;     /* tuning: harvest_fetch_kv takes its one-kernel form for block tables of up to this
+                                       many cells (n_seq * max_blocks); 0 = default (4096) */
+    uint32_t reserved[4];           /* must be 0 */
     void *d_shared_cache;           /* optional shared cache pool (device memory, 256-byte aligned), see below */
     uint64_t shared_cache_bytes;    /* its size: a multiple of the granule, at most 2^30 granules */
 } harvest_config;

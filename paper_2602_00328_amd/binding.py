@@ -36,7 +36,7 @@ class harvest_class_config(ctypes.Structure):
 
 class harvest_config(ctypes.Structure):
     _fields_ = [("flags", u32), ("device", i32), ("cls", harvest_class_config * 2),
-                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("reserved", u32 * 5),
+                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("small_fetch_cells", u32), ("reserved", u32 * 4),
                 ("d_shared_cache", vp), ("shared_cache_bytes", u64)]
 
 
@@ -156,7 +156,8 @@ class Harvest:
     """A library context plus the pools it borrows (allocated here with torch / harvest_pinned_alloc)."""
 
     def __init__(self, kv: ClassSpec | None = None, expert: ClassSpec | None = None, flags: int = 0, device: int = 0,
-                 gather_wg_per_cu: int = 0, host_wgs: int = 0, shared_cache_bytes: int = 0, shared_granule: int = 0):
+                 gather_wg_per_cu: int = 0, host_wgs: int = 0, shared_cache_bytes: int = 0, shared_granule: int = 0,
+                 small_fetch_cells: int = 0):
         """shared_cache_bytes > 0: one device pool of that size from which every class with n_cache_slots == 0 carves
         its cache-tier segments (best-fit)."""
         self.flags, self.device = flags, device
@@ -171,6 +172,7 @@ class Harvest:
         cfg = harvest_config()
         cfg.flags, cfg.device = flags, device
         cfg.gather_wg_per_cu, cfg.host_wgs = gather_wg_per_cu, host_wgs
+        cfg.small_fetch_cells = small_fetch_cells
         cfg.shared_cache_bytes, cfg.shared_granule = shared_cache_bytes, shared_granule
         self.shared_cache = None
         if shared_cache_bytes and not self.no_device:

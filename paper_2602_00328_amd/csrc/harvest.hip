@@ -204,6 +204,7 @@ struct harvest_ctx {
     bool no_device = false, poison = false, profile = false, general_fetch = false;
     int n_cu = 256;
     uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0, pcie_grid = 0;
+    uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
     hipEvent_t ctl_evt = nullptr;            // recorded after every directory edit on the control stream
@@ -366,8 +367,9 @@ int release_after(Staging *st, hipStream_t s)
     return HARVEST_OK;
 }
 
-constexpr uint64_t SMALL_FETCH_CELLS = 1024;      // block tables up to this many cells (and tiles) are fetched by one kernel
-constexpr uint64_t SMALL_FETCH_TILES = 65535;
+constexpr uint64_t SMALL_FETCH_CELLS = 4096;      // block tables up to this many cells are fetched by one kernel (measured:
+                                                  // it wins up to 4 096 cells and loses from 8 192 on)
+constexpr uint64_t SMALL_FETCH_TILES = 1u << 22;      // and never more workgroups than this in x
 constexpr uint32_t MARKED_BATCH_IDS = 32768;      // routing-id batches beyond this take the two-kernel resolve
 constexpr uint32_t GROUPED_SCAN_ROWS = 1024;      // block tables of more than 262 144 cells take the three-kernel compaction
 
@@ -665,6 +667,7 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
     ctx->poison = cfg->flags & HARVEST_FLAG_POISON;
     ctx->profile = cfg->flags & HARVEST_FLAG_PROFILE;
     ctx->general_fetch = cfg->flags & HARVEST_FLAG_GENERAL_FETCH;
+    ctx->small_cells = cfg->small_fetch_cells ? cfg->small_fetch_cells : SMALL_FETCH_CELLS;
     const uint64_t granule = cfg->shared_granule ? cfg->shared_granule : 4096;
     const bool shared = cfg->d_shared_cache != nullptr || ((cfg->flags & HARVEST_FLAG_NO_DEVICE) && cfg->shared_cache_bytes);
     if (shared) {
@@ -1043,7 +1046,7 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     uint32_t *cnt = ss->cnt;
     const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
-    if (!ctx->general_fetch && !head_major && n_layers == 1 && total <= SMALL_FETCH_CELLS && total * tpc <= SMALL_FETCH_TILES) {
+    if (!ctx->general_fetch && !head_major && n_layers == 1 && total <= ctx->small_cells && total * tpc <= SMALL_FETCH_TILES) {
         // a small table: the whole fetch is one kernel (no compaction, no second stream) - see fetch_kv_small
         GatherArgs ga{};
         const ClassDev cd = class_dev(c);

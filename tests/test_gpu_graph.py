@@ -14,13 +14,13 @@ import parity as P
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("min_len,max_len", [(2000, 6000), (200, 600)], ids=["general path", "one-kernel path"])
-def test_captured_fetch_follows_residency_changes_across_replays(min_len, max_len):
-    """The larger table goes through resolve, compaction and the two gathers; the smaller one (under 1 024 cells) is
-    fetched by the single kernel that serves small tables."""
+@pytest.mark.parametrize("general", [True, False], ids=["general path", "one-kernel path"])
+def test_captured_fetch_follows_residency_changes_across_replays(general):
+    """Once through resolve, compaction and the two gathers, once through the single kernel that serves small tables
+    (this one has 1 125 cells)."""
     print("graph capture", flush=True)
-    wl = W.kv_decode(seed=11, n_layers=2, n_seq=3, min_len=min_len, max_len=max_len, p_cache=0.6, n_steps=1)
-    eo, eh = P.make_engines(wl, poison=True, cache_slack=64)
+    wl = W.kv_decode(seed=11, n_layers=2, n_seq=3, min_len=2000, max_len=6000, p_cache=0.6, n_steps=1)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=64, hip_kwargs=dict(general_fetch=general))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         dev = eh.dev
@@ -65,7 +65,7 @@ def test_captured_fetch_follows_residency_changes_across_replays(min_len, max_le
         assert c0 == c1
         ids_o, _ = ro.revoke_quarter(1)
         ids_h, _ = rh.revoke_quarter(1)
-        assert np.array_equal(ids_o, ids_h) and len(ids_h) > (50 if min_len >= 2000 else 5)
+        assert np.array_equal(ids_o, ids_h) and len(ids_h) > 50
         c2 = replay_and_check("replay 3 (a quarter revoked, slots poisoned)")
         assert c2["n_host"] > c1["n_host"] and c2["n_cache"] < c1["n_cache"]
         host_only = [b for b in range(wl.n_closed) if eh.lookup(S.KV, b)[0] == S.HOST][:40]

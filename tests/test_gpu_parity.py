@@ -108,7 +108,7 @@ def test_fetch_sizes_that_jump_between_calls():
     before runs on a grid far too short and has to loop, one far smaller finds most of its grid empty."""
     say("jumping fetch sizes")
     wl = W.kv_decode(seed=31, n_layers=2, n_seq=3, min_len=12000, max_len=24000, p_cache=0.8, n_steps=1)
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=True))          # the path whose grids are sized that way
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         table, nb = rh.table_arrays()
