@@ -1046,7 +1046,7 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     uint32_t *cnt = ss->cnt;
     const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
-    if (!ctx->general_fetch && !head_major && n_layers == 1 && total <= ctx->small_cells && total * tpc <= SMALL_FETCH_TILES) {
+    if (!ctx->general_fetch && !head_major && n_layers <= 65535 && total <= ctx->small_cells && total * tpc <= SMALL_FETCH_TILES) {
         // a small table: the whole fetch is one kernel (no compaction, no second stream) - see fetch_kv_small
         GatherArgs ga{};
         const ClassDev cd = class_dev(c);
@@ -1057,9 +1057,9 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
         }
         ga.dst_base[0] = (uint64_t)d_dst_k; ga.dst_base[1] = (uint64_t)d_dst_v;
         ga.chunk_bytes = c.cfg.chunk_bytes; ga.tiles_per_chunk = tpc; ga.n_planes = c.cfg.n_planes;
-        hipLaunchKernelGGL(fetch_kv_small, dim3((uint32_t)(total * tpc), c.cfg.n_planes), dim3(WG), 0, ss->s, cd, layer,
-                           d_block_table, d_n_blocks, n_seq, max_blocks, d_seq_dst_block, dst_capacity_blocks, ga,
-                           ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
+        hipLaunchKernelGGL(fetch_kv_small, dim3((uint32_t)(total * tpc), c.cfg.n_planes, n_layers), dim3(WG), 0, ss->s, cd,
+                           layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_seq_dst_block, dst_capacity_blocks, ga,
+                           dst_layer_stride, ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
                            ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV);
         HIP_TRY(hipGetLastError());
         ss->fetched = true;

@@ -524,14 +524,16 @@ __global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const
 // made of launch gaps, not of bytes: resolve, compaction and the two gathers are four dependent kernels of a few
 // microseconds each.  Here workgroup (cell r, tile k, plane p) resolves cell r by itself and copies its tile from whichever
 // tier holds the block (a host-tier tile is read over PCIe by the same 16-byte loads); nothing is compacted, so the grid
-// covers the padded table - which is why this is for small tables only.  The books (counters, miss list in request
+// covers the padded table - which is why this is for small tables only.  blockIdx.z counts consecutive layers (an object
+// has the same slot in every layer): layer + z is read, dst_step * z further into the destination is written.  The books (counters, miss list in request
 // order) are kept by the first workgroup alone, which walks the whole table once more, a cell per thread: no atomics on
 // shared counters (a thousand of them on one address take longer than the copy), nothing to zero.
 __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer, const int32_t *__restrict__ table,
                                                      const int32_t *__restrict__ n_blocks, uint32_t n_seq,
                                                      uint32_t max_blocks, const uint64_t *__restrict__ seq_dst_block,
-                                                     uint64_t dst_cap, GatherArgs a, uint32_t *__restrict__ miss_idx,
-                                                     uint32_t *cnt, unsigned long long *totals, uint32_t *feedback_hbm,
+                                                     uint64_t dst_cap, GatherArgs a, uint64_t dst_step,
+                                                     uint32_t *__restrict__ miss_idx, uint32_t *cnt,
+                                                     unsigned long long *totals, uint32_t *feedback_hbm,
                                                      uint32_t *feedback_host)
 {
     uint32_t tpc = a.tiles_per_chunk;
@@ -539,17 +541,17 @@ __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer,
     uint32_t total = n_seq * max_blocks;                       // the host launches exactly total * tpc workgroups in x
     {
         Rec rec = { 0, 0 };
-        int tier = resolve_cell(c, layer, table, n_blocks, max_blocks, seq_dst_block, dst_cap, nullptr, 0, r, rec);
+        int tier = resolve_cell(c, layer + blockIdx.z, table, n_blocks, max_blocks, seq_dst_block, dst_cap, nullptr, 0, r, rec);
         if (tier == T_HOST || tier == T_CACHE || tier == T_LOCAL) {
             uint64_t off = (uint64_t)k * TILE_HBM;
             uint64_t src = src_base_of(a, (uint32_t)tier, plane) + (rec.src & 0x0000FFFFFFFFFFFCull) + off;
-            uint64_t dst = (plane ? a.dst_base[1] : a.dst_base[0]) + rec.dst + off;
+            uint64_t dst = (plane ? a.dst_base[1] : a.dst_base[0]) + (uint64_t)blockIdx.z * dst_step + rec.dst + off;
             if (tier == T_HOST) copy_tile<1, false>(src, dst, a.chunk_bytes - off, threadIdx.x);
             else copy_tile<1, true>(src, dst, a.chunk_bytes - off, threadIdx.x);
         }
     }
-    if (blockIdx.x != 0 || plane != 0) return;
-    // ---- the books: every cell once more, one per thread ----
+    if (blockIdx.x != 0 || plane != 0 || blockIdx.z != 0) return;
+    // ---- the books: every cell once more, one per thread (residency is the same for every layer) ----
     __shared__ uint32_t s_cnt[C_N];
     __shared__ uint32_t s_wave[WAVES];
     __shared__ uint32_t s_base;

@@ -570,15 +570,16 @@ def test_one_plane_kv_class():
 
 # ---- several layers in one call --------------------------------------------------------------------------------
 
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("shared", [False, True])
-def test_fetch_of_several_layers_in_one_call(shared):
-    say(f"multi-layer fetch, shared pool {shared}")
+def test_fetch_of_several_layers_in_one_call(shared, general):
+    say(f"multi-layer fetch, shared pool {shared}, general path {general}")
     wl = W.kv_decode(seed=24, n_layers=5, n_seq=3, min_len=300, max_len=900, n_steps=20)
     kw = {}
     if shared:
         obj = 5 * 2 * wl.shape.chunk_bytes
         kw = dict(shared_cache_bytes=(int(wl.resident.sum()) - 3) * obj, shared_granule=4096)
-    eo, eh = P.make_engines(wl, poison=True, **kw)
+    eo, eh = P.make_engines(wl, poison=True, hip_kwargs=dict(general_fetch=general), **kw)
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(20):
