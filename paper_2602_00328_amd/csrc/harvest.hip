@@ -502,7 +502,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
         uint64_t seen_host = *(volatile uint32_t *)&ss->h_feedback[HARVEST_N_CLASSES + cls];
-        uint64_t guess = std::max<uint64_t>(1, seen - seen / 8) * tpc_hbm;
+        // (the head-major kernel, whose tiles cost more address arithmetic, does best on an exact grid: +0.8 %)
+        uint64_t guess = std::max<uint64_t>(1, hm ? seen : seen - seen / 8) * tpc_hbm;
         want = std::min(max_tiles, std::max<uint64_t>(guess, 16ull * ctx->n_cu));
         host_stays = host_tier && seen_host * 48 > seen;
         double bytes = (double)planes * c.cfg.chunk_bytes * n_rep;
