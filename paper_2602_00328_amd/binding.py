@@ -195,6 +195,7 @@ class Harvest:
                     if not ptr:
                         raise HarvestError(EHIP, f"pinned allocation of {nbytes} bytes")
                     self._host_ptr[(k, p)] = ptr
+                    ctypes.memset(ptr, 0, nbytes)          # like the device pools: slots nobody has written read as zeros
                     buf = (ctypes.c_uint8 * nbytes).from_address(ptr)
                     self._host_np[(k, p)] = np.frombuffer(buf, dtype=np.uint8).reshape(
                         sp.n_layers, sp.n_host_slots, sp.chunk_bytes)
