@@ -156,3 +156,75 @@ def test_random_operations_in_lock_step(seed, general, shared):
             P.assert_shared_pools_equal(eo, eh, "after the random sequence")
     finally:
         eh.close(); eo.close()
+
+
+EXPERT = 1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_expert_operations_in_lock_step(seed):
+    """The expert class: routing batches of every size (also beyond the batch size at which the routed set is marked by
+    many workgroups), staging buffers that overflow, placements from the host and from the staging buffer the fetch
+    has just filled, revocations, write-backs of new expert bytes."""
+    print(f"random expert operations, seed {seed}", flush=True)
+    g = W.rng(seed, 901)
+    n_layers, E, chunk = 3, 12, 208
+    n = n_layers * E
+    sp = SimpleNamespace(n_layers=1, n_planes=1, chunk_bytes=chunk, max_objects=n, n_host_slots=n, n_cache_slots=14,
+                         n_local_slots=6, n_experts=E)
+    eo = OracleEngine(expert=sp, poison=True)
+    eh = HipEngine(expert=sp, poison=True)
+    try:
+        local = set(int(i) for i in g.permutation(n)[:5])
+        hs = g.permutation(n)
+        for i in range(n):                                             # ids follow (layer, expert): one call per object
+            tier = LOCAL if i in local else HOST
+            ro, rh, err = both(lambda: eo.register(EXPERT, 1, [int(hs[i])], tier), lambda: eh.register(EXPERT, 1, [int(hs[i])], tier))
+            assert err is None and int(ro[0]) == int(rh[0]) == i
+        val = g.integers(0, 256, size=n * chunk, dtype=np.uint8)
+        both(lambda: eo.evict(EXPERT, 0, np.arange(n), val, None, np.arange(n), n),
+             lambda: eh.evict(EXPERT, 0, np.arange(n), val, None, np.arange(n), n))
+        last = None                                                    # (layer, kind, where, n_staging) of the last fetch
+        n_from = 0
+        for step in range(120):
+            op = int(g.integers(0, 8))
+            ids = g.integers(0, n + (1 if g.random() < 0.04 else 0), size=int(g.integers(1, 6))).astype(np.uint32)
+            if op == 0:
+                ro, rh, err = both(lambda: eo.place(EXPERT, ids), lambda: eh.place(EXPERT, ids))
+                assert err is not None or np.array_equal(ro, rh)
+            elif op == 1:
+                ro, rh, err = both(lambda: eo.revoke(EXPERT, ids), lambda: eh.revoke(EXPERT, ids))
+                assert err is not None or [int(i) for i in ro] == [int(i) for i in rh]
+            elif op == 2:
+                uniq = np.unique(ids)
+                y = g.integers(0, 256, size=uniq.size * chunk, dtype=np.uint8)
+                both(lambda: eo.evict(EXPERT, 0, uniq, y, None, np.arange(uniq.size), uniq.size),
+                     lambda: eh.evict(EXPERT, 0, uniq, y, None, np.arange(uniq.size), uniq.size))
+            elif op == 3 and last is not None:                          # from the staging buffer of the last fetch
+                layer, kind, where, n_staging = last
+                staged = [layer * E + e for e in range(E) if kind[e] == 2]
+                if staged:
+                    pick = [int(i) for i in g.permutation(staged)[:3]]
+                    ranks = [int(where[i - layer * E]) for i in pick]
+                    ro, rh, err = both(lambda: eo.place_from(EXPERT, pick, eo.last_staging(), None, ranks, n_staging),
+                                       lambda: eh.place_from(EXPERT, pick, eh.last_staging(), None, ranks, n_staging))
+                    assert err is None and np.array_equal(ro, rh)
+                    n_from += int((ro == 0).sum())
+            else:
+                layer = int(g.integers(0, n_layers))
+                n_tok = int(g.choice([0, 1, 3, 40, 9000]))
+                topk = g.integers(0, E, size=(n_tok, 4)).astype(np.int32)
+                if n_tok:
+                    topk[g.random(topk.shape) < 0.01] = int(g.integers(-2, E + 3))
+                    if g.random() < 0.5:
+                        topk = (topk // 3) * 3                          # a sparse set of experts
+                n_staging = int(g.choice([E, E, 5, 1]))
+                a, b = eo.fetch_experts(layer, topk, n_staging), eh.fetch_experts(layer, topk, n_staging)
+                P.assert_experts_equal(a, b, f"step {step}")
+                last = (layer, b[1], b[2], n_staging)
+            for i in range(n):
+                assert eo.lookup(EXPERT, i) == eh.lookup(EXPERT, i), (step, i)
+        assert n_from > 3
+        P.assert_tiers_equal(eo, eh, EXPERT, 1, what="after the random expert sequence")
+    finally:
+        eh.close(); eo.close()
