@@ -5,8 +5,10 @@
 //   StreamState - per caller stream: device scratch (HBM list, host list, miss list, counters), a side stream for
 //                 the host-tier gather, fork/join events and the "last operation" event the revocation drain waits on.
 //   Staging     - pinned host blocks through which host-built lists reach the device without blocking the caller.
-//   ctl stream  - the single writer of the device directory: every directory edit is a dir_write kernel on it, so
-//                 edits reach the device in the order the host made them (paper Section 3.2: revocation is ordered).
+//   edit chain  - every directory edit is a dir_write kernel that waits for the edit before it, on whatever stream that
+//                 ran, so edits reach the device in the order the host made them (paper Section 3.2: revocation is
+//                 ordered).  Placements and write-backs edit on the caller's stream, right behind their copy;
+//                 register, restore and revoke, which have no caller stream, edit on the library's control stream.
 #include "../../include/harvest.h"
 #include "kernels.h"
 #include <hip/hip_ext.h>
@@ -172,7 +174,7 @@ struct ProfPair { hipEvent_t a, b; int which; };
 struct StreamState {
     hipStream_t s = nullptr;
     hipStream_t side = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, last = nullptr, ctl_done = nullptr, pre_ctl = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, last = nullptr;
     bool last_valid = false;
     // fetch scratch
     uint32_t req_cap = 0;
@@ -207,8 +209,12 @@ struct harvest_ctx {
     uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
-    hipEvent_t ctl_evt = nullptr;            // recorded after every directory edit on the control stream
-    uint64_t ctl_seq = 0;                    // number of directory edits enqueued so far
+    // Directory edits form one chain on the device, in the order the host made them: every edit is a dir_write kernel
+    // on some stream (the caller's for place / evict, the control stream for register / restore / revoke) that first
+    // waits for edit_evt - the previous edit - unless that ran on the same stream, and then records edit_evt itself.
+    hipEvent_t edit_evt = nullptr;
+    hipStream_t edit_stream = nullptr;       // where the latest edit was enqueued
+    uint64_t edit_seq = 0;                   // number of directory edits enqueued so far
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
@@ -253,7 +259,7 @@ bool is_capturing(hipStream_t s)
 void free_stream_state(StreamState *ss)
 {
     if (ss->side) (void)hipStreamDestroy(ss->side);
-    for (hipEvent_t e : { ss->fork, ss->join, ss->last, ss->ctl_done, ss->pre_ctl }) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : { ss->fork, ss->join, ss->last }) if (e) (void)hipEventDestroy(e);
     (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
     (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
     (void)hipFree(ss->grp_totals); (void)hipFree(ss->row_prefix); (void)hipFree(ss->mark);
@@ -264,7 +270,7 @@ void free_stream_state(StreamState *ss)
 int init_stream_state(StreamState *ss)
 {
     HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
-    for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last, &ss->ctl_done, &ss->pre_ctl })
+    for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last })
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
     HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
@@ -409,9 +415,10 @@ ClassDev class_dev(const ClassState &c)
     return d;
 }
 
-// Publishes the mirror entries of `ids` to the device directory on the ctl stream.  If `after` is given, the write
-// waits for that event first (the copy that makes the new entry true).
-int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipEvent_t after)
+// Publishes the mirror entries of `ids` to the device directory with a dir_write kernel on stream `on`, ordered after
+// everything enqueued on `on` so far (for a placement: the copy that makes the new entry true) and after every earlier
+// directory edit, wherever that ran.
+int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipStream_t on)
 {
     if (ctx->no_device || ids.empty()) return HARVEST_OK;
     size_t n = ids.size();
@@ -422,26 +429,28 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
     uint64_t *ent = (uint64_t *)st->h;
     uint32_t *idv = (uint32_t *)(ent + n);
     for (size_t i = 0; i < n; ++i) { ent[i] = c.packed(ids[i]); idv[i] = ids[i]; }
-    if (after) HIP_TRY(hipStreamWaitEvent(ctx->ctl, after, 0));
+    if (ctx->edit_seq && ctx->edit_stream != on) HIP_TRY(hipStreamWaitEvent(on, ctx->edit_evt, 0));
     void *d_st = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&d_st, st->h, 0));
     uint64_t *d_ent = (uint64_t *)d_st;
     uint32_t *d_ids = (uint32_t *)(d_ent + n);
-    hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, ctx->ctl, c.d_dir, d_ids, d_ent,
+    hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, on, c.d_dir, d_ids, d_ent,
                        (uint32_t)n);
     HIP_TRY(hipGetLastError());
-    ctx->ctl_seq++;
-    HIP_TRY(hipEventRecord(ctx->ctl_evt, ctx->ctl));
-    return release_after(st, ctx->ctl);
+    ctx->edit_seq++;
+    ctx->edit_stream = on;
+    HIP_TRY(hipEventRecord(ctx->edit_evt, on));
+    return release_after(st, on);
 }
 
 // Orders the caller's stream after every directory edit made so far, so that a fetch enqueued after register / place /
-// evict(DEMOTE) returned reads entries at least that new - without the host ever waiting for the control stream.
+// evict(DEMOTE) returned reads entries at least that new - without the host ever waiting.  Nothing to do when the
+// latest edit ran on this very stream: the chain put every earlier one before it.
 int order_after_directory_edits(harvest_ctx *ctx, StreamState *ss)
 {
-    if (ss->seen_seq == ctx->ctl_seq || is_capturing(ss->s)) return HARVEST_OK;
-    HIP_TRY(hipStreamWaitEvent(ss->s, ctx->ctl_evt, 0));
-    ss->seen_seq = ctx->ctl_seq;
+    if (ss->seen_seq == ctx->edit_seq || is_capturing(ss->s)) return HARVEST_OK;
+    if (ctx->edit_stream != ss->s) HIP_TRY(hipStreamWaitEvent(ss->s, ctx->edit_evt, 0));
+    ss->seen_seq = ctx->edit_seq;
     return HARVEST_OK;
 }
 
@@ -597,7 +606,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
                                                    // GB/s against 55.2 with 2048 workgroups)
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&ctx->ctl_evt, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->edit_evt, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
@@ -745,7 +754,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
-        if (ctx->ctl_evt) (void)hipEventDestroy(ctx->ctl_evt);
+        if (ctx->edit_evt) (void)hipEventDestroy(ctx->edit_evt);
         (void)hipStreamDestroy(ctx->ctl);
     }
     delete ctx;
@@ -786,7 +795,7 @@ int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_
         c.slot.push_back(s);
         if (out_ids) out_ids[i] = id;
     }
-    if ((rc = publish(ctx, c, ids, nullptr))) return rc;
+    if ((rc = publish(ctx, c, ids, ctx->ctl))) return rc;
     // Later fetches are ordered after this edit on their own streams; only replays of recorded graphs, which the library
     // does not see, need the entry to be there before this call returns.
     if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
@@ -814,7 +823,7 @@ int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t 
         c.tier[id] = T_LOCAL;
         c.gen[id] += 1;
     }
-    if ((rc = publish(ctx, c, changed, nullptr))) return rc;
+    if ((rc = publish(ctx, c, changed, ctx->ctl))) return rc;
     if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
     return HARVEST_OK;
 }
@@ -893,11 +902,9 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
     hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
                        c.cfg.chunk_bytes, tpc);
     HIP_TRY(hipGetLastError());
-    // the new entries become visible only after the copy; later work on `stream` waits for the publication
-    HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
-    if ((rc = publish(ctx, c, moved, ss->pre_ctl))) return rc;
-    HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
-    HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
+    // the new entries are written on the same stream, behind the copy: visible only once the bytes are in the slot,
+    // and before anything enqueued on `stream` later
+    if ((rc = publish(ctx, c, moved, ss->s))) return rc;
     return mark_last(ctx, ss);
 }
 
@@ -945,7 +952,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         }
         if (hit.empty()) return HARVEST_OK;
         if (!ctx->no_device) {
-            if ((rc = publish(ctx, c, hit, nullptr))) return rc;
+            if ((rc = publish(ctx, c, hit, ctx->ctl))) return rc;
             HIP_TRY(hipStreamSynchronize(ctx->ctl));
             // 2. drain: everything enqueued so far that could still read the slots
             if (ctx->captured_work) HIP_TRY(hipDeviceSynchronize());
@@ -1388,10 +1395,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         HIP_TRY(hipGetLastError());
     }
     if (!demoted.empty()) {
-        HIP_TRY(hipEventRecord(ss->pre_ctl, ss->s));
-        if ((rc = publish(ctx, c, demoted, ss->pre_ctl))) return rc;
-        HIP_TRY(hipEventRecord(ss->ctl_done, ctx->ctl));
-        HIP_TRY(hipStreamWaitEvent(ss->s, ss->ctl_done, 0));
+        if ((rc = publish(ctx, c, demoted, ss->s))) return rc;
     }
     return mark_last(ctx, ss);
 }
