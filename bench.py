@@ -191,14 +191,24 @@ def bench_tiny(args):
     import torch
     import workloads as W
     from workloads import scenarios as S
-    from oracle.engine import OracleEngine
     from paper_2602_00328_amd.engine import HipEngine
     wl = W.kv_tiny(args.seed)
     chunk = wl.shape.chunk_bytes
-    eo = OracleEngine(kv=S.kv_spec(wl))
-    ro = S.KVRun(eo, wl)
-    want = ro.fetch(0)
-    res, exact = {}, True
+    want, cpu_baseline = None, None
+    if not args.no_cpu_baseline:                         # the CPU-baseline leg: the oracle's result and its speed
+        from oracle.engine import OracleEngine
+        eo = OracleEngine(kv=S.kv_spec(wl))
+        ro = S.KVRun(eo, wl)
+        want = ro.fetch(0)
+        a, n_rep = time.perf_counter(), 0
+        while time.perf_counter() - a < 2.0:
+            ro.fetch(0)
+            n_rep += 1
+        sec = (time.perf_counter() - a) / n_rep
+        cpu_baseline = {"value": round(2 * 256 * 2 * chunk / sec / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                        "sample": f"the same fetch (256 blocks, 16 MiB), repeated for 2 s on one thread ({n_rep} times)"}
+        eo.close()
+    res, exact = {}, (True if want is not None else None)
     for name, general in (("one_kernel", False), ("general_path", True)):
         eng = HipEngine(kv=S.kv_spec(wl), general_fetch=general)
         run = S.KVRun(eng, wl)
@@ -235,13 +245,14 @@ def bench_tiny(args):
         torch.cuda.synchronize()
         trip = (time.perf_counter() - a) / args.steps
         counts, _, _ = eng.h.fetch_info()
-        exact &= bool(np.array_equal(dst[0].cpu().numpy(), want[0]) and np.array_equal(dst[1].cpu().numpy(), want[1])
-                      and counts == want[3])
+        if want is not None:
+            exact &= bool(np.array_equal(dst[0].cpu().numpy(), want[0]) and np.array_equal(dst[1].cpu().numpy(), want[1])
+                          and counts == want[3])
         res[name] = {"latency_us": round(float(np.median(lat)) * 1e6, 1), "back_to_back_us": round(b2b * 1e6, 1),
                      "fetch_plus_write_back_us": round(trip * 1e6, 1)}
         log(f"[bench] kv_tiny {name}: {res[name]}")
+        served = counts
         eng.close()
-    eo.close()
     payload = ids.size * 2 * chunk
     best = res["one_kernel"]["back_to_back_us"] * 1e-6
     print(json.dumps({
@@ -252,8 +263,8 @@ def bench_tiny(args):
         "config": {"workload": "configs[0]: tiny KV fetch, 16 sequences x 16 blocks of 2 x 32 KiB, 60% in the cache tier / 40% "
                                "on the host, one layer; a latency case - too small to say anything about bandwidth",
                    "seed": args.seed},
-        "objects_per_s": round(ids.size / best), "bit_exact": exact, "served": want[3], "latency": res,
-        "roofline": None, "cpu_baseline": None}), flush=True)
+        "objects_per_s": round(ids.size / best), "bit_exact": exact, "served": served, "latency": res,
+        "roofline": None, "cpu_baseline": cpu_baseline}), flush=True)
 
 
 def bench_experts(args):
