@@ -118,7 +118,7 @@ def test_random_operations_in_lock_step(seed, general, shared):
                 pick = lost if lost and g.random() < 0.8 else [int(ids[0])]
                 both(lambda: eo.restore(KV, pick), lambda: eh.restore(KV, pick))
                 for i in pick:                                                           # rebuilt bytes for what came back
-                    if eo.lookup(KV, i)[0] == LOCAL and i in lost:
+                    if i in lost and eo.lookup(KV, i)[0] == LOCAL:
                         s0, s1 = src_planes()
                         both(lambda: eo.evict(KV, -1, [i], s0, s1, [0], stride), lambda: eh.evict(KV, -1, [i], s0, s1, [0], stride))
             else:                                                                        # a fetch, in one of its forms
