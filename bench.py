@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--place-from-host", action="store_true",
                     help="experts_qwen only: the LRU's placements read the host copies over PCIe (harvest_place) instead of "
                          "the staging buffer the fetch has just filled (harvest_place_from)")
+    ap.add_argument("--fetch-again", action="store_true",
+                    help="variant: after the first fetch every fetch is harvest_fetch_kv_again (same block table, another "
+                         "layer): the request lists are made again only when the directory has been edited")
     ap.add_argument("--prefetch", action="store_true",
                     help="experts_phi only: also time the double-buffered prefetch ring against fetch-then-use")
     ap.add_argument("--graph-steps", type=int, default=64,
@@ -77,7 +80,7 @@ class DeviceDecode:
     """Keeps the decode state of workloads.scenarios.KVRun on the device so that a timed step moves no table or
     payload over PCIe except what the method itself moves."""
 
-    def __init__(self, run, eng, wl, n_steps, head_major=False, fetch_layers=1):
+    def __init__(self, run, eng, wl, n_steps, head_major=False, fetch_layers=1, again=False):
         import numpy as np
         import torch
         import workloads as W
@@ -89,6 +92,7 @@ class DeviceDecode:
         self.d_nb = torch.from_numpy(nb).to(self.dev)
         self.d_sdb = torch.from_numpy(run.seq_dst_block.view(np.int64)).to(self.dev)
         self.fetch_layers = fetch_layers
+        self.again, self.fetched_once = again, False
         self.layer_bytes = run.cap * sh.chunk_bytes
         self.dst_all = [torch.zeros(fetch_layers * self.layer_bytes, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         self.dst = [t[:self.layer_bytes] for t in self.dst_all]            # the first fetched layer
@@ -115,6 +119,7 @@ class DeviceDecode:
         live in device memory and keep changing underneath."""
         import torch
         s = torch.cuda.Stream(self.dev)
+        again, self.again = self.again, False          # a recorded fetch must resolve the table at every replay
         with torch.cuda.stream(s):
             self.fetch(0)                              # outside capture: this stream's scratch is allocated here
         s.synchronize()
@@ -124,7 +129,7 @@ class DeviceDecode:
             with torch.cuda.graph(g, stream=s):
                 self.fetch(layer)
             graphs.append(g)
-        self.graphs = graphs
+        self.graphs, self.again = graphs, again
 
     def first_layer(self, t):
         return (t * self.fetch_layers) % self.wl.shape.n_layers
@@ -137,6 +142,11 @@ class DeviceDecode:
         if self.graphs:
             self.graphs[layer].replay()
             return
+        if self.again and self.fetched_once:
+            # the same table as the fetch before (a roll-over edits the directory, which makes the library resolve again)
+            self.eng.h.fetch_kv_again(layer, self.dst[0], self.dst[1])
+            return
+        self.fetched_once = True
         if self.head_major:
             sh = self.wl.shape
             self.eng.h.fetch_kv_head_major(layer, self.d_table, self.d_nb, self.dst[0], self.dst[1], self.d_sdb,
@@ -492,7 +502,7 @@ def main():
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
-    dd = DeviceDecode(run, eng, wl, n_total, head_major=args.head_major, fetch_layers=args.fetch_layers)
+    dd = DeviceDecode(run, eng, wl, n_total, head_major=args.head_major, fetch_layers=args.fetch_layers, again=args.fetch_again)
 
     # ---- calibration kernel of known size (for hardware byte counters) + achievable-copy ceiling ----
     cal_bytes = 2 << 30
@@ -721,6 +731,7 @@ def main():
                                   f"{chunk // 1024} KiB blocks"),
                    "working_layout": "head-major" if args.head_major else "token-major",
                    "layers_per_fetch": args.fetch_layers, "placement": args.placement,
+                   **({"fetch_again": True} if args.fetch_again else {}),
                    "cache_tier": "shared pool of best-fit segments" if args.shared_cache else "equal-size slots",
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},

@@ -263,6 +263,17 @@ int harvest_fetch_kv_layers(harvest_ctx *ctx, uint32_t layer_first, uint32_t n_l
                             void *d_dst_v, uint64_t dst_layer_stride_bytes, const uint64_t *d_seq_dst_block,
                             uint64_t dst_capacity_blocks, void *stream);
 
+/* Repeats the latest single-layer KV fetch enqueued on `stream` (harvest_fetch_kv or harvest_fetch_kv_head_major) for
+ * another layer and another destination: same block table, lengths and destination map - the way a decode step walks its
+ * layers (Section 5.2: the table says where every block of the step is; it does not change from layer to layer).  The
+ * caller vouches that the table arrays of that call have not changed and are still valid device memory.  When no directory
+ * edit has happened since that call, its request lists are used again (an object occupies the same slot in every layer),
+ * which saves resolving and compacting the table; otherwise, and for the small tables that are fetched without lists, the
+ * table is resolved again - the result is the same either way.  Counters and miss list are those of a fetch of this
+ * layer; the running totals count the requests again.  EINVAL: no such earlier fetch on this stream (a multi-layer call
+ * does not count), layer out of range, missing / misaligned destination. */
+int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void *d_dst_v, void *stream);
+
 /* The same fetch into a head-major working layout (the paper leaves layouts open; attention kernels that walk one head at
  * a time want this one).  A pool block is [block_tokens][n_heads][head_bytes] with head_bytes = chunk_bytes /
  * (block_tokens * n_heads), a multiple of 16.  Sequence s owns d_seq_cap_blocks[s] (< 65536) destination blocks starting at

@@ -103,8 +103,16 @@ class OracleEngine:
     def has_layer(self, layer):
         return layer in self.kv_layers
 
+    def fetch_kv_again(self, layer, dst_fill=0):
+        """The latest single-layer fetch once more, for another layer: plainly a fetch with the same arguments."""
+        form, args = self._last_kv
+        if form == "token-major":
+            return self.fetch_kv(layer, *args)
+        return self.fetch_kv_head_major(layer, *args, dst_fill=dst_fill)
+
     def fetch_kv(self, layer, table, n_blocks, seq_dst_block, cap):
         """-> (k bytes, v bytes, sorted miss list, counts) as numpy / dict."""
+        self._last_kv = ("token-major", (table, n_blocks, seq_dst_block, cap))
         c = self.c[KV]
         k, v, miss, counts = c.fetch_kv(self.kv_layers.index(layer), table, n_blocks, seq_dst_block, cap,
                                         threads=self.threads)
@@ -112,6 +120,7 @@ class OracleEngine:
 
     def fetch_kv_head_major(self, layer, table, n_blocks, seq_dst_block, seq_cap_blocks, cap, n_heads, block_tokens,
                             dst_fill=0):
+        self._last_kv = ("head-major", (table, n_blocks, seq_dst_block, seq_cap_blocks, cap, n_heads, block_tokens))
         c = self.c[KV]
         n = cap * c.chunk_bytes
         k, v, miss, counts = c.fetch_kv_head_major(self.kv_layers.index(layer), table, n_blocks, seq_dst_block,

@@ -74,6 +74,7 @@ SYMBOLS = {
     "harvest_free": (ctypes.c_int, [vp, ctypes.c_int, u32]),
     "harvest_register_cb": (ctypes.c_int, [vp, ctypes.c_int, u32, REVOKE_CB, vp]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
+    "harvest_fetch_kv_again": (ctypes.c_int, [vp, u32, vp, vp, vp]),
     "harvest_fetch_kv_layers": (ctypes.c_int, [vp, u32, u32, vp, vp, u32, u32, vp, vp, u64, vp, u64, vp]),
     "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
     "harvest_fetch_experts": (ctypes.c_int, [vp, u32, vp, u32, u32, vp, u32, vp, vp]),
@@ -304,6 +305,10 @@ class Harvest:
         _chk(lib.harvest_fetch_kv(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
                                   _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block), dst_capacity_blocks,
                                   _stream_ptr(stream)), "harvest_fetch_kv")
+
+    def fetch_kv_again(self, layer, d_dst_k, d_dst_v, stream=None):
+        _chk(lib.harvest_fetch_kv_again(self.h, layer, _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _stream_ptr(stream)),
+             "harvest_fetch_kv_again")
 
     def fetch_kv_layers(self, layer_first, n_layers, d_table, d_n_blocks, d_dst_k, d_dst_v, dst_layer_stride_bytes,
                         d_seq_dst_block, cap_blocks, stream=None):

@@ -187,6 +187,15 @@ struct StreamState {
     uint32_t *mark = nullptr;               // [MAX_EXPERTS / 32 + 1] routed-set bitmap and invalid-id count of large batches;
                                             // zero between fetches
     bool fetched = false;                   // a fetch has been enqueued on this stream
+    // the latest single-layer KV fetch, for harvest_fetch_kv_again
+    struct {
+        bool valid = false, lists = false;  // lists: the general path ran, so the compacted lists describe it
+        uint32_t layer = 0, n_seq = 0, max_blocks = 0, n_heads = 0, block_tokens = 0;
+        const int32_t *table = nullptr, *n_blocks = nullptr;
+        const uint64_t *seq_dst_block = nullptr;
+        const uint32_t *seq_cap_blocks = nullptr;
+        uint64_t dst_cap = 0, edit_seq = 0;
+    } last_kv;
     uint64_t seen_seq = 0;                  // directory edits this stream has been ordered after
     // control scratch (host-built lists)
     void *ctl_buf = nullptr;
@@ -483,8 +492,11 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 // the link never waits for a join between layers.
 int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
                    uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr, uint32_t n_rep = 1,
-                   uint64_t dst_step = 0)
+                   uint64_t dst_step = 0, int64_t layer_delta = 0, bool repeat = false)
 {
+    // layer_delta: the lists were made for another layer; an object has the same slot in every layer, so adding that many
+    // layer strides to every pool base retargets them.  repeat: these requests have been counted for the lists' first
+    // use only - add them to the running totals again.
     const ClassDev cd = class_dev(c);
     GatherArgs ga{};
     ga.chunk_bytes = c.cfg.chunk_bytes;
@@ -517,7 +529,9 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         host_stays = host_tier && seen_host * 48 > seen;
         double bytes = (double)planes * c.cfg.chunk_bytes * n_rep;
         double us_hbm = 2.0 * seen * bytes / 6.0e6, us_host = seen_host * bytes / 57.0e3;     // at 6 TB/s and 57 GB/s
-        serial = serial || std::max(us_hbm, us_host) < 35.0;
+        // ... or when the shorter one is next to nothing (a fetch served by one tier alone): waiting for the other
+        // stream costs the caller's stream more than running a few microseconds of kernel itself
+        serial = serial || std::max(us_hbm, us_host) < 35.0 || std::min(us_hbm, us_host) < 8.0;
     }
     if (!serial) {
         HIP_TRY(hipEventRecord(ss->fork, ss->s));
@@ -527,9 +541,10 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     uint32_t grid = ctx->gather_grid ? grid_for(want, ctx->gather_grid) : grid_for(want, MAX_GRID);
     for (uint32_t r = 0; r < n_rep; ++r) {
         for (uint32_t p = 0; p < 2; ++p) {
-            ga.src_base[T_HOST][p] = c.host_dev[p] + r * cd.layer_stride[T_HOST];
-            ga.src_base[T_CACHE][p] = c.cache_base(p) + r * cd.layer_stride[T_CACHE];
-            ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p] + r * cd.layer_stride[T_LOCAL];
+            const uint64_t k = (uint64_t)((int64_t)r + layer_delta);          // may be "negative": the sums wrap back
+            ga.src_base[T_HOST][p] = c.host_dev[p] + k * cd.layer_stride[T_HOST];
+            ga.src_base[T_CACHE][p] = c.cache_base(p) + k * cd.layer_stride[T_CACHE];
+            ga.src_base[T_LOCAL][p] = (uint64_t)c.cfg.d_local_pool[p] + k * cd.layer_stride[T_LOCAL];
         }
         ga.dst_base[0] = dst_base0 + r * dst_step;
         ga.dst_base[1] = dst_base1 + r * dst_step;
@@ -579,6 +594,11 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         }
     }
     ss->feedback_valid[cls] = true;
+    if (repeat) {                                   // off the longer gather's stream where there are two
+        hipLaunchKernelGGL(repeat_totals, dim3(1), dim3(64), 0, serial ? ss->s : ss->side, (const uint32_t *)cnt,
+                           ctx->d_totals + cls * C_N);
+        HIP_TRY(hipGetLastError());
+    }
     if (!serial) {
         HIP_TRY(hipEventRecord(ss->join, ss->side));
         HIP_TRY(hipStreamWaitEvent(ss->s, ss->join, 0));
@@ -1016,6 +1036,12 @@ int harvest_register_cb(harvest_ctx *ctx, int cls, harvest_obj id, harvest_revok
     return HARVEST_OK;
 }
 
+static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                           uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                           const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
+                           uint32_t n_heads, uint32_t block_tokens, void *stream, uint32_t n_layers,
+                           uint64_t dst_layer_stride);
+
 static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
                          uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                          const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
@@ -1026,6 +1052,18 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
     if (ctx->no_device) return HARVEST_ENODEV;
     std::lock_guard<std::mutex> lk(ctx->mu);
+    return fetch_kv_locked(ctx, layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v, d_seq_dst_block,
+                           d_seq_cap_blocks, dst_capacity_blocks, n_heads, block_tokens, stream, n_layers, dst_layer_stride);
+}
+
+// The body of every KV fetch; the context's lock is held.
+static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                           uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                           const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
+                           uint32_t n_heads, uint32_t block_tokens, void *stream, uint32_t n_layers,
+                           uint64_t dst_layer_stride)
+{
+    int rc;
     ClassState &c = ctx->cls[HARVEST_KV];
     if (n_layers == 0 || (uint64_t)layer + n_layers > c.cfg.n_layers) return HARVEST_EINVAL;
     if (n_layers > 1 && (dst_layer_stride % 16 || dst_layer_stride < dst_capacity_blocks * c.cfg.chunk_bytes))
@@ -1046,7 +1084,16 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
+    ss->last_kv.valid = false;
     if (total == 0) { ss->fetched = false; return HARVEST_OK; }
+    auto remember = [&](bool lists) {
+        if (n_layers != 1) return;
+        auto &k = ss->last_kv;
+        k.valid = true; k.lists = lists; k.layer = layer; k.n_seq = n_seq; k.max_blocks = max_blocks;
+        k.n_heads = n_heads; k.block_tokens = block_tokens; k.table = d_block_table; k.n_blocks = d_n_blocks;
+        k.seq_dst_block = d_seq_dst_block; k.seq_cap_blocks = d_seq_cap_blocks; k.dst_cap = dst_capacity_blocks;
+        k.edit_seq = ctx->edit_seq;
+    };
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
@@ -1072,6 +1119,7 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
         HIP_TRY(hipGetLastError());
         ss->fetched = true;
         ss->feedback_valid[HARVEST_KV] = true;
+        remember(false);
         return mark_last(ctx, ss);
     }
     uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
@@ -1094,8 +1142,40 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
                        grouped ? (const uint32_t *)ss->row_prefix : (const uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
     ss->fetched = true;
+    remember(true);
     return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
                           head_major ? &hm : nullptr, n_layers, dst_layer_stride);
+}
+
+int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void *d_dst_v, void *stream)
+{
+    int rc = check_class(ctx, HARVEST_KV);
+    if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ClassState &c = ctx->cls[HARVEST_KV];
+    if (layer >= c.cfg.n_layers) return HARVEST_EINVAL;
+    auto it = ctx->streams.find((hipStream_t)stream);
+    if (it == ctx->streams.end() || !it->second->last_kv.valid) return HARVEST_EINVAL;
+    StreamState *ss = it->second.get();
+    const auto k = ss->last_kv;
+    // The lists of that fetch still describe this one when nothing has edited the directory since (and that fetch made
+    // lists at all: small tables are fetched without); otherwise the table is resolved again.
+    if (!k.lists || k.edit_seq != ctx->edit_seq)
+        return fetch_kv_locked(ctx, layer, k.table, k.n_blocks, k.n_seq, k.max_blocks, d_dst_k, d_dst_v, k.seq_dst_block,
+                               k.seq_cap_blocks, k.dst_cap, k.n_heads, k.block_tokens, stream, 1, 0);
+    if (!d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v) || (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15)) return HARVEST_EINVAL;
+    if ((rc = device_guard(ctx))) return rc;
+    HmArgs hm{};
+    const bool head_major = k.n_heads != 0;
+    if (head_major) {
+        hm.n_heads = k.n_heads;
+        hm.upr = (uint32_t)(c.cfg.chunk_bytes / ((uint64_t)k.n_heads * k.block_tokens) / 16);
+        hm.ups = hm.upr * k.block_tokens;
+    }
+    ss->fetched = true;
+    return launch_gathers(ctx, ss, c, HARVEST_KV, ss->cnt, (uint64_t)k.n_seq * k.max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
+                          head_major ? &hm : nullptr, 1, 0, (int64_t)layer - (int64_t)k.layer, true);
 }
 
 int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,

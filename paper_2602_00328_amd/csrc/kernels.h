@@ -845,6 +845,13 @@ __global__ __launch_bounds__(WG) void dir_write(uint64_t *dir, const uint32_t *_
     if (i < n) dir[ids[i]] = entries[i];
 }
 
+// A fetch repeated from the lists of the one before it serves the same requests again: they are added to the running totals.
+__global__ void repeat_totals(const uint32_t *__restrict__ cnt, unsigned long long *totals)
+{
+    uint32_t i = threadIdx.x;
+    if (i <= C_INVALID && cnt[i]) atomicAdd(&totals[i], (unsigned long long)cnt[i]);
+}
+
 // Plain contiguous copy with the HBM-tier inner loop (reference ceiling / counter calibration).
 __global__ __launch_bounds__(WG) void plain_copy(uint64_t dst, uint64_t src, uint64_t bytes)
 {

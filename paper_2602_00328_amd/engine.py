@@ -146,7 +146,16 @@ class HipEngine:
                 d_cap = torch.from_numpy(np.ascontiguousarray(caps, dtype=np.uint32).view(np.int32)).to(self.dev)
                 self.h.fetch_kv_head_major(layer, d_table, d_nb, dst[0], dst[1] if len(dst) > 1 else None, d_sdb, d_cap,
                                            cap, n_heads, block_tokens)
+        self._last_kv = (dst[0].numel(), len(dst), table.size, (d_table, d_nb, d_sdb, d_cap))   # the arrays stay alive for "again"
         return ("kv", dst, table.size, (d_table, d_nb, d_sdb, d_cap))
+
+    def fetch_kv_again(self, layer, dst_fill=0):
+        """harvest_fetch_kv_again: the latest single-layer fetch of the KV stream for another layer, into fresh buffers."""
+        nbytes, n_planes, n_req, keep = self._last_kv
+        with self._on(KV):
+            dst = [torch.full((nbytes,), dst_fill, dtype=torch.uint8, device=self.dev) for _ in range(n_planes)]
+            self.h.fetch_kv_again(layer, dst[0], dst[1] if n_planes > 1 else None)
+        return self.fetch_end(("kv", dst, n_req, keep))
 
     def fetch_kv_head_major(self, layer, table, n_blocks, seq_dst_block, seq_cap_blocks, cap, n_heads, block_tokens,
                             dst_fill=0):

@@ -568,6 +568,53 @@ def test_one_plane_kv_class():
         eh.close(); eo.close()
 
 
+# ---- the same fetch again for another layer ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
+@pytest.mark.parametrize("head_major", [False, True])
+def test_fetch_again_for_another_layer(general, head_major):
+    """harvest_fetch_kv_again walks the layers of a step on the lists of the first fetch; every directory edit in between
+    (placement, revocation, demotion, registration) makes it resolve again.  Either way it must deliver what a fetch of
+    that layer delivers."""
+    say(f"fetch again, general path {general}, head-major {head_major}")
+    wl = W.kv_decode(seed=41, n_layers=4, n_seq=3, min_len=600, max_len=1500, p_cache=0.6, n_steps=48)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=32, hip_kwargs=dict(general_fetch=general))
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        heads, tokens = wl.shape.n_kv_heads, wl.shape.block_tokens
+        final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
+
+        def first(e, r, layer):
+            table, nb = r.table_arrays()
+            if head_major:
+                return e.fetch_kv_head_major(layer, table, nb, r.seq_dst_block, np.array(final, np.uint32), r.cap, heads,
+                                             tokens, dst_fill=0x5A)
+            return e.fetch_kv(layer, table, nb, r.seq_dst_block, r.cap)
+
+        fill = 0x5A if head_major else 0
+        for t in range(12):
+            P.assert_kv_equal(first(eo, ro, t % 4), first(eh, rh, t % 4), f"step {t}, first layer")
+            for layer in ((t + 1) % 4, (t + 3) % 4, t % 4):
+                if t % 3 == 1 and layer == (t + 3) % 4:                      # an edit between two layers of the step
+                    if t % 2:
+                        ids_o, ids_h = ro.revoke_quarter(t)[0], rh.revoke_quarter(t)[0]
+                        assert np.array_equal(ids_o, ids_h)
+                    else:
+                        assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+                P.assert_kv_equal(eo.fetch_kv_again(layer, fill), eh.fetch_kv_again(layer, fill), f"step {t}, again at layer {layer}")
+            for k in range(4):                                               # appends, roll-overs: registrations and demotions
+                ro.append(4 * t + k); rh.append(4 * t + k)
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        st = eh.h.stats()
+        f = st.fetch[0]                              # repeated fetches are counted in the running totals too
+        assert f.n_requests == f.n_local + f.n_cache + f.n_host + f.n_lost + f.n_invalid
+        assert f.n_requests >= 12 * 4 * sum(len(x) for x in wl.tables)
+        with pytest.raises(Exception):
+            eh.h.fetch_kv_again(99, None, None)
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- several layers in one call --------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
