@@ -171,22 +171,37 @@ struct Staging {
 
 struct ProfPair { hipEvent_t a, b; int which; };
 
+// What a fetch leaves behind for its gathers and for harvest_fetch_info: the two request lists, the miss list and the
+// counters.  Each class has its own set on every stream, so an expert fetch never touches what a KV fetch left (a
+// decode step walks its layers with KV and expert fetches in turn, and harvest_fetch_kv_again reads the KV lists
+// layers later).
+struct Lists {
+    Rec *hbm = nullptr, *host = nullptr;
+    uint32_t *miss = nullptr;
+    uint32_t *cnt = nullptr;                // [C_N] counters of the class's last fetch; every fetch overwrites all of them
+    uint32_t cap = 0;                       // requests the three lists have room for
+};
+
+// Intermediate arrays of the KV resolve (classify_kv -> scan_groups -> compact_kv), one entry or row per table cell.
+struct KvWork {
+    Rec *tmp = nullptr;
+    uint8_t *kind = nullptr;
+    uint32_t *blk_counts = nullptr;
+    uint32_t *grp_totals = nullptr, *row_prefix = nullptr;     // large tables: the middle pass of the compaction
+};
+
 struct StreamState {
     hipStream_t s = nullptr;
     hipStream_t side = nullptr;
     hipEvent_t fork = nullptr, join = nullptr, last = nullptr;
     bool last_valid = false;
     // fetch scratch
-    uint32_t req_cap = 0;
-    Rec *hbm_recs = nullptr, *host_recs = nullptr, *tmp_recs = nullptr;
-    uint8_t *kind = nullptr;
-    uint32_t *blk_counts = nullptr;
-    uint32_t *grp_totals = nullptr, *row_prefix = nullptr;     // large tables: the middle pass of the compaction
-    uint32_t *miss_idx = nullptr;
-    uint32_t *cnt = nullptr;                // [C_N] counters of the last fetch; every fetch overwrites all of them
+    Lists lists[HARVEST_N_CLASSES];
+    KvWork work;
+    uint32_t *cnt_block = nullptr;          // the counters of both classes: one allocation
     uint32_t *mark = nullptr;               // [MAX_EXPERTS / 32 + 1] routed-set bitmap and invalid-id count of large batches;
                                             // zero between fetches
-    bool fetched = false;                   // a fetch has been enqueued on this stream
+    int last_cls = -1;                      // class of the latest fetch enqueued on this stream, -1: none yet (or an empty one)
     // the latest single-layer KV fetch, for harvest_fetch_kv_again
     struct {
         bool valid = false, lists = false;  // lists: the general path ran, so the compacted lists describe it
@@ -269,9 +284,10 @@ void free_stream_state(StreamState *ss)
 {
     if (ss->side) (void)hipStreamDestroy(ss->side);
     for (hipEvent_t e : { ss->fork, ss->join, ss->last }) if (e) (void)hipEventDestroy(e);
-    (void)hipFree(ss->hbm_recs); (void)hipFree(ss->host_recs); (void)hipFree(ss->tmp_recs);
-    (void)hipFree(ss->kind); (void)hipFree(ss->blk_counts); (void)hipFree(ss->miss_idx); (void)hipFree(ss->cnt);
-    (void)hipFree(ss->grp_totals); (void)hipFree(ss->row_prefix); (void)hipFree(ss->mark);
+    for (Lists &l : ss->lists) { (void)hipFree(l.hbm); (void)hipFree(l.host); (void)hipFree(l.miss); }
+    (void)hipFree(ss->work.tmp); (void)hipFree(ss->work.kind); (void)hipFree(ss->work.blk_counts);
+    (void)hipFree(ss->work.grp_totals); (void)hipFree(ss->work.row_prefix);
+    (void)hipFree(ss->cnt_block); (void)hipFree(ss->mark);
     (void)hipFree(ss->ctl_buf);
     if (ss->h_feedback) (void)hipHostFree(ss->h_feedback);
 }
@@ -281,8 +297,9 @@ int init_stream_state(StreamState *ss)
     HIP_TRY(hipStreamCreateWithFlags(&ss->side, hipStreamNonBlocking));
     for (hipEvent_t *e : { &ss->fork, &ss->join, &ss->last })
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
-    HIP_TRY(hipMalloc(&ss->cnt, C_N * sizeof(uint32_t)));
-    HIP_TRY(hipMemset(ss->cnt, 0, C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ss->cnt_block, HARVEST_N_CLASSES * C_N * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(ss->cnt_block, 0, HARVEST_N_CLASSES * C_N * sizeof(uint32_t)));
+    for (int k = 0; k < HARVEST_N_CLASSES; ++k) ss->lists[k].cnt = ss->cnt_block + k * C_N;
     HIP_TRY(hipMalloc(&ss->mark, (MAX_EXPERTS / 32 + 1) * sizeof(uint32_t)));
     HIP_TRY(hipMemset(ss->mark, 0, (MAX_EXPERTS / 32 + 1) * sizeof(uint32_t)));
     HIP_TRY(hipHostMalloc((void **)&ss->h_feedback, 64, hipHostMallocDefault));
@@ -311,32 +328,48 @@ int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
     return HARVEST_OK;
 }
 
-int ensure_req_cap(StreamState *ss, uint32_t n_req)
+// Room for n_req requests in the lists of class cls (and, for KV, in the arrays of the resolve).  Growing waits for
+// the stream's earlier work, which may still read the old arrays; the new ones are all there before the old ones go,
+// so a failed allocation leaves the stream as it was.
+int ensure_req_cap(StreamState *ss, int cls, uint32_t n_req)
 {
-    if (n_req <= ss->req_cap) return HARVEST_OK;
+    Lists &l = ss->lists[cls];
+    if (n_req <= l.cap) return HARVEST_OK;
     if (is_capturing(ss->s)) {
         fprintf(stderr, "libharvest: this fetch needs larger scratch lists - run it once outside graph capture\n");
         return HARVEST_EINVAL;
     }
-    // growing: earlier work on this stream may still read the old lists
     HIP_TRY(hipStreamSynchronize(ss->s));
     HIP_TRY(hipStreamSynchronize(ss->side));
-    for (void *p : { (void *)ss->hbm_recs, (void *)ss->host_recs, (void *)ss->tmp_recs, (void *)ss->kind,
-                     (void *)ss->blk_counts, (void *)ss->grp_totals, (void *)ss->row_prefix, (void *)ss->miss_idx })
-        if (p) HIP_TRY(hipFree(p));
-    ss->hbm_recs = ss->host_recs = ss->tmp_recs = nullptr;
-    ss->kind = nullptr; ss->blk_counts = ss->grp_totals = ss->row_prefix = nullptr; ss->miss_idx = nullptr; ss->req_cap = 0;
     uint32_t cap = std::max<uint32_t>(1024, n_req + n_req / 4);
-    HIP_TRY(hipMalloc(&ss->hbm_recs, (size_t)cap * sizeof(Rec)));
-    HIP_TRY(hipMalloc(&ss->host_recs, (size_t)cap * sizeof(Rec)));
-    HIP_TRY(hipMalloc(&ss->tmp_recs, (size_t)cap * sizeof(Rec)));
-    HIP_TRY(hipMalloc(&ss->kind, (size_t)cap));
     size_t n_rows = (cap + WG - 1) / WG;
-    HIP_TRY(hipMalloc(&ss->blk_counts, n_rows * BC_N * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ss->grp_totals, ((n_rows + WG - 1) / WG) * BC_N * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ss->row_prefix, n_rows * 3 * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ss->miss_idx, (size_t)cap * sizeof(uint32_t)));
-    ss->req_cap = cap;
+    const bool kv = cls == HARVEST_KV;
+    void *fresh[8] = { nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr };
+    const size_t bytes[8] = { (size_t)cap * sizeof(Rec), (size_t)cap * sizeof(Rec), (size_t)cap * sizeof(uint32_t),
+                              kv ? (size_t)cap * sizeof(Rec) : 0, kv ? (size_t)cap : 0,
+                              kv ? n_rows * BC_N * sizeof(uint32_t) : 0,
+                              kv ? ((n_rows + WG - 1) / WG) * BC_N * sizeof(uint32_t) : 0,
+                              kv ? n_rows * 3 * sizeof(uint32_t) : 0 };
+    for (int i = 0; i < 8; ++i) {
+        if (!bytes[i]) continue;
+        hipError_t e = hipMalloc(&fresh[i], bytes[i]);
+        if (e != hipSuccess) {
+            fprintf(stderr, "libharvest: hipMalloc(%zu) failed: %s\n", bytes[i], hipGetErrorString(e));
+            for (int j = 0; j < i; ++j) (void)hipFree(fresh[j]);
+            return HARVEST_EHIP;
+        }
+    }
+    (void)hipFree(l.hbm); (void)hipFree(l.host); (void)hipFree(l.miss);
+    l.hbm = (Rec *)fresh[0]; l.host = (Rec *)fresh[1]; l.miss = (uint32_t *)fresh[2];
+    if (kv) {
+        KvWork &w = ss->work;
+        (void)hipFree(w.tmp); (void)hipFree(w.kind); (void)hipFree(w.blk_counts); (void)hipFree(w.grp_totals);
+        (void)hipFree(w.row_prefix);
+        w.tmp = (Rec *)fresh[3]; w.kind = (uint8_t *)fresh[4]; w.blk_counts = (uint32_t *)fresh[5];
+        w.grp_totals = (uint32_t *)fresh[6]; w.row_prefix = (uint32_t *)fresh[7];
+        ss->last_kv.valid = false;              // the lists that fetch left are gone
+    }
+    l.cap = cap;
     return HARVEST_OK;
 }
 
@@ -490,7 +523,7 @@ hipEvent_t prof_event(harvest_ctx *ctx)
 // in every layer): repetition r reads layer_stride(tier) * r further into every pool and writes dst_step * r further
 // into the destination.  The host-tier gathers of all repetitions queue up behind each other on one stream, so
 // the link never waits for a join between layers.
-int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, uint32_t *cnt, uint64_t max_req,
+int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, const Lists &lists, uint64_t max_req,
                    uint64_t dst_base0, uint64_t dst_base1, const HmArgs *hm = nullptr, uint32_t n_rep = 1,
                    uint64_t dst_step = 0, int64_t layer_delta = 0, bool repeat = false)
 {
@@ -553,8 +586,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
         if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); }
         if (profile && host_tier) { pc = prof_event(ctx); pd = prof_event(ctx); }
         if (host_tier) {             // first, so that the long PCIe transfer starts before the CUs fill up
-            const Rec *recs = (const Rec *)ss->host_recs;
-            const uint32_t *n_req = (const uint32_t *)(cnt + C_HOST_REQ);
+            const Rec *recs = (const Rec *)lists.host;
+            const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HOST_REQ);
             uint32_t *fb = ss->d_feedback + HARVEST_N_CLASSES + cls;
             dim3 g(ctx->host_grid);
             if (hm) {
@@ -572,8 +605,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
             }
             HIP_TRY(hipGetLastError());
         }
-        const Rec *recs = (const Rec *)ss->hbm_recs;
-        const uint32_t *n_req = (const uint32_t *)(cnt + C_HBM_REQ);
+        const Rec *recs = (const Rec *)lists.hbm;
+        const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HBM_REQ);
         if (hm) {
             if (pa)
                 hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req,
@@ -595,7 +628,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, ui
     }
     ss->feedback_valid[cls] = true;
     if (repeat) {                                   // off the longer gather's stream where there are two
-        hipLaunchKernelGGL(repeat_totals, dim3(1), dim3(64), 0, serial ? ss->s : ss->side, (const uint32_t *)cnt,
+        hipLaunchKernelGGL(repeat_totals, dim3(1), dim3(64), 0, serial ? ss->s : ss->side, (const uint32_t *)lists.cnt,
                            ctx->d_totals + cls * C_N);
         HIP_TRY(hipGetLastError());
     }
@@ -1085,7 +1118,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     ss->last_kv.valid = false;
-    if (total == 0) { ss->fetched = false; return HARVEST_OK; }
+    if (total == 0) { ss->last_cls = -1; return HARVEST_OK; }
     auto remember = [&](bool lists) {
         if (n_layers != 1) return;
         auto &k = ss->last_kv;
@@ -1097,9 +1130,11 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
-    if ((rc = ensure_req_cap(ss, (uint32_t)total))) return rc;
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
-    uint32_t *cnt = ss->cnt;
+    if ((rc = ensure_req_cap(ss, HARVEST_KV, (uint32_t)total))) return rc;
+    const Lists &lists = ss->lists[HARVEST_KV];
+    const KvWork &work = ss->work;
+    uint32_t *cnt = lists.cnt;
     const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
     if (!ctx->general_fetch && !head_major && n_layers <= 65535 && total <= ctx->small_cells && total * tpc <= SMALL_FETCH_TILES) {
         // a small table: the whole fetch is one kernel (no compaction, no second stream) - see fetch_kv_small
@@ -1114,36 +1149,37 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
         ga.chunk_bytes = c.cfg.chunk_bytes; ga.tiles_per_chunk = tpc; ga.n_planes = c.cfg.n_planes;
         hipLaunchKernelGGL(fetch_kv_small, dim3((uint32_t)(total * tpc), c.cfg.n_planes, n_layers), dim3(WG), 0, ss->s, cd,
                            layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_seq_dst_block, dst_capacity_blocks, ga,
-                           dst_layer_stride, ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
+                           dst_layer_stride, lists.miss, cnt, ctx->d_totals + HARVEST_KV * C_N,
                            ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV);
         HIP_TRY(hipGetLastError());
-        ss->fetched = true;
+        ss->last_cls = HARVEST_KV;
         ss->feedback_valid[HARVEST_KV] = true;
         remember(false);
         return mark_last(ctx, ss);
     }
     uint32_t n_wg = (uint32_t)((total + WG - 1) / WG);
     hipLaunchKernelGGL(classify_kv, dim3(n_wg), dim3(WG), 0, ss->s, class_dev(c), layer, d_block_table, d_n_blocks, n_seq,
-                       max_blocks, d_seq_dst_block, dst_capacity_blocks, ss->tmp_recs, ss->kind, ss->blk_counts,
+                       max_blocks, d_seq_dst_block, dst_capacity_blocks, work.tmp, work.kind, work.blk_counts,
                        d_seq_cap_blocks, (uint64_t)hm.ups * 16);
     HIP_TRY(hipGetLastError());
     // Beyond this many rows of workgroup totals the compaction's own adding-up of all earlier rows (quadratic) costs more
     // than one more small kernel that groups them first (2 M cells: 70 us against about 10).
     const bool grouped = n_wg > GROUPED_SCAN_ROWS;
     if (grouped) {
-        hipLaunchKernelGGL(scan_groups, dim3((n_wg + WG - 1) / WG), dim3(WG), 0, ss->s, (const uint32_t *)ss->blk_counts, n_wg,
-                           ss->grp_totals, ss->row_prefix);
+        hipLaunchKernelGGL(scan_groups, dim3((n_wg + WG - 1) / WG), dim3(WG), 0, ss->s, (const uint32_t *)work.blk_counts, n_wg,
+                           work.grp_totals, work.row_prefix);
         HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)ss->tmp_recs,
-                       (const uint8_t *)ss->kind, (const uint32_t *)ss->blk_counts, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_KV * C_N,
-                       grouped ? (const uint32_t *)ss->grp_totals : (const uint32_t *)nullptr,
-                       grouped ? (const uint32_t *)ss->row_prefix : (const uint32_t *)nullptr);
+    hipLaunchKernelGGL(compact_kv, dim3(n_wg), dim3(WG), 0, ss->s, (uint32_t)total, (const Rec *)work.tmp,
+                       (const uint8_t *)work.kind, (const uint32_t *)work.blk_counts, lists.hbm, lists.host,
+                       lists.miss, cnt, ctx->d_totals + HARVEST_KV * C_N,
+                       grouped ? (const uint32_t *)work.grp_totals : (const uint32_t *)nullptr,
+                       grouped ? (const uint32_t *)work.row_prefix : (const uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
-    ss->fetched = true;
-    remember(true);
-    return launch_gathers(ctx, ss, c, HARVEST_KV, cnt, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
+    ss->last_cls = HARVEST_KV;
+    // lists recorded into a graph exist only once the graph has been replayed: nothing to use again
+    remember(!is_capturing(ss->s));
+    return launch_gathers(ctx, ss, c, HARVEST_KV, lists, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
                           head_major ? &hm : nullptr, n_layers, dst_layer_stride);
 }
 
@@ -1161,7 +1197,8 @@ int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void
     const auto k = ss->last_kv;
     // The lists of that fetch still describe this one when nothing has edited the directory since (and that fetch made
     // lists at all: small tables are fetched without); otherwise the table is resolved again.
-    if (!k.lists || k.edit_seq != ctx->edit_seq)
+    // A recorded fetch resolves for itself too: by the time its graph is replayed, residency may be another.
+    if (!k.lists || k.edit_seq != ctx->edit_seq || is_capturing((hipStream_t)stream))
         return fetch_kv_locked(ctx, layer, k.table, k.n_blocks, k.n_seq, k.max_blocks, d_dst_k, d_dst_v, k.seq_dst_block,
                                k.seq_cap_blocks, k.dst_cap, k.n_heads, k.block_tokens, stream, 1, 0);
     if (!d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v) || (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15)) return HARVEST_EINVAL;
@@ -1173,8 +1210,8 @@ int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void
         hm.upr = (uint32_t)(c.cfg.chunk_bytes / ((uint64_t)k.n_heads * k.block_tokens) / 16);
         hm.ups = hm.upr * k.block_tokens;
     }
-    ss->fetched = true;
-    return launch_gathers(ctx, ss, c, HARVEST_KV, ss->cnt, (uint64_t)k.n_seq * k.max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
+    ss->last_cls = HARVEST_KV;
+    return launch_gathers(ctx, ss, c, HARVEST_KV, ss->lists[HARVEST_KV], (uint64_t)k.n_seq * k.max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
                           head_major ? &hm : nullptr, 1, 0, (int64_t)layer - (int64_t)k.layer, true);
 }
 
@@ -1222,9 +1259,10 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
-    if ((rc = ensure_req_cap(ss, E))) return rc;
+    if ((rc = ensure_req_cap(ss, HARVEST_EXPERT, E))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
-    uint32_t *cnt = ss->cnt;
+    const Lists &lists = ss->lists[HARVEST_EXPERT];
+    uint32_t *cnt = lists.cnt;
     // a large batch of routing ids is marked by many workgroups first; the single resolving workgroup reads the bitmap
     const bool marked = n_ids > MARKED_BATCH_IDS;
     if (marked) {
@@ -1234,12 +1272,12 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
         HIP_TRY(hipGetLastError());
     }
     hipLaunchKernelGGL(resolve_experts, dim3(1), dim3(WG), 0, ss->s, class_dev(c), layer, E, d_topk_ids, (uint32_t)n_ids,
-                       (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, ss->hbm_recs, ss->host_recs,
-                       ss->miss_idx, cnt, ctx->d_totals + HARVEST_EXPERT * C_N, marked ? ss->mark : (uint32_t *)nullptr,
+                       (uint64_t)d_staging, n_staging_slots, (uint64_t *)d_expert_ptr, lists.hbm, lists.host,
+                       lists.miss, cnt, ctx->d_totals + HARVEST_EXPERT * C_N, marked ? ss->mark : (uint32_t *)nullptr,
                        marked ? ss->mark + MAX_EXPERTS / 32 : (uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
-    ss->fetched = true;
-    return launch_gathers(ctx, ss, c, HARVEST_EXPERT, cnt, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
+    ss->last_cls = HARVEST_EXPERT;
+    return launch_gathers(ctx, ss, c, HARVEST_EXPERT, lists, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
 }
 
 int harvest_prefetcher_create(harvest_ctx *ctx, void *const d_staging[2], uint32_t n_staging_slots,
@@ -1367,14 +1405,15 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
     HIP_TRY(hipStreamSynchronize(ss->s));
     std::lock_guard<std::mutex> lk(ctx->mu);
     uint32_t h[C_N] = { 0 };
-    if (ss->fetched) HIP_TRY(hipMemcpy(h, ss->cnt, sizeof h, hipMemcpyDeviceToHost));
+    const Lists *l = ss->last_cls >= 0 ? &ss->lists[ss->last_cls] : nullptr;
+    if (l) HIP_TRY(hipMemcpy(h, l->cnt, sizeof h, hipMemcpyDeviceToHost));
     if (counts) {
         counts->n_requests = h[C_REQ]; counts->n_local = h[C_LOCAL]; counts->n_cache = h[C_CACHE];
         counts->n_host = h[C_HOST]; counts->n_lost = h[C_LOST]; counts->n_invalid = h[C_INVALID];
     }
     if (n_miss) *n_miss = h[C_MISS];
     uint32_t m = std::min(h[C_MISS], miss_cap);
-    if (miss_idx && m) HIP_TRY(hipMemcpy(miss_idx, ss->miss_idx, m * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    if (miss_idx && m) HIP_TRY(hipMemcpy(miss_idx, l->miss, m * sizeof(uint32_t), hipMemcpyDeviceToHost));
     return HARVEST_OK;
 }
 

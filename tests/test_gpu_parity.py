@@ -615,6 +615,35 @@ def test_fetch_again_for_another_layer(general, head_major):
         eh.close(); eo.close()
 
 
+@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
+@pytest.mark.parametrize("many_experts", [False, True], ids=["few-experts", "more-experts-than-table-cells"])
+def test_fetch_again_after_an_expert_fetch_on_the_same_stream(general, many_experts):
+    """A decode step walks its layers with KV and expert fetches in turn, all on one stream: KV fetch, expert fetch, the
+    KV fetch again for the next layer.  Each class keeps request lists of its own on the stream, so the repeated KV
+    fetch must deliver that layer's blocks whatever the expert fetch in between wrote - also when the expert class has
+    more experts per layer than the block table has cells, which makes the expert fetch the one that sizes its lists."""
+    say(f"fetch again after an expert fetch, general path {general}, many experts {many_experts}")
+    wl = W.kv_decode(seed=43, n_layers=3, n_seq=2, min_len=300, max_len=700, p_cache=0.6, n_steps=8)
+    n_exp = 2500 if many_experts else 12
+    ex = W.expert_offload(seed=43, shape=W.ExpertShape(n_layers=3, n_experts=n_exp, d_model=16, d_ff=24), n_tokens=40,
+                          n_local=2, fill_mode=W.FILL_TAG)
+    eo, eh = P.make_engines(wl, ex, poison=True, hip_kwargs=dict(general_fetch=general))      # one stream for both classes
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        assert eh.streams[S.KV] is None and eh.streams[S.EXPERT] is None
+        assert max(len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)) * wl.n_seq < 2500
+        for t in range(6):
+            P.assert_kv_equal(ro.fetch(0), rh.fetch(0), f"step {t}, layer 0")
+            for layer in (0, 1, 2):
+                P.assert_experts_equal(xo.fetch(t, layer), xh.fetch(t, layer), f"step {t}, experts of layer {layer}")
+                nxt = (layer + 1) % 3
+                P.assert_kv_equal(eo.fetch_kv_again(nxt), eh.fetch_kv_again(nxt), f"step {t}, again at layer {nxt}")
+            ro.append(t); rh.append(t)
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- several layers in one call --------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
