@@ -89,7 +89,9 @@ enum harvest_status {
     HARVEST_EHIP = -4,     /* a HIP runtime call failed */
     HARVEST_ELOST = -5,    /* lossy object whose cache copy was revoked (Section 3.1) */
     HARVEST_ENODEV = -6,   /* data-moving call on a context created with HARVEST_FLAG_NO_DEVICE */
-    HARVEST_EBUSY = -7     /* prefetcher: both buffers are in use (issue), or no issued fetch is left (acquire) */
+    HARVEST_EBUSY = -7,    /* prefetcher: both buffers are in use (issue), or no issued fetch is left (acquire);
+                              harvest_fetch_kv_static: the context already serves its 4 streams */
+    HARVEST_E2BIG = -8     /* harvest_fetch_kv_static: the block table has more cells than its fixed scratch holds */
 };
 
 enum harvest_class { HARVEST_KV = 0, HARVEST_EXPERT = 1, HARVEST_N_CLASSES = 2 };
@@ -285,6 +287,28 @@ int harvest_fetch_kv_head_major(harvest_ctx *ctx, uint32_t layer, const int32_t 
                                 const int32_t *d_n_blocks, uint32_t n_seq, uint32_t max_blocks, void *d_dst_k,
                                 void *d_dst_v, const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks,
                                 uint64_t dst_capacity_blocks, uint32_t n_heads, uint32_t block_tokens, void *stream);
+
+/* harvest_fetch_kv for callers that cannot allocate device memory when they call: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same requests, same bytes in d_dst_k / d_dst_v, but this call never
+ * allocates (no hipMalloc / hipFree / hipHostMalloc, no event or stream creation, on any call including the first):
+ * everything it needs beyond its arguments - the arrays of the resolve, the two request lists, the counters - lives in
+ * a statically allocated device array of about 3.4 MiB, which every GPU the library has created a context on holds
+ * until the process ends.  The limit that follows: n_seq * max_blocks <= HARVEST_STATIC_MAX_CELLS table cells,
+ * HARVEST_E2BIG (and a message on stderr, nothing enqueued) beyond.  Both gathers run on `stream` one after the other
+ * (there is no side stream to overlap the host tier on), so a fetch with a large host-tier share takes the sum of the
+ * two, not the longer one.  The fetch may be recorded into a HIP graph without any earlier call.
+ *   d_info     (device, 8 words, may be NULL) receives: requests, local, cache, host, lost, invalid, length of the miss
+ *              list, 0 - what harvest_fetch_info reports for harvest_fetch_kv;
+ *   d_miss_idx (device, n_seq * max_blocks words, may be NULL) receives the miss list in request order.
+ * All calls on one GPU - any stream, any context - share that GPU's array and each call overwrites all of it that it
+ * reads (nothing in it has to be zero): calls whose execution may overlap on one GPU race, so the caller orders them
+ * (one stream, or events).  A context serves up to 4 different streams this way (HARVEST_EBUSY for a fifth).  Revocation
+ * drains these fetches like any other.  harvest_fetch_kv_again and harvest_fetch_info do not see them. */
+#define HARVEST_STATIC_MAX_CELLS 65536u
+int harvest_fetch_kv_static(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                            uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                            const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, uint32_t *d_info,
+                            uint32_t *d_miss_idx, void *stream);
 
 /* Expert fetch (Section 4.3: experts are paged whole and must be resident before the FFN runs).  U = the distinct
  * valid expert numbers in d_topk_ids[n_tokens][k].  For e in U ascending: a local expert is used in place

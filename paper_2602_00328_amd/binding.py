@@ -20,7 +20,8 @@ import torch  # noqa: F401  - must be imported BEFORE the library is loaded: PyT
 from . import _build
 
 HOST, CACHE, LOCAL, NONE = 0, 1, 2, 3
-OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV, EBUSY = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV, EBUSY, E2BIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
+STATIC_MAX_CELLS = 65536
 KV, EXPERT = 0, 1
 FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE, FLAG_GENERAL_FETCH = 1, 2, 4, 8
 EVICT_DEMOTE = 1
@@ -74,6 +75,7 @@ SYMBOLS = {
     "harvest_free": (ctypes.c_int, [vp, ctypes.c_int, u32]),
     "harvest_register_cb": (ctypes.c_int, [vp, ctypes.c_int, u32, REVOKE_CB, vp]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
+    "harvest_fetch_kv_static": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp]),
     "harvest_fetch_kv_again": (ctypes.c_int, [vp, u32, vp, vp, vp]),
     "harvest_fetch_kv_layers": (ctypes.c_int, [vp, u32, u32, vp, vp, u32, u32, vp, vp, u64, vp, u64, vp]),
     "harvest_fetch_kv_head_major": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, vp, u64, u32, u32, vp]),
@@ -305,6 +307,16 @@ class Harvest:
         _chk(lib.harvest_fetch_kv(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
                                   _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block), dst_capacity_blocks,
                                   _stream_ptr(stream)), "harvest_fetch_kv")
+
+    def fetch_kv_static(self, layer, d_table, d_n_blocks, d_dst_k, d_dst_v, d_seq_dst_block, dst_capacity_blocks,
+                        d_info=None, d_miss_idx=None, stream=None):
+        """As fetch_kv, through the entry point that allocates nothing; d_info int32 [8], d_miss_idx int32 [n_seq *
+        max_blocks]: torch device tensors or None."""
+        n_seq, max_blocks = d_table.shape
+        _chk(lib.harvest_fetch_kv_static(self.h, layer, _dev_ptr(d_table), _dev_ptr(d_n_blocks), n_seq, max_blocks,
+                                         _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _dev_ptr(d_seq_dst_block),
+                                         dst_capacity_blocks, _dev_ptr(d_info), _dev_ptr(d_miss_idx), _stream_ptr(stream)),
+             "harvest_fetch_kv_static")
 
     def fetch_kv_again(self, layer, d_dst_k, d_dst_v, stream=None):
         _chk(lib.harvest_fetch_kv_again(self.h, layer, _dev_ptr(d_dst_k), _dev_ptr(d_dst_v), _stream_ptr(stream)),

@@ -202,6 +202,8 @@ struct StreamState {
     uint32_t *mark = nullptr;               // [MAX_EXPERTS / 32 + 1] routed-set bitmap and invalid-id count of large batches;
                                             // zero between fetches
     int last_cls = -1;                      // class of the latest fetch enqueued on this stream, -1: none yet (or an empty one)
+    bool fixed = false;                     // the lists are borrowed, of a fixed size, and there is no side stream: the
+                                            // state of a stream that harvest_fetch_kv_static serves
     // the latest single-layer KV fetch, for harvest_fetch_kv_again
     struct {
         bool valid = false, lists = false;  // lists: the general path ran, so the compacted lists describe it
@@ -220,6 +222,48 @@ struct StreamState {
     uint32_t *d_feedback = nullptr;
     bool feedback_valid[HARVEST_N_CLASSES] = { false, false };
 };
+
+// ---- fixed scratch of harvest_fetch_kv_static -------------------------------------------------------------------
+// Everything a KV fetch of up to HARVEST_STATIC_MAX_CELLS table cells needs beyond its inputs and outputs - the arrays
+// of the resolve, the two request lists, the miss list, the counters - in one file-scope device array, so that the
+// call allocates nothing.  Each GPU the library runs on holds its own copy, at its own address, until the process
+// ends; the address is asked for once per device (scratch_of_device), with that device current, and only that
+// address is ever handed to a kernel - the array's name is a host-side stand-in, not a device address.
+constexpr uint32_t STATIC_CELLS = HARVEST_STATIC_MAX_CELLS;
+constexpr size_t STATIC_ROWS = (STATIC_CELLS + WG - 1) / WG;
+constexpr size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr size_t SO_TMP = 0;
+constexpr size_t SO_HBM = SO_TMP + align256((size_t)STATIC_CELLS * sizeof(Rec));
+constexpr size_t SO_HOST = SO_HBM + align256((size_t)STATIC_CELLS * sizeof(Rec));
+constexpr size_t SO_MISS = SO_HOST + align256((size_t)STATIC_CELLS * sizeof(Rec));
+constexpr size_t SO_KIND = SO_MISS + align256((size_t)STATIC_CELLS * sizeof(uint32_t));
+constexpr size_t SO_BLK = SO_KIND + align256((size_t)STATIC_CELLS);
+constexpr size_t SO_CNT = SO_BLK + align256(STATIC_ROWS * BC_N * sizeof(uint32_t));
+constexpr size_t STATIC_BYTES = SO_CNT + align256(C_N * sizeof(uint32_t));
+static_assert(STATIC_ROWS <= 1024, "the fixed scratch has no room for the grouped compaction of very large tables");
+
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[MAX_DEVICES];          // per device: where that GPU's copy of `scratch` lives
+
+// The device address of `scratch` on device `dev`, which must be the current device.
+int scratch_of_device(int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= MAX_DEVICES) return HARVEST_EINVAL;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return HARVEST_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HARVEST_OK;
+}
+
+constexpr int STATIC_STREAMS = 4;                   // caller streams one context serves through harvest_fetch_kv_static
 
 }  // namespace
 
@@ -247,6 +291,10 @@ struct harvest_ctx {
     bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
     SegAlloc shared;                      // free space of cfg.d_shared_cache
     std::vector<harvest_prefetcher *> prefetchers;   // live ones: destroyed with the context if the caller did not
+    // harvest_fetch_kv_static: stream states made when the context is created (events, a pinned feedback word each), their
+    // lists inside the device's fixed scratch; a caller stream takes the first unused one
+    StreamState fixed_streams[STATIC_STREAMS];
+    int n_fixed_streams = 0;                         // how many have a caller stream
     std::mutex mu;
 };
 
@@ -284,6 +332,10 @@ void free_stream_state(StreamState *ss)
 {
     if (ss->side) (void)hipStreamDestroy(ss->side);
     for (hipEvent_t e : { ss->fork, ss->join, ss->last }) if (e) (void)hipEventDestroy(e);
+    if (ss->fixed) {
+        if (ss->h_feedback) (void)hipHostFree(ss->h_feedback);
+        return;
+    }
     for (Lists &l : ss->lists) { (void)hipFree(l.hbm); (void)hipFree(l.host); (void)hipFree(l.miss); }
     (void)hipFree(ss->work.tmp); (void)hipFree(ss->work.kind); (void)hipFree(ss->work.blk_counts);
     (void)hipFree(ss->work.grp_totals); (void)hipFree(ss->work.row_prefix);
@@ -335,6 +387,10 @@ int ensure_req_cap(StreamState *ss, int cls, uint32_t n_req)
 {
     Lists &l = ss->lists[cls];
     if (n_req <= l.cap) return HARVEST_OK;
+    if (ss->fixed) {
+        fprintf(stderr, "libharvest: a fetch of %u requests does not fit the fixed scratch (%u)\n", n_req, l.cap);
+        return HARVEST_E2BIG;
+    }
     if (is_capturing(ss->s)) {
         fprintf(stderr, "libharvest: this fetch needs larger scratch lists - run it once outside graph capture\n");
         return HARVEST_EINVAL;
@@ -537,7 +593,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
     uint32_t planes = c.cfg.n_planes;
     ga.tiles_per_chunk = tpc_hbm;                      // both tiers walk 4 KiB tiles
     ga.n_planes = planes;
-    const bool profile = ctx->profile && !is_capturing(ss->s);        // timing events cannot be recorded into a graph
+    // timing events cannot be recorded into a graph, and taking one from the pool may allocate
+    const bool profile = ctx->profile && !ss->fixed && !is_capturing(ss->s);
     const bool host_tier = c.cfg.n_host_slots != 0;
     // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
     // sized from what the previous gather of this class on this stream reported, never below a floor that still fills the
@@ -552,7 +609,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
     // And whether there is a detour at all: when even the longer of the two is expected to be over in less time than the
     // two crossings take (a small fetch: a few dozen blocks from the host, or some tens of MiB from HBM), both run on the
     // caller's stream one after the other, and so they do when the class has no host tier.
-    bool host_stays = host_tier, serial = !host_tier;
+    bool host_stays = host_tier, serial = !host_tier || !ss->side;
     if (ss->feedback_valid[cls]) {
         uint64_t seen = *(volatile uint32_t *)&ss->h_feedback[cls];
         uint64_t seen_host = *(volatile uint32_t *)&ss->h_feedback[HARVEST_N_CLASSES + cls];
@@ -677,6 +734,23 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
             c.host_dev[p] = (uint64_t)d;
         }
     }
+    if (ctx->cls[HARVEST_KV].used) {
+        unsigned char *base = nullptr;
+        int rc = scratch_of_device(cfg->device, &base);
+        if (rc) return rc;
+        for (StreamState &ss : ctx->fixed_streams) {
+            ss.fixed = true;
+            HIP_TRY(hipEventCreateWithFlags(&ss.last, hipEventDisableTiming));
+            HIP_TRY(hipHostMalloc((void **)&ss.h_feedback, 64, hipHostMallocDefault));
+            memset(ss.h_feedback, 0, 64);
+            HIP_TRY(hipHostGetDevicePointer((void **)&ss.d_feedback, ss.h_feedback, 0));
+            Lists &l = ss.lists[HARVEST_KV];
+            l.hbm = (Rec *)(base + SO_HBM); l.host = (Rec *)(base + SO_HOST); l.miss = (uint32_t *)(base + SO_MISS);
+            l.cnt = (uint32_t *)(base + SO_CNT); l.cap = STATIC_CELLS;
+            ss.work.tmp = (Rec *)(base + SO_TMP); ss.work.kind = base + SO_KIND;
+            ss.work.blk_counts = (uint32_t *)(base + SO_BLK);
+        }
+    }
     HIP_TRY(hipDeviceSynchronize());
     return HARVEST_OK;
 }
@@ -696,7 +770,8 @@ const char *harvest_strerror(int status)
     case HARVEST_EHIP: return "HIP runtime error";
     case HARVEST_ELOST: return "lossy object was revoked";
     case HARVEST_ENODEV: return "context has no device";
-    case HARVEST_EBUSY: return "both prefetch buffers are in use, or none is ready";
+    case HARVEST_EBUSY: return "both prefetch buffers are in use, or none is ready; or no fixed stream state is left";
+    case HARVEST_E2BIG: return "the request does not fit the fixed scratch of an entry point that allocates nothing";
     }
     return "unknown status";
 }
@@ -802,6 +877,8 @@ int harvest_destroy(harvest_ctx *ctx)
         }
         (void)hipStreamSynchronize(ctx->ctl);
         for (auto &kv : ctx->streams) free_stream_state(kv.second.get());
+        for (int i = 0; i < ctx->n_fixed_streams; ++i) (void)hipStreamSynchronize(ctx->fixed_streams[i].s);
+        for (StreamState &ss : ctx->fixed_streams) free_stream_state(&ss);
         for (auto &st : ctx->staging) { (void)hipEventDestroy(st.done); (void)hipHostFree(st.h); }
         for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
@@ -988,9 +1065,12 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
         if ((rc = device_guard(ctx))) return rc;
         // the drain waits for streams: impossible while one of them is being recorded into a graph
-        if (!ctx->no_device)
+        if (!ctx->no_device) {
             for (auto &kv : ctx->streams)
                 if (is_capturing(kv.first)) return HARVEST_EINVAL;
+            for (int i = 0; i < ctx->n_fixed_streams; ++i)
+                if (is_capturing(ctx->fixed_streams[i].s)) return HARVEST_EINVAL;
+        }
         // 1. invalidate
         for (uint32_t i = 0; i < n; ++i) {
             uint32_t id = ids[i];
@@ -1011,6 +1091,8 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             if (ctx->captured_work) HIP_TRY(hipDeviceSynchronize());
             for (auto &kv : ctx->streams)
                 if (kv.second->last_valid) HIP_TRY(hipEventSynchronize(kv.second->last));
+            for (int i = 0; i < ctx->n_fixed_streams; ++i)
+                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipEventSynchronize(ctx->fixed_streams[i].last));
             // 3. (poison and) free
             if (ctx->poison) {
                 std::vector<Item> items;
@@ -1073,7 +1155,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
                            uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                            const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
                            uint32_t n_heads, uint32_t block_tokens, void *stream, uint32_t n_layers,
-                           uint64_t dst_layer_stride);
+                           uint64_t dst_layer_stride, StreamState *fixed_ss = nullptr, uint32_t *miss_out = nullptr);
 
 static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
                          uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
@@ -1089,12 +1171,13 @@ static int fetch_kv_impl(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bloc
                            d_seq_cap_blocks, dst_capacity_blocks, n_heads, block_tokens, stream, n_layers, dst_layer_stride);
 }
 
-// The body of every KV fetch; the context's lock is held.
+// The body of every KV fetch; the context's lock is held.  fixed_ss: the stream's state when it is not one of
+// ctx->streams (harvest_fetch_kv_static); miss_out: where the miss list goes instead of the stream's own array.
 static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
                            uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
                            const uint64_t *d_seq_dst_block, const uint32_t *d_seq_cap_blocks, uint64_t dst_capacity_blocks,
                            uint32_t n_heads, uint32_t block_tokens, void *stream, uint32_t n_layers,
-                           uint64_t dst_layer_stride)
+                           uint64_t dst_layer_stride, StreamState *fixed_ss, uint32_t *miss_out)
 {
     int rc;
     ClassState &c = ctx->cls[HARVEST_KV];
@@ -1114,8 +1197,8 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
         hm.ups = hm.upr * block_tokens;
     }
     if ((rc = device_guard(ctx))) return rc;
-    StreamState *ss;
-    if ((rc = get_stream(ctx, stream, &ss))) return rc;
+    StreamState *ss = fixed_ss;
+    if (!ss && (rc = get_stream(ctx, stream, &ss))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     ss->last_kv.valid = false;
     if (total == 0) { ss->last_cls = -1; return HARVEST_OK; }
@@ -1132,7 +1215,8 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
     if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, HARVEST_KV, (uint32_t)total))) return rc;
-    const Lists &lists = ss->lists[HARVEST_KV];
+    Lists lists = ss->lists[HARVEST_KV];
+    if (miss_out) lists.miss = miss_out;
     const KvWork &work = ss->work;
     uint32_t *cnt = lists.cnt;
     const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
@@ -1213,6 +1297,41 @@ int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void
     ss->last_cls = HARVEST_KV;
     return launch_gathers(ctx, ss, c, HARVEST_KV, ss->lists[HARVEST_KV], (uint64_t)k.n_seq * k.max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
                           head_major ? &hm : nullptr, 1, 0, (int64_t)layer - (int64_t)k.layer, true);
+}
+
+int harvest_fetch_kv_static(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,
+                            uint32_t n_seq, uint32_t max_blocks, void *d_dst_k, void *d_dst_v,
+                            const uint64_t *d_seq_dst_block, uint64_t dst_capacity_blocks, uint32_t *d_info,
+                            uint32_t *d_miss_idx, void *stream)
+{
+    int rc = check_class(ctx, HARVEST_KV);
+    if (rc) return rc == HARVEST_ENOENT ? HARVEST_EINVAL : rc;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    const uint64_t total = (uint64_t)n_seq * max_blocks;
+    if (total > STATIC_CELLS) {
+        fprintf(stderr, "libharvest: harvest_fetch_kv_static serves block tables of up to %u cells, this one has %llu\n",
+                STATIC_CELLS, (unsigned long long)total);
+        return HARVEST_E2BIG;
+    }
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    StreamState *ss = nullptr;
+    for (int i = 0; i < ctx->n_fixed_streams && !ss; ++i)
+        if (ctx->fixed_streams[i].s == (hipStream_t)stream) ss = &ctx->fixed_streams[i];
+    if (!ss) {
+        if (ctx->n_fixed_streams == STATIC_STREAMS) {
+            fprintf(stderr, "libharvest: harvest_fetch_kv_static serves %d streams per context\n", STATIC_STREAMS);
+            return HARVEST_EBUSY;
+        }
+        ss = &ctx->fixed_streams[ctx->n_fixed_streams++];
+        ss->s = (hipStream_t)stream;
+    }
+    rc = fetch_kv_locked(ctx, layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_dst_k, d_dst_v, d_seq_dst_block, nullptr,
+                         dst_capacity_blocks, 0, 0, stream, 1, 0, ss, d_miss_idx);
+    if (rc || !d_info) return rc;
+    hipLaunchKernelGGL(export_info, dim3(1), dim3(64), 0, ss->s, (const uint32_t *)ss->lists[HARVEST_KV].cnt, d_info,
+                       total ? 1u : 0u);
+    HIP_TRY(hipGetLastError());
+    return mark_last(ctx, ss);
 }
 
 int harvest_fetch_kv(harvest_ctx *ctx, uint32_t layer, const int32_t *d_block_table, const int32_t *d_n_blocks,

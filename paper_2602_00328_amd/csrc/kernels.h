@@ -852,6 +852,14 @@ __global__ void repeat_totals(const uint32_t *__restrict__ cnt, unsigned long lo
     if (i <= C_INVALID && cnt[i]) atomicAdd(&totals[i], (unsigned long long)cnt[i]);
 }
 
+// The counters of a fetch, as harvest_fetch_kv_static hands them to its caller: requests, local, cache, host, lost,
+// invalid, length of the miss list, 0.  any == 0: the fetch had no table cell and ran no kernel - all zero.
+__global__ void export_info(const uint32_t *__restrict__ cnt, uint32_t *__restrict__ info, uint32_t any)
+{
+    uint32_t i = threadIdx.x;
+    if (i < 8) info[i] = !any ? 0u : (i <= C_INVALID ? cnt[i] : (i == 6 ? cnt[C_MISS] : 0u));
+}
+
 // Plain contiguous copy with the HBM-tier inner loop (reference ceiling / counter calibration).
 __global__ __launch_bounds__(WG) void plain_copy(uint64_t dst, uint64_t src, uint64_t bytes)
 {
