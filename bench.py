@@ -201,7 +201,7 @@ def bench_tiny(args):
     import torch
     import workloads as W
     from workloads import scenarios as S
-    from paper_2602_00328_amd.engine import HipEngine
+    from workloads.hip_engine import HipEngine
     wl = W.kv_tiny(args.seed)
     chunk = wl.shape.chunk_bytes
     want, cpu_baseline = None, None
@@ -285,7 +285,7 @@ def bench_experts(args):
     import torch
     import workloads as W
     from workloads import scenarios as S
-    from paper_2602_00328_amd.engine import HipEngine
+    from workloads.hip_engine import HipEngine
     dev = torch.device("cuda", 0)
     phi = args.workload == "experts_phi"
     L = min(args.layers, 32 if phi else 24)
@@ -477,7 +477,7 @@ def main():
     import workloads as W
     from workloads import scenarios as S
     from paper_2602_00328_amd import binding as B
-    from paper_2602_00328_amd.engine import HipEngine
+    from workloads.hip_engine import HipEngine
 
     torch.cuda.set_device(0)
     if args.workload == "kv_tiny":

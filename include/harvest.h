@@ -348,6 +348,13 @@ int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream);
 int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
                        uint32_t miss_cap, uint32_t *n_miss);
 
+/* The same for the last fetch of class cls enqueued on `stream` (Sections 4.3 and 5.2: a decode step fetches KV blocks
+ * and experts layer by layer, typically on one stream; each class keeps counters and a miss list of its own there, so a
+ * later fetch of the other class does not hide them).  cls < 0: the latest fetch of either class, i.e.
+ * harvest_fetch_info.  EINVAL: cls >= HARVEST_N_CLASSES. */
+int harvest_fetch_info_of(harvest_ctx *ctx, void *stream, int cls, harvest_fetch_counts *counts, uint32_t *miss_idx,
+                          uint32_t miss_cap, uint32_t *n_miss);
+
 /* ---- write-back (Sections 5.1, 5.2) ----------------------------------------------------------------------- */
 
 /* Eviction / write-back: the source bytes become the value of each object: they are written to its host slot (when

@@ -9,6 +9,7 @@ from __future__ import annotations
 import numpy as np
 
 import workloads as W
+from workloads.digest import digest as _digest
 from . import OracleClass, SegPool, HOST, CACHE, LOCAL, NONE, EVICT_DEMOTE, IN_PLACE, STAGED  # noqa: F401
 
 KV, EXPERT = 0, 1
@@ -128,12 +129,22 @@ class OracleEngine:
                                                    dst_k=np.full(n, dst_fill, np.uint8), dst_v=np.full(n, dst_fill, np.uint8))
         return k, (v if c.n_planes == 2 else None), np.sort(miss), counts
 
-    def fetch_experts(self, layer, topk, n_staging):
-        """-> (list over experts: None or the expert's bytes as the FFN would see them, kinds, sorted miss, counts)."""
+    def fetch_experts(self, layer, topk, n_staging, digest=False):
+        """-> (list over experts: None or the expert's bytes as the FFN would see them, kinds, sorted miss, counts).
+        digest: the first element is the checksum of the staging slots in use instead (long runs at full size)."""
         c = self.c[EXPERT]
         E = self.spec[EXPERT].n_experts
-        staging, kind, where, miss, counts = c.fetch_experts(layer, E, topk, n_staging)
+        buf = None
+        if digest:               # one staging buffer for the whole run: only the slots a fetch fills are looked at
+            buf = getattr(self, "_staging_buf", None)
+            if buf is None or buf.size != n_staging * c.chunk_bytes:
+                buf = self._staging_buf = np.zeros(n_staging * c.chunk_bytes, dtype=np.uint8)
+        staging, kind, where, miss, counts = c.fetch_experts(layer, E, topk, n_staging, staging=buf)
         self._last_expert_fetch = (staging, where, kind, layer)
+        if digest:
+            n_staged = int((kind == STAGED).sum())
+            assert sorted(where[kind == STAGED]) == list(range(n_staged))
+            return _digest(staging[:n_staged * c.chunk_bytes]), kind, where, np.sort(miss), counts
         out = []
         for e in range(E):
             if kind[e] == IN_PLACE:
@@ -151,7 +162,10 @@ class OracleEngine:
     def fetch_experts_begin(self, *a, **k):
         return self.fetch_experts(*a, **k)
 
-    def fetch_end(self, handle):
+    def fetch_end(self, handle, digest=False):
+        if digest and len(handle) == 4:                  # a KV fetch: (k, v, miss, counts)
+            k, v, miss, counts = handle
+            return _digest(k), (None if v is None else _digest(v)), miss, counts
         return handle
 
     def evict(self, cls, layer, ids, src0, src1, src_block, stride, flags=0):

@@ -87,6 +87,7 @@ SYMBOLS = {
     "harvest_prefetch_acquire": (ctypes.c_int, [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]),
     "harvest_prefetch_release": (ctypes.c_int, [vp, vp]),
     "harvest_fetch_info": (ctypes.c_int, [vp, vp, ctypes.POINTER(harvest_fetch_counts), vp, u32, vp]),
+    "harvest_fetch_info_of": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.POINTER(harvest_fetch_counts), vp, u32, vp]),
     "harvest_evict": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, vp, u32, vp, vp, vp, u64, ctypes.c_int, vp]),
     "harvest_stats": (ctypes.c_int, [vp, ctypes.POINTER(harvest_stats_t)]),
     "harvest_profile": (ctypes.c_int, [vp, ctypes.POINTER(harvest_profile_t)]),
@@ -345,12 +346,17 @@ class Harvest:
                                        n_staging_slots, _dev_ptr(d_expert_ptr), _stream_ptr(stream)),
              "harvest_fetch_experts")
 
-    def fetch_info(self, stream=None, miss_cap=0):
+    def fetch_info(self, stream=None, miss_cap=0, cls=None):
+        """cls: the latest fetch of that class on the stream (harvest_fetch_info_of); None: the latest fetch."""
         counts = harvest_fetch_counts()
         miss = np.zeros(max(1, miss_cap), dtype=np.uint32)
         n_miss = u32()
-        _chk(lib.harvest_fetch_info(self.h, _stream_ptr(stream), ctypes.byref(counts), _np_ptr(miss), miss_cap,
-                                    ctypes.byref(n_miss)), "harvest_fetch_info")
+        if cls is None:
+            _chk(lib.harvest_fetch_info(self.h, _stream_ptr(stream), ctypes.byref(counts), _np_ptr(miss), miss_cap,
+                                        ctypes.byref(n_miss)), "harvest_fetch_info")
+        else:
+            _chk(lib.harvest_fetch_info_of(self.h, _stream_ptr(stream), cls, ctypes.byref(counts), _np_ptr(miss),
+                                           miss_cap, ctypes.byref(n_miss)), "harvest_fetch_info_of")
         return counts.as_dict(), miss[:min(n_miss.value, miss_cap)].copy(), n_miss.value
 
     def evict(self, cls, layer, ids, d_src0, d_src1, src_block, src_layer_stride, flags=0, stream=None):

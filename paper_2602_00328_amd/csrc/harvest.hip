@@ -201,7 +201,9 @@ struct StreamState {
     uint32_t *cnt_block = nullptr;          // the counters of both classes: one allocation
     uint32_t *mark = nullptr;               // [MAX_EXPERTS / 32 + 1] routed-set bitmap and invalid-id count of large batches;
                                             // zero between fetches
-    int last_cls = -1;                      // class of the latest fetch enqueued on this stream, -1: none yet (or an empty one)
+    int last_cls = -1;                      // class of the latest fetch enqueued on this stream, -1: none yet
+    bool counted[HARVEST_N_CLASSES] = { false, false };   // the class's latest fetch ran kernels, so its counters are its own
+                                            // (an empty block table runs none: that fetch reports zeros)
     bool fixed = false;                     // the lists are borrowed, of a fixed size, and there is no side stream: the
                                             // state of a stream that harvest_fetch_kv_static serves
     // the latest single-layer KV fetch, for harvest_fetch_kv_again
@@ -1201,7 +1203,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if (!ss && (rc = get_stream(ctx, stream, &ss))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     ss->last_kv.valid = false;
-    if (total == 0) { ss->last_cls = -1; return HARVEST_OK; }
+    if (total == 0) { ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = false; return HARVEST_OK; }
     auto remember = [&](bool lists) {
         if (n_layers != 1) return;
         auto &k = ss->last_kv;
@@ -1236,7 +1238,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
                            dst_layer_stride, lists.miss, cnt, ctx->d_totals + HARVEST_KV * C_N,
                            ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV);
         HIP_TRY(hipGetLastError());
-        ss->last_cls = HARVEST_KV;
+        ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = true;
         ss->feedback_valid[HARVEST_KV] = true;
         remember(false);
         return mark_last(ctx, ss);
@@ -1260,7 +1262,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
                        grouped ? (const uint32_t *)work.grp_totals : (const uint32_t *)nullptr,
                        grouped ? (const uint32_t *)work.row_prefix : (const uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
-    ss->last_cls = HARVEST_KV;
+    ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = true;
     // lists recorded into a graph exist only once the graph has been replayed: nothing to use again
     remember(!is_capturing(ss->s));
     return launch_gathers(ctx, ss, c, HARVEST_KV, lists, total, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
@@ -1294,7 +1296,7 @@ int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void
         hm.upr = (uint32_t)(c.cfg.chunk_bytes / ((uint64_t)k.n_heads * k.block_tokens) / 16);
         hm.ups = hm.upr * k.block_tokens;
     }
-    ss->last_cls = HARVEST_KV;
+    ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = true;
     return launch_gathers(ctx, ss, c, HARVEST_KV, ss->lists[HARVEST_KV], (uint64_t)k.n_seq * k.max_blocks, (uint64_t)d_dst_k, (uint64_t)d_dst_v,
                           head_major ? &hm : nullptr, 1, 0, (int64_t)layer - (int64_t)k.layer, true);
 }
@@ -1395,7 +1397,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
                        lists.miss, cnt, ctx->d_totals + HARVEST_EXPERT * C_N, marked ? ss->mark : (uint32_t *)nullptr,
                        marked ? ss->mark + MAX_EXPERTS / 32 : (uint32_t *)nullptr);
     HIP_TRY(hipGetLastError());
-    ss->last_cls = HARVEST_EXPERT;
+    ss->last_cls = HARVEST_EXPERT; ss->counted[HARVEST_EXPERT] = true;
     return launch_gathers(ctx, ss, c, HARVEST_EXPERT, lists, std::min<uint64_t>(E, n_staging_slots), (uint64_t)d_staging, 0);
 }
 
@@ -1505,11 +1507,12 @@ int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream)
     return HARVEST_OK;
 }
 
-int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
-                       uint32_t miss_cap, uint32_t *n_miss)
+int harvest_fetch_info_of(harvest_ctx *ctx, void *stream, int cls, harvest_fetch_counts *counts, uint32_t *miss_idx,
+                          uint32_t miss_cap, uint32_t *n_miss)
 {
     if (!ctx) return HARVEST_EINVAL;
     if (ctx->no_device) return HARVEST_ENODEV;
+    if (cls >= HARVEST_N_CLASSES) return HARVEST_EINVAL;
     int rc = device_guard(ctx);
     if (rc) return rc;
     StreamState *ss = nullptr;
@@ -1523,8 +1526,9 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
     // state stays where it is until the context (or the prefetcher that owns the stream) is destroyed
     HIP_TRY(hipStreamSynchronize(ss->s));
     std::lock_guard<std::mutex> lk(ctx->mu);
+    if (cls < 0) cls = ss->last_cls;                       // the latest fetch, whichever class it was
     uint32_t h[C_N] = { 0 };
-    const Lists *l = ss->last_cls >= 0 ? &ss->lists[ss->last_cls] : nullptr;
+    const Lists *l = cls >= 0 && ss->counted[cls] ? &ss->lists[cls] : nullptr;
     if (l) HIP_TRY(hipMemcpy(h, l->cnt, sizeof h, hipMemcpyDeviceToHost));
     if (counts) {
         counts->n_requests = h[C_REQ]; counts->n_local = h[C_LOCAL]; counts->n_cache = h[C_CACHE];
@@ -1534,6 +1538,12 @@ int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *cou
     uint32_t m = std::min(h[C_MISS], miss_cap);
     if (miss_idx && m) HIP_TRY(hipMemcpy(miss_idx, l->miss, m * sizeof(uint32_t), hipMemcpyDeviceToHost));
     return HARVEST_OK;
+}
+
+int harvest_fetch_info(harvest_ctx *ctx, void *stream, harvest_fetch_counts *counts, uint32_t *miss_idx,
+                       uint32_t miss_cap, uint32_t *n_miss)
+{
+    return harvest_fetch_info_of(ctx, stream, -1, counts, miss_idx, miss_cap, n_miss);
 }
 
 int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, uint32_t n, const void *d_src0,

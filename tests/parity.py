@@ -10,7 +10,7 @@ def make_engines(kv_wl=None, ex_wl=None, poison=False, two_streams=False, kv_lay
                  local_slack=0, hip_kwargs=None, kv_spec=None, ex_spec=None, shared_cache_bytes=0, shared_granule=0):
     """shared_cache_bytes > 0: both classes carve their cache tier from one pool of that size (best-fit segments)."""
     from oracle.engine import OracleEngine
-    from paper_2602_00328_amd.engine import HipEngine
+    from workloads.hip_engine import HipEngine
     shared = shared_cache_bytes > 0
     kv = kv_spec or (S.kv_spec(kv_wl, cache_slack, local_slack, shared=shared) if kv_wl is not None else None)
     ex = ex_spec or (S.expert_spec(ex_wl, shared=shared) if ex_wl is not None else None)

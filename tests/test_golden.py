@@ -34,6 +34,6 @@ def test_oracle_still_produces_the_stored_digests():
 
 @pytest.mark.gpu
 def test_hip_path_produces_the_stored_digests():
-    from paper_2602_00328_amd.engine import HipEngine
+    from workloads.hip_engine import HipEngine
     print("golden digests", flush=True)
     compare(G.digests(lambda **kw: HipEngine(**kw)), stored())

@@ -12,7 +12,7 @@ import parity as P
 from oracle import OracleError
 from oracle.engine import OracleEngine
 from paper_2602_00328_amd.binding import HarvestError
-from paper_2602_00328_amd.engine import HipEngine
+from workloads.hip_engine import HipEngine
 
 pytestmark = pytest.mark.gpu
 

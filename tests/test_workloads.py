@@ -1,5 +1,6 @@
 """The seeded input generators: determinism, the structure the configs ask for, regenerable chunks."""
 import numpy as np
+import pytest
 
 import workloads as W
 
@@ -108,3 +109,42 @@ def test_revoke_draw_is_a_quarter_and_order_independent():
     a = W.revoke_draw(0, 10, 0, {5, 1, 9, 3, 7, 11, 13, 15})
     b = W.revoke_draw(0, 10, 0, [15, 13, 11, 9, 7, 5, 3, 1])
     assert a.size == 2 and np.array_equal(a, b)
+
+
+# ---- the checksum long runs compare outputs with ---------------------------------------------------------------
+
+def _digest_by_definition(buf):
+    """The definition in digest.c, in Python integers."""
+    from workloads import digest as D
+    x = [int(v) for v in buf.view(np.uint64)]
+    w = [int(v) for v in D.weights()]
+    mask = (1 << 64) - 1
+    total = 0
+    for p in range((len(x) + D.M - 1) // D.M):
+        s = sum(x[p * D.M + j] * w[j] for j in range(min(D.M, len(x) - p * D.M))) & mask
+        total = (total + int(D.piece_factors(p + 1)[p]) * s) & mask
+    return total
+
+
+@pytest.mark.parametrize("n_bytes", [8, 4096, 8 * 65536, 8 * 65536 + 8, 8 * (2 * 65536 + 1234)])
+def test_digest_on_host_and_as_tensor_operations_follow_the_definition(n_bytes):
+    import torch
+    from workloads.digest import digest
+    buf = W.rng(9, n_bytes).integers(0, 256, size=n_bytes, dtype=np.uint8)
+    want = _digest_by_definition(buf)
+    assert digest(buf) == want
+    assert digest(torch.from_numpy(buf)) == want
+
+
+def test_digest_notices_single_bytes_and_moved_blocks():
+    from workloads.digest import digest
+    buf = W.rng(10).integers(0, 256, size=64 * 32768, dtype=np.uint8)
+    d0 = digest(buf)
+    one = buf.copy(); one[1234567] ^= 1
+    assert digest(one) != d0
+    swapped = buf.copy().reshape(64, 32768)
+    swapped[[3, 41]] = swapped[[41, 3]]                      # two blocks delivered to each other's place
+    assert digest(swapped.reshape(-1)) != d0
+    shifted = np.roll(buf, 16)
+    assert digest(shifted) != d0
+    assert digest(buf.copy()) == d0

@@ -5,6 +5,10 @@ draws, sequence lengths and routing traces, shaped like the KV-offload and
 expert-offload workloads of the Harvest paper (Sections 4.3-4.4 and 5.2-5.3).
 It holds nothing of the fetch method (no directory, no gather) and is the one
 module that both the CPU checker and the GPU library's tests may share.
+Beside the generators live the harness's own pieces: the scenario drivers
+(``scenarios``), the adapter that lets them drive the HIP library
+(``hip_engine``) and a checksum with which long runs compare what the two
+sides delivered without keeping it (``digest``).
 
 All structure draws use numpy's counter-based Philox generator keyed by
 (seed, stream); bulk payload bytes come from ``fill.c`` (splitmix64 on a
@@ -33,11 +37,11 @@ _lib = None
 
 
 def build(force: bool = True) -> str:
-    """Compile fill.c into libwlfill.so (gcc, OpenMP)."""
+    """Compile fill.c and digest.c into libwlfill.so (gcc, OpenMP)."""
     if force or not os.path.exists(_LIB_PATH):
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB_PATH,
-             os.path.join(_HERE, "fill.c")])
+             os.path.join(_HERE, "fill.c"), os.path.join(_HERE, "digest.c")])
     return _LIB_PATH
 
 

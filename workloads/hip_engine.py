@@ -1,4 +1,5 @@
-"""Harness-facing wrapper of the HIP library: numpy in, numpy out, device buffers managed with torch.
+"""Harness-side adapter of the HIP library: numpy in, numpy out, device buffers managed with torch.  It lives with the
+harness (scenario drivers, generators), not in the library's package: the library's Python side is the binding alone.
 
 This is what tests and the benchmark drive.  It only marshals: tables, routing ids and sources are copied to device
 tensors, the library is called through the C ABI, destinations are copied back for comparison.  No payload byte is
@@ -10,8 +11,9 @@ import numpy as np
 import torch
 
 import workloads as W
-from . import binding as B
-from .binding import KV, EXPERT, HOST, CACHE, LOCAL, NONE  # noqa: F401
+from workloads.digest import digest as _digest
+from paper_2602_00328_amd import binding as B
+from paper_2602_00328_amd.binding import KV, EXPERT, HOST, CACHE, LOCAL, NONE  # noqa: F401
 
 IN_PLACE, STAGED, OVERFLOW_OR_LOST = 1, 2, 3
 
@@ -202,12 +204,17 @@ class HipEngine:
     def fetch_experts(self, layer, topk, n_staging, staging_fill=0):
         return self.fetch_end(self.fetch_experts_begin(layer, topk, n_staging, staging_fill))
 
-    def fetch_end(self, handle):
+    def fetch_end(self, handle, digest=False):
+        """Waits for a fetch and returns what it delivered.  digest: instead of the delivered bytes, their checksum,
+        computed on the device (nothing but counters and the miss list is copied back): KV -> (digest of K, digest of V,
+        ...), experts -> (digest of the staging slots in use, ...)."""
         if handle[0] == "kv":
             _, dst, n_req, _keep = handle
             with self._on(KV):
-                counts, miss, n_miss = self.h.fetch_info(miss_cap=n_req)
+                counts, miss, n_miss = self.h.fetch_info(miss_cap=n_req, cls=KV)
                 assert n_miss == miss.size
+                if digest:
+                    return _digest(dst[0]), (_digest(dst[1]) if len(dst) > 1 else None), np.sort(miss), counts
                 k = dst[0].cpu().numpy()
                 v = dst[1].cpu().numpy() if len(dst) > 1 else None
             return k, v, np.sort(miss), counts
@@ -215,7 +222,7 @@ class HipEngine:
         sp = self.spec[EXPERT]
         E = sp.n_experts
         with self._on(EXPERT):
-            counts, miss, n_miss = self.h.fetch_info(miss_cap=E)
+            counts, miss, n_miss = self.h.fetch_info(miss_cap=E, cls=EXPERT)
             ptrs = ptrs.cpu().numpy()
             local = self.h.dev_plane(EXPERT, LOCAL, 0) if sp.n_local_slots else None
             s0 = staging.data_ptr()
@@ -228,13 +235,17 @@ class HipEngine:
                     r = (p - s0) // sp.chunk_bytes
                     assert (p - s0) % sp.chunk_bytes == 0
                     kind[e], where[e] = STAGED, r
-                    out.append(staging[r * sp.chunk_bytes:(r + 1) * sp.chunk_bytes].cpu().numpy())
+                    out.append(None if digest else staging[r * sp.chunk_bytes:(r + 1) * sp.chunk_bytes].cpu().numpy())
                 else:
                     l0 = local.data_ptr()
                     assert l0 <= p < l0 + sp.n_local_slots * sp.chunk_bytes and (p - l0) % sp.chunk_bytes == 0
                     slot = (p - l0) // sp.chunk_bytes
                     kind[e], where[e] = IN_PLACE, slot
-                    out.append(local[0, slot].cpu().numpy())
+                    out.append(None if digest else local[0, slot].cpu().numpy())
+            if digest:                           # staged experts fill the slots 0 .. n-1; experts used in place moved no byte
+                n_staged = int((kind == STAGED).sum())
+                assert sorted(where[kind == STAGED]) == list(range(n_staged))
+                out = _digest(staging[:n_staged * sp.chunk_bytes])
         return out, kind, where, np.sort(miss), counts
 
     def evict(self, cls, layer, ids, src0, src1, src_block, stride, flags=0):

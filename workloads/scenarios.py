@@ -75,8 +75,11 @@ class KVRun:
             table[s, :len(t)] = t
         return table, np.array([len(t) for t in self.tables], dtype=np.int32)
 
-    def fetch(self, layer):
+    def fetch(self, layer, digest=False):
+        """digest: checksums of the two destination planes instead of the planes themselves."""
         table, nb = self.table_arrays()
+        if digest:
+            return self.e.fetch_end(self.e.fetch_kv_begin(layer, table, nb, self.seq_dst_block, self.cap), digest=True)
         return self.e.fetch_kv(layer, table, nb, self.seq_dst_block, self.cap)
 
     def fetch_begin(self, layer):
@@ -159,10 +162,15 @@ class ExpertRun:
         self.n_staging = n_staging if n_staging is not None else E
         self.lru = [LRU(wl.lru_capacity) for _ in range(sh.n_layers)] if wl.lru_capacity else None
 
-    def fetch(self, t, layer):
+    def fetch(self, t, layer, digest=False):
+        """digest: a checksum of the staged bytes instead of the experts' bytes."""
+        if digest:
+            return self.e.fetch_end(self.fetch_begin(t, layer, digest=True), digest=True)
         return self.e.fetch_experts(layer, self.wl.routing(t, layer), self.n_staging)
 
-    def fetch_begin(self, t, layer):
+    def fetch_begin(self, t, layer, digest=False):
+        if digest and self.e.name == "oracle":           # a CPU has nothing in flight: "begin" does the work
+            return self.e.fetch_experts(layer, self.wl.routing(t, layer), self.n_staging, digest=True)
         return self.e.fetch_experts_begin(layer, self.wl.routing(t, layer), self.n_staging)
 
     def staged_ranks(self, t, layer):
