@@ -65,6 +65,11 @@ def parse():
                     help="experts_phi only: also time the double-buffered prefetch ring against fetch-then-use")
     ap.add_argument("--graph-steps", type=int, default=64,
                     help="extra decode steps whose fetches replay recorded HIP graphs (one per layer); 0 = skip")
+    ap.add_argument("--gather-threads", type=int, default=0, choices=[0, 64, 128, 256],
+                    help="tuning: threads per workgroup of the HBM-tier gather (0 = the library's default, 64)")
+    ap.add_argument("--cache-layout", default="adjacent", choices=["adjacent", "planes"],
+                    help="kv_decode, equal-size slots: 'adjacent' = one cache pool [layer][slot][K|V][chunk] (a block's K and "
+                         "V are neighbours, one 64 KiB source run per block); 'planes' = a K pool and a V pool")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     args = ap.parse_args()
     if args.no_profile:
@@ -498,7 +503,8 @@ def main():
     n_cache_slots = int(wl.resident.sum()) + (0 if args.no_isolation else all_cache_slack)
     shared_bytes = n_cache_slots * (-(-(2 * chunk * args.layers) // 4096) * 4096) if args.shared_cache else 0
     eng = HipEngine(kv=S.kv_spec(wl, cache_slack=0 if args.no_isolation else all_cache_slack, shared=args.shared_cache),
-                    profile=not args.no_profile, host_wgs=args.host_wgs, shared_cache_bytes=shared_bytes)
+                    profile=not args.no_profile, host_wgs=args.host_wgs, shared_cache_bytes=shared_bytes,
+                    gather_threads=args.gather_threads, cache_planes_adjacent=args.cache_layout == "adjacent")
     run = S.KVRun(eng, wl)
     torch.cuda.synchronize()
     log(f"[bench] pools filled and {len(run.live)} blocks placed in {time.time() - t0:.1f}s")
@@ -732,7 +738,9 @@ def main():
                    "working_layout": "head-major" if args.head_major else "token-major",
                    "layers_per_fetch": args.fetch_layers, "placement": args.placement,
                    **({"fetch_again": True} if args.fetch_again else {}),
-                   "cache_tier": "shared pool of best-fit segments" if args.shared_cache else "equal-size slots",
+                   "cache_tier": "shared pool of best-fit segments" if args.shared_cache else
+                                 ("equal-size slots, one pool [layer][slot][K|V][chunk]" if args.cache_layout == "adjacent"
+                                  else "equal-size slots, a K pool and a V pool [layer][slot][chunk]"),
                    "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
                    "payload_bytes_per_step": payload // args.steps},
         "objects_per_s": round(d["n_requests"] * args.fetch_layers / sec),

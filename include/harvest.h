@@ -101,9 +101,13 @@ enum harvest_flags {
     HARVEST_FLAG_POISON = 2,     /* revoke overwrites the freed cache slot with 0xA5 after the drain */
     HARVEST_FLAG_PROFILE = 4,    /* bracket the gather kernels with events; read them with harvest_profile
                                     (launches recorded into a graph are not timed) */
-    HARVEST_FLAG_GENERAL_FETCH = 8 /* harvest_fetch_kv never takes its one-kernel form for small block tables (up to
+    HARVEST_FLAG_GENERAL_FETCH = 8, /* harvest_fetch_kv never takes its one-kernel form for small block tables (up to
                                     4096 cells): every fetch runs resolve, compaction and the two gathers - for
                                     measurements and tests of that path; results are the same either way */
+    HARVEST_FLAG_CACHE_PLANES_ADJACENT = 16 /* two-plane classes with cache slots of their own keep them in ONE buffer,
+                                    d_cache_pool[0], laid out [layer][slot][plane][chunk_bytes] (d_cache_pool[1] is ignored):
+                                    the K and V chunk of a block are neighbours, as they are in a segment of the shared
+                                    pool, and a fetch reads one run of 2 * chunk_bytes per block instead of two */
 };
 
 enum harvest_evict_flags {
@@ -138,7 +142,9 @@ typedef struct harvest_config {
                                        0 = 4096 */
     uint32_t small_fetch_cells;     /* tuning: harvest_fetch_kv takes its one-kernel form for block tables of up to this
                                        many cells (n_seq * max_blocks); 0 = default (4096) */
-    uint32_t reserved[4];           /* must be 0 */
+    uint32_t gather_threads;        /* tuning: threads per workgroup of the HBM-tier gather, 64, 128 or 256; 0 = default
+                                       (64: one wavefront per workgroup, 1 KiB tiles) */
+    uint32_t reserved[3];           /* must be 0 */
     void *d_shared_cache;           /* optional shared cache pool (device memory, 256-byte aligned), see below */
     uint64_t shared_cache_bytes;    /* its size: a multiple of the granule, at most 2^30 granules */
 } harvest_config;

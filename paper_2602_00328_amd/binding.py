@@ -23,7 +23,7 @@ HOST, CACHE, LOCAL, NONE = 0, 1, 2, 3
 OK, EINVAL, ENOSPC, ENOENT, EHIP, ELOST, ENODEV, EBUSY, E2BIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
 STATIC_MAX_CELLS = 65536
 KV, EXPERT = 0, 1
-FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE, FLAG_GENERAL_FETCH = 1, 2, 4, 8
+FLAG_NO_DEVICE, FLAG_POISON, FLAG_PROFILE, FLAG_GENERAL_FETCH, FLAG_CACHE_PLANES_ADJACENT = 1, 2, 4, 8, 16
 EVICT_DEMOTE = 1
 
 u32, u64, i32, i64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
@@ -37,7 +37,7 @@ class harvest_class_config(ctypes.Structure):
 
 class harvest_config(ctypes.Structure):
     _fields_ = [("flags", u32), ("device", i32), ("cls", harvest_class_config * 2),
-                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("small_fetch_cells", u32), ("reserved", u32 * 4),
+                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("small_fetch_cells", u32), ("gather_threads", u32), ("reserved", u32 * 3),
                 ("d_shared_cache", vp), ("shared_cache_bytes", u64)]
 
 
@@ -161,7 +161,7 @@ class Harvest:
 
     def __init__(self, kv: ClassSpec | None = None, expert: ClassSpec | None = None, flags: int = 0, device: int = 0,
                  gather_wg_per_cu: int = 0, host_wgs: int = 0, shared_cache_bytes: int = 0, shared_granule: int = 0,
-                 small_fetch_cells: int = 0):
+                 small_fetch_cells: int = 0, gather_threads: int = 0):
         """shared_cache_bytes > 0: one device pool of that size from which every class with n_cache_slots == 0 carves
         its cache-tier segments (best-fit)."""
         self.flags, self.device = flags, device
@@ -177,6 +177,8 @@ class Harvest:
         cfg.flags, cfg.device = flags, device
         cfg.gather_wg_per_cu, cfg.host_wgs = gather_wg_per_cu, host_wgs
         cfg.small_fetch_cells = small_fetch_cells
+        cfg.gather_threads = gather_threads
+        adjacent = bool(flags & FLAG_CACHE_PLANES_ADJACENT)
         cfg.shared_cache_bytes, cfg.shared_granule = shared_cache_bytes, shared_granule
         self.shared_cache = None
         if shared_cache_bytes and not self.no_device:
@@ -206,10 +208,18 @@ class Harvest:
                     cc.host_pool[p] = ptr
                 for tier, n_slots, field in ((CACHE, sp.n_cache_slots, cc.d_cache_pool),
                                              (LOCAL, sp.n_local_slots, cc.d_local_pool)):
-                    if n_slots:
-                        t = torch.zeros((sp.n_layers, n_slots, sp.chunk_bytes), dtype=torch.uint8, device=dev)
-                        self._dev[(k, tier, p)] = t
-                        field[p] = t.data_ptr()
+                    if not n_slots:
+                        continue
+                    if tier == CACHE and adjacent and sp.n_planes == 2:
+                        # one buffer [layer][slot][plane][chunk]; the planes are strided views of it
+                        if p == 0:
+                            self._cache_kv = torch.zeros((sp.n_layers, n_slots, 2, sp.chunk_bytes), dtype=torch.uint8, device=dev)
+                            field[0] = self._cache_kv.data_ptr()
+                        self._dev[(k, tier, p)] = self._cache_kv[:, :, p, :]
+                        continue
+                    t = torch.zeros((sp.n_layers, n_slots, sp.chunk_bytes), dtype=torch.uint8, device=dev)
+                    self._dev[(k, tier, p)] = t
+                    field[p] = t.data_ptr()
         h = vp()
         _chk(lib.harvest_create(ctypes.byref(cfg), ctypes.byref(h)), "harvest_create")
         self.h = h

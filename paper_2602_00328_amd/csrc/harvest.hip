@@ -104,6 +104,7 @@ struct ClassState {
     SegAlloc *seg = nullptr;
     uint64_t seg_base = 0, granule = 0, obj_granules = 0, n_granules = 0;
     uint64_t cache_in_use = 0;
+    bool adjacent = false;                  // equal-size cache slots laid out [layer][slot][plane][chunk] in one buffer
     uint64_t *d_dir = nullptr;
     // duplicate detection within one call without hashing: an object is marked with the number of the call
     std::vector<uint32_t> stamp;
@@ -150,11 +151,16 @@ struct ClassState {
     }
     uint64_t cache_base(uint32_t plane) const
     {
-        return seg ? seg_base + plane * cfg.chunk_bytes : (uint64_t)cfg.d_cache_pool[plane];
+        if (seg) return seg_base + plane * cfg.chunk_bytes;
+        return adjacent ? (uint64_t)cfg.d_cache_pool[0] + plane * cfg.chunk_bytes : (uint64_t)cfg.d_cache_pool[plane];
     }
+    // the planes of an object's chunk are neighbours in the cache tier: one source run per request instead of two
+    bool cache_planes_adjacent() const { return cfg.n_planes == 2 && (seg || adjacent); }
     uint64_t addr(int t, uint32_t plane, uint32_t layer, uint64_t s) const
     {
         if (t == T_CACHE && seg) return cache_base(plane) + s * granule + (uint64_t)layer * cfg.n_planes * cfg.chunk_bytes;
+        if (t == T_CACHE && adjacent)
+            return cache_base(plane) + ((uint64_t)layer * cfg.n_cache_slots + s) * cfg.n_planes * cfg.chunk_bytes;
         uint64_t base = t == T_HOST ? host_dev[plane]
                                     : (t == T_CACHE ? (uint64_t)cfg.d_cache_pool[plane] : (uint64_t)cfg.d_local_pool[plane]);
         uint64_t ns = t == T_HOST ? cfg.n_host_slots : (t == T_CACHE ? cfg.n_cache_slots : cfg.n_local_slots);
@@ -276,6 +282,7 @@ struct harvest_ctx {
     bool no_device = false, poison = false, profile = false, general_fetch = false;
     int n_cu = 256;
     uint32_t gather_grid = 0, host_grid = 0, ctl_grid = 0, pcie_grid = 0;
+    uint32_t gather_threads = HBM_WG;     // threads per workgroup of the HBM-tier gather (64, 128 or 256)
     uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
@@ -511,6 +518,9 @@ ClassDev class_dev(const ClassState &c)
     if (c.seg) {
         d.slot_stride[T_CACHE] = c.granule;
         d.layer_stride[T_CACHE] = (uint64_t)c.cfg.n_planes * c.cfg.chunk_bytes;
+    } else if (c.adjacent) {
+        d.slot_stride[T_CACHE] = (uint64_t)c.cfg.n_planes * c.cfg.chunk_bytes;
+        d.layer_stride[T_CACHE] = (uint64_t)c.cfg.n_cache_slots * c.cfg.n_planes * c.cfg.chunk_bytes;
     }
     return d;
 }
@@ -591,13 +601,16 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
     const ClassDev cd = class_dev(c);
     GatherArgs ga{};
     ga.chunk_bytes = c.cfg.chunk_bytes;
-    uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
+    // the head-major gather and the host tier walk 4 KiB tiles, the token-major HBM-tier gather gather_threads * 16 bytes
+    const uint32_t tile_hbm = hm ? TILE_4K : ctx->gather_threads * 16;
+    uint32_t tpc_hbm = tiles_per_chunk(c.cfg.chunk_bytes, tile_hbm);
     uint32_t planes = c.cfg.n_planes;
-    ga.tiles_per_chunk = tpc_hbm;                      // both tiers walk 4 KiB tiles
     ga.n_planes = planes;
     // timing events cannot be recorded into a graph, and taking one from the pool may allocate
     const bool profile = ctx->profile && !ss->fixed && !is_capturing(ss->s);
     const bool host_tier = c.cfg.n_host_slots != 0;
+    // one pass over both planes of each request where the cache tier keeps them side by side (see gather)
+    const bool fold = !hm && c.cache_planes_adjacent() && !ctx->gather_grid;
     // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
     // sized from what the previous gather of this class on this stream reported, never below a floor that still fills the
     // chip, never above the bound; the kernel loops where the grid is short, so any size is correct.  The guess is
@@ -645,6 +658,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
         if (profile) { pa = prof_event(ctx); pb = prof_event(ctx); }
         if (profile && host_tier) { pc = prof_event(ctx); pd = prof_event(ctx); }
         if (host_tier) {             // first, so that the long PCIe transfer starts before the CUs fill up
+            ga.tiles_per_chunk = tiles_per_chunk(c.cfg.chunk_bytes, TILE_4K);
             const Rec *recs = (const Rec *)lists.host;
             const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HOST_REQ);
             uint32_t *fb = ss->d_feedback + HARVEST_N_CLASSES + cls;
@@ -664,6 +678,7 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
             }
             HIP_TRY(hipGetLastError());
         }
+        ga.tiles_per_chunk = tpc_hbm;
         const Rec *recs = (const Rec *)lists.hbm;
         const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HBM_REQ);
         if (hm) {
@@ -673,12 +688,16 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
             else
                 hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, recs, n_req, ga, *hm,
                                    ss->d_feedback + cls);
-        } else if (pa)
-            hipExtLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req, ga,
-                                  ss->d_feedback + cls);
-        else
-            hipLaunchKernelGGL((gather<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, recs, n_req, ga,
-                               ss->d_feedback + cls);
+        } else {
+            const uint32_t nthr = ctx->gather_threads;
+            auto kernel = fold ? (nthr == 64 ? gather<64, true, true> : (nthr == 128 ? gather<128, true, true> : gather<256, true, true>))
+                               : (nthr == 64 ? gather<64, true, false> : (nthr == 128 ? gather<128, true, false> : gather<256, true, false>));
+            const dim3 g = fold ? dim3(grid_for(want * planes, MAX_GRID)) : dim3(grid, planes);
+            if (pa)
+                hipExtLaunchKernelGGL(kernel, g, dim3(nthr), 0, s_hbm, pa, pb, 0, recs, n_req, ga, ss->d_feedback + cls);
+            else
+                hipLaunchKernelGGL(kernel, g, dim3(nthr), 0, s_hbm, recs, n_req, ga, ss->d_feedback + cls);
+        }
         HIP_TRY(hipGetLastError());
         if (profile) {
             ctx->prof.push_back({ pa, pb, 0 });
@@ -714,6 +733,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->n_cu = prop.multiProcessorCount;
     ctx->gather_grid = cfg->gather_wg_per_cu * ctx->n_cu;         // 0: one workgroup per tile
     ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 24;
+    ctx->gather_threads = cfg->gather_threads ? cfg->gather_threads : HBM_WG;
     ctx->ctl_grid = 8 * ctx->n_cu;                 // HBM-bound fills
     ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
                                                    // GB/s against 55.2 with 2048 workgroups)
@@ -801,6 +821,8 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
     if (!cfg || !out) return HARVEST_EINVAL;
     *out = nullptr;
     for (uint32_t r : cfg->reserved) if (r) return HARVEST_EINVAL;
+    if (cfg->gather_threads != 0 && cfg->gather_threads != 64 && cfg->gather_threads != 128 && cfg->gather_threads != 256)
+        return HARVEST_EINVAL;
     auto ctx = std::make_unique<harvest_ctx>();
     ctx->cfg = *cfg;
     ctx->no_device = cfg->flags & HARVEST_FLAG_NO_DEVICE;
@@ -832,7 +854,8 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
         if (!ctx->no_device) {
             for (uint32_t p = 0; p < cc.n_planes; ++p) {
                 if (cc.n_host_slots && !cc.host_pool[p]) return HARVEST_EINVAL;
-                if (cc.n_cache_slots && !cc.d_cache_pool[p]) return HARVEST_EINVAL;
+                if (cc.n_cache_slots && !cc.d_cache_pool[p] && !(p == 1 && (cfg->flags & HARVEST_FLAG_CACHE_PLANES_ADJACENT)))
+                    return HARVEST_EINVAL;
                 if (cc.n_local_slots && !cc.d_local_pool[p]) return HARVEST_EINVAL;
                 if (((uint64_t)cc.host_pool[p] | (uint64_t)cc.d_cache_pool[p] | (uint64_t)cc.d_local_pool[p]) & 15)
                     return HARVEST_EINVAL;
@@ -841,6 +864,7 @@ int harvest_create(const harvest_config *cfg, harvest_ctx **out)
         ClassState &c = ctx->cls[k];
         c.cfg = cc;
         c.used = true;
+        c.adjacent = (cfg->flags & HARVEST_FLAG_CACHE_PLANES_ADJACENT) && cc.n_planes == 2 && cc.n_cache_slots;
         any = true;
         c.host_used.assign(cc.n_host_slots, 0);
         if (shared && cc.n_cache_slots == 0) {
@@ -1029,10 +1053,17 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
     memcpy(st->h, items.data(), bytes);
     HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
     if ((rc = release_after(st, ss->s))) return rc;
-    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-    uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);   // HBM to HBM, or over PCIe
-    hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
-                       c.cfg.chunk_bytes, tpc);
+    const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+    if (from && tiles_hbm < (1ull << 32)) {        // HBM to HBM: a workgroup per 1 KiB tile, as in the gather
+        hipLaunchKernelGGL(copy_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ss->s,
+                           (const Item *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                           tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
+    } else {                                       // over PCIe: a few dozen persistent workgroups
+        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+        uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);
+        hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
+                           c.cfg.chunk_bytes, tpc);
+    }
     HIP_TRY(hipGetLastError());
     // the new entries are written on the same stream, behind the copy: visible only once the bytes are in the slot,
     // and before anything enqueued on `stream` later
@@ -1107,10 +1138,17 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
                 memcpy(st->h, items.data(), bytes);
                 void *d_items = nullptr;
                 HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
-                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-                uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
-                hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items,
-                                   (uint32_t)items.size(), c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
+                const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+                if (tiles_hbm < (1ull << 32)) {
+                    hipLaunchKernelGGL(fill_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ctx->ctl,
+                                       (const Item *)d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                                       tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16), 0xA5A5A5A5u);
+                } else {
+                    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+                    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
+                    hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items,
+                                       (uint32_t)items.size(), c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
+                }
                 HIP_TRY(hipGetLastError());
                 HIP_TRY(hipStreamSynchronize(ctx->ctl));
             }
@@ -1215,13 +1253,13 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
     if (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15) return HARVEST_EINVAL;
-    if (total * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
+    if (total * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16) * c.cfg.n_planes >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, HARVEST_KV, (uint32_t)total))) return rc;
     Lists lists = ss->lists[HARVEST_KV];
     if (miss_out) lists.miss = miss_out;
     const KvWork &work = ss->work;
     uint32_t *cnt = lists.cnt;
-    const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM);
+    const uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_4K);
     if (!ctx->general_fetch && !head_major && n_layers <= 65535 && total <= ctx->small_cells && total * tpc <= SMALL_FETCH_TILES) {
         // a small table: the whole fetch is one kernel (no compaction, no second stream) - see fetch_kv_small
         GatherArgs ga{};
@@ -1379,7 +1417,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss;
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
-    if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, TILE_HBM) >= (1ull << 32)) return HARVEST_EINVAL;
+    if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, HARVEST_EXPERT, E))) return rc;
     if ((rc = order_after_directory_edits(ctx, ss))) return rc;
     const Lists &lists = ss->lists[HARVEST_EXPERT];
@@ -1634,12 +1672,19 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         memcpy(st->h, items.data(), bytes);
         HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
         if ((rc = release_after(st, ss->s))) return rc;
-        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
         bool to_host = false;                          // lossy objects move between HBM pools only
         for (const Item2 &it : items) to_host |= it.dst0 != 0;
-        uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
-        hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
-                           (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+        const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+        if (!to_host && tiles_hbm < (1ull << 32)) {
+            hipLaunchKernelGGL(copy_items2_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ss->s,
+                               (const Item2 *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                               tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
+        } else {
+            uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+            uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
+            hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
+                               (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+        }
         HIP_TRY(hipGetLastError());
     }
     if (!demoted.empty()) {
@@ -1705,9 +1750,9 @@ int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *str
 {
     if (!d_dst || !d_src || bytes % 16 || (((uint64_t)d_dst | (uint64_t)d_src) & 15)) return HARVEST_EINVAL;
     if (bytes == 0) return HARVEST_OK;
-    uint64_t n_tiles = (bytes + TILE_HBM - 1) / TILE_HBM;
+    uint64_t n_tiles = (bytes + HBM_WG * 16 - 1) / (HBM_WG * 16);
     uint32_t grid = grid_for(n_tiles, MAX_GRID);
-    hipLaunchKernelGGL(plain_copy, dim3(grid), dim3(WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
+    hipLaunchKernelGGL(plain_copy<HBM_WG>, dim3(grid), dim3(HBM_WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
                        bytes);
     HIP_TRY(hipGetLastError());
     return HARVEST_OK;

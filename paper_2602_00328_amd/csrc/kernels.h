@@ -34,7 +34,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WG = 256;                         // 4 wavefronts
 constexpr int WAVES = WG / 64;
-constexpr uint32_t TILE_HBM = WG * 16;          // 4 KiB: one 16-byte access per thread
+constexpr uint32_t TILE_4K = WG * 16;           // 4 KiB: one 16-byte access per thread of a 256-thread workgroup
+constexpr int HBM_WG = 64;                      // the HBM-tier gather runs one wavefront per workgroup (see gather)
 constexpr int UNROLL_HOST = 8;
 constexpr uint32_t TILE_HOST = WG * 16 * UNROLL_HOST;   // 32 KiB tiles of the host-built copy lists (place, write-back)
 constexpr int HOST_LOADS = 2;                   // 16-byte loads a thread of the host-tier gather keeps in flight
@@ -467,21 +468,22 @@ __device__ inline void st16(u32x4 *p, u32x4 v)
     else *g = v;
 }
 
-template <int UNROLL, bool NT>
+// One tile of NTHR * 16 * UNROLL bytes (or the first len bytes of it) by a workgroup of NTHR threads.
+template <int NTHR, int UNROLL, bool NT>
 __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint32_t tid)
 {
-    constexpr uint32_t TILE = WG * 16 * UNROLL;
+    constexpr uint32_t TILE = NTHR * 16 * UNROLL;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
     u32x4 *d = reinterpret_cast<u32x4 *>(dst);
     if (len >= TILE) {
         u32x4 v[UNROLL];
 #pragma unroll
-        for (int i = 0; i < UNROLL; ++i) v[i] = ld16<NT>(s + tid + i * WG);
+        for (int i = 0; i < UNROLL; ++i) v[i] = ld16<NT>(s + tid + i * NTHR);
 #pragma unroll
-        for (int i = 0; i < UNROLL; ++i) st16<NT>(d + tid + i * WG, v[i]);
+        for (int i = 0; i < UNROLL; ++i) st16<NT>(d + tid + i * NTHR, v[i]);
     } else {
         uint32_t n_vec = (uint32_t)(len >> 4);
-        for (uint32_t i = tid; i < n_vec; i += WG) st16<NT>(d + i, ld16<NT>(s + i));
+        for (uint32_t i = tid; i < n_vec; i += NTHR) st16<NT>(d + i, ld16<NT>(s + i));
     }
 }
 
@@ -490,32 +492,45 @@ __device__ inline void copy_tile(uint64_t src, uint64_t dst, uint64_t len, uint3
 // runs once; a smaller grid loops.  `feedback`, when given, is a word of pinned host memory that receives the list
 // length: the host sizes the next launch from it, because workgroups that find no tile are not free (about 0.2 ns
 // each on MI355X) while a grid somewhat short of the tile count is.
-template <int UNROLL, bool NT>
-__global__ __launch_bounds__(WG) void gather(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                             GatherArgs a, uint32_t *feedback)
+//
+// NTHR threads per workgroup, one 16-byte load and store each: a tile is NTHR * 16 bytes.  Measured on MI355X
+// (768 MiB gathered from scattered runs, read+write): one-wavefront workgroups (1 KiB tiles) move 6.29 TB/s from 32 KiB
+// runs and 6.57 TB/s from 64 KiB runs, 256-thread workgroups 6.12 and 6.40 - a wavefront that is its own workgroup
+// frees its slot the moment it is done instead of waiting for three others.
+//
+// FOLD: the planes of a request are taken in one pass - tile numbers run through plane 0, then plane 1, of each
+// request - instead of plane after plane over the whole list (blockIdx.y).  Where the cache tier keeps the planes of an
+// object next to each other this turns two 32 KiB source runs into one 64 KiB run, the length from which scattered
+// runs read as fast as a contiguous buffer (6.29 -> 6.57 TB/s in the measurement above); where the planes live in
+// pools of their own, plane after plane is the faster order (6.24 against 6.11 TB/s).
+template <int NTHR, bool NT, bool FOLD>
+__global__ __launch_bounds__(NTHR) void gather(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
+                                               GatherArgs a, uint32_t *feedback)
 {
-    constexpr uint32_t TILE = WG * 16 * UNROLL;
+    constexpr uint32_t TILE = NTHR * 16;
     uint32_t bx = blockIdx.x, gx = gridDim.x;
     // The first tile's list entry is fetched before the length is known, so that the two scalar loads overlap: a
     // workgroup lives for one load and one store, and every dependent load in front of them costs bandwidth.  The
     // host never launches more workgroups (in x) than the list has room for tiles, so the early read stays inside
-    // the list; it also guarantees capacity * tiles_per_chunk < 2^32, so tile numbers fit 32-bit division.
+    // the list; it also guarantees capacity * tiles per request < 2^32, so tile numbers fit 32-bit division.
     uint32_t tpc = a.tiles_per_chunk;
+    uint32_t tpr = FOLD ? tpc * a.n_planes : tpc;              // tiles per request in this grid's x dimension
     uint64_t t = bx;
-    uint32_t idx = (uint32_t)t / tpc;
+    uint32_t idx = (uint32_t)t / tpr;
     Rec x = recs[idx];
     uint32_t n_req = *n_req_ptr;
-    uint32_t plane = blockIdx.y;
-    if (feedback && bx == 0 && plane == 0 && threadIdx.x == 0) *feedback = n_req;
-    uint64_t n_tiles = (uint64_t)n_req * tpc;
-    uint64_t dst_base = plane ? a.dst_base[1] : a.dst_base[0];
+    if (feedback && bx == 0 && blockIdx.y == 0 && threadIdx.x == 0) *feedback = n_req;
+    uint64_t n_tiles = (uint64_t)n_req * tpr;
     while (t < n_tiles) {
-        uint64_t off = (uint64_t)((uint32_t)t - idx * tpc) * TILE;
+        uint32_t k = (uint32_t)t - idx * tpr;
+        uint32_t plane = FOLD ? (k >= tpc ? 1u : 0u) : blockIdx.y;
+        uint64_t off = (uint64_t)(FOLD ? k - plane * tpc : k) * TILE;
         uint64_t src = src_base_of(a, (uint32_t)(x.src & 3), plane) + (x.src & ~(uint64_t)3) + off;
-        copy_tile<UNROLL, NT>(src, dst_base + x.dst + off, a.chunk_bytes - off, threadIdx.x);
+        uint64_t dst_base = plane ? a.dst_base[1] : a.dst_base[0];
+        copy_tile<NTHR, 1, NT>(src, dst_base + x.dst + off, a.chunk_bytes - off, threadIdx.x);
         t += gx;
         if (t >= n_tiles) break;
-        idx = (uint32_t)t / tpc;
+        idx = (uint32_t)t / tpr;
         x = recs[idx];
     }
 }
@@ -543,11 +558,11 @@ __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer,
         Rec rec = { 0, 0 };
         int tier = resolve_cell(c, layer + blockIdx.z, table, n_blocks, max_blocks, seq_dst_block, dst_cap, nullptr, 0, r, rec);
         if (tier == T_HOST || tier == T_CACHE || tier == T_LOCAL) {
-            uint64_t off = (uint64_t)k * TILE_HBM;
+            uint64_t off = (uint64_t)k * TILE_4K;
             uint64_t src = src_base_of(a, (uint32_t)tier, plane) + (rec.src & 0x0000FFFFFFFFFFFCull) + off;
             uint64_t dst = (plane ? a.dst_base[1] : a.dst_base[0]) + (uint64_t)blockIdx.z * dst_step + rec.dst + off;
-            if (tier == T_HOST) copy_tile<1, false>(src, dst, a.chunk_bytes - off, threadIdx.x);
-            else copy_tile<1, true>(src, dst, a.chunk_bytes - off, threadIdx.x);
+            if (tier == T_HOST) copy_tile<WG, 1, false>(src, dst, a.chunk_bytes - off, threadIdx.x);
+            else copy_tile<WG, 1, true>(src, dst, a.chunk_bytes - off, threadIdx.x);
         }
     }
     if (blockIdx.x != 0 || plane != 0 || blockIdx.z != 0) return;
@@ -779,7 +794,7 @@ __global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items,
         uint64_t it = t / tiles_per_chunk;
         uint64_t off = (t - it * tiles_per_chunk) * TILE_HOST;
         Item x = items[it];
-        copy_tile<UNROLL_HOST, false>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
+        copy_tile<WG, UNROLL_HOST, false>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
     }
 }
 
@@ -838,6 +853,63 @@ __global__ __launch_bounds__(WG) void fill_items(const Item *__restrict__ items,
     }
 }
 
+// The same three between HBM pools only (placement from a staged copy, poisoning, demotion of lossy objects): nothing
+// crosses PCIe, so they take the HBM-tier gather's shape - one wavefront per workgroup, one 1 KiB tile each,
+// non-temporal accesses - instead of the few fat persistent workgroups that suit the link (measured on 17 GB of
+// staged experts: 4.99 TB/s in the persistent form).  Tile numbers are 32-bit: the host checks n_items * tiles_per_chunk.
+template <int NTHR>
+__global__ __launch_bounds__(NTHR) void copy_items_hbm(const Item *__restrict__ items, uint32_t n_items,
+                                                       uint64_t chunk_bytes, uint32_t tiles_per_chunk)
+{
+    constexpr uint32_t TILE = NTHR * 16;
+    uint32_t n_tiles = n_items * tiles_per_chunk;
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint32_t it = t / tiles_per_chunk;
+        uint64_t off = (uint64_t)(t - it * tiles_per_chunk) * TILE;
+        Item x = items[it];
+        copy_tile<NTHR, 1, true>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
+        if (n_tiles - t <= gridDim.x) break;
+    }
+}
+
+template <int NTHR>
+__global__ __launch_bounds__(NTHR) void copy_items2_hbm(const Item2 *__restrict__ items, uint32_t n_items,
+                                                        uint64_t chunk_bytes, uint32_t tiles_per_chunk)
+{
+    constexpr uint32_t TILE = NTHR * 16;
+    uint32_t n_tiles = n_items * tiles_per_chunk;
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint32_t it = t / tiles_per_chunk;
+        uint64_t off = (uint64_t)(t - it * tiles_per_chunk) * TILE;
+        Item2 x = items[it];
+        uint64_t len = chunk_bytes - off;
+        uint32_t n_vec = (uint32_t)((len > TILE ? TILE : len) >> 4);
+        if (threadIdx.x < n_vec) {
+            u32x4 v = ld16<true>(reinterpret_cast<const u32x4 *>(x.src + off) + threadIdx.x);
+            if (x.dst0) st16<true>(reinterpret_cast<u32x4 *>(x.dst0 + off) + threadIdx.x, v);
+            if (x.dst1) st16<true>(reinterpret_cast<u32x4 *>(x.dst1 + off) + threadIdx.x, v);
+        }
+        if (n_tiles - t <= gridDim.x) break;
+    }
+}
+
+template <int NTHR>
+__global__ __launch_bounds__(NTHR) void fill_items_hbm(const Item *__restrict__ items, uint32_t n_items,
+                                                       uint64_t chunk_bytes, uint32_t tiles_per_chunk, uint32_t pattern)
+{
+    constexpr uint32_t TILE = NTHR * 16;
+    uint32_t n_tiles = n_items * tiles_per_chunk;
+    u32x4 v = { pattern, pattern, pattern, pattern };
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint32_t it = t / tiles_per_chunk;
+        uint64_t off = (uint64_t)(t - it * tiles_per_chunk) * TILE;
+        uint64_t len = chunk_bytes - off;
+        uint32_t n_vec = (uint32_t)((len > TILE ? TILE : len) >> 4);
+        if (threadIdx.x < n_vec) st16<true>(reinterpret_cast<u32x4 *>(items[it].dst + off) + threadIdx.x, v);
+        if (n_tiles - t <= gridDim.x) break;
+    }
+}
+
 __global__ __launch_bounds__(WG) void dir_write(uint64_t *dir, const uint32_t *__restrict__ ids,
                                                 const uint64_t *__restrict__ entries, uint32_t n)
 {
@@ -861,12 +933,14 @@ __global__ void export_info(const uint32_t *__restrict__ cnt, uint32_t *__restri
 }
 
 // Plain contiguous copy with the HBM-tier inner loop (reference ceiling / counter calibration).
-__global__ __launch_bounds__(WG) void plain_copy(uint64_t dst, uint64_t src, uint64_t bytes)
+template <int NTHR>
+__global__ __launch_bounds__(NTHR) void plain_copy(uint64_t dst, uint64_t src, uint64_t bytes)
 {
-    uint64_t n_tiles = (bytes + TILE_HBM - 1) / TILE_HBM;
+    constexpr uint32_t TILE = NTHR * 16;
+    uint64_t n_tiles = (bytes + TILE - 1) / TILE;
     for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint64_t off = t * TILE_HBM;
-        copy_tile<1, true>(src + off, dst + off, bytes - off, threadIdx.x);
+        uint64_t off = t * TILE;
+        copy_tile<NTHR, 1, true>(src + off, dst + off, bytes - off, threadIdx.x);
     }
 }
 

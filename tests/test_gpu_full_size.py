@@ -28,12 +28,12 @@ def test_config2_long_context_decode_200_steps_real_shapes():
     start, 0.74 GiB of payload per step) and appends one token to each.  All 32 layers are materialised on both sides.
     Every step's K and V destinations are compared through a position-dependent checksum (the HIP side's computed on
     the device, so nothing but counters and the miss list crosses PCIe), counts and miss list exactly, and every tenth
-    step byte for byte."""
+    step byte for byte.  The cache tier keeps K and V of a block side by side, as bench.py's default run does."""
     L, steps = 32, 200
     say(f"config 2 at real shapes, {L} layers materialised, {steps} steps")
     wl = W.kv_decode(seed=0, n_layers=L, n_steps=steps)
     assert int(sum(len(t) for t in wl.tables)) > 12000 and wl.shape.chunk_bytes == 32768
-    eo, eh = P.make_engines(wl)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(cache_planes_adjacent=True))
     eo.threads = 8
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)

@@ -20,12 +20,16 @@ def say(msg):
 
 # ---- config 1: tiny KV fetch, scatter back, round trip ------------------------------------------------------
 
+LAYOUTS = pytest.mark.parametrize("adjacent", [False, True], ids=["k-pool-and-v-pool", "k-v-adjacent"])
+
+
+@LAYOUTS
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("fill", [W.FILL_NORMAL, W.FILL_TAG])
-def test_config1_tiny_kv_fetch_and_round_trip(fill, general):
+def test_config1_tiny_kv_fetch_and_round_trip(fill, general, adjacent):
     say(f"config1 fill={fill}")
     wl = W.kv_tiny(0, fill_mode=fill)
-    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=adjacent))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         assert np.array_equal(ro.place_status, rh.place_status) and (rh.place_status == 0).all()
@@ -86,11 +90,12 @@ def test_fetch_is_the_same_for_every_residency(p_cache, general):
 
 # ---- config 2, small: decode steps with append, write-back, demotion, placement -------------------------------
 
+@LAYOUTS
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
-def test_kv_decode_steps_small(general):
+def test_kv_decode_steps_small(general, adjacent):
     say("kv decode small")
     wl = W.kv_decode(seed=2, n_layers=3, n_seq=4, min_len=500, max_len=2000, n_steps=40)
-    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=adjacent))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(40):
@@ -161,14 +166,17 @@ def test_block_table_large_enough_for_the_grouped_compaction():
 
 @pytest.mark.parametrize("heads,dim,tokens,elt", [(1, 8, 1, 2), (3, 8, 16, 2), (8, 129 - 1, 16, 2), (8, 136, 16, 2),
                                                   (5, 200, 48, 2), (8, 128, 16, 1), (8, 128, 16, 4), (2, 80, 16, 1)])
-@pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
-def test_ragged_chunk_sizes(heads, dim, tokens, elt, general):
-    """Block sizes off the 4 KiB / 32 KiB tiles, and the element sizes of fp8, fp16 / bf16 and fp32 KV caches."""
+@pytest.mark.parametrize("general,threads,adjacent", [(False, 0, False), (True, 0, False), (True, 0, True), (True, 128, True),
+                                                      (True, 256, False)],
+                         ids=["one-kernel", "general", "general-adjacent", "general-128-threads-adjacent", "general-256-threads"])
+def test_ragged_chunk_sizes(heads, dim, tokens, elt, general, threads, adjacent):
+    """Block sizes off the 1 KiB / 4 KiB / 32 KiB tiles, and the element sizes of fp8, fp16 / bf16 and fp32 KV caches; the
+    gather with one, two and four wavefronts per workgroup, plane after plane and both planes of a request in one pass."""
     shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=elt)
     say(f"ragged chunk {shape.chunk_bytes} bytes")
     wl = W.kv_decode(seed=4, n_seq=3, min_len=20 * tokens, max_len=60 * tokens, n_steps=2 * tokens, shape=shape,
                      fill_mode=W.FILL_TAG)
-    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general))
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=general, gather_threads=threads, cache_planes_adjacent=adjacent))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(2 * tokens):
@@ -347,7 +355,9 @@ def test_revocation_stress_two_streams(overlap_revoke, general):
     wl = W.kv_decode(seed=8, n_layers=2, n_seq=3, min_len=400, max_len=1200, n_steps=N_STRESS)
     sh = W.ExpertShape(n_layers=2, n_experts=16, d_model=64, d_ff=100)
     ex = W.expert_offload(seed=8, shape=sh, n_tokens=64)
-    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True, hip_kwargs=dict(general_fetch=general))
+    # (the runs with overlapping revocations also keep K and V of a block side by side in the cache tier)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True,
+                            hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=overlap_revoke))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
