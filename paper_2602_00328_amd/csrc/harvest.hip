@@ -610,6 +610,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
     const bool profile = ctx->profile && !ss->fixed && !is_capturing(ss->s);
     const bool host_tier = c.cfg.n_host_slots != 0;
     // one pass over both planes of each request where the cache tier keeps them side by side (see gather)
+    // (not the head-major gather: its stores are 4 KiB strips, and with two planes' strips interleaved it was measured to
+    // lose - 5.60 against 5.98 TB/s alone)
     const bool fold = !hm && c.cache_planes_adjacent() && !ctx->gather_grid;
     // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
     // sized from what the previous gather of this class on this stream reported, never below a floor that still fills the
@@ -682,12 +684,12 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
         const Rec *recs = (const Rec *)lists.hbm;
         const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HBM_REQ);
         if (hm) {
+            auto kernel = fold ? gather_hm<1, true, true> : gather_hm<1, true, false>;
+            const dim3 g = fold ? dim3(grid_for(want * planes, MAX_GRID)) : dim3(grid, planes);
             if (pa)
-                hipExtLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req,
-                                      ga, *hm, ss->d_feedback + cls);
+                hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req, ga, *hm, ss->d_feedback + cls);
             else
-                hipLaunchKernelGGL((gather_hm<1, true>), dim3(grid, planes), dim3(WG), 0, s_hbm, recs, n_req, ga, *hm,
-                                   ss->d_feedback + cls);
+                hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_hbm, recs, n_req, ga, *hm, ss->d_feedback + cls);
         } else {
             const uint32_t nthr = ctx->gather_threads;
             auto kernel = fold ? (nthr == 64 ? gather<64, true, true> : (nthr == 128 ? gather<128, true, true> : gather<256, true, true>))

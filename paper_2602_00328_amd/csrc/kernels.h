@@ -626,23 +626,27 @@ struct HmArgs {
     uint32_t pad;
 };
 
-template <int UNROLL, bool NT>
+template <int UNROLL, bool NT, bool FOLD>
 __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
                                                 GatherArgs a, HmArgs h, uint32_t *feedback)
 {
+    // FOLD: both planes of a request in one pass, as in gather
     constexpr uint32_t UNITS = WG * UNROLL;
     uint32_t tpc = a.tiles_per_chunk;
+    uint32_t tpr = FOLD ? tpc * a.n_planes : tpc;
     uint64_t t = blockIdx.x;
-    uint32_t idx = (uint32_t)t / tpc;
+    uint32_t idx = (uint32_t)t / tpr;
     Rec x = recs[idx];                                   // speculative, as in gather
     uint32_t n_req = *n_req_ptr;
-    uint32_t plane = blockIdx.y;
-    if (feedback && blockIdx.x == 0 && plane == 0 && threadIdx.x == 0) *feedback = n_req;
-    uint64_t n_tiles = (uint64_t)n_req * tpc;
-    uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
+    if (feedback && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *feedback = n_req;
+    uint64_t n_tiles = (uint64_t)n_req * tpr;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     while (t < n_tiles) {
-        uint32_t u0 = ((uint32_t)t - idx * tpc) * UNITS + threadIdx.x;
+        uint32_t k = (uint32_t)t - idx * tpr;
+        uint32_t plane = FOLD ? (k >= tpc ? 1u : 0u) : blockIdx.y;
+        if (FOLD) k -= plane * tpc;
+        uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
+        uint32_t u0 = k * UNITS + threadIdx.x;
         uint64_t cap = x.src >> 48;
         uint64_t src = src_base_of(a, (uint32_t)(x.src & 3), plane) + (x.src & 0x0000FFFFFFFFFFFCull);
         uint64_t dst = dst_plane + x.dst;
@@ -654,7 +658,7 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
             s_unit = (tok * h.n_heads + head) * h.upr + col;
             d_off = head * head_stride + (uint64_t)rem * 16;
         };
-        uint32_t tile_first = ((uint32_t)t - idx * tpc) * UNITS;
+        uint32_t tile_first = k * UNITS;
         if (tile_first + UNITS <= chunk_units) {
             // whole tile: no per-element branches, so all loads are in flight before the first store
             u32x4 v[UNROLL];
@@ -677,7 +681,7 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
         }
         t += gridDim.x;
         if (t >= n_tiles) break;
-        idx = (uint32_t)t / tpc;
+        idx = (uint32_t)t / tpr;
         x = recs[idx];
     }
 }
