@@ -220,9 +220,10 @@ int harvest_lookup(harvest_ctx *ctx, int cls, harvest_obj id, int *tier, int64_t
 
 /* Placement = the paper's harvest_alloc + explicit migration + placement-map update (Sections 3.2, 4.3): for each
  * id on the host, take the lowest free cache slot, copy host copy -> slot on `stream`, then publish
- * (CACHE, slot, gen+1).  per_obj_status[i] (may be NULL): OK (also for objects already in HBM: no-op), ENOSPC (cache
- * pool full - object stays on the host), ELOST, EINVAL (lossy object).  The call fails as a whole, changing
- * nothing, only for unknown ids (ENOENT). */
+ * (CACHE, slot, gen+1).  per_obj_status[i] (may be NULL, written on success only): OK (also for objects already in HBM:
+ * no-op), ENOSPC (cache pool full - object stays on the host), ELOST, EINVAL (lossy object).  The call fails as a
+ * whole, changing nothing, for unknown ids (ENOENT) and when a HIP call fails before the new entries are enqueued
+ * (EHIP: slots, directory and statistics are as before). */
 int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *per_obj_status);
 
 /* Placement from a copy the application already holds in device memory (Section 3.2: the allocation only allocates
@@ -243,7 +244,12 @@ int harvest_place_from(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
 /* Revocation (Section 3.2: an explicit call whose steps come in a fixed order): for each id in the cache tier: publish (HOST, gen+1) - or
  * (NONE) for a lossy object -, wait until every fetch / evict / place enqueued so far on any stream this context
  * has seen has completed (the drain), free the slot (poison it if asked), then invoke the callback.  Ids not in the
- * cache tier are skipped.  Synchronous; ENOENT for unknown ids (nothing changed). */
+ * cache tier are skipped.  Synchronous; ENOENT for unknown ids (nothing changed).
+ * The context is locked while the directory changes and while work is enqueued, not while the host waits for the
+ * drain: other threads may meanwhile call anything on their own streams.  They see the revoked objects on the host
+ * already, and the slots being revoked are handed to nobody before the wait has ended.  EHIP before the new entries
+ * were enqueued: nothing changed; EHIP afterwards (the wait itself failed): the objects are on the host and their
+ * slots stay out of use. */
 int harvest_revoke(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n);
 
 /* ---- fetch (Sections 4.3, 5.2) ---------------------------------------------------------------------------- */
@@ -372,7 +378,13 @@ int harvest_fetch_info_of(harvest_ctx *ctx, void *stream, int cls, harvest_fetch
  * copy is done; the source may be the local pool itself.  A lossy local object (no host slot; Section 5.2: KV state
  * need not be duplicated in a lower tier) moves into the lowest free cache slot instead -> (CACHE, slot, gen+1);
  * ENOSPC, with nothing changed, if the cache tier cannot take every lossy object of the call.  EINVAL: repeated id,
- * src_block out of range; ENOENT; ELOST (the object was revoked).  On error nothing is enqueued or changed. */
+ * src_block out of range; ENOENT; ELOST (the object was revoked).  On error nothing is changed (EHIP included, as long as
+ * the call had not yet enqueued its last step).
+ * A demoted object's local slot is free the moment the call returns, and the next harvest_register / harvest_restore may
+ * hand it out.  Fetches enqueued through this library afterwards see the new entry; a fetch of the same object that is
+ * still queued on ANOTHER stream must have been ordered before this call by the caller (as for every operation on one
+ * object from two streams), or it may read the slot after its new owner has written it.  While the context has fetches
+ * recorded into graphs, a call that demotes waits until the new entries are on the device before it returns. */
 int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, uint32_t n, const void *d_src0,
                   const void *d_src1, const uint64_t *src_block, uint64_t src_layer_stride, int flags, void *stream);
 

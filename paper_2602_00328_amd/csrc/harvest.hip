@@ -17,6 +17,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <functional>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -34,6 +35,32 @@ using namespace hv;
                     __LINE__);                                                                          \
             return HARVEST_EHIP;                                                                        \
         }                                                                                               \
+    } while (0)
+
+// Failure injection for the CPU tests of the error paths (built only with -DHARVEST_FAULT_INJECTION, never into the
+// product library): harvest_test_fail_at(n) makes the n-th device step from now fail as a HIP error would.  "Device
+// step" = every place in place / evict / revoke where a HIP call can fail; a context without a device walks the same
+// steps without making the calls, so the roll-back code runs on a CPU.
+#ifdef HARVEST_FAULT_INJECTION
+#include <atomic>
+static std::atomic<int> g_fail_at{ 0 };
+extern "C" void harvest_test_fail_at(int nth) { g_fail_at = nth; }
+static inline bool fault_due()
+{
+    int v = g_fail_at.load();
+    if (v <= 0) return false;
+    g_fail_at = v - 1;
+    return v == 1;
+}
+#else
+static inline constexpr bool fault_due() { return false; }
+#endif
+
+// A device step of a call that has a roll-back: fails when the injected fault is due, is skipped without a device.
+#define DEV_TRY(expr)                                  \
+    do {                                               \
+        if (fault_due()) return HARVEST_EHIP;          \
+        if (!ctx->no_device) HIP_TRY(expr);            \
     } while (0)
 
 namespace {
@@ -172,7 +199,29 @@ struct Staging {
     void *h = nullptr;
     size_t cap = 0;
     hipEvent_t done = nullptr;
-    bool busy = false;
+    bool busy = false;      // the device may still read it: free again once `done` has passed
+    bool held = false;      // a call has taken it and not yet handed it to the device (or given it back)
+};
+
+// What a call has changed in the host mirror so far, undone in reverse order unless the call commits: the calls that edit
+// the directory change the mirror first and the device afterwards, and a device step that fails in between must leave
+// no trace ("on error nothing is enqueued or changed").
+struct Undo {
+    std::vector<std::function<void()>> steps;
+    bool armed = true;
+    void add(std::function<void()> f) { steps.push_back(std::move(f)); }
+    void commit() { armed = false; }
+    ~Undo()
+    {
+        if (armed)
+            for (auto it = steps.rbegin(); it != steps.rend(); ++it) (*it)();
+    }
+};
+
+// Gives a staging block back if the call ends before the device got it.
+struct Hold {
+    Staging *st = nullptr;
+    ~Hold() { if (st && st->held) st->held = false; }
 };
 
 struct ProfPair { hipEvent_t a, b; int which; };
@@ -297,6 +346,7 @@ struct harvest_ctx {
     std::deque<Staging> staging;          // deque: references stay valid when it grows
     std::vector<ProfPair> prof;
     std::vector<hipEvent_t> prof_pool;
+    std::vector<hipEvent_t> evt_pool;     // events (no timing) of finished revocations, for the next ones
     bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
     SegAlloc shared;                      // free space of cfg.d_shared_cache
     std::vector<harvest_prefetcher *> prefetchers;   // live ones: destroyed with the context if the caller did not
@@ -438,9 +488,10 @@ int ensure_req_cap(StreamState *ss, int cls, uint32_t n_req)
     return HARVEST_OK;
 }
 
-int ensure_ctl_cap(StreamState *ss, size_t bytes)
+int ensure_ctl_cap(harvest_ctx *ctx, StreamState *ss, size_t bytes)
 {
-    if (bytes <= ss->ctl_cap) return HARVEST_OK;
+    if (fault_due()) return HARVEST_EHIP;
+    if (ctx->no_device || bytes <= ss->ctl_cap) return HARVEST_OK;
     HIP_TRY(hipStreamSynchronize(ss->s));
     if (ss->ctl_buf) HIP_TRY(hipFree(ss->ctl_buf));
     ss->ctl_buf = nullptr; ss->ctl_cap = 0;
@@ -453,30 +504,42 @@ int ensure_ctl_cap(StreamState *ss, size_t bytes)
 // A pinned block nobody on the device still reads.
 int acquire_staging(harvest_ctx *ctx, size_t bytes, Staging **out)
 {
+    *out = nullptr;
+    if (fault_due()) return HARVEST_EHIP;
+    if (ctx->no_device) return HARVEST_OK;
     for (auto &st : ctx->staging) {
-        if (st.cap < bytes) continue;
+        if (st.cap < bytes || st.held) continue;
         if (st.busy) {
             hipError_t q = hipEventQuery(st.done);
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) return HARVEST_EHIP;
             st.busy = false;
         }
+        st.held = true;
         *out = &st;
         return HARVEST_OK;
     }
     Staging st;
     st.cap = std::max<size_t>(1 << 16, bytes);
     HIP_TRY(hipHostMalloc(&st.h, st.cap, hipHostMallocDefault));
-    HIP_TRY(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
+    if (hipEventCreateWithFlags(&st.done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(st.h);
+        return HARVEST_EHIP;
+    }
+    st.held = true;
     ctx->staging.push_back(st);
     *out = &ctx->staging.back();
     return HARVEST_OK;
 }
 
-int release_after(Staging *st, hipStream_t s)
+// The device reads the block in work enqueued on `s` so far: it is free again when that work has passed.
+int release_after(harvest_ctx *ctx, Staging *st, hipStream_t s)
 {
+    if (fault_due()) return HARVEST_EHIP;
+    if (ctx->no_device || !st) return HARVEST_OK;
     HIP_TRY(hipEventRecord(st->done, s));
     st->busy = true;
+    st->held = false;
     return HARVEST_OK;
 }
 
@@ -527,30 +590,42 @@ ClassDev class_dev(const ClassState &c)
 
 // Publishes the mirror entries of `ids` to the device directory with a dir_write kernel on stream `on`, ordered after
 // everything enqueued on `on` so far (for a placement: the copy that makes the new entry true) and after every earlier
-// directory edit, wherever that ran.
-int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipStream_t on)
+// directory edit, wherever that ran.  pre: a staging block of n * 12 bytes taken earlier, so that this step cannot fail
+// for want of one.  *committed (if given) says whether the dir_write was enqueued: from then on the device will apply
+// the edit, and a failure reported by a later step no longer entitles the caller to roll its mirror back.
+int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipStream_t on, Staging *pre = nullptr,
+            bool *committed = nullptr)
 {
-    if (ctx->no_device || ids.empty()) return HARVEST_OK;
+    if (committed) *committed = ids.empty();
+    if (ids.empty()) return HARVEST_OK;
     size_t n = ids.size();
     size_t bytes = n * (sizeof(uint64_t) + sizeof(uint32_t));
-    Staging *st;
-    int rc = acquire_staging(ctx, bytes, &st);
-    if (rc) return rc;
-    uint64_t *ent = (uint64_t *)st->h;
-    uint32_t *idv = (uint32_t *)(ent + n);
-    for (size_t i = 0; i < n; ++i) { ent[i] = c.packed(ids[i]); idv[i] = ids[i]; }
-    if (ctx->edit_seq && ctx->edit_stream != on) HIP_TRY(hipStreamWaitEvent(on, ctx->edit_evt, 0));
+    Hold hold;
+    Staging *st = pre;
+    if (!st) {
+        int rc = acquire_staging(ctx, bytes, &st);
+        if (rc) return rc;
+        hold.st = st;
+    }
+    if (ctx->edit_seq && ctx->edit_stream != on) DEV_TRY(hipStreamWaitEvent(on, ctx->edit_evt, 0));
     void *d_st = nullptr;
-    HIP_TRY(hipHostGetDevicePointer(&d_st, st->h, 0));
-    uint64_t *d_ent = (uint64_t *)d_st;
-    uint32_t *d_ids = (uint32_t *)(d_ent + n);
-    hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, on, c.d_dir, d_ids, d_ent,
-                       (uint32_t)n);
-    HIP_TRY(hipGetLastError());
+    DEV_TRY(hipHostGetDevicePointer(&d_st, st->h, 0));
+    if (!ctx->no_device) {
+        uint64_t *ent = (uint64_t *)st->h;
+        uint32_t *idv = (uint32_t *)(ent + n);
+        for (size_t i = 0; i < n; ++i) { ent[i] = c.packed(ids[i]); idv[i] = ids[i]; }
+        uint64_t *d_ent = (uint64_t *)d_st;
+        uint32_t *d_ids = (uint32_t *)(d_ent + n);
+        hipLaunchKernelGGL(dir_write, dim3((uint32_t)((n + WG - 1) / WG)), dim3(WG), 0, on, c.d_dir, d_ids, d_ent,
+                           (uint32_t)n);
+    }
+    DEV_TRY(hipGetLastError());
+    if (committed) *committed = true;
     ctx->edit_seq++;
     ctx->edit_stream = on;
+    if (ctx->no_device) return HARVEST_OK;
     HIP_TRY(hipEventRecord(ctx->edit_evt, on));
-    return release_after(st, on);
+    return release_after(ctx, st, on);
 }
 
 // Orders the caller's stream after every directory edit made so far, so that a fetch enqueued after register / place /
@@ -910,6 +985,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto &st : ctx->staging) { (void)hipEventDestroy(st.done); (void)hipHostFree(st.h); }
         for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
+        for (auto e : ctx->evt_pool) (void)hipEventDestroy(e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
         if (ctx->edit_evt) (void)hipEventDestroy(ctx->edit_evt);
@@ -1021,56 +1097,84 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
         if ((from->plane[0] | from->plane[1]) & 15) return HARVEST_EINVAL;
     }
     if ((rc = device_guard(ctx))) return rc;
-    // directory edits go through the control stream and pinned staging: they cannot be recorded into a graph
+    // directory edits go through pinned staging: they cannot be recorded into a graph
     if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;
-    StreamState *ss = nullptr;                     // before the mirror changes: a failure here leaves nothing half done
+    // Everything the call may have to create or allocate comes first - the stream's state, room for the copy list on the
+    // device, the two staging blocks - so that nothing has changed yet when one of them fails; what can still fail
+    // afterwards (enqueueing on a broken stream) is undone below.
+    StreamState *ss = nullptr;
     if (!ctx->no_device && (rc = get_stream(ctx, stream, &ss))) return rc;
+    hipStream_t s = ss ? ss->s : nullptr;
+    const size_t max_items = (size_t)n * c.cfg.n_planes * c.cfg.n_layers;
+    Hold h_items, h_dir;
+    if (n) {
+        if ((rc = ensure_ctl_cap(ctx, ss, max_items * sizeof(Item)))) return rc;
+        if ((rc = acquire_staging(ctx, max_items * sizeof(Item), &h_items.st))) return rc;
+        if ((rc = acquire_staging(ctx, (size_t)n * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
+    }
+    Undo undo;
     std::vector<uint32_t> moved;
     std::vector<Item> items;
+    std::vector<int> st_all(n, HARVEST_OK);
     for (uint32_t i = 0; i < n; ++i) {
         uint32_t id = ids[i];
         int st = HARVEST_OK;
         if (c.tier[id] == T_NONE) st = HARVEST_ELOST;
         else if (c.tier[id] != T_HOST) st = HARVEST_OK;
         else if (c.host_slot[id] < 0) st = HARVEST_EINVAL;
-        else if (int64_t s = c.cache_take(); s < 0) { st = HARVEST_ENOSPC; c.n_enospc++; }
-        else {
+        else if (int64_t slot = c.cache_take(); slot < 0) {
+            st = HARVEST_ENOSPC;
+            c.n_enospc++;
+            undo.add([&c] { c.n_enospc--; });
+        } else {
             for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
                 for (uint32_t l = 0; l < c.cfg.n_layers; ++l) {
                     uint64_t src = from ? from->plane[p] + ((uint64_t)l * from->stride + from->block[i]) * c.cfg.chunk_bytes
                                         : c.addr(T_HOST, p, l, (uint64_t)c.host_slot[id]);
-                    items.push_back({ src, c.addr(T_CACHE, p, l, (uint64_t)s) });
+                    items.push_back({ src, c.addr(T_CACHE, p, l, (uint64_t)slot) });
                 }
-            c.tier[id] = T_CACHE; c.slot[id] = s; c.gen[id] += 1;
+            const uint32_t old_gen = c.gen[id];
+            c.tier[id] = T_CACHE; c.slot[id] = slot; c.gen[id] += 1;
             c.n_placed++;
+            undo.add([&c, id, slot, old_gen] {
+                c.cache_release(slot);
+                c.tier[id] = T_HOST; c.slot[id] = -1; c.gen[id] = old_gen;
+                c.n_placed--;
+            });
             moved.push_back(id);
         }
-        if (status) status[i] = st;
+        st_all[i] = st;
     }
-    if (ctx->no_device || moved.empty()) return HARVEST_OK;
-    size_t bytes = items.size() * sizeof(Item);
-    if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
-    Staging *st;
-    if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
-    memcpy(st->h, items.data(), bytes);
-    HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
-    if ((rc = release_after(st, ss->s))) return rc;
-    const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
-    if (from && tiles_hbm < (1ull << 32)) {        // HBM to HBM: a workgroup per 1 KiB tile, as in the gather
-        hipLaunchKernelGGL(copy_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ss->s,
-                           (const Item *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
-                           tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
-    } else {                                       // over PCIe: a few dozen persistent workgroups
-        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-        uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);
-        hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, ss->s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
-                           c.cfg.chunk_bytes, tpc);
+    if (!moved.empty()) {
+        size_t bytes = items.size() * sizeof(Item);
+        if (!ctx->no_device) memcpy(h_items.st->h, items.data(), bytes);
+        DEV_TRY(hipMemcpyAsync(ss->ctl_buf, h_items.st->h, bytes, hipMemcpyHostToDevice, s));
+        if ((rc = release_after(ctx, h_items.st, s))) return rc;
+        if (!ctx->no_device) {
+            const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+            if (from && tiles_hbm < (1ull << 32)) {        // HBM to HBM: a workgroup per 1 KiB tile, as in the gather
+                hipLaunchKernelGGL(copy_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, s,
+                                   (const Item *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                                   tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
+            } else {                                       // over PCIe: a few dozen persistent workgroups
+                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+                uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);
+                hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
+                                   c.cfg.chunk_bytes, tpc);
+            }
+        }
+        DEV_TRY(hipGetLastError());
+        // the new entries are written on the same stream, behind the copy: visible only once the bytes are in the slot,
+        // and before anything enqueued on `stream` later
+        bool committed = false;
+        rc = publish(ctx, c, moved, s, h_dir.st, &committed);
+        if (committed) undo.commit();
+        if (rc) return rc;
+        if (!ctx->no_device && (rc = mark_last(ctx, ss))) return rc;
     }
-    HIP_TRY(hipGetLastError());
-    // the new entries are written on the same stream, behind the copy: visible only once the bytes are in the slot,
-    // and before anything enqueued on `stream` later
-    if ((rc = publish(ctx, c, moved, ss->s))) return rc;
-    return mark_last(ctx, ss);
+    undo.commit();
+    if (status) memcpy(status, st_all.data(), n * sizeof(int));
+    return HARVEST_OK;
 }
 
 int harvest_place(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, void *stream, int *status)
@@ -1086,6 +1190,35 @@ int harvest_place_from(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     return place_impl(ctx, cls, ids, n, &from, stream, status);
 }
 
+// Enqueues the poisoning of the given cache slots on the control stream (the list travels through `st`).
+static int enqueue_poison(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &slots, Staging *st)
+{
+    std::vector<Item> items;
+    for (uint32_t s : slots)
+        for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
+            for (uint32_t l = 0; l < c.cfg.n_layers; ++l) items.push_back({ 0, c.addr(T_CACHE, p, l, s) });
+    memcpy(st->h, items.data(), items.size() * sizeof(Item));
+    void *d_items = nullptr;
+    HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
+    const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+    if (tiles_hbm < (1ull << 32)) {
+        hipLaunchKernelGGL(fill_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ctx->ctl,
+                           (const Item *)d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                           tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16), 0xA5A5A5A5u);
+    } else {
+        uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+        uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
+        hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items, (uint32_t)items.size(),
+                           c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
+    }
+    HIP_TRY(hipGetLastError());
+    return release_after(ctx, st, ctx->ctl);
+}
+
+// Revocation (paper Section 3.2).  The context's lock is held while the directory changes and while work is enqueued, and
+// released while the host waits for the drain: the thread that drives another stream keeps enqueuing meanwhile.  What
+// keeps that safe: the revoked objects already read HOST (mirror and, in stream order, device), so nothing new is pointed
+// at their slots, and the slots return to the allocator only after the wait, so nobody else is given them.
 static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, bool notify)
 {
     int rc = check_class(ctx, cls);
@@ -1094,9 +1227,12 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     std::vector<uint32_t> hit;
     std::vector<uint32_t> old_slot;
     std::vector<std::pair<harvest_revoke_cb, void *>> cbs;
+    ClassState &c = ctx->cls[cls];
+    hipEvent_t drained = nullptr;
+    bool whole_device = false;
+    Staging *st_fill = nullptr;
     {
         std::lock_guard<std::mutex> lk(ctx->mu);
-        ClassState &c = ctx->cls[cls];
         for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
         if ((rc = device_guard(ctx))) return rc;
         // the drain waits for streams: impossible while one of them is being recorded into a graph
@@ -1106,55 +1242,88 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             for (int i = 0; i < ctx->n_fixed_streams; ++i)
                 if (is_capturing(ctx->fixed_streams[i].s)) return HARVEST_EINVAL;
         }
+        size_t n_hit = 0;
+        c.new_call();
+        for (uint32_t i = 0; i < n; ++i) n_hit += c.tier[ids[i]] == T_CACHE && c.first_time(ids[i]);
+        if (n_hit == 0) return HARVEST_OK;
+        // what the call may have to allocate comes before any change: staging for the new entries and for the poison
+        // list, the event the host will wait on
+        Hold h_dir, h_fill;
+        if ((rc = acquire_staging(ctx, n_hit * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
+        if (ctx->poison &&
+            (rc = acquire_staging(ctx, n_hit * c.cfg.n_planes * c.cfg.n_layers * sizeof(Item), &h_fill.st)))
+            return rc;
+        if (fault_due()) return HARVEST_EHIP;
+        if (!ctx->no_device) {
+            if (!ctx->evt_pool.empty()) { drained = ctx->evt_pool.back(); ctx->evt_pool.pop_back(); }
+            else HIP_TRY(hipEventCreateWithFlags(&drained, hipEventDisableTiming));
+        }
+        struct PutBack {                       // the event goes back to the pool on every early return
+            harvest_ctx *ctx; hipEvent_t e; bool armed;
+            ~PutBack() { if (armed && e) ctx->evt_pool.push_back(e); }
+        } put_back{ ctx, drained, true };
         // 1. invalidate
+        Undo undo;
         for (uint32_t i = 0; i < n; ++i) {
             uint32_t id = ids[i];
             if (c.tier[id] != T_CACHE) continue;
+            const uint32_t slot = (uint32_t)c.slot[id], old_gen = c.gen[id];
             hit.push_back(id);
-            old_slot.push_back((uint32_t)c.slot[id]);
+            old_slot.push_back(slot);
             c.tier[id] = c.host_slot[id] >= 0 ? T_HOST : T_NONE;
             c.slot[id] = -1;
             c.gen[id] += 1;
             c.n_revoked++;
+            undo.add([&c, id, slot, old_gen] { c.tier[id] = T_CACHE; c.slot[id] = slot; c.gen[id] = old_gen; c.n_revoked--; });
             cbs.push_back({ c.cb[id], c.cb_user[id] });
         }
-        if (hit.empty()) return HARVEST_OK;
+        bool committed = false;
+        rc = publish(ctx, c, hit, ctx->ctl, h_dir.st, &committed);
+        if (committed) undo.commit();
+        if (rc) return rc;
         if (!ctx->no_device) {
-            if ((rc = publish(ctx, c, hit, ctx->ctl))) return rc;
-            HIP_TRY(hipStreamSynchronize(ctx->ctl));
-            // 2. drain: everything enqueued so far that could still read the slots
-            if (ctx->captured_work) HIP_TRY(hipDeviceSynchronize());
+            // 2. the drain: the control stream waits for everything the library has enqueued so far on every stream that
+            // could still read the slots (each stream's latest work is an event; the waits take the events as they are
+            // now, later calls on those streams do not move them), then poisons the slots - in stream order, so after the
+            // drain - and records the event the host waits on.  Work recorded into graphs is invisible to those events:
+            // then the host waits for the whole device, and the poisoning comes after that wait.
             for (auto &kv : ctx->streams)
-                if (kv.second->last_valid) HIP_TRY(hipEventSynchronize(kv.second->last));
+                if (kv.second->last_valid) HIP_TRY(hipStreamWaitEvent(ctx->ctl, kv.second->last, 0));
             for (int i = 0; i < ctx->n_fixed_streams; ++i)
-                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipEventSynchronize(ctx->fixed_streams[i].last));
-            // 3. (poison and) free
-            if (ctx->poison) {
-                std::vector<Item> items;
-                for (uint32_t s : old_slot)
-                    for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
-                        for (uint32_t l = 0; l < c.cfg.n_layers; ++l) items.push_back({ 0, c.addr(T_CACHE, p, l, s) });
-                size_t bytes = items.size() * sizeof(Item);
-                Staging *st;
-                if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
-                memcpy(st->h, items.data(), bytes);
-                void *d_items = nullptr;
-                HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
-                const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
-                if (tiles_hbm < (1ull << 32)) {
-                    hipLaunchKernelGGL(fill_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ctx->ctl,
-                                       (const Item *)d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
-                                       tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16), 0xA5A5A5A5u);
-                } else {
-                    uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-                    uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
-                    hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items,
-                                       (uint32_t)items.size(), c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
-                }
-                HIP_TRY(hipGetLastError());
-                HIP_TRY(hipStreamSynchronize(ctx->ctl));
+                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipStreamWaitEvent(ctx->ctl, ctx->fixed_streams[i].last, 0));
+            whole_device = ctx->captured_work;
+            if (ctx->poison && !whole_device) {
+                if ((rc = enqueue_poison(ctx, c, old_slot, h_fill.st))) return rc;
+            } else if (ctx->poison) {
+                st_fill = h_fill.st;               // stays held until the second phase
+                h_fill.st = nullptr;
             }
+            HIP_TRY(hipEventRecord(drained, ctx->ctl));
         }
+        put_back.armed = false;                    // from here on the event is returned by hand, after the wait
+    }
+    if (!ctx->no_device) {
+        hipError_t e = whole_device ? hipDeviceSynchronize() : hipSuccess;
+        if (e == hipSuccess) e = hipEventSynchronize(drained);
+        std::unique_lock<std::mutex> lk(ctx->mu);
+        ctx->evt_pool.push_back(drained);
+        if (e != hipSuccess) {                     // the slots stay out of the allocator: nobody may be given them
+            if (st_fill) st_fill->held = false;
+            fprintf(stderr, "libharvest: the revocation drain failed: %s\n", hipGetErrorString(e));
+            return HARVEST_EHIP;
+        }
+        if (st_fill) {                             // recorded work: poison now, after the wait for the whole device
+            rc = enqueue_poison(ctx, c, old_slot, st_fill);
+            if (st_fill->held) st_fill->held = false;
+            if (rc) return rc;
+            lk.unlock();
+            HIP_TRY(hipStreamSynchronize(ctx->ctl));
+            lk.lock();
+        }
+        // 3. free
+        for (uint32_t s : old_slot) c.cache_release(s);
+    } else {
+        std::lock_guard<std::mutex> lk(ctx->mu);
         for (uint32_t s : old_slot) c.cache_release(s);
     }
     // 4. notify (outside the lock: a callback may call back into the library)
@@ -1597,6 +1766,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     if (layer >= (int)c.cfg.n_layers) return HARVEST_EINVAL;
     bool demote_flag = flags & HARVEST_EVICT_DEMOTE;
     if (demote_flag && layer >= 0 && c.cfg.n_layers != 1) return HARVEST_EINVAL;
+    size_t n_demote = 0;
     {
         c.new_call();
         size_t need_cache = 0;
@@ -1604,6 +1774,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
             if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
             if (src_block[i] >= src_layer_stride) return HARVEST_EINVAL;
             if (c.tier[ids[i]] == T_NONE) return HARVEST_ELOST;
+            if (demote_flag && c.tier[ids[i]] == T_LOCAL) n_demote++;
             if (demote_flag && c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) need_cache++;
             if (!c.first_time(ids[i])) return HARVEST_EINVAL;
         }
@@ -1616,24 +1787,30 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     }
     if ((rc = device_guard(ctx))) return rc;
     if (!ctx->no_device && is_capturing((hipStream_t)stream)) return HARVEST_EINVAL;     // as for harvest_place
+    // as in harvest_place: what may have to be created or allocated comes before any change
     StreamState *ss = nullptr;
     if (!ctx->no_device && (rc = get_stream(ctx, stream, &ss))) return rc;
+    hipStream_t s = ss ? ss->s : nullptr;
+    const uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
+    const size_t max_items = (size_t)n * c.cfg.n_planes * (l1 - l0);
+    Hold h_items, h_dir;
+    if ((rc = ensure_ctl_cap(ctx, ss, max_items * sizeof(Item2)))) return rc;
+    if ((rc = acquire_staging(ctx, max_items * sizeof(Item2), &h_items.st))) return rc;
+    if (n_demote && (rc = acquire_staging(ctx, n_demote * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
     const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
-    uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     std::vector<Item2> items;
-    items.reserve((size_t)n * c.cfg.n_planes * (l1 - l0));
+    items.reserve(max_items);
     std::vector<uint32_t> demoted;
+    Undo undo;
     // room for every lossy object that leaves local HBM, taken in request order before anything changes: all or nothing
     std::vector<int64_t> room;
     if (demote_flag)
         for (uint32_t i = 0; i < n; ++i)
             if (c.tier[ids[i]] == T_LOCAL && c.host_slot[ids[i]] < 0) {
-                int64_t s = c.cache_take();
-                if (s < 0) {
-                    while (!room.empty()) { c.cache_release(room.back()); room.pop_back(); }
-                    return HARVEST_ENOSPC;
-                }
-                room.push_back(s);
+                int64_t slot = c.cache_take();
+                if (slot < 0) return HARVEST_ENOSPC;           // (the slots taken so far go back: undo)
+                room.push_back(slot);
+                undo.add([&c, slot] { c.cache_release(slot); });
             }
     size_t n_room = 0;
     for (uint32_t i = 0; i < n; ++i) {
@@ -1656,43 +1833,57 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
                 if (it.dst0 || it.dst1) items.push_back(it);
             }
         c.n_evicted++;
+        undo.add([&c] { c.n_evicted--; });
         if (demote) {
-            c.local_free.insert((uint32_t)c.slot[id]);
+            const int64_t old_slot = c.slot[id];
+            const uint32_t old_gen = c.gen[id];
+            c.local_free.insert((uint32_t)old_slot);
             if (to_cache >= 0) { c.tier[id] = T_CACHE; c.slot[id] = to_cache; }
             else { c.tier[id] = T_HOST; c.slot[id] = -1; }
             c.gen[id] += 1;
             c.n_demoted++;
+            undo.add([&c, id, old_slot, old_gen] {
+                c.local_free.erase((uint32_t)old_slot);
+                c.tier[id] = T_LOCAL; c.slot[id] = old_slot; c.gen[id] = old_gen;
+                c.n_demoted--;
+            });
             demoted.push_back(id);
         }
     }
-    if (ctx->no_device) return HARVEST_OK;
     if (!items.empty()) {
         size_t bytes = items.size() * sizeof(Item2);
-        if ((rc = ensure_ctl_cap(ss, bytes))) return rc;
-        Staging *st;
-        if ((rc = acquire_staging(ctx, bytes, &st))) return rc;
-        memcpy(st->h, items.data(), bytes);
-        HIP_TRY(hipMemcpyAsync(ss->ctl_buf, st->h, bytes, hipMemcpyHostToDevice, ss->s));
-        if ((rc = release_after(st, ss->s))) return rc;
-        bool to_host = false;                          // lossy objects move between HBM pools only
-        for (const Item2 &it : items) to_host |= it.dst0 != 0;
-        const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
-        if (!to_host && tiles_hbm < (1ull << 32)) {
-            hipLaunchKernelGGL(copy_items2_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ss->s,
-                               (const Item2 *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
-                               tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
-        } else {
-            uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
-            uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
-            hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, ss->s, (const Item2 *)ss->ctl_buf,
-                               (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+        if (!ctx->no_device) memcpy(h_items.st->h, items.data(), bytes);
+        DEV_TRY(hipMemcpyAsync(ss->ctl_buf, h_items.st->h, bytes, hipMemcpyHostToDevice, s));
+        if ((rc = release_after(ctx, h_items.st, s))) return rc;
+        if (!ctx->no_device) {
+            bool to_host = false;                          // lossy objects move between HBM pools only
+            for (const Item2 &it : items) to_host |= it.dst0 != 0;
+            const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
+            if (!to_host && tiles_hbm < (1ull << 32)) {
+                hipLaunchKernelGGL(copy_items2_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, s,
+                                   (const Item2 *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                                   tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
+            } else {
+                uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
+                uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
+                hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, s, (const Item2 *)ss->ctl_buf,
+                                   (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+            }
         }
-        HIP_TRY(hipGetLastError());
+        DEV_TRY(hipGetLastError());
     }
-    if (!demoted.empty()) {
-        if ((rc = publish(ctx, c, demoted, ss->s))) return rc;
-    }
-    return mark_last(ctx, ss);
+    // Without demotions the write-back itself is the commit point: once the copy is enqueued the bytes will change.
+    bool committed = demoted.empty();
+    if (!demoted.empty()) rc = publish(ctx, c, demoted, s, h_dir.st, &committed);
+    if (committed) undo.commit();
+    if (rc) return rc;
+    if (ctx->no_device) return HARVEST_OK;
+    if ((rc = mark_last(ctx, ss))) return rc;
+    // A freed local slot may be handed out by the very next harvest_register.  Fetches enqueued through the library are
+    // ordered behind the new entry, replays of recorded graphs are not: with recorded work around, the entry has to be
+    // on the device before this call returns.
+    if (!demoted.empty() && ctx->captured_work) HIP_TRY(hipStreamSynchronize(s));
+    return HARVEST_OK;
 }
 
 int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out)

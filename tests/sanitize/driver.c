@@ -45,6 +45,10 @@ int orc_fetch_experts(orc_class *c, uint32_t layer, uint32_t n_experts, const in
 int orc_evict(orc_class *c, int layer, const uint32_t *ids, uint32_t n, const uint8_t *src_k, const uint8_t *src_v,
               const uint64_t *src_block, uint64_t src_layer_stride, int flags);
 
+/* Only in this build of the library (-DHARVEST_FAULT_INJECTION): the nth device step from now fails like a HIP error.
+ * A context without a device walks the same steps as one with a device, so every roll-back path runs here. */
+void harvest_test_fail_at(int nth);
+
 static uint64_t rng_state = 0x9E3779B97F4A7C15ull;
 static uint32_t rnd(uint32_t n)
 {
@@ -73,6 +77,36 @@ static void compare_all(harvest_ctx *h, orc_class *oc[2])
         }
     if (n_cb_lib != n_cb_orc) FAIL("callbacks: library %d oracle %d", n_cb_lib, n_cb_orc);
 }
+
+static int n_injected, n_rolled_back;
+
+/* r1 = call, about every third time with a fault injected at a random device step first.  A call that reports the
+ * injected failure must have changed nothing - directory, callbacks and every statistic are as before - and is then made
+ * again for real; a call that ended before the fault was due counts as the real one. */
+#define CALL(r1, h, oc, call)                                                                                \
+    do {                                                                                                     \
+        int done_ = 0;                                                                                       \
+        if (rnd(3) == 0) {                                                                                   \
+            harvest_stats_t before_, after_;                                                                 \
+            if (harvest_stats(h, &before_)) FAIL("stats");                                                   \
+            int cb_before_ = n_cb_lib;                                                                       \
+            harvest_test_fail_at(1 + (int)rnd(7));                                                           \
+            int r_ = (call);                                                                                 \
+            harvest_test_fail_at(0);                                                                         \
+            n_injected++;                                                                                    \
+            if (r_ == HARVEST_EHIP) {                                                                        \
+                n_rolled_back++;                                                                             \
+                if (harvest_stats(h, &after_)) FAIL("stats");                                                \
+                if (memcmp(&before_, &after_, sizeof before_)) FAIL("statistics changed by a call that failed"); \
+                if (n_cb_lib != cb_before_) FAIL("a call that failed invoked callbacks");                    \
+                compare_all(h, oc);                                                                          \
+            } else {                                                                                         \
+                r1 = r_;                                                                                     \
+                done_ = 1;                                                                                   \
+            }                                                                                                \
+        }                                                                                                    \
+        if (!done_) r1 = (call);                                                                             \
+    } while (0)
 
 static void one_run(int shared)
 {
@@ -132,13 +166,17 @@ static void one_run(int shared)
         case 1: case 2: {
             if (!n_obj) break;
             int st0[6], st1[6];
-            int r0 = orc_place(c, ids, n, st0), r1 = harvest_place(h, cls, ids, n, NULL, st1);
+            int r1;
+            CALL(r1, h, oc, harvest_place(h, cls, ids, n, NULL, st1));
+            int r0 = orc_place(c, ids, n, st0);
             if (r0 != r1 || (!r0 && memcmp(st0, st1, n * sizeof(int)))) FAIL("place: %d %d", r0, r1);
             break;
         }
         case 3: {
             if (!n_obj) break;
-            int r0 = orc_revoke(c, ids, n, cb_orc, NULL), r1 = harvest_revoke(h, cls, ids, n);
+            int r1;
+            CALL(r1, h, oc, harvest_revoke(h, cls, ids, n));
+            int r0 = orc_revoke(c, ids, n, cb_orc, NULL);
             if (r0 != r1) FAIL("revoke: %d %d", r0, r1);
             break;
         }
@@ -148,8 +186,9 @@ static void one_run(int shared)
             for (uint32_t i = 0; i < n; ++i) sb[i] = rnd(8 + (rnd(30) == 0));
             int layer = (cls == HARVEST_KV && rnd(2)) ? (int)rnd(KV_LAYERS) : -1;
             int flags = rnd(2) ? HARVEST_EVICT_DEMOTE : 0;
+            int r1;
+            CALL(r1, h, oc, harvest_evict(h, cls, layer, ids, n, NULL, NULL, sb, 8, flags, NULL));
             int r0 = orc_evict(c, layer, ids, n, src, src + 64, sb, 8, flags);
-            int r1 = harvest_evict(h, cls, layer, ids, n, NULL, NULL, sb, 8, flags, NULL);
             if (r0 != r1) FAIL("evict: %d %d", r0, r1);
             break;
         }
@@ -214,6 +253,8 @@ static void one_run(int shared)
 int main(void)
 {
     for (run_no = 0; run_no < 4; ++run_no) one_run(run_no & 1);
+    if (n_rolled_back < 1000) { fprintf(stderr, "only %d of %d injected faults were hit\n", n_rolled_back, n_injected); return 1; }
+    printf("injected faults rolled back: %d\n", n_rolled_back);
     printf("sanitizer run: ok\n");
     return 0;
 }

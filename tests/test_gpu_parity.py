@@ -451,6 +451,73 @@ def test_two_threads_drive_one_context():
         eh.close(); eo.close()
 
 
+def test_a_revocation_waits_without_holding_up_the_other_thread():
+    """The expert thread places several large experts (milliseconds of PCIe traffic queued on its stream) and at once
+    revokes others, which has to wait for that queue to drain; the KV thread keeps fetching on its own stream meanwhile.
+    The wait happens outside the context's lock: fetch calls start and return while the revocation is still waiting."""
+    import threading
+    import time
+    import torch
+    say("revocation without stalling the other thread")
+    wl = W.kv_decode(seed=30, n_layers=1, n_seq=2, min_len=1500, max_len=2500, n_steps=1)
+    ex = W.expert_offload(seed=30, shape=W.ExpertShape(n_layers=1, n_experts=16, d_model=4096, d_ff=4096), n_local=0)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        cached = sorted(xh.live)
+        on_host = [i for i in range(ex.n_objects) if i not in xh.live]
+        assert len(cached) >= 4 and len(on_host) >= 4
+        half = cached[:len(cached) // 2]
+        for e in (eo, eh):                                   # room in the cache tier for what will be placed
+            e.revoke(S.EXPERT, half)
+        table, nb = rh.table_arrays()
+        dev = eh.dev
+        d_table, d_nb = torch.from_numpy(table).to(dev), torch.from_numpy(nb).to(dev)
+        d_sdb = torch.from_numpy(rh.seq_dst_block.view(np.int64)).to(dev)
+        dst = [torch.zeros(rh.cap * wl.shape.chunk_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+        kv_stream = eh.streams[S.KV]
+        with torch.cuda.stream(kv_stream):
+            eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)          # the stream's scratch exists from here on
+        torch.cuda.synchronize()
+        window, calls, stop, errors = [], [], threading.Event(), []
+
+        def kv_side():
+            try:
+                with torch.cuda.stream(kv_stream):
+                    while not stop.is_set():
+                        a = time.perf_counter()
+                        eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+                        calls.append((a, time.perf_counter()))
+                        kv_stream.synchronize()
+            except BaseException as e:
+                errors.append(e)
+
+        th = threading.Thread(target=kv_side)
+        th.start()
+        time.sleep(0.02)
+        n_place = min(len(half), len(on_host))
+        st = eh.place(S.EXPERT, on_host[:n_place])            # ~100 MiB each over PCIe: milliseconds of queued work
+        a = time.perf_counter()
+        revoked = eh.revoke(S.EXPERT, cached[len(cached) // 2:])     # has to wait for the placements
+        window = (a, time.perf_counter())
+        stop.set()
+        th.join(30)
+        assert not th.is_alive() and not errors, errors
+        assert (st == 0).all() and len(revoked) == len(cached) - len(cached) // 2
+        inside = [c for c in calls if c[0] > window[0] and c[1] < window[1]]
+        say(f"  the revocation waited {1e3 * (window[1] - window[0]):.1f} ms; {len(inside)} KV fetch calls ran inside it")
+        assert window[1] - window[0] > 2e-3 and len(inside) >= 3
+        # and nothing is wrong afterwards
+        assert np.array_equal(eo.place(S.EXPERT, on_host[:n_place]), st)
+        eo.revoke(S.EXPERT, cached[len(cached) // 2:])
+        P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "kv after the overlap")
+        P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts after the overlap")
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- head-major working layout ----------------------------------------------------------------------------------
 
 @LAYOUTS

@@ -14,8 +14,10 @@ SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-
 @pytest.mark.skipif(shutil.which("hipcc") is None or shutil.which("gcc") is None, reason="needs hipcc and gcc")
 def test_host_logic_and_oracle_under_sanitizers(tmp_path):
     lib = tmp_path / "libharvest_san.so"
+    # -DHARVEST_FAULT_INJECTION: this build (and only this one) can be told to fail at its n-th device step, which is how
+    # the driver reaches the roll-back code of place / evict / revoke
     hip = ["hipcc", "--offload-arch=gfx950", "-O1", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-DHARVEST_FAULT_INJECTION"]
     for f in SAN:
         hip += ["-Xarch_host", f]
     hip += ["-o", str(lib), os.path.join(ROOT, "paper_2602_00328_amd", "csrc", "harvest.hip")]
@@ -32,4 +34,4 @@ def test_host_logic_and_oracle_under_sanitizers(tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([str(exe)], env=env, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-6000:]
-    assert "sanitizer run: ok" in r.stdout
+    assert "sanitizer run: ok" in r.stdout and "injected faults rolled back" in r.stdout
