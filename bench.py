@@ -70,6 +70,9 @@ def parse():
     ap.add_argument("--cache-layout", default="adjacent", choices=["adjacent", "planes"],
                     help="kv_decode, equal-size slots: 'adjacent' = one cache pool [layer][slot][K|V][chunk] (a block's K and "
                          "V are neighbours, one 64 KiB source run per block); 'planes' = a K pool and a V pool")
+    ap.add_argument("--no-other-legs", dest="other_legs", action="store_false",
+                    help="kv_decode: skip the short extra legs (the next seed's draw, the two expert configurations with two "
+                         "layers materialised) that the default run appends under 'other_legs'")
     ap.add_argument("--calibrate", type=int, default=3, help="plain-copy launches of 2 GiB (counter calibration)")
     args = ap.parse_args()
     if args.no_profile:
@@ -282,10 +285,46 @@ def bench_tiny(args):
         "roofline": None, "cpu_baseline": cpu_baseline}), flush=True)
 
 
-def bench_experts(args):
+def experts_vs_oracle(args, wl, run, eng, n_total, L):
+    """The oracle walks the same steps (fetches, and for the LRU config the policy's revocations and placements), then
+    both fetch every layer once more for the step after the timed ones: pointers, staged bytes, counts and miss list must
+    agree.  Also times the oracle's fetch of one layer (single-threaded: a reported baseline, not a target)."""
+    import numpy as np
+    from workloads import scenarios as S
+    from oracle.engine import OracleEngine
+    t0 = time.time()
+    eo = OracleEngine(expert=run._spec)
+    xo = S.ExpertRun(eo, wl)
+    for t in range(n_total):
+        for l in range(L):
+            if wl.lru_capacity:
+                xo.fetch(t, l, digest=True)                 # the LRU's placements copy from the staging buffer of this fetch
+                xo.lru_update(t, l, from_staging=not args.place_from_host)
+    exact = True
+    for l in range(L):
+        a, b = xo.fetch(n_total, l), run.fetch(n_total, l)
+        exact &= all((x is None) == (y is None) and (x is None or np.array_equal(x, y)) for x, y in zip(a[0], b[0]))
+        exact &= bool(np.array_equal(np.where(a[1] >= 3, 0, a[1]), b[1]) and np.array_equal(a[3], b[3]) and a[4] == b[4])
+    staged = sum(1 for x in a[0] if x is not None) - int((a[1] == 1).sum())
+    n, t1 = 0, time.perf_counter()
+    while n < 2 or time.perf_counter() - t1 < 3.0:
+        xo.fetch(n_total, L - 1, digest=True)
+        n += 1
+    sec = (time.perf_counter() - t1) / n
+    chunk = eng.spec[1].chunk_bytes
+    base = {"value": round(2 * staged * chunk / sec / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"the fetch of one layer ({staged} experts of {chunk / 2**20:.1f} MiB copied into staging), repeated "
+                      f"{n} times (>= 3 s), its checksum included; all tiers in host DRAM"}
+    eo.close()
+    log(f"[bench] experts vs oracle after {n_total} steps: bit_exact={bool(exact)}; oracle {base['value']} GB/s on one thread "
+        f"({time.time() - t0:.1f}s)")
+    return bool(exact), base
+
+
+def bench_experts(args, embed=False):
     """configs[2] (Phi-3.5-MoE-shaped, static residency) and configs[3] (Qwen-MoE-shaped, LRU-driven cache tier): one step
     = the expert fetch of every materialised layer for one batch of routed tokens (plus, for the LRU config, the
-    revocations and placements the policy asks for after each layer)."""
+    revocations and placements the policy asks for after each layer).  embed: return the result instead of printing it."""
     import numpy as np
     import torch
     import workloads as W
@@ -302,8 +341,9 @@ def bench_experts(args):
     spec = S.expert_spec(wl)
     if not args.no_isolation:
         spec.n_cache_slots = wl.n_objects              # room for the all-cache isolation point
-    eng = HipEngine(expert=spec, profile=True, host_wgs=args.host_wgs)
+    eng = HipEngine(expert=spec, profile=True, host_wgs=args.host_wgs, gather_threads=args.gather_threads)
     run = S.ExpertRun(eng, wl)
+    run._spec = spec
     torch.cuda.synchronize()
     sp = eng.spec[1]
     E = sp.n_experts
@@ -357,7 +397,7 @@ def bench_experts(args):
         "objects_per_s": round(d["n_requests"] / sec), "bit_exact": None,
         "served_per_step": {k: round(v / args.steps, 2) for k, v in d.items()},
         "placed_per_step": round(placed / args.steps, 2),
-        "roofline": {"bound": "hbm", "kernel": "gather<1,true> (HBM-tier gather of whole experts)", "achieved": round(hbm_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "gather<64,true,false> (HBM-tier gather of whole experts)", "achieved": round(hbm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "launches": int(pr.hbm_launches)},
         "host_tier": {"bound": "pcie", "kernel": "gather_host", "achieved": round(host_gbs, 2), "unit": "GB/s",
@@ -366,6 +406,8 @@ def bench_experts(args):
     }
     log(f"[bench] {args.steps} steps in {sec:.3f}s: {out['ms_per_step']} ms/step; HBM tier {hbm_gbs:.0f} GB/s, host tier "
         f"{host_gbs:.1f} GB/s; per step {out['served_per_step']}, placed {out['placed_per_step']}")
+    if not args.no_cpu_baseline:
+        out["bit_exact"], out["cpu_baseline"] = experts_vs_oracle(args, wl, run, eng, n_total, L)
     if not args.no_isolation:
         # ---- isolation points: the same routing with every non-local expert in the cache tier, then on the host ----
         iso = {}
@@ -403,6 +445,8 @@ def bench_experts(args):
         out["prefetch"] = bench_prefetch(eng, wl, topk, staging, ptrs, L, E, sp.chunk_bytes, sec / (args.steps * L),
                                          range(args.warmup, n_total))
     eng.close()
+    if embed:
+        return out
     print(json.dumps(out), flush=True)
 
 
@@ -477,23 +521,53 @@ def main():
         log(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); the path has no collectives - "
             "objects are independent, so several GPUs would each run this same fetch over their own share.")
         sys.exit(2)
+    import torch
+    torch.cuda.set_device(0)
+    if args.workload == "kv_tiny":
+        return bench_tiny(args)
+    if args.workload != "kv_decode":
+        return bench_experts(args)
+    out = bench_kv(args, args.seed, full=True)
+    if args.other_legs and not args.head_major and args.fetch_layers == 1:
+        # Beside the benchmark line: the same configuration at another draw of the sequence lengths (seed 0 happens to draw
+        # short ones), and the two expert configurations with two layers materialised - short runs, each checked against
+        # the oracle, so that one default run shows every kernel at its real per-step shape.
+        import copy
+        extra = {}
+        a2 = copy.copy(args)
+        a2.steps, a2.warmup, a2.graph_steps, a2.no_isolation = min(args.steps, 40), 5, 0, True
+        r = bench_kv(a2, args.seed + 1, full=False)
+        extra["configs[1], seed %d" % (args.seed + 1)] = {
+            k: r[k] for k in ("value", "unit", "ms_per_step", "objects_per_s", "bit_exact", "served")} | {
+            "blocks_per_step": r["config"]["blocks_per_step"],
+            "hbm_tier_gather_gbs": r["roofline"]["achieved"], "hbm_tier_gather_frac": r["roofline"]["frac"],
+            "host_tier_gbs": r["host_tier"]["achieved"], "host_tier_frac": r["host_tier"]["frac"]}
+        for wlname, key in (("experts_phi", "configs[2]"), ("experts_qwen", "configs[3]")):
+            a3 = copy.copy(args)
+            a3.workload, a3.layers, a3.steps, a3.warmup, a3.no_isolation, a3.prefetch = wlname, 2, 3, 1, True, False
+            r = bench_experts(a3, embed=True)
+            extra[key] = {k: r[k] for k in ("value", "unit", "ms_per_step", "objects_per_s", "bit_exact", "served_per_step",
+                                            "placed_per_step", "cpu_baseline")} | {
+                "layers_materialised": 2, "hbm_tier_gather_gbs": r["roofline"]["achieved"],
+                "hbm_tier_gather_frac": r["roofline"]["frac"], "host_tier_gbs": r["host_tier"]["achieved"]}
+        out["other_legs"] = extra
+    print(json.dumps(no_nan(out)), flush=True)
+
+
+def bench_kv(args, seed, full):
+    """configs[1] at one seed.  full: every leg (calibration copies, graph replay, the oracle's speed, isolation points,
+    write paths); otherwise the timed steps and the check against the oracle only.  Returns the result line as a dict."""
     import numpy as np
     import torch
     import workloads as W
     from workloads import scenarios as S
     from paper_2602_00328_amd import binding as B
     from workloads.hip_engine import HipEngine
-
-    torch.cuda.set_device(0)
-    if args.workload == "kv_tiny":
-        return bench_tiny(args)
-    if args.workload != "kv_decode":
-        return bench_experts(args)
     dev = torch.device("cuda", 0)
     n_total = args.warmup + args.steps + args.graph_steps
     t0 = time.time()
     kv_shape = W.KVShape(n_layers=args.layers, elt_bytes=args.kv_elt_bytes)
-    wl = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
+    wl = W.kv_decode(seed=seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
     sh = wl.shape
     chunk = sh.chunk_bytes
     n_blocks0 = int(sum(len(t) for t in wl.tables))
@@ -604,7 +678,7 @@ def main():
         from oracle.engine import OracleEngine
         layer = dd.first_layer(dd.t)
         ncores = len(os.sched_getaffinity(0))
-        wl1 = W.kv_decode(seed=args.seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
+        wl1 = W.kv_decode(seed=seed, n_layers=args.layers, n_steps=n_total, shape=kv_shape, placement=args.placement)
         eo = OracleEngine(kv=S.kv_spec(wl1, cache_slack=0 if args.no_isolation else all_cache_slack), kv_layers=[layer],
                           threads=ncores)
         ro = S.KVRun(eo, wl1)
@@ -626,7 +700,7 @@ def main():
         log(f"[bench] layer {layer} after {n_total} steps vs oracle: bit_exact={bit_exact}")
         step_payload = want[3]["n_requests"] * 2 * chunk
         res = {}
-        for threads in (1, ncores):
+        for threads in (1, ncores) if full else ():
             eo.threads = threads
             ro.fetch(layer)
             a = time.perf_counter()
@@ -635,12 +709,13 @@ def main():
                 ro.fetch(layer)
                 n += 1
             res[threads] = 2 * step_payload * n / (time.perf_counter() - a) / 1e9
-        cpu_baseline = {"value": round(res[ncores], 2), "unit": "GB/s", "cores": ncores, "kind": "oracle",
-                        "single_thread_value": round(res[1], 2),
-                        "sample": f"the same decode state, one layer's full fetch ({want[3]['n_requests']} blocks, "
-                                  f"{step_payload / 2**30:.2f} GiB payload) repeated for >= 6 s per thread count, "
-                                  "all tiers in host DRAM"}
-        log(f"[bench] oracle: {res[1]:.1f} GB/s on 1 thread, {res[ncores]:.1f} GB/s on {ncores} threads")
+        if full:
+            cpu_baseline = {"value": round(res[ncores], 2), "unit": "GB/s", "cores": ncores, "kind": "oracle",
+                            "single_thread_value": round(res[1], 2),
+                            "sample": f"the same decode state, one layer's full fetch ({want[3]['n_requests']} blocks, "
+                                      f"{step_payload / 2**30:.2f} GiB payload) repeated for >= 6 s per thread count, "
+                                      "all tiers in host DRAM"}
+            log(f"[bench] oracle: {res[1]:.1f} GB/s on 1 thread, {res[ncores]:.1f} GB/s on {ncores} threads")
         eo.close()
 
     # ---- isolation points: the same request list with every block in the cache tier, then every block on the host ----
@@ -718,12 +793,22 @@ def main():
                              "objects_per_s": round(counts["n_requests"] / (dt / n_it))}
             log(f"[bench] isolation {name}: {iso[name]}")
 
-    traffic = None
+    # Hardware byte counters cannot be read from inside this process: `traffic` is what two rocprofv3 --pmc passes over
+    # this same command measured, kept with their command lines in the file named below - a stored figure of the
+    # configuration (seed 0, default layout), not a measurement of this run; null when the file is not there or this run
+    # is another configuration.
+    traffic, traffic_source = None, None
     tf = os.path.join(ROOT, "profiles", "gather_hbm_kv_decode_pmc.txt")
-    if os.path.exists(tf):
+    default_config = (seed == 0 and not args.head_major and not args.shared_cache and args.cache_layout == "adjacent"
+                      and args.kv_elt_bytes == 2 and args.fetch_layers == 1 and args.placement == "shuffled")
+    if os.path.exists(tf) and default_config:
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tf).read())
         if m:
             traffic = float(m.group(1))
+            traffic_source = ("profiles/gather_hbm_kv_decode_pmc.txt: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE passes over "
+                              "this command, scaled by the same counters' reading of a 2 GiB plain copy; stored, not measured "
+                              "by this run")
+    alone = iso.get("all_cache", {}).get("hbm_gbs_read_write")
 
     out = {
         "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
@@ -741,17 +826,28 @@ def main():
                    "cache_tier": "shared pool of best-fit segments" if args.shared_cache else
                                  ("equal-size slots, one pool [layer][slot][K|V][chunk]" if args.cache_layout == "adjacent"
                                   else "equal-size slots, a K pool and a V pool [layer][slot][chunk]"),
-                   "seed": args.seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
+                   "seed": seed, "layers_materialised": args.layers, "blocks_per_step": d["n_requests"] // args.steps,
+                   "blocks_per_step_mean_of_config": 20480,
+                   "blocks_per_step_note": "4 lengths ~U[32K,128K] tokens: 8192..32768 blocks, mean 20480; this seed's draw is "
+                                           f"{n_blocks0}",
                    "payload_bytes_per_step": payload // args.steps},
         "objects_per_s": round(d["n_requests"] * args.fetch_layers / sec),
         "bit_exact": bit_exact,
         "graph_replay": graph_replay,
         "served": {k: v // args.steps for k, v in d.items()},
-        "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true>" if args.head_major else "gather<1,true>") + " (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true,false>" if args.head_major else
+                                                "gather<%d,true,%s>" % (args.gather_threads or 64, "true" if args.shared_cache or
+                                                                        args.cache_layout == "adjacent" else "false"))
+                                               + " (HBM-tier gather)", "achieved": round(hbm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
-                     "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1)},
-        "host_tier": {"bound": "pcie", "kernel": ("gather_hm<8,false,true>" if args.head_major else "gather_host") + " (host-tier gather, zero-copy over PCIe)",
+                     "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1),
+                     "frac_of_plain_copy": round(hbm_gbs / plain_gbs, 4),
+                     "note": "achieved / frac: the kernel inside the timed step, where the host-tier kernel reads over PCIe "
+                             "beside it; alone: the same request list with every block in the cache tier (isolation.all_cache)",
+                     "achieved_alone": alone, "frac_alone": round(alone / HBM_PEAK_GBS, 4) if alone else None},
+        "host_tier": {"bound": "pcie", "kernel": ("gather_hm_host<2>" if args.head_major else "gather_host<2>") + " (host-tier gather, zero-copy over PCIe)",
                       "achieved": round(host_gbs, 2), "peak": round(pcie_peak_gbs, 2), "unit": "GB/s",
                       "frac": round(host_gbs / pcie_peak_gbs, 4), "launches": int(pr.host_launches),
                       "avg_launch_ms": round(host_ms, 5), "bytes_per_launch": round(host_bytes),
@@ -762,7 +858,7 @@ def main():
         "cpu_baseline": cpu_baseline,
     }
     eng.close()
-    print(json.dumps(no_nan(out)), flush=True)
+    return out
 
 
 if __name__ == "__main__":
