@@ -521,13 +521,14 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
 # ---- head-major working layout ----------------------------------------------------------------------------------
 
 @LAYOUTS
-@pytest.mark.parametrize("heads,dim,tokens,elt", [(8, 128, 16, 2), (8, 128, 16, 1), (3, 24, 4, 2), (1, 8, 1, 2), (5, 104, 48, 2)])
+@pytest.mark.parametrize("heads,dim,tokens,elt", [(8, 128, 16, 2), (8, 128, 16, 1), (3, 24, 4, 2), (1, 8, 1, 2), (5, 104, 48, 2),
+                                                  (4, 512, 8, 2), (16, 32, 12, 2), (8, 128, 6, 2)])
 def test_head_major_fetch(heads, dim, tokens, elt, adjacent):
     shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=elt)
     say(f"head-major: {heads} heads x {dim} x {elt} B, {tokens}-token blocks, chunk {shape.chunk_bytes}")
     wl = W.kv_decode(seed=12, n_seq=3, min_len=30 * tokens, max_len=90 * tokens, n_steps=tokens + 3, shape=shape,
                      fill_mode=W.FILL_NORMAL)
-    eo, eh = P.make_engines(wl, hip_kwargs=dict(cache_planes_adjacent=adjacent))
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(cache_planes_adjacent=adjacent, general_fetch=True))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         final = [len(t) + len(f) for t, f in zip(wl.tables, wl.future_blocks)]
