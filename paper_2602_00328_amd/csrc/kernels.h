@@ -13,17 +13,20 @@
 //   resolve_experts          : the same for expert weights (Section 4.3: residency map) - one workgroup forms the
 //                              distinct set of routed experts and walks it in ascending order (very large batches of
 //                              routing ids are marked by many workgroups first: mark_experts).
-//   gather                   : the copy itself.  HBM tier: one workgroup per 4 KiB tile, one 16-byte non-temporal
-//                              load and store per thread, as many workgroups as tiles, plane K before plane V
-//                              (measured on MI355X: short workgroups beat deep unrolling and persistent grids by
-//                              ~15%, non-temporal accesses are worth ~11%, one plane at a time ~2%).
+//   gather                   : the copy itself.  HBM tier: one wavefront per workgroup and 1 KiB tile, one 16-byte
+//                              non-temporal load and store per thread, as many workgroups as tiles; plane K before
+//                              plane V, or - where the cache tier keeps them side by side - both planes of a request
+//                              in one pass (measured on MI355X: short workgroups beat deep unrolling and persistent
+//                              grids by ~15%, one-wavefront workgroups beat four-wavefront ones by 2-5%, non-temporal
+//                              accesses are worth ~11%, 64 KiB source runs 4-5% over 32 KiB ones).
 //   gather_host              : host tier - a couple of dozen persistent workgroups with two loads in flight per
 //                              thread over 4 KiB sub-tiles: enough compute units to keep the PCIe link full, and no
 //                              more host reads in flight than the link absorbs, because the rest would only stand in
 //                              the HBM tier's way.
 //   gather_hm, gather_hm_host: the same two into a head-major working layout.
 //   copy_items, copy_items2, fill_items, dir_write : host-built lists - placement, write-back (one source, up to two
-//                              destinations), slot poisoning after revocation, directory publication.
+//                              destinations), slot poisoning after revocation, directory publication; the _hbm forms
+//                              of the first three serve copies that stay inside HBM.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
