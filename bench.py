@@ -38,9 +38,12 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
-    ap.add_argument("--workload", default="kv_decode", choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen"],
+    ap.add_argument("--workload", default="kv_decode",
+                    choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen", "latency_by_size"],
                     help="kv_decode = configs[1] (the benchmark line); kv_tiny = configs[0] (fetch latency, both forms of the "
-                         "fetch); experts_* = configs[2] / configs[3], extra lines")
+                         "fetch); experts_* = configs[2] / configs[3], extra lines; latency_by_size = time of one fetch from "
+                         "the cache tier against the same fetch from the host, by object size (the paper's Figures 3 and 7 "
+                         "on this machine: context, not a benchmark line)")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
@@ -506,6 +509,85 @@ def bench_prefetch(eng, wl, topk, staging, ptrs, L, E, chunk, fetch_s_per_layer,
     return res
 
 
+def bench_latency(args):
+    """The paper's two transfer-latency figures on this machine (Section 2.3 / Figure 3: copies the size of one expert,
+    peer GPU against host; Section 5.4 / Figure 7: KV chunks of 100 ... 8 000 entries): the time of one fetch whose objects
+    all sit in the cache tier against the same fetch after their revocation, when they come from the host.  Here the cache
+    tier is HBM on the same GPU, so the ratio is HBM against PCIe, not NVLink against PCIe: context, not a target."""
+    import numpy as np
+    import torch
+    from types import SimpleNamespace
+    from paper_2602_00328_amd import binding as B
+    dev = torch.device("cuda", 0)
+    reps = max(5, args.steps // 10)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - a)
+        return float(np.median(ts))
+
+    out = {"experts": [], "kv": []}
+    for name, mib in (("1 MiB", 1.0), ("4 MiB", 4.0), ("Qwen-MoE-shaped expert, 16.5 MiB", 16.5), ("64 MiB", 64.0),
+                      ("Phi-3.5-MoE-shaped expert, 150 MiB", 150.0), ("Mixtral-8x7B-shaped expert (3 x 4096 x 14336 bf16), 336 MiB", 336.0)):
+        chunk = int(mib * 2**20)
+        E = 4
+        h = B.Harvest(expert=B.ClassSpec(n_layers=1, n_planes=1, chunk_bytes=chunk, max_objects=E, n_host_slots=E,
+                                         n_cache_slots=E, n_local_slots=0, n_experts=E))
+        h.host_plane(B.EXPERT)[:] = np.random.default_rng(1).integers(0, 256, size=(1, E, 4096), dtype=np.uint8).repeat(chunk // 4096, axis=2)
+        h.register(B.EXPERT, E, np.arange(E), B.HOST)
+        assert (h.place(B.EXPERT, np.arange(E)) == 0).all()
+        topk = torch.tensor([[2]], dtype=torch.int32, device=dev)
+        staging = torch.zeros(chunk, dtype=torch.uint8, device=dev)
+        ptrs = torch.zeros(E, dtype=torch.int64, device=dev)
+        fetch = lambda: h.fetch_experts(0, topk, staging, 1, ptrs)
+        t_cache = timed(fetch)
+        from_cache = staging.clone()
+        h.revoke(B.EXPERT, np.arange(E))
+        t_host = timed(fetch)
+        same = bool(torch.equal(from_cache, staging))
+        out["experts"].append({"object": name, "bytes": chunk, "cache_tier_us": round(t_cache * 1e6, 1), "host_tier_us": round(t_host * 1e6, 1),
+                               "speed_up": round(t_host / t_cache, 2), "same_bytes": same})
+        log(f"[bench] one expert, {name}: cache tier {t_cache * 1e6:.1f} us, host {t_host * 1e6:.1f} us, x{t_host / t_cache:.1f}, same bytes {same}")
+        h.close()
+        del staging, from_cache
+    chunk, n_max = 32768, 8000
+    h = B.Harvest(kv=B.ClassSpec(n_layers=1, n_planes=2, chunk_bytes=chunk, max_objects=n_max, n_host_slots=n_max,
+                                 n_cache_slots=n_max, n_local_slots=0), flags=B.FLAG_CACHE_PLANES_ADJACENT)
+    rng = np.random.default_rng(2)
+    for p in range(2):
+        h.host_plane(B.KV, p)[:] = rng.integers(0, 256, size=(1, n_max, 64), dtype=np.uint8).repeat(chunk // 64, axis=2)
+    h.register(B.KV, n_max, rng.permutation(n_max), B.HOST)
+    dst = [torch.zeros(n_max * chunk, dtype=torch.uint8, device=dev) for _ in range(2)]
+    order = rng.permutation(n_max).astype(np.int32)
+    for n in (100, 500, 1000, 2000, 4000, 8000):
+        assert (h.place(B.KV, np.arange(n_max)) == 0).all()
+        d_table = torch.from_numpy(order[:n].reshape(1, n).copy()).to(dev)
+        d_nb = torch.tensor([n], dtype=torch.int32, device=dev)
+        d_sdb = torch.zeros(1, dtype=torch.int64, device=dev)
+        fetch = lambda: h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, n_max)
+        t_cache = timed(fetch)
+        from_cache = [t[:n * chunk].clone() for t in dst]
+        h.revoke(B.KV, np.arange(n_max))
+        t_host = timed(fetch)
+        same = all(bool(torch.equal(a, t[:n * chunk])) for a, t in zip(from_cache, dst))
+        out["kv"].append({"blocks": n, "bytes": 2 * n * chunk, "cache_tier_us": round(t_cache * 1e6, 1), "host_tier_us": round(t_host * 1e6, 1),
+                          "speed_up": round(t_host / t_cache, 2), "same_bytes": same})
+        log(f"[bench] {n} KV blocks of 2 x 32 KiB: cache tier {t_cache * 1e6:.1f} us, host {t_host * 1e6:.1f} us, x{t_host / t_cache:.1f}, same bytes {same}")
+    h.close()
+    print(json.dumps({"metric": "fetch latency of one request by object size, cache tier against host tier (call to completion, median of "
+                                f"{reps})", "unit": "us", "n_gpus": 1, "data": "synthetic", "dtype": "u8",
+                      "config": {"workload": "the paper's Figure 3 (expert-sized chunks) and Figure 7 (KV chunks of 100 ... 8000 entries) on one "
+                                             "MI355X: cache tier = HBM on the same GPU, host tier = pinned DRAM over PCIe"},
+                      "paper": "2 x H100, peer GPU over NVLink against host over PCIe 5: expert-sized chunks 7.5x ... 9.5x, KV chunks 3x ... 5.68x",
+                      **out}), flush=True)
+
+
 def no_nan(x):
     """JSON has no NaN: figures that were not measured (--no-profile) are reported as null."""
     if isinstance(x, dict):
@@ -525,6 +607,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "kv_tiny":
         return bench_tiny(args)
+    if args.workload == "latency_by_size":
+        return bench_latency(args)
     if args.workload != "kv_decode":
         return bench_experts(args)
     out = bench_kv(args, args.seed, full=True)
