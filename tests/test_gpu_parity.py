@@ -715,9 +715,14 @@ def test_fetch_again_after_an_expert_fetch_on_the_same_stream(general, many_expe
         for t in range(6):
             P.assert_kv_equal(ro.fetch(0), rh.fetch(0), f"step {t}, layer 0")
             for layer in (0, 1, 2):
-                P.assert_experts_equal(xo.fetch(t, layer), xh.fetch(t, layer), f"step {t}, experts of layer {layer}")
+                want_x = xo.fetch(t, layer)
+                P.assert_experts_equal(want_x, xh.fetch(t, layer), f"step {t}, experts of layer {layer}")
                 nxt = (layer + 1) % 3
-                P.assert_kv_equal(eo.fetch_kv_again(nxt), eh.fetch_kv_again(nxt), f"step {t}, again at layer {nxt}")
+                want_kv = eo.fetch_kv_again(nxt)
+                P.assert_kv_equal(want_kv, eh.fetch_kv_again(nxt), f"step {t}, again at layer {nxt}")
+                # each class keeps its own counters on the stream; harvest_fetch_info reports the latest fetch of either
+                assert eh.h.fetch_info(cls=S.EXPERT)[0] == want_x[4] and eh.h.fetch_info(cls=S.KV)[0] == want_kv[3]
+                assert eh.h.fetch_info()[0] == want_kv[3]
             ro.append(t); rh.append(t)
     finally:
         eh.close(); eo.close()
