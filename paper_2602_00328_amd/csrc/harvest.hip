@@ -17,7 +17,6 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
-#include <functional>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -195,27 +194,48 @@ struct ClassState {
     }
 };
 
+// What a call has changed in the host mirror so far, undone in reverse order unless the call commits: the calls that edit
+// the directory change the mirror first and the device afterwards, and a device step that fails in between must leave
+// no trace ("on error nothing is enqueued or changed").
+struct Undo {
+    enum Kind : uint8_t { PLACED, REVOKED, DEMOTED, TOOK_CACHE_SLOT, COUNTED_ENOSPC, COUNTED_EVICTED };
+    struct Step { Kind kind; uint32_t id; uint32_t gen; int64_t slot; };
+    ClassState &c;
+    std::vector<Step> steps;
+    bool armed = true;
+    explicit Undo(ClassState &cls) : c(cls) {}
+    void add(Kind k, uint32_t id = 0, int64_t slot = -1, uint32_t gen = 0) { steps.push_back({ k, id, gen, slot }); }
+    void commit() { armed = false; }
+    ~Undo()
+    {
+        if (!armed) return;
+        for (auto it = steps.rbegin(); it != steps.rend(); ++it) {
+            switch (it->kind) {
+            case PLACED:               // the object took cache slot `slot`: back to the host entry of generation `gen`
+                c.cache_release(it->slot);
+                c.tier[it->id] = T_HOST; c.slot[it->id] = -1; c.gen[it->id] = it->gen; c.n_placed--;
+                break;
+            case REVOKED:              // the object left cache slot `slot`
+                c.tier[it->id] = T_CACHE; c.slot[it->id] = it->slot; c.gen[it->id] = it->gen; c.n_revoked--;
+                break;
+            case DEMOTED:              // the object left local slot `slot`
+                c.local_free.erase((uint32_t)it->slot);
+                c.tier[it->id] = T_LOCAL; c.slot[it->id] = it->slot; c.gen[it->id] = it->gen; c.n_demoted--;
+                break;
+            case TOOK_CACHE_SLOT: c.cache_release(it->slot); break;
+            case COUNTED_ENOSPC: c.n_enospc--; break;
+            case COUNTED_EVICTED: c.n_evicted--; break;
+            }
+        }
+    }
+};
+
 struct Staging {
     void *h = nullptr;
     size_t cap = 0;
     hipEvent_t done = nullptr;
     bool busy = false;      // the device may still read it: free again once `done` has passed
     bool held = false;      // a call has taken it and not yet handed it to the device (or given it back)
-};
-
-// What a call has changed in the host mirror so far, undone in reverse order unless the call commits: the calls that edit
-// the directory change the mirror first and the device afterwards, and a device step that fails in between must leave
-// no trace ("on error nothing is enqueued or changed").
-struct Undo {
-    std::vector<std::function<void()>> steps;
-    bool armed = true;
-    void add(std::function<void()> f) { steps.push_back(std::move(f)); }
-    void commit() { armed = false; }
-    ~Undo()
-    {
-        if (armed)
-            for (auto it = steps.rbegin(); it != steps.rend(); ++it) (*it)();
-    }
 };
 
 // Gives a staging block back if the call ends before the device got it.
@@ -1112,7 +1132,7 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
         if ((rc = acquire_staging(ctx, max_items * sizeof(Item), &h_items.st))) return rc;
         if ((rc = acquire_staging(ctx, (size_t)n * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
     }
-    Undo undo;
+    Undo undo(c);
     std::vector<uint32_t> moved;
     std::vector<Item> items;
     std::vector<int> st_all(n, HARVEST_OK);
@@ -1125,7 +1145,7 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
         else if (int64_t slot = c.cache_take(); slot < 0) {
             st = HARVEST_ENOSPC;
             c.n_enospc++;
-            undo.add([&c] { c.n_enospc--; });
+            undo.add(Undo::COUNTED_ENOSPC);
         } else {
             for (uint32_t p = 0; p < c.cfg.n_planes; ++p)
                 for (uint32_t l = 0; l < c.cfg.n_layers; ++l) {
@@ -1136,11 +1156,7 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
             const uint32_t old_gen = c.gen[id];
             c.tier[id] = T_CACHE; c.slot[id] = slot; c.gen[id] += 1;
             c.n_placed++;
-            undo.add([&c, id, slot, old_gen] {
-                c.cache_release(slot);
-                c.tier[id] = T_HOST; c.slot[id] = -1; c.gen[id] = old_gen;
-                c.n_placed--;
-            });
+            undo.add(Undo::PLACED, id, slot, old_gen);
             moved.push_back(id);
         }
         st_all[i] = st;
@@ -1263,7 +1279,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             ~PutBack() { if (armed && e) ctx->evt_pool.push_back(e); }
         } put_back{ ctx, drained, true };
         // 1. invalidate
-        Undo undo;
+        Undo undo(c);
         for (uint32_t i = 0; i < n; ++i) {
             uint32_t id = ids[i];
             if (c.tier[id] != T_CACHE) continue;
@@ -1274,7 +1290,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             c.slot[id] = -1;
             c.gen[id] += 1;
             c.n_revoked++;
-            undo.add([&c, id, slot, old_gen] { c.tier[id] = T_CACHE; c.slot[id] = slot; c.gen[id] = old_gen; c.n_revoked--; });
+            undo.add(Undo::REVOKED, id, slot, old_gen);
             cbs.push_back({ c.cb[id], c.cb_user[id] });
         }
         bool committed = false;
@@ -1801,7 +1817,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     std::vector<Item2> items;
     items.reserve(max_items);
     std::vector<uint32_t> demoted;
-    Undo undo;
+    Undo undo(c);
     // room for every lossy object that leaves local HBM, taken in request order before anything changes: all or nothing
     std::vector<int64_t> room;
     if (demote_flag)
@@ -1810,7 +1826,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
                 int64_t slot = c.cache_take();
                 if (slot < 0) return HARVEST_ENOSPC;           // (the slots taken so far go back: undo)
                 room.push_back(slot);
-                undo.add([&c, slot] { c.cache_release(slot); });
+                undo.add(Undo::TOOK_CACHE_SLOT, 0, slot);
             }
     size_t n_room = 0;
     for (uint32_t i = 0; i < n; ++i) {
@@ -1833,7 +1849,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
                 if (it.dst0 || it.dst1) items.push_back(it);
             }
         c.n_evicted++;
-        undo.add([&c] { c.n_evicted--; });
+        undo.add(Undo::COUNTED_EVICTED);
         if (demote) {
             const int64_t old_slot = c.slot[id];
             const uint32_t old_gen = c.gen[id];
@@ -1842,11 +1858,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
             else { c.tier[id] = T_HOST; c.slot[id] = -1; }
             c.gen[id] += 1;
             c.n_demoted++;
-            undo.add([&c, id, old_slot, old_gen] {
-                c.local_free.erase((uint32_t)old_slot);
-                c.tier[id] = T_LOCAL; c.slot[id] = old_slot; c.gen[id] = old_gen;
-                c.n_demoted--;
-            });
+            undo.add(Undo::DEMOTED, id, old_slot, old_gen);
             demoted.push_back(id);
         }
     }
