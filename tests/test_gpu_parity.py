@@ -310,10 +310,11 @@ def test_place_from_device_memory_kv_all_layers():
     hold exactly the named source blocks, the host pool must stay as it was, fetches serve the new bytes until the
     objects are revoked and the host bytes afterwards.  Equal-size slots and best-fit segments."""
     say("place_from, kv")
-    for shared in (0, 1):
+    for shared, adjacent in ((0, False), (1, False), (0, True)):
         wl = W.kv_decode(seed=33, n_layers=3, n_seq=2, min_len=200, max_len=400, p_cache=0.0, n_steps=1)
         nbytes = 64 * 256 * 3 * 2 * wl.shape.chunk_bytes // 64 if shared else 0
-        eo, eh = P.make_engines(wl, poison=True, cache_slack=16, shared_cache_bytes=nbytes, shared_granule=256 if shared else 0)
+        eo, eh = P.make_engines(wl, poison=True, cache_slack=16, shared_cache_bytes=nbytes, shared_granule=256 if shared else 0,
+                                hip_kwargs=dict(cache_planes_adjacent=adjacent))
         try:
             ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
             chunk, stride = wl.shape.chunk_bytes, 7
@@ -649,15 +650,17 @@ def test_one_plane_kv_class():
 
 # ---- the same fetch again for another layer ------------------------------------------------------------------------
 
+@LAYOUTS
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
 @pytest.mark.parametrize("head_major", [False, True])
-def test_fetch_again_for_another_layer(general, head_major):
+def test_fetch_again_for_another_layer(general, head_major, adjacent):
     """harvest_fetch_kv_again walks the layers of a step on the lists of the first fetch; every directory edit in between
     (placement, revocation, demotion, registration) makes it resolve again.  Either way it must deliver what a fetch of
     that layer delivers."""
     say(f"fetch again, general path {general}, head-major {head_major}")
     wl = W.kv_decode(seed=41, n_layers=4, n_seq=3, min_len=600, max_len=1500, p_cache=0.6, n_steps=48)
-    eo, eh = P.make_engines(wl, poison=True, cache_slack=32, hip_kwargs=dict(general_fetch=general))
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=32,
+                            hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=adjacent))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         heads, tokens = wl.shape.n_kv_heads, wl.shape.block_tokens
@@ -731,15 +734,16 @@ def test_fetch_again_after_an_expert_fetch_on_the_same_stream(general, many_expe
 # ---- several layers in one call --------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
-@pytest.mark.parametrize("shared", [False, True])
-def test_fetch_of_several_layers_in_one_call(shared, general):
+@pytest.mark.parametrize("shared,adjacent", [(False, False), (True, False), (False, True)],
+                         ids=["k-pool-and-v-pool", "shared-pool", "k-v-adjacent"])
+def test_fetch_of_several_layers_in_one_call(shared, adjacent, general):
     say(f"multi-layer fetch, shared pool {shared}, general path {general}")
     wl = W.kv_decode(seed=24, n_layers=5, n_seq=3, min_len=300, max_len=900, n_steps=20)
     kw = {}
     if shared:
         obj = 5 * 2 * wl.shape.chunk_bytes
         kw = dict(shared_cache_bytes=(int(wl.resident.sum()) - 3) * obj, shared_granule=4096)
-    eo, eh = P.make_engines(wl, poison=True, hip_kwargs=dict(general_fetch=general), **kw)
+    eo, eh = P.make_engines(wl, poison=True, hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=adjacent), **kw)
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         for t in range(20):
@@ -895,13 +899,14 @@ def test_lossy_objects_demote_into_shared_segments():
 
 # ---- lossy objects ------------------------------------------------------------------------------------------------
 
-def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation():
+@LAYOUTS
+def test_lossy_objects_move_to_the_cache_tier_and_are_lost_on_revocation(adjacent):
     from types import SimpleNamespace
     say("lossy objects")
     chunk = 4096 + 48
     spec = SimpleNamespace(n_layers=2, n_planes=2, chunk_bytes=chunk, max_objects=8, n_host_slots=4, n_cache_slots=3,
                            n_local_slots=3, n_experts=0)
-    eo, eh = P.make_engines(kv_spec=spec, poison=True)
+    eo, eh = P.make_engines(kv_spec=spec, poison=True, hip_kwargs=dict(cache_planes_adjacent=adjacent))
     try:
         for e in (eo, eh):
             lossy = e.register(S.KV, 3, None, S.LOCAL)
