@@ -50,3 +50,16 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     assert legs["configs[2]"]["cpu_baseline"]["kind"] == "oracle" and legs["configs[3]"]["placed_per_step"] > 0
     assert out["value"] > 0 and abs(out["ms_per_step"] - 2 * out["config"]["payload_bytes_per_step"] / out["value"] / 1e6) \
         < 0.02 * out["ms_per_step"]
+
+
+@pytest.mark.gpu
+def test_latency_by_size_workload_delivers_the_same_bytes_from_either_tier():
+    print("bench latency_by_size", flush=True)
+    r = subprocess.run([sys.executable, BENCH, "--workload", "latency_by_size", "--steps", "50"], capture_output=True, text=True,
+                       timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    out = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert len(out["experts"]) == 6 and len(out["kv"]) == 6
+    for row in out["experts"] + out["kv"]:
+        assert row["same_bytes"] is True and row["host_tier_us"] > row["cache_tier_us"] > 0
+    assert out["kv"][-1]["speed_up"] > 10 and out["experts"][-1]["speed_up"] > 10      # bandwidth-bound sizes: HBM against PCIe
