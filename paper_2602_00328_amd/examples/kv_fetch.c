@@ -1,8 +1,8 @@
 /*
  * The C ABI used from plain C, with no Python and no PyTorch in the process: pools from hipMalloc and
  * harvest_pinned_alloc, a block table in device memory, and one round of the path - register, place, fetch, revoke,
- * fetch again (now from the host copies), write new bytes back, fetch them.  Every fetched byte is checked on the host
- * against the pattern its block was filled with.  Prints "kv_fetch example: ok" and exits 0 when all of it holds.
+ * fetch again (now from the host copies), write new bytes back, fetch them, and fetch them once more through the entry
+ * point that allocates nothing.  Every fetched byte is checked on the host against the pattern its block was filled with.  Prints "kv_fetch example: ok" and exits 0 when all of it holds.
  *
  *   hipcc -x hip --offload-arch=gfx950 -I include paper_2602_00328_amd/examples/kv_fetch.c -x none \
  *         -o paper_2602_00328_amd/examples/kv_fetch -L paper_2602_00328_amd -l:libharvest.so -Wl,-rpath,'$ORIGIN/..'
@@ -146,6 +146,40 @@ int main(void)
     CHECK_HIP(hipStreamSynchronize(stream));
     CHECK_HIP(hipMemcpy(k, d_k, cap * CHUNK, hipMemcpyDeviceToHost)); CHECK_HIP(hipMemcpy(v, d_v, cap * CHUNK, hipMemcpyDeviceToHost));
     if (verify(k, v, table, nb, first, 2, version, "after the write-back")) return 1;
+
+    /* the same fetch through the entry point that allocates nothing, on a stream the library has never seen: same bytes,
+     * same counts; free device memory is the same after the call as before it */
+    {
+        hipStream_t fresh;
+        CHECK_HIP(hipStreamCreate(&fresh));
+        uint8_t *d_k2, *d_v2; uint32_t *d_info, *d_miss, info[8];
+        CHECK_HIP(hipMalloc(&d_k2, cap * CHUNK)); CHECK_HIP(hipMalloc(&d_v2, cap * CHUNK));
+        CHECK_HIP(hipMalloc(&d_info, sizeof info)); CHECK_HIP(hipMalloc(&d_miss, N_SEQ * MAX_BLOCKS * sizeof(uint32_t)));
+        CHECK_HIP(hipMemset(d_k2, 0, cap * CHUNK)); CHECK_HIP(hipMemset(d_v2, 0, cap * CHUNK));
+        CHECK_HIP(hipDeviceSynchronize());
+        size_t free_before = 0, free_after = 0, total = 0;
+        CHECK_HIP(hipMemGetInfo(&free_before, &total));
+        CHECK(harvest_fetch_kv_static(h, 2, d_table, d_nb, N_SEQ, MAX_BLOCKS, d_k2, d_v2, d_first, cap, d_info, d_miss, fresh));
+        CHECK_HIP(hipStreamSynchronize(fresh));
+        CHECK_HIP(hipMemGetInfo(&free_after, &total));
+        if (free_after != free_before) { fprintf(stderr, "harvest_fetch_kv_static changed the free device memory\n"); return 1; }
+        CHECK(harvest_fetch_info(h, stream, &counts, NULL, 0, &n_miss));          /* of the fetch above, on `stream` */
+        CHECK_HIP(hipMemcpy(info, d_info, sizeof info, hipMemcpyDeviceToHost));
+        uint8_t *k2 = (uint8_t *)malloc(cap * CHUNK), *v2 = (uint8_t *)malloc(cap * CHUNK);
+        CHECK_HIP(hipMemcpy(k2, d_k2, cap * CHUNK, hipMemcpyDeviceToHost)); CHECK_HIP(hipMemcpy(v2, d_v2, cap * CHUNK, hipMemcpyDeviceToHost));
+        if (verify(k2, v2, table, nb, first, 2, version, "the fetch that allocates nothing")) return 1;
+        if (info[0] != counts.n_requests || info[2] != counts.n_cache || info[3] != counts.n_host || info[6] != n_miss) {
+            fprintf(stderr, "harvest_fetch_kv_static counted %u requests, %u cache, %u host, %u misses\n", info[0], info[2], info[3], info[6]);
+            return 1;
+        }
+        if (harvest_fetch_kv_static(h, 2, d_table, d_nb, 4096, 4096, d_k2, d_v2, d_first, cap, NULL, NULL, fresh) != HARVEST_E2BIG) {
+            fprintf(stderr, "a table beyond the fixed scratch was not refused\n");
+            return 1;
+        }
+        free(k2); free(v2);
+        CHECK_HIP(hipFree(d_k2)); CHECK_HIP(hipFree(d_v2)); CHECK_HIP(hipFree(d_info)); CHECK_HIP(hipFree(d_miss));
+        CHECK_HIP(hipStreamDestroy(fresh));
+    }
 
     harvest_stats_t st;
     CHECK(harvest_stats(h, &st));
