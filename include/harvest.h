@@ -136,7 +136,8 @@ typedef struct harvest_config {
     int32_t device;                 /* HIP device ordinal the pools live on */
     harvest_class_config cls[HARVEST_N_CLASSES];
     uint32_t gather_wg_per_cu;      /* tuning: cap the HBM-tier gather at this many workgroups per CU (they then loop
-                                       over tiles); 0 = default, one workgroup per 4 KiB tile */
+                                       over tiles, and take a request's planes one after the other); 0 = default, one workgroup
+                                       per tile of gather_threads * 16 bytes */
     uint32_t host_wgs;              /* tuning: persistent workgroups of the host-tier (PCIe) gather; 0 = default (24) */
     uint32_t shared_granule;        /* segment granule of the shared cache pool in bytes: a power of two >= 256;
                                        0 = 4096 */

@@ -14,13 +14,15 @@ import parity as P
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("general", [True, False], ids=["general path", "one-kernel path"])
-def test_captured_fetch_follows_residency_changes_across_replays(general):
+@pytest.mark.parametrize("general,adjacent", [(True, False), (True, True), (False, False)],
+                         ids=["general path", "general path, K|V adjacent in the cache tier", "one-kernel path"])
+def test_captured_fetch_follows_residency_changes_across_replays(general, adjacent):
     """Once through resolve, compaction and the two gathers, once through the single kernel that serves small tables
     (this one has 1 125 cells)."""
     print("graph capture", flush=True)
     wl = W.kv_decode(seed=11, n_layers=2, n_seq=3, min_len=2000, max_len=6000, p_cache=0.6, n_steps=1)
-    eo, eh = P.make_engines(wl, poison=True, cache_slack=64, hip_kwargs=dict(general_fetch=general))
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=64,
+                            hip_kwargs=dict(general_fetch=general, cache_planes_adjacent=adjacent))
     try:
         ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
         dev = eh.dev
