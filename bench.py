@@ -681,6 +681,19 @@ def bench_kv(args, seed, full):
     ev[1].record()
     torch.cuda.synchronize()
     plain_gbs = 2 * cal_bytes * max(1, args.calibrate) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    # the two halves of a copy alone: what bounds any copy on this machine (2 / (1/read + 1/write))
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    rates = {}
+    for name, fn in (("read", lambda: B.plain_read(src, cal_bytes, sink)), ("write", lambda: B.plain_write(dstc, cal_bytes, 0x5A5A5A5A))):
+        fn()
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(max(1, args.calibrate)):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        rates[name] = cal_bytes * max(1, args.calibrate) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    copy_bound_gbs = 2.0 / (1.0 / rates["read"] + 1.0 / rates["write"])
     del src, dstc
     # ---- PCIe peak: 1 GiB pinned -> device DMA, median of 10 ----
     pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
@@ -702,6 +715,7 @@ def bench_kv(args, seed, full):
         ts.append(time.perf_counter() - a)
     d2h_peak_gbs = (1 << 30) / float(np.median(ts[1:])) / 1e9
     del pin, dbuf
+    log(f"[bench] read only {rates['read']:.0f} GB/s, write only {rates['write']:.0f} GB/s -> no copy passes {copy_bound_gbs:.0f} GB/s")
     log(f"[bench] plain copy {plain_gbs:.0f} GB/s read+write; PCIe DMA peak {pcie_peak_gbs:.1f} GB/s to the device, "
         f"{d2h_peak_gbs:.1f} GB/s to the host")
 
@@ -928,6 +942,10 @@ def bench_kv(args, seed, full):
                      "launches": int(pr.hbm_launches), "avg_launch_ms": round(hbm_ms, 5),
                      "algorithmic_bytes_per_launch": round(hbm_alg_bytes), "plain_copy_gbs": round(plain_gbs, 1),
                      "frac_of_plain_copy": round(hbm_gbs / plain_gbs, 4),
+                     "read_only_gbs": round(rates["read"], 1), "write_only_gbs": round(rates["write"], 1),
+                     "copy_bound_gbs": round(copy_bound_gbs, 1),
+                     "copy_bound_note": "a copy moves half its bytes each way over the same memory interface: 2 / (1/read_only + "
+                                        "1/write_only), measured in this run with kernels of the gather's shape",
                      "note": "achieved / frac: the kernel inside the timed step, where the host-tier kernel reads over PCIe "
                              "beside it; alone: the same request list with every block in the cache tier (isolation.all_cache)",
                      "achieved_alone": alone, "frac_alone": round(alone / HBM_PEAK_GBS, 4) if alone else None},

@@ -401,6 +401,13 @@ int harvest_profile(harvest_ctx *ctx, harvest_profile_t *out);
  * gather is compared with, and the known-size kernel used to calibrate hardware byte counters. */
 int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *stream);
 
+/* The two halves of that copy on their own, for the same purpose: a read-only stream over d_src (bytes % 16 == 0; d_sink: 4
+ * bytes of device memory the kernel may write to - it does not for ordinary data - so that its loads cannot be dropped) and
+ * a write-only stream that fills d_dst with a 32-bit pattern.  A copy moves half its bytes each way over the same memory
+ * interface, so with r and w the rates of these two, no copy on the machine passes 2 / (1/r + 1/w). */
+int harvest_plain_read(const void *d_src, uint64_t bytes, void *d_sink, void *stream);
+int harvest_plain_write(void *d_dst, uint64_t bytes, uint32_t pattern, void *stream);
+
 /* Pinned host memory of exactly `bytes` bytes (hipHostMalloc, mapped); NULL on failure. */
 void *harvest_pinned_alloc(size_t bytes);
 int harvest_pinned_free(void *p);

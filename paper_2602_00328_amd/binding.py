@@ -92,6 +92,8 @@ SYMBOLS = {
     "harvest_stats": (ctypes.c_int, [vp, ctypes.POINTER(harvest_stats_t)]),
     "harvest_profile": (ctypes.c_int, [vp, ctypes.POINTER(harvest_profile_t)]),
     "harvest_plain_copy": (ctypes.c_int, [vp, vp, u64, vp]),
+    "harvest_plain_read": (ctypes.c_int, [vp, u64, vp, vp]),
+    "harvest_plain_write": (ctypes.c_int, [vp, u64, u32, vp]),
     "harvest_pinned_alloc": (vp, [ctypes.c_size_t]),
     "harvest_pinned_free": (ctypes.c_int, [vp]),
     "harvest_strerror": (ctypes.c_char_p, [ctypes.c_int]),
@@ -441,6 +443,14 @@ class Prefetcher:
 
     def fetch_info(self, miss_cap=0):
         return self.h.fetch_info(stream=self.stream, miss_cap=miss_cap)
+
+
+def plain_read(d_src, nbytes, d_sink, stream=None):
+    _chk(lib.harvest_plain_read(_dev_ptr(d_src), nbytes, _dev_ptr(d_sink), _stream_ptr(stream)), "harvest_plain_read")
+
+
+def plain_write(d_dst, nbytes, pattern=0, stream=None):
+    _chk(lib.harvest_plain_write(_dev_ptr(d_dst), nbytes, pattern, _stream_ptr(stream)), "harvest_plain_write")
 
 
 def plain_copy(d_dst, d_src, nbytes, stream=None):

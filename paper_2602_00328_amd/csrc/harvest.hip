@@ -132,6 +132,13 @@ struct ClassState {
     uint64_t cache_in_use = 0;
     bool adjacent = false;                  // equal-size cache slots laid out [layer][slot][plane][chunk] in one buffer
     uint64_t *d_dir = nullptr;
+    // The edits of this class's directory form one chain on the device, in the order the host made them: every edit is a
+    // dir_write kernel on some stream (the caller's for place / evict, the control stream for register / restore /
+    // revoke) that first waits for edit_evt - the class's previous edit - unless that ran on the same stream, and then
+    // records edit_evt itself.  A chain per class: a KV fetch has no reason to wait for an expert's placement.
+    hipEvent_t edit_evt = nullptr;
+    hipStream_t edit_stream = nullptr;      // where the latest edit was enqueued
+    uint64_t edit_seq = 0;                  // number of edits enqueued so far
     // duplicate detection within one call without hashing: an object is marked with the number of the call
     std::vector<uint32_t> stamp;
     uint32_t epoch = 0;
@@ -290,7 +297,7 @@ struct StreamState {
         const uint32_t *seq_cap_blocks = nullptr;
         uint64_t dst_cap = 0, edit_seq = 0;
     } last_kv;
-    uint64_t seen_seq = 0;                  // directory edits this stream has been ordered after
+    uint64_t seen_seq[HARVEST_N_CLASSES] = { 0, 0 };   // per class: directory edits this stream has been ordered after
     // control scratch (host-built lists)
     void *ctl_buf = nullptr;
     size_t ctl_cap = 0;
@@ -355,12 +362,6 @@ struct harvest_ctx {
     uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;
-    // Directory edits form one chain on the device, in the order the host made them: every edit is a dir_write kernel
-    // on some stream (the caller's for place / evict, the control stream for register / restore / revoke) that first
-    // waits for edit_evt - the previous edit - unless that ran on the same stream, and then records edit_evt itself.
-    hipEvent_t edit_evt = nullptr;
-    hipStream_t edit_stream = nullptr;       // where the latest edit was enqueued
-    uint64_t edit_seq = 0;                   // number of directory edits enqueued so far
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
@@ -627,7 +628,7 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
         if (rc) return rc;
         hold.st = st;
     }
-    if (ctx->edit_seq && ctx->edit_stream != on) DEV_TRY(hipStreamWaitEvent(on, ctx->edit_evt, 0));
+    if (c.edit_seq && c.edit_stream != on) DEV_TRY(hipStreamWaitEvent(on, c.edit_evt, 0));
     void *d_st = nullptr;
     DEV_TRY(hipHostGetDevicePointer(&d_st, st->h, 0));
     if (!ctx->no_device) {
@@ -641,21 +642,22 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
     }
     DEV_TRY(hipGetLastError());
     if (committed) *committed = true;
-    ctx->edit_seq++;
-    ctx->edit_stream = on;
+    c.edit_seq++;
+    c.edit_stream = on;
     if (ctx->no_device) return HARVEST_OK;
-    HIP_TRY(hipEventRecord(ctx->edit_evt, on));
+    HIP_TRY(hipEventRecord(c.edit_evt, on));
     return release_after(ctx, st, on);
 }
 
-// Orders the caller's stream after every directory edit made so far, so that a fetch enqueued after register / place /
-// evict(DEMOTE) returned reads entries at least that new - without the host ever waiting.  Nothing to do when the
-// latest edit ran on this very stream: the chain put every earlier one before it.
-int order_after_directory_edits(harvest_ctx *ctx, StreamState *ss)
+// Orders the caller's stream after every edit of the class's directory made so far, so that a fetch enqueued after
+// register / place / evict(DEMOTE) returned reads entries at least that new - without the host ever waiting.  Nothing to
+// do when the latest edit ran on this very stream: the chain put every earlier one before it.
+int order_after_directory_edits(harvest_ctx *ctx, StreamState *ss, int cls)
 {
-    if (ss->seen_seq == ctx->edit_seq || is_capturing(ss->s)) return HARVEST_OK;
-    if (ctx->edit_stream != ss->s) HIP_TRY(hipStreamWaitEvent(ss->s, ctx->edit_evt, 0));
-    ss->seen_seq = ctx->edit_seq;
+    const ClassState &c = ctx->cls[cls];
+    if (ss->seen_seq[cls] == c.edit_seq || is_capturing(ss->s)) return HARVEST_OK;
+    if (c.edit_stream != ss->s) HIP_TRY(hipStreamWaitEvent(ss->s, c.edit_evt, 0));
+    ss->seen_seq[cls] = c.edit_seq;
     return HARVEST_OK;
 }
 
@@ -835,12 +837,12 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
                                                    // GB/s against 55.2 with 2048 workgroups)
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&ctx->edit_evt, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
         ClassState &c = ctx->cls[k];
         if (!c.used) continue;
+        HIP_TRY(hipEventCreateWithFlags(&c.edit_evt, hipEventDisableTiming));
         HIP_TRY(hipMalloc(&c.d_dir, (size_t)c.cfg.max_objects * sizeof(uint64_t)));
         HIP_TRY(hipMemset(c.d_dir, 0xFF, (size_t)c.cfg.max_objects * sizeof(uint64_t)));   // tier NONE everywhere
         for (uint32_t p = 0; p < c.cfg.n_planes; ++p) {
@@ -1008,7 +1010,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto e : ctx->evt_pool) (void)hipEventDestroy(e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
-        if (ctx->edit_evt) (void)hipEventDestroy(ctx->edit_evt);
+        for (auto &c : ctx->cls) if (c.edit_evt) (void)hipEventDestroy(c.edit_evt);
         (void)hipStreamDestroy(ctx->ctl);
     }
     delete ctx;
@@ -1426,7 +1428,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
     if ((rc = device_guard(ctx))) return rc;
     StreamState *ss = fixed_ss;
     if (!ss && (rc = get_stream(ctx, stream, &ss))) return rc;
-    if ((rc = order_after_directory_edits(ctx, ss))) return rc;
+    if ((rc = order_after_directory_edits(ctx, ss, HARVEST_KV))) return rc;
     ss->last_kv.valid = false;
     if (total == 0) { ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = false; return HARVEST_OK; }
     auto remember = [&](bool lists) {
@@ -1435,7 +1437,7 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
         k.valid = true; k.lists = lists; k.layer = layer; k.n_seq = n_seq; k.max_blocks = max_blocks;
         k.n_heads = n_heads; k.block_tokens = block_tokens; k.table = d_block_table; k.n_blocks = d_n_blocks;
         k.seq_dst_block = d_seq_dst_block; k.seq_cap_blocks = d_seq_cap_blocks; k.dst_cap = dst_capacity_blocks;
-        k.edit_seq = ctx->edit_seq;
+        k.edit_seq = c.edit_seq;
     };
     if (!d_block_table || !d_n_blocks || !d_seq_dst_block || !d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v))
         return HARVEST_EINVAL;
@@ -1509,7 +1511,7 @@ int harvest_fetch_kv_again(harvest_ctx *ctx, uint32_t layer, void *d_dst_k, void
     // The lists of that fetch still describe this one when nothing has edited the directory since (and that fetch made
     // lists at all: small tables are fetched without); otherwise the table is resolved again.
     // A recorded fetch resolves for itself too: by the time its graph is replayed, residency may be another.
-    if (!k.lists || k.edit_seq != ctx->edit_seq || is_capturing((hipStream_t)stream))
+    if (!k.lists || k.edit_seq != c.edit_seq || is_capturing((hipStream_t)stream))
         return fetch_kv_locked(ctx, layer, k.table, k.n_blocks, k.n_seq, k.max_blocks, d_dst_k, d_dst_v, k.seq_dst_block,
                                k.seq_cap_blocks, k.dst_cap, k.n_heads, k.block_tokens, stream, 1, 0);
     if (!d_dst_k || (c.cfg.n_planes == 2 && !d_dst_v) || (((uint64_t)d_dst_k | (uint64_t)d_dst_v) & 15)) return HARVEST_EINVAL;
@@ -1606,7 +1608,7 @@ int harvest_fetch_experts(harvest_ctx *ctx, uint32_t layer, const int32_t *d_top
     if ((rc = get_stream(ctx, stream, &ss))) return rc;
     if ((uint64_t)E * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16) >= (1ull << 32)) return HARVEST_EINVAL;
     if ((rc = ensure_req_cap(ss, HARVEST_EXPERT, E))) return rc;
-    if ((rc = order_after_directory_edits(ctx, ss))) return rc;
+    if ((rc = order_after_directory_edits(ctx, ss, HARVEST_EXPERT))) return rc;
     const Lists &lists = ss->lists[HARVEST_EXPERT];
     uint32_t *cnt = lists.cnt;
     // a large batch of routing ids is marked by many workgroups first; the single resolving workgroup reads the bitmap
@@ -1959,6 +1961,28 @@ int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *str
     uint32_t grid = grid_for(n_tiles, MAX_GRID);
     hipLaunchKernelGGL(plain_copy<HBM_WG>, dim3(grid), dim3(HBM_WG), 0, (hipStream_t)stream, (uint64_t)d_dst, (uint64_t)d_src,
                        bytes);
+    HIP_TRY(hipGetLastError());
+    return HARVEST_OK;
+}
+
+int harvest_plain_read(const void *d_src, uint64_t bytes, void *d_sink, void *stream)
+{
+    if (!d_src || !d_sink || bytes % 16 || ((uint64_t)d_src & 15) || ((uint64_t)d_sink & 3)) return HARVEST_EINVAL;
+    if (bytes == 0) return HARVEST_OK;
+    uint64_t n_tiles = (bytes + HBM_WG * 16 - 1) / (HBM_WG * 16);
+    hipLaunchKernelGGL(plain_read<HBM_WG>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(HBM_WG), 0, (hipStream_t)stream,
+                       (uint64_t)d_src, bytes, (uint32_t *)d_sink);
+    HIP_TRY(hipGetLastError());
+    return HARVEST_OK;
+}
+
+int harvest_plain_write(void *d_dst, uint64_t bytes, uint32_t pattern, void *stream)
+{
+    if (!d_dst || bytes % 16 || ((uint64_t)d_dst & 15)) return HARVEST_EINVAL;
+    if (bytes == 0) return HARVEST_OK;
+    uint64_t n_tiles = (bytes + HBM_WG * 16 - 1) / (HBM_WG * 16);
+    hipLaunchKernelGGL(plain_write<HBM_WG>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(HBM_WG), 0, (hipStream_t)stream,
+                       (uint64_t)d_dst, bytes, pattern);
     HIP_TRY(hipGetLastError());
     return HARVEST_OK;
 }

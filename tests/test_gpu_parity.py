@@ -455,7 +455,9 @@ def test_two_threads_drive_one_context():
 def test_a_revocation_waits_without_holding_up_the_other_thread():
     """The expert thread places several large experts (milliseconds of PCIe traffic queued on its stream) and at once
     revokes others, which has to wait for that queue to drain; the KV thread keeps fetching on its own stream meanwhile.
-    The wait happens outside the context's lock: fetch calls start and return while the revocation is still waiting."""
+    The wait happens outside the context's lock: fetch calls start and return while the revocation is still waiting.
+    And each class orders its fetches after its own directory edits only: the KV fetches complete while the experts'
+    placements - whose new entries are published behind their copies - are still in flight."""
     import threading
     import time
     import torch
@@ -489,8 +491,9 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
                     while not stop.is_set():
                         a = time.perf_counter()
                         eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
-                        calls.append((a, time.perf_counter()))
+                        b = time.perf_counter()
                         kv_stream.synchronize()
+                        calls.append((a, b, time.perf_counter()))
             except BaseException as e:
                 errors.append(e)
 
@@ -507,13 +510,71 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
         assert not th.is_alive() and not errors, errors
         assert (st == 0).all() and len(revoked) == len(cached) - len(cached) // 2
         inside = [c for c in calls if c[0] > window[0] and c[1] < window[1]]
-        say(f"  the revocation waited {1e3 * (window[1] - window[0]):.1f} ms; {len(inside)} KV fetch calls ran inside it")
-        assert window[1] - window[0] > 2e-3 and len(inside) >= 3
+        from conftest import live
+        live(f"  the revocation waited {1e3 * (window[1] - window[0]):.1f} ms; {len(inside)} KV fetch calls ran inside it")
+        live("  KV calls (start, returned, stream idle; ms after the revocation began): " + " ".join(
+            f"({1e3 * (c[0] - a):.2f} {1e3 * (c[1] - a):.2f} {1e3 * (c[2] - a):.2f})" for c in calls if a < c[2] < window[1])[:400])
+        # One call that took the lock and returned inside the window shows that the lock was free during the wait. How many
+        # fit depends on the device: the KV fetch's host-tier reads share PCIe with the placements, and in a process that has
+        # made many streams the two streams can share a hardware queue (alone, this test sees ~25 calls inside).
+        assert window[1] - window[0] > 2e-3 and len(inside) >= 1
         # and nothing is wrong afterwards
         assert np.array_equal(eo.place(S.EXPERT, on_host[:n_place]), st)
         eo.revoke(S.EXPERT, cached[len(cached) // 2:])
         P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "kv after the overlap")
         P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts after the overlap")
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
+def test_a_kv_fetch_does_not_wait_for_the_experts_directory_edits():
+    """Directory edits are ordered per class. The expert stream is held up by a sleeping kernel with a placement (copies,
+    then the directory write that publishes them) queued behind it; a KV fetch on the other stream completes while that
+    kernel still sleeps. Skipped when the device runs the two streams through one hardware queue."""
+    import torch
+    say("a KV fetch while the experts' directory edits are pending")
+    wl = W.kv_decode(seed=31, n_layers=1, n_seq=2, min_len=300, max_len=600, n_steps=1)
+    ex = W.expert_offload(seed=31, shape=W.ExpertShape(n_layers=1, n_experts=8, d_model=256, d_ff=512), n_local=0)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        cached = sorted(xh.live)
+        for e in (eo, eh):
+            e.revoke(S.EXPERT, cached[:2])
+        P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "kv before")         # every stream's scratch exists from here on
+        kv_stream, x_stream = eh.streams[S.KV], eh.streams[S.EXPERT]
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(x_stream):
+            t0.record(); torch.cuda._sleep(20_000_000); t1.record()
+        torch.cuda.synchronize()
+        cycles = int(20_000_000 * 60.0 / max(t0.elapsed_time(t1), 1e-3))   # about 60 ms
+        flag = torch.zeros(64, dtype=torch.uint8, device=eh.dev)
+        still = torch.cuda.Event()
+        with torch.cuda.stream(x_stream):
+            torch.cuda._sleep(cycles); still.record()
+        with torch.cuda.stream(kv_stream):
+            flag.fill_(1)
+        kv_stream.synchronize()
+        independent = not still.query()
+        torch.cuda.synchronize()
+        if not independent:
+            pytest.skip("the two streams share a hardware queue in this process")
+        with torch.cuda.stream(x_stream):
+            torch.cuda._sleep(cycles)
+        st = eh.place(S.EXPERT, cached[:2])                                # queued behind the sleeping kernel
+        still = torch.cuda.Event()
+        with torch.cuda.stream(x_stream):
+            still.record()
+        got = rh.fetch(0)                                                  # returns with the KV stream idle
+        pending = not still.query()
+        torch.cuda.synchronize()
+        assert pending, "the KV fetch waited for the expert class's directory edits"
+        assert np.array_equal(eo.place(S.EXPERT, cached[:2]), st)
+        P.assert_kv_equal(ro.fetch(0), got, "kv during")
+        P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts after")
         P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
     finally:
         eh.close(); eo.close()
@@ -964,6 +1025,17 @@ def test_plain_copy_and_profile_counters():
         assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
     with pytest.raises(B.HarvestError):
         B.plain_copy(dst, src, 24)
+    # the two halves of the copy on their own: the write fills exactly its range, the read touches nothing
+    for n in (16, 1024 + 16, 5 * 32768, (1 << 20) + 48):
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        B.plain_write(dst, n, 0x04030201)
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.plain_read(dst, n, sink)
+        torch.cuda.synchronize()
+        want = torch.tensor([1, 2, 3, 4], dtype=torch.uint8, device="cuda").repeat(n // 4)
+        assert torch.equal(dst[:n], want) and int(dst[n:].sum()) == 0 and int(sink[0]) == 0
+    with pytest.raises(B.HarvestError):
+        B.plain_write(dst, 24)
 
 
 def test_smoke_entry():
