@@ -945,7 +945,7 @@ def bench_kv(args, seed, full):
                      "read_only_gbs": round(rates["read"], 1), "write_only_gbs": round(rates["write"], 1),
                      "copy_bound_gbs": round(copy_bound_gbs, 1),
                      "copy_bound_note": "a copy moves half its bytes each way over the same memory interface: 2 / (1/read_only + "
-                                        "1/write_only), measured in this run with kernels of the gather's shape",
+                                        "1/write_only), both measured in this run (one 16-byte access per thread; 1024-thread workgroups for the reads, 256 for the writes: one-wavefront workgroups with a single access each are bound by the dispatcher, not by memory)",
                      "note": "achieved / frac: the kernel inside the timed step, where the host-tier kernel reads over PCIe "
                              "beside it; alone: the same request list with every block in the cache tier (isolation.all_cache)",
                      "achieved_alone": alone, "frac_alone": round(alone / HBM_PEAK_GBS, 4) if alone else None},

@@ -1967,10 +1967,11 @@ int harvest_plain_copy(void *d_dst, const void *d_src, uint64_t bytes, void *str
 
 int harvest_plain_read(const void *d_src, uint64_t bytes, void *d_sink, void *stream)
 {
+    constexpr int NTHR = 1024;
     if (!d_src || !d_sink || bytes % 16 || ((uint64_t)d_src & 15) || ((uint64_t)d_sink & 3)) return HARVEST_EINVAL;
     if (bytes == 0) return HARVEST_OK;
-    uint64_t n_tiles = (bytes + HBM_WG * 16 - 1) / (HBM_WG * 16);
-    hipLaunchKernelGGL(plain_read<HBM_WG>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(HBM_WG), 0, (hipStream_t)stream,
+    uint64_t n_tiles = (bytes + NTHR * 16 - 1) / (NTHR * 16);
+    hipLaunchKernelGGL(plain_read<NTHR>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(NTHR), 0, (hipStream_t)stream,
                        (uint64_t)d_src, bytes, (uint32_t *)d_sink);
     HIP_TRY(hipGetLastError());
     return HARVEST_OK;
@@ -1978,10 +1979,11 @@ int harvest_plain_read(const void *d_src, uint64_t bytes, void *d_sink, void *st
 
 int harvest_plain_write(void *d_dst, uint64_t bytes, uint32_t pattern, void *stream)
 {
+    constexpr int NTHR = 256;
     if (!d_dst || bytes % 16 || ((uint64_t)d_dst & 15)) return HARVEST_EINVAL;
     if (bytes == 0) return HARVEST_OK;
-    uint64_t n_tiles = (bytes + HBM_WG * 16 - 1) / (HBM_WG * 16);
-    hipLaunchKernelGGL(plain_write<HBM_WG>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(HBM_WG), 0, (hipStream_t)stream,
+    uint64_t n_tiles = (bytes + NTHR * 16 - 1) / (NTHR * 16);
+    hipLaunchKernelGGL(plain_write<NTHR>, dim3(grid_for(n_tiles, MAX_GRID)), dim3(NTHR), 0, (hipStream_t)stream,
                        (uint64_t)d_dst, bytes, pattern);
     HIP_TRY(hipGetLastError());
     return HARVEST_OK;

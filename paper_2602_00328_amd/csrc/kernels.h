@@ -955,8 +955,10 @@ __global__ __launch_bounds__(NTHR) void plain_copy(uint64_t dst, uint64_t src, u
     }
 }
 
-// Read-only and write-only streams of the same shape (one wavefront per workgroup, one non-temporal 16-byte access per
-// thread): what the memory system delivers in each direction alone, from which the bound of any copy follows.
+// Read-only and write-only streams (one non-temporal 16-byte access per thread): what the memory system delivers in each
+// direction alone, from which the bound of any copy follows.  With one-wavefront workgroups these two measure the
+// dispatcher instead (one access per workgroup: 4.8 TB/s, 4.7 G workgroups/s), so the host launches them with the
+// workgroup size that was measured fastest: 1024 threads for reads (7.5 TB/s), 256 for writes (6.7 TB/s).
 template <int NTHR>
 __global__ __launch_bounds__(NTHR) void plain_read(uint64_t src, uint64_t bytes, uint32_t *sink)
 {
