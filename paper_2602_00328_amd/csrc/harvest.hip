@@ -9,6 +9,9 @@
 //                 ran, so edits reach the device in the order the host made them (paper Section 3.2: revocation is
 //                 ordered).  Placements and write-backs edit on the caller's stream, right behind their copy;
 //                 register, restore and revoke, which have no caller stream, edit on the library's control stream.
+//                 Each class has a chain of its own.
+//   drain       - a revocation's waits for the other streams, and the poisoning behind them, run on a third kind of
+//                 stream, so that the control stream never holds an edit up behind a drain.
 #include "../../include/harvest.h"
 #include "kernels.h"
 #include <hip/hip_ext.h>
@@ -361,7 +364,9 @@ struct harvest_ctx {
     uint32_t gather_threads = HBM_WG;     // threads per workgroup of the HBM-tier gather (64, 128 or 256)
     uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
-    hipStream_t ctl = nullptr;
+    hipStream_t ctl = nullptr;            // directory edits that have no caller stream (register, restore, revoke)
+    hipStream_t drain = nullptr;          // the waits of the revocation drain and the poisoning behind them: kept off `ctl`, so
+                                          // that no directory edit ever queues up behind a drain
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
@@ -837,6 +842,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
                                                    // GB/s against 55.2 with 2048 workgroups)
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
+    HIP_TRY(hipStreamCreateWithFlags(&ctx->drain, hipStreamNonBlocking));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
@@ -1001,6 +1007,7 @@ int harvest_destroy(harvest_ctx *ctx)
             (void)hipStreamSynchronize(ss->side);
         }
         (void)hipStreamSynchronize(ctx->ctl);
+        if (ctx->drain) (void)hipStreamSynchronize(ctx->drain);
         for (auto &kv : ctx->streams) free_stream_state(kv.second.get());
         for (int i = 0; i < ctx->n_fixed_streams; ++i) (void)hipStreamSynchronize(ctx->fixed_streams[i].s);
         for (StreamState &ss : ctx->fixed_streams) free_stream_state(&ss);
@@ -1011,7 +1018,8 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
         for (auto &c : ctx->cls) if (c.edit_evt) (void)hipEventDestroy(c.edit_evt);
-        (void)hipStreamDestroy(ctx->ctl);
+        if (ctx->ctl) (void)hipStreamDestroy(ctx->ctl);
+        if (ctx->drain) (void)hipStreamDestroy(ctx->drain);
     }
     delete ctx;
     return HARVEST_OK;
@@ -1208,7 +1216,7 @@ int harvest_place_from(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     return place_impl(ctx, cls, ids, n, &from, stream, status);
 }
 
-// Enqueues the poisoning of the given cache slots on the control stream (the list travels through `st`).
+// Enqueues the poisoning of the given cache slots on the drain stream (the list travels through `st`).
 static int enqueue_poison(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &slots, Staging *st)
 {
     std::vector<Item> items;
@@ -1220,17 +1228,17 @@ static int enqueue_poison(harvest_ctx *ctx, ClassState &c, const std::vector<uin
     HIP_TRY(hipHostGetDevicePointer(&d_items, st->h, 0));
     const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
     if (tiles_hbm < (1ull << 32)) {
-        hipLaunchKernelGGL(fill_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ctx->ctl,
+        hipLaunchKernelGGL(fill_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, ctx->drain,
                            (const Item *)d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
                            tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16), 0xA5A5A5A5u);
     } else {
         uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
         uint32_t grid = grid_for((uint64_t)items.size() * tpc, ctx->ctl_grid);
-        hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->ctl, (const Item *)d_items, (uint32_t)items.size(),
+        hipLaunchKernelGGL(fill_items, dim3(grid), dim3(WG), 0, ctx->drain, (const Item *)d_items, (uint32_t)items.size(),
                            c.cfg.chunk_bytes, tpc, 0xA5A5A5A5u);
     }
     HIP_TRY(hipGetLastError());
-    return release_after(ctx, st, ctx->ctl);
+    return release_after(ctx, st, ctx->drain);
 }
 
 // Revocation (paper Section 3.2).  The context's lock is held while the directory changes and while work is enqueued, and
@@ -1300,15 +1308,16 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         if (committed) undo.commit();
         if (rc) return rc;
         if (!ctx->no_device) {
-            // 2. the drain: the control stream waits for everything the library has enqueued so far on every stream that
+            // 2. the drain: a stream of its own waits for everything the library has enqueued so far on every stream that
             // could still read the slots (each stream's latest work is an event; the waits take the events as they are
             // now, later calls on those streams do not move them), then poisons the slots - in stream order, so after the
-            // drain - and records the event the host waits on.  Work recorded into graphs is invisible to those events:
-            // then the host waits for the whole device, and the poisoning comes after that wait.
+            // drain - and records the event the host waits on.  Fetches enqueued from now on need no waiting for: they are
+            // ordered after the invalidation above by the class's edit chain.  Work recorded into graphs is invisible to
+            // those events: then the host waits for the whole device, and the poisoning comes after that wait.
             for (auto &kv : ctx->streams)
-                if (kv.second->last_valid) HIP_TRY(hipStreamWaitEvent(ctx->ctl, kv.second->last, 0));
+                if (kv.second->last_valid) HIP_TRY(hipStreamWaitEvent(ctx->drain, kv.second->last, 0));
             for (int i = 0; i < ctx->n_fixed_streams; ++i)
-                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipStreamWaitEvent(ctx->ctl, ctx->fixed_streams[i].last, 0));
+                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipStreamWaitEvent(ctx->drain, ctx->fixed_streams[i].last, 0));
             whole_device = ctx->captured_work;
             if (ctx->poison && !whole_device) {
                 if ((rc = enqueue_poison(ctx, c, old_slot, h_fill.st))) return rc;
@@ -1316,7 +1325,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
                 st_fill = h_fill.st;               // stays held until the second phase
                 h_fill.st = nullptr;
             }
-            HIP_TRY(hipEventRecord(drained, ctx->ctl));
+            HIP_TRY(hipEventRecord(drained, ctx->drain));
         }
         put_back.armed = false;                    // from here on the event is returned by hand, after the wait
     }
@@ -1335,7 +1344,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             if (st_fill->held) st_fill->held = false;
             if (rc) return rc;
             lk.unlock();
-            HIP_TRY(hipStreamSynchronize(ctx->ctl));
+            HIP_TRY(hipStreamSynchronize(ctx->drain));
             lk.lock();
         }
         // 3. free
@@ -1910,6 +1919,7 @@ int harvest_stats(harvest_ctx *ctx, harvest_stats_t *out)
         int rc = device_guard(ctx);
         if (rc) return rc;
         for (auto &kv : ctx->streams) HIP_TRY(hipStreamSynchronize(kv.second->s));
+        for (int i = 0; i < ctx->n_fixed_streams; ++i) HIP_TRY(hipStreamSynchronize(ctx->fixed_streams[i].s));
         HIP_TRY(hipMemcpy(h, ctx->d_totals, sizeof h, hipMemcpyDeviceToHost));
     }
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
