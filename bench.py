@@ -808,8 +808,18 @@ def bench_kv(args, seed, full):
                 n += 1
             res[threads] = 2 * step_payload * n / (time.perf_counter() - a) / 1e9
         if full:
+            # what one core's memcpy moves on this host (read+write, as every figure here): the oracle's single-thread
+            # figure is that, scattered
+            big = np.ones(1 << 28, dtype=np.uint8)
+            into = np.empty_like(big)
+            np.copyto(into, big)
+            a = time.perf_counter()
+            for _ in range(8):
+                np.copyto(into, big)
+            memcpy_gbs = 2 * 8 * big.nbytes / (time.perf_counter() - a) / 1e9
+            del big, into
             cpu_baseline = {"value": round(res[ncores], 2), "unit": "GB/s", "cores": ncores, "kind": "oracle",
-                            "single_thread_value": round(res[1], 2),
+                            "single_thread_value": round(res[1], 2), "host_memcpy_gbs_one_thread": round(memcpy_gbs, 2),
                             "sample": f"the same decode state, one layer's full fetch ({want[3]['n_requests']} blocks, "
                                       f"{step_payload / 2**30:.2f} GiB payload) repeated for >= 6 s per thread count, "
                                       "all tiers in host DRAM"}
