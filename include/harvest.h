@@ -145,7 +145,10 @@ typedef struct harvest_config {
                                        many cells (n_seq * max_blocks); 0 = default (4096) */
     uint32_t gather_threads;        /* tuning: threads per workgroup of the HBM-tier gather, 64, 128 or 256; 0 = default
                                        (64: one wavefront per workgroup, 1 KiB tiles) */
-    uint32_t reserved[3];           /* must be 0 */
+    uint32_t pcie_wgs;              /* tuning: persistent workgroups of the copies that cross PCIe outside a fetch (place,
+                                       write-back), each with one 32 KiB tile in flight; 0 = default (12: enough to fill the link
+                                       when alone, few enough that a fetch on another stream keeps most of it) */
+    uint32_t reserved[2];           /* must be 0 */
     void *d_shared_cache;           /* optional shared cache pool (device memory, 256-byte aligned), see below */
     uint64_t shared_cache_bytes;    /* its size: a multiple of the granule, at most 2^30 granules */
 } harvest_config;

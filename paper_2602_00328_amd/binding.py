@@ -37,7 +37,7 @@ class harvest_class_config(ctypes.Structure):
 
 class harvest_config(ctypes.Structure):
     _fields_ = [("flags", u32), ("device", i32), ("cls", harvest_class_config * 2),
-                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("small_fetch_cells", u32), ("gather_threads", u32), ("reserved", u32 * 3),
+                ("gather_wg_per_cu", u32), ("host_wgs", u32), ("shared_granule", u32), ("small_fetch_cells", u32), ("gather_threads", u32), ("pcie_wgs", u32), ("reserved", u32 * 2),
                 ("d_shared_cache", vp), ("shared_cache_bytes", u64)]
 
 
@@ -163,7 +163,7 @@ class Harvest:
 
     def __init__(self, kv: ClassSpec | None = None, expert: ClassSpec | None = None, flags: int = 0, device: int = 0,
                  gather_wg_per_cu: int = 0, host_wgs: int = 0, shared_cache_bytes: int = 0, shared_granule: int = 0,
-                 small_fetch_cells: int = 0, gather_threads: int = 0):
+                 small_fetch_cells: int = 0, gather_threads: int = 0, pcie_wgs: int = 0):
         """shared_cache_bytes > 0: one device pool of that size from which every class with n_cache_slots == 0 carves
         its cache-tier segments (best-fit)."""
         self.flags, self.device = flags, device
@@ -180,6 +180,7 @@ class Harvest:
         cfg.gather_wg_per_cu, cfg.host_wgs = gather_wg_per_cu, host_wgs
         cfg.small_fetch_cells = small_fetch_cells
         cfg.gather_threads = gather_threads
+        cfg.pcie_wgs = pcie_wgs
         adjacent = bool(flags & FLAG_CACHE_PLANES_ADJACENT)
         cfg.shared_cache_bytes, cfg.shared_granule = shared_cache_bytes, shared_granule
         self.shared_cache = None

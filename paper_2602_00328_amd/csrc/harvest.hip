@@ -839,8 +839,14 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->host_grid = cfg->host_wgs ? cfg->host_wgs : 24;
     ctx->gather_threads = cfg->gather_threads ? cfg->gather_threads : HBM_WG;
     ctx->ctl_grid = 8 * ctx->n_cu;                 // HBM-bound fills
-    ctx->pcie_grid = 64;                           // copies that cross PCIe: a few dozen CUs saturate the link (place 56.6
-                                                   // GB/s against 55.2 with 2048 workgroups)
+    // Copies that cross PCIe outside a fetch (place, write-back): persistent workgroups with one 32 KiB tile in flight
+    // each.  Alone, 8 of them already fill the link (a 906 MB placement: 15.9 ms = 57 GB/s with 8, 12, 16 or 64; 19.5 ms
+    // with 4); what the number decides is who gets the link when a fetch on another stream wants it too - the link
+    // serves its clients by what they have in flight.  Beside a PCIe-bound KV fetch of 1.04 ms, a placement with 64
+    // workgroups makes that fetch take 12.6 ms, with 16: 2.1 ms, with 12: 1.6 ms, with 8: 1.3 ms.  A miss waits on
+    // the link, where its transfer contends with whatever else crosses it (paper Section 2.2), and a placement is best
+    // effort (Section 3.1), so the copies run narrow.
+    ctx->pcie_grid = cfg->pcie_wgs ? cfg->pcie_wgs : 12;
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
     HIP_TRY(hipStreamCreateWithFlags(&ctx->drain, hipStreamNonBlocking));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));

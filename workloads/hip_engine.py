@@ -22,7 +22,7 @@ class HipEngine:
     name = "hip"
 
     def __init__(self, kv=None, expert=None, poison=False, device=0, profile=False, gather_wg_per_cu=0, host_wgs=0,
-                 two_streams=False, shared_cache_bytes=0, shared_granule=0, general_fetch=False, gather_threads=0,
+                 two_streams=False, shared_cache_bytes=0, shared_granule=0, general_fetch=False, gather_threads=0, pcie_wgs=0,
                  cache_planes_adjacent=False):
         """two_streams: KV work and expert work are enqueued on two HIP streams of their own (default priority).
         shared_cache_bytes: one cache pool for every class that has no cache slots of its own."""
@@ -34,7 +34,7 @@ class HipEngine:
         self.streams = {k: (torch.cuda.Stream(self.dev) if two_streams else None) for k in (KV, EXPERT)}
         self.h = B.Harvest(kv=kv, expert=expert, flags=flags, device=device, gather_wg_per_cu=gather_wg_per_cu,
                            host_wgs=host_wgs, shared_cache_bytes=shared_cache_bytes, shared_granule=shared_granule,
-                           gather_threads=gather_threads)
+                           gather_threads=gather_threads, pcie_wgs=pcie_wgs)
         self._dst = {}
 
     def _on(self, cls):
