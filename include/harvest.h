@@ -33,6 +33,10 @@
  *     revoke / evict(DEMOTE) / register are visible to every fetch enqueued
  *     after the call returns (place: on the same stream; other streams may
  *     still see the older, equally correct, host entry for a while).
+ *     harvest_register / restore / revoke have no stream argument; their directory edit runs on a stream of the
+ *     library - or, while the class's previous edit (a placement, say) is still queued on the caller stream it was
+ *     made on, right behind it on that stream, so that no stream of the library ever waits for a caller's.  The
+ *     host-side waits of harvest_revoke are waits of the calling thread only.
  *   - Return value: HARVEST_OK (0) or a negative harvest_status.  A fetch never
  *     fails because of residency (Section 3.1: what the cache tier holds or
  *     has lost changes no result).

@@ -10,8 +10,8 @@
 //                 ordered).  Placements and write-backs edit on the caller's stream, right behind their copy;
 //                 register, restore and revoke, which have no caller stream, edit on the library's control stream.
 //                 Each class has a chain of its own.
-//   drain       - a revocation's waits for the other streams, and the poisoning behind them, run on a third kind of
-//                 stream, so that the control stream never holds an edit up behind a drain.
+//   drain       - a revocation waits for the other streams' work on the host (it blocks anyway); no library stream is ever
+//                 parked behind a caller's stream.  The poisoning that follows runs on a stream of its own.
 #include "../../include/harvest.h"
 #include "kernels.h"
 #include <hip/hip_ext.h>
@@ -365,8 +365,8 @@ struct harvest_ctx {
     uint64_t small_cells = 0;             // block tables up to this many cells are fetched by one kernel
     ClassState cls[HARVEST_N_CLASSES];
     hipStream_t ctl = nullptr;            // directory edits that have no caller stream (register, restore, revoke)
-    hipStream_t drain = nullptr;          // the waits of the revocation drain and the poisoning behind them: kept off `ctl`, so
-                                          // that no directory edit ever queues up behind a drain
+    hipStream_t drain = nullptr;          // the poisoning of revoked slots (hundreds of MiB at times): kept off `ctl`, so that no
+                                          // directory edit queues up behind it
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
@@ -632,6 +632,16 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
         int rc = acquire_staging(ctx, bytes, &st);
         if (rc) return rc;
         hold.st = st;
+    }
+    // An edit that has no caller stream (register, restore, revoke: on == the control stream) whose predecessor is still
+    // queued on a caller's stream goes onto that stream, right behind it, instead of making the control stream wait: a
+    // wait parked on a library stream occupies one of the device's few hardware queues for as long as the awaited work
+    // takes (a placement of some hundred MiB: milliseconds), and a caller stream that HIP happens to map to the same
+    // queue stands still meanwhile.  (Not onto a stream that is being recorded into a graph: then the control stream waits.)
+    if (on == ctx->ctl && c.edit_seq && c.edit_stream != ctx->ctl && !ctx->no_device && !is_capturing(c.edit_stream)) {
+        hipError_t q = hipEventQuery(c.edit_evt);
+        if (q == hipErrorNotReady) on = c.edit_stream;
+        else if (q != hipSuccess) HIP_TRY(q);
     }
     if (c.edit_seq && c.edit_stream != on) DEV_TRY(hipStreamWaitEvent(on, c.edit_evt, 0));
     void *d_st = nullptr;
@@ -1068,7 +1078,7 @@ int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_
     if ((rc = publish(ctx, c, ids, ctx->ctl))) return rc;
     // Later fetches are ordered after this edit on their own streams; only replays of recorded graphs, which the library
     // does not see, need the entry to be there before this call returns.
-    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
+    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipEventSynchronize(c.edit_evt));
     return HARVEST_OK;
 }
 
@@ -1094,7 +1104,7 @@ int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t 
         c.gen[id] += 1;
     }
     if ((rc = publish(ctx, c, changed, ctx->ctl))) return rc;
-    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipStreamSynchronize(ctx->ctl));
+    if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipEventSynchronize(c.edit_evt));
     return HARVEST_OK;
 }
 
@@ -1251,6 +1261,13 @@ static int enqueue_poison(harvest_ctx *ctx, ClassState &c, const std::vector<uin
 // released while the host waits for the drain: the thread that drives another stream keeps enqueuing meanwhile.  What
 // keeps that safe: the revoked objects already read HOST (mirror and, in stream order, device), so nothing new is pointed
 // at their slots, and the slots return to the allocator only after the wait, so nobody else is given them.
+//
+// The drain is a wait of the host, not of a stream: this call blocks anyway, and a wait parked on a library stream
+// would occupy one of the device's few hardware queues until the slowest caller stream has caught up - long enough for
+// a caller stream that HIP maps to the same queue to stand still behind it (seen: KV fetches on one stream held up for
+// the 7 ms of a placement queued on another).  Each stream's "latest work" event is taken out of the stream's state and
+// replaced by a fresh one, so the event the host then waits on is nobody else's: later calls on that stream record the
+// new event, and destroying a prefetcher's stream state meanwhile does not touch the one being waited on.
 static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, bool notify)
 {
     int rc = check_class(ctx, cls);
@@ -1260,7 +1277,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     std::vector<uint32_t> old_slot;
     std::vector<std::pair<harvest_revoke_cb, void *>> cbs;
     ClassState &c = ctx->cls[cls];
-    hipEvent_t drained = nullptr;
+    std::vector<hipEvent_t> waits;             // the latest work of every stream, as of the invalidation
     bool whole_device = false;
     Staging *st_fill = nullptr;
     {
@@ -1268,32 +1285,42 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         for (uint32_t i = 0; i < n; ++i) if (ids[i] >= c.n_objects) return HARVEST_ENOENT;
         if ((rc = device_guard(ctx))) return rc;
         // the drain waits for streams: impossible while one of them is being recorded into a graph
+        std::vector<StreamState *> busy;       // the streams with work the drain has to wait for
         if (!ctx->no_device) {
-            for (auto &kv : ctx->streams)
+            for (auto &kv : ctx->streams) {
                 if (is_capturing(kv.first)) return HARVEST_EINVAL;
-            for (int i = 0; i < ctx->n_fixed_streams; ++i)
+                if (kv.second->last_valid) busy.push_back(kv.second.get());
+            }
+            for (int i = 0; i < ctx->n_fixed_streams; ++i) {
                 if (is_capturing(ctx->fixed_streams[i].s)) return HARVEST_EINVAL;
+                if (ctx->fixed_streams[i].last_valid) busy.push_back(&ctx->fixed_streams[i]);
+            }
         }
         size_t n_hit = 0;
         c.new_call();
         for (uint32_t i = 0; i < n; ++i) n_hit += c.tier[ids[i]] == T_CACHE && c.first_time(ids[i]);
         if (n_hit == 0) return HARVEST_OK;
         // what the call may have to allocate comes before any change: staging for the new entries and for the poison
-        // list, the event the host will wait on
+        // list, one fresh event per stream that has work in flight
         Hold h_dir, h_fill;
         if ((rc = acquire_staging(ctx, n_hit * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
         if (ctx->poison &&
             (rc = acquire_staging(ctx, n_hit * c.cfg.n_planes * c.cfg.n_layers * sizeof(Item), &h_fill.st)))
             return rc;
         if (fault_due()) return HARVEST_EHIP;
-        if (!ctx->no_device) {
-            if (!ctx->evt_pool.empty()) { drained = ctx->evt_pool.back(); ctx->evt_pool.pop_back(); }
-            else HIP_TRY(hipEventCreateWithFlags(&drained, hipEventDisableTiming));
-        }
-        struct PutBack {                       // the event goes back to the pool on every early return
-            harvest_ctx *ctx; hipEvent_t e; bool armed;
-            ~PutBack() { if (armed && e) ctx->evt_pool.push_back(e); }
-        } put_back{ ctx, drained, true };
+        whole_device = ctx->captured_work;
+        std::vector<hipEvent_t> fresh;
+        struct PutBack {                       // unused events go back to the pool on every return
+            harvest_ctx *ctx; std::vector<hipEvent_t> &v;
+            ~PutBack() { for (hipEvent_t e : v) ctx->evt_pool.push_back(e); }
+        } put_back{ ctx, fresh };
+        if (!whole_device)
+            for (size_t i = 0; i < busy.size(); ++i) {
+                hipEvent_t e = nullptr;
+                if (!ctx->evt_pool.empty()) { e = ctx->evt_pool.back(); ctx->evt_pool.pop_back(); }
+                else HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                fresh.push_back(e);
+            }
         // 1. invalidate
         Undo undo(c);
         for (uint32_t i = 0; i < n; ++i) {
@@ -1313,39 +1340,35 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         rc = publish(ctx, c, hit, ctx->ctl, h_dir.st, &committed);
         if (committed) undo.commit();
         if (rc) return rc;
-        if (!ctx->no_device) {
-            // 2. the drain: a stream of its own waits for everything the library has enqueued so far on every stream that
-            // could still read the slots (each stream's latest work is an event; the waits take the events as they are
-            // now, later calls on those streams do not move them), then poisons the slots - in stream order, so after the
-            // drain - and records the event the host waits on.  Fetches enqueued from now on need no waiting for: they are
-            // ordered after the invalidation above by the class's edit chain.  Work recorded into graphs is invisible to
-            // those events: then the host waits for the whole device, and the poisoning comes after that wait.
-            for (auto &kv : ctx->streams)
-                if (kv.second->last_valid) HIP_TRY(hipStreamWaitEvent(ctx->drain, kv.second->last, 0));
-            for (int i = 0; i < ctx->n_fixed_streams; ++i)
-                if (ctx->fixed_streams[i].last_valid) HIP_TRY(hipStreamWaitEvent(ctx->drain, ctx->fixed_streams[i].last, 0));
-            whole_device = ctx->captured_work;
-            if (ctx->poison && !whole_device) {
-                if ((rc = enqueue_poison(ctx, c, old_slot, h_fill.st))) return rc;
-            } else if (ctx->poison) {
-                st_fill = h_fill.st;               // stays held until the second phase
-                h_fill.st = nullptr;
+        // 2. the drain, first half: everything the library has enqueued so far on every stream that could still read the
+        // slots is what each stream's latest-work event stands for; those events are taken now (later calls on the
+        // streams get the fresh ones) and waited for below, with the lock released.  Fetches enqueued from now on need no
+        // waiting for: they are ordered after the invalidation above by the class's edit chain.  Work recorded into
+        // graphs is invisible to those events: then the host waits for the whole device.
+        if (!whole_device)
+            for (StreamState *ss : busy) {
+                waits.push_back(ss->last);
+                ss->last = fresh.back();
+                fresh.pop_back();
+                ss->last_valid = false;
             }
-            HIP_TRY(hipEventRecord(drained, ctx->drain));
+        if (ctx->poison && !ctx->no_device) {      // stays held until the slots are poisoned, after the wait
+            st_fill = h_fill.st;
+            h_fill.st = nullptr;
         }
-        put_back.armed = false;                    // from here on the event is returned by hand, after the wait
     }
     if (!ctx->no_device) {
         hipError_t e = whole_device ? hipDeviceSynchronize() : hipSuccess;
-        if (e == hipSuccess) e = hipEventSynchronize(drained);
+        for (hipEvent_t w : waits)
+            if (e == hipSuccess) e = hipEventSynchronize(w);
         std::unique_lock<std::mutex> lk(ctx->mu);
-        ctx->evt_pool.push_back(drained);
+        for (hipEvent_t w : waits) ctx->evt_pool.push_back(w);
         if (e != hipSuccess) {                     // the slots stay out of the allocator: nobody may be given them
             if (st_fill) st_fill->held = false;
             fprintf(stderr, "libharvest: the revocation drain failed: %s\n", hipGetErrorString(e));
             return HARVEST_EHIP;
         }
-        if (st_fill) {                             // recorded work: poison now, after the wait for the whole device
+        if (st_fill) {                             // debug aid: overwrite the slots, now that nothing reads them
             rc = enqueue_poison(ctx, c, old_slot, st_fill);
             if (st_fill->held) st_fill->held = false;
             if (rc) return rc;

@@ -104,3 +104,26 @@ def smoke():
         finally:
             eh.close()
             eo.close()
+
+
+def streams_run_independently(dev, a, b, ms=30.0):
+    """True if work on stream b completes while stream a is still busy: a sleeping kernel of about `ms` on a, a tiny fill
+    on b.  False when the device runs the two streams one after the other (HIP has a few hardware queues - 4 here - and
+    streams that map to the same one take turns)."""
+    import torch
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(a):
+        t0.record(); torch.cuda._sleep(20_000_000); t1.record()
+    torch.cuda.synchronize()
+    cycles = int(20_000_000 * ms / max(t0.elapsed_time(t1), 1e-3))
+    flag = torch.zeros(64, dtype=torch.uint8, device=dev)
+    still = torch.cuda.Event()
+    with torch.cuda.stream(a):
+        torch.cuda._sleep(cycles); still.record()
+    with torch.cuda.stream(b):
+        flag.fill_(1)
+    b.synchronize()
+    independent = not still.query()
+    torch.cuda.synchronize()
+    return independent, cycles

@@ -483,7 +483,7 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
         kv_stream = eh.streams[S.KV]
         with torch.cuda.stream(kv_stream):
             eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)          # the stream's scratch exists from here on
-        torch.cuda.synchronize()
+        independent, _ = P.streams_run_independently(dev, eh.streams[S.EXPERT], kv_stream)
         window, calls, looks, stop, errors = [], [], [], threading.Event(), []
 
         def kv_side():
@@ -526,15 +526,18 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
         inside = [c for c in calls if c[0] > window[0] and c[1] < window[1]]
         looks_inside = [c for c in looks if c[0] > window[0] and c[1] < window[1]]
         from conftest import live
+        live(f"  (the device runs the two streams independently: {independent})")
         live(f"  the revocation waited {1e3 * (window[1] - window[0]):.1f} ms; inside it {len(looks_inside)} lookups and "
              f"{len(inside)} KV fetch calls started and returned")
         live("  KV calls (start, returned, stream idle; ms after the revocation began): " + " ".join(
             f"({1e3 * (c[0] - a):.2f} {1e3 * (c[1] - a):.2f} {1e3 * (c[2] - a):.2f})" for c in calls if a < c[2])[:400])
-        # Calls that took the lock and returned inside the window show that the lock was free during the wait.  The lookups
-        # are the measure: they need the lock and nothing of the device.  How many KV fetches fit as well depends on the
-        # device - their host-tier reads share PCIe with the placements, and in a process that has made many streams the
-        # two streams can share a hardware queue (alone, this test sees ~25 of them inside, after other tests sometimes 1).
+        # Calls that took the lock and returned inside the window show that the lock was free during the wait: the lookups
+        # need the lock and nothing of the device.  The KV fetches also need the device to run their stream while the
+        # other one is busy - which it does as long as no stream of the library sits waiting in a hardware queue that the
+        # KV stream shares (the drain is a wait of the host for that reason): they take their usual 0.15 ms each.
         assert window[1] - window[0] > 2e-3 and len(looks_inside) >= 5
+        if independent:
+            assert len(inside) >= 3
         # and nothing is wrong afterwards
         assert np.array_equal(eo.place(S.EXPERT, on_host[:n_place]), st)
         eo.revoke(S.EXPERT, cached[len(cached) // 2:])
@@ -563,20 +566,7 @@ def test_a_kv_fetch_does_not_wait_for_the_experts_directory_edits():
         P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "kv before")         # every stream's scratch exists from here on
         kv_stream, x_stream = eh.streams[S.KV], eh.streams[S.EXPERT]
         torch.cuda.synchronize()
-        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        with torch.cuda.stream(x_stream):
-            t0.record(); torch.cuda._sleep(20_000_000); t1.record()
-        torch.cuda.synchronize()
-        cycles = int(20_000_000 * 60.0 / max(t0.elapsed_time(t1), 1e-3))   # about 60 ms
-        flag = torch.zeros(64, dtype=torch.uint8, device=eh.dev)
-        still = torch.cuda.Event()
-        with torch.cuda.stream(x_stream):
-            torch.cuda._sleep(cycles); still.record()
-        with torch.cuda.stream(kv_stream):
-            flag.fill_(1)
-        kv_stream.synchronize()
-        independent = not still.query()
-        torch.cuda.synchronize()
+        independent, cycles = P.streams_run_independently(eh.dev, x_stream, kv_stream, ms=60.0)
         if not independent:
             pytest.skip("the two streams share a hardware queue in this process")
         with torch.cuda.stream(x_stream):
