@@ -850,12 +850,13 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->gather_threads = cfg->gather_threads ? cfg->gather_threads : HBM_WG;
     ctx->ctl_grid = 8 * ctx->n_cu;                 // HBM-bound fills
     // Copies that cross PCIe outside a fetch (place, write-back): persistent workgroups with one 32 KiB tile in flight
-    // each.  Alone, 8 of them already fill the link (a 906 MB placement: 15.9 ms = 57 GB/s with 8, 12, 16 or 64; 19.5 ms
-    // with 4); what the number decides is who gets the link when a fetch on another stream wants it too - the link
-    // serves its clients by what they have in flight.  Beside a PCIe-bound KV fetch of 1.04 ms, a placement with 64
-    // workgroups makes that fetch take 12.6 ms, with 16: 2.1 ms, with 12: 1.6 ms, with 8: 1.3 ms.  A miss waits on
-    // the link, where its transfer contends with whatever else crosses it (paper Section 2.2), and a placement is best
-    // effort (Section 3.1), so the copies run narrow.
+    // each, the tiles counted out to them one at a time.  Alone, 8 of them already fill the link (a 906 MB placement:
+    // 15.9 ms = 57 GB/s with 8, 12, 16 or 64; 19.5 ms with 4); what the number decides is who gets the link when a fetch on
+    // another stream wants it too - the link serves its clients by what they have in flight.  Beside a stream of
+    // PCIe-bound KV fetches of 1.04 ms each, a placement with 64 workgroups makes a fetch take 12.6 ms, with 16: 1.8 ms,
+    // with 12: 1.5 ms (and the placement 48 ms), with 8: 1.3 ms (70 ms).  A miss waits on the link, where its transfer
+    // contends with whatever else crosses it (paper Section 2.2), and a placement is best effort (Section 3.1), so the
+    // copies run narrow.
     ctx->pcie_grid = cfg->pcie_wgs ? cfg->pcie_wgs : 12;
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
     HIP_TRY(hipStreamCreateWithFlags(&ctx->drain, hipStreamNonBlocking));
@@ -1154,8 +1155,8 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
     const size_t max_items = (size_t)n * c.cfg.n_planes * c.cfg.n_layers;
     Hold h_items, h_dir;
     if (n) {
-        if ((rc = ensure_ctl_cap(ctx, ss, max_items * sizeof(Item)))) return rc;
-        if ((rc = acquire_staging(ctx, max_items * sizeof(Item), &h_items.st))) return rc;
+        if ((rc = ensure_ctl_cap(ctx, ss, LIST_HEADER + max_items * sizeof(Item)))) return rc;
+        if ((rc = acquire_staging(ctx, LIST_HEADER + max_items * sizeof(Item), &h_items.st))) return rc;
         if ((rc = acquire_staging(ctx, (size_t)n * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
     }
     Undo undo(c);
@@ -1188,21 +1189,25 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
         st_all[i] = st;
     }
     if (!moved.empty()) {
-        size_t bytes = items.size() * sizeof(Item);
-        if (!ctx->no_device) memcpy(h_items.st->h, items.data(), bytes);
+        size_t bytes = LIST_HEADER + items.size() * sizeof(Item);
+        if (!ctx->no_device) {
+            memset(h_items.st->h, 0, LIST_HEADER);         // the copy kernel's tile counter
+            memcpy((char *)h_items.st->h + LIST_HEADER, items.data(), items.size() * sizeof(Item));
+        }
         DEV_TRY(hipMemcpyAsync(ss->ctl_buf, h_items.st->h, bytes, hipMemcpyHostToDevice, s));
         if ((rc = release_after(ctx, h_items.st, s))) return rc;
         if (!ctx->no_device) {
+            const Item *d_items = (const Item *)((char *)ss->ctl_buf + LIST_HEADER);
             const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
             if (from && tiles_hbm < (1ull << 32)) {        // HBM to HBM: a workgroup per 1 KiB tile, as in the gather
                 hipLaunchKernelGGL(copy_items_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, s,
-                                   (const Item *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                                   d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
                                    tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
-            } else {                                       // over PCIe: a few dozen persistent workgroups
+            } else {                                       // over PCIe: a dozen persistent workgroups, tiles counted out
                 uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
                 uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);
-                hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, s, (const Item *)ss->ctl_buf, (uint32_t)items.size(),
-                                   c.cfg.chunk_bytes, tpc);
+                hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, s, d_items, (uint32_t)items.size(),
+                                   c.cfg.chunk_bytes, tpc, from ? (unsigned long long *)nullptr : (unsigned long long *)ss->ctl_buf);
             }
         }
         DEV_TRY(hipGetLastError());
@@ -1850,8 +1855,8 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     const uint32_t l0 = layer < 0 ? 0 : (uint32_t)layer, l1 = layer < 0 ? c.cfg.n_layers : (uint32_t)layer + 1;
     const size_t max_items = (size_t)n * c.cfg.n_planes * (l1 - l0);
     Hold h_items, h_dir;
-    if ((rc = ensure_ctl_cap(ctx, ss, max_items * sizeof(Item2)))) return rc;
-    if ((rc = acquire_staging(ctx, max_items * sizeof(Item2), &h_items.st))) return rc;
+    if ((rc = ensure_ctl_cap(ctx, ss, LIST_HEADER + max_items * sizeof(Item2)))) return rc;
+    if ((rc = acquire_staging(ctx, LIST_HEADER + max_items * sizeof(Item2), &h_items.st))) return rc;
     if (n_demote && (rc = acquire_staging(ctx, n_demote * (sizeof(uint64_t) + sizeof(uint32_t)), &h_dir.st))) return rc;
     const uint64_t src[2] = { (uint64_t)d_src0, (uint64_t)d_src1 };
     std::vector<Item2> items;
@@ -1903,23 +1908,27 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
         }
     }
     if (!items.empty()) {
-        size_t bytes = items.size() * sizeof(Item2);
-        if (!ctx->no_device) memcpy(h_items.st->h, items.data(), bytes);
+        size_t bytes = LIST_HEADER + items.size() * sizeof(Item2);
+        if (!ctx->no_device) {
+            memset(h_items.st->h, 0, LIST_HEADER);         // the copy kernel's tile counter
+            memcpy((char *)h_items.st->h + LIST_HEADER, items.data(), items.size() * sizeof(Item2));
+        }
         DEV_TRY(hipMemcpyAsync(ss->ctl_buf, h_items.st->h, bytes, hipMemcpyHostToDevice, s));
         if ((rc = release_after(ctx, h_items.st, s))) return rc;
         if (!ctx->no_device) {
+            const Item2 *d_items = (const Item2 *)((char *)ss->ctl_buf + LIST_HEADER);
             bool to_host = false;                          // lossy objects move between HBM pools only
             for (const Item2 &it : items) to_host |= it.dst0 != 0;
             const uint64_t tiles_hbm = (uint64_t)items.size() * tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16);
             if (!to_host && tiles_hbm < (1ull << 32)) {
                 hipLaunchKernelGGL(copy_items2_hbm<HBM_WG>, dim3(grid_for(tiles_hbm, MAX_GRID)), dim3(HBM_WG), 0, s,
-                                   (const Item2 *)ss->ctl_buf, (uint32_t)items.size(), c.cfg.chunk_bytes,
+                                   d_items, (uint32_t)items.size(), c.cfg.chunk_bytes,
                                    tiles_per_chunk(c.cfg.chunk_bytes, HBM_WG * 16));
             } else {
                 uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
                 uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
-                hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, s, (const Item2 *)ss->ctl_buf,
-                                   (uint32_t)items.size(), c.cfg.chunk_bytes, tpc);
+                hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, s, d_items, (uint32_t)items.size(),
+                                   c.cfg.chunk_bytes, tpc, to_host ? (unsigned long long *)ss->ctl_buf : (unsigned long long *)nullptr);
             }
         }
         DEV_TRY(hipGetLastError());

@@ -797,25 +797,48 @@ __global__ __launch_bounds__(WG) void gather_hm_host(const Rec *__restrict__ rec
 // ---------------------------------------------------------------------------------------------------------
 // Host-built lists (absolute addresses).
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
-                                                 uint32_t tiles_per_chunk)
+constexpr size_t LIST_HEADER = 16;       // a host-built list travels behind this many bytes, the first 8 of them the
+                                         // zeroed tile counter of the kernel that walks it
+// The tiles of a persistent copy.  next == nullptr: workgroup b takes tiles b, b + grid, b + 2 grid, ...  Otherwise the
+// tiles are counted out one at a time from *next (zero at launch): when something else is using the link as well, the
+// workgroups of one launch progress at very different rates (a 3.4-fold spread was measured), and with fixed shares
+// the launch ends with a few workgroups working off their backlog alone - a 906 MB placement beside a stream of
+// fetches took 106 ms that way.  Every thread of the workgroup gets the same tile number and leaves the loop together.
+template <typename F>
+__device__ inline void for_each_tile(unsigned long long *next, uint64_t n_tiles, F body)
 {
-    uint64_t n_tiles = (uint64_t)n_items * tiles_per_chunk;
-    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    if (!next) {
+        for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) body(t);
+        return;
+    }
+    __shared__ unsigned long long s_tile;
+    for (;;) {
+        if (threadIdx.x == 0) s_tile = atomicAdd(next, 1ull);
+        __syncthreads();
+        const uint64_t t = s_tile;
+        __syncthreads();                          // all have read it before thread 0 writes the next one
+        if (t >= n_tiles) return;
+        body(t);
+    }
+}
+
+__global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
+                                                 uint32_t tiles_per_chunk, unsigned long long *next)
+{
+    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, [&](uint64_t t) {
         uint64_t it = t / tiles_per_chunk;
         uint64_t off = (t - it * tiles_per_chunk) * TILE_HOST;
         Item x = items[it];
         copy_tile<WG, UNROLL_HOST, false>(x.src + off, x.dst + off, chunk_bytes - off, threadIdx.x);
-    }
+    });
 }
 
 // One source, one or two destinations (dst == 0: none): the write-back path reads each source byte once.
 __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ items, uint32_t n_items,
-                                                  uint64_t chunk_bytes, uint32_t tiles_per_chunk)
+                                                  uint64_t chunk_bytes, uint32_t tiles_per_chunk, unsigned long long *next)
 {
     constexpr uint32_t TILE = TILE_HOST;
-    uint64_t n_tiles = (uint64_t)n_items * tiles_per_chunk;
-    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, [&](uint64_t t) {
         uint64_t it = t / tiles_per_chunk;
         uint64_t off = (t - it * tiles_per_chunk) * TILE;
         Item2 x = items[it];
@@ -844,7 +867,7 @@ __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ item
                 if (x.dst1) st16<false>(d1 + i, v);
             }
         }
-    }
+    });
 }
 
 __global__ __launch_bounds__(WG) void fill_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
