@@ -362,6 +362,15 @@ int harvest_prefetch_issue(harvest_prefetcher *pf, uint32_t layer, const int32_t
 int harvest_prefetch_acquire(harvest_prefetcher *pf, void *compute_stream, void **d_staging, void ***d_expert_ptr);
 int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream);
 
+/* Forgets a caller stream: waits for what the library has enqueued on it, then frees the scratch lists, the side stream and
+ * the events the context keeps for it - or, for a stream served by harvest_fetch_kv_static, gives its fixed state back,
+ * so that another stream can take it.  For applications that create and destroy streams while a context lives: call it
+ * before destroying the stream (a new stream that happens to get the same handle later simply starts afresh).  The next
+ * call on the stream sets its state up again, with the allocations of a first call.  ENOENT: the context has no state for
+ * this stream; EINVAL: the stream is being recorded into a graph, or belongs to a prefetcher (harvest_prefetcher_destroy
+ * releases that one).  Must not run concurrently with another call that uses the same stream. */
+int harvest_release_stream(harvest_ctx *ctx, void *stream);
+
 /* Synchronises `stream` and reports the last fetch enqueued on it: its counts and its miss list (requests served
  * from host or lost: KV request numbers r, or expert numbers e; order unspecified).  miss_idx may be NULL; at most
  * miss_cap entries are written, *n_miss receives the full count. */

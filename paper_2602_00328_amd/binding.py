@@ -74,6 +74,7 @@ SYMBOLS = {
     "harvest_alloc": (ctypes.c_int, [vp, ctypes.c_int, u32, vp]),
     "harvest_free": (ctypes.c_int, [vp, ctypes.c_int, u32]),
     "harvest_register_cb": (ctypes.c_int, [vp, ctypes.c_int, u32, REVOKE_CB, vp]),
+    "harvest_release_stream": (ctypes.c_int, [vp, vp]),
     "harvest_fetch_kv": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp]),
     "harvest_fetch_kv_static": (ctypes.c_int, [vp, u32, vp, vp, u32, u32, vp, vp, vp, u64, vp, vp, vp]),
     "harvest_fetch_kv_again": (ctypes.c_int, [vp, u32, vp, vp, vp]),
@@ -358,6 +359,9 @@ class Harvest:
         _chk(lib.harvest_fetch_experts(self.h, layer, _dev_ptr(d_topk), n_tokens, k, _dev_ptr(d_staging),
                                        n_staging_slots, _dev_ptr(d_expert_ptr), _stream_ptr(stream)),
              "harvest_fetch_experts")
+
+    def release_stream(self, stream=None):
+        _chk(lib.harvest_release_stream(self.h, _stream_ptr(stream)), "harvest_release_stream")
 
     def fetch_info(self, stream=None, miss_cap=0, cls=None):
         """cls: the latest fetch of that class on the stream (harvest_fetch_info_of); None: the latest fetch."""

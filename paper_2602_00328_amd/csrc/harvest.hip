@@ -1777,6 +1777,51 @@ int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream)
     return HARVEST_OK;
 }
 
+int harvest_release_stream(harvest_ctx *ctx, void *stream)
+{
+    if (!ctx) return HARVEST_EINVAL;
+    if (ctx->no_device) return HARVEST_ENODEV;
+    int rc = device_guard(ctx);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (is_capturing(s)) return HARVEST_EINVAL;
+    std::unique_ptr<StreamState> gone;
+    bool found = false;
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        for (harvest_prefetcher *pf : ctx->prefetchers)
+            if (pf->fetch == s) return HARVEST_EINVAL;
+        auto it = ctx->streams.find(s);
+        if (it != ctx->streams.end()) {
+            gone = std::move(it->second);          // out of the map: no later call, no revocation sees it any more
+            ctx->streams.erase(it);
+            found = true;
+        }
+        for (int i = 0; i < ctx->n_fixed_streams; ++i) {
+            StreamState &f = ctx->fixed_streams[i];
+            if (f.s != s) continue;
+            // the fixed state keeps its event, its feedback words and its place in the device's fixed scratch; only what
+            // ties it to this stream is reset, and the last state in use moves into the gap
+            HIP_TRY(hipStreamSynchronize(s));
+            f.s = nullptr;
+            f.last_valid = false; f.last_cls = -1; f.last_kv.valid = false;
+            for (int k = 0; k < HARVEST_N_CLASSES; ++k) { f.counted[k] = false; f.feedback_valid[k] = false; f.seen_seq[k] = 0; }
+            std::swap(f, ctx->fixed_streams[ctx->n_fixed_streams - 1]);
+            ctx->n_fixed_streams--;
+            found = true;
+            break;
+        }
+    }
+    if (!found) return HARVEST_ENOENT;
+    if (gone) {                                    // the waits run with the lock released
+        hipError_t e = hipStreamSynchronize(gone->s);
+        if (e == hipSuccess) e = hipStreamSynchronize(gone->side);
+        free_stream_state(gone.get());
+        if (e != hipSuccess) return HARVEST_EHIP;
+    }
+    return HARVEST_OK;
+}
+
 int harvest_fetch_info_of(harvest_ctx *ctx, void *stream, int cls, harvest_fetch_counts *counts, uint32_t *miss_idx,
                           uint32_t miss_cap, uint32_t *n_miss)
 {

@@ -79,6 +79,7 @@ def test_data_calls_refuse_to_run_without_a_device():
     rc = B.lib.harvest_fetch_experts(h.h, 0, None, 1, 1, None, 0, None, None)
     assert rc == B.ENODEV
     assert B.lib.harvest_fetch_info(h.h, None, None, None, 0, None) == B.ENODEV
+    assert B.lib.harvest_release_stream(h.h, None) == B.ENODEV
     h.close()
 
 

@@ -587,6 +587,45 @@ def test_a_kv_fetch_does_not_wait_for_the_experts_directory_edits():
         eh.close(); eo.close()
 
 
+def test_a_released_stream_starts_afresh():
+    """harvest_release_stream frees what the context keeps for a caller stream; the next call on the stream sets it up
+    again and fetches the same bytes; a prefetcher's stream is not the caller's to release."""
+    import torch
+    from paper_2602_00328_amd import binding as B
+    say("release of a stream's state")
+    wl = W.kv_decode(seed=33, n_layers=2, n_seq=3, min_len=9000, max_len=20000, n_steps=1)
+    ex = W.expert_offload(seed=33, shape=W.ExpertShape(n_layers=1, n_experts=8, d_model=256, d_ff=512), n_local=1)
+    eo, eh = P.make_engines(wl, ex, two_streams=True)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        want = ro.fetch(1)
+        P.assert_kv_equal(want, rh.fetch(1), "before the release")
+        P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts before")
+        kv_stream = eh.streams[S.KV]
+        eh.h.release_stream(kv_stream)
+        with pytest.raises(B.HarvestError) as e:
+            eh.h.fetch_info(stream=kv_stream, cls=S.KV)
+        assert e.value.code == B.ENOENT
+        with pytest.raises(B.HarvestError) as e:
+            eh.h.release_stream(kv_stream)
+        assert e.value.code == B.ENOENT
+        with pytest.raises(B.HarvestError) as e:                   # no single-layer fetch to repeat any more
+            with torch.cuda.stream(kv_stream):
+                d = torch.zeros(16, dtype=torch.uint8, device=eh.dev)
+                eh.h.fetch_kv_again(0, d, d)
+        assert e.value.code == B.EINVAL
+        P.assert_kv_equal(want, rh.fetch(1), "after the release")
+        # a revocation between two uses of a released and re-made stream state still drains what is in flight
+        a, b = ro.revoke_quarter(0), rh.revoke_quarter(0)
+        assert np.array_equal(a[0], b[0])
+        P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "after a revocation")
+        P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts after")
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- head-major working layout ----------------------------------------------------------------------------------
 
 @LAYOUTS

@@ -57,6 +57,9 @@ def test_double_buffered_prefetch_against_layer_by_layer_oracle_fetches():
             if i == 13:
                 assert np.array_equal(xo.replace_revoked(), xh.replace_revoked())
         counts, miss, n_miss = pf.fetch_info(miss_cap=E)          # synchronises the fetch stream: the last layer's fetch
+        with pytest.raises(B.HarvestError) as e:                  # the ring's stream is the ring's to release
+            eh.h.release_stream(pf.stream)
+        assert e.value.code == B.EINVAL
         torch.cuda.synchronize()
         # the oracle, layer by layer, for the residency at the end (bytes do not depend on residency; pointers of
         # staged experts depend only on the routed set)

@@ -130,6 +130,38 @@ def test_static_fetch_refuses_tables_beyond_its_fixed_scratch():
         eh.close(); eo.close()
 
 
+def test_static_fetch_serves_four_streams_and_a_released_state_goes_to_the_next():
+    from paper_2602_00328_amd import binding as B
+    say("fetch without allocation: four streams per context, release")
+    wl = W.kv_decode(seed=64, n_layers=1, n_seq=2, min_len=3000, max_len=6000, p_cache=0.6, n_steps=1)
+    eo, eh = P.make_engines(wl, hip_kwargs=dict(general_fetch=True))
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        args = _device_args(eh, rh)
+        streams = [torch.cuda.Stream(eh.dev) for _ in range(5)]
+        for st in streams[:4]:
+            with torch.cuda.stream(st):
+                _compare_one(eh, eo, 0, args, rh.cap, "one of four streams", stream=st)
+        table, nb, sdb, d_table, d_nb, d_sdb = args
+        dst = [torch.zeros(rh.cap * eh.spec[S.KV].chunk_bytes, dtype=torch.uint8, device=eh.dev) for _ in range(2)]
+        with pytest.raises(B.HarvestError) as e:
+            eh.h.fetch_kv_static(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap, stream=streams[4])
+        assert e.value.code == B.EBUSY
+        eh.h.release_stream(streams[1])                    # its fixed state is free again ...
+        with pytest.raises(B.HarvestError) as e:
+            eh.h.release_stream(streams[1])
+        assert e.value.code == B.ENOENT
+        with torch.cuda.stream(streams[4]):                # ... and the fifth stream takes it
+            _compare_one(eh, eo, 0, args, rh.cap, "fifth stream after a release", stream=streams[4])
+        with torch.cuda.stream(streams[3]):                # the state that moved into the gap still serves its stream
+            _compare_one(eh, eo, 0, args, rh.cap, "fourth stream after the release", stream=streams[3])
+        with pytest.raises(B.HarvestError) as e:
+            eh.h.fetch_kv_static(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap, stream=streams[1])
+        assert e.value.code == B.EBUSY
+    finally:
+        eh.close(); eo.close()
+
+
 def test_static_fetch_recorded_into_a_graph_with_no_earlier_call_on_the_stream():
     say("fetch without allocation: graph capture on a fresh stream")
     wl = W.kv_decode(seed=63, n_layers=2, n_seq=3, min_len=9000, max_len=30000, p_cache=0.6, n_steps=2)
