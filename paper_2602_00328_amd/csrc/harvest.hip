@@ -142,6 +142,9 @@ struct ClassState {
     hipEvent_t edit_evt = nullptr;
     hipStream_t edit_stream = nullptr;      // where the latest edit was enqueued
     uint64_t edit_seq = 0;                  // number of edits enqueued so far
+    uint64_t must_seq = 0;                  // edit_seq after the latest edit that every later fetch has to see (register,
+                                            // restore, revoke, demotion); a placement is not one: until it is seen, the
+                                            // older entry names the host copy, which holds the same bytes
     // duplicate detection within one call without hashing: an object is marked with the number of the call
     std::vector<uint32_t> stamp;
     uint32_t epoch = 0;
@@ -619,8 +622,8 @@ ClassDev class_dev(const ClassState &c)
 // directory edit, wherever that ran.  pre: a staging block of n * 12 bytes taken earlier, so that this step cannot fail
 // for want of one.  *committed (if given) says whether the dir_write was enqueued: from then on the device will apply
 // the edit, and a failure reported by a later step no longer entitles the caller to roll its mirror back.
-int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipStream_t on, Staging *pre = nullptr,
-            bool *committed = nullptr)
+int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, hipStream_t on, bool must_see,
+            Staging *pre = nullptr, bool *committed = nullptr)
 {
     if (committed) *committed = ids.empty();
     if (ids.empty()) return HARVEST_OK;
@@ -659,18 +662,21 @@ int publish(harvest_ctx *ctx, ClassState &c, const std::vector<uint32_t> &ids, h
     if (committed) *committed = true;
     c.edit_seq++;
     c.edit_stream = on;
+    if (must_see) c.must_seq = c.edit_seq;
     if (ctx->no_device) return HARVEST_OK;
     HIP_TRY(hipEventRecord(c.edit_evt, on));
     return release_after(ctx, st, on);
 }
 
-// Orders the caller's stream after every edit of the class's directory made so far, so that a fetch enqueued after
-// register / place / evict(DEMOTE) returned reads entries at least that new - without the host ever waiting.  Nothing to
-// do when the latest edit ran on this very stream: the chain put every earlier one before it.
+// Orders the caller's stream after the edits of the class's directory that a fetch enqueued now has to see - every
+// registration, restore, revocation and demotion made so far - without the host ever waiting.  Placements alone are
+// not waited for: a fetch is on the critical path and a placement is best effort (it may sit behind hundreds of MiB of
+// copies on another stream), and until its entry is seen the older one names the host copy, which holds the same bytes.
+// Nothing to do either when the latest edit ran on this very stream: the chain put every earlier one before it.
 int order_after_directory_edits(harvest_ctx *ctx, StreamState *ss, int cls)
 {
     const ClassState &c = ctx->cls[cls];
-    if (ss->seen_seq[cls] == c.edit_seq || is_capturing(ss->s)) return HARVEST_OK;
+    if (ss->seen_seq[cls] >= c.must_seq || is_capturing(ss->s)) return HARVEST_OK;
     if (c.edit_stream != ss->s) HIP_TRY(hipStreamWaitEvent(ss->s, c.edit_evt, 0));
     ss->seen_seq[cls] = c.edit_seq;
     return HARVEST_OK;
@@ -1076,7 +1082,7 @@ int harvest_register(harvest_ctx *ctx, int cls, uint32_t n, const int64_t *host_
         c.slot.push_back(s);
         if (out_ids) out_ids[i] = id;
     }
-    if ((rc = publish(ctx, c, ids, ctx->ctl))) return rc;
+    if ((rc = publish(ctx, c, ids, ctx->ctl, true))) return rc;
     // Later fetches are ordered after this edit on their own streams; only replays of recorded graphs, which the library
     // does not see, need the entry to be there before this call returns.
     if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipEventSynchronize(c.edit_evt));
@@ -1104,7 +1110,7 @@ int harvest_restore(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t 
         c.tier[id] = T_LOCAL;
         c.gen[id] += 1;
     }
-    if ((rc = publish(ctx, c, changed, ctx->ctl))) return rc;
+    if ((rc = publish(ctx, c, changed, ctx->ctl, true))) return rc;
     if (!ctx->no_device && ctx->captured_work) HIP_TRY(hipEventSynchronize(c.edit_evt));
     return HARVEST_OK;
 }
@@ -1214,7 +1220,7 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
         // the new entries are written on the same stream, behind the copy: visible only once the bytes are in the slot,
         // and before anything enqueued on `stream` later
         bool committed = false;
-        rc = publish(ctx, c, moved, s, h_dir.st, &committed);
+        rc = publish(ctx, c, moved, s, false, h_dir.st, &committed);
         if (committed) undo.commit();
         if (rc) return rc;
         if (!ctx->no_device && (rc = mark_last(ctx, ss))) return rc;
@@ -1342,7 +1348,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
             cbs.push_back({ c.cb[id], c.cb_user[id] });
         }
         bool committed = false;
-        rc = publish(ctx, c, hit, ctx->ctl, h_dir.st, &committed);
+        rc = publish(ctx, c, hit, ctx->ctl, true, h_dir.st, &committed);
         if (committed) undo.commit();
         if (rc) return rc;
         // 2. the drain, first half: everything the library has enqueued so far on every stream that could still read the
@@ -1837,10 +1843,15 @@ int harvest_fetch_info_of(harvest_ctx *ctx, void *stream, int cls, harvest_fetch
         if (it == ctx->streams.end()) return HARVEST_ENOENT;
         ss = it->second.get();
     }
-    // the wait runs outside the lock, so that another thread can enqueue on its own stream meanwhile; the stream's
-    // state stays where it is until the context (or the prefetcher that owns the stream) is destroyed
-    HIP_TRY(hipStreamSynchronize(ss->s));
+    // the wait runs outside the lock, so that another thread can enqueue on its own stream meanwhile (it waits for the
+    // stream, whose handle it has, and touches the stream's state only once it holds the lock again and has found it
+    // still in place)
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     std::lock_guard<std::mutex> lk(ctx->mu);
+    {
+        auto it = ctx->streams.find((hipStream_t)stream);
+        if (it == ctx->streams.end() || it->second.get() != ss) return HARVEST_ENOENT;
+    }
     if (cls < 0) cls = ss->last_cls;                       // the latest fetch, whichever class it was
     uint32_t h[C_N] = { 0 };
     const Lists *l = cls >= 0 && ss->counted[cls] ? &ss->lists[cls] : nullptr;
@@ -1980,7 +1991,7 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
     }
     // Without demotions the write-back itself is the commit point: once the copy is enqueued the bytes will change.
     bool committed = demoted.empty();
-    if (!demoted.empty()) rc = publish(ctx, c, demoted, s, h_dir.st, &committed);
+    if (!demoted.empty()) rc = publish(ctx, c, demoted, s, true, h_dir.st, &committed);
     if (committed) undo.commit();
     if (rc) return rc;
     if (ctx->no_device) return HARVEST_OK;

@@ -587,6 +587,62 @@ def test_a_kv_fetch_does_not_wait_for_the_experts_directory_edits():
         eh.close(); eo.close()
 
 
+def test_a_kv_fetch_does_not_wait_for_a_placement_on_another_stream():
+    """A placement is best effort and a fetch is not: KV blocks are placed on a second stream that is held up by a sleeping
+    kernel, and a fetch of the same blocks on the first stream completes meanwhile, served from the host copies - the same
+    bytes.  Once the placement is through, the next fetch finds the blocks in the cache tier.  A revocation made while the
+    placement is still queued is seen by every later fetch, as always."""
+    import torch
+    say("a KV fetch while a placement of the same class is queued on another stream")
+    wl = W.kv_decode(seed=34, n_layers=1, n_seq=2, min_len=9000, max_len=12000, p_cache=0.3, n_steps=1)
+    eo, eh = P.make_engines(wl, poison=True, cache_slack=2000)
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        want = ro.fetch(0)
+        P.assert_kv_equal(want, rh.fetch(0), "before")
+        on_host = [b for s in range(wl.n_seq) for b in rh.tables[s][:-1] if eh.lookup(S.KV, b)[0] == S.HOST][:302]
+        assert len(on_host) == 302
+        warm, on_host = on_host[300:], on_host[:300]
+        other = torch.cuda.Stream(eh.dev)
+        main = torch.cuda.current_stream()
+        independent, cycles = P.streams_run_independently(eh.dev, other, main, ms=150.0)
+        if not independent:
+            pytest.skip("the two streams share a hardware queue in this process")
+        table, nb = rh.table_arrays()
+        d_table, d_nb = torch.from_numpy(table).to(eh.dev), torch.from_numpy(nb).to(eh.dev)
+        d_sdb = torch.from_numpy(rh.seq_dst_block.view(np.int64)).to(eh.dev)
+        dst = [torch.zeros(rh.cap * wl.shape.chunk_bytes, dtype=torch.uint8, device=eh.dev) for _ in range(2)]
+        with torch.cuda.stream(other):                                    # this stream's scratch exists from here on: a first
+            eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)   # fetch or placement waits for the stream and allocates
+            assert np.array_equal(eh.h.place(S.KV, warm), eo.place(S.KV, warm))
+        want = ro.fetch(0)
+        torch.cuda.synchronize()
+        for t in dst:
+            t.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(other):
+            torch.cuda._sleep(cycles)
+            st = eh.h.place(S.KV, on_host)                                # queued behind the sleeping kernel
+            still = torch.cuda.Event(); still.record()
+        eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+        main.synchronize()
+        pending = not still.query()
+        counts, miss, n_miss = eh.h.fetch_info(miss_cap=table.size, cls=S.KV)
+        assert pending, "the fetch waited for the other stream's placement"
+        assert (st == 0).all() and np.array_equal(eo.place(S.KV, on_host), st)
+        got = (dst[0].cpu().numpy(), dst[1].cpu().numpy(), np.sort(miss), counts)
+        P.assert_kv_equal(want, got, "during the placement", counts=False)
+        assert got[3]["n_host"] == want[3]["n_host"], "the fetch was served through entries that were not published yet"
+        # a revocation while the placement is still queued: later fetches see it (and, behind it in the chain, the placement)
+        a, b = ro.revoke_quarter(0), rh.revoke_quarter(0)
+        assert np.array_equal(a[0], b[0])
+        P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "after the placement and a revocation")
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, tiers=(S.CACHE,), what="cache tier")
+    finally:
+        eh.close(); eo.close()
+
+
 def test_a_released_stream_starts_afresh():
     """harvest_release_stream frees what the context keeps for a caller stream; the next call on the stream sets it up
     again and fetches the same bytes; a prefetcher's stream is not the caller's to release."""
