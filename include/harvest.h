@@ -21,8 +21,8 @@
  *   - Data-moving calls are asynchronous: they enqueue on `stream` and return;
  *     results are valid in stream order.  The first call on a stream, and a
  *     call with more requests than any before it on that stream, allocates
- *     per-stream scratch (hipMalloc) and waits for that stream's earlier work;
- *     steady-state calls allocate nothing.  harvest_fetch_kv and
+ *     per-stream scratch (hipMalloc), the latter after waiting for that
+ *     stream's earlier work; steady-state calls allocate nothing.  harvest_fetch_kv and
  *     harvest_fetch_experts may be recorded into a HIP graph (stream capture)
  *     once such a call has run on that stream outside capture: they use no
  *     memset and read residency from device memory, so a replay follows every

@@ -468,9 +468,9 @@ int get_stream(harvest_ctx *ctx, void *stream, StreamState **out)
     return HARVEST_OK;
 }
 
-// Room for n_req requests in the lists of class cls (and, for KV, in the arrays of the resolve).  Growing waits for
-// the stream's earlier work, which may still read the old arrays; the new ones are all there before the old ones go,
-// so a failed allocation leaves the stream as it was.
+// Room for n_req requests in the lists of class cls (and, for KV, in the arrays of the resolve).  Growing (not the
+// first allocation) waits for the stream's earlier work, which may still read the old arrays; the new ones are all
+// there before the old ones go, so a failed allocation leaves the stream as it was.
 int ensure_req_cap(StreamState *ss, int cls, uint32_t n_req)
 {
     Lists &l = ss->lists[cls];
@@ -483,8 +483,10 @@ int ensure_req_cap(StreamState *ss, int cls, uint32_t n_req)
         fprintf(stderr, "libharvest: this fetch needs larger scratch lists - run it once outside graph capture\n");
         return HARVEST_EINVAL;
     }
-    HIP_TRY(hipStreamSynchronize(ss->s));
-    HIP_TRY(hipStreamSynchronize(ss->side));
+    if (l.cap) {                              // the stream's earlier work may still read the arrays that are about to go
+        HIP_TRY(hipStreamSynchronize(ss->s));
+        HIP_TRY(hipStreamSynchronize(ss->side));
+    }
     uint32_t cap = std::max<uint32_t>(1024, n_req + n_req / 4);
     size_t n_rows = (cap + WG - 1) / WG;
     const bool kv = cls == HARVEST_KV;
@@ -521,8 +523,10 @@ int ensure_ctl_cap(harvest_ctx *ctx, StreamState *ss, size_t bytes)
 {
     if (fault_due()) return HARVEST_EHIP;
     if (ctx->no_device || bytes <= ss->ctl_cap) return HARVEST_OK;
-    HIP_TRY(hipStreamSynchronize(ss->s));
-    if (ss->ctl_buf) HIP_TRY(hipFree(ss->ctl_buf));
+    if (ss->ctl_buf) {                        // the stream's earlier work may still read the list that is about to go
+        HIP_TRY(hipStreamSynchronize(ss->s));
+        HIP_TRY(hipFree(ss->ctl_buf));
+    }
     ss->ctl_buf = nullptr; ss->ctl_cap = 0;
     size_t cap = std::max<size_t>(1 << 16, bytes + bytes / 4);
     HIP_TRY(hipMalloc(&ss->ctl_buf, cap));
