@@ -943,7 +943,7 @@ def bench_kv(args, seed, full):
         "bit_exact": bit_exact,
         "graph_replay": graph_replay,
         "served": {k: v // args.steps for k, v in d.items()},
-        "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true,false>" if args.head_major else
+        "roofline": {"bound": "hbm", "kernel": ("gather_hm<1,true>" if args.head_major else
                                                 "gather<%d,true,%s>" % (args.gather_threads or 64, "true" if args.shared_cache or
                                                                         args.cache_layout == "adjacent" else "false"))
                                                + " (HBM-tier gather)", "achieved": round(hbm_gbs, 1),

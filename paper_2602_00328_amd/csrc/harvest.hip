@@ -731,9 +731,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
     // timing events cannot be recorded into a graph, and taking one from the pool may allocate
     const bool profile = ctx->profile && !ss->fixed && !is_capturing(ss->s);
     const bool host_tier = c.cfg.n_host_slots != 0;
-    // one pass over both planes of each request where the cache tier keeps them side by side (see gather)
-    // (not the head-major gather: its stores are 4 KiB strips, and with two planes' strips interleaved it was measured to
-    // lose - 5.60 against 5.98 TB/s alone)
+    // one pass over both planes of each request where the cache tier keeps them side by side (see gather; not the
+    // head-major gather, see gather_hm)
     const bool fold = !hm && c.cache_planes_adjacent() && !ctx->gather_grid;
     // Grid of the HBM-tier gather: about one workgroup per tile.  The request count lives on the device, so the grid is
     // sized from what the previous gather of this class on this stream reported, never below a floor that still fills the
@@ -806,8 +805,8 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
         const Rec *recs = (const Rec *)lists.hbm;
         const uint32_t *n_req = (const uint32_t *)(lists.cnt + C_HBM_REQ);
         if (hm) {
-            auto kernel = fold ? gather_hm<1, true, true> : gather_hm<1, true, false>;
-            const dim3 g = fold ? dim3(grid_for(want * planes, MAX_GRID)) : dim3(grid, planes);
+            auto kernel = gather_hm<1, true>;
+            const dim3 g(grid, planes);
             if (pa)
                 hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_hbm, pa, pb, 0, recs, n_req, ga, *hm, ss->d_feedback + cls);
             else

@@ -633,14 +633,15 @@ struct HmArgs {
     uint32_t pad;
 };
 
-template <int UNROLL, bool NT, bool FOLD>
+template <int UNROLL, bool NT>
 __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
                                                 GatherArgs a, HmArgs h, uint32_t *feedback)
 {
-    // FOLD: both planes of a request in one pass, as in gather
+    // blockIdx.y is the plane: taking both planes of a request in one pass, as gather does for a cache tier that keeps
+    // them side by side, was measured to lose here (5.60 against 5.98 TB/s alone): the stores are 4 KiB strips, and with
+    // two planes' strips interleaved they no longer follow each other
     constexpr uint32_t UNITS = WG * UNROLL;
-    uint32_t tpc = a.tiles_per_chunk;
-    uint32_t tpr = FOLD ? tpc * a.n_planes : tpc;
+    uint32_t tpr = a.tiles_per_chunk;
     uint64_t t = blockIdx.x;
     uint32_t idx = (uint32_t)t / tpr;
     Rec x = recs[idx];                                   // speculative, as in gather
@@ -650,8 +651,7 @@ __global__ __launch_bounds__(WG) void gather_hm(const Rec *__restrict__ recs, co
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     while (t < n_tiles) {
         uint32_t k = (uint32_t)t - idx * tpr;
-        uint32_t plane = FOLD ? (k >= tpc ? 1u : 0u) : blockIdx.y;
-        if (FOLD) k -= plane * tpc;
+        uint32_t plane = blockIdx.y;
         uint64_t dst_plane = plane ? a.dst_base[1] : a.dst_base[0];
         uint32_t u0 = k * UNITS + threadIdx.x;
         uint64_t cap = x.src >> 48;
