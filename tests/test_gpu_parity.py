@@ -186,6 +186,30 @@ def test_ragged_chunk_sizes(heads, dim, tokens, elt, general, threads, adjacent)
         eh.close(); eo.close()
 
 
+@pytest.mark.parametrize("pcie_wgs", [1, 5, 300])
+@pytest.mark.parametrize("heads,dim,tokens", [(5, 200, 48), (8, 128, 16)])
+def test_pcie_copies_with_any_number_of_workgroups(pcie_wgs, heads, dim, tokens):
+    """Placements and write-backs count their tiles out to however many persistent workgroups the context was given:
+    one, a few, more than there are tiles; 93.75 KiB chunks (two whole 32 KiB tiles and a ragged third) and 32 KiB ones."""
+    shape = W.KVShape(n_layers=2, block_tokens=tokens, n_kv_heads=heads, head_dim=dim, elt_bytes=2)
+    say(f"pcie copies with {pcie_wgs} workgroups, chunk {shape.chunk_bytes} bytes")
+    wl = W.kv_decode(seed=6, n_seq=3, min_len=20 * tokens, max_len=60 * tokens, n_steps=2 * tokens, shape=shape,
+                     fill_mode=W.FILL_TAG)
+    eo, eh = P.make_engines(wl, poison=True, hip_kwargs=dict(pcie_wgs=pcie_wgs))
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        for t in range(2 * tokens):                              # roll-overs: write-back, placement, registration
+            P.assert_kv_equal(ro.step(t), rh.step(t), f"step {t}")
+        a, b = ro.revoke_quarter(0), rh.revoke_quarter(0)        # and one larger batch each way
+        assert np.array_equal(a[0], b[0]) and len(a[0]) > 0
+        assert np.array_equal(ro.replace_revoked(), rh.replace_revoked())
+        P.assert_kv_equal(ro.fetch(1), rh.fetch(1), "after re-placing")
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_tiers_equal(eo, eh, S.KV, 2, what=f"{pcie_wgs} workgroups")
+    finally:
+        eh.close(); eo.close()
+
+
 # ---- degenerate requests ----------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("general", [False, True], ids=["one-kernel", "general"])
