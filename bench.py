@@ -39,11 +39,13 @@ def parse():
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
     ap.add_argument("--workload", default="kv_decode",
-                    choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen", "latency_by_size"],
+                    choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen", "latency_by_size", "link_contention"],
                     help="kv_decode = configs[1] (the benchmark line); kv_tiny = configs[0] (fetch latency, both forms of the "
                          "fetch); experts_* = configs[2] / configs[3], extra lines; latency_by_size = time of one fetch from "
                          "the cache tier against the same fetch from the host, by object size (the paper's Figures 3 and 7 "
-                         "on this machine: context, not a benchmark line)")
+                         "on this machine: context, not a benchmark line); link_contention = a PCIe-bound KV fetch repeated on one stream "
+                         "while a placement of experts runs on another, by the number of workgroups the placement's copy runs "
+                         "with (harvest_config.pcie_wgs): who gets the link")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
@@ -588,6 +590,76 @@ def bench_latency(args):
                       **out}), flush=True)
 
 
+def bench_contention(args):
+    """Who gets the PCIe link: a KV fetch that is bound by its host tier, repeated back to back on one stream, beside a
+    placement of experts (host -> cache tier) on another, for several widths of the placement's copy kernel.  The paper
+    puts the miss on the critical path, where its transfer contends with other traffic on the link (Section 2.2), and
+    makes placement best effort (Section 3.1): the figures say what a fetch pays for a placement running beside it."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from workloads import scenarios as S
+    from workloads.hip_engine import HipEngine
+    rows = []
+    for wgs in (0, 4, 8, 16, 32, 64):
+        wl = W.kv_decode(seed=30, n_layers=1, n_seq=2, min_len=20000, max_len=30000, n_steps=1)
+        ex = W.expert_offload(seed=30, shape=W.ExpertShape(n_layers=1, n_experts=16, d_model=4096, d_ff=4096), n_local=0)
+        eh = HipEngine(kv=S.kv_spec(wl, 0, 0), expert=S.expert_spec(ex), two_streams=True, pcie_wgs=wgs)
+        try:
+            rh, xh = S.KVRun(eh, wl), S.ExpertRun(eh, ex)
+            eh.revoke(S.EXPERT, sorted(xh.live))                  # the whole expert cache tier is free
+            ids = list(range(ex.n_objects))
+            table, nb = rh.table_arrays()
+            dev = eh.dev
+            d_table, d_nb = torch.from_numpy(table).to(dev), torch.from_numpy(nb).to(dev)
+            d_sdb = torch.from_numpy(rh.seq_dst_block.view(np.int64)).to(dev)
+            dst = [torch.zeros(rh.cap * wl.shape.chunk_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+            ks, xs = eh.streams[S.KV], eh.streams[S.EXPERT]
+
+            def fetch():
+                a = time.perf_counter()
+                with torch.cuda.stream(ks):
+                    eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)
+                ks.synchronize()
+                return time.perf_counter() - a
+
+            for _ in range(5):
+                fetch()
+            alone = float(np.median([fetch() for _ in range(20)]))
+            want = [t.clone() for t in dst]
+            counts, _, _ = eh.h.fetch_info(stream=ks, cls=S.KV)
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            st = eh.place(S.EXPERT, ids)
+            xs.synchronize()
+            place_alone = time.perf_counter() - a
+            n_placed = int((st == 0).sum())
+            eh.revoke(S.EXPERT, ids)
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            eh.place(S.EXPERT, ids)
+            beside = []
+            while not xs.query():
+                beside.append(fetch())
+            xs.synchronize()
+            place_beside = time.perf_counter() - a
+            same = all(bool(torch.equal(x, y)) for x, y in zip(want, dst))
+            rows.append({"pcie_wgs": wgs or "default (12)", "fetch_alone_ms": round(alone * 1e3, 3),
+                         "fetch_beside_placement_ms_median": round(float(np.median(beside)) * 1e3, 3),
+                         "fetch_beside_placement_ms_max": round(float(np.max(beside)) * 1e3, 3), "fetches_beside": len(beside),
+                         "placement_alone_ms": round(place_alone * 1e3, 2), "placement_beside_fetches_ms": round(place_beside * 1e3, 2),
+                         "placement_bytes": n_placed * ex.shape.chunk_bytes, "fetch_host_tier_blocks": counts["n_host"],
+                         "same_bytes": same})
+            log(f"[bench] link contention, {rows[-1]}")
+        finally:
+            eh.close()
+    print(json.dumps({"metric": "time of a PCIe-bound KV fetch alone and beside a placement on another stream, by the width of the "
+                                "placement's copy kernel", "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "u8",
+                      "config": {"workload": "2 sequences of 20K-30K tokens (Llama-3-8B-shaped blocks, 30 % of them on the host) fetched "
+                                             "back to back on one stream; 16 experts of 96 MiB placed host -> cache tier on another"},
+                      "rows": rows}), flush=True)
+
+
 def no_nan(x):
     """JSON has no NaN: figures that were not measured (--no-profile) are reported as null."""
     if isinstance(x, dict):
@@ -609,6 +681,8 @@ def main():
         return bench_tiny(args)
     if args.workload == "latency_by_size":
         return bench_latency(args)
+    if args.workload == "link_contention":
+        return bench_contention(args)
     if args.workload != "kv_decode":
         return bench_experts(args)
     out = bench_kv(args, args.seed, full=True)

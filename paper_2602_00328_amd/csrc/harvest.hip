@@ -862,7 +862,7 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     // each, the tiles counted out to them one at a time.  Alone, 8 of them already fill the link (a 906 MB placement:
     // 15.9 ms = 57 GB/s with 8, 12, 16 or 64; 19.5 ms with 4); what the number decides is who gets the link when a fetch on
     // another stream wants it too - the link serves its clients by what they have in flight.  Beside a stream of
-    // PCIe-bound KV fetches of 1.04 ms each, a placement with 64 workgroups makes a fetch take 12.6 ms, with 16: 1.8 ms,
+    // PCIe-bound KV fetches of 1.04 ms each, a placement with 64 workgroups makes a fetch take 16.8 ms, with 16: 1.8 ms,
     // with 12: 1.5 ms (and the placement 48 ms), with 8: 1.3 ms (70 ms).  A miss waits on the link, where its transfer
     // contends with whatever else crosses it (paper Section 2.2), and a placement is best effort (Section 3.1), so the
     // copies run narrow.

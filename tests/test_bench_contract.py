@@ -63,3 +63,19 @@ def test_latency_by_size_workload_delivers_the_same_bytes_from_either_tier():
     for row in out["experts"] + out["kv"]:
         assert row["same_bytes"] is True and row["host_tier_us"] > row["cache_tier_us"] > 0
     assert out["kv"][-1]["speed_up"] > 10 and out["experts"][-1]["speed_up"] > 10      # bandwidth-bound sizes: HBM against PCIe
+
+
+@pytest.mark.gpu
+def test_link_contention_workload():
+    """Beside a placement on another stream a PCIe-bound fetch still delivers the same bytes, pays less the narrower the
+    placement's copy runs, and with the default width keeps most of the link."""
+    print("bench link_contention", flush=True)
+    r = subprocess.run([sys.executable, BENCH, "--workload", "link_contention"], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip().splitlines()[-1])
+    rows = {str(x["pcie_wgs"]): x for x in d["rows"]}
+    assert all(x["same_bytes"] for x in d["rows"])
+    assert rows["64"]["fetch_beside_placement_ms_median"] > 2 * rows["8"]["fetch_beside_placement_ms_median"]
+    default = rows["default (12)"]
+    assert default["fetch_beside_placement_ms_median"] < 2.5 * default["fetch_alone_ms"]
+    assert default["placement_alone_ms"] < 1.1 * rows["64"]["placement_alone_ms"]
