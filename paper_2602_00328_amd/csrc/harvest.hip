@@ -20,6 +20,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <list>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -376,6 +377,11 @@ struct harvest_ctx {
     std::vector<ProfPair> prof;
     std::vector<hipEvent_t> prof_pool;
     std::vector<hipEvent_t> evt_pool;     // events (no timing) of finished revocations, for the next ones
+    // Latest-work events that revocations have taken out of their streams' states and are waiting for right now, with the
+    // number of revocations waiting on each.  A second revocation that starts meanwhile no longer finds those events in
+    // the stream states, yet the work they stand for is as much in flight for it: it waits for everything listed here too.
+    struct DrainEvt { hipEvent_t e; int refs; };
+    std::list<DrainEvt> draining;
     bool captured_work = false;           // a fetch was recorded into a HIP graph: replays are invisible to the events
     SegAlloc shared;                      // free space of cfg.d_shared_cache
     std::vector<harvest_prefetcher *> prefetchers;   // live ones: destroyed with the context if the caller did not
@@ -1041,6 +1047,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto &pp : ctx->prof) { (void)hipEventDestroy(pp.a); (void)hipEventDestroy(pp.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
         for (auto e : ctx->evt_pool) (void)hipEventDestroy(e);
+        for (auto &d : ctx->draining) (void)hipEventDestroy(d.e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
         for (auto &c : ctx->cls) if (c.edit_evt) (void)hipEventDestroy(c.edit_evt);
@@ -1281,7 +1288,9 @@ static int enqueue_poison(harvest_ctx *ctx, ClassState &c, const std::vector<uin
 // a caller stream that HIP maps to the same queue to stand still behind it (seen: KV fetches on one stream held up for
 // the 7 ms of a placement queued on another).  Each stream's "latest work" event is taken out of the stream's state and
 // replaced by a fresh one, so the event the host then waits on is nobody else's: later calls on that stream record the
-// new event, and destroying a prefetcher's stream state meanwhile does not touch the one being waited on.
+// new event, and destroying a prefetcher's stream state meanwhile does not touch the one being waited on.  The events
+// taken are listed in the context while the wait lasts: a revocation that another thread starts meanwhile finds the
+// stream states without them, and waits for the listed ones as well.
 static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_t n, bool notify)
 {
     int rc = check_class(ctx, cls);
@@ -1291,7 +1300,7 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     std::vector<uint32_t> old_slot;
     std::vector<std::pair<harvest_revoke_cb, void *>> cbs;
     ClassState &c = ctx->cls[cls];
-    std::vector<hipEvent_t> waits;             // the latest work of every stream, as of the invalidation
+    std::vector<harvest_ctx::DrainEvt *> waits;   // the latest work of every stream, as of the invalidation
     bool whole_device = false;
     Staging *st_fill = nullptr;
     {
@@ -1359,13 +1368,19 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
         // streams get the fresh ones) and waited for below, with the lock released.  Fetches enqueued from now on need no
         // waiting for: they are ordered after the invalidation above by the class's edit chain.  Work recorded into
         // graphs is invisible to those events: then the host waits for the whole device.
-        if (!whole_device)
+        if (!whole_device) {
+            for (auto &d : ctx->draining) {        // what other revocations took before this one is in flight for it too
+                d.refs++;
+                waits.push_back(&d);
+            }
             for (StreamState *ss : busy) {
-                waits.push_back(ss->last);
+                ctx->draining.push_back({ ss->last, 1 });
+                waits.push_back(&ctx->draining.back());
                 ss->last = fresh.back();
                 fresh.pop_back();
                 ss->last_valid = false;
             }
+        }
         if (ctx->poison && !ctx->no_device) {      // stays held until the slots are poisoned, after the wait
             st_fill = h_fill.st;
             h_fill.st = nullptr;
@@ -1373,10 +1388,14 @@ static int revoke_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32
     }
     if (!ctx->no_device) {
         hipError_t e = whole_device ? hipDeviceSynchronize() : hipSuccess;
-        for (hipEvent_t w : waits)
-            if (e == hipSuccess) e = hipEventSynchronize(w);
+        for (harvest_ctx::DrainEvt *w : waits)
+            if (e == hipSuccess) e = hipEventSynchronize(w->e);    // (the list's entries stay put while anyone refers to them)
         std::unique_lock<std::mutex> lk(ctx->mu);
-        for (hipEvent_t w : waits) ctx->evt_pool.push_back(w);
+        for (harvest_ctx::DrainEvt *w : waits)
+            if (--w->refs == 0) {
+                ctx->evt_pool.push_back(w->e);
+                ctx->draining.remove_if([w](const harvest_ctx::DrainEvt &d) { return &d == w; });
+            }
         if (e != hipSuccess) {                     // the slots stay out of the allocator: nobody may be given them
             if (st_fill) st_fill->held = false;
             fprintf(stderr, "libharvest: the revocation drain failed: %s\n", hipGetErrorString(e));

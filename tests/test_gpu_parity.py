@@ -572,6 +572,72 @@ def test_a_revocation_waits_without_holding_up_the_other_thread():
         eh.close(); eo.close()
 
 
+def test_two_revocations_at_once_both_wait_for_the_work_in_flight():
+    """A revocation takes each stream's latest-work event out of the stream's state while it waits.  A second revocation,
+    started by another thread meanwhile, must wait for that work too: here a gather that reads cache slots (a repeat of
+    an earlier fetch, so its lists name the slots already) is queued behind a sleeping kernel; one thread revokes experts
+    - and takes the KV stream's event -, then the main thread revokes the very KV blocks the gather will read, with
+    poisoning on.  The gather must still deliver the blocks' bytes, not the poison."""
+    import threading
+    import time
+    import torch
+    say("two revocations at once")
+    wl = W.kv_decode(seed=35, n_layers=2, n_seq=2, min_len=5000, max_len=8000, p_cache=0.6, n_steps=1)
+    ex = W.expert_offload(seed=35, shape=W.ExpertShape(n_layers=1, n_experts=8, d_model=256, d_ff=512), n_local=0)
+    eo, eh = P.make_engines(wl, ex, poison=True, two_streams=True, hip_kwargs=dict(general_fetch=True))
+    try:
+        ro, rh = S.KVRun(eo, wl), S.KVRun(eh, wl)
+        xo, xh = S.ExpertRun(eo, ex), S.ExpertRun(eh, ex)
+        want = ro.fetch(1)
+        table, nb = rh.table_arrays()
+        dev = eh.dev
+        d_table, d_nb = torch.from_numpy(table).to(dev), torch.from_numpy(nb).to(dev)
+        d_sdb = torch.from_numpy(rh.seq_dst_block.view(np.int64)).to(dev)
+        dst = [torch.zeros(rh.cap * wl.shape.chunk_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+        kv_stream, x_stream = eh.streams[S.KV], eh.streams[S.EXPERT]
+        P.assert_experts_equal(xo.fetch(0, 0), xh.fetch(0, 0), "experts before")      # the expert stream has work on record
+        with torch.cuda.stream(kv_stream):
+            eh.h.fetch_kv(0, d_table, d_nb, dst[0], dst[1], d_sdb, rh.cap)            # resolves: the lists name cache slots
+        independent, cycles = P.streams_run_independently(dev, kv_stream, x_stream, ms=150.0)
+        for t in dst:
+            t.zero_()
+        torch.cuda.synchronize()
+        in_cache = [b for s in range(wl.n_seq) for b in rh.tables[s][:-1] if eh.lookup(S.KV, b)[0] == S.CACHE]
+        assert len(in_cache) > 100
+        with torch.cuda.stream(kv_stream):
+            torch.cuda._sleep(cycles)
+            eh.h.fetch_kv_again(1, dst[0], dst[1])                                    # a gather from those slots, behind the sleep
+        errors = []
+
+        def expert_side():
+            try:
+                eh.revoke(S.EXPERT, sorted(xh.live)[:2])                              # waits for both streams' work
+            except BaseException as e:
+                errors.append(e)
+
+        th = threading.Thread(target=expert_side)
+        th.start()
+        time.sleep(0.03)                                                              # the other revocation is waiting by now
+        a = time.perf_counter()
+        eh.revoke(S.KV, in_cache)                                                     # frees and poisons what the gather reads
+        waited = time.perf_counter() - a
+        th.join(30)
+        assert not th.is_alive() and not errors, errors
+        torch.cuda.synchronize()
+        from conftest import live
+        live(f"  the second revocation waited {1e3 * waited:.1f} ms for a gather queued behind a sleep of 150 ms")
+        got = (dst[0].cpu().numpy(), dst[1].cpu().numpy())
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), "the gather read slots that were already freed"
+        assert waited > 0.05
+        # lock step again, and nothing else is wrong
+        eo.revoke(S.EXPERT, sorted(xo.live)[:2]); eo.revoke(S.KV, in_cache)
+        P.assert_kv_equal(ro.fetch(0), rh.fetch(0), "kv afterwards")
+        P.assert_dirs_equal(eo, eh, S.KV, wl.n_objects)
+        P.assert_dirs_equal(eo, eh, S.EXPERT, ex.n_objects)
+    finally:
+        eh.close(); eo.close()
+
+
 def test_a_kv_fetch_does_not_wait_for_the_experts_directory_edits():
     """Directory edits are ordered per class. The expert stream is held up by a sleeping kernel with a placement (copies,
     then the directory write that publishes them) queued behind it; a KV fetch on the other stream completes while that
