@@ -372,6 +372,7 @@ struct harvest_ctx {
     hipStream_t drain = nullptr;          // the poisoning of revoked slots (hundreds of MiB at times): kept off `ctl`, so that no
                                           // directory edit queues up behind it
     unsigned long long *d_totals = nullptr;  // [HARVEST_N_CLASSES][C_N]
+    unsigned long long *d_lease = nullptr;   // until when (device clock) a fetch expects to need the PCIe link: see link_announce
     std::map<hipStream_t, std::unique_ptr<StreamState>> streams;
     std::deque<Staging> staging;          // deque: references stay valid when it grows
     std::vector<ProfPair> prof;
@@ -795,15 +796,15 @@ int launch_gathers(harvest_ctx *ctx, StreamState *ss, ClassState &c, int cls, co
             if (hm) {
                 auto kernel = planes == 2 ? gather_hm_host<2> : gather_hm_host<1>;
                 if (pc)
-                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, *hm, fb);
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, *hm, fb, ctx->d_lease);
                 else
-                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, *hm, fb);
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, *hm, fb, ctx->d_lease);
             } else {
                 auto kernel = planes == 2 ? gather_host<2> : gather_host<1>;
                 if (pc)
-                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, fb);
+                    hipExtLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, pc, pd, 0, recs, n_req, ga, fb, ctx->d_lease);
                 else
-                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, fb);
+                    hipLaunchKernelGGL(kernel, g, dim3(WG), 0, s_host, recs, n_req, ga, fb, ctx->d_lease);
             }
             HIP_TRY(hipGetLastError());
         }
@@ -865,18 +866,21 @@ int init_device(harvest_ctx *ctx, const harvest_config *cfg)
     ctx->gather_threads = cfg->gather_threads ? cfg->gather_threads : HBM_WG;
     ctx->ctl_grid = 8 * ctx->n_cu;                 // HBM-bound fills
     // Copies that cross PCIe outside a fetch (place, write-back): persistent workgroups with one 32 KiB tile in flight
-    // each, the tiles counted out to them one at a time.  Alone, 8 of them already fill the link (a 906 MB placement:
-    // 15.9 ms = 57 GB/s with 8, 12, 16 or 64; 19.5 ms with 4); what the number decides is who gets the link when a fetch on
-    // another stream wants it too - the link serves its clients by what they have in flight.  Beside a stream of
-    // PCIe-bound KV fetches of 1.04 ms each, a placement with 64 workgroups makes a fetch take 16.8 ms, with 16: 1.8 ms,
-    // with 12: 1.5 ms (and the placement 48 ms), with 8: 1.3 ms (70 ms).  A miss waits on the link, where its transfer
-    // contends with whatever else crosses it (paper Section 2.2), and a placement is best effort (Section 3.1), so the
-    // copies run narrow.
+    // each, the tiles counted out to them one at a time; they stand back while a fetch says it needs the link (see
+    // link_announce).  Alone, 8 of them already fill the link (a 906 MB placement: 15.9 ms = 57 GB/s with 8, 12, 16 or
+    // 64; 24 ms with 4); what the number decides is who gets the link when a fetch on another stream wants it too - the
+    // link serves its clients by what they have in flight.  Beside a stream of PCIe-bound KV fetches of 1.04 ms each, a
+    // placement with 64 workgroups makes a fetch take 8.1 ms, with 32 or 16: 1.3 ms, with 12: 1.2 ms, with 8: 1.1 ms
+    // (without the standing back: 16.8, 4.4, 1.8, 1.5, 1.3 ms).  A miss waits on the link, where its transfer contends
+    // with whatever else crosses it (paper Section 2.2), and a placement is best effort (Section 3.1), so the copies
+    // run narrow.
     ctx->pcie_grid = cfg->pcie_wgs ? cfg->pcie_wgs : 12;
     HIP_TRY(hipStreamCreateWithFlags(&ctx->ctl, hipStreamNonBlocking));
     HIP_TRY(hipStreamCreateWithFlags(&ctx->drain, hipStreamNonBlocking));
     HIP_TRY(hipMalloc(&ctx->d_totals, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
     HIP_TRY(hipMemset(ctx->d_totals, 0, HARVEST_N_CLASSES * C_N * sizeof(unsigned long long)));
+    HIP_TRY(hipMalloc(&ctx->d_lease, 256));
+    HIP_TRY(hipMemset(ctx->d_lease, 0, 256));
     for (int k = 0; k < HARVEST_N_CLASSES; ++k) {
         ClassState &c = ctx->cls[k];
         if (!c.used) continue;
@@ -1050,6 +1054,7 @@ int harvest_destroy(harvest_ctx *ctx)
         for (auto &d : ctx->draining) (void)hipEventDestroy(d.e);
         for (auto &c : ctx->cls) if (c.d_dir) (void)hipFree(c.d_dir);
         (void)hipFree(ctx->d_totals);
+        (void)hipFree(ctx->d_lease);
         for (auto &c : ctx->cls) if (c.edit_evt) (void)hipEventDestroy(c.edit_evt);
         if (ctx->ctl) (void)hipStreamDestroy(ctx->ctl);
         if (ctx->drain) (void)hipStreamDestroy(ctx->drain);
@@ -1223,7 +1228,8 @@ static int place_impl(harvest_ctx *ctx, int cls, const harvest_obj *ids, uint32_
                 uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
                 uint32_t grid = grid_for((uint64_t)items.size() * tpc, from ? ctx->ctl_grid : ctx->pcie_grid);
                 hipLaunchKernelGGL(copy_items, dim3(grid), dim3(WG), 0, s, d_items, (uint32_t)items.size(),
-                                   c.cfg.chunk_bytes, tpc, from ? (unsigned long long *)nullptr : (unsigned long long *)ss->ctl_buf);
+                                   c.cfg.chunk_bytes, tpc, from ? (unsigned long long *)nullptr : (unsigned long long *)ss->ctl_buf,
+                                   from ? (const unsigned long long *)nullptr : (const unsigned long long *)ctx->d_lease);
             }
         }
         DEV_TRY(hipGetLastError());
@@ -1534,7 +1540,8 @@ static int fetch_kv_locked(harvest_ctx *ctx, uint32_t layer, const int32_t *d_bl
         hipLaunchKernelGGL(fetch_kv_small, dim3((uint32_t)(total * tpc), c.cfg.n_planes, n_layers), dim3(WG), 0, ss->s, cd,
                            layer, d_block_table, d_n_blocks, n_seq, max_blocks, d_seq_dst_block, dst_capacity_blocks, ga,
                            dst_layer_stride, lists.miss, cnt, ctx->d_totals + HARVEST_KV * C_N,
-                           ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV);
+                           ss->d_feedback + HARVEST_KV, ss->d_feedback + HARVEST_N_CLASSES + HARVEST_KV,
+                           c.cfg.n_host_slots ? ctx->d_lease : (unsigned long long *)nullptr);
         HIP_TRY(hipGetLastError());
         ss->last_cls = HARVEST_KV; ss->counted[HARVEST_KV] = true;
         ss->feedback_valid[HARVEST_KV] = true;
@@ -2006,7 +2013,8 @@ int harvest_evict(harvest_ctx *ctx, int cls, int layer, const harvest_obj *ids, 
                 uint32_t tpc = tiles_per_chunk(c.cfg.chunk_bytes, TILE_HOST);
                 uint32_t grid = grid_for((uint64_t)items.size() * tpc, to_host ? ctx->pcie_grid : ctx->ctl_grid);
                 hipLaunchKernelGGL(copy_items2, dim3(grid), dim3(WG), 0, s, d_items, (uint32_t)items.size(),
-                                   c.cfg.chunk_bytes, tpc, to_host ? (unsigned long long *)ss->ctl_buf : (unsigned long long *)nullptr);
+                                   c.cfg.chunk_bytes, tpc, to_host ? (unsigned long long *)ss->ctl_buf : (unsigned long long *)nullptr,
+                                   to_host ? (const unsigned long long *)ctx->d_lease : (const unsigned long long *)nullptr);
             }
         }
         DEV_TRY(hipGetLastError());

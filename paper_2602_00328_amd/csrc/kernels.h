@@ -538,6 +538,33 @@ __global__ __launch_bounds__(NTHR) void gather(const Rec *__restrict__ recs, con
     }
 }
 
+// Who gets the PCIe link.  A fetch that reads from the host announces, in a word of device memory, until when it
+// expects to need the link (link_announce: now + its host-tier bytes at the link's rate, on the device's constant 100 MHz
+// clock); the copies that cross the link outside a fetch - placements, write-backs - look at that word before they take
+// their next tile and stand back while the time has not come (yield_link), though never for longer than YIELD_TICKS per
+// tile, so that they always get on (at a tenth of the link's rate or so when fetches never pause).  A miss is on the
+// critical path and a placement is best effort (paper Sections 2.2 and 3.1).  An estimate instead of an exact begin /
+// end: nothing has to be counted or taken back, and a word that is stale means no more than "nobody is fetching".  The
+// estimate is on the short side (the rate of an undisturbed fetch, no margin): a copy that follows the fetch on the same
+// stream, which cannot run beside it anyway, must not be kept waiting for a fetch that is already over.
+constexpr uint64_t LINK_BYTES_PER_TICK = 575;      // 57.5 GB/s at 100 MHz
+constexpr uint64_t YIELD_TICKS = 6000;             // 60 us
+__device__ inline void link_announce(unsigned long long *lease, uint64_t host_bytes)
+{
+    if (!lease || !host_bytes) return;
+    atomicMax(lease, (unsigned long long)(wall_clock64() + host_bytes / LINK_BYTES_PER_TICK));
+}
+__device__ inline void yield_link(const unsigned long long *lease)
+{
+    if (!lease) return;
+    const uint64_t t0 = wall_clock64();
+    for (;;) {
+        const uint64_t now = wall_clock64();
+        if (now - t0 >= YIELD_TICKS || now >= __hip_atomic_load(lease, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+        __builtin_amdgcn_s_sleep(127);
+    }
+}
+
 // The whole KV fetch in one kernel, for small block tables (token-major layout, one layer).  A fetch of a few blocks is
 // made of launch gaps, not of bytes: resolve, compaction and the two gathers are four dependent kernels of a few
 // microseconds each.  Here workgroup (cell r, tile k, plane p) resolves cell r by itself and copies its tile from whichever
@@ -552,7 +579,7 @@ __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer,
                                                      uint64_t dst_cap, GatherArgs a, uint64_t dst_step,
                                                      uint32_t *__restrict__ miss_idx, uint32_t *cnt,
                                                      unsigned long long *totals, uint32_t *feedback_hbm,
-                                                     uint32_t *feedback_host)
+                                                     uint32_t *feedback_host, unsigned long long *lease)
 {
     uint32_t tpc = a.tiles_per_chunk;
     uint32_t r = blockIdx.x / tpc, k = blockIdx.x - r * tpc, plane = blockIdx.y;
@@ -615,6 +642,7 @@ __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer,
         cnt[C_MISS] = s_base;
         *feedback_hbm = hbm;
         *feedback_host = host;
+        link_announce(lease, (uint64_t)host * a.chunk_bytes * a.n_planes * gridDim.z);
     }
 }
 
@@ -736,12 +764,13 @@ __device__ inline HostSub host_sub(const Rec *__restrict__ recs, uint64_t g, uin
 
 template <int PLANES>
 __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                                  GatherArgs a, uint32_t *feedback)
+                                                  GatherArgs a, uint32_t *feedback, unsigned long long *lease)
 {
     constexpr int U = HOST_LOADS / PLANES;                     // sub-tiles per step
     uint32_t spc = a.tiles_per_chunk;                          // 4 KiB sub-tiles per chunk
     uint32_t n_req = *n_req_ptr;
     if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = n_req;      // as in gather: a hint for the host
+    if (blockIdx.x == 0 && threadIdx.x == 0) link_announce(lease, (uint64_t)n_req * a.chunk_bytes * PLANES);
     uint64_t n_sub = (uint64_t)n_req * spc;
     uint64_t n_steps = (n_sub + U - 1) / U;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
@@ -771,11 +800,12 @@ __global__ __launch_bounds__(WG) void gather_host(const Rec *__restrict__ recs, 
 // computation serves both.
 template <int PLANES>
 __global__ __launch_bounds__(WG) void gather_hm_host(const Rec *__restrict__ recs, const uint32_t *__restrict__ n_req_ptr,
-                                                     GatherArgs a, HmArgs h, uint32_t *feedback)
+                                                     GatherArgs a, HmArgs h, uint32_t *feedback, unsigned long long *lease)
 {
     uint32_t spc = a.tiles_per_chunk;
     uint32_t n_req = *n_req_ptr;
     if (feedback && blockIdx.x == 0 && threadIdx.x == 0) *feedback = n_req;
+    if (blockIdx.x == 0 && threadIdx.x == 0) link_announce(lease, (uint64_t)n_req * a.chunk_bytes * PLANES);
     uint64_t n_sub = (uint64_t)n_req * spc;
     uint32_t chunk_units = (uint32_t)(a.chunk_bytes >> 4);
     uint32_t tid = threadIdx.x;
@@ -805,7 +835,7 @@ constexpr size_t LIST_HEADER = 16;       // a host-built list travels behind thi
 // the launch ends with a few workgroups working off their backlog alone - a 906 MB placement beside a stream of
 // fetches took 106 ms that way.  Every thread of the workgroup gets the same tile number and leaves the loop together.
 template <typename F>
-__device__ inline void for_each_tile(unsigned long long *next, uint64_t n_tiles, F body)
+__device__ inline void for_each_tile(unsigned long long *next, uint64_t n_tiles, const unsigned long long *lease, F body)
 {
     if (!next) {
         for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) body(t);
@@ -813,7 +843,10 @@ __device__ inline void for_each_tile(unsigned long long *next, uint64_t n_tiles,
     }
     __shared__ unsigned long long s_tile;
     for (;;) {
-        if (threadIdx.x == 0) s_tile = atomicAdd(next, 1ull);
+        if (threadIdx.x == 0) {
+            yield_link(lease);                    // a fetch that is using the link goes first
+            s_tile = atomicAdd(next, 1ull);
+        }
         __syncthreads();
         const uint64_t t = s_tile;
         __syncthreads();                          // all have read it before thread 0 writes the next one
@@ -823,9 +856,10 @@ __device__ inline void for_each_tile(unsigned long long *next, uint64_t n_tiles,
 }
 
 __global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items, uint32_t n_items, uint64_t chunk_bytes,
-                                                 uint32_t tiles_per_chunk, unsigned long long *next)
+                                                 uint32_t tiles_per_chunk, unsigned long long *next,
+                                                 const unsigned long long *lease)
 {
-    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, [&](uint64_t t) {
+    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, lease, [&](uint64_t t) {
         uint64_t it = t / tiles_per_chunk;
         uint64_t off = (t - it * tiles_per_chunk) * TILE_HOST;
         Item x = items[it];
@@ -835,10 +869,11 @@ __global__ __launch_bounds__(WG) void copy_items(const Item *__restrict__ items,
 
 // One source, one or two destinations (dst == 0: none): the write-back path reads each source byte once.
 __global__ __launch_bounds__(WG) void copy_items2(const Item2 *__restrict__ items, uint32_t n_items,
-                                                  uint64_t chunk_bytes, uint32_t tiles_per_chunk, unsigned long long *next)
+                                                  uint64_t chunk_bytes, uint32_t tiles_per_chunk, unsigned long long *next,
+                                                  const unsigned long long *lease)
 {
     constexpr uint32_t TILE = TILE_HOST;
-    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, [&](uint64_t t) {
+    for_each_tile(next, (uint64_t)n_items * tiles_per_chunk, lease, [&](uint64_t t) {
         uint64_t it = t / tiles_per_chunk;
         uint64_t off = (t - it * tiles_per_chunk) * TILE;
         Item2 x = items[it];
