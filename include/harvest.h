@@ -22,7 +22,8 @@
  *     results are valid in stream order.  The first call on a stream, and a
  *     call with more requests than any before it on that stream, allocates
  *     per-stream scratch (hipMalloc), the latter after waiting for that
- *     stream's earlier work; steady-state calls allocate nothing.  harvest_fetch_kv and
+ *     stream's earlier work and freeing the smaller scratch (hipFree waits for
+ *     the whole device); steady-state calls allocate nothing.  harvest_fetch_kv and
  *     harvest_fetch_experts may be recorded into a HIP graph (stream capture)
  *     once such a call has run on that stream outside capture: they use no
  *     memset and read residency from device memory, so a replay follows every
@@ -366,7 +367,8 @@ int harvest_prefetch_release(harvest_prefetcher *pf, void *compute_stream);
  * the events the context keeps for it - or, for a stream served by harvest_fetch_kv_static, gives its fixed state back,
  * so that another stream can take it.  For applications that create and destroy streams while a context lives: call it
  * before destroying the stream (a new stream that happens to get the same handle later simply starts afresh).  The next
- * call on the stream sets its state up again, with the allocations of a first call.  ENOENT: the context has no state for
+ * call on the stream sets its state up again, with the allocations of a first call.  Freeing device memory waits for the
+ * whole device, so this is no call for a latency-critical moment.  ENOENT: the context has no state for
  * this stream; EINVAL: the stream is being recorded into a graph, or belongs to a prefetcher (harvest_prefetcher_destroy
  * releases that one).  Must not run concurrently with another call that uses the same stream. */
 int harvest_release_stream(harvest_ctx *ctx, void *stream);
