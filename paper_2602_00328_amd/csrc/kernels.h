@@ -26,7 +26,9 @@
 //   gather_hm, gather_hm_host: the same two into a head-major working layout.
 //   copy_items, copy_items2, fill_items, dir_write : host-built lists - placement, write-back (one source, up to two
 //                              destinations), slot poisoning after revocation, directory publication; the _hbm forms
-//                              of the first three serve copies that stay inside HBM.
+//                              of the first three serve copies that stay inside HBM.  The forms that cross PCIe are a
+//                              dozen persistent workgroups whose tiles are counted out one at a time, and they stand
+//                              back while a fetch has announced that it needs the link (link_announce, yield_link).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
