@@ -39,13 +39,16 @@ def parse():
     ap.add_argument("--no-isolation", action="store_true")
     ap.add_argument("--host-wgs", type=int, default=0, help="tuning: workgroups of the host-tier gather (0 = default)")
     ap.add_argument("--workload", default="kv_decode",
-                    choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen", "latency_by_size", "link_contention"],
+                    choices=["kv_decode", "kv_tiny", "experts_phi", "experts_qwen", "latency_by_size", "link_contention",
+                             "kv_and_experts"],
                     help="kv_decode = configs[1] (the benchmark line); kv_tiny = configs[0] (fetch latency, both forms of the "
                          "fetch); experts_* = configs[2] / configs[3], extra lines; latency_by_size = time of one fetch from "
                          "the cache tier against the same fetch from the host, by object size (the paper's Figures 3 and 7 "
                          "on this machine: context, not a benchmark line); link_contention = a PCIe-bound KV fetch repeated on one stream "
                          "while a placement of experts runs on another, by the number of workgroups the placement's copy runs "
-                         "with (harvest_config.pcie_wgs): who gets the link")
+                         "with (harvest_config.pcie_wgs): who gets the link; kv_and_experts = configs[4]: the KV decode fetch on one "
+                         "stream and the Phi-shaped expert fetch on another at the same time, a quarter of each cache tier "
+                         "revoked every 10 steps and placed again 5 steps later")
     ap.add_argument("--head-major", action="store_true", help="gather into the head-major working layout instead")
     ap.add_argument("--kv-elt-bytes", type=int, default=2, choices=[1, 2, 4],
                     help="bytes per KV element: 2 = the bf16 / fp16 of the named config, 1 = an fp8 KV cache (16 KiB blocks)")
@@ -182,8 +185,8 @@ class DeviceDecode:
             if run.lens[s] % sh.block_tokens == 0:
                 tail = run.tables[s][-1]
                 self.eng.evict_from_local(0, [tail], 1)
-                if wl.resident[tail]:
-                    self.eng.place(0, [tail])
+                if wl.resident[tail] and self.eng.place(0, [tail])[0] == 0:
+                    run.live.add(tail)
                 new = int(wl.future_blocks[s][run.n_future[s]])
                 run.n_future[s] += 1
                 got = self.eng.register(0, 1, wl.host_slot[new:new + 1], 2)
@@ -660,6 +663,150 @@ def bench_contention(args):
                       "rows": rows}), flush=True)
 
 
+def bench_mixed(args):
+    """configs[4]: configs[1]'s KV decode on one stream and configs[2]'s expert fetch on another, both enqueued every step;
+    at t = 10, 20, ... a seeded quarter of the live cache-tier allocations of each class is revoked with the step's fetches
+    in flight (Section 3.2), at t = 5 mod 10 the revoked objects are placed again.  Timed: the two classes alone, then
+    together; checked against the oracle at the end.  Both fetches are bound by the same PCIe link, so together they take
+    about as long as one after the other - what the figure shows is that nothing else is lost."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from workloads import scenarios as S
+    from workloads.hip_engine import HipEngine
+    steps = min(args.steps, 60)
+    warm = min(args.warmup, 5)
+    n_total = warm + 3 * steps
+    layers_kv, layers_ex = min(args.layers, 8), 2
+    t0 = time.time()
+    wl = W.kv_decode(seed=args.seed, n_layers=layers_kv, n_steps=n_total, shape=W.KVShape(n_layers=layers_kv))
+    ex = W.expert_offload(seed=args.seed, shape=W.ExpertShape(n_layers=layers_ex))
+    sp = S.expert_spec(ex)
+    eng = HipEngine(kv=S.kv_spec(wl), expert=sp, two_streams=True, poison=True, cache_planes_adjacent=True)
+    run, xrun = S.KVRun(eng, wl), S.ExpertRun(eng, ex)
+    dd = DeviceDecode(run, eng, wl, n_total)
+    dev = eng.dev
+    ks, xs = eng.streams[S.KV], eng.streams[S.EXPERT]
+    E = ex.shape.n_experts
+    staging = torch.empty(E * sp.chunk_bytes, dtype=torch.uint8, device=dev)
+    ptrs = torch.zeros(E, dtype=torch.int64, device=dev)
+    topk = {t: torch.from_numpy(ex.routing(t, t % layers_ex)).to(dev) for t in range(n_total)}
+    torch.cuda.synchronize()
+    log(f"[bench] kv_and_experts: KV {layers_kv} layers, experts {layers_ex} layers, set up in {time.time() - t0:.1f}s")
+
+    def kv_step():
+        with torch.cuda.stream(ks):
+            dd.step()
+
+    def ex_step(t):
+        with torch.cuda.stream(xs):
+            eng.h.fetch_experts(t % layers_ex, topk[t], staging, E, ptrs)
+
+    def churn(t, kv, experts):
+        if t % 10 == 0 and t > 0:
+            if kv:
+                run.revoke_quarter(t)
+            if experts:
+                xrun.revoke_quarter(t)
+        if t % 10 == 5:
+            if kv:
+                run.replace_revoked()
+            if experts:
+                xrun.replace_revoked()
+
+    def leg(t_first, n, kv, experts):
+        torch.cuda.synchronize()
+        s0 = eng.h.stats()
+        a = time.perf_counter()
+        for t in range(t_first, t_first + n):
+            if kv:
+                kv_step()
+            if experts:
+                ex_step(t)
+            churn(t, kv, experts)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - a
+        s1 = eng.h.stats()
+        moved = 0
+        for k, b in ((0, 2 * wl.shape.chunk_bytes), (1, sp.chunk_bytes)):
+            served = sum(int(getattr(s1.fetch[k], f)) - int(getattr(s0.fetch[k], f)) for f in ("n_cache", "n_host"))
+            moved += served * b
+        return sec, moved, {"revoked": [int(s1.n_revoked[k] - s0.n_revoked[k]) for k in (0, 1)],
+                            "placed": [int(s1.n_placed[k] - s0.n_placed[k]) for k in (0, 1)]}
+
+    for t in range(warm):
+        kv_step(); ex_step(t)
+    t = warm
+    # experts alone, KV alone (the decode state advances only in the legs that run the KV side), then both
+    sec_x, moved_x, churn_x = leg(t, steps, False, True); t += steps
+    sec_k, moved_k, churn_k = leg(t, steps, True, False); t += steps
+    sec_b, moved_b, churn_b = leg(t, steps, True, True); t += steps
+    log(f"[bench] {steps} steps: experts alone {sec_x / steps * 1e3:.2f} ms/step, KV alone {sec_k / steps * 1e3:.2f} ms/step, "
+        f"together {sec_b / steps * 1e3:.2f} ms/step")
+
+    bit_exact = None
+    if not args.no_cpu_baseline:                              # the oracle goes through the same appends, revocations and placements
+        from oracle.engine import OracleEngine
+        layer = dd.first_layer(dd.t)
+        wl1 = W.kv_decode(seed=args.seed, n_layers=layers_kv, n_steps=n_total, shape=W.KVShape(n_layers=layers_kv))
+        eo = OracleEngine(kv=S.kv_spec(wl1), expert=sp, poison=True, kv_layers=[layer], threads=len(os.sched_getaffinity(0)))
+        ro, xo = S.KVRun(eo, wl1), S.ExpertRun(eo, ex)
+        kt = 0                                                # the KV side's own step count (DeviceDecode.t)
+        for _ in range(warm):
+            ro.append(kt); kt += 1
+        tt = warm
+        for kv, experts in ((False, True), (True, False), (True, True)):
+            for _ in range(steps):
+                if kv:
+                    ro.append(kt); kt += 1
+                if tt % 10 == 0 and tt > 0:
+                    if kv:
+                        ro.revoke_quarter(tt)
+                    if experts:
+                        xo.revoke_quarter(tt)
+                if tt % 10 == 5:
+                    if kv:
+                        ro.replace_revoked()
+                    if experts:
+                        xo.replace_revoked()
+                tt += 1
+        assert kt == dd.t
+        want = ro.fetch(layer)
+        with torch.cuda.stream(ks):
+            dd.fetch(layer)
+        torch.cuda.synchronize()
+        got_k, got_v = dd.dst[0].cpu().numpy(), dd.dst[1].cpu().numpy()
+        counts, miss, _ = eng.h.fetch_info(stream=ks, miss_cap=dd.d_table.numel(), cls=S.KV)
+        ok_kv = bool(np.array_equal(want[0], got_k) and np.array_equal(want[1], got_v) and counts == want[3]
+                     and np.array_equal(np.sort(miss), want[2]))
+        xw = xo.fetch(tt, tt % layers_ex)
+        xg = xrun.fetch(tt, tt % layers_ex)
+        ok_x = all((a is None and b is None) or (a is not None and b is not None and np.array_equal(a, b))
+                   for a, b in zip(xw[0], xg[0])) and xw[4] == xg[4] and np.array_equal(xw[3], xg[3])
+        bit_exact = bool(ok_kv and ok_x)
+        log(f"[bench] after {n_total} steps vs oracle: KV {ok_kv}, experts {ok_x}")
+        eo.close()
+    print(json.dumps({
+        "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
+        "value": round(2 * moved_b / sec_b / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": round(sec_b / steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "configs[4]: configs[1]'s KV decode fetch on one stream and configs[2]'s expert fetch (16 Phi-shaped "
+                               "experts of 150 MiB per layer) on another, both every step; a quarter of each cache tier revoked every "
+                               "10 steps with the fetches in flight, placed again 5 steps later; poisoning on",
+                   "kv_layers_materialised": layers_kv, "expert_layers_materialised": layers_ex, "seed": args.seed},
+        "bit_exact": bit_exact,
+        "alone": {"kv_ms_per_step": round(sec_k / steps * 1e3, 4), "kv_gbs": round(2 * moved_k / sec_k / 1e9, 2),
+                  "experts_ms_per_step": round(sec_x / steps * 1e3, 4), "experts_gbs": round(2 * moved_x / sec_x / 1e9, 2),
+                  "churn": {"kv": churn_k, "experts": churn_x}},
+        "together": {"ms_per_step": round(sec_b / steps * 1e3, 4), "churn": churn_b,
+                     "over_sum_of_alone": round(sec_b / (sec_k + sec_x), 4),
+                     "note": "both fetches and the placements are bound by the one PCIe link: together cannot take less than the "
+                             "sum of what each needs of it; anything above 1 is what running side by side costs"},
+        "roofline": None, "cpu_baseline": None}), flush=True)
+    eng.close()
+
+
 def no_nan(x):
     """JSON has no NaN: figures that were not measured (--no-profile) are reported as null."""
     if isinstance(x, dict):
@@ -683,6 +830,8 @@ def main():
         return bench_latency(args)
     if args.workload == "link_contention":
         return bench_contention(args)
+    if args.workload == "kv_and_experts":
+        return bench_mixed(args)
     if args.workload != "kv_decode":
         return bench_experts(args)
     out = bench_kv(args, args.seed, full=True)

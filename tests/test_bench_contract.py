@@ -79,3 +79,17 @@ def test_link_contention_workload():
     default = rows["default (12)"]
     assert default["fetch_beside_placement_ms_median"] < 2.5 * default["fetch_alone_ms"]
     assert default["placement_alone_ms"] < 1.1 * rows["64"]["placement_alone_ms"]
+
+
+@pytest.mark.gpu
+def test_kv_and_experts_workload():
+    """configs[4] as a benchmark line: both classes every step on two streams, revocations with fetches in flight; the
+    end state agrees with the oracle's, and side by side the two cost no more than one after the other."""
+    print("bench kv_and_experts", flush=True)
+    r = subprocess.run([sys.executable, BENCH, "--workload", "kv_and_experts", "--steps", "30"], capture_output=True, text=True,
+                       timeout=400)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip().splitlines()[-1])
+    assert d["bit_exact"] is True and d["steps"] == 30
+    assert d["together"]["churn"]["revoked"][0] > 1000 and d["together"]["churn"]["revoked"][1] > 0
+    assert d["together"]["over_sum_of_alone"] < 1.1
