@@ -655,7 +655,8 @@ __global__ __launch_bounds__(WG) void fetch_kv_small(ClassDev c, uint32_t layer,
 // measured on MI355X and lost: a whole 32 KiB block per workgroup (source-order loads, 8 strips of 4 KiB stored) moves
 // 5.31 TB/s against 5.81 for this kernel (12 041 scattered blocks, alone), and tiles of 4 tokens x 4 heads (every wave
 // instruction a contiguous kilobyte on both sides) 5.91 in isolation but 5.85 against 5.94 once inside the library's
-// looping, feedback-sized launch.
+// looping, feedback-sized launch.  One-wavefront workgroups (1 KiB tiles), the token-major gather's shape, are a
+// wash here: 5.95 against 5.90 TB/s alone, 5.32 against 5.35 inside the step.
 struct HmArgs {
     uint32_t n_heads;
     uint32_t upr;             // 16-byte units per head row (head_bytes / 16)
