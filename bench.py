@@ -209,7 +209,7 @@ def kv_totals(stats):
     return {k: int(getattr(stats.fetch[0], k)) for k in COUNT_KEYS}
 
 
-def bench_tiny(args):
+def bench_tiny(args, embed=False):
     """configs[0]: the tiny KV fetch (16 sequences x 16 blocks, 60 % in the cache tier), its write-back and the fetch
     again, checked against the oracle.  Its size says nothing about bandwidth; what it shows is the latency floor of a
     fetch, for the one-kernel form small tables take and for the general path."""
@@ -281,7 +281,7 @@ def bench_tiny(args):
         eng.close()
     payload = ids.size * 2 * chunk
     best = res["one_kernel"]["back_to_back_us"] * 1e-6
-    print(json.dumps({
+    out = {
         "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
         "value": round(2 * payload / best / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(best * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
@@ -290,7 +290,10 @@ def bench_tiny(args):
                                "on the host, one layer; a latency case - too small to say anything about bandwidth",
                    "seed": args.seed},
         "objects_per_s": round(ids.size / best), "bit_exact": exact, "served": served, "latency": res,
-        "roofline": None, "cpu_baseline": cpu_baseline}), flush=True)
+        "roofline": None, "cpu_baseline": cpu_baseline}
+    if embed:
+        return out
+    print(json.dumps(out), flush=True)
 
 
 def experts_vs_oracle(args, wl, run, eng, n_total, L):
@@ -663,7 +666,7 @@ def bench_contention(args):
                       "rows": rows}), flush=True)
 
 
-def bench_mixed(args):
+def bench_mixed(args, embed=False):
     """configs[4]: configs[1]'s KV decode on one stream and configs[2]'s expert fetch on another, both enqueued every step;
     at t = 10, 20, ... a seeded quarter of the live cache-tier allocations of each class is revoked with the step's fetches
     in flight (Section 3.2), at t = 5 mod 10 the revoked objects are placed again.  Timed: the two classes alone, then
@@ -786,7 +789,7 @@ def bench_mixed(args):
         bit_exact = bool(ok_kv and ok_x)
         log(f"[bench] after {n_total} steps vs oracle: KV {ok_kv}, experts {ok_x}")
         eo.close()
-    print(json.dumps({
+    out = {
         "metric": "fetch GB/s (read+write) and % of HBM/PCIe peak; objects/s; bit-exact vs oracle",
         "value": round(2 * moved_b / sec_b / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm,
         "ms_per_step": round(sec_b / steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -801,10 +804,14 @@ def bench_mixed(args):
                   "churn": {"kv": churn_k, "experts": churn_x}},
         "together": {"ms_per_step": round(sec_b / steps * 1e3, 4), "churn": churn_b,
                      "over_sum_of_alone": round(sec_b / (sec_k + sec_x), 4),
-                     "note": "both fetches and the placements are bound by the one PCIe link: together cannot take less than the "
-                             "sum of what each needs of it; anything above 1 is what running side by side costs"},
-        "roofline": None, "cpu_baseline": None}), flush=True)
+                     "note": "both fetches and the placements are bound by the one PCIe link, so side by side cannot beat one "
+                             "after the other; the three legs cover different steps, whose revocations and placements differ "
+                             "somewhat (see churn): a ratio near 1 says that running side by side costs nothing on top"},
+        "roofline": None, "cpu_baseline": None}
     eng.close()
+    if embed:
+        return out
+    print(json.dumps(out), flush=True)
 
 
 def no_nan(x):
@@ -837,8 +844,9 @@ def main():
     out = bench_kv(args, args.seed, full=True)
     if args.other_legs and not args.head_major and args.fetch_layers == 1:
         # Beside the benchmark line: the same configuration at another draw of the sequence lengths (seed 0 happens to draw
-        # short ones), and the two expert configurations with two layers materialised - short runs, each checked against
-        # the oracle, so that one default run shows every kernel at its real per-step shape.
+        # short ones), the two expert configurations with two layers materialised, the tiny configuration and the mixed
+        # one - short runs, each checked against the oracle, so that one default run shows all five configurations and
+        # every kernel at its real per-step shape.
         import copy
         extra = {}
         a2 = copy.copy(args)
@@ -857,6 +865,14 @@ def main():
                                             "placed_per_step", "cpu_baseline")} | {
                 "layers_materialised": 2, "hbm_tier_gather_gbs": r["roofline"]["achieved"],
                 "hbm_tier_gather_frac": r["roofline"]["frac"], "host_tier_gbs": r["host_tier"]["achieved"]}
+        a4 = copy.copy(args)
+        a4.steps, a4.warmup = 50, 10
+        r = bench_tiny(a4, embed=True)
+        extra["configs[0]"] = {k: r[k] for k in ("value", "unit", "ms_per_step", "objects_per_s", "bit_exact", "served", "latency")}
+        a5 = copy.copy(args)
+        a5.steps, a5.warmup = 30, 5
+        r = bench_mixed(a5, embed=True)
+        extra["configs[4]"] = {k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "bit_exact", "alone", "together")}
         out["other_legs"] = extra
     print(json.dumps(no_nan(out)), flush=True)
 

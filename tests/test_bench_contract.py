@@ -45,8 +45,10 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     assert rf["traffic"] is None or "profiles/" in rf["traffic_source"]
     assert rf["frac_alone"] is not None and 0 < rf["frac_alone"] < 1 and 0 < rf["frac_of_plain_copy"] < 1.1
     assert out["config"]["blocks_per_step_mean_of_config"] == 20480
-    legs = out["other_legs"]                       # the next seed's draw and the two expert configurations, each checked
-    assert len(legs) == 3 and all(leg["bit_exact"] is True and leg["value"] > 0 for leg in legs.values())
+    legs = out["other_legs"]                       # the next seed's draw and the four other configurations, each checked
+    assert len(legs) == 5 and all(leg["bit_exact"] is True and leg["value"] > 0 for leg in legs.values())
+    assert {"configs[0]", "configs[2]", "configs[3]", "configs[4]"} <= set(legs)
+    assert legs["configs[4]"]["together"]["over_sum_of_alone"] < 1.1
     assert legs["configs[2]"]["cpu_baseline"]["kind"] == "oracle" and legs["configs[3]"]["placed_per_step"] > 0
     assert out["value"] > 0 and abs(out["ms_per_step"] - 2 * out["config"]["payload_bytes_per_step"] / out["value"] / 1e6) \
         < 0.02 * out["ms_per_step"]
